@@ -1,0 +1,443 @@
+/*
+ * CPU oracle for the 8-bit decentralized-training hot path (arXiv 2111.09389).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, by-definition
+ * statement of what the GPU library must compute.  It shares no code, header,
+ * table or constant with the HIP path; only tests/, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.  Never tuned for speed: loops are
+ * written in the order the definitions are written; OpenMP is used only across
+ * independent outputs.
+ *
+ * Floating point is fp64 except where a rounding decision produces an integer
+ * (quantizer codes, top-k membership, arg-extrema): those decisions are taken
+ * in fp32 with single IEEE operations, the precision the method's inputs have.
+ *
+ * Layouts: activations / gradients NHWC, filters KRSC, parameters [n][d].
+ *
+ * Pins (tests/test_oracle_*.py): Philox known-answer vectors of the SC'11
+ * publication; quantizer grid invariants and a hand example; float64
+ * library convolution + autograd; adjoint identities; Range-EvoNorm closed
+ * forms, hand example, finite differences and float64 autograd; ring
+ * eigen-modes and average preservation for the mix; brute-force sort for
+ * top-k.  Whole-step accuracy against the paper's tables: parity unpinned
+ * (needs the datasets).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_OK 0
+#define ORC_EOVERFLOW -1
+#define ORC_EINVAL -2
+
+typedef struct {
+    int N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w;
+} orc_conv_desc;
+
+static int out_dim(int in, int pad, int filt, int stride) { return (in + 2 * pad - filt) / stride + 1; }
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): 10 rounds; each round
+ * multiplies counter words 0 and 2 by two fixed odd constants, and mixes the
+ * high halves with the other counter words and the key; the key is advanced
+ * by two Weyl constants between rounds. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Uniform in [0,1) with 24-bit granularity for logical element i of a tensor:
+ * key = seed, counter = (offset + i/4, 0, 0), word i%4, top 24 bits. */
+static float sr_uniform(uint64_t seed, uint64_t offset, uint64_t i)
+{
+    uint64_t blk = offset + (i >> 2);
+    uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    return (float)(w[i & 3] >> 8) * 0x1.0p-24f;
+}
+
+void orc_sr_uniform(uint64_t seed, uint64_t offset, uint64_t first, uint64_t count, float *u)
+{
+    for (uint64_t i = 0; i < count; ++i) u[i] = sr_uniform(seed, offset, first + i);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Symmetric per-tensor 8-bit quantizer (Section 3 "Low Precision Training";
+ * grid fixed by the benchmark statement: scale = absmax/127, codes in
+ * [-127,127], round-to-nearest-even or stochastic rounding).
+ * rounding: 0 = nearest (ties to even), 1 = stochastic. */
+int orc_quantize(const float *x, size_t len, int rounding, uint64_t seed, uint64_t offset,
+                 int8_t *q, float *scale)
+{
+    float a = 0.0f;
+    for (size_t i = 0; i < len; ++i) {
+        float m = fabsf(x[i]);
+        if (!(m <= 3.4028234663852886e38f)) return ORC_EINVAL; /* NaN / Inf: caller error */
+        if (m > a) a = m;
+    }
+    volatile float inv = (a > 0.0f) ? 127.0f / a : 0.0f; /* one fp32 divide */
+    *scale = a / 127.0f;
+    for (size_t i = 0; i < len; ++i) {
+        volatile float t = x[i] * inv; /* one fp32 multiply, never fused */
+        float r;
+        if (rounding == 0) {
+            r = rintf(t); /* default rounding mode: ties to even */
+        } else {
+            float f = floorf(t);
+            volatile float frac = t - f; /* exact */
+            float u = sr_uniform(seed, offset, (uint64_t)i);
+            r = f + ((u < frac) ? 1.0f : 0.0f);
+        }
+        if (r > 127.0f) r = 127.0f;
+        if (r < -127.0f) r = -127.0f;
+        q[i] = (int8_t)(int)r;
+    }
+    return ORC_OK;
+}
+
+/* y = sA * sB * acc : the real value an int32 accumulator of two quantized
+ * tensors stands for. */
+void orc_dequantize(const int32_t *acc, size_t len, float sA, float sB, double *y)
+{
+    double s = (double)sA * (double)sB;
+    for (size_t i = 0; i < len; ++i) y[i] = s * (double)acc[i];
+}
+
+/* ------------------------------------------------------------------------- */
+/* The three convolution sums (Table "hardware_training", row Conv: forward,
+ * gradient w.r.t. input, gradient w.r.t. filter), cross-correlation with
+ * zero padding, exact integer arithmetic.  The result must fit int32. */
+int orc_qconv_fwd(const orc_conv_desc *d, const int8_t *x, const int8_t *w, int32_t *acc)
+{
+    const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+    int bad = 0;
+#pragma omp parallel for collapse(2) reduction(| : bad)
+    for (int n = 0; n < d->N; ++n)
+        for (int p = 0; p < P; ++p)
+            for (int q = 0; q < Q; ++q)
+                for (int k = 0; k < d->K; ++k) {
+                    int64_t s = 0;
+                    for (int r = 0; r < d->R; ++r)
+                        for (int t = 0; t < d->S; ++t) {
+                            int h = p * d->stride_h + r - d->pad_h, ww = q * d->stride_w + t - d->pad_w;
+                            if (h < 0 || h >= d->H || ww < 0 || ww >= d->W) continue;
+                            for (int c = 0; c < d->C; ++c)
+                                s += (int64_t)x[(((size_t)n * d->H + h) * d->W + ww) * d->C + c] *
+                                     (int64_t)w[(((size_t)k * d->R + r) * d->S + t) * d->C + c];
+                        }
+                    if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+                    acc[(((size_t)n * P + p) * Q + q) * d->K + k] = (int32_t)s;
+                }
+    return bad ? ORC_EOVERFLOW : ORC_OK;
+}
+
+int orc_qconv_bwd_data(const orc_conv_desc *d, const int8_t *g, const int8_t *w, int32_t *dx)
+{
+    const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+    int bad = 0;
+#pragma omp parallel for collapse(2) reduction(| : bad)
+    for (int n = 0; n < d->N; ++n)
+        for (int h = 0; h < d->H; ++h)
+            for (int ww = 0; ww < d->W; ++ww)
+                for (int c = 0; c < d->C; ++c) {
+                    int64_t s = 0;
+                    /* every (p,q,r,t) with p*stride + r - pad == h and q*stride + t - pad == ww */
+                    for (int p = 0; p < P; ++p)
+                        for (int q = 0; q < Q; ++q) {
+                            int r = h - p * d->stride_h + d->pad_h, t = ww - q * d->stride_w + d->pad_w;
+                            if (r < 0 || r >= d->R || t < 0 || t >= d->S) continue;
+                            for (int k = 0; k < d->K; ++k)
+                                s += (int64_t)g[(((size_t)n * P + p) * Q + q) * d->K + k] *
+                                     (int64_t)w[(((size_t)k * d->R + r) * d->S + t) * d->C + c];
+                        }
+                    if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+                    dx[(((size_t)n * d->H + h) * d->W + ww) * d->C + c] = (int32_t)s;
+                }
+    return bad ? ORC_EOVERFLOW : ORC_OK;
+}
+
+int orc_qconv_bwd_weight(const orc_conv_desc *d, const int8_t *g, const int8_t *x, int32_t *dw)
+{
+    const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+    int bad = 0;
+#pragma omp parallel for collapse(2) reduction(| : bad)
+    for (int k = 0; k < d->K; ++k)
+        for (int r = 0; r < d->R; ++r)
+            for (int t = 0; t < d->S; ++t)
+                for (int c = 0; c < d->C; ++c) {
+                    int64_t s = 0;
+                    for (int n = 0; n < d->N; ++n)
+                        for (int p = 0; p < P; ++p)
+                            for (int q = 0; q < Q; ++q) {
+                                int h = p * d->stride_h + r - d->pad_h, ww = q * d->stride_w + t - d->pad_w;
+                                if (h < 0 || h >= d->H || ww < 0 || ww >= d->W) continue;
+                                s += (int64_t)g[(((size_t)n * P + p) * Q + q) * d->K + k] *
+                                     (int64_t)x[(((size_t)n * d->H + h) * d->W + ww) * d->C + c];
+                            }
+                    if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+                    dw[(((size_t)k * d->R + r) * d->S + t) * d->C + c] = (int32_t)s;
+                }
+    return bad ? ORC_EOVERFLOW : ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Range-EvoNorm (Eq. "ren"): per sample and channel group, divide
+ * x * hard_sigmoid(v x) by C(m) * (max - min) of the group's raw inputs,
+ * m = channels per group, C(m) = 1/sqrt(2 ln m); then the affine gamma, beta.
+ * eps is added to the denominator (the equation has none; eps = 0 reproduces
+ * it literally).  Also returns, per (sample, group), the range and the first
+ * position (lowest index in (h, w, channel-in-group) order) of max and min. */
+static double hard_sigmoid(double z) { return fmax(0.0, fmin(1.0, (z + 3.0) / 6.0)); }
+
+int orc_range_evonorm_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                          const float *gamma, const float *beta, double eps, double *y,
+                          double *range_out, int32_t *argmax_out, int32_t *argmin_out)
+{
+    if (groups <= 0 || C % groups != 0 || C / groups < 2) return ORC_EINVAL;
+    const int m = C / groups;
+    const double Cm = 1.0 / sqrt(2.0 * log((double)m));
+#pragma omp parallel for collapse(2)
+    for (int n = 0; n < N; ++n)
+        for (int G = 0; G < groups; ++G) {
+            float mx = 0, mn = 0;
+            int32_t imx = -1, imn = -1;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        float e = x[(((size_t)n * H + h) * W + w) * C + G * m + cc];
+                        int32_t idx = (h * W + w) * m + cc;
+                        if (imx < 0 || e > mx) { mx = e; imx = idx; }
+                        if (imn < 0 || e < mn) { mn = e; imn = idx; }
+                    }
+            double R = (double)mx - (double)mn;
+            double D = Cm * R + eps;
+            range_out[(size_t)n * groups + G] = R;
+            argmax_out[(size_t)n * groups + G] = imx;
+            argmin_out[(size_t)n * groups + G] = imn;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        int c = G * m + cc;
+                        size_t at = (((size_t)n * H + h) * W + w) * C + c;
+                        double xe = x[at];
+                        double u = xe * hard_sigmoid((double)v[c] * xe);
+                        y[at] = (double)gamma[c] * u / D + (double)beta[c];
+                    }
+        }
+    return ORC_OK;
+}
+
+/* Chain rule of the forward above.  Hard-sigmoid slope is 1/6 strictly inside
+ * (-3, 3) and 0 elsewhere; the whole gradient of the range goes to the saved
+ * first arg-max (+) and first arg-min (-). */
+int orc_range_evonorm_bwd(const double *dy, const float *x, int N, int H, int W, int C, int groups,
+                          const float *v, const float *gamma, double eps, double *dx, double *dv,
+                          double *dgamma, double *dbeta)
+{
+    if (groups <= 0 || C % groups != 0 || C / groups < 2) return ORC_EINVAL;
+    const int m = C / groups;
+    const double Cm = 1.0 / sqrt(2.0 * log((double)m));
+    for (int c = 0; c < C; ++c) dv[c] = dgamma[c] = dbeta[c] = 0.0;
+    for (int n = 0; n < N; ++n)
+        for (int G = 0; G < groups; ++G) {
+            float mx = 0, mn = 0;
+            size_t amx = 0, amn = 0;
+            int first = 1;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        size_t at = (((size_t)n * H + h) * W + w) * C + G * m + cc;
+                        float e = x[at];
+                        if (first || e > mx) { mx = e; amx = at; }
+                        if (first || e < mn) { mn = e; amn = at; }
+                        first = 0;
+                    }
+            double D = Cm * ((double)mx - (double)mn) + eps;
+            double dD = 0.0;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        int c = G * m + cc;
+                        size_t at = (((size_t)n * H + h) * W + w) * C + c;
+                        double xe = x[at], z = (double)v[c] * xe;
+                        double s = hard_sigmoid(z);
+                        double sp = (z > -3.0 && z < 3.0) ? 1.0 / 6.0 : 0.0;
+                        double u = xe * s;
+                        double du = dy[at] * (double)gamma[c] / D;
+                        dbeta[c] += dy[at];
+                        dgamma[c] += dy[at] * u / D;
+                        dv[c] += du * xe * xe * sp;
+                        dx[at] = du * (s + xe * (double)v[c] * sp);
+                        dD -= dy[at] * (double)gamma[c] * u / (D * D);
+                    }
+            double dR = Cm * dD;
+            dx[amx] += dR;
+            dx[amn] -= dR;
+        }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gossip step (Algorithm 1 step 7; Algorithms 2 and 3 of the supplement).
+ *   xhat == NULL : x_i+ = x_i + eta * (sum_j W_ij x_j - x_i)
+ *   xhat != NULL : CHOCO.  v = x_i - xhat_i (fp32);  q = v on the top-k |v| of
+ *                  each segment, k = max(1, ceil(keep_ratio*len)), ties to the
+ *                  lower index;  xhat_i += q (fp32) for every agent first;
+ *                  x_i+ = x_i + eta * sum_j W_ij (xhat_j - xhat_i).
+ * W is row-major, W[i*n+j] = weight node i gives node j's model. */
+typedef struct { uint32_t mag; uint32_t idx; } orc_key;
+static int key_cmp(const void *a, const void *b)
+{
+    const orc_key *p = (const orc_key *)a, *q = (const orc_key *)b;
+    if (p->mag != q->mag) return (p->mag > q->mag) ? -1 : 1; /* larger magnitude first */
+    return (p->idx < q->idx) ? -1 : (p->idx > q->idx);        /* then lower index */
+}
+
+int orc_gossip_mix(const float *x, float *xhat, int n, size_t d, const float *Wm, float eta,
+                   double keep_ratio, const int64_t *seg_offsets, int nseg, double *x_out)
+{
+    if (xhat) {
+        for (int i = 0; i < n; ++i)
+            for (int sgm = 0; sgm < nseg; ++sgm) {
+                size_t lo = (size_t)seg_offsets[sgm], hi = (size_t)seg_offsets[sgm + 1], len = hi - lo;
+                if (len == 0) continue;
+                int64_t k = (int64_t)ceil(keep_ratio * (double)len);
+                if (k < 1) k = 1;
+                if ((size_t)k > len) k = (int64_t)len;
+                orc_key *keys = (orc_key *)malloc(len * sizeof(orc_key));
+                float *vv = (float *)malloc(len * sizeof(float));
+                if (!keys || !vv) { free(keys); free(vv); return ORC_EINVAL; }
+                for (size_t e = 0; e < len; ++e) {
+                    volatile float dv = x[(size_t)i * d + lo + e] - xhat[(size_t)i * d + lo + e];
+                    vv[e] = dv;
+                    float ab = fabsf(dv);
+                    uint32_t bits;
+                    memcpy(&bits, &ab, 4);
+                    keys[e].mag = bits;
+                    keys[e].idx = (uint32_t)e;
+                }
+                qsort(keys, len, sizeof(orc_key), key_cmp);
+                for (int64_t t = 0; t < k; ++t) {
+                    size_t e = keys[t].idx;
+                    volatile float s = xhat[(size_t)i * d + lo + e] + vv[e];
+                    xhat[(size_t)i * d + lo + e] = s;
+                }
+                free(keys);
+                free(vv);
+            }
+    }
+#pragma omp parallel for
+    for (int i = 0; i < n; ++i)
+        for (size_t e = 0; e < d; ++e) {
+            double s = 0.0;
+            if (xhat) {
+                for (int j = 0; j < n; ++j)
+                    s += (double)Wm[(size_t)i * n + j] * ((double)xhat[(size_t)j * d + e] - (double)xhat[(size_t)i * d + e]);
+            } else {
+                for (int j = 0; j < n; ++j) s += (double)Wm[(size_t)i * n + j] * (double)x[(size_t)j * d + e];
+                s -= (double)x[(size_t)i * d + e];
+            }
+            x_out[(size_t)i * d + e] = (double)x[(size_t)i * d + e] + (double)eta * s;
+        }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Glue layers of the benchmark networks (Table "hardware_training": skip
+ * connections, average pool; plus max-pool and the softmax cross-entropy
+ * loss, standard definitions), all NHWC, fp64. */
+void orc_add(const double *a, const double *b, size_t len, double *y)
+{
+    for (size_t i = 0; i < len; ++i) y[i] = a[i] + b[i];
+}
+
+/* window kxk, stride st, pad pd (padding never wins); idx = winning flat
+ * (h*W+w) position, first in window scan order on ties. */
+void orc_maxpool_fwd(const float *x, int N, int H, int W, int C, int k, int st, int pd, float *y, int32_t *idx)
+{
+    int P = out_dim(H, pd, k, st), Q = out_dim(W, pd, k, st);
+    for (int n = 0; n < N; ++n)
+        for (int p = 0; p < P; ++p)
+            for (int q = 0; q < Q; ++q)
+                for (int c = 0; c < C; ++c) {
+                    float best = 0;
+                    int32_t bi = -1;
+                    for (int r = 0; r < k; ++r)
+                        for (int t = 0; t < k; ++t) {
+                            int h = p * st + r - pd, w = q * st + t - pd;
+                            if (h < 0 || h >= H || w < 0 || w >= W) continue;
+                            float e = x[(((size_t)n * H + h) * W + w) * C + c];
+                            if (bi < 0 || e > best) { best = e; bi = h * W + w; }
+                        }
+                    size_t o = (((size_t)n * P + p) * Q + q) * C + c;
+                    y[o] = best;
+                    idx[o] = bi;
+                }
+}
+
+void orc_maxpool_bwd(const double *dy, const int32_t *idx, int N, int H, int W, int C, int P, int Q, double *dx)
+{
+    memset(dx, 0, sizeof(double) * (size_t)N * H * W * C);
+    for (int n = 0; n < N; ++n)
+        for (int pq = 0; pq < P * Q; ++pq)
+            for (int c = 0; c < C; ++c) {
+                size_t o = ((size_t)n * P * Q + pq) * C + c;
+                dx[((size_t)n * H * W + idx[o]) * C + c] += dy[o];
+            }
+}
+
+void orc_avgpool_fwd(const float *x, int N, int HW, int C, double *y)
+{
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c) {
+            double s = 0;
+            for (int i = 0; i < HW; ++i) s += x[((size_t)n * HW + i) * C + c];
+            y[(size_t)n * C + c] = s / HW;
+        }
+}
+
+void orc_avgpool_bwd(const double *dy, int N, int HW, int C, double *dx)
+{
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i)
+            for (int c = 0; c < C; ++c) dx[((size_t)n * HW + i) * C + c] = dy[(size_t)n * C + c] / HW;
+}
+
+/* mean over the batch of -log softmax(logits)[label]; dlogits = (softmax - onehot)/N */
+double orc_softmax_xent(const float *logits, const int32_t *labels, int N, int classes, double *dlogits)
+{
+    double loss = 0;
+    for (int n = 0; n < N; ++n) {
+        double mx = logits[(size_t)n * classes];
+        for (int j = 1; j < classes; ++j) mx = fmax(mx, (double)logits[(size_t)n * classes + j]);
+        double z = 0;
+        for (int j = 0; j < classes; ++j) z += exp((double)logits[(size_t)n * classes + j] - mx);
+        loss += log(z) + mx - (double)logits[(size_t)n * classes + labels[n]];
+        for (int j = 0; j < classes; ++j)
+            dlogits[(size_t)n * classes + j] =
+                (exp((double)logits[(size_t)n * classes + j] - mx) / z - (j == labels[n] ? 1.0 : 0.0)) / N;
+    }
+    return loss / N;
+}
+
+/* local SGD step of Algorithm 1 step 3: x~ = x - lr * g */
+void orc_sgd(const float *x, const float *g, size_t len, float lr, double *y)
+{
+    for (size_t i = 0; i < len; ++i) y[i] = (double)x[i] - (double)lr * (double)g[i];
+}
