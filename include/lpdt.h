@@ -1,0 +1,209 @@
+/*
+ * lpdt - the hot path of low-precision decentralized training (arXiv 2111.09389)
+ * as a C-ABI library of hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * One agent's 8-bit training step (Section 3, "Low Precision Training"):
+ * quantize -> int8 convolution forward / backward-data / backward-weight with
+ * int32 accumulation -> Range-EvoNorm (Eq. "ren"), plus the gossip step of
+ * Algorithm 1 (plain and CHOCO-SGD with layer-wise top-k, supplement
+ * Algorithm 3) for several agents simulated on one GPU.
+ *
+ * Conventions shared by every entry point
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *  - The caller owns every buffer; the library borrows them until the work it
+ *    enqueued on `stream` has finished.  No entry point allocates, frees or
+ *    synchronises; all work is asynchronous on `stream` (a hipStream_t passed
+ *    as void*, NULL = the default stream), so calls can be captured in a HIP
+ *    graph.
+ *  - Scratch memory comes from the caller: `ws` / `ws_bytes`, sized by the
+ *    matching *_workspace_bytes() call; `ws` must be 256-byte aligned.
+ *    Workspace contents are undefined on entry and on return.
+ *  - Arguments are checked on the host before anything is enqueued.  Return
+ *    value 0 = success, negative = lpdt_status; lpdt_last_error() gives a
+ *    thread-local message for the last failure.
+ *  - Layouts: activations and their gradients NHWC, filters KRSC (K output
+ *    channels, R x S taps, C input channels), parameter matrices row-major
+ *    [n agents][d parameters].  Tensors are dense and contiguous.
+ *  - Scales of quantized tensors are fp32 scalars resident in device memory,
+ *    so no call needs a host round trip.
+ */
+#ifndef LPDT_H
+#define LPDT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LPDT_OK = 0,
+    LPDT_EINVAL = -1,       /* null pointer, non-positive size, misaligned buffer, bad enum */
+    LPDT_EUNSUPPORTED = -2, /* a shape or mode outside what the kernels implement */
+    LPDT_EWORKSPACE = -3,   /* ws is NULL / misaligned / smaller than *_workspace_bytes() */
+    LPDT_EHIP = -4          /* a HIP runtime call (launch) failed */
+} lpdt_status;
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char *lpdt_last_error(void);
+/* Library version, e.g. 100 = 0.1.0. */
+int lpdt_version(void);
+
+/* ------------------------------------------------------------------ quantizer
+ * Section 3 "Low Precision Training": weights, activations and layer gradients
+ * are quantized to 8 bits in every iteration.  Grid: symmetric, per tensor,
+ * scale = absmax/127, codes in [-127,127] (-128 is never produced).
+ *   a = max|x_i| ; inv = 127/a (one fp32 divide) ; t_i = x_i*inv (fp32 multiply)
+ *   LPDT_ROUND_NEAREST    : q_i = round-half-to-even(t_i)
+ *   LPDT_ROUND_STOCHASTIC : q_i = floor(t_i) + [u_i < t_i - floor(t_i)],
+ *        u_i = (top 24 bits of a Philox4x32-10 word) * 2^-24, key = seed,
+ *        counter = (offset + i/4, 0, 0), word i%4 -- a function of the logical
+ *        element index i only, never of the launch geometry.
+ *   a == 0 gives all-zero codes and scale 0.  Non-finite inputs are a caller error.
+ */
+enum { LPDT_ROUND_NEAREST = 0, LPDT_ROUND_STOCHASTIC = 1 };
+
+size_t lpdt_quantize_workspace_bytes(size_t len);
+
+/* x[len] fp32 in; q[len] int8 out; scale: one fp32 out (absmax/127).
+ * Two passes over x (abs-max, then rounding). */
+int lpdt_quantize(const float *x, size_t len, int rounding, uint64_t seed, uint64_t offset,
+                  int8_t *q, float *scale, void *ws, size_t ws_bytes, void *stream);
+
+/* Same, but the abs-max is supplied by the producer of x (one fp32 in device
+ * memory, e.g. written by lpdt_range_evonorm_fwd / _bwd): one pass over x. */
+int lpdt_quantize_with_absmax(const float *x, size_t len, const float *absmax, int rounding,
+                              uint64_t seed, uint64_t offset, int8_t *q, float *scale, void *stream);
+
+/* y_i = (sA*sB) * acc_i, the real value of an int32 accumulator of two quantized
+ * tensors; sA, sB: device scalars.  If accumulate != 0, y_i += that value. */
+int lpdt_dequantize(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y,
+                    int accumulate, void *stream);
+
+/* --------------------------------------------------------------- convolutions
+ * Table "hardware_training", row Conv: the forward product and the two
+ * backward products of a convolution layer, on int8 codes with exact int32
+ * accumulation (cross-correlation, zero padding, dilation 1, one group).
+ * Output size P = (H + 2*pad_h - R)/stride_h + 1, Q likewise.
+ * Linear layers are the case R = S = H = W = 1.
+ * The exact sums must fit int32 (always true when the reduction length is
+ * <= 133144; see the bound in the design notes); no saturation is applied.
+ */
+typedef struct {
+    int N, C, H, W;       /* input: batch, channels, height, width */
+    int K, R, S;          /* filter: output channels, taps */
+    int stride_h, stride_w, pad_h, pad_w;
+} lpdt_conv_desc;
+
+size_t lpdt_qconv_fwd_workspace_bytes(const lpdt_conv_desc *d);
+size_t lpdt_qconv_bwd_data_workspace_bytes(const lpdt_conv_desc *d);
+size_t lpdt_qconv_bwd_weight_workspace_bytes(const lpdt_conv_desc *d);
+
+/* acc[n,p,q,k] = sum_{r,s,c} xq[n, p*stride_h+r-pad_h, q*stride_w+s-pad_w, c] * wq[k,r,s,c]
+ * xq int8 [N,H,W,C]; wq int8 [K,R,S,C]; acc int32 [N,P,Q,K], overwritten. */
+int lpdt_qconv_fwd(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, int32_t *acc,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/* dx[n,h,w,c] = sum over (p,q,r,s,k) with p*stride_h+r-pad_h == h, q*stride_w+s-pad_w == w
+ *               of gq[n,p,q,k] * wq[k,r,s,c]
+ * gq int8 [N,P,Q,K] (8-bit layer gradient); dx int32 [N,H,W,C], overwritten. */
+int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, int32_t *dx,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* dw[k,r,s,c] = sum_{n,p,q} gq[n,p,q,k] * xq[n, p*stride_h+r-pad_h, q*stride_w+s-pad_w, c]
+ * dw int32 [K,R,S,C], overwritten.  (The weight gradient leaves the library as
+ * fp32 after lpdt_dequantize and is never re-quantized: gradient bifurcation.) */
+int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------ Range-EvoNorm
+ * Eq. "ren": for every sample n and channel group G (m = C/groups channels),
+ *   range = max - min of x over the group's (h, w, channel) slab
+ *   D     = C(m)*range + eps,  C(m) = 1/sqrt(2 ln m)
+ *   y     = gamma_c * x * hardsigmoid(v_c * x) / D + beta_c,
+ *   hardsigmoid(z) = max(0, min(1, (z+3)/6)).
+ * fp32 arithmetic.  groups must divide C and m must be >= 2 (C(1) is infinite):
+ * otherwise LPDT_EUNSUPPORTED.  eps = 0 is allowed.
+ */
+size_t lpdt_range_evonorm_fwd_workspace_bytes(int N, int H, int W, int C, int groups);
+size_t lpdt_range_evonorm_bwd_workspace_bytes(int N, int H, int W, int C, int groups);
+
+/* x, y fp32 [N,H,W,C]; v, gamma, beta fp32 [C].
+ * Saved for the backward pass, each [N*groups]: range_out (max - min), argmax_out /
+ * argmin_out = position of the first maximum / minimum inside the slab, counted as
+ * (h*W + w)*m + channel_in_group (lowest such index on ties).
+ * absmax_out: optional (may be NULL) fp32 scalar, set to max|y| for a following
+ * lpdt_quantize_with_absmax. */
+int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                           const float *gamma, const float *beta, float eps, float *y,
+                           float *range_out, int32_t *argmax_out, int32_t *argmin_out,
+                           float *absmax_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Gradient of the forward above.  dy, x, dx fp32 [N,H,W,C]; range/argmax/argmin as
+ * saved by the forward.  The hard-sigmoid slope is 1/6 strictly inside (-3,3), else 0;
+ * the gradient through the range goes entirely to the saved arg-max (+) and arg-min (-).
+ * dv, dgamma, dbeta fp32 [C] are overwritten (not accumulated).  Results do not depend
+ * on launch geometry or run (fixed-order reductions).
+ * absmax_out: optional fp32 scalar, set to max|dx|. */
+int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W, int C, int groups,
+                           const float *v, const float *gamma, float eps, const float *range,
+                           const int32_t *argmax, const int32_t *argmin, float *dx, float *dv,
+                           float *dgamma, float *dbeta, float *absmax_out, void *ws, size_t ws_bytes,
+                           void *stream);
+
+/* ------------------------------------------------------------------- gossip
+ * Algorithm 1 step 7 for n agents whose parameter vectors are the rows of x.
+ *   xhat == NULL (plain, D-PSGD / Algorithm 2 without compression):
+ *       x_i <- x_i + rate * ( sum_j W_ij x_j - x_i )
+ *   xhat != NULL (CHOCO-SGD, supplement Algorithm 3), per agent i and segment:
+ *       v = x_i - xhat_i ;  q = v on the k entries of largest |v|, 0 elsewhere,
+ *       k = max(1, ceil(keep_ratio*len)), ties resolved towards the lower index,
+ *       |v| compared by fp32 bit pattern ;  xhat_i <- xhat_i + q  for all i ;  then
+ *       x_i <- x_i + rate * sum_j W_ij (xhat_j - xhat_i).
+ * W: HOST pointer, row-major [n][n], W[i*n+j] = weight node i gives node j's model;
+ * read during the call (not retained).  Limits: n <= 64 and at most 8 non-zeros per
+ * row, else LPDT_EUNSUPPORTED.  seg_offsets: HOST pointer, nseg+1 increasing offsets
+ * with seg_offsets[0] = 0 and seg_offsets[nseg] = d (the layers of the model, for
+ * layer-wise top-k); NULL / nseg = 0 means one segment [0,d).  Each segment must be
+ * shorter than 2^31 elements.  x (and xhat) are updated in place.
+ */
+size_t lpdt_gossip_mix_workspace_bytes(int n, size_t d, int nseg, int choco);
+
+int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const float *W, float rate,
+                    double keep_ratio, const int64_t *seg_offsets, int nseg, void *ws, size_t ws_bytes,
+                    void *stream);
+
+/* --------------------------------------------------------------------- glue
+ * Table "hardware_training", rows Skip Connections and Average Pool, plus the
+ * max-pool, loss and local SGD step (Algorithm 1 step 3) of the benchmark
+ * networks.  All fp32, NHWC. */
+
+/* y = a + b (y may alias a or b). */
+int lpdt_add(const float *a, const float *b, size_t len, float *y, void *stream);
+
+/* k x k window, stride st, padding pd (padding never wins).  idx[n,p,q,c] = h*W+w of the
+ * winner (first in window scan order on ties). */
+int lpdt_maxpool_fwd(const float *x, int N, int H, int W, int C, int k, int st, int pd, float *y,
+                     int32_t *idx, void *stream);
+/* dx[N,H,W,C] is overwritten: zero, then dx[n, idx, c] += dy[n,p,q,c]. */
+int lpdt_maxpool_bwd(const float *dy, const int32_t *idx, int N, int H, int W, int C, int k, int st,
+                     int pd, float *dx, void *stream);
+
+/* global average pool: y[n,c] = mean over h,w ; dx[n,h,w,c] = dy[n,c]/(H*W). */
+int lpdt_avgpool_fwd(const float *x, int N, int HW, int C, float *y, void *stream);
+int lpdt_avgpool_bwd(const float *dy, int N, int HW, int C, float *dx, void *stream);
+
+/* loss[0] = mean_n -log softmax(logits[n])[labels[n]] ; dlogits = (softmax - onehot)/N.
+ * logits, dlogits fp32 [N,classes] (classes <= 1024); labels int32 [N] in [0,classes).
+ * loss must have room for 1 + N floats: loss[1..N] receive the per-sample losses. */
+int lpdt_softmax_xent(const float *logits, const int32_t *labels, int N, int classes, float *loss,
+                      float *dlogits, void *stream);
+
+/* x <- x - lr*g. */
+int lpdt_sgd(float *x, const float *g, size_t len, float lr, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPDT_H */

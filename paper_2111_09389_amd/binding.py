@@ -1,0 +1,306 @@
+"""ctypes binding of liblpdt.so with the same names as the C entry points."""
+import ctypes
+import os
+
+import torch
+
+__all__ = [
+    "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
+    "quantize", "quantize_with_absmax", "dequantize",
+    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight",
+    "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix",
+    "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
+    "Workspace", "EXPORTS",
+]
+
+ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblpdt.so")
+
+# every symbol include/lpdt.h declares
+EXPORTS = [
+    "lpdt_last_error", "lpdt_version",
+    "lpdt_quantize_workspace_bytes", "lpdt_quantize", "lpdt_quantize_with_absmax", "lpdt_dequantize",
+    "lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes", "lpdt_qconv_bwd_weight_workspace_bytes",
+    "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
+    "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
+    "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
+    "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix",
+    "lpdt_add", "lpdt_maxpool_fwd", "lpdt_maxpool_bwd", "lpdt_avgpool_fwd", "lpdt_avgpool_bwd",
+    "lpdt_softmax_xent", "lpdt_sgd",
+]
+
+
+class LpdtError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"lpdt error {code}: {message}")
+        self.code = code
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of lpdt_conv_desc."""
+    _fields_ = [(k, ctypes.c_int) for k in
+                ("N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+    @classmethod
+    def make(cls, N, C, H, W, K, R, S, stride=1, pad=0):
+        return cls(N, C, H, W, K, R, S, stride, stride, pad, pad)
+
+    @property
+    def P(self):
+        return (self.H + 2 * self.pad_h - self.R) // self.stride_h + 1
+
+    @property
+    def Q(self):
+        return (self.W + 2 * self.pad_w - self.S) // self.stride_w + 1
+
+
+_lib = None
+_sz = ctypes.c_size_t
+_vp = ctypes.c_void_p
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Loads liblpdt.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise LpdtError(-100, f"{_LIB_PATH} is missing: run `python -m paper_2111_09389_amd.build` "
+                                  "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.lpdt_last_error.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name.endswith("_workspace_bytes"):
+                getattr(L, name).restype = _sz
+        L.lpdt_quantize_workspace_bytes.argtypes = [_sz]
+        for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
+                     "lpdt_qconv_bwd_weight_workspace_bytes"):
+            getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
+        for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes"):
+            getattr(L, name).argtypes = [ctypes.c_int] * 5
+        L.lpdt_gossip_mix_workspace_bytes.argtypes = [ctypes.c_int, _sz, ctypes.c_int, ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise LpdtError(rc, lib().lpdt_last_error().decode())
+
+
+def _ptr(t):
+    return _vp(0) if t is None else _vp(t.data_ptr())
+
+
+def _stream():
+    return _vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise LpdtError(-1, f"{what}: expected a contiguous CUDA tensor of dtype {dtype}")
+    return t
+
+
+class Workspace:
+    """A caller-owned scratch buffer that grows on demand (allocation happens here, in Python,
+    never inside the library)."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.buf = None
+
+    def get(self, nbytes):
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=self.device)
+        off = (-self.buf.data_ptr()) % 256
+        return self.buf[off:], self.buf.numel() - off
+
+
+_default_ws = None
+
+
+def _ws(ws, nbytes):
+    global _default_ws
+    if ws is None:
+        if _default_ws is None:
+            _default_ws = Workspace()
+        ws = _default_ws
+    return ws.get(nbytes)
+
+
+# ---------------------------------------------------------------- quantizer
+def quantize(x, rounding=ROUND_NEAREST, seed=0, offset=0, q=None, scale=None, ws=None):
+    """x fp32 -> (int8 codes of x's shape, fp32 device scalar scale)."""
+    _dev(x, torch.float32, "quantize x")
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device) if q is None else q
+    scale = torch.empty(1, dtype=torch.float32, device=x.device) if scale is None else scale
+    n = x.numel()
+    buf, nb = _ws(ws, lib().lpdt_quantize_workspace_bytes(n))
+    _check(lib().lpdt_quantize(_ptr(x), _sz(n), int(rounding), ctypes.c_uint64(seed), ctypes.c_uint64(offset),
+                               _ptr(q), _ptr(scale), _ptr(buf), _sz(nb), _stream()))
+    return q, scale
+
+
+def quantize_with_absmax(x, absmax, rounding=ROUND_NEAREST, seed=0, offset=0, q=None, scale=None):
+    _dev(x, torch.float32, "quantize x")
+    _dev(absmax, torch.float32, "quantize absmax")
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device) if q is None else q
+    scale = torch.empty(1, dtype=torch.float32, device=x.device) if scale is None else scale
+    _check(lib().lpdt_quantize_with_absmax(_ptr(x), _sz(x.numel()), _ptr(absmax), int(rounding), ctypes.c_uint64(seed),
+                                           ctypes.c_uint64(offset), _ptr(q), _ptr(scale), _stream()))
+    return q, scale
+
+
+def dequantize(acc, sA, sB, y=None, accumulate=False):
+    _dev(acc, torch.int32, "dequantize acc")
+    y = torch.empty(acc.shape, dtype=torch.float32, device=acc.device) if y is None else y
+    _check(lib().lpdt_dequantize(_ptr(acc), _sz(acc.numel()), _ptr(sA), _ptr(sB), _ptr(y), int(bool(accumulate)), _stream()))
+    return y
+
+
+# ---------------------------------------------------------------- convolutions
+def qconv_fwd(d, xq, wq, acc=None, ws=None):
+    _dev(xq, torch.int8, "qconv_fwd xq"); _dev(wq, torch.int8, "qconv_fwd wq")
+    assert tuple(xq.shape) == (d.N, d.H, d.W, d.C) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    acc = torch.empty((d.N, d.P, d.Q, d.K), dtype=torch.int32, device=xq.device) if acc is None else acc
+    buf, nb = _ws(ws, lib().lpdt_qconv_fwd_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_fwd(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(acc), _ptr(buf), _sz(nb), _stream()))
+    return acc
+
+
+def qconv_bwd_data(d, gq, wq, dx=None, ws=None):
+    _dev(gq, torch.int8, "qconv_bwd_data gq"); _dev(wq, torch.int8, "qconv_bwd_data wq")
+    assert tuple(gq.shape) == (d.N, d.P, d.Q, d.K) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    dx = torch.empty((d.N, d.H, d.W, d.C), dtype=torch.int32, device=gq.device) if dx is None else dx
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_data_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_data(ctypes.byref(d), _ptr(gq), _ptr(wq), _ptr(dx), _ptr(buf), _sz(nb), _stream()))
+    return dx
+
+
+def qconv_bwd_weight(d, gq, xq, dw=None, ws=None):
+    _dev(gq, torch.int8, "qconv_bwd_weight gq"); _dev(xq, torch.int8, "qconv_bwd_weight xq")
+    assert tuple(gq.shape) == (d.N, d.P, d.Q, d.K) and tuple(xq.shape) == (d.N, d.H, d.W, d.C)
+    dw = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.int32, device=gq.device) if dw is None else dw
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_weight_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_weight(ctypes.byref(d), _ptr(gq), _ptr(xq), _ptr(dw), _ptr(buf), _sz(nb), _stream()))
+    return dw
+
+
+# ---------------------------------------------------------------- Range-EvoNorm
+def range_evonorm_fwd(x, groups, v, gamma, beta, eps=1e-5, y=None, want_absmax=False, ws=None):
+    """-> (y, range [N,groups], argmax, argmin[, absmax])."""
+    _dev(x, torch.float32, "range_evonorm_fwd x")
+    N, H, W, C = x.shape
+    dev = x.device
+    y = torch.empty_like(x) if y is None else y
+    rng = torch.empty((N, groups), dtype=torch.float32, device=dev)
+    amx = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    amn = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    absmax = torch.empty(1, dtype=torch.float32, device=dev) if want_absmax else None
+    buf, nb = _ws(ws, lib().lpdt_range_evonorm_fwd_workspace_bytes(N, H, W, C, groups))
+    _check(lib().lpdt_range_evonorm_fwd(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta),
+                                        ctypes.c_float(eps), _ptr(y), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(absmax),
+                                        _ptr(buf), _sz(nb), _stream()))
+    return (y, rng, amx, amn, absmax) if want_absmax else (y, rng, amx, amn)
+
+
+def range_evonorm_bwd(dy, x, groups, v, gamma, rng, amx, amn, eps=1e-5, dx=None, want_absmax=False, ws=None):
+    """-> (dx, dv, dgamma, dbeta[, absmax])."""
+    _dev(x, torch.float32, "range_evonorm_bwd x"); _dev(dy, torch.float32, "range_evonorm_bwd dy")
+    N, H, W, C = x.shape
+    dev = x.device
+    dx = torch.empty_like(x) if dx is None else dx
+    dv, dg, db = (torch.empty(C, dtype=torch.float32, device=dev) for _ in range(3))
+    absmax = torch.empty(1, dtype=torch.float32, device=dev) if want_absmax else None
+    buf, nb = _ws(ws, lib().lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, groups))
+    _check(lib().lpdt_range_evonorm_bwd(_ptr(dy), _ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma),
+                                        ctypes.c_float(eps), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(dx), _ptr(dv), _ptr(dg),
+                                        _ptr(db), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
+    return (dx, dv, dg, db, absmax) if want_absmax else (dx, dv, dg, db)
+
+
+# ---------------------------------------------------------------- gossip
+def gossip_mix(x, xhat, W, rate=1.0, keep_ratio=1.0, seg_offsets=None, ws=None):
+    """In-place gossip step on x [n,d] (and xhat for CHOCO).  W: host matrix (numpy / nested list / CPU tensor)."""
+    _dev(x, torch.float32, "gossip_mix x")
+    n, d = x.shape
+    if xhat is not None:
+        _dev(xhat, torch.float32, "gossip_mix xhat")
+        assert tuple(xhat.shape) == (n, d)
+    Wh = torch.as_tensor(W, dtype=torch.float32, device="cpu").contiguous()
+    assert tuple(Wh.shape) == (n, n)
+    Wc = (ctypes.c_float * (n * n)).from_buffer_copy(Wh.numpy().tobytes())
+    if seg_offsets is None:
+        seg, nseg = None, 0
+    else:
+        so = [int(v) for v in seg_offsets]
+        seg, nseg = (ctypes.c_int64 * len(so))(*so), len(so) - 1
+    buf, nb = _ws(ws, lib().lpdt_gossip_mix_workspace_bytes(n, _sz(d), nseg, int(xhat is not None)))
+    _check(lib().lpdt_gossip_mix(_ptr(x), _ptr(xhat), n, _sz(d), Wc, ctypes.c_float(rate), ctypes.c_double(keep_ratio),
+                                 seg, nseg, _ptr(buf), _sz(nb), _stream()))
+    return x, xhat
+
+
+# ---------------------------------------------------------------- glue
+def add(a, b, y=None):
+    _dev(a, torch.float32, "add a"); _dev(b, torch.float32, "add b")
+    y = torch.empty_like(a) if y is None else y
+    _check(lib().lpdt_add(_ptr(a), _ptr(b), _sz(a.numel()), _ptr(y), _stream()))
+    return y
+
+
+def maxpool_fwd(x, k, stride, pad):
+    _dev(x, torch.float32, "maxpool_fwd x")
+    N, H, W, C = x.shape
+    P, Q = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    y = torch.empty((N, P, Q, C), dtype=torch.float32, device=x.device)
+    idx = torch.empty((N, P, Q, C), dtype=torch.int32, device=x.device)
+    _check(lib().lpdt_maxpool_fwd(_ptr(x), N, H, W, C, k, stride, pad, _ptr(y), _ptr(idx), _stream()))
+    return y, idx
+
+
+def maxpool_bwd(dy, idx, in_shape, k, stride, pad):
+    _dev(dy, torch.float32, "maxpool_bwd dy"); _dev(idx, torch.int32, "maxpool_bwd idx")
+    N, H, W, C = in_shape
+    dx = torch.empty(in_shape, dtype=torch.float32, device=dy.device)
+    _check(lib().lpdt_maxpool_bwd(_ptr(dy), _ptr(idx), N, H, W, C, k, stride, pad, _ptr(dx), _stream()))
+    return dx
+
+
+def avgpool_fwd(x):
+    _dev(x, torch.float32, "avgpool_fwd x")
+    N, H, W, C = x.shape
+    y = torch.empty((N, C), dtype=torch.float32, device=x.device)
+    _check(lib().lpdt_avgpool_fwd(_ptr(x), N, H * W, C, _ptr(y), _stream()))
+    return y
+
+
+def avgpool_bwd(dy, in_shape):
+    _dev(dy, torch.float32, "avgpool_bwd dy")
+    N, H, W, C = in_shape
+    dx = torch.empty(in_shape, dtype=torch.float32, device=dy.device)
+    _check(lib().lpdt_avgpool_bwd(_ptr(dy), N, H * W, C, _ptr(dx), _stream()))
+    return dx
+
+
+def softmax_xent(logits, labels):
+    """-> (loss buffer [1+N]: mean loss then per-sample losses, dlogits)."""
+    _dev(logits, torch.float32, "softmax_xent logits"); _dev(labels, torch.int32, "softmax_xent labels")
+    N, classes = logits.shape
+    loss = torch.empty(1 + N, dtype=torch.float32, device=logits.device)
+    dl = torch.empty_like(logits)
+    _check(lib().lpdt_softmax_xent(_ptr(logits), _ptr(labels), N, classes, _ptr(loss), _ptr(dl), _stream()))
+    return loss, dl
+
+
+def sgd(x, g, lr):
+    _dev(x, torch.float32, "sgd x"); _dev(g, torch.float32, "sgd g")
+    _check(lib().lpdt_sgd(_ptr(x), _ptr(g), _sz(x.numel()), ctypes.c_float(lr), _stream()))
+    return x

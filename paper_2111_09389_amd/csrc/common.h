@@ -1,0 +1,42 @@
+// Shared host/device helpers of the lpdt HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/lpdt.h"
+
+namespace lpdt {
+
+// Records a thread-local message and returns `code`.
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+// Checks hipGetLastError() after a launch.
+int launch_status(const char *what);
+
+static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int conv_out(int in, int pad, int filt, int stride) { return (in + 2 * pad - filt) / stride + 1; }
+
+// Validates a convolution descriptor; on success fills P, Q.
+int check_conv(const lpdt_conv_desc *d, int *P, int *Q);
+int check_ws(const void *ws, size_t ws_bytes, size_t need);
+
+#define LPDT_REQUIRE(cond, code, ...) \
+    do { if (!(cond)) return ::lpdt::fail(code, __VA_ARGS__); } while (0)
+
+constexpr int kWave = 64;
+
+// ---- device helpers --------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace lpdt

@@ -1,0 +1,406 @@
+// Gossip step of Algorithm 1 (step 7) for n agents simulated on one GPU:
+// plain neighbourhood averaging and CHOCO-SGD (supplement Algorithm 3) with
+// exact layer-wise top-k of |x - xhat|.  Everything is HBM-bound streaming.
+//
+// Mixing: one thread owns one parameter column e and holds all n agents' values
+// of it in registers, so the in-place update has no cross-thread hazard and each
+// row is read once and written once.
+//
+// Top-k: MSB-first radix select on the 64-bit key (|v| bit pattern << 32 | ~index
+// inside the segment).  Keys are unique, so "key >= k-th largest key" selects
+// exactly k entries and resolves ties towards the lower index.  Pass 1 histograms
+// the top 12 key bits over the full data; pass 2 copies the keys that fall in the
+// threshold bin (a fraction of a percent of the data for smooth distributions) to
+// a candidate list; the remaining 51 bits are resolved on the candidates only.
+#include "common.h"
+#include <cmath>
+#include <cstring>
+#include <type_traits>
+#include <vector>
+
+namespace lpdt {
+
+constexpr int kMaxAgents = 64;
+constexpr int kMaxDeg = 8;
+constexpr int kGThreads = 256;
+constexpr int kTile = 4096;        // elements per block in the full-data passes
+constexpr int kCandTile = 65536;   // candidate slots per block in the candidate passes
+constexpr int kBins = 8192;        // histogram bins per (agent, segment)
+constexpr int kUploadChunk = 384;  // int64 values per upload launch (kernel-argument space)
+
+struct MixGraph {  // sparse rows of W, passed by value
+    float w[kMaxAgents][kMaxDeg];
+    uint8_t nbr[kMaxAgents][kMaxDeg];
+    uint8_t deg[kMaxAgents];
+};
+
+struct UploadChunk { long long v[kUploadChunk]; };
+
+struct PairState {        // one per (agent, segment)
+    unsigned long long prefix;  // key bits fixed so far (right aligned); finally the threshold key
+    unsigned int rank;          // the wanted key is the rank-th largest among keys matching prefix
+    unsigned int cand;          // candidates stored
+};
+
+// ---- plain mix ---------------------------------------------------------------
+template <int NMAX>
+__global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict__ x, int n, size_t d, MixGraph g, float rate) {
+    // column values staged in LDS: neighbour ids are run-time values, and LDS takes a
+    // run-time row index where registers cannot.  Each thread touches its own column only.
+    __shared__ float sv[NMAX][kGThreads];
+    const size_t e = (size_t)blockIdx.x * kGThreads + threadIdx.x;
+    if (e >= d) return;
+    for (int i = 0; i < n; ++i) sv[i][threadIdx.x] = x[(size_t)i * d + e];
+    for (int i = 0; i < n; ++i) {
+        const float vi = sv[i][threadIdx.x];
+        float s = 0.0f;
+        for (int t = 0; t < g.deg[i]; ++t) s += g.w[i][t] * sv[g.nbr[i][t]][threadIdx.x];
+        x[(size_t)i * d + e] = vi + rate * (s - vi);
+    }
+}
+
+// ---- CHOCO: set-up -----------------------------------------------------------
+__global__ void upload_kernel(UploadChunk c, long long *dst, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = c.v[i];
+}
+
+__global__ void choco_init_kernel(PairState *st, const long long *kk, int n, int nseg, unsigned int *hist, size_t hist_words) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < hist_words) hist[i] = 0u;
+    if (i < (size_t)n * nseg) {
+        PairState s;
+        s.prefix = 0ull;
+        s.rank = (unsigned int)kk[i % nseg];
+        s.cand = 0u;
+        st[i] = s;
+    }
+}
+
+__device__ __forceinline__ int find_segment(const long long *off, int nseg, long long e) {
+    int lo = 0, hi = nseg - 1;  // largest s with off[s] <= e
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ unsigned long long make_key(float xv, float hv, unsigned int idx_in_seg) {
+    const float v = __fsub_rn(xv, hv);
+    return ((unsigned long long)(__float_as_uint(v) & 0x7fffffffu) << 32) | (unsigned long long)(~idx_in_seg);
+}
+
+// Pass 1: histogram of key bits 62..51 (the top 12 bits of |v|).
+__global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
+                                                               size_t d, const long long *__restrict__ off, int nseg,
+                                                               unsigned int *__restrict__ hist) {
+    __shared__ unsigned int sh[4096];
+    __shared__ int s_first;
+    const int agent = blockIdx.y;
+    const long long e0 = (long long)blockIdx.x * kTile;
+    const long long e1 = min(e0 + (long long)kTile, (long long)d);
+    for (int i = threadIdx.x; i < 4096; i += kGThreads) sh[i] = 0u;
+    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    __syncthreads();
+    const int sfirst = s_first;
+    int s = sfirst;
+    const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
+    for (long long e = e0 + threadIdx.x; e < e1; e += kGThreads) {
+        while (e >= off[s + 1]) ++s;
+        const unsigned int bin = (__float_as_uint(__fsub_rn(xr[e], hr[e])) & 0x7fffffffu) >> 19;
+        if (s == sfirst) atomicAdd(&sh[bin], 1u);
+        else atomicAdd(&hist[((size_t)agent * nseg + s) * kBins + bin], 1u);
+    }
+    __syncthreads();
+    unsigned int *gh = hist + ((size_t)agent * nseg + sfirst) * kBins;
+    for (int i = threadIdx.x; i < 4096; i += kGThreads)
+        if (sh[i]) atomicAdd(&gh[i], sh[i]);
+}
+
+// Finds, per (agent, segment), the bin holding the rank-th largest key; extends the
+// prefix by `bits`, reduces the rank to the rank inside that bin, clears the histogram.
+__global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__restrict__ st, unsigned int *__restrict__ hist, int bits) {
+    __shared__ unsigned int part[kGThreads];
+    __shared__ unsigned int s_above;
+    __shared__ int s_thread;
+    const int pair = blockIdx.x;
+    unsigned int *h = hist + (size_t)pair * kBins;
+    const int nb = 1 << bits, per = kBins / kGThreads;  // thread t owns bins [hi - per*t - per + 1, hi - per*t], descending
+    const unsigned int rank = st[pair].rank;
+    if (rank == 0u) {  // empty segment: nothing to select
+        for (int i = threadIdx.x; i < kBins; i += kGThreads) h[i] = 0u;
+        if (threadIdx.x == 0) st[pair].prefix = ~0ull;
+        return;
+    }
+    unsigned int mine[kBins / kGThreads];
+    unsigned int sum = 0;
+    for (int k = 0; k < per; ++k) {
+        const int b = kBins - 1 - (threadIdx.x * per + k);
+        mine[k] = (b < nb) ? h[b] : 0u;
+        sum += mine[k];
+    }
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned int run = 0;
+        int t = 0;
+        for (; t < kGThreads; ++t) {
+            if (run + part[t] >= rank) break;
+            run += part[t];
+        }
+        s_above = run;
+        s_thread = t;  // t < kGThreads because the matching keys number at least rank
+    }
+    __syncthreads();
+    if ((int)threadIdx.x == s_thread) {
+        unsigned int run = s_above;
+        for (int k = 0; k < per; ++k) {
+            if (run + mine[k] >= rank) {
+                const int b = kBins - 1 - (threadIdx.x * per + k);
+                st[pair].prefix = (st[pair].prefix << bits) | (unsigned long long)b;
+                st[pair].rank = rank - run;
+                break;
+            }
+            run += mine[k];
+        }
+    }
+    for (int i = threadIdx.x; i < kBins; i += kGThreads) h[i] = 0u;
+}
+
+// Pass 2: copy the keys whose top 12 bits equal the prefix to the candidate list of
+// their (agent, segment); the list lives at the segment's own offset in `cand`.
+__global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
+                                                                  size_t d, const long long *__restrict__ off, int nseg,
+                                                                  PairState *__restrict__ st,
+                                                                  unsigned long long *__restrict__ cand) {
+    __shared__ int s_first;
+    const int agent = blockIdx.y;
+    const long long e0 = (long long)blockIdx.x * kTile;
+    const long long e1 = min(e0 + (long long)kTile, (long long)d);
+    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    __syncthreads();
+    int s = s_first;
+    const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
+    for (long long e = e0 + threadIdx.x; e < e1; e += kGThreads) {
+        while (e >= off[s + 1]) ++s;
+        const unsigned long long key = make_key(xr[e], hr[e], (unsigned int)(e - off[s]));
+        PairState *ps = &st[(size_t)agent * nseg + s];
+        if ((key >> 51) == ps->prefix) {
+            const unsigned int slot = atomicAdd(&ps->cand, 1u);
+            cand[(size_t)agent * d + off[s] + slot] = key;
+        }
+    }
+}
+
+// Candidate pass: histogram of key bits [shift, shift+bits) among candidates that match the prefix.
+__global__ __launch_bounds__(kGThreads) void choco_cand_hist_kernel(const unsigned long long *__restrict__ cand, size_t d,
+                                                                    const long long *__restrict__ off, int nseg,
+                                                                    const PairState *__restrict__ st, int shift, int bits,
+                                                                    unsigned int *__restrict__ hist) {
+    __shared__ int s_first;
+    const int agent = blockIdx.y;
+    const long long e0 = (long long)blockIdx.x * kCandTile;
+    const long long e1 = min(e0 + (long long)kCandTile, (long long)d);
+    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    __syncthreads();
+    const unsigned long long mask = (1ull << bits) - 1ull;
+    for (int s = s_first; s < nseg && off[s] < e1; ++s) {
+        const PairState ps = st[(size_t)agent * nseg + s];
+        const long long lo = max(off[s], e0), hi = min(off[s] + (long long)ps.cand, e1);
+        unsigned int *h = hist + ((size_t)agent * nseg + s) * kBins;
+        for (long long e = lo + threadIdx.x; e < hi; e += kGThreads) {
+            const unsigned long long key = cand[(size_t)agent * d + e];
+            if ((key >> (shift + bits)) == ps.prefix) atomicAdd(&h[(key >> shift) & mask], 1u);
+        }
+    }
+}
+
+// Final pass: xhat += top-k(x - xhat) for every agent, then the gossip update of x.
+template <int NMAX>
+__global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__restrict__ x, float *__restrict__ xhat, int n,
+                                                                    size_t d, const long long *__restrict__ off, int nseg,
+                                                                    const PairState *__restrict__ st, int select_all,
+                                                                    MixGraph g, float rate) {
+    __shared__ int s_first;
+    const long long e0 = (long long)blockIdx.x * kGThreads;
+    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    __syncthreads();
+    const long long e = e0 + threadIdx.x;
+    if (e >= (long long)d) return;
+    int s = s_first;
+    while (e >= off[s + 1]) ++s;
+    const unsigned int idx = (unsigned int)(e - off[s]);
+    __shared__ float sh[NMAX][kGThreads];  // this thread's column of xhat (after the update)
+    float xv[NMAX];
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i)
+        if (i < n) {
+            xv[i] = x[(size_t)i * d + e];
+            float hv = xhat[(size_t)i * d + e];
+            const unsigned long long key = make_key(xv[i], hv, idx);
+            const bool sel = select_all || key >= st[(size_t)i * nseg + s].prefix;
+            if (sel) {
+                hv = __fadd_rn(hv, __fsub_rn(xv[i], hv));
+                xhat[(size_t)i * d + e] = hv;
+            }
+            sh[i][threadIdx.x] = hv;
+        }
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i)
+        if (i < n) {
+            const float hi = sh[i][threadIdx.x];
+            float sum = 0.0f;
+            for (int t = 0; t < g.deg[i]; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][threadIdx.x] - hi);
+            x[(size_t)i * d + e] = xv[i] + rate * sum;
+        }
+}
+
+struct ChocoLayout {
+    size_t off_bytes, k_bytes, state_bytes, hist_bytes, cand_bytes, total;
+};
+static ChocoLayout choco_layout(int n, size_t d, int nseg) {
+    ChocoLayout L;
+    L.off_bytes = round_up((size_t)(nseg + 1) * sizeof(long long), 256);
+    L.k_bytes = round_up((size_t)nseg * sizeof(long long), 256);
+    L.state_bytes = round_up((size_t)n * nseg * sizeof(PairState), 256);
+    L.hist_bytes = round_up((size_t)n * nseg * kBins * sizeof(unsigned int), 256);
+    L.cand_bytes = round_up((size_t)n * d * sizeof(unsigned long long), 256);
+    L.total = L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes + L.cand_bytes;
+    return L;
+}
+
+static int build_graph(const float *W, int n, MixGraph *g) {
+    for (int i = 0; i < n; ++i) {
+        int deg = 0;
+        double row = 0.0;
+        for (int j = 0; j < n; ++j) {
+            const float w = W[(size_t)i * n + j];
+            LPDT_REQUIRE(std::isfinite(w) && w >= 0.0f && w <= 1.0f, LPDT_EINVAL,
+                         "gossip_mix: W[%d][%d] = %g is outside [0,1]", i, j, (double)w);
+            row += w;
+            if (w != 0.0f) {
+                LPDT_REQUIRE(deg < kMaxDeg, LPDT_EUNSUPPORTED, "gossip_mix: row %d of W has more than %d non-zeros", i, kMaxDeg);
+                g->w[i][deg] = w;
+                g->nbr[i][deg] = (uint8_t)j;
+                ++deg;
+            }
+        }
+        LPDT_REQUIRE(std::fabs(row - 1.0) <= 1e-5, LPDT_EINVAL, "gossip_mix: row %d of W sums to %.8f, not 1", i, row);
+        g->deg[i] = (uint8_t)deg;
+    }
+    for (int j = 0; j < n; ++j) {
+        double col = 0.0;
+        for (int i = 0; i < n; ++i) col += W[(size_t)i * n + j];
+        LPDT_REQUIRE(std::fabs(col - 1.0) <= 1e-5, LPDT_EINVAL,
+                     "gossip_mix: column %d of W sums to %.8f, not 1 (W must be doubly stochastic)", j, col);
+    }
+    return LPDT_OK;
+}
+
+template <typename F>
+static void dispatch_nmax(int n, F f) {
+    if (n <= 8) f(std::integral_constant<int, 8>());
+    else if (n <= 16) f(std::integral_constant<int, 16>());
+    else if (n <= 32) f(std::integral_constant<int, 32>());
+    else f(std::integral_constant<int, 64>());
+}
+
+static void upload(const long long *src, int count, long long *dst, hipStream_t st) {
+    for (int o = 0; o < count; o += kUploadChunk) {
+        UploadChunk c;
+        const int m = count - o < kUploadChunk ? count - o : kUploadChunk;
+        for (int i = 0; i < m; ++i) c.v[i] = src[o + i];
+        hipLaunchKernelGGL(upload_kernel, dim3((m + 127) / 128), dim3(128), 0, st, c, dst + o, m);
+    }
+}
+
+}  // namespace lpdt
+
+using namespace lpdt;
+
+extern "C" size_t lpdt_gossip_mix_workspace_bytes(int n, size_t d, int nseg, int choco) {
+    if (!choco || n <= 0 || d == 0) return 0;
+    if (nseg <= 0) nseg = 1;
+    return choco_layout(n, d, nseg).total;
+}
+
+extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const float *W, float rate, double keep_ratio,
+                               const int64_t *seg_offsets, int nseg, void *ws, size_t ws_bytes, void *stream) {
+    LPDT_REQUIRE(x && W, LPDT_EINVAL, "gossip_mix: x and W must be non-NULL");
+    LPDT_REQUIRE(n > 0 && d > 0, LPDT_EINVAL, "gossip_mix: n and d must be positive");
+    LPDT_REQUIRE(n <= kMaxAgents, LPDT_EUNSUPPORTED, "gossip_mix: at most %d agents", kMaxAgents);
+    LPDT_REQUIRE(std::isfinite(rate), LPDT_EINVAL, "gossip_mix: rate must be finite");
+    LPDT_REQUIRE((d + kGThreads - 1) / kGThreads <= 0x7fffffffull, LPDT_EUNSUPPORTED, "gossip_mix: d too large");
+    MixGraph g;
+    std::memset(&g, 0, sizeof(g));
+    int rc = build_graph(W, n, &g);
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    const unsigned int col_blocks = (unsigned int)((d + kGThreads - 1) / kGThreads);
+
+    if (!xhat) {
+        dispatch_nmax(n, [&](auto tag) {
+            constexpr int NMAX = decltype(tag)::value;
+            hipLaunchKernelGGL(mix_plain_kernel<NMAX>, dim3(col_blocks), dim3(kGThreads), 0, st, x, n, d, g, rate);
+        });
+        return launch_status("lpdt_gossip_mix");
+    }
+
+    LPDT_REQUIRE(keep_ratio > 0.0 && std::isfinite(keep_ratio), LPDT_EINVAL, "gossip_mix: keep_ratio must be positive");
+    std::vector<long long> off, kk;
+    if (!seg_offsets || nseg <= 0) {
+        nseg = 1;
+        off = {0, (long long)d};
+    } else {
+        off.assign(seg_offsets, seg_offsets + nseg + 1);
+        LPDT_REQUIRE(off[0] == 0 && off[nseg] == (long long)d, LPDT_EINVAL,
+                     "gossip_mix: seg_offsets must start at 0 and end at d");
+    }
+    bool select_all = true;
+    for (int s = 0; s < nseg; ++s) {
+        const long long len = off[s + 1] - off[s];
+        LPDT_REQUIRE(len >= 0, LPDT_EINVAL, "gossip_mix: seg_offsets must be non-decreasing");
+        LPDT_REQUIRE(len < 0x7fffffffLL, LPDT_EUNSUPPORTED, "gossip_mix: segment %d has 2^31-1 or more elements", s);
+        long long k = (long long)std::ceil(keep_ratio * (double)len);
+        if (k < 1) k = 1;
+        if (k > len) k = len;
+        if (k < len) select_all = false;
+        kk.push_back(k);
+    }
+    const ChocoLayout L = choco_layout(n, d, nseg);
+    rc = check_ws(ws, ws_bytes, L.total);
+    if (rc) return rc;
+    char *base = static_cast<char *>(ws);
+    long long *d_off = reinterpret_cast<long long *>(base);
+    long long *d_k = reinterpret_cast<long long *>(base + L.off_bytes);
+    PairState *d_st = reinterpret_cast<PairState *>(base + L.off_bytes + L.k_bytes);
+    unsigned int *d_hist = reinterpret_cast<unsigned int *>(base + L.off_bytes + L.k_bytes + L.state_bytes);
+    unsigned long long *d_cand =
+        reinterpret_cast<unsigned long long *>(base + L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes);
+
+    upload(off.data(), nseg + 1, d_off, st);
+    if (!select_all) {
+        upload(kk.data(), nseg, d_k, st);
+        const size_t hist_words = (size_t)n * nseg * kBins;
+        hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
+                           nseg, d_hist, hist_words);
+        const dim3 tiles((unsigned int)((d + kTile - 1) / kTile), n);
+        const dim3 ctiles((unsigned int)((d + kCandTile - 1) / kCandTile), n);
+        hipLaunchKernelGGL(choco_hist_kernel, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
+        hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12);
+        hipLaunchKernelGGL(choco_collect_kernel, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
+        const int shifts[4] = {38, 25, 12, 0}, widths[4] = {13, 13, 13, 12};
+        for (int p = 0; p < 4; ++p) {
+            hipLaunchKernelGGL(choco_cand_hist_kernel, ctiles, dim3(kGThreads), 0, st, d_cand, d, d_off, nseg, d_st, shifts[p],
+                               widths[p], d_hist);
+            hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, widths[p]);
+        }
+    }
+    dispatch_nmax(n, [&](auto tag) {
+        constexpr int NMAX = decltype(tag)::value;
+        hipLaunchKernelGGL(choco_apply_mix_kernel<NMAX>, dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg,
+                           d_st, select_all ? 1 : 0, g, rate);
+    });
+    return launch_status("lpdt_gossip_mix");
+}

@@ -1,0 +1,562 @@
+// int8 convolution forward, backward-data and backward-weight with exact int32
+// accumulation (Table "hardware_training", row Conv) as implicit GEMMs on the
+// gfx950 matrix cores (v_mfma_i32_32x32x32_i8), im2col-free.
+//
+//  forward / backward-data ("igemm"): out[m][j] = sum_{tap,c} in[pix(m,tap)][c] * wt[j][tap][c]
+//      m = output pixel, j = output channel.  The reduction axis is cut into 16-byte
+//      granules (16 channels of one filter tap); a K-step is 4 granules.  Both operands
+//      are gathered by 16-byte loads (zero for padding), staged through LDS in
+//      [granule][row][16 B] planes -- exactly the operand order of the MFMA, so every
+//      LDS read is a contiguous, conflict-free ds_read_b128 -- and double buffered.
+//      backward-data is the same kernel reading the gradient tensor with the
+//      transposed filter (built once per call in the workspace).
+//  backward-weight ("wgrad"): dw[k][tap][c] = sum_m g[m][k] * x[pix(m,tap)][c]
+//      the reduction runs over pixels, which is the strided axis of both NHWC operands.
+//      Tiles are staged in LDS in their natural [pixel][channel] order and read with
+//      the transposing LDS load (ds_read_b64_tr_b8), which hands each lane 8 pixels of
+//      one channel: the MFMA operand, with no transposed copy in memory.  One block
+//      accumulates all taps of a 3x3 filter for a 64x64 channel tile, so the gradient
+//      tile is loaded once for 9 products; blocks split the pixel range and combine
+//      with int32 atomic adds (exact, order-free).
+//  Shapes whose channel counts are not multiples of 16 take plain per-output kernels.
+#include "common.h"
+
+namespace lpdt {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kCThreads = 256;
+
+// ------------------------------------------------------------------ igemm
+struct IgemmParams {
+    const int8_t *in;   // [N][IH][IW][Cin]
+    const int8_t *wt;   // [Cout][R][S][Cin]
+    int32_t *out;       // [M][Cout], M = N*OH*OW
+    int M, Cin, Cout;
+    int IH, IW, OH, OW;
+    int R, S, stride, pad;
+    int gpt;            // granules per tap = Cin/16
+    int gtot;           // R*S*gpt
+    int nk;             // K-steps = ceil(gtot/4)
+    int k_per_split;    // K-steps per blockIdx.z
+    int atomic_out;     // combine splits with atomicAdd into a zeroed output
+    int tiles_n;
+};
+
+template <int BM, int BN, int WM, int WN, bool BWD>
+__global__ __launch_bounds__(kCThreads) void igemm_kernel(const IgemmParams p) {
+    constexpr int PLANE_A = BM * 16 + 64, PLANE_B = BN * 16 + 64;  // +64 B: the 4 planes start 16 banks apart
+    constexpr int BUF = 4 * (PLANE_A + PLANE_B);
+    constexpr int RA = BM / 64, RB = (BN + 63) / 64;               // 16-byte items per thread
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+
+    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
+    const int g4 = t % 4, row0 = t / 4;
+    const int tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int ks_begin = blockIdx.z * p.k_per_split;
+    const int ks_end = min(p.nk, ks_begin + p.k_per_split);
+
+    // this thread's output pixels (rows of the A tile)
+    int rbase[RA], ry[RA], rx[RA];
+#pragma unroll
+    for (int j = 0; j < RA; ++j) {
+        const int m = m0 + row0 + 64 * j;
+        if (m < p.M) {
+            const int n = m / (p.OH * p.OW), rem = m % (p.OH * p.OW);
+            const int oy = rem / p.OW, ox = rem % p.OW;
+            rbase[j] = n * p.IH * p.IW;
+            ry[j] = BWD ? oy + p.pad : oy * p.stride - p.pad;
+            rx[j] = BWD ? ox + p.pad : ox * p.stride - p.pad;
+        } else {
+            rbase[j] = -1; ry[j] = 0; rx[j] = 0;
+        }
+    }
+    // this thread's granule: tap (tr, ts) and channel granule cg, advanced by 4 granules per K-step
+    int gi = ks_begin * 4 + g4;
+    int cg = gi % p.gpt, tap = gi / p.gpt;
+    int tr = tap / p.S, ts = tap % p.S;
+
+    v4i sa[RA], sb[RB];
+    auto load_tiles = [&]() {
+        const bool gvalid = tr < p.R;
+#pragma unroll
+        for (int j = 0; j < RA; ++j) {
+            int iy, ix;
+            bool ok = gvalid && rbase[j] >= 0;
+            if (BWD) {
+                const int ty = ry[j] - tr, tx = rx[j] - ts;
+                iy = ty / p.stride; ix = tx / p.stride;
+                ok = ok && ty >= 0 && tx >= 0 && iy * p.stride == ty && ix * p.stride == tx && iy < p.IH && ix < p.IW;
+            } else {
+                iy = ry[j] + tr; ix = rx[j] + ts;
+                ok = ok && iy >= 0 && iy < p.IH && ix >= 0 && ix < p.IW;
+            }
+            v4i v = {0, 0, 0, 0};
+            if (ok) v = *reinterpret_cast<const v4i *>(p.in + ((size_t)(rbase[j] + iy * p.IW + ix) * p.Cin + cg * 16));
+            sa[j] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const int row = row0 + 64 * j;
+            v4i v = {0, 0, 0, 0};
+            if (gvalid && row < BN && n0 + row < p.Cout)
+                v = *reinterpret_cast<const v4i *>(p.wt + ((size_t)(n0 + row) * p.gtot + gi) * 16);
+            sb[j] = v;
+        }
+    };
+    auto advance = [&]() {
+        gi += 4;
+        cg += 4;
+        while (cg >= p.gpt) {
+            cg -= p.gpt;
+            if (++ts == p.S) { ts = 0; ++tr; }
+        }
+    };
+    auto store_tiles = [&](int buf) {
+        unsigned char *A = lds + buf * BUF, *B = A + 4 * PLANE_A;
+#pragma unroll
+        for (int j = 0; j < RA; ++j) *reinterpret_cast<v4i *>(A + g4 * PLANE_A + (row0 + 64 * j) * 16) = sa[j];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const int row = row0 + 64 * j;
+            if (row < BN) *reinterpret_cast<v4i *>(B + g4 * PLANE_B + row * 16) = sb[j];
+        }
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int wm = wave / WN, wn = wave % WN;
+    const int a_row = wm * (BM / WM) + lane % 32, b_row = wn * (BN / WN) + lane % 32, half = lane / 32;
+
+    if (ks_begin < ks_end) {
+        load_tiles();
+        store_tiles(0);
+        advance();
+    }
+    __syncthreads();
+    for (int ks = ks_begin; ks < ks_end; ++ks) {
+        const int buf = (ks - ks_begin) & 1;
+        const bool more = ks + 1 < ks_end;
+        if (more) load_tiles();
+        const unsigned char *A = lds + buf * BUF, *B = A + 4 * PLANE_A;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            v4i a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a[i] = *reinterpret_cast<const v4i *>(A + (2 * kk + half) * PLANE_A + (a_row + 32 * i) * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                b[j] = *reinterpret_cast<const v4i *>(B + (2 * kk + half) * PLANE_B + (b_row + 32 * j) * 16);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            store_tiles(buf ^ 1);
+            advance();
+        }
+        __syncthreads();
+    }
+
+    // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * (BN / WN) + 32 * j + lane % 32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * (BM / WM) + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+                if (m < p.M && col < p.Cout) {
+                    int32_t *dst = p.out + (size_t)m * p.Cout + col;
+                    if (p.atomic_out) atomicAdd(dst, acc[i][j][r]);
+                    else *dst = acc[i][j][r];
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------ wgrad
+struct WgradParams {
+    const int8_t *g;   // [M][K], M = N*P*Q
+    const int8_t *x;   // [N][H][W][C]
+    int32_t *dw;       // [K][R*S][C], zeroed before the launch
+    int M, K, C, H, W, P, Q, R, S, stride, pad;
+    int tiles_k;       // ceil(K/64)
+    int chunks;        // ceil(M/32)
+    int chunks_per_split;
+};
+
+constexpr int kWRow = 96;              // LDS bytes per pixel row: 64 channels + 32 pad (8 rows tile the 64 banks)
+constexpr int kWTile = 32 * kWRow;     // one [32 px][64 ch] tile
+
+template <int TG>
+__global__ __launch_bounds__(kCThreads) void wgrad_kernel(const WgradParams p) {
+    constexpr int NT = 1 + TG;             // tile 0 = gradient, tile 1+i = input shifted by tap i
+    constexpr int ITEMS = (NT + 1) / 2;    // 16-byte items per thread (128 items per tile, 256 threads)
+    constexpr int BUF = NT * kWTile;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+
+    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
+    const int g4 = t % 4, px = (t % 128) / 4, tp = t / 128;
+    const int k0 = (blockIdx.x % p.tiles_k) * 64, c0 = (blockIdx.x / p.tiles_k) * 64;
+    const int tap0 = blockIdx.y * TG, ntaps = p.R * p.S;
+    const int ch_begin = blockIdx.z * p.chunks_per_split;
+    const int ch_end = min(p.chunks, ch_begin + p.chunks_per_split);
+
+    // this thread's pixel (n, oy, ox), advanced by 32 pixels per step
+    const int step_q = 32 / p.Q, step_r = 32 % p.Q;
+    int m = ch_begin * 32 + px;
+    int n = m / (p.P * p.Q), oy = (m % (p.P * p.Q)) / p.Q, ox = m % p.Q;
+
+    v4i stage[ITEMS];
+    auto load_tiles = [&]() {
+        const bool mvalid = m < p.M;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const int tile = tp + 2 * j;
+            v4i v = {0, 0, 0, 0};
+            if (tile == 0) {
+                if (mvalid && k0 + g4 * 16 < p.K) v = *reinterpret_cast<const v4i *>(p.g + (size_t)m * p.K + k0 + g4 * 16);
+            } else if (tile < NT) {
+                const int tap = tap0 + tile - 1;
+                const int r = tap / p.S, s = tap % p.S;
+                const int iy = oy * p.stride + r - p.pad, ix = ox * p.stride + s - p.pad;
+                if (mvalid && tap < ntaps && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W && c0 + g4 * 16 < p.C)
+                    v = *reinterpret_cast<const v4i *>(p.x + ((size_t)(n * p.H + iy) * p.W + ix) * p.C + c0 + g4 * 16);
+            }
+            stage[j] = v;
+        }
+    };
+    auto advance = [&]() {
+        m += 32;
+        ox += step_r;
+        oy += step_q;
+        if (ox >= p.Q) { ox -= p.Q; ++oy; }
+        while (oy >= p.P) { oy -= p.P; ++n; }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const int tile = tp + 2 * j;
+            if (tile < NT) *reinterpret_cast<v4i *>(lds + buf * BUF + tile * kWTile + px * kWRow + g4 * 16) = stage[j];
+        }
+    };
+
+    v16i acc[TG];
+#pragma unroll
+    for (int i = 0; i < TG; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+
+    // Transposing LDS read: in each block of 16 lanes, source lane j supplies 8 bytes and result
+    // lane i receives byte (i%8) of source lanes i/8, i/8+2, ..., i/8+14.  With source lane j
+    // reading pixel j/2 at channel offset 8*(j%2), result lane i holds channel i of 8 pixels.
+    const int ti = wave / 2, tj = wave % 2;
+    const int blk = lane / 16, j16 = lane % 16;
+    const int src_px = 16 * (blk / 2) + j16 / 2;                  // + 8*h for the second half of the operand
+    const int src_ch = 16 * (blk % 2) + 8 * (j16 % 2);
+    const int a_off = src_px * kWRow + 32 * ti + src_ch;
+    const int b_off = src_px * kWRow + 32 * tj + src_ch;
+    typedef __attribute__((address_space(3))) v2i lds_v2i;
+
+    if (ch_begin < ch_end) {
+        load_tiles();
+        store_tiles(0);
+        advance();
+    }
+    __syncthreads();
+    for (int ch = ch_begin; ch < ch_end; ++ch) {
+        const int buf = (ch - ch_begin) & 1;
+        const bool more = ch + 1 < ch_end;
+        if (more) load_tiles();
+        unsigned char *base = lds + buf * BUF;
+        const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off));
+        const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off + 8 * kWRow));
+        const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+#pragma unroll
+        for (int i = 0; i < TG; ++i) {
+            if (tap0 + i < ntaps) {
+                unsigned char *xt = base + (1 + i) * kWTile;
+                const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(xt + b_off));
+                const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(xt + b_off + 8 * kWRow));
+                const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+            }
+        }
+        if (more) {
+            store_tiles(buf ^ 1);
+            advance();
+        }
+        __syncthreads();
+    }
+
+    const int c = c0 + 32 * tj + lane % 32;
+#pragma unroll
+    for (int i = 0; i < TG; ++i) {
+        const int tap = tap0 + i;
+        if (tap < ntaps && c < p.C) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = k0 + 32 * ti + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+                if (k < p.K && acc[i][r] != 0) atomicAdd(p.dw + ((size_t)k * ntaps + tap) * p.C + c, acc[i][r]);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ helpers and plain kernels
+__global__ void fill_i32_kernel(int32_t *dst, size_t len) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < len; i += (size_t)gridDim.x * blockDim.x) dst[i] = 0;
+}
+
+// wt[c][r][s][k] = w[k][r][s][c]
+__global__ void transpose_filter_kernel(const int8_t *__restrict__ w, int K, int RS, int C, int8_t *__restrict__ wt) {
+    const size_t total = (size_t)K * RS * C;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const int k = (int)(o % K);
+        const int rs = (int)((o / K) % RS);
+        const int c = (int)(o / ((size_t)K * RS));
+        wt[o] = w[((size_t)k * RS + rs) * C + c];
+    }
+}
+
+// one thread per output element; any shape
+__global__ __launch_bounds__(kCThreads) void conv_fwd_plain_kernel(const int8_t *__restrict__ x, const int8_t *__restrict__ w,
+                                                                   int32_t *__restrict__ acc, lpdt_conv_desc d, int P, int Q) {
+    const size_t total = (size_t)d.N * P * Q * d.K;
+    for (size_t o = (size_t)blockIdx.x * kCThreads + threadIdx.x; o < total; o += (size_t)gridDim.x * kCThreads) {
+        const int k = (int)(o % d.K);
+        size_t rest = o / d.K;
+        const int q = (int)(rest % Q); rest /= Q;
+        const int pp = (int)(rest % P);
+        const int n = (int)(rest / P);
+        int s = 0;
+        for (int r = 0; r < d.R; ++r) {
+            const int h = pp * d.stride_h + r - d.pad_h;
+            if (h < 0 || h >= d.H) continue;
+            for (int t = 0; t < d.S; ++t) {
+                const int ww = q * d.stride_w + t - d.pad_w;
+                if (ww < 0 || ww >= d.W) continue;
+                const int8_t *xp = x + (((size_t)n * d.H + h) * d.W + ww) * d.C;
+                const int8_t *wp = w + (((size_t)k * d.R + r) * d.S + t) * d.C;
+                for (int c = 0; c < d.C; ++c) s += (int)xp[c] * (int)wp[c];
+            }
+        }
+        acc[o] = s;
+    }
+}
+
+__global__ __launch_bounds__(kCThreads) void conv_bwd_data_plain_kernel(const int8_t *__restrict__ g, const int8_t *__restrict__ w,
+                                                                        int32_t *__restrict__ dx, lpdt_conv_desc d, int P, int Q) {
+    const size_t total = (size_t)d.N * d.H * d.W * d.C;
+    for (size_t o = (size_t)blockIdx.x * kCThreads + threadIdx.x; o < total; o += (size_t)gridDim.x * kCThreads) {
+        const int c = (int)(o % d.C);
+        size_t rest = o / d.C;
+        const int ww = (int)(rest % d.W); rest /= d.W;
+        const int h = (int)(rest % d.H);
+        const int n = (int)(rest / d.H);
+        int s = 0;
+        for (int r = 0; r < d.R; ++r) {
+            const int ty = h + d.pad_h - r;
+            if (ty < 0 || ty % d.stride_h) continue;
+            const int pp = ty / d.stride_h;
+            if (pp >= P) continue;
+            for (int t = 0; t < d.S; ++t) {
+                const int tx = ww + d.pad_w - t;
+                if (tx < 0 || tx % d.stride_w) continue;
+                const int q = tx / d.stride_w;
+                if (q >= Q) continue;
+                const int8_t *gp = g + (((size_t)n * P + pp) * Q + q) * d.K;
+                for (int k = 0; k < d.K; ++k) s += (int)gp[k] * (int)w[(((size_t)k * d.R + r) * d.S + t) * d.C + c];
+            }
+        }
+        dx[o] = s;
+    }
+}
+
+// one thread per filter element and pixel slice, int32 atomic combine
+__global__ __launch_bounds__(kCThreads) void conv_bwd_weight_plain_kernel(const int8_t *__restrict__ g, const int8_t *__restrict__ x,
+                                                                          int32_t *__restrict__ dw, lpdt_conv_desc d, int P, int Q,
+                                                                          int pix_per_slice) {
+    const int total = d.K * d.R * d.S * d.C;
+    const int o = blockIdx.x * kCThreads + threadIdx.x;
+    if (o >= total) return;
+    const int c = o % d.C;
+    int rest = o / d.C;
+    const int t = rest % d.S; rest /= d.S;
+    const int r = rest % d.R;
+    const int k = rest / d.R;
+    const long long M = (long long)d.N * P * Q;
+    const long long m_begin = (long long)blockIdx.y * pix_per_slice, m_end = min(M, m_begin + pix_per_slice);
+    int s = 0;
+    int n = (int)(m_begin / (P * Q)), pp = (int)((m_begin % (P * Q)) / Q), q = (int)(m_begin % Q);
+    for (long long m = m_begin; m < m_end; ++m) {
+        const int h = pp * d.stride_h + r - d.pad_h, ww = q * d.stride_w + t - d.pad_w;
+        if (h >= 0 && h < d.H && ww >= 0 && ww < d.W)
+            s += (int)g[(size_t)m * d.K + k] * (int)x[(((size_t)n * d.H + h) * d.W + ww) * d.C + c];
+        if (++q == Q) { q = 0; if (++pp == P) { pp = 0; ++n; } }
+    }
+    if (s) atomicAdd(dw + o, s);
+}
+
+static int blocks_for(size_t total, int cap = 65536) {
+    size_t b = (total + kCThreads - 1) / kCThreads;
+    if (b < 1) b = 1;
+    if (b > (size_t)cap) b = cap;
+    return (int)b;
+}
+
+template <int BM, int BN, int WM, int WN, bool BWD>
+static void launch_igemm(IgemmParams p, hipStream_t st) {
+    const int tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.Cout + BN - 1) / BN;
+    const long long blocks = (long long)tiles_m * p.tiles_n;
+    int splits = 1;
+    if (blocks < 256 && p.nk >= 8) {  // too few tiles to fill 256 CUs: split the reduction
+        splits = (int)((512 + blocks - 1) / blocks);
+        if (splits > p.nk / 4) splits = p.nk / 4;
+        if (splits < 1) splits = 1;
+    }
+    p.k_per_split = (p.nk + splits - 1) / splits;
+    splits = (p.nk + p.k_per_split - 1) / p.k_per_split;
+    p.atomic_out = splits > 1;
+    if (p.atomic_out)
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for((size_t)p.M * p.Cout, 4096)), dim3(kCThreads), 0, st, p.out,
+                           (size_t)p.M * p.Cout);
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, BWD>), dim3((unsigned)blocks, 1, splits), dim3(kCThreads), 0, st, p);
+}
+
+template <bool BWD>
+static void dispatch_igemm(const IgemmParams &p, hipStream_t st) {
+    if (p.Cout >= 128) launch_igemm<256, 128, 2, 2, BWD>(p, st);
+    else if (p.Cout >= 48) launch_igemm<256, 64, 4, 1, BWD>(p, st);
+    else launch_igemm<128, 32, 4, 1, BWD>(p, st);
+}
+
+static bool same_stride_pad(const lpdt_conv_desc *d) { return d->stride_h == d->stride_w && d->pad_h == d->pad_w; }
+
+}  // namespace lpdt
+
+using namespace lpdt;
+
+extern "C" size_t lpdt_qconv_fwd_workspace_bytes(const lpdt_conv_desc *d) {
+    (void)d;
+    return 0;
+}
+extern "C" size_t lpdt_qconv_bwd_data_workspace_bytes(const lpdt_conv_desc *d) {
+    if (!d || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->C <= 0) return 0;
+    return round_up((size_t)d->K * d->R * d->S * d->C, 256);
+}
+extern "C" size_t lpdt_qconv_bwd_weight_workspace_bytes(const lpdt_conv_desc *d) {
+    (void)d;
+    return 0;
+}
+
+extern "C" int lpdt_qconv_fwd(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, int32_t *acc, void *ws,
+                              size_t ws_bytes, void *stream) {
+    (void)ws; (void)ws_bytes;
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(xq && wq && acc, LPDT_EINVAL, "qconv_fwd: NULL tensor");
+    LPDT_REQUIRE(aligned(acc, 4), LPDT_EINVAL, "qconv_fwd: acc must be 4-byte aligned");
+    hipStream_t st = as_stream(stream);
+    if (d->C % 16 == 0 && same_stride_pad(d) && aligned(xq, 16) && aligned(wq, 16)) {
+        IgemmParams p = {};
+        p.in = xq; p.wt = wq; p.out = acc;
+        p.M = d->N * P * Q; p.Cin = d->C; p.Cout = d->K;
+        p.IH = d->H; p.IW = d->W; p.OH = P; p.OW = Q;
+        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
+        p.gpt = d->C / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
+        dispatch_igemm<false>(p, st);
+    } else {
+        hipLaunchKernelGGL(conv_fwd_plain_kernel, dim3(blocks_for((size_t)d->N * P * Q * d->K)), dim3(kCThreads), 0, st, xq, wq,
+                           acc, *d, P, Q);
+    }
+    return launch_status("lpdt_qconv_fwd");
+}
+
+extern "C" int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, int32_t *dx, void *ws,
+                                   size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && wq && dx, LPDT_EINVAL, "qconv_bwd_data: NULL tensor");
+    LPDT_REQUIRE(aligned(dx, 4), LPDT_EINVAL, "qconv_bwd_data: dx must be 4-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_data_workspace_bytes(d));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    if (d->K % 16 == 0 && same_stride_pad(d) && aligned(gq, 16)) {
+        int8_t *wt = static_cast<int8_t *>(ws);
+        const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
+        hipLaunchKernelGGL(transpose_filter_kernel, dim3(blocks_for(wlen, 2048)), dim3(kCThreads), 0, st, wq, d->K, d->R * d->S,
+                           d->C, wt);
+        IgemmParams p = {};
+        p.in = gq; p.wt = wt; p.out = dx;
+        p.M = d->N * d->H * d->W; p.Cin = d->K; p.Cout = d->C;
+        p.IH = P; p.IW = Q; p.OH = d->H; p.OW = d->W;
+        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
+        p.gpt = d->K / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
+        dispatch_igemm<true>(p, st);
+    } else {
+        hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for((size_t)d->N * d->H * d->W * d->C)), dim3(kCThreads), 0, st,
+                           gq, wq, dx, *d, P, Q);
+    }
+    return launch_status("lpdt_qconv_bwd_data");
+}
+
+extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw, void *ws,
+                                     size_t ws_bytes, void *stream) {
+    (void)ws; (void)ws_bytes;
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && xq && dw, LPDT_EINVAL, "qconv_bwd_weight: NULL tensor");
+    LPDT_REQUIRE(aligned(dw, 4), LPDT_EINVAL, "qconv_bwd_weight: dw must be 4-byte aligned");
+    hipStream_t st = as_stream(stream);
+    const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
+    const long long M = (long long)d->N * P * Q;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(wlen, 1024)), dim3(kCThreads), 0, st, dw, wlen);
+    if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d) && aligned(gq, 16) && aligned(xq, 16)) {
+        WgradParams p = {};
+        p.g = gq; p.x = xq; p.dw = dw;
+        p.M = (int)M; p.K = d->K; p.C = d->C; p.H = d->H; p.W = d->W; p.P = P; p.Q = Q;
+        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
+        p.tiles_k = (d->K + 63) / 64;
+        const int tiles_c = (d->C + 63) / 64;
+        p.chunks = (int)((M + 31) / 32);
+        const int ntaps = d->R * d->S;
+        const int tg = ntaps == 1 ? 1 : 9;
+        const int groups = (ntaps + tg - 1) / tg;
+        const long long base_blocks = (long long)p.tiles_k * tiles_c * groups;
+        long long splits = (1024 + base_blocks - 1) / base_blocks;  // aim at >= 4 blocks per CU
+        if (splits > p.chunks / 8) splits = p.chunks / 8;             // but at least 8 steps per block
+        if (splits < 1) splits = 1;
+        p.chunks_per_split = (int)((p.chunks + splits - 1) / splits);
+        splits = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+        const dim3 grid((unsigned)(p.tiles_k * tiles_c), (unsigned)groups, (unsigned)splits);
+        if (tg == 1) hipLaunchKernelGGL(wgrad_kernel<1>, grid, dim3(kCThreads), 0, st, p);
+        else hipLaunchKernelGGL(wgrad_kernel<9>, grid, dim3(kCThreads), 0, st, p);
+    } else {
+        long long slices = (M + 4095) / 4096;
+        if (slices > 1024) slices = 1024;
+        const int pix = (int)((M + slices - 1) / slices);
+        slices = (M + pix - 1) / pix;
+        hipLaunchKernelGGL(conv_bwd_weight_plain_kernel, dim3((unsigned)((wlen + kCThreads - 1) / kCThreads), (unsigned)slices),
+                           dim3(kCThreads), 0, st, gq, xq, dw, *d, P, Q, pix);
+    }
+    return launch_status("lpdt_qconv_bwd_weight");
+}

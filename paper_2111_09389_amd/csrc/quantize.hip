@@ -1,0 +1,211 @@
+// 8-bit symmetric per-tensor quantizer with round-to-nearest-even or Philox
+// stochastic rounding, and the dequantizing scale of int32 accumulators
+// (Section 3, "Low Precision Training").  HBM-bound kernels: 16-byte loads,
+// 4-byte packed code stores, no atomics (abs-max goes through per-block
+// partials that every block of the rounding pass re-reduces from L2).
+#include "common.h"
+
+namespace lpdt {
+
+constexpr int kQThreads = 256;
+constexpr int kMaxParts = 1024;  // abs-max partials = upper bound of the first pass's grid
+
+// ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------
+// One call yields the four 32-bit words used by four consecutive elements.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t out[4]) {
+    uint32_t c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint64_t lo = (uint64_t)c0 * 0xD2511F53ull;
+        const uint64_t hi = (uint64_t)c2 * 0xCD9E8D57ull;
+        const uint32_t t0 = (uint32_t)(hi >> 32) ^ c1 ^ k0;
+        const uint32_t t2 = (uint32_t)(lo >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)hi;
+        c3 = (uint32_t)lo;
+        c0 = t0;
+        c2 = t2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ float block_max(float v, float *lds) {
+    v = wave_max(v);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    float r = lds[0];
+#pragma unroll
+    for (int w = 1; w < kQThreads / kWave; ++w) r = fmaxf(r, lds[w]);
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(kQThreads) void absmax_kernel(const float *__restrict__ x, size_t len,
+                                                           float *__restrict__ parts) {
+    __shared__ float lds[kQThreads / kWave];
+    const size_t nvec = len / 4;
+    const float4 *xv = reinterpret_cast<const float4 *>(x);
+    float m = 0.0f;
+    for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < nvec; i += (size_t)gridDim.x * kQThreads) {
+        const float4 a = xv[i];
+        m = fmaxf(fmaxf(m, fmaxf(fabsf(a.x), fabsf(a.y))), fmaxf(fabsf(a.z), fabsf(a.w)));
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (len & 3)) m = fmaxf(m, fabsf(x[nvec * 4 + threadIdx.x]));
+    m = block_max(m, lds);
+    if (threadIdx.x == 0) parts[blockIdx.x] = m;
+}
+
+__device__ __forceinline__ int round_code(float x, float inv, bool stochastic, uint32_t word) {
+    const float t = __fmul_rn(x, inv);  // never contracted into an FMA
+    float r;
+    if (stochastic) {
+        const float f = floorf(t);
+        const float frac = __fsub_rn(t, f);
+        const float u = __fmul_rn((float)(word >> 8), 0x1.0p-24f);
+        r = f + ((u < frac) ? 1.0f : 0.0f);
+    } else {
+        r = rintf(t);
+    }
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+template <bool kStochastic>
+__global__ __launch_bounds__(kQThreads) void round_kernel(const float *__restrict__ x, size_t len,
+                                                          const float *__restrict__ parts, int nparts,
+                                                          uint64_t seed, uint64_t offset, int8_t *__restrict__ q,
+                                                          float *__restrict__ scale) {
+    __shared__ float lds[kQThreads / kWave];
+    float a = 0.0f;
+    for (int i = threadIdx.x; i < nparts; i += kQThreads) a = fmaxf(a, parts[i]);
+    a = block_max(a, lds);
+    const float inv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale = __fdiv_rn(a, 127.0f);
+
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const size_t nvec = len / 4;
+    const float4 *xv = reinterpret_cast<const float4 *>(x);
+    uint32_t *qv = reinterpret_cast<uint32_t *>(q);
+    for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < nvec; i += (size_t)gridDim.x * kQThreads) {
+        const float4 v = xv[i];
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (kStochastic) {
+            const uint64_t blk = offset + i;
+            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
+        }
+        const uint32_t b0 = (uint32_t)round_code(v.x, inv, kStochastic, w[0]) & 0xffu;
+        const uint32_t b1 = (uint32_t)round_code(v.y, inv, kStochastic, w[1]) & 0xffu;
+        const uint32_t b2 = (uint32_t)round_code(v.z, inv, kStochastic, w[2]) & 0xffu;
+        const uint32_t b3 = (uint32_t)round_code(v.w, inv, kStochastic, w[3]) & 0xffu;
+        qv[i] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+    }
+    const int tail = (int)(len & 3);
+    if (blockIdx.x == 0 && threadIdx.x < tail) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (kStochastic) {
+            const uint64_t blk = offset + nvec;
+            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
+        }
+        q[nvec * 4 + threadIdx.x] = (int8_t)round_code(x[nvec * 4 + threadIdx.x], inv, kStochastic, w[threadIdx.x]);
+    }
+}
+
+template <bool kAccumulate>
+__global__ __launch_bounds__(kQThreads) void dequant_kernel(const int32_t *__restrict__ acc, size_t len,
+                                                            const float *__restrict__ sA,
+                                                            const float *__restrict__ sB, float *__restrict__ y) {
+    const float s = __fmul_rn(*sA, *sB);
+    const size_t nvec = len / 4;
+    const int4 *av = reinterpret_cast<const int4 *>(acc);
+    float4 *yv = reinterpret_cast<float4 *>(y);
+    for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < nvec; i += (size_t)gridDim.x * kQThreads) {
+        const int4 a = av[i];
+        float4 o = make_float4(s * (float)a.x, s * (float)a.y, s * (float)a.z, s * (float)a.w);
+        if (kAccumulate) {
+            const float4 p = yv[i];
+            o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w;
+        }
+        yv[i] = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (len & 3)) {
+        const size_t i = nvec * 4 + threadIdx.x;
+        const float o = s * (float)acc[i];
+        y[i] = kAccumulate ? y[i] + o : o;
+    }
+}
+
+static int grid_for(size_t len, int per_thread) {
+    size_t blocks = (len + (size_t)kQThreads * per_thread - 1) / ((size_t)kQThreads * per_thread);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    return (int)blocks;
+}
+
+static int check_quant_args(const float *x, size_t len, int rounding, const int8_t *q, const float *scale) {
+    LPDT_REQUIRE(x && q && scale, LPDT_EINVAL, "quantize: x, q and scale must be non-NULL");
+    LPDT_REQUIRE(len > 0, LPDT_EUNSUPPORTED, "quantize: len must be positive");
+    LPDT_REQUIRE(rounding == LPDT_ROUND_NEAREST || rounding == LPDT_ROUND_STOCHASTIC, LPDT_EINVAL,
+                 "quantize: rounding must be LPDT_ROUND_NEAREST or LPDT_ROUND_STOCHASTIC (got %d)", rounding);
+    LPDT_REQUIRE(aligned(x, 16) && aligned(q, 4) && aligned(scale, 4), LPDT_EINVAL,
+                 "quantize: x must be 16-byte aligned, q and scale 4-byte aligned");
+    return LPDT_OK;
+}
+
+}  // namespace lpdt
+
+using namespace lpdt;
+
+extern "C" size_t lpdt_quantize_workspace_bytes(size_t len) {
+    (void)len;
+    return kMaxParts * sizeof(float);
+}
+
+extern "C" int lpdt_quantize(const float *x, size_t len, int rounding, uint64_t seed, uint64_t offset, int8_t *q,
+                             float *scale, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_quant_args(x, len, rounding, q, scale);
+    if (rc) return rc;
+    rc = check_ws(ws, ws_bytes, lpdt_quantize_workspace_bytes(len));
+    if (rc) return rc;
+    float *parts = static_cast<float *>(ws);
+    int g1 = grid_for(len, 16);
+    if (g1 > kMaxParts) g1 = kMaxParts;
+    hipLaunchKernelGGL(absmax_kernel, dim3(g1), dim3(kQThreads), 0, as_stream(stream), x, len, parts);
+    const int g2 = grid_for(len, 16);
+    if (rounding == LPDT_ROUND_STOCHASTIC)
+        hipLaunchKernelGGL(round_kernel<true>, dim3(g2), dim3(kQThreads), 0, as_stream(stream), x, len, parts, g1,
+                           seed, offset, q, scale);
+    else
+        hipLaunchKernelGGL(round_kernel<false>, dim3(g2), dim3(kQThreads), 0, as_stream(stream), x, len, parts, g1,
+                           seed, offset, q, scale);
+    return launch_status("lpdt_quantize");
+}
+
+extern "C" int lpdt_quantize_with_absmax(const float *x, size_t len, const float *absmax, int rounding,
+                                         uint64_t seed, uint64_t offset, int8_t *q, float *scale, void *stream) {
+    int rc = check_quant_args(x, len, rounding, q, scale);
+    if (rc) return rc;
+    LPDT_REQUIRE(absmax && aligned(absmax, 4), LPDT_EINVAL, "quantize_with_absmax: absmax must be a non-NULL device scalar");
+    const int g2 = grid_for(len, 16);
+    if (rounding == LPDT_ROUND_STOCHASTIC)
+        hipLaunchKernelGGL(round_kernel<true>, dim3(g2), dim3(kQThreads), 0, as_stream(stream), x, len, absmax, 1,
+                           seed, offset, q, scale);
+    else
+        hipLaunchKernelGGL(round_kernel<false>, dim3(g2), dim3(kQThreads), 0, as_stream(stream), x, len, absmax, 1,
+                           seed, offset, q, scale);
+    return launch_status("lpdt_quantize_with_absmax");
+}
+
+extern "C" int lpdt_dequantize(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y,
+                               int accumulate, void *stream) {
+    LPDT_REQUIRE(acc && sA && sB && y, LPDT_EINVAL, "dequantize: NULL argument");
+    LPDT_REQUIRE(len > 0, LPDT_EUNSUPPORTED, "dequantize: len must be positive");
+    LPDT_REQUIRE(aligned(acc, 16) && aligned(y, 16), LPDT_EINVAL, "dequantize: acc and y must be 16-byte aligned");
+    const int g = grid_for(len, 16);
+    if (accumulate)
+        hipLaunchKernelGGL(dequant_kernel<true>, dim3(g), dim3(kQThreads), 0, as_stream(stream), acc, len, sA, sB, y);
+    else
+        hipLaunchKernelGGL(dequant_kernel<false>, dim3(g), dim3(kQThreads), 0, as_stream(stream), acc, len, sA, sB, y);
+    return launch_status("lpdt_dequantize");
+}

@@ -1,0 +1,486 @@
+// Range-EvoNorm forward and backward (Eq. "ren"), fp32, NHWC.
+//
+// Both directions are HBM-bound.  A block owns a run of consecutive pixels of
+// one sample, so its loads are one contiguous stream; the block's thread count
+// is a multiple of C/4, which pins every thread to one quad of channels and lets
+// it keep its running extrema / channel sums in registers.
+//   forward : stats pass (per-(sample,group) first arg-max / arg-min through packed
+//             64-bit atomic max keys) -> finalize -> elementwise apply
+//   backward: one pass writes the elementwise part of dx and per-block channel
+//             partials; fixed-order reductions give dv, dgamma, dbeta and the range
+//             gradient, which is then added at the saved arg-max / arg-min.
+#include "common.h"
+#include <cmath>
+
+namespace lpdt {
+
+constexpr int kRThreads = 256;
+constexpr int kPixIters = 16;  // pixels per thread in the streaming passes
+
+struct RenGeom {
+    int N, HW, C, groups, m;
+    int cq;       // float4 quads per pixel (C/4)
+    int threads;  // working threads per block, multiple of cq
+    int block;    // launched block size: threads rounded up to whole waves (the extra threads only join reductions)
+    int ppi;      // pixels per block iteration
+    int chunks;   // blocks per sample
+    int pix_per_block;
+};
+
+static RenGeom ren_geom(int N, int H, int W, int C, int groups) {
+    RenGeom g;
+    g.N = N; g.HW = H * W; g.C = C; g.groups = groups; g.m = C / groups;
+    g.cq = C / 4;
+    g.threads = (kRThreads / g.cq) * g.cq;
+    g.block = (g.threads + kWave - 1) / kWave * kWave;
+    g.ppi = g.threads / g.cq;
+    g.pix_per_block = g.ppi * kPixIters;
+    g.chunks = (g.HW + g.pix_per_block - 1) / g.pix_per_block;
+    return g;
+}
+
+// monotone map float -> uint32 (larger float <=> larger key); -0 is folded onto +0
+__device__ __forceinline__ uint32_t ordered_bits(float x) {
+    const uint32_t b = __float_as_uint(x + 0.0f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_bits(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+__device__ __forceinline__ float hard_sigmoid(float z) { return fminf(1.0f, fmaxf(0.0f, (z + 3.0f) * (1.0f / 6.0f))); }
+
+__global__ void ren_clear_kernel(unsigned long long *stats, int count, float *absmax) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) stats[i] = 0ull;
+    if (i == 0 && absmax) *absmax = 0.0f;
+}
+
+// stats[(n*groups+g)*2+0] = max key, +1 = min key.  Key = ordered value (inverted for
+// the minimum) in the high word, ~slab_index in the low word: the largest key is the
+// extreme value at its lowest slab index.
+__global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__restrict__ x, RenGeom g,
+                                                              unsigned long long *__restrict__ stats) {
+    extern __shared__ unsigned long long skeys[];  // [groups][2]
+    const int n = blockIdx.y;
+    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) skeys[i] = 0ull;
+    __syncthreads();
+    const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
+    const int p0 = blockIdx.x * g.pix_per_block;
+    const int p1 = min(p0 + g.pix_per_block, g.HW);
+    float mx[4], mn[4];
+    int imx[4], imn[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { imx[e] = -1; imn[e] = -1; mx[e] = 0.f; mn[e] = 0.f; }
+    const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
+    for (int p = p0 + pl; p < p1 && (int)threadIdx.x < g.threads; p += g.ppi) {
+        const float4 a = xv[(size_t)p * g.cq + qd];
+        const float v[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (imx[e] < 0 || v[e] > mx[e]) { mx[e] = v[e]; imx[e] = p; }
+            if (imn[e] < 0 || v[e] < mn[e]) { mn[e] = v[e]; imn[e] = p; }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (imx[e] < 0) continue;
+        const int c = qd * 4 + e, grp = c / g.m, cc = c % g.m;
+        const uint32_t lo_mx = ~(uint32_t)(imx[e] * g.m + cc), lo_mn = ~(uint32_t)(imn[e] * g.m + cc);
+        atomicMax(&skeys[grp * 2 + 0], ((unsigned long long)ordered_bits(mx[e]) << 32) | lo_mx);
+        atomicMax(&skeys[grp * 2 + 1], ((unsigned long long)(~ordered_bits(mn[e])) << 32) | lo_mn);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x)
+        if (skeys[i]) atomicMax(&stats[(size_t)n * g.groups * 2 + i], skeys[i]);
+}
+
+// Any channel count: one element per thread step, keys straight into LDS atomics.
+__global__ __launch_bounds__(kRThreads) void ren_stats_generic_kernel(const float *__restrict__ x, int HW, int C,
+                                                                      int groups, int m, int elems_per_block,
+                                                                      unsigned long long *__restrict__ stats) {
+    extern __shared__ unsigned long long skeys[];
+    const int n = blockIdx.y;
+    for (int i = threadIdx.x; i < 2 * groups; i += blockDim.x) skeys[i] = 0ull;
+    __syncthreads();
+    const long long total = (long long)HW * C;
+    const long long e0 = (long long)blockIdx.x * elems_per_block;
+    const long long e1 = min(e0 + (long long)elems_per_block, total);
+    const float *xs = x + (size_t)n * total;
+    for (long long i = e0 + threadIdx.x; i < e1; i += blockDim.x) {
+        const float v = xs[i];
+        const int p = (int)(i / C), c = (int)(i % C), grp = c / m, cc = c % m;
+        const uint32_t lo = ~(uint32_t)(p * m + cc);
+        atomicMax(&skeys[grp * 2 + 0], ((unsigned long long)ordered_bits(v) << 32) | lo);
+        atomicMax(&skeys[grp * 2 + 1], ((unsigned long long)(~ordered_bits(v)) << 32) | lo);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * groups; i += blockDim.x)
+        if (skeys[i]) atomicMax(&stats[(size_t)n * groups * 2 + i], skeys[i]);
+}
+
+__global__ void ren_finalize_kernel(const unsigned long long *__restrict__ stats, int count, float *__restrict__ range_out,
+                                    int32_t *__restrict__ argmax_out, int32_t *__restrict__ argmin_out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const unsigned long long kmx = stats[2 * i], kmn = stats[2 * i + 1];
+    const float mx = from_ordered_bits((uint32_t)(kmx >> 32));
+    const float mn = from_ordered_bits(~(uint32_t)(kmn >> 32));
+    range_out[i] = __fsub_rn(mx, mn);
+    argmax_out[i] = (int32_t)(~(uint32_t)kmx);
+    argmin_out[i] = (int32_t)(~(uint32_t)kmn);
+}
+
+__device__ __forceinline__ float inv_denominator(float range, float cm, float eps) {
+    return __fdiv_rn(1.0f, __fmaf_rn(cm, range, eps));
+}
+
+__device__ __forceinline__ void block_absmax_commit(float m, float *absmax_out, float *lds) {
+    m = wave_max(m);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    if (lane == 0) lds[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = lds[0];
+        for (int w = 1; w < (int)(blockDim.x + kWave - 1) / kWave; ++w) r = fmaxf(r, lds[w]);
+        atomicMax(reinterpret_cast<unsigned int *>(absmax_out), __float_as_uint(r));  // r >= 0: bit order = value order
+    }
+}
+
+__global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__restrict__ x, RenGeom g,
+                                                              const float *__restrict__ v,
+                                                              const float *__restrict__ gamma,
+                                                              const float *__restrict__ beta, float cm, float eps,
+                                                              const float *__restrict__ range,
+                                                              float *__restrict__ y, float *__restrict__ absmax_out) {
+    __shared__ float lds[kRThreads / kWave];
+    const int n = blockIdx.y;
+    const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
+    const int p0 = blockIdx.x * g.pix_per_block;
+    const int p1 = min(p0 + g.pix_per_block, g.HW);
+    const bool active = (int)threadIdx.x < g.threads;
+    float vv[4], gg[4], bb[4], inv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int c = qd * 4 + e;
+        vv[e] = v[c]; gg[e] = gamma[c]; bb[e] = beta[c];
+        inv[e] = inv_denominator(range[(size_t)n * g.groups + c / g.m], cm, eps);
+    }
+    const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
+    float4 *yv = reinterpret_cast<float4 *>(y + (size_t)n * g.HW * g.C);
+    float am = 0.0f;
+    for (int p = p0 + pl; p < p1 && active; p += g.ppi) {
+        const float4 a = xv[(size_t)p * g.cq + qd];
+        const float xe[4] = {a.x, a.y, a.z, a.w};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float u = xe[e] * hard_sigmoid(vv[e] * xe[e]);
+            o[e] = gg[e] * u * inv[e] + bb[e];
+            am = fmaxf(am, fabsf(o[e]));
+        }
+        yv[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+}
+
+__global__ __launch_bounds__(kRThreads) void ren_apply_generic_kernel(const float *__restrict__ x, int HW, int C, int groups,
+                                                                      int m, int elems_per_block,
+                                                                      const float *__restrict__ v,
+                                                                      const float *__restrict__ gamma,
+                                                                      const float *__restrict__ beta, float cm, float eps,
+                                                                      const float *__restrict__ range,
+                                                                      float *__restrict__ y, float *__restrict__ absmax_out) {
+    __shared__ float lds[kRThreads / kWave];
+    const int n = blockIdx.y;
+    const long long total = (long long)HW * C;
+    const long long e0 = (long long)blockIdx.x * elems_per_block;
+    const long long e1 = min(e0 + (long long)elems_per_block, total);
+    float am = 0.0f;
+    for (long long i = e0 + threadIdx.x; i < e1; i += blockDim.x) {
+        const int c = (int)(i % C);
+        const float xe = x[(size_t)n * total + i];
+        const float inv = inv_denominator(range[(size_t)n * groups + c / m], cm, eps);
+        const float o = gamma[c] * (xe * hard_sigmoid(v[c] * xe)) * inv + beta[c];
+        y[(size_t)n * total + i] = o;
+        am = fmaxf(am, fabsf(o));
+    }
+    if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+}
+
+// ---- backward ---------------------------------------------------------------
+// Per element: z = v x, s = hs(z), s' = 1/6 on (-3,3), u = x s, du = dy gamma / D,
+//   dx = du (s + x v s'),  dbeta += dy,  dgamma += dy u / D,  dv += du x^2 s',
+//   T += dy gamma u   (dD = -T / D^2, dRange = C(m) dD).
+// parts layout: [row = n*chunks + chunk][4 quantities][C]
+__global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__restrict__ dy, const float *__restrict__ x,
+                                                                 RenGeom g, const float *__restrict__ v,
+                                                                 const float *__restrict__ gamma, float cm, float eps,
+                                                                 const float *__restrict__ range,
+                                                                 const int32_t *__restrict__ argmax,
+                                                                 const int32_t *__restrict__ argmin,
+                                                                 float *__restrict__ dx, float *__restrict__ parts,
+                                                                 float *__restrict__ absmax_out) {
+    extern __shared__ float sred[];  // [4][threads*4]
+    __shared__ float lds[kRThreads / kWave];
+    const int n = blockIdx.y;
+    const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
+    const int p0 = blockIdx.x * g.pix_per_block;
+    const int p1 = min(p0 + g.pix_per_block, g.HW);
+    float vv[4], gg[4], inv[4];
+    int skip_a[4], skip_b[4];  // pixel of this channel's arg-max / arg-min element (or -1)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int c = qd * 4 + e, grp = c / g.m, cc = c % g.m;
+        vv[e] = v[c]; gg[e] = gamma[c];
+        inv[e] = inv_denominator(range[(size_t)n * g.groups + grp], cm, eps);
+        const int ia = argmax[(size_t)n * g.groups + grp], ib = argmin[(size_t)n * g.groups + grp];
+        skip_a[e] = (ia % g.m == cc) ? ia / g.m : -1;
+        skip_b[e] = (ib % g.m == cc) ? ib / g.m : -1;
+    }
+    float sb[4] = {0, 0, 0, 0}, sg[4] = {0, 0, 0, 0}, sv[4] = {0, 0, 0, 0}, st[4] = {0, 0, 0, 0};
+    const size_t base = (size_t)n * g.HW * g.C;
+    const float4 *xv = reinterpret_cast<const float4 *>(x + base);
+    const float4 *dv4 = reinterpret_cast<const float4 *>(dy + base);
+    float4 *ov = reinterpret_cast<float4 *>(dx + base);
+    float am = 0.0f;
+    const bool active = (int)threadIdx.x < g.threads;
+    for (int p = p0 + pl; p < p1 && active; p += g.ppi) {
+        const float4 a = xv[(size_t)p * g.cq + qd];
+        const float4 d = dv4[(size_t)p * g.cq + qd];
+        const float xe[4] = {a.x, a.y, a.z, a.w};
+        const float de[4] = {d.x, d.y, d.z, d.w};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float z = vv[e] * xe[e];
+            const float s = hard_sigmoid(z);
+            const float sp = (z > -3.0f && z < 3.0f) ? (1.0f / 6.0f) : 0.0f;
+            const float u = xe[e] * s;
+            const float du = de[e] * gg[e] * inv[e];
+            o[e] = du * (s + xe[e] * vv[e] * sp);
+            sb[e] += de[e];
+            sg[e] += de[e] * u;
+            sv[e] += du * xe[e] * xe[e] * sp;
+            st[e] += de[e] * gg[e] * u;
+            if (p != skip_a[e] && p != skip_b[e]) am = fmaxf(am, fabsf(o[e]));
+        }
+        ov[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    // fixed-order block reduction over the threads that share a channel quad
+    const int T4 = g.threads * 4;
+    if (active) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            sred[0 * T4 + threadIdx.x * 4 + e] = sb[e];
+            sred[1 * T4 + threadIdx.x * 4 + e] = sg[e] * inv[e];
+            sred[2 * T4 + threadIdx.x * 4 + e] = sv[e];
+            sred[3 * T4 + threadIdx.x * 4 + e] = st[e];
+        }
+    }
+    __syncthreads();
+    const size_t row = (size_t)n * g.chunks + blockIdx.x;
+    for (int i = threadIdx.x; i < 4 * g.C; i += blockDim.x) {
+        const int qn = i / g.C, c = i % g.C;
+        float s = 0.0f;
+        for (int k = 0; k < g.ppi; ++k) s += sred[qn * T4 + (k * g.cq) * 4 + c];
+        parts[(row * 4 + qn) * g.C + c] = s;
+    }
+    if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+}
+
+__global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float *__restrict__ dy, const float *__restrict__ x,
+                                                                    int HW, int C, int groups, int m, int pix_per_block,
+                                                                    int chunks, const float *__restrict__ v,
+                                                                    const float *__restrict__ gamma, float cm, float eps,
+                                                                    const float *__restrict__ range,
+                                                                    const int32_t *__restrict__ argmax,
+                                                                    const int32_t *__restrict__ argmin,
+                                                                    float *__restrict__ dx, float *__restrict__ parts,
+                                                                    float *__restrict__ absmax_out) {
+    // one thread per channel (strided), serial over the block's pixels: slow, any C
+    __shared__ float lds[kRThreads / kWave];
+    const int n = blockIdx.y;
+    const int p0 = blockIdx.x * pix_per_block, p1 = min(p0 + pix_per_block, HW);
+    const size_t row = (size_t)n * chunks + blockIdx.x;
+    float am = 0.0f;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        const int grp = c / m, cc = c % m;
+        const float vv = v[c], gg = gamma[c];
+        const float inv = inv_denominator(range[(size_t)n * groups + grp], cm, eps);
+        const int ia = argmax[(size_t)n * groups + grp], ib = argmin[(size_t)n * groups + grp];
+        const int skip_a = (ia % m == cc) ? ia / m : -1, skip_b = (ib % m == cc) ? ib / m : -1;
+        float sb = 0, sg = 0, sv = 0, st = 0;
+        for (int p = p0; p < p1; ++p) {
+            const size_t at = ((size_t)n * HW + p) * C + c;
+            const float xe = x[at], de = dy[at];
+            const float z = vv * xe, s = hard_sigmoid(z);
+            const float sp = (z > -3.0f && z < 3.0f) ? (1.0f / 6.0f) : 0.0f;
+            const float u = xe * s, du = de * gg * inv;
+            const float o = du * (s + xe * vv * sp);
+            dx[at] = o;
+            sb += de; sg += de * u; sv += du * xe * xe * sp; st += de * gg * u;
+            if (p != skip_a && p != skip_b) am = fmaxf(am, fabsf(o));
+        }
+        parts[(row * 4 + 0) * C + c] = sb;
+        parts[(row * 4 + 1) * C + c] = sg * inv;
+        parts[(row * 4 + 2) * C + c] = sv;
+        parts[(row * 4 + 3) * C + c] = st;
+    }
+    if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+}
+
+// dbeta, dgamma, dv: column sums of parts over all rows, fixed order.
+// block = 32 channels x 8 row slices
+__global__ __launch_bounds__(256) void ren_bwd_param_kernel(const float *__restrict__ parts, int rows, int C,
+                                                            float *__restrict__ dbeta, float *__restrict__ dgamma,
+                                                            float *__restrict__ dv) {
+    __shared__ float s[3][8][32];
+    const int cl = threadIdx.x % 32, sl = threadIdx.x / 32;
+    const int c = blockIdx.x * 32 + cl;
+    float a0 = 0, a1 = 0, a2 = 0;
+    if (c < C)
+        for (int r = sl; r < rows; r += 8) {
+            a0 += parts[((size_t)r * 4 + 0) * C + c];
+            a1 += parts[((size_t)r * 4 + 1) * C + c];
+            a2 += parts[((size_t)r * 4 + 2) * C + c];
+        }
+    s[0][sl][cl] = a0; s[1][sl][cl] = a1; s[2][sl][cl] = a2;
+    __syncthreads();
+    if (sl == 0 && c < C) {
+        float b0 = 0, b1 = 0, b2 = 0;
+        for (int k = 0; k < 8; ++k) { b0 += s[0][k][cl]; b1 += s[1][k][cl]; b2 += s[2][k][cl]; }
+        dbeta[c] = b0; dgamma[c] = b1; dv[c] = b2;
+    }
+}
+
+// one thread per (sample, group): gradient through the range, added at the saved extrema
+__global__ void ren_bwd_range_kernel(const float *__restrict__ parts, int N, int HW, int C, int groups, int m, int chunks,
+                                     float cm, float eps, const float *__restrict__ range,
+                                     const int32_t *__restrict__ argmax, const int32_t *__restrict__ argmin,
+                                     float *__restrict__ dx, float *__restrict__ absmax_out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N * groups) return;
+    const int n = i / groups, grp = i % groups;
+    float t = 0.0f;
+    for (int ch = 0; ch < chunks; ++ch)
+        for (int cc = 0; cc < m; ++cc) t += parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc];
+    const float inv = inv_denominator(range[i], cm, eps);
+    const float dR = -cm * t * inv * inv;
+    const int ia = argmax[i], ib = argmin[i];
+    const size_t base = (size_t)n * HW * C + (size_t)grp * m;
+    const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
+    dx[pa] += dR;
+    dx[pb] -= dR;
+    if (absmax_out) {
+        const float mm = fmaxf(fabsf(dx[pa]), fabsf(dx[pb]));
+        atomicMax(reinterpret_cast<unsigned int *>(absmax_out), __float_as_uint(mm));
+    }
+}
+
+static int check_ren(const void *x, int N, int H, int W, int C, int groups) {
+    LPDT_REQUIRE(x, LPDT_EINVAL, "range_evonorm: NULL tensor");
+    LPDT_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, LPDT_EINVAL, "range_evonorm: sizes must be positive");
+    LPDT_REQUIRE(groups > 0 && C % groups == 0, LPDT_EUNSUPPORTED, "range_evonorm: groups (%d) must divide C (%d)", groups, C);
+    LPDT_REQUIRE(C / groups >= 2, LPDT_EUNSUPPORTED,
+                 "range_evonorm: needs at least 2 channels per group (C(1) = 1/sqrt(2 ln 1) is infinite)");
+    LPDT_REQUIRE(groups <= 2048, LPDT_EUNSUPPORTED, "range_evonorm: at most 2048 groups");
+    LPDT_REQUIRE((long long)H * W * (C / groups) < 0x7fffffffLL && (long long)N * H * W * C < (1LL << 40), LPDT_EUNSUPPORTED,
+                 "range_evonorm: slab too large");
+    return LPDT_OK;
+}
+static bool ren_fast(int C) { return C % 4 == 0 && C / 4 <= kRThreads; }
+static float ren_cm(int m) { return (float)(1.0 / std::sqrt(2.0 * std::log((double)m))); }
+constexpr int kGenericElems = 8192;
+constexpr int kGenericPix = 64;
+
+}  // namespace lpdt
+
+using namespace lpdt;
+
+extern "C" size_t lpdt_range_evonorm_fwd_workspace_bytes(int N, int H, int W, int C, int groups) {
+    (void)H; (void)W; (void)C;
+    if (N <= 0 || groups <= 0) return 0;
+    return round_up((size_t)N * groups * 2 * sizeof(unsigned long long), 256);
+}
+
+extern "C" size_t lpdt_range_evonorm_bwd_workspace_bytes(int N, int H, int W, int C, int groups) {
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups) return 0;
+    size_t rows;
+    if (ren_fast(C)) rows = (size_t)N * ren_geom(N, H, W, C, groups).chunks;
+    else rows = (size_t)N * (((size_t)H * W + kGenericPix - 1) / kGenericPix);
+    return round_up(rows * 4 * C * sizeof(float), 256);
+}
+
+extern "C" int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                                      const float *gamma, const float *beta, float eps, float *y, float *range_out,
+                                      int32_t *argmax_out, int32_t *argmin_out, float *absmax_out, void *ws,
+                                      size_t ws_bytes, void *stream) {
+    int rc = check_ren(x, N, H, W, C, groups);
+    if (rc) return rc;
+    LPDT_REQUIRE(v && gamma && beta && y && range_out && argmax_out && argmin_out, LPDT_EINVAL,
+                 "range_evonorm_fwd: NULL argument");
+    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_fwd: eps must be >= 0");
+    LPDT_REQUIRE(aligned(x, 16) && aligned(y, 16), LPDT_EINVAL, "range_evonorm_fwd: x and y must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_fwd_workspace_bytes(N, H, W, C, groups));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    unsigned long long *stats = static_cast<unsigned long long *>(ws);
+    const int count = N * groups, m = C / groups;
+    const float cm = ren_cm(m);
+    hipLaunchKernelGGL(ren_clear_kernel, dim3((2 * count + 255) / 256), dim3(256), 0, st, stats, 2 * count, absmax_out);
+    const size_t smem = (size_t)2 * groups * sizeof(unsigned long long);
+    if (ren_fast(C)) {
+        const RenGeom g = ren_geom(N, H, W, C, groups);
+        hipLaunchKernelGGL(ren_stats_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats);
+        hipLaunchKernelGGL(ren_finalize_kernel, dim3((count + 255) / 256), dim3(256), 0, st, stats, count, range_out,
+                           argmax_out, argmin_out);
+        hipLaunchKernelGGL(ren_apply_kernel, dim3(g.chunks, N), dim3(g.block), 0, st, x, g, v, gamma, beta, cm, eps,
+                           range_out, y, absmax_out);
+    } else {
+        const long long total = (long long)H * W * C;
+        const int blocks = (int)((total + kGenericElems - 1) / kGenericElems);
+        hipLaunchKernelGGL(ren_stats_generic_kernel, dim3(blocks, N), dim3(kRThreads), smem, st, x, H * W, C, groups, m,
+                           kGenericElems, stats);
+        hipLaunchKernelGGL(ren_finalize_kernel, dim3((count + 255) / 256), dim3(256), 0, st, stats, count, range_out,
+                           argmax_out, argmin_out);
+        hipLaunchKernelGGL(ren_apply_generic_kernel, dim3(blocks, N), dim3(kRThreads), 0, st, x, H * W, C, groups, m,
+                           kGenericElems, v, gamma, beta, cm, eps, range_out, y, absmax_out);
+    }
+    return launch_status("lpdt_range_evonorm_fwd");
+}
+
+extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W, int C, int groups,
+                                      const float *v, const float *gamma, float eps, const float *range,
+                                      const int32_t *argmax, const int32_t *argmin, float *dx, float *dv, float *dgamma,
+                                      float *dbeta, float *absmax_out, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_ren(x, N, H, W, C, groups);
+    if (rc) return rc;
+    LPDT_REQUIRE(dy && v && gamma && range && argmax && argmin && dx && dv && dgamma && dbeta, LPDT_EINVAL,
+                 "range_evonorm_bwd: NULL argument");
+    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_bwd: eps must be >= 0");
+    LPDT_REQUIRE(aligned(x, 16) && aligned(dy, 16) && aligned(dx, 16), LPDT_EINVAL,
+                 "range_evonorm_bwd: x, dy and dx must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, groups));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    float *parts = static_cast<float *>(ws);
+    const int m = C / groups, count = N * groups;
+    const float cm = ren_cm(m);
+    int chunks;
+    if (absmax_out) hipLaunchKernelGGL(ren_clear_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)nullptr, 0, absmax_out);
+    if (ren_fast(C)) {
+        const RenGeom g = ren_geom(N, H, W, C, groups);
+        chunks = g.chunks;
+        const size_t smem = (size_t)16 * g.threads * sizeof(float);
+        hipLaunchKernelGGL(ren_bwd_main_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, dy, x, g, v, gamma, cm, eps,
+                           range, argmax, argmin, dx, parts, absmax_out);
+    } else {
+        chunks = (H * W + kGenericPix - 1) / kGenericPix;
+        hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,
+                           kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, absmax_out);
+    }
+    hipLaunchKernelGGL(ren_bwd_param_kernel, dim3((C + 31) / 32), dim3(256), 0, st, parts, N * chunks, C, dbeta, dgamma, dv);
+    hipLaunchKernelGGL(ren_bwd_range_kernel, dim3((count + 127) / 128), dim3(128), 0, st, parts, N, H * W, C, groups, m,
+                       chunks, cm, eps, range, argmax, argmin, dx, absmax_out);
+    return launch_status("lpdt_range_evonorm_bwd");
+}

@@ -1,0 +1,83 @@
+"""GPU parity of the gossip step (plain and CHOCO top-k) and of the glue layers against the oracle."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import assert_close, dev, host
+
+pytestmark = pytest.mark.gpu
+lpdt = pytest.importorskip("paper_2111_09389_amd")
+
+
+@pytest.mark.parametrize("n,d,topo", [(16, 272_474, "ring"), (8, 1000, "ring"), (16, 5003, "torus"), (3, 17, "ring"),
+                                      (33, 2049, "ring"), (64, 300, "ring")])
+@pytest.mark.parametrize("rate", [1.0, 0.37])
+def test_plain_mix(orc, n, d, topo, rate):
+    x = wl.agent_params(800, n, d)
+    Wm = wl.ring_matrix(n) if topo == "ring" else wl.torus_matrix(4, 4)
+    ref, _ = orc.gossip_mix(x, None, Wm, eta=rate)
+    xd = dev(x)
+    lpdt.gossip_mix(xd, None, Wm, rate=rate)
+    # x + rate*(sum_j W_ij x_j - x_i): a few fp32 roundings of terms of size max|x|
+    assert_close(host(xd), ref, 1e-5, float(np.abs(x).max()), "plain mix")
+    assert np.abs(host(xd).astype(np.float64).mean(0) - x.astype(np.float64).mean(0)).max() < 1e-6
+
+
+def _choco_case(orc, n, d, seg, rho, rate, seed, ties=False):
+    if ties:
+        g = wl.rng(seed)
+        x = (g.integers(-6, 7, size=(n, d)) * 0.125).astype(np.float32)
+        xhat = (g.integers(-2, 3, size=(n, d)) * 0.125).astype(np.float32)
+    else:
+        x = wl.agent_params(seed, n, d)
+        xhat = wl.agent_params(seed + 1, n, d, spread=2e-3)
+    Wm = wl.ring_matrix(n)
+    ref_x, ref_h = orc.gossip_mix(x, xhat, Wm, eta=rate, keep_ratio=rho, seg_offsets=seg)
+    xd, hd = dev(x), dev(xhat)
+    lpdt.gossip_mix(xd, hd, Wm, rate=rate, keep_ratio=rho, seg_offsets=seg)
+    assert np.array_equal(host(hd), ref_h), "xhat (top-k membership and update) must be bit-exact"
+    assert_close(host(xd), ref_x, 1e-5, float(np.abs(x).max()), "choco mix")
+
+
+def test_choco_layerwise_topk(orc):
+    # segments shaped like a small conv net's parameter tensors, including tiny ones
+    seg = [0, 432, 448, 464, 480, 2784, 2800, 2816, 2832, 20000, 20001, 20001, 20010, 60000]
+    _choco_case(orc, 16, 60000, seg, 0.01, 0.3, 810)
+    _choco_case(orc, 16, 60000, seg, 0.1, 0.5, 812)
+
+
+def test_choco_global_topk_and_ties(orc):
+    _choco_case(orc, 8, 100_003, None, 0.01, 0.2, 820)
+    _choco_case(orc, 5, 9000, [0, 100, 4500, 9000], 0.05, 0.4, 822, ties=True)   # massive exact ties, zeros
+    _choco_case(orc, 4, 3000, [0, 3000], 0.999, 1.0, 824, ties=True)
+
+
+def test_choco_no_compression(orc):
+    _choco_case(orc, 8, 5000, [0, 1200, 5000], 1.0, 1.0, 830)
+
+
+def test_glue(orc):
+    x = wl.images(840, 3, 9, 9, 20)
+    for k, st, pd in [(2, 2, 0), (3, 2, 1)]:
+        y_ref, idx_ref = orc.maxpool_fwd(x, k, st, pd)
+        y, idx = lpdt.maxpool_fwd(dev(x), k, st, pd)
+        assert np.array_equal(host(y), y_ref) and np.array_equal(host(idx), idx_ref)
+        dy = wl.upstream_grad(841, y_ref.shape)
+        dx = lpdt.maxpool_bwd(dev(dy), idx, x.shape, k, st, pd)
+        assert_close(host(dx), orc.maxpool_bwd(dy.astype(np.float64), idx_ref, x.shape), 1e-6, 1e-3, "maxpool bwd")
+    assert_close(host(lpdt.avgpool_fwd(dev(x))), orc.avgpool_fwd(x), 1e-5, 1e-2, "avgpool fwd")
+    dya = wl.upstream_grad(842, (3, 20))
+    assert_close(host(lpdt.avgpool_bwd(dev(dya), x.shape)), orc.avgpool_bwd(dya.astype(np.float64), x.shape), 1e-6, 0.0, "avgpool bwd")
+    for N, classes in [(7, 10), (64, 100)]:
+        lg = (wl.rng(843).standard_normal((N, classes)) * 3).astype(np.float32)
+        lb = wl.labels_uniform(844, N, classes)
+        loss_ref, dl_ref = orc.softmax_xent(lg, lb)
+        loss, dl = lpdt.softmax_xent(dev(lg), dev(lb))
+        assert abs(host(loss)[0] - loss_ref) < 1e-5 * max(1.0, abs(loss_ref))
+        assert_close(host(dl), dl_ref, 1e-4, 1e-3 / N, "dlogits")
+    a, b = wl.images(845, 2, 5, 5, 7), wl.images(846, 2, 5, 5, 7)
+    # 350 elements: exercises the scalar tail
+    assert np.array_equal(host(lpdt.add(dev(a), dev(b))), (a + b))
+    p = dev(a.copy())
+    lpdt.sgd(p, dev(b), 0.1)
+    assert_close(host(p), orc.sgd(a, b, 0.1), 1e-6, 1e-2, "sgd")

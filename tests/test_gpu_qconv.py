@@ -1,0 +1,73 @@
+"""GPU parity of the three int8 convolutions against the oracle: int32 results bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+lpdt = pytest.importorskip("paper_2111_09389_amd")
+
+# N C H W K R S stride pad -- sizes the oracle finishes in seconds, spanning several tiles with ragged tails
+CASES = [
+    (8, 16, 32, 32, 16, 3, 3, 1, 1),      # the single-layer benchmark configuration
+    (2, 64, 14, 14, 64, 3, 3, 1, 1),
+    (3, 32, 9, 11, 48, 3, 3, 1, 1),       # ragged: M = 297, Cout = 48
+    (2, 64, 15, 15, 128, 3, 3, 2, 1),     # stride 2
+    (2, 128, 8, 8, 256, 3, 3, 1, 1),      # large-tile path, split reduction
+    (2, 64, 16, 16, 128, 1, 1, 2, 0),     # 1x1 stride-2 projection shortcut
+    (5, 48, 7, 7, 80, 1, 1, 1, 0),
+    (70, 64, 1, 1, 10, 1, 1, 1, 0),       # linear layer 64 -> 10
+    (33, 512, 1, 1, 512, 1, 1, 1, 0),     # linear layer
+    (2, 3, 32, 32, 16, 3, 3, 1, 1),       # first layer, 3 input channels
+    (1, 3, 37, 37, 64, 7, 7, 2, 3),       # stem-like 7x7 stride 2
+    (2, 16, 12, 12, 32, 7, 7, 2, 3),      # 49 taps with channel-multiple-of-16
+    (1, 20, 6, 6, 24, 3, 3, 1, 1),        # channel counts that are not multiples of 16
+    (1, 256, 4, 4, 512, 3, 3, 1, 1),
+]
+
+
+def _data(shp, seed, kind):
+    N, C, H, W, K, R, S, st, pd = shp
+    P, Q = wl.conv_out(H, pd, R, st), wl.conv_out(W, pd, S, st)
+    return (wl.int8_codes(seed, (N, H, W, C), kind), wl.int8_codes(seed + 1, (K, R, S, C), kind),
+            wl.int8_codes(seed + 2, (N, P, Q, K), kind))
+
+
+@pytest.mark.parametrize("shp", CASES)
+@pytest.mark.parametrize("kind", ["gauss", "uniform"])
+def test_three_convs_bit_exact(orc, shp, kind):
+    x, w, g = _data(shp, 300, kind)
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    print("case", shp, kind, flush=True)
+    acc = lpdt.qconv_fwd(ld, dev(x), dev(w))
+    assert np.array_equal(host(acc), orc.qconv_fwd(od, x, w)), "forward"
+    dx = lpdt.qconv_bwd_data(ld, dev(g), dev(w))
+    assert np.array_equal(host(dx), orc.qconv_bwd_data(od, g, w)), "backward-data"
+    dw = lpdt.qconv_bwd_weight(ld, dev(g), dev(x))
+    assert np.array_equal(host(dw), orc.qconv_bwd_weight(od, g, x)), "backward-weight"
+
+
+def test_extreme_codes_no_overflow_in_range(orc):
+    # all +-127 with reduction length 4608 (fwd) / 1152 (wgrad): the largest magnitudes the path can see here
+    shp = (2, 512, 6, 6, 64, 3, 3, 1, 1)
+    x, w, g = _data(shp, 400, "extreme")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert np.array_equal(host(lpdt.qconv_fwd(ld, dev(x), dev(w))), orc.qconv_fwd(od, x, w))
+    assert np.array_equal(host(lpdt.qconv_bwd_data(ld, dev(g), dev(w))), orc.qconv_bwd_data(od, g, w))
+    assert np.array_equal(host(lpdt.qconv_bwd_weight(ld, dev(g), dev(x))), orc.qconv_bwd_weight(od, g, x))
+
+
+def test_output_buffers_are_overwritten_and_deterministic():
+    shp = (2, 128, 8, 8, 256, 3, 3, 1, 1)
+    x, w, g = _data(shp, 500, "gauss")
+    ld = lpdt.ConvDesc.make(*shp)
+    junk = torch.full((2, 8, 8, 256), 12345, dtype=torch.int32, device="cuda")
+    a = lpdt.qconv_fwd(ld, dev(x), dev(w), acc=junk)
+    b = lpdt.qconv_fwd(ld, dev(x), dev(w))
+    assert torch.equal(a, b)
+    junk = torch.full((256, 3, 3, 128), -7, dtype=torch.int32, device="cuda")
+    a = lpdt.qconv_bwd_weight(ld, dev(g), dev(x), dw=junk)
+    b = lpdt.qconv_bwd_weight(ld, dev(g), dev(x))
+    assert torch.equal(a, b)
