@@ -58,7 +58,8 @@ __global__ __launch_bounds__(kQThreads) void absmax_kernel(const float *__restri
 }
 
 __device__ __forceinline__ int round_code(float x, float inv, bool stochastic, uint32_t word) {
-    const float t = __fmul_rn(x, inv);  // never contracted into an FMA
+#pragma clang fp contract(off)
+    const float t = __fmul_rn(x, inv);  // its own rounding: must not fuse with the subtraction below
     float r;
     if (stochastic) {
         const float f = floorf(t);
