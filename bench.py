@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the 8-bit decentralized-training hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: one agent's
+8-bit training step (quantize, int8 conv fwd / bwd-data / bwd-weight, Range-EvoNorm fwd / bwd,
+glue, local SGD) followed, for the multi-agent configurations, by one gossip step over all
+simulated agents' parameter vectors.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` = int8 convolution operations of a step (2 x MACs by the paper's
+count, Table "hardware_training") divided by the wall time of the WHOLE step.  The conv kernels'
+own rate (ops / time spent inside the three conv entry points, HIP events on the launch stream)
+is in `roofline`, against the published dense int8 MFMA peak.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+HBM_PEAK_GBS = 8000.0
+
+CONFIGS = {
+    1: dict(name="single 3x3 16->16 conv + Range-EvoNorm(g=8), batch 8, 32x32", net="single_layer", batch=8, agents=1, mix=None),
+    2: dict(name="ResNet-20 (REN g=8), batch 128, 32x32x3", net="resnet20", batch=128, agents=1, mix=None),
+    3: dict(name="16 ring agents x ResNet-20 batch 32 + plain gossip mix", net="resnet20", batch=32, agents=16, mix="plain"),
+    4: dict(name="VGG-11 (REN g=32), batch 256, 32x32x3", net="vgg11", batch=256, agents=1, mix=None),
+    5: dict(name="ResNet-18 (REN g=32), batch 64, 224x224x3, 100 classes + CHOCO gossip over 16 ring agents, "
+                 "layer-wise top-1%", net="resnet18", batch=64, agents=16, mix="choco"),
+}
+
+
+def build_workload(cfg_id, device):
+    import numpy as np
+    import torch
+    import workloads as wl
+    from workloads import nets
+    from paper_2111_09389_amd.step import TrainStep
+    cfg = CONFIGS[cfg_id]
+    net = getattr(nets, cfg["net"])()
+    seed = wl.BASE_SEED + cfg_id
+    d = net.num_params()
+    n_agents = cfg["agents"]
+    H, W, C = net.in_shape
+    params0 = nets.init_params(net, seed)
+    flat = np.concatenate([params0[n].ravel() for n, _ in net.params]).astype(np.float32)
+    # agents start from one synchronised model (Section 3) plus a small per-agent drift so that the mix has work to do
+    X = torch.from_numpy(flat).to(device).repeat(n_agents, 1).contiguous()
+    if n_agents > 1:
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        X[1:] += 1e-3 * torch.randn((n_agents - 1, d), generator=gen, device=device)
+    steps = []
+    trained = n_agents if cfg["mix"] == "plain" else 1     # config 5 times one agent's step (its real shape) + the full mix
+    for a in range(trained):
+        x = torch.from_numpy(wl.images(seed + 100 + a, cfg["batch"], H, W, C)).to(device)
+        if net.classes:
+            if cfg_id == 3:
+                lb = wl.labels_dirichlet(seed + 200 + a, cfg["batch"], net.classes, 0.1)
+            else:
+                lb = wl.labels_uniform(seed + 200 + a, cfg["batch"], net.classes)
+            labels, upstream = torch.from_numpy(lb).to(device), None
+        else:
+            labels, upstream = None, torch.from_numpy(wl.upstream_grad(seed + 300, (cfg["batch"], H, W, C))).to(device)
+        grads = torch.zeros(d, dtype=torch.float32, device=device)
+        steps.append(TrainStep(net, cfg["batch"], X[a], grads, x, labels, upstream, lr=0.05, seed=wl.PHILOX_SEED + a))
+    mix = None
+    if cfg["mix"]:
+        import paper_2111_09389_amd as lpdt
+        Wm = wl.ring_matrix(n_agents)
+        ws = lpdt.Workspace(device)
+        if cfg["mix"] == "plain":
+            mix = lambda: lpdt.gossip_mix(X, None, Wm, rate=1.0, ws=ws)
+        else:
+            Xhat = X.clone()
+            gen = torch.Generator(device=device)
+            gen.manual_seed(seed + 1)
+            Xhat += 1e-3 * torch.randn((n_agents, d), generator=gen, device=device)
+            seg = net.param_offsets()
+            mix = lambda: lpdt.gossip_mix(X, Xhat, Wm, rate=0.1, keep_ratio=0.01, seg_offsets=seg, ws=ws)
+            mix()                                               # sizes the workspace outside the timed region
+    return cfg, net, steps, mix, X
+
+
+def cpu_baseline(cfg_id, budget_s=20.0):
+    """The oracle, as it stands, on this host's cores: one training step of the same network at a reduced batch."""
+    import numpy as np
+    import workloads as wl
+    from workloads import nets
+    import oracle
+    from oracle import step as ostep
+    oracle.build()
+    cfg = CONFIGS[cfg_id]
+    net = getattr(nets, cfg["net"])()
+    H, W, C = net.in_shape
+    params = nets.init_params(net, wl.BASE_SEED + cfg_id)
+    batch = 1
+    total_ops, total_t, used = 0, 0.0, 0
+    while True:
+        x = wl.images(9, batch, H, W, C)
+        kw = dict(labels=wl.labels_uniform(10, batch, net.classes)) if net.classes else dict(upstream=wl.upstream_grad(11, (batch, H, W, C)))
+        t0 = time.time()
+        ostep.run_step(net, batch, params, x, seed=1, **kw)
+        dt = time.time() - t0
+        total_ops += 2 * net.conv_macs(batch)[1]
+        total_t += dt
+        used += batch
+        if total_t > budget_s / 3 or batch >= cfg["batch"]:
+            break
+        batch = min(cfg["batch"], batch * 2)
+    cores = len(os.sched_getaffinity(0))
+    try:
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    except ValueError:
+        pass
+    return {"value": total_ops / total_t / 1e12, "unit": "TOPS", "cores": cores, "kind": "oracle",
+            "sample": f"{cfg['net']} training step(s) at batch <= {batch} ({used} images in {total_t:.1f} s), no gossip"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=sorted(CONFIGS))
+    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph (launch-bound configs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (agents are simulated on one device); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists for the product path)", file=sys.stderr)
+        sys.exit(2)
+    import paper_2111_09389_amd as lpdt
+    lpdt.lib()
+    device = torch.device("cuda:0")
+    cfg, net, steps, mix, X = build_workload(args.config, device)
+
+    def one_step(i):
+        for ts in steps:
+            ts.run(i)
+        if mix:
+            mix()
+
+    graph = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one_step(0)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                one_step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+
+    for i in range(args.warmup):
+        graph.replay() if graph else one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        graph.replay() if graph else one_step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+
+    trained_images = cfg["batch"] * len(steps)
+    conv_ops = 2 * net.conv_macs(cfg["batch"])[1] * len(steps)
+    value = conv_ops / (ms_step * 1e-3) / 1e12
+
+    # per-entry-point time of one more step (HIP events on the launch stream)
+    per = {}
+    reps = 3
+    for r in range(reps):
+        for ts in steps:
+            for name, ms in ts.run_timed(args.warmup + args.steps + r):
+                per[name] = per.get(name, 0.0) + ms / reps
+    mix_ms = None
+    if mix:
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            mix()
+        b.record()
+        torch.cuda.synchronize()
+        mix_ms = a.elapsed_time(b) / reps
+    conv_names = ("lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight")
+    conv_ms = sum(per.get(n, 0.0) for n in conv_names)
+    work = {}
+    for ts in steps:
+        for name, macs in ts.conv_work():
+            work[name] = work.get(name, 0) + 2 * macs
+    kind_tops = {n: (work.get(n, 0) / (per[n] * 1e-3) / 1e12 if per.get(n) else None) for n in conv_names}
+    achieved = sum(work.values()) / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else 0.0
+
+    out = {
+        "metric": "int8 qconv fwd+bwd TOPS (conv ops of a step / whole-step time)",
+        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 (int32 accumulate; fp32 normalisation and mixing)", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg['name']}", "batch": cfg["batch"], "agents": cfg["agents"],
+                   "params_per_agent": net.num_params(), "graph_replay": bool(graph)},
+        "images_per_s": trained_images / (ms_step * 1e-3),
+        "pct_of_int8_peak_whole_step": 100.0 * value / INT8_PEAK_TOPS,
+        "entry_point_ms": {k: round(v, 4) for k, v in sorted(per.items())},
+        "gossip_mix_ms": mix_ms,
+        "conv_tops_by_kind": kind_tops,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": achieved / INT8_PEAK_TOPS, "traffic": None,
+                     "kernel": "igemm_kernel + wgrad_kernel (all conv launches of one step: ops / summed duration)"},
+    }
+    if mix_ms:
+        d, n = net.num_params(), cfg["agents"]
+        per_param = 28 if cfg["mix"] == "choco" else 8
+        out["gossip_mix_gbs"] = per_param * n * d / (mix_ms * 1e-3) / 1e9
+        out["gossip_mix_frac_of_hbm_peak"] = out["gossip_mix_gbs"] / HBM_PEAK_GBS
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,300 @@
+"""One agent's 8-bit training step as a fixed sequence of liblpdt calls.
+
+This is sequencing only: it plans buffers once (torch supplies device memory), then
+`run()` issues the library calls of the forward pass, the loss, the backward pass and the
+local SGD step on the current stream.  No arithmetic happens in Python, nothing is
+allocated inside `run()`, so the step can be captured in a HIP graph.
+
+Per quantized convolution (Section 3, "Low Precision Training"):
+  forward : Wq = Q_nearest(W), Xq = Q_nearest(X) (shared by all consumers of X),
+            Y = sX*sW * conv(Xq, Wq)
+  backward: Gq = Q_stochastic(dY), quantized once and used by both products,
+            dX (+)= sG*sW * conv_bwd_data(Gq, Wq)      (skipped for the network input)
+            dW   = sG*sX * conv_bwd_weight(Gq, Xq)      (fp32, never re-quantized)
+Range-EvoNorm hands the abs-max of its outputs to the quantizer that follows it, so that
+quantizer makes a single pass.
+"""
+import ctypes
+
+import torch
+
+from .binding import ConvDesc, LpdtError, lib, ROUND_NEAREST, ROUND_STOCHASTIC
+
+_sz, _vp, _u64, _f32 = ctypes.c_size_t, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_float
+
+
+def _p(t):
+    return _vp(0) if t is None else _vp(t.data_ptr())
+
+
+class TrainStep:
+    """net: a workloads.nets.Net-like object (ops, params, shapes, in_shape, classes).
+    params / grads: flat fp32 device vectors of net.num_params() elements (e.g. a row of the
+    agents' matrix); x: [batch,H,W,C] fp32 device tensor; labels: int32 device tensor or None
+    (then `upstream` must be the gradient of the last tensor)."""
+
+    def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5):
+        self.L = lib()
+        self.net, self.N, self.lr, self.seed, self.eps = net, batch, lr, seed, eps
+        self.dev = params.device
+        self.params, self.grads = params, grads
+        f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=self.dev)
+        i8 = lambda *s: torch.empty(s, dtype=torch.int8, device=self.dev)
+        i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=self.dev)
+        self.pview, self.gview = {}, {}
+        at = 0
+        for name, shp in net.params:
+            k = 1
+            for s in shp:
+                k *= s
+            if at % 4:
+                raise LpdtError(-1, "parameter tensors must start at multiples of 4 elements (16-byte alignment)")
+            self.pview[name] = params[at:at + k].view(shp)
+            self.gview[name] = grads[at:at + k].view(shp)
+            at += k
+        self.act = {"x": x}
+        self.absmax = {}                 # tensor name -> device scalar max|t| (when its producer supplies it)
+        self.calls = []                  # (function, [args...], sr_layer or None)
+        self.ws = torch.empty(1, dtype=torch.uint8, device=self.dev)
+        self._ws_need = 256
+        self.loss = None
+        consumers = {}
+        for op in net.ops:
+            for src in (op[2:4] if op[0] == "add" else ([op[1]] if op[0] == "loss" else [op[2]])):
+                consumers[src] = consumers.get(src, 0) + 1
+        self.consumers = consumers
+        max_acc = 1
+        for op in net.ops:
+            if op[0] == "conv":
+                P, Q, K = net.shapes[op[1]]
+                H, W, C = net.shapes[op[2]]
+                a = op[3]
+                max_acc = max(max_acc, batch * P * Q * K, batch * H * W * C, K * a["R"] * a["R"] * C)
+        self.acc = i32(max_acc)          # int32 accumulators of the convolution in flight
+        self._f32, self._i8, self._i32 = f32, i8, i32
+        self._plan_forward(labels, upstream)
+        self._plan_backward()
+        self.ws = torch.empty(self._ws_need + 256, dtype=torch.uint8, device=self.dev)
+        off = (-self.ws.data_ptr()) % 256
+        self._ws_ptr, self._ws_bytes = _vp(self.ws.data_ptr() + off), _sz(self._ws_need)
+        for c in self.calls:             # workspace arguments were planned as placeholders
+            for i, a in enumerate(c[1]):
+                if a == "WS":
+                    c[1][i] = self._ws_ptr
+                elif a == "WSB":
+                    c[1][i] = self._ws_bytes
+
+    # ------------------------------------------------------------------ planning helpers
+    def _need_ws(self, nbytes):
+        self._ws_need = max(self._ws_need, int(nbytes))
+
+    def _emit(self, fn, args, sr_layer=None):
+        self.calls.append((fn, list(args), sr_layer))
+
+    def _quantize(self, src, q, scale, rounding, absmax=None, sr_layer=None):
+        n = src.numel()
+        if absmax is not None:
+            self._emit(self.L.lpdt_quantize_with_absmax,
+                       [_p(src), _sz(n), _p(absmax), rounding, _u64(self.seed), _u64(0), _p(q), _p(scale)], sr_layer)
+        else:
+            self._need_ws(self.L.lpdt_quantize_workspace_bytes(n))
+            self._emit(self.L.lpdt_quantize,
+                       [_p(src), _sz(n), rounding, _u64(self.seed), _u64(0), _p(q), _p(scale), "WS", "WSB"], sr_layer)
+
+    def _desc(self, inp, a):
+        H, W, C = self.net.shapes[inp]
+        return ConvDesc.make(self.N, C, H, W, a["K"], a["R"], a["R"], a["stride"], a["pad"])
+
+    # ------------------------------------------------------------------ forward
+    def _plan_forward(self, labels, upstream):
+        net, N, L = self.net, self.N, self.L
+        self.xq, self.sx, self.wq, self.sw, self.desc, self.ren_saved, self.pool_idx = {}, {}, {}, {}, {}, {}, {}
+        for op in net.ops:
+            kind = op[0]
+            if kind == "conv":
+                _, out, inp, a = op
+                d = self._desc(inp, a)
+                self.desc[out] = d
+                w = self.pview[a["w"]]
+                self.wq[out], self.sw[out] = self._i8(*w.shape), self._f32(1)
+                self._quantize(w, self.wq[out], self.sw[out], ROUND_NEAREST)
+                if inp not in self.xq:       # one quantization per tensor, shared by its consumers
+                    src = self.act[inp]
+                    self.xq[inp], self.sx[inp] = self._i8(*src.shape), self._f32(1)
+                    self._quantize(src, self.xq[inp], self.sx[inp], ROUND_NEAREST, self.absmax.get(inp))
+                y = self._f32(N, *net.shapes[out])
+                self.act[out] = y
+                self._need_ws(L.lpdt_qconv_fwd_workspace_bytes(ctypes.byref(d)))
+                self._emit(L.lpdt_qconv_fwd, [ctypes.byref(d), _p(self.xq[inp]), _p(self.wq[out]), _p(self.acc), "WS", "WSB"])
+                self._emit(L.lpdt_dequantize, [_p(self.acc), _sz(y.numel()), _p(self.sx[inp]), _p(self.sw[out]), _p(y), 0])
+            elif kind == "ren":
+                _, out, inp, a = op
+                H, W, C = net.shapes[inp]
+                g = a["groups"]
+                y = self._f32(N, H, W, C)
+                self.act[out] = y
+                rng, amx, amn = self._f32(N, g), self._i32(N, g), self._i32(N, g)
+                self.ren_saved[out] = (rng, amx, amn)
+                self.absmax[out] = self._f32(1)
+                self._need_ws(L.lpdt_range_evonorm_fwd_workspace_bytes(N, H, W, C, g))
+                pv = self.pview
+                self._emit(L.lpdt_range_evonorm_fwd,
+                           [_p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
+                            _p(pv[a["p"] + ".beta"]), _f32(self.eps), _p(y), _p(rng), _p(amx), _p(amn),
+                            _p(self.absmax[out]), "WS", "WSB"])
+            elif kind == "add":
+                _, out, a_, b_ = op
+                y = self._f32(N, *net.shapes[out])
+                self.act[out] = y
+                self._emit(L.lpdt_add, [_p(self.act[a_]), _p(self.act[b_]), _sz(y.numel()), _p(y)])
+            elif kind == "maxpool":
+                _, out, inp, a = op
+                H, W, C = net.shapes[inp]
+                y = self._f32(N, *net.shapes[out])
+                idx = self._i32(N, *net.shapes[out])
+                self.act[out], self.pool_idx[out] = y, idx
+                self._emit(L.lpdt_maxpool_fwd, [_p(self.act[inp]), N, H, W, C, a["k"], a["stride"], a["pad"], _p(y), _p(idx)])
+            elif kind == "avgpool":
+                _, out, inp = op
+                H, W, C = net.shapes[inp]
+                y = self._f32(N, 1, 1, C)
+                self.act[out] = y
+                self._emit(L.lpdt_avgpool_fwd, [_p(self.act[inp]), N, H * W, C, _p(y)])
+            elif kind == "loss":
+                inp = op[1]
+                self.loss = self._f32(1 + N)
+                self.grad = {inp: self._f32(N, 1, 1, net.classes)}
+                self._emit(L.lpdt_softmax_xent, [_p(self.act[inp]), _p(labels), N, net.classes, _p(self.loss), _p(self.grad[inp])])
+        if net.ops[-1][0] != "loss":
+            self.grad = {net.ops[-1][1]: upstream}
+
+    # ------------------------------------------------------------------ backward
+    def _grad_target(self, name, pending):
+        """Buffer that receives a gradient contribution for tensor `name` and whether to accumulate.
+        A buffer still owed to another tensor whose producer has not run yet is never updated in place."""
+        if name not in self.grad:
+            self.grad[name] = self._f32(self.N, *self.net.shapes[name])
+            return self.grad[name], 0
+        buf = self.grad[name]
+        for other, t in self.grad.items():
+            if other != name and other in pending and t.data_ptr() == buf.data_ptr():
+                raise LpdtError(-2, f"gradient buffer of {name} is shared with pending tensor {other}")
+        return buf, 1
+
+    def _plan_backward(self):
+        net, N, L = self.net, self.N, self.L
+        self.gabsmax = {}
+        pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
+        conv_index = 0
+        for op in reversed(net.ops):
+            kind = op[0]
+            if kind == "loss":
+                continue
+            out = op[1]
+            pending.discard(out)
+            dy = self.grad.get(out)
+            if dy is None:
+                raise LpdtError(-2, f"tensor {out} has no gradient (dead branch)")
+            if kind == "conv":
+                _, _, inp, a = op
+                d = self.desc[out]
+                conv_index += 1
+                gq, sg = self._i8(*dy.shape), self._f32(1)
+                self._quantize(dy, gq, sg, ROUND_STOCHASTIC, self.gabsmax.get(out), sr_layer=conv_index)
+                if inp != "x":
+                    buf, accumulate = self._grad_target(inp, pending)
+                    self.gabsmax.pop(inp, None)
+                    self._need_ws(L.lpdt_qconv_bwd_data_workspace_bytes(ctypes.byref(d)))
+                    self._emit(L.lpdt_qconv_bwd_data, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(self.acc), "WS", "WSB"])
+                    self._emit(L.lpdt_dequantize, [_p(self.acc), _sz(buf.numel()), _p(sg), _p(self.sw[out]), _p(buf), accumulate])
+                gw = self.gview[a["w"]]
+                self._need_ws(L.lpdt_qconv_bwd_weight_workspace_bytes(ctypes.byref(d)))
+                self._emit(L.lpdt_qconv_bwd_weight, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(self.acc), "WS", "WSB"])
+                self._emit(L.lpdt_dequantize, [_p(self.acc), _sz(gw.numel()), _p(sg), _p(self.sx[inp]), _p(gw), 0])
+            elif kind == "ren":
+                _, _, inp, a = op
+                H, W, C = net.shapes[inp]
+                g = a["groups"]
+                if inp in self.grad:
+                    raise LpdtError(-2, f"Range-EvoNorm input {inp} has another consumer")
+                dx = self._f32(N, H, W, C)
+                self.grad[inp] = dx
+                self.gabsmax[inp] = self._f32(1)
+                rng, amx, amn = self.ren_saved[out]
+                pv, gv = self.pview, self.gview
+                self._need_ws(L.lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, g))
+                self._emit(L.lpdt_range_evonorm_bwd,
+                           [_p(dy), _p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
+                            _f32(self.eps), _p(rng), _p(amx), _p(amn), _p(dx), _p(gv[a["p"] + ".v"]),
+                            _p(gv[a["p"] + ".gamma"]), _p(gv[a["p"] + ".beta"]), _p(self.gabsmax[inp]), "WS", "WSB"])
+            elif kind == "add":
+                _, _, a_, b_ = op
+                for src in (a_, b_):
+                    if src not in self.grad:
+                        self.grad[src] = dy                      # fan-out of the same gradient: no copy
+                        if out in self.gabsmax:
+                            self.gabsmax[src] = self.gabsmax[out]
+                    else:
+                        buf, _ = self._grad_target(src, pending)
+                        self.gabsmax.pop(src, None)
+                        self._emit(L.lpdt_add, [_p(buf), _p(dy), _sz(buf.numel()), _p(buf)])
+            elif kind == "maxpool":
+                _, _, inp, a = op
+                H, W, C = net.shapes[inp]
+                if inp in self.grad:
+                    raise LpdtError(-2, f"max-pool input {inp} has another consumer")
+                dx = self._f32(N, H, W, C)
+                self.grad[inp] = dx
+                self._emit(L.lpdt_maxpool_bwd, [_p(dy), _p(self.pool_idx[out]), N, H, W, C, a["k"], a["stride"], a["pad"], _p(dx)])
+            elif kind == "avgpool":
+                _, _, inp = op
+                H, W, C = net.shapes[inp]
+                if inp in self.grad:
+                    raise LpdtError(-2, f"average-pool input {inp} has another consumer")
+                dx = self._f32(N, H, W, C)
+                self.grad[inp] = dx
+                self._emit(L.lpdt_avgpool_bwd, [_p(dy), N, H * W, C, _p(dx)])
+        # Algorithm 1 step 3: x~ = x - lr * g
+        self._emit(L.lpdt_sgd, [_p(self.params), _p(self.grads), _sz(self.params.numel()), _f32(self.lr)])
+
+    # ------------------------------------------------------------------ execution
+    def run(self, step=0, upto=None):
+        """Enqueue the whole step on the current stream.  Stochastic-rounding counters are
+        offset = step * 2^32 + conv_index * 2^24 (in Philox blocks of 4 elements)."""
+        stream = _vp(torch.cuda.current_stream().cuda_stream)
+        last = self.L.lpdt_last_error
+        for fn, args, sr in (self.calls if upto is None else self.calls[:upto]):
+            if sr is not None:
+                pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
+                args[pos] = _u64((int(step) << 32) + (sr << 24))
+            rc = fn(*args, stream)
+            if rc != 0:
+                raise LpdtError(rc, last().decode())
+
+    def run_timed(self, step=0):
+        """Like run(), but brackets every library call with events on the launch stream and returns
+        [(entry point name, milliseconds)] in call order (one synchronisation at the end)."""
+        stream = _vp(torch.cuda.current_stream().cuda_stream)
+        marks = []
+        for fn, args, sr in self.calls:
+            if sr is not None:
+                pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
+                args[pos] = _u64((int(step) << 32) + (sr << 24))
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rc = fn(*args, stream)
+            b.record()
+            if rc != 0:
+                raise LpdtError(rc, self.L.lpdt_last_error().decode())
+            marks.append((fn.__name__, a, b))
+        torch.cuda.synchronize()
+        return [(name, a.elapsed_time(b)) for name, a, b in marks]
+
+    def conv_work(self):
+        """[(entry point name, int8 multiply-adds)] for every convolution call of one step, in call order."""
+        out = []
+        for fn, args, _ in self.calls:
+            if fn.__name__ in ("lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight"):
+                d = args[0]._obj
+                out.append((fn.__name__, d.N * d.P * d.Q * d.K * d.C * d.R * d.S))
+        return out
