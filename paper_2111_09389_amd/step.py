@@ -183,7 +183,7 @@ class TrainStep:
 
     def _plan_backward(self):
         net, N, L = self.net, self.N, self.L
-        self.gabsmax = {}
+        self.gabsmax, self.gq, self.sg = {}, {}, {}
         pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
         conv_index = 0
         for op in reversed(net.ops):
@@ -200,6 +200,7 @@ class TrainStep:
                 d = self.desc[out]
                 conv_index += 1
                 gq, sg = self._i8(*dy.shape), self._f32(1)
+                self.gq[out], self.sg[out] = gq, sg
                 self._quantize(dy, gq, sg, ROUND_STOCHASTIC, self.gabsmax.get(out), sr_layer=conv_index)
                 if inp != "x":
                     buf, accumulate = self._grad_target(inp, pending)
