@@ -2,9 +2,9 @@
 // plain neighbourhood averaging and CHOCO-SGD (supplement Algorithm 3) with
 // exact layer-wise top-k of |x - xhat|.  Everything is HBM-bound streaming.
 //
-// Mixing: one thread owns one parameter column e and holds all n agents' values
-// of it in registers, so the in-place update has no cross-thread hazard and each
-// row is read once and written once.
+// Mixing: one thread owns one parameter column e and stages all n agents' values of
+// it in its own LDS column, so the in-place update has no cross-thread hazard and
+// each row is read once and written once.
 //
 // Top-k: MSB-first radix select on the 64-bit key (|v| bit pattern << 32 | ~index
 // inside the segment).  Keys are unique, so "key >= k-th largest key" selects
@@ -170,27 +170,42 @@ __global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__rest
 
 // Pass 2: copy the keys whose top 12 bits equal the prefix to the candidate list of
 // their (agent, segment); the list lives at the segment's own offset in `cand`.
+// Matches of the block's first segment are gathered in LDS and get their room in the list
+// with one global atomic per block; the (few) elements of later segments in the same tile
+// reserve their slots one by one.
 __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
                                                                   size_t d, const long long *__restrict__ off, int nseg,
                                                                   PairState *__restrict__ st,
                                                                   unsigned long long *__restrict__ cand) {
+    __shared__ unsigned long long stage[kTile];
     __shared__ int s_first;
+    __shared__ unsigned int s_count, s_base;
     const int agent = blockIdx.y;
     const long long e0 = (long long)blockIdx.x * kTile;
     const long long e1 = min(e0 + (long long)kTile, (long long)d);
-    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    if (threadIdx.x == 0) { s_first = find_segment(off, nseg, e0); s_count = 0u; }
     __syncthreads();
-    int s = s_first;
+    const int sfirst = s_first;
+    int s = sfirst;
+    const unsigned long long first_prefix = st[(size_t)agent * nseg + sfirst].prefix;
     const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
     for (long long e = e0 + threadIdx.x; e < e1; e += kGThreads) {
         while (e >= off[s + 1]) ++s;
         const unsigned long long key = make_key(xr[e], hr[e], (unsigned int)(e - off[s]));
-        PairState *ps = &st[(size_t)agent * nseg + s];
-        if ((key >> 51) == ps->prefix) {
-            const unsigned int slot = atomicAdd(&ps->cand, 1u);
-            cand[(size_t)agent * d + off[s] + slot] = key;
+        if (s == sfirst) {
+            if ((key >> 51) == first_prefix) stage[atomicAdd(&s_count, 1u)] = key;
+        } else {
+            PairState *ps = &st[(size_t)agent * nseg + s];
+            if ((key >> 51) == ps->prefix) cand[(size_t)agent * d + off[s] + atomicAdd(&ps->cand, 1u)] = key;
         }
     }
+    __syncthreads();
+    const unsigned int count = s_count;
+    if (count == 0u) return;
+    if (threadIdx.x == 0) s_base = atomicAdd(&st[(size_t)agent * nseg + sfirst].cand, count);
+    __syncthreads();
+    unsigned long long *dst = cand + (size_t)agent * d + off[sfirst] + s_base;
+    for (unsigned int i = threadIdx.x; i < count; i += kGThreads) dst[i] = stage[i];
 }
 
 // Candidate pass: histogram of key bits [shift, shift+bits) among candidates that match the prefix.

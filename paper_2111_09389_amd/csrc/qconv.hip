@@ -19,7 +19,7 @@
 //      tile is loaded once for 9 products; blocks split the pixel range and combine
 //      with int32 atomic adds (exact, order-free).
 //  Shapes whose channel counts are not multiples of 16 take plain per-output kernels.
-#include "common.h"
+#include "qconv_internal.h"
 
 namespace lpdt {
 
@@ -441,8 +441,9 @@ static void launch_igemm(IgemmParams p, hipStream_t st) {
 
 template <bool BWD>
 static void dispatch_igemm(const IgemmParams &p, hipStream_t st) {
-    if (p.Cout >= 128) launch_igemm<256, 128, 2, 2, BWD>(p, st);
-    else if (p.Cout >= 48) launch_igemm<256, 64, 4, 1, BWD>(p, st);
+    // 128x64 tiles: small enough that every layer of the benchmark networks yields several blocks per CU,
+    // which is what hides the gather latency (measured: faster than 256-row tiles on every ResNet-18 / VGG shape)
+    if (p.Cout >= 48) launch_igemm<128, 64, 2, 2, BWD>(p, st);
     else launch_igemm<128, 32, 4, 1, BWD>(p, st);
 }
 
@@ -452,29 +453,37 @@ static bool same_stride_pad(const lpdt_conv_desc *d) { return d->stride_h == d->
 
 using namespace lpdt;
 
+static bool narrow_ok(const lpdt_conv_desc *d) {
+    if (!d || d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->stride_h <= 0 ||
+        d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0 || d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S)
+        return false;
+    return narrow_conv_supported(d, conv_out(d->H, d->pad_h, d->R, d->stride_h), conv_out(d->W, d->pad_w, d->S, d->stride_w));
+}
+
 extern "C" size_t lpdt_qconv_fwd_workspace_bytes(const lpdt_conv_desc *d) {
-    (void)d;
-    return 0;
+    return narrow_ok(d) ? narrow_fwd_workspace(d) : 0;
 }
 extern "C" size_t lpdt_qconv_bwd_data_workspace_bytes(const lpdt_conv_desc *d) {
     if (!d || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->C <= 0) return 0;
     return round_up((size_t)d->K * d->R * d->S * d->C, 256);
 }
 extern "C" size_t lpdt_qconv_bwd_weight_workspace_bytes(const lpdt_conv_desc *d) {
-    (void)d;
-    return 0;
+    return narrow_ok(d) ? narrow_wgrad_workspace(d) : 0;
 }
 
 extern "C" int lpdt_qconv_fwd(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, int32_t *acc, void *ws,
                               size_t ws_bytes, void *stream) {
-    (void)ws; (void)ws_bytes;
     int P, Q;
     int rc = check_conv(d, &P, &Q);
     if (rc) return rc;
     LPDT_REQUIRE(xq && wq && acc, LPDT_EINVAL, "qconv_fwd: NULL tensor");
     LPDT_REQUIRE(aligned(acc, 4), LPDT_EINVAL, "qconv_fwd: acc must be 4-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_fwd_workspace_bytes(d));
+    if (rc) return rc;
     hipStream_t st = as_stream(stream);
-    if (d->C % 16 == 0 && same_stride_pad(d) && aligned(xq, 16) && aligned(wq, 16)) {
+    if (narrow_conv_supported(d, P, Q)) {
+        launch_narrow_fwd(d, P, Q, xq, wq, acc, ws, st);
+    } else if (d->C % 16 == 0 && same_stride_pad(d) && aligned(xq, 16) && aligned(wq, 16)) {
         IgemmParams p = {};
         p.in = xq; p.wt = wq; p.out = acc;
         p.M = d->N * P * Q; p.Cin = d->C; p.Cout = d->K;
@@ -520,17 +529,20 @@ extern "C" int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, co
 
 extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw, void *ws,
                                      size_t ws_bytes, void *stream) {
-    (void)ws; (void)ws_bytes;
     int P, Q;
     int rc = check_conv(d, &P, &Q);
     if (rc) return rc;
     LPDT_REQUIRE(gq && xq && dw, LPDT_EINVAL, "qconv_bwd_weight: NULL tensor");
     LPDT_REQUIRE(aligned(dw, 4), LPDT_EINVAL, "qconv_bwd_weight: dw must be 4-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_weight_workspace_bytes(d));
+    if (rc) return rc;
     hipStream_t st = as_stream(stream);
     const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
     const long long M = (long long)d->N * P * Q;
     hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(wlen, 1024)), dim3(kCThreads), 0, st, dw, wlen);
-    if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d) && aligned(gq, 16) && aligned(xq, 16)) {
+    if (narrow_conv_supported(d, P, Q) && aligned(gq, 16)) {
+        launch_narrow_wgrad(d, P, Q, gq, xq, dw, ws, st);
+    } else if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d) && aligned(gq, 16) && aligned(xq, 16)) {
         WgradParams p = {};
         p.g = gq; p.x = xq; p.dw = dw;
         p.M = (int)M; p.K = d->K; p.C = d->C; p.H = d->H; p.W = d->W; p.P = P; p.Q = Q;

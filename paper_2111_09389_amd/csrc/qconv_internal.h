@@ -1,0 +1,16 @@
+// Internal interfaces between the convolution translation units.
+#pragma once
+#include "common.h"
+
+namespace lpdt {
+
+// First-layer path (few input channels): one filter row per MFMA K-step, on a zero-padded copy of the image.
+bool narrow_conv_supported(const lpdt_conv_desc *d, int P, int Q);
+size_t narrow_fwd_workspace(const lpdt_conv_desc *d);
+size_t narrow_wgrad_workspace(const lpdt_conv_desc *d);
+void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, void *ws,
+                       hipStream_t st);
+void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
+                         hipStream_t st);
+
+}  // namespace lpdt

@@ -1,0 +1,321 @@
+// First-layer convolutions: very few input channels (the RGB image), so one filter
+// ROW (S taps x C channels <= 32 bytes) is one MFMA K-step instead of one tap.
+//
+// The int8 image is first copied into a zero-padded buffer, so every later access is
+// in bounds and needs no mask.  For output pixel (n, oy, ox) and filter row r the
+// operand is then the 32 contiguous bytes starting at xp[n][oy*stride + r][ox*stride][0]
+// (bytes past S*C meet zero filter entries), read with byte-aligned 16-byte loads.
+//   forward : filter rows live in registers for the whole kernel; each wave streams
+//             32-pixel row blocks: R loads + R*ceil(K/32) MFMAs + the int32 store, which
+//             is what bounds it (4 bytes written per output element).
+//   weight gradient: dw[k][r][s*C+c] = sum_m g[m][k] * window(m, r)[s*C+c]; gradient tile
+//             and window tile are staged in LDS in [pixel][byte] order and read with the
+//             transposing LDS load, exactly as in the general weight-gradient kernel; one
+//             filter row is one 32-column MFMA tile.
+#include "qconv_internal.h"
+
+namespace lpdt {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kNR = 8;  // filter rows supported
+
+__device__ __forceinline__ v4i load16_any(const int8_t *p) {  // no alignment assumed
+    v4i v;
+    __builtin_memcpy(&v, p, 16);
+    return v;
+}
+
+// q = m / d for m < 2^24 through one float multiply and a correction step
+__device__ __forceinline__ int div24(int m, int d, float inv) {
+    int q = (int)((float)m * inv);
+    int r = m - q * d;
+    if (r < 0) { --q; r += d; }
+    if (r >= d) ++q;
+    return q;
+}
+
+// xp[n][yy][xx][c] = x[n][yy-pad][xx-pad][c] inside the image, 0 in the border and in the slack after the last image
+__global__ void pad_image_kernel(const int8_t *__restrict__ x, int N, int H, int W, int C, int pad, int PH, int PW,
+                                 int8_t *__restrict__ xp, size_t total) {
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(o % C);
+        size_t rest = o / C;
+        const int xx = (int)(rest % PW); rest /= PW;
+        const int yy = (int)(rest % PH);
+        const size_t n = rest / PH;
+        const int iy = yy - pad, ix = xx - pad;
+        int8_t v = 0;
+        if (n < (size_t)N && iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[((n * H + iy) * W + ix) * C + c];
+        xp[o] = v;
+    }
+}
+
+// wr[k][r][j] = w[k][r][j / C][j % C] for j < S*C, else 0   (32 bytes per filter row)
+__global__ void pack_filter_rows_kernel(const int8_t *__restrict__ w, int K, int R, int SC, int8_t *__restrict__ wr) {
+    const int o = blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= K * R * 32) return;
+    const int j = o % 32, kr = o / 32;
+    wr[o] = j < SC ? w[(size_t)kr * SC + j] : (int8_t)0;
+}
+
+struct NarrowParams {
+    const int8_t *xp;   // padded image [N][PH][PW][C] (+ slack)
+    const int8_t *wr;   // packed filter rows [K][R][32]            (forward)
+    const int8_t *g;    // gradient codes [M][K]                     (weight gradient)
+    int32_t *out;       // forward: [M][K] ; weight gradient: dw [K][R][S*C], zeroed before the launch
+    int M, K, C, R, SC, stride, PH, PW, P, Q;
+    float inv_pq, inv_q;
+    int blocks_total;   // row blocks (forward) / 32-pixel steps (weight gradient)
+    int steps_per_block;
+};
+
+__global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
+    const int lane = threadIdx.x % 64, half = lane / 32;
+    const int gwave = blockIdx.x * 4 + threadIdx.x / 64, nwaves = gridDim.x * 4;
+    const int pq = p.P * p.Q;
+    v4i b[kNR][2];
+#pragma unroll
+    for (int r = 0; r < kNR; ++r)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const int n = lane % 32 + 32 * tn;
+            b[r][tn] = v4i{0, 0, 0, 0};
+            if (r < p.R && n < p.K) b[r][tn] = *reinterpret_cast<const v4i *>(p.wr + ((size_t)n * p.R + r) * 32 + 16 * half);
+        }
+    const int row_bytes = p.PW * p.C;
+    for (int rb = gwave; rb < p.blocks_total; rb += nwaves) {
+        const int m = min(rb * 32 + lane % 32, p.M - 1);
+        const int n = div24(m, pq, p.inv_pq), rem = m - n * pq;
+        const int oy = div24(rem, p.Q, p.inv_q), ox = rem - oy * p.Q;
+        const int8_t *src = p.xp + ((size_t)(n * p.PH + oy * p.stride) * p.PW + ox * p.stride) * p.C + 16 * half;
+        v16i acc[2];
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tn][i] = 0;
+        v4i a[kNR];
+#pragma unroll
+        for (int r = 0; r < kNR; ++r)
+            if (r < p.R) a[r] = load16_any(src + (size_t)r * row_bytes);
+#pragma unroll
+        for (int r = 0; r < kNR; ++r)
+            if (r < p.R) {
+                acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[r][0], acc[0], 0, 0, 0);
+                if (p.K > 32) acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[r][1], acc[1], 0, 0, 0);
+            }
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const int col = lane % 32 + 32 * tn;
+            if (col < p.K) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int mm = rb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                    if (mm < p.M) p.out[(size_t)mm * p.K + col] = acc[tn][i];
+                }
+            }
+        }
+    }
+}
+
+constexpr int kGS = 96;  // LDS bytes per pixel of the gradient tile (64 channels + pad)
+
+__global__ __launch_bounds__(256) void narrow_wgrad_kernel(const NarrowParams p) {
+    constexpr int ITEMS = 3;  // 16-byte items per thread and step: 128 gradient + 32*2R window items <= 768
+    const int XS = p.R * 32 + 16;   // LDS bytes per pixel of the window tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int buf_bytes = 32 * kGS + 32 * XS;
+
+    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
+    const int pq = p.P * p.Q, row_bytes = p.PW * p.C;
+    const int step_begin = blockIdx.x * p.steps_per_block;
+    const int step_end = min(p.blocks_total, step_begin + p.steps_per_block);
+    if (step_begin >= step_end) return;
+
+    // this thread's items: id < 128 -> gradient (pixel id/4, granule id%4); else window chunk
+    int kind[ITEMS], ipx[ITEMS], m_it[ITEMS], dst[ITEMS], aux[ITEMS];
+    int in_[ITEMS], oy_[ITEMS], ox_[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int id = t + 256 * j;
+        if (id < 128) {
+            kind[j] = 0; ipx[j] = id / 4; aux[j] = (id % 4) * 16;
+            dst[j] = ipx[j] * kGS + aux[j];
+        } else if (id - 128 < 32 * 2 * p.R) {
+            const int id2 = id - 128, chunk = id2 % (2 * p.R);
+            kind[j] = 1; ipx[j] = id2 / (2 * p.R);
+            aux[j] = (chunk / 2) * row_bytes + (chunk % 2) * 16;             // byte offset from the pixel's window origin
+            dst[j] = 32 * kGS + ipx[j] * XS + (chunk / 2) * 32 + (chunk % 2) * 16;
+        } else {
+            kind[j] = 2; ipx[j] = 0; aux[j] = 0; dst[j] = 0;
+        }
+        m_it[j] = step_begin * 32 + ipx[j];
+        in_[j] = div24(min(m_it[j], p.M - 1), pq, p.inv_pq);
+        const int rem = min(m_it[j], p.M - 1) - in_[j] * pq;
+        oy_[j] = div24(rem, p.Q, p.inv_q);
+        ox_[j] = rem - oy_[j] * p.Q;
+    }
+    const int step_q = 32 / p.Q, step_r = 32 % p.Q;
+
+    v4i stage[ITEMS];
+    auto load_items = [&]() {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            v4i v = {0, 0, 0, 0};
+            if (m_it[j] < p.M) {
+                if (kind[j] == 0) {
+                    if (aux[j] < p.K) v = *reinterpret_cast<const v4i *>(p.g + (size_t)m_it[j] * p.K + aux[j]);
+                } else if (kind[j] == 1) {
+                    v = load16_any(p.xp + ((size_t)(in_[j] * p.PH + oy_[j] * p.stride) * p.PW + ox_[j] * p.stride) * p.C + aux[j]);
+                }
+            }
+            stage[j] = v;
+        }
+    };
+    auto advance = [&]() {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            m_it[j] += 32;
+            ox_[j] += step_r;
+            oy_[j] += step_q;
+            if (ox_[j] >= p.Q) { ox_[j] -= p.Q; ++oy_[j]; }
+            while (oy_[j] >= p.P) { oy_[j] -= p.P; ++in_[j]; }
+        }
+    };
+    auto store_items = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if (kind[j] != 2) *reinterpret_cast<v4i *>(lds + buf * buf_bytes + dst[j]) = stage[j];
+    };
+
+    // wave -> channel tile kt (32 gradient channels) and filter rows r = w/2, w/2+2, ...
+    const int kt = wave % 2, r0 = wave / 2;
+    v16i acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0;
+
+    // transposing LDS read: source lane j of a 16-lane block reads pixel j/2, byte offset 8*(j%2);
+    // result lane i then holds byte column i of 8 pixels (see the general weight-gradient kernel)
+    const int blk = lane / 16, j16 = lane % 16;
+    const int src_px = 16 * (blk / 2) + j16 / 2, src_ch = 16 * (blk % 2) + 8 * (j16 % 2);
+    const int a_off = src_px * kGS + 32 * kt + src_ch;
+    const int b_off = 32 * kGS + src_px * XS + src_ch;
+    typedef __attribute__((address_space(3))) v2i lds_v2i;
+
+    load_items();
+    store_items(0);
+    advance();
+    __syncthreads();
+    for (int st = step_begin; st < step_end; ++st) {
+        const int buf = (st - step_begin) & 1;
+        const bool more = st + 1 < step_end;
+        if (more) load_items();
+        unsigned char *base = lds + buf * buf_bytes;
+        const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off));
+        const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off + 8 * kGS));
+        const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = r0 + 2 * i;
+            if (r < p.R) {
+                const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + r * 32));
+                const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + r * 32 + 8 * XS));
+                const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+            }
+        }
+        if (more) {
+            store_items(buf ^ 1);
+            advance();
+        }
+        __syncthreads();
+    }
+    const int j = lane % 32;
+    if (j < p.SC) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = r0 + 2 * i;
+            if (r < p.R) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int k = 32 * kt + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
+                    if (k < p.K && acc[i][e] != 0) atomicAdd(p.out + ((size_t)k * p.R + r) * p.SC + j, acc[i][e]);
+                }
+            }
+        }
+    }
+}
+
+static size_t padded_bytes(int N, int C, int H, int W, int pad_h, int pad_w) {
+    return (size_t)N * (H + 2 * pad_h) * (W + 2 * pad_w) * C + 64;
+}
+
+bool narrow_conv_supported(const lpdt_conv_desc *d, int P, int Q) {
+    if (d->C % 16 == 0) return false;                 // wide inputs take the gather kernels
+    if (d->S * d->C > 32 || d->R > kNR) return false;
+    if (d->K % 16 || d->K > 64) return false;
+    if (d->stride_h != d->stride_w || d->pad_h != d->pad_w) return false;
+    if ((long long)d->N * P * Q >= (1 << 24)) return false;  // div24 range
+    if (padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w) >= (1ull << 31)) return false;
+    return true;
+}
+
+size_t narrow_fwd_workspace(const lpdt_conv_desc *d) {
+    return round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256) + round_up((size_t)d->K * d->R * 32, 256);
+}
+size_t narrow_wgrad_workspace(const lpdt_conv_desc *d) {
+    return round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256);
+}
+
+static NarrowParams narrow_params(const lpdt_conv_desc *d, int P, int Q, const int8_t *xp) {
+    NarrowParams p = {};
+    p.xp = xp;
+    p.M = d->N * P * Q; p.K = d->K; p.C = d->C; p.R = d->R; p.SC = d->S * d->C; p.stride = d->stride_h;
+    p.PH = d->H + 2 * d->pad_h; p.PW = d->W + 2 * d->pad_w; p.P = P; p.Q = Q;
+    p.inv_pq = 1.0f / (float)(P * Q);
+    p.inv_q = 1.0f / (float)Q;
+    return p;
+}
+
+static void launch_pad(const lpdt_conv_desc *d, const int8_t *x, int8_t *xp, hipStream_t st) {
+    const size_t total = padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w);
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(pad_image_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, d->N, d->H, d->W, d->C, d->pad_h,
+                       d->H + 2 * d->pad_h, d->W + 2 * d->pad_w, xp, total);
+}
+
+void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, void *ws,
+                       hipStream_t st) {
+    int8_t *xp = static_cast<int8_t *>(ws);
+    int8_t *wr = xp + round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256);
+    launch_pad(d, x, xp, st);
+    hipLaunchKernelGGL(pack_filter_rows_kernel, dim3((d->K * d->R * 32 + 255) / 256), dim3(256), 0, st, w, d->K, d->R, d->S * d->C, wr);
+    NarrowParams p = narrow_params(d, P, Q, xp);
+    p.wr = wr; p.out = acc;
+    p.blocks_total = (p.M + 31) / 32;
+    int grid = (p.blocks_total + 3) / 4;
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(narrow_fwd_kernel, dim3(grid), dim3(256), 0, st, p);
+}
+
+void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
+                         hipStream_t st) {
+    int8_t *xp = static_cast<int8_t *>(ws);
+    launch_pad(d, x, xp, st);
+    NarrowParams p = narrow_params(d, P, Q, xp);
+    p.g = g; p.out = dw;
+    p.blocks_total = (p.M + 31) / 32;
+    int grid = 512;
+    if (grid > p.blocks_total / 8) grid = p.blocks_total / 8 > 0 ? p.blocks_total / 8 : 1;
+    p.steps_per_block = (p.blocks_total + grid - 1) / grid;
+    grid = (p.blocks_total + p.steps_per_block - 1) / p.steps_per_block;
+    const size_t lds = 2 * (size_t)(32 * kGS + 32 * (d->R * 32 + 16));
+    hipLaunchKernelGGL(narrow_wgrad_kernel, dim3(grid), dim3(256), lds, st, p);
+}
+
+}  // namespace lpdt
