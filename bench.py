@@ -191,7 +191,7 @@ def main():
         b.record()
         torch.cuda.synchronize()
         mix_ms = a.elapsed_time(b) / reps
-    conv_names = ("lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight")
+    conv_names = ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32")
     conv_ms = sum(per.get(n, 0.0) for n in conv_names)
     work = {}
     for ts in steps:

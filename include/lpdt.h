@@ -117,6 +117,24 @@ int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, const int8_t 
 int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw,
                           void *ws, size_t ws_bytes, void *stream);
 
+/* The same three products with the dequantizing scale applied in the kernel epilogue: the result
+ * is the fp32 tensor (s_a*s_b)*sum, bit-identical to the int32 call followed by lpdt_dequantize,
+ * without the int32 tensor making a round trip through HBM.  s_*: fp32 device scalars (the scales
+ * lpdt_quantize wrote).  accumulate != 0 (backward-data only) adds to the gradient already in dx,
+ * for tensors that fan out to several consumers.  Shapes whose reduction is split over blocks
+ * stage their int32 sums in the workspace, which the *_f32_workspace_bytes queries include. */
+size_t lpdt_qconv_fwd_f32_workspace_bytes(const lpdt_conv_desc *d);
+size_t lpdt_qconv_bwd_data_f32_workspace_bytes(const lpdt_conv_desc *d);
+size_t lpdt_qconv_bwd_weight_f32_workspace_bytes(const lpdt_conv_desc *d);
+
+int lpdt_qconv_fwd_f32(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx,
+                       const float *sw, float *y, void *ws, size_t ws_bytes, void *stream);
+int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, const float *sg,
+                            const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes,
+                            void *stream);
+int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, const float *sg,
+                              const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------ Range-EvoNorm
  * Eq. "ren": for every sample n and channel group G (m = C/groups channels),
  *   range = max - min of x over the group's (h, w, channel) slab

@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
     "quantize", "quantize_with_absmax", "dequantize",
-    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight",
+    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
@@ -23,6 +23,8 @@ EXPORTS = [
     "lpdt_quantize_workspace_bytes", "lpdt_quantize", "lpdt_quantize_with_absmax", "lpdt_dequantize",
     "lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes", "lpdt_qconv_bwd_weight_workspace_bytes",
     "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
+    "lpdt_qconv_fwd_f32_workspace_bytes", "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
+    "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix",
@@ -78,7 +80,8 @@ def lib():
                 getattr(L, name).restype = _sz
         L.lpdt_quantize_workspace_bytes.argtypes = [_sz]
         for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
-                     "lpdt_qconv_bwd_weight_workspace_bytes"):
+                     "lpdt_qconv_bwd_weight_workspace_bytes", "lpdt_qconv_fwd_f32_workspace_bytes",
+                     "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
@@ -190,6 +193,35 @@ def qconv_bwd_weight(d, gq, xq, dw=None, ws=None):
     dw = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.int32, device=gq.device) if dw is None else dw
     buf, nb = _ws(ws, lib().lpdt_qconv_bwd_weight_workspace_bytes(ctypes.byref(d)))
     _check(lib().lpdt_qconv_bwd_weight(ctypes.byref(d), _ptr(gq), _ptr(xq), _ptr(dw), _ptr(buf), _sz(nb), _stream()))
+    return dw
+
+
+def qconv_fwd_f32(d, xq, wq, sx, sw, y=None, ws=None):
+    _dev(xq, torch.int8, "qconv_fwd_f32 xq"); _dev(wq, torch.int8, "qconv_fwd_f32 wq")
+    assert tuple(xq.shape) == (d.N, d.H, d.W, d.C) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    y = torch.empty((d.N, d.P, d.Q, d.K), dtype=torch.float32, device=xq.device) if y is None else y
+    buf, nb = _ws(ws, lib().lpdt_qconv_fwd_f32_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_fwd_f32(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(sx), _ptr(sw), _ptr(y), _ptr(buf), _sz(nb), _stream()))
+    return y
+
+
+def qconv_bwd_data_f32(d, gq, wq, sg, sw, dx=None, accumulate=False, ws=None):
+    _dev(gq, torch.int8, "qconv_bwd_data_f32 gq"); _dev(wq, torch.int8, "qconv_bwd_data_f32 wq")
+    assert tuple(gq.shape) == (d.N, d.P, d.Q, d.K) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    dx = torch.empty((d.N, d.H, d.W, d.C), dtype=torch.float32, device=gq.device) if dx is None else dx
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_data_f32(ctypes.byref(d), _ptr(gq), _ptr(wq), _ptr(sg), _ptr(sw), _ptr(dx), int(bool(accumulate)),
+                                         _ptr(buf), _sz(nb), _stream()))
+    return dx
+
+
+def qconv_bwd_weight_f32(d, gq, xq, sg, sx, dw=None, ws=None):
+    _dev(gq, torch.int8, "qconv_bwd_weight_f32 gq"); _dev(xq, torch.int8, "qconv_bwd_weight_f32 xq")
+    assert tuple(gq.shape) == (d.N, d.P, d.Q, d.K) and tuple(xq.shape) == (d.N, d.H, d.W, d.C)
+    dw = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.float32, device=gq.device) if dw is None else dw
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_weight_f32(ctypes.byref(d), _ptr(gq), _ptr(xq), _ptr(sg), _ptr(sx), _ptr(dw), _ptr(buf), _sz(nb),
+                                           _stream()))
     return dw
 
 

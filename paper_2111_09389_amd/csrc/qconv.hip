@@ -33,7 +33,9 @@ constexpr int kCThreads = 256;
 struct IgemmParams {
     const int8_t *in;   // [N][IH][IW][Cin]
     const int8_t *wt;   // [Cout][R][S][Cin]
-    int32_t *out;       // [M][Cout], M = N*OH*OW
+    int32_t *out;       // [M][Cout], M = N*OH*OW; fp32 when out_mode != 0
+    int out_mode;       // 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32, added to what is there
+    const float *sA, *sB;
     int M, Cin, Cout;
     int IH, IW, OH, OW;
     int R, S, stride, pad;
@@ -171,6 +173,7 @@ __global__ __launch_bounds__(kCThreads) void igemm_kernel(const IgemmParams p) {
     }
 
     // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
+    const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -181,7 +184,11 @@ __global__ __launch_bounds__(kCThreads) void igemm_kernel(const IgemmParams p) {
                 const int m = m0 + wm * (BM / WM) + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
                 if (m < p.M && col < p.Cout) {
                     int32_t *dst = p.out + (size_t)m * p.Cout + col;
-                    if (p.atomic_out) atomicAdd(dst, acc[i][j][r]);
+                    if (p.out_mode) {  // the dequantizing scale applied in the epilogue: same arithmetic as lpdt_dequantize
+                        float *fdst = reinterpret_cast<float *>(dst);
+                        const float v = scale * (float)acc[i][j][r];
+                        *fdst = p.out_mode == 2 ? *fdst + v : v;
+                    } else if (p.atomic_out) atomicAdd(dst, acc[i][j][r]);
                     else *dst = acc[i][j][r];
                 }
             }
@@ -419,20 +426,34 @@ static int blocks_for(size_t total, int cap = 65536) {
     return (int)b;
 }
 
+static int igemm_splits(int M, int Cout, int nk, int BM, int BN) {
+    const long long blocks = (long long)((M + BM - 1) / BM) * ((Cout + BN - 1) / BN);
+    int splits = 1;
+    if (blocks < 256 && nk >= 8) {  // too few tiles to fill 256 CUs: split the reduction
+        splits = (int)((512 + blocks - 1) / blocks);
+        if (splits > nk / 4) splits = nk / 4;
+        if (splits < 1) splits = 1;
+    }
+    const int per = (nk + splits - 1) / splits;
+    return (nk + per - 1) / per;
+}
+// tile shape by output channels: 128x64 tiles are small enough that every layer of the benchmark networks yields
+// several blocks per CU, which is what hides the gather latency (measured faster than 256-row tiles everywhere)
+static void igemm_tile(int Cout, int *BM, int *BN) { *BM = 128; *BN = Cout >= 48 ? 64 : 32; }
+static bool igemm_is_split(int M, int Cout, int nk) {
+    int BM, BN;
+    igemm_tile(Cout, &BM, &BN);
+    return igemm_splits(M, Cout, nk, BM, BN) > 1;
+}
+
 template <int BM, int BN, int WM, int WN, bool BWD>
 static void launch_igemm(IgemmParams p, hipStream_t st) {
     const int tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.Cout + BN - 1) / BN;
     const long long blocks = (long long)tiles_m * p.tiles_n;
-    int splits = 1;
-    if (blocks < 256 && p.nk >= 8) {  // too few tiles to fill 256 CUs: split the reduction
-        splits = (int)((512 + blocks - 1) / blocks);
-        if (splits > p.nk / 4) splits = p.nk / 4;
-        if (splits < 1) splits = 1;
-    }
+    const int splits = igemm_splits(p.M, p.Cout, p.nk, BM, BN);
     p.k_per_split = (p.nk + splits - 1) / splits;
-    splits = (p.nk + p.k_per_split - 1) / p.k_per_split;
-    p.atomic_out = splits > 1;
+    p.atomic_out = splits > 1;  // callers never combine a split reduction with a fused fp32 epilogue
     if (p.atomic_out)
         hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for((size_t)p.M * p.Cout, 4096)), dim3(kCThreads), 0, st, p.out,
                            (size_t)p.M * p.Cout);
@@ -441,8 +462,6 @@ static void launch_igemm(IgemmParams p, hipStream_t st) {
 
 template <bool BWD>
 static void dispatch_igemm(const IgemmParams &p, hipStream_t st) {
-    // 128x64 tiles: small enough that every layer of the benchmark networks yields several blocks per CU,
-    // which is what hides the gather latency (measured: faster than 256-row tiles on every ResNet-18 / VGG shape)
     if (p.Cout >= 48) launch_igemm<128, 64, 2, 2, BWD>(p, st);
     else launch_igemm<128, 32, 4, 1, BWD>(p, st);
 }
@@ -471,6 +490,48 @@ extern "C" size_t lpdt_qconv_bwd_weight_workspace_bytes(const lpdt_conv_desc *d)
     return narrow_ok(d) ? narrow_wgrad_workspace(d) : 0;
 }
 
+// Forward product.  out_mode 0: int32 sums to `out`; 1: fp32 sA*sB*sum.  When the kernel that runs cannot apply the
+// scale itself (split reduction, plain kernel) the sums go to the tail of the workspace and a dequantize pass follows.
+static size_t fwd_base_ws(const lpdt_conv_desc *d) { return narrow_ok(d) ? narrow_fwd_workspace(d) : 0; }
+static bool fwd_vec(const lpdt_conv_desc *d) { return d->C % 16 == 0 && same_stride_pad(d); }
+static bool fwd_fusable(const lpdt_conv_desc *d, int P, int Q) {
+    if (narrow_conv_supported(d, P, Q)) return true;
+    if (!fwd_vec(d)) return false;
+    const int gtot = d->R * d->S * (d->C / 16);
+    return !igemm_is_split(d->N * P * Q, d->K, (gtot + 3) / 4);
+}
+
+static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq, const int8_t *wq, void *out, int out_mode,
+                         const float *sA, const float *sB, void *ws, hipStream_t st) {
+    const size_t out_len = (size_t)d->N * P * Q * d->K;
+    const bool stage = out_mode != 0 && !(fwd_fusable(d, P, Q) && aligned(xq, 16) && aligned(wq, 16));
+    int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + round_up(fwd_base_ws(d), 256))
+                         : static_cast<int32_t *>(out);
+    const int mode = stage ? 0 : out_mode;
+    if (narrow_conv_supported(d, P, Q)) {
+        launch_narrow_fwd(d, P, Q, xq, wq, acc, mode, sA, sB, ws, st);
+    } else if (fwd_vec(d) && aligned(xq, 16) && aligned(wq, 16)) {
+        IgemmParams p = {};
+        p.in = xq; p.wt = wq; p.out = acc; p.out_mode = mode; p.sA = sA; p.sB = sB;
+        p.M = d->N * P * Q; p.Cin = d->C; p.Cout = d->K;
+        p.IH = d->H; p.IW = d->W; p.OH = P; p.OW = Q;
+        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
+        p.gpt = d->C / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
+        dispatch_igemm<false>(p, st);
+    } else {
+        hipLaunchKernelGGL(conv_fwd_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, xq, wq, acc, *d, P, Q);
+    }
+    if (stage) launch_dequant(acc, out_len, sA, sB, static_cast<float *>(out), 0, st);
+    return LPDT_OK;
+}
+
+extern "C" size_t lpdt_qconv_fwd_f32_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) return 0;
+    clear_error();
+    return round_up(fwd_base_ws(d), 256) + (fwd_fusable(d, P, Q) ? 0 : round_up((size_t)d->N * P * Q * d->K * 4, 256));
+}
+
 extern "C" int lpdt_qconv_fwd(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, int32_t *acc, void *ws,
                               size_t ws_bytes, void *stream) {
     int P, Q;
@@ -480,22 +541,66 @@ extern "C" int lpdt_qconv_fwd(const lpdt_conv_desc *d, const int8_t *xq, const i
     LPDT_REQUIRE(aligned(acc, 4), LPDT_EINVAL, "qconv_fwd: acc must be 4-byte aligned");
     rc = check_ws(ws, ws_bytes, lpdt_qconv_fwd_workspace_bytes(d));
     if (rc) return rc;
-    hipStream_t st = as_stream(stream);
-    if (narrow_conv_supported(d, P, Q)) {
-        launch_narrow_fwd(d, P, Q, xq, wq, acc, ws, st);
-    } else if (d->C % 16 == 0 && same_stride_pad(d) && aligned(xq, 16) && aligned(wq, 16)) {
-        IgemmParams p = {};
-        p.in = xq; p.wt = wq; p.out = acc;
-        p.M = d->N * P * Q; p.Cin = d->C; p.Cout = d->K;
-        p.IH = d->H; p.IW = d->W; p.OH = P; p.OW = Q;
-        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
-        p.gpt = d->C / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
-        dispatch_igemm<false>(p, st);
-    } else {
-        hipLaunchKernelGGL(conv_fwd_plain_kernel, dim3(blocks_for((size_t)d->N * P * Q * d->K)), dim3(kCThreads), 0, st, xq, wq,
-                           acc, *d, P, Q);
-    }
+    conv_fwd_impl(d, P, Q, xq, wq, acc, 0, nullptr, nullptr, ws, as_stream(stream));
     return launch_status("lpdt_qconv_fwd");
+}
+
+extern "C" int lpdt_qconv_fwd_f32(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx, const float *sw,
+                                  float *y, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(xq && wq && y && sx && sw, LPDT_EINVAL, "qconv_fwd_f32: NULL argument");
+    LPDT_REQUIRE(aligned(y, 16), LPDT_EINVAL, "qconv_fwd_f32: y must be 16-byte aligned");
+    // a misaligned operand forces the plain kernel, which stages its sums: ask for that room too
+    const bool al = aligned(xq, 16) && aligned(wq, 16);
+    const size_t need = al ? lpdt_qconv_fwd_f32_workspace_bytes(d)
+                           : round_up(fwd_base_ws(d), 256) + round_up((size_t)d->N * P * Q * d->K * 4, 256);
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc) return rc;
+    conv_fwd_impl(d, P, Q, xq, wq, y, 1, sx, sw, ws, as_stream(stream));
+    return launch_status("lpdt_qconv_fwd_f32");
+}
+
+// Backward-data product; out_mode 2 adds to the gradient already in `out` (fan-out of a skip connection).
+static size_t bwd_data_base_ws(const lpdt_conv_desc *d) { return round_up((size_t)d->K * d->R * d->S * d->C, 256); }
+static bool bwd_data_vec(const lpdt_conv_desc *d) { return d->K % 16 == 0 && same_stride_pad(d); }
+static bool bwd_data_fusable(const lpdt_conv_desc *d) {
+    if (!bwd_data_vec(d)) return false;
+    const int gtot = d->R * d->S * (d->K / 16);
+    return !igemm_is_split(d->N * d->H * d->W, d->C, (gtot + 3) / 4);
+}
+
+static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *wq, void *out,
+                              int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st) {
+    const size_t out_len = (size_t)d->N * d->H * d->W * d->C;
+    const bool stage = out_mode != 0 && !(bwd_data_fusable(d) && aligned(gq, 16));
+    int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_data_base_ws(d)) : static_cast<int32_t *>(out);
+    const int mode = stage ? 0 : out_mode;
+    if (bwd_data_vec(d) && aligned(gq, 16)) {
+        int8_t *wt = static_cast<int8_t *>(ws);
+        const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
+        hipLaunchKernelGGL(transpose_filter_kernel, dim3(blocks_for(wlen, 2048)), dim3(kCThreads), 0, st, wq, d->K, d->R * d->S,
+                           d->C, wt);
+        IgemmParams p = {};
+        p.in = gq; p.wt = wt; p.out = acc; p.out_mode = mode; p.sA = sA; p.sB = sB;
+        p.M = d->N * d->H * d->W; p.Cin = d->K; p.Cout = d->C;
+        p.IH = P; p.IW = Q; p.OH = d->H; p.OW = d->W;
+        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
+        p.gpt = d->K / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
+        dispatch_igemm<true>(p, st);
+    } else {
+        hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, gq, wq, acc, *d, P, Q);
+    }
+    if (stage) launch_dequant(acc, out_len, sA, sB, static_cast<float *>(out), out_mode == 2, st);
+    return LPDT_OK;
+}
+
+extern "C" size_t lpdt_qconv_bwd_data_f32_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) return 0;
+    clear_error();
+    return bwd_data_base_ws(d) + (bwd_data_fusable(d) ? 0 : round_up((size_t)d->N * d->H * d->W * d->C * 4, 256));
 }
 
 extern "C" int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, int32_t *dx, void *ws,
@@ -507,24 +612,23 @@ extern "C" int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, co
     LPDT_REQUIRE(aligned(dx, 4), LPDT_EINVAL, "qconv_bwd_data: dx must be 4-byte aligned");
     rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_data_workspace_bytes(d));
     if (rc) return rc;
-    hipStream_t st = as_stream(stream);
-    if (d->K % 16 == 0 && same_stride_pad(d) && aligned(gq, 16)) {
-        int8_t *wt = static_cast<int8_t *>(ws);
-        const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
-        hipLaunchKernelGGL(transpose_filter_kernel, dim3(blocks_for(wlen, 2048)), dim3(kCThreads), 0, st, wq, d->K, d->R * d->S,
-                           d->C, wt);
-        IgemmParams p = {};
-        p.in = gq; p.wt = wt; p.out = dx;
-        p.M = d->N * d->H * d->W; p.Cin = d->K; p.Cout = d->C;
-        p.IH = P; p.IW = Q; p.OH = d->H; p.OW = d->W;
-        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
-        p.gpt = d->K / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
-        dispatch_igemm<true>(p, st);
-    } else {
-        hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for((size_t)d->N * d->H * d->W * d->C)), dim3(kCThreads), 0, st,
-                           gq, wq, dx, *d, P, Q);
-    }
+    conv_bwd_data_impl(d, P, Q, gq, wq, dx, 0, nullptr, nullptr, ws, as_stream(stream));
     return launch_status("lpdt_qconv_bwd_data");
+}
+
+extern "C" int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, const float *sg,
+                                       const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && wq && dx && sg && sw, LPDT_EINVAL, "qconv_bwd_data_f32: NULL argument");
+    LPDT_REQUIRE(aligned(dx, 16), LPDT_EINVAL, "qconv_bwd_data_f32: dx must be 16-byte aligned");
+    const size_t need = aligned(gq, 16) ? lpdt_qconv_bwd_data_f32_workspace_bytes(d)
+                                        : bwd_data_base_ws(d) + round_up((size_t)d->N * d->H * d->W * d->C * 4, 256);
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc) return rc;
+    conv_bwd_data_impl(d, P, Q, gq, wq, dx, accumulate ? 2 : 1, sg, sw, ws, as_stream(stream));
+    return launch_status("lpdt_qconv_bwd_data_f32");
 }
 
 extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw, void *ws,
@@ -571,4 +675,30 @@ extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, 
                            dim3(kCThreads), 0, st, gq, xq, dw, *d, P, Q, pix);
     }
     return launch_status("lpdt_qconv_bwd_weight");
+}
+
+extern "C" size_t lpdt_qconv_bwd_weight_f32_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) return 0;
+    clear_error();
+    return round_up(lpdt_qconv_bwd_weight_workspace_bytes(d), 256) + round_up((size_t)d->K * d->R * d->S * d->C * 4, 256);
+}
+
+// The weight-gradient reduction is split over blocks and combined with int32 atomics, so its sums are always staged
+// in the workspace; the filter-sized dequantize pass that follows is negligible.
+extern "C" int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, const float *sg,
+                                         const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && xq && dw && sg && sx, LPDT_EINVAL, "qconv_bwd_weight_f32: NULL argument");
+    LPDT_REQUIRE(aligned(dw, 16), LPDT_EINVAL, "qconv_bwd_weight_f32: dw must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_weight_f32_workspace_bytes(d));
+    if (rc) return rc;
+    const size_t base = round_up(lpdt_qconv_bwd_weight_workspace_bytes(d), 256);
+    int32_t *acc = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + base);
+    rc = lpdt_qconv_bwd_weight(d, gq, xq, acc, ws, base, stream);
+    if (rc) return rc;
+    launch_dequant(acc, (size_t)d->K * d->R * d->S * d->C, sg, sx, dw, 0, as_stream(stream));
+    return launch_status("lpdt_qconv_bwd_weight_f32");
 }

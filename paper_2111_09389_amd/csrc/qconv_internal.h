@@ -8,9 +8,12 @@ namespace lpdt {
 bool narrow_conv_supported(const lpdt_conv_desc *d, int P, int Q);
 size_t narrow_fwd_workspace(const lpdt_conv_desc *d);
 size_t narrow_wgrad_workspace(const lpdt_conv_desc *d);
-void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, void *ws,
-                       hipStream_t st);
+void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, int out_mode,
+                       const float *sA, const float *sB, void *ws, hipStream_t st);
 void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
                          hipStream_t st);
+
+// y = (sA*sB) * acc (+ y when accumulate): the kernel behind lpdt_dequantize
+void launch_dequant(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y, bool accumulate, hipStream_t st);
 
 }  // namespace lpdt

@@ -65,7 +65,9 @@ struct NarrowParams {
     const int8_t *xp;   // padded image [N][PH][PW][C] (+ slack)
     const int8_t *wr;   // packed filter rows [K][R][32]            (forward)
     const int8_t *g;    // gradient codes [M][K]                     (weight gradient)
-    int32_t *out;       // forward: [M][K] ; weight gradient: dw [K][R][S*C], zeroed before the launch
+    int32_t *out;       // forward: [M][K] (fp32 when out_mode != 0) ; weight gradient: dw [K][R][S*C], zeroed before the launch
+    int out_mode;       // forward only: 0 int32 sums, 1 fp32 sA*sB*sum
+    const float *sA, *sB;
     int M, K, C, R, SC, stride, PH, PW, P, Q;
     float inv_pq, inv_q;
     int blocks_total;   // row blocks (forward) / 32-pixel steps (weight gradient)
@@ -86,6 +88,7 @@ __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
             if (r < p.R && n < p.K) b[r][tn] = *reinterpret_cast<const v4i *>(p.wr + ((size_t)n * p.R + r) * 32 + 16 * half);
         }
     const int row_bytes = p.PW * p.C;
+    const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
     for (int rb = gwave; rb < p.blocks_total; rb += nwaves) {
         const int m = min(rb * 32 + lane % 32, p.M - 1);
         const int n = div24(m, pq, p.inv_pq), rem = m - n * pq;
@@ -113,7 +116,10 @@ __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int mm = rb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                    if (mm < p.M) p.out[(size_t)mm * p.K + col] = acc[tn][i];
+                    if (mm < p.M) {
+                        if (p.out_mode) reinterpret_cast<float *>(p.out)[(size_t)mm * p.K + col] = scale * (float)acc[tn][i];
+                        else p.out[(size_t)mm * p.K + col] = acc[tn][i];
+                    }
                 }
             }
         }
@@ -289,14 +295,14 @@ static void launch_pad(const lpdt_conv_desc *d, const int8_t *x, int8_t *xp, hip
                        d->H + 2 * d->pad_h, d->W + 2 * d->pad_w, xp, total);
 }
 
-void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, void *ws,
-                       hipStream_t st) {
+void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, int out_mode,
+                       const float *sA, const float *sB, void *ws, hipStream_t st) {
     int8_t *xp = static_cast<int8_t *>(ws);
     int8_t *wr = xp + round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256);
     launch_pad(d, x, xp, st);
     hipLaunchKernelGGL(pack_filter_rows_kernel, dim3((d->K * d->R * 32 + 255) / 256), dim3(256), 0, st, w, d->K, d->R, d->S * d->C, wr);
     NarrowParams p = narrow_params(d, P, Q, xp);
-    p.wr = wr; p.out = acc;
+    p.wr = wr; p.out = acc; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
     p.blocks_total = (p.M + 31) / 32;
     int grid = (p.blocks_total + 3) / 4;
     if (grid > 2048) grid = 2048;

@@ -3,7 +3,7 @@
 // (Section 3, "Low Precision Training").  HBM-bound kernels: 16-byte loads,
 // 4-byte packed code stores, no atomics (abs-max goes through per-block
 // partials that every block of the rounding pass re-reduces from L2).
-#include "common.h"
+#include "qconv_internal.h"
 
 namespace lpdt {
 
@@ -154,6 +154,12 @@ static int check_quant_args(const float *x, size_t len, int rounding, const int8
     return LPDT_OK;
 }
 
+void launch_dequant(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y, bool accumulate, hipStream_t st) {
+    const int g = grid_for(len, 16);
+    if (accumulate) hipLaunchKernelGGL(dequant_kernel<true>, dim3(g), dim3(kQThreads), 0, st, acc, len, sA, sB, y);
+    else hipLaunchKernelGGL(dequant_kernel<false>, dim3(g), dim3(kQThreads), 0, st, acc, len, sA, sB, y);
+}
+
 }  // namespace lpdt
 
 using namespace lpdt;
@@ -203,10 +209,6 @@ extern "C" int lpdt_dequantize(const int32_t *acc, size_t len, const float *sA, 
     LPDT_REQUIRE(acc && sA && sB && y, LPDT_EINVAL, "dequantize: NULL argument");
     LPDT_REQUIRE(len > 0, LPDT_EUNSUPPORTED, "dequantize: len must be positive");
     LPDT_REQUIRE(aligned(acc, 16) && aligned(y, 16), LPDT_EINVAL, "dequantize: acc and y must be 16-byte aligned");
-    const int g = grid_for(len, 16);
-    if (accumulate)
-        hipLaunchKernelGGL(dequant_kernel<true>, dim3(g), dim3(kQThreads), 0, as_stream(stream), acc, len, sA, sB, y);
-    else
-        hipLaunchKernelGGL(dequant_kernel<false>, dim3(g), dim3(kQThreads), 0, as_stream(stream), acc, len, sA, sB, y);
+    launch_dequant(acc, len, sA, sB, y, accumulate != 0, as_stream(stream));
     return launch_status("lpdt_dequantize");
 }

@@ -4,18 +4,21 @@
 // one sample, so its loads are one contiguous stream; the block's thread count
 // is a multiple of C/4, which pins every thread to one quad of channels and lets
 // it keep its running extrema / channel sums in registers.
-//   forward : stats pass (per-(sample,group) first arg-max / arg-min through packed
-//             64-bit atomic max keys) -> finalize -> elementwise apply
+//   forward : stats pass (per-block, per-group first arg-max / arg-min as packed 64-bit
+//             keys, no global atomics) -> apply pass (each block first folds the block
+//             keys of its sample, then does the elementwise work).  Two launches.
 //   backward: one pass writes the elementwise part of dx and per-block channel
-//             partials; fixed-order reductions give dv, dgamma, dbeta and the range
-//             gradient, which is then added at the saved arg-max / arg-min.
+//             partials; a second launch does the fixed-order reductions for dv, dgamma,
+//             dbeta and, in its last block, adds the range gradient at the saved
+//             arg-max / arg-min and reduces max|dx|.  Two launches.
 #include "common.h"
 #include <cmath>
 
 namespace lpdt {
 
 constexpr int kRThreads = 256;
-constexpr int kPixIters = 16;  // pixels per thread in the streaming passes
+constexpr int kPixIters = 16;    // least pixels per thread in the streaming passes
+constexpr int kMaxBlocks = 2048;  // the streaming grids are kept near this size: enough to fill the chip, few partial rows
 
 struct RenGeom {
     int N, HW, C, groups, m;
@@ -34,7 +37,9 @@ static RenGeom ren_geom(int N, int H, int W, int C, int groups) {
     g.threads = (kRThreads / g.cq) * g.cq;
     g.block = (g.threads + kWave - 1) / kWave * kWave;
     g.ppi = g.threads / g.cq;
-    g.pix_per_block = g.ppi * kPixIters;
+    int iters = kPixIters;
+    while ((long long)N * ((g.HW + g.ppi * iters - 1) / (g.ppi * iters)) > kMaxBlocks && iters < 4096) iters *= 2;
+    g.pix_per_block = g.ppi * iters;
     g.chunks = (g.HW + g.pix_per_block - 1) / g.pix_per_block;
     return g;
 }
@@ -55,13 +60,15 @@ __global__ void ren_clear_kernel(unsigned long long *stats, int count, float *ab
     if (i == 0 && absmax) *absmax = 0.0f;
 }
 
-// stats[(n*groups+g)*2+0] = max key, +1 = min key.  Key = ordered value (inverted for
-// the minimum) in the high word, ~slab_index in the low word: the largest key is the
-// extreme value at its lowest slab index.
+// Key = ordered value (inverted for the minimum) in the high word, ~slab_index in the low word: the
+// largest key is the extreme value at its lowest slab index.  pstats[((n*chunks + chunk)*groups + g)*2 + {0,1}]
+// = this block's max key / min key (0 = the block saw no element of the group).
 __global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__restrict__ x, RenGeom g,
-                                                              unsigned long long *__restrict__ stats) {
+                                                              unsigned long long *__restrict__ pstats,
+                                                              float *__restrict__ absmax_out) {
     extern __shared__ unsigned long long skeys[];  // [groups][2]
     const int n = blockIdx.y;
+    if (absmax_out && blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *absmax_out = 0.0f;  // the apply pass max-es into it
     for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) skeys[i] = 0ull;
     __syncthreads();
     const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
@@ -90,8 +97,8 @@ __global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__res
         atomicMax(&skeys[grp * 2 + 1], ((unsigned long long)(~ordered_bits(mn[e])) << 32) | lo_mn);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x)
-        if (skeys[i]) atomicMax(&stats[(size_t)n * g.groups * 2 + i], skeys[i]);
+    unsigned long long *dst = pstats + ((size_t)n * g.chunks + blockIdx.x) * g.groups * 2;
+    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) dst[i] = skeys[i];
 }
 
 // Any channel count: one element per thread step, keys straight into LDS atomics.
@@ -146,14 +153,50 @@ __device__ __forceinline__ void block_absmax_commit(float m, float *absmax_out, 
     }
 }
 
+// max over the block, written (not max-ed) to *dst: partial results, one per block
+__device__ __forceinline__ void block_absmax_store(float m, float *dst, float *lds) {
+    m = wave_max(m);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    if (lane == 0) lds[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = lds[0];
+        for (int w = 1; w < (int)(blockDim.x + kWave - 1) / kWave; ++w) r = fmaxf(r, lds[w]);
+        *dst = r;
+    }
+}
+
 __global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__restrict__ x, RenGeom g,
                                                               const float *__restrict__ v,
                                                               const float *__restrict__ gamma,
                                                               const float *__restrict__ beta, float cm, float eps,
-                                                              const float *__restrict__ range,
-                                                              float *__restrict__ y, float *__restrict__ absmax_out) {
+                                                              const unsigned long long *__restrict__ pstats,
+                                                              float *__restrict__ y, float *__restrict__ range_out,
+                                                              int32_t *__restrict__ argmax_out, int32_t *__restrict__ argmin_out,
+                                                              float *__restrict__ absmax_out) {
+    extern __shared__ unsigned long long skeys[];  // [groups][2], then float range[groups]
     __shared__ float lds[kRThreads / kWave];
+    float *srange = reinterpret_cast<float *>(skeys + 2 * g.groups);
     const int n = blockIdx.y;
+    // fold the per-block keys of this sample (every block of the sample does it: a few KB out of L2)
+    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) {
+        unsigned long long k = 0ull;
+        const unsigned long long *src = pstats + (size_t)n * g.chunks * g.groups * 2 + i;
+        for (int ch = 0; ch < g.chunks; ++ch) k = max(k, src[(size_t)ch * g.groups * 2]);
+        skeys[i] = k;
+    }
+    __syncthreads();
+    for (int grp = threadIdx.x; grp < g.groups; grp += blockDim.x) {
+        const unsigned long long kmx = skeys[2 * grp], kmn = skeys[2 * grp + 1];
+        const float r = __fsub_rn(from_ordered_bits((uint32_t)(kmx >> 32)), from_ordered_bits(~(uint32_t)(kmn >> 32)));
+        srange[grp] = r;
+        if (blockIdx.x == 0) {
+            range_out[(size_t)n * g.groups + grp] = r;
+            argmax_out[(size_t)n * g.groups + grp] = (int32_t)(~(uint32_t)kmx);
+            argmin_out[(size_t)n * g.groups + grp] = (int32_t)(~(uint32_t)kmn);
+        }
+    }
+    __syncthreads();
     const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
     const int p0 = blockIdx.x * g.pix_per_block;
     const int p1 = min(p0 + g.pix_per_block, g.HW);
@@ -163,7 +206,7 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__res
     for (int e = 0; e < 4; ++e) {
         const int c = qd * 4 + e;
         vv[e] = v[c]; gg[e] = gamma[c]; bb[e] = beta[c];
-        inv[e] = inv_denominator(range[(size_t)n * g.groups + c / g.m], cm, eps);
+        inv[e] = inv_denominator(srange[c / g.m], cm, eps);
     }
     const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
     float4 *yv = reinterpret_cast<float4 *>(y + (size_t)n * g.HW * g.C);
@@ -219,7 +262,7 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
                                                                  const int32_t *__restrict__ argmax,
                                                                  const int32_t *__restrict__ argmin,
                                                                  float *__restrict__ dx, float *__restrict__ parts,
-                                                                 float *__restrict__ absmax_out) {
+                                                                 float *__restrict__ pabs) {
     extern __shared__ float sred[];  // [4][threads*4]
     __shared__ float lds[kRThreads / kWave];
     const int n = blockIdx.y;
@@ -285,7 +328,7 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
         for (int k = 0; k < g.ppi; ++k) s += sred[qn * T4 + (k * g.cq) * 4 + c];
         parts[(row * 4 + qn) * g.C + c] = s;
     }
-    if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+    block_absmax_store(am, pabs + row, lds);
 }
 
 __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float *__restrict__ dy, const float *__restrict__ x,
@@ -296,7 +339,7 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float 
                                                                     const int32_t *__restrict__ argmax,
                                                                     const int32_t *__restrict__ argmin,
                                                                     float *__restrict__ dx, float *__restrict__ parts,
-                                                                    float *__restrict__ absmax_out) {
+                                                                    float *__restrict__ pabs) {
     // one thread per channel (strided), serial over the block's pixels: slow, any C
     __shared__ float lds[kRThreads / kWave];
     const int n = blockIdx.y;
@@ -326,54 +369,59 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float 
         parts[(row * 4 + 2) * C + c] = sv;
         parts[(row * 4 + 3) * C + c] = st;
     }
-    if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+    block_absmax_store(am, pabs + row, lds);
 }
 
-// dbeta, dgamma, dv: column sums of parts over all rows, fixed order.
-// block = 32 channels x 8 row slices
-__global__ __launch_bounds__(256) void ren_bwd_param_kernel(const float *__restrict__ parts, int rows, int C,
-                                                            float *__restrict__ dbeta, float *__restrict__ dgamma,
-                                                            float *__restrict__ dv) {
+// Second backward launch.  Blocks [0, ceil(C/32)): dbeta, dgamma, dv = column sums of parts over all rows in a fixed
+// order (32 channels x 8 row slices per block).  Last block: per (sample, group) the gradient through the range,
+// added at the saved extrema, and max|dx| = max(block partials, the elements just changed).
+__global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__restrict__ parts, const float *__restrict__ pabs,
+                                                             int rows, int N, int HW, int C, int groups, int m, int chunks,
+                                                             float cm, float eps, const float *__restrict__ range,
+                                                             const int32_t *__restrict__ argmax, const int32_t *__restrict__ argmin,
+                                                             float *__restrict__ dx, float *__restrict__ dbeta,
+                                                             float *__restrict__ dgamma, float *__restrict__ dv,
+                                                             float *__restrict__ absmax_out) {
     __shared__ float s[3][8][32];
-    const int cl = threadIdx.x % 32, sl = threadIdx.x / 32;
-    const int c = blockIdx.x * 32 + cl;
-    float a0 = 0, a1 = 0, a2 = 0;
-    if (c < C)
-        for (int r = sl; r < rows; r += 8) {
-            a0 += parts[((size_t)r * 4 + 0) * C + c];
-            a1 += parts[((size_t)r * 4 + 1) * C + c];
-            a2 += parts[((size_t)r * 4 + 2) * C + c];
+    __shared__ float lds[256 / kWave];
+    const int param_blocks = (C + 31) / 32;
+    if ((int)blockIdx.x < param_blocks) {
+        const int cl = threadIdx.x % 32, sl = threadIdx.x / 32;
+        const int c = blockIdx.x * 32 + cl;
+        float a0 = 0, a1 = 0, a2 = 0;
+        if (c < C)
+            for (int r = sl; r < rows; r += 8) {
+                a0 += parts[((size_t)r * 4 + 0) * C + c];
+                a1 += parts[((size_t)r * 4 + 1) * C + c];
+                a2 += parts[((size_t)r * 4 + 2) * C + c];
+            }
+        s[0][sl][cl] = a0; s[1][sl][cl] = a1; s[2][sl][cl] = a2;
+        __syncthreads();
+        if (sl == 0 && c < C) {
+            float b0 = 0, b1 = 0, b2 = 0;
+            for (int k = 0; k < 8; ++k) { b0 += s[0][k][cl]; b1 += s[1][k][cl]; b2 += s[2][k][cl]; }
+            dbeta[c] = b0; dgamma[c] = b1; dv[c] = b2;
         }
-    s[0][sl][cl] = a0; s[1][sl][cl] = a1; s[2][sl][cl] = a2;
-    __syncthreads();
-    if (sl == 0 && c < C) {
-        float b0 = 0, b1 = 0, b2 = 0;
-        for (int k = 0; k < 8; ++k) { b0 += s[0][k][cl]; b1 += s[1][k][cl]; b2 += s[2][k][cl]; }
-        dbeta[c] = b0; dgamma[c] = b1; dv[c] = b2;
+        return;
     }
-}
-
-// one thread per (sample, group): gradient through the range, added at the saved extrema
-__global__ void ren_bwd_range_kernel(const float *__restrict__ parts, int N, int HW, int C, int groups, int m, int chunks,
-                                     float cm, float eps, const float *__restrict__ range,
-                                     const int32_t *__restrict__ argmax, const int32_t *__restrict__ argmin,
-                                     float *__restrict__ dx, float *__restrict__ absmax_out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= N * groups) return;
-    const int n = i / groups, grp = i % groups;
-    float t = 0.0f;
-    for (int ch = 0; ch < chunks; ++ch)
-        for (int cc = 0; cc < m; ++cc) t += parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc];
-    const float inv = inv_denominator(range[i], cm, eps);
-    const float dR = -cm * t * inv * inv;
-    const int ia = argmax[i], ib = argmin[i];
-    const size_t base = (size_t)n * HW * C + (size_t)grp * m;
-    const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
-    dx[pa] += dR;
-    dx[pb] -= dR;
+    float am = 0.0f;
+    for (int i = threadIdx.x; i < N * groups; i += blockDim.x) {
+        const int n = i / groups, grp = i % groups;
+        float t = 0.0f;
+        for (int ch = 0; ch < chunks; ++ch)
+            for (int cc = 0; cc < m; ++cc) t += parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc];
+        const float inv = inv_denominator(range[i], cm, eps);
+        const float dR = -cm * t * inv * inv;
+        const int ia = argmax[i], ib = argmin[i];
+        const size_t base = (size_t)n * HW * C + (size_t)grp * m;
+        const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
+        dx[pa] += dR;
+        dx[pb] -= dR;
+        am = fmaxf(am, fmaxf(fabsf(dx[pa]), fabsf(dx[pb])));
+    }
     if (absmax_out) {
-        const float mm = fmaxf(fabsf(dx[pa]), fabsf(dx[pb]));
-        atomicMax(reinterpret_cast<unsigned int *>(absmax_out), __float_as_uint(mm));
+        for (int r = threadIdx.x; r < rows; r += blockDim.x) am = fmaxf(am, pabs[r]);
+        block_absmax_store(am, absmax_out, lds);
     }
 }
 
@@ -397,18 +445,21 @@ constexpr int kGenericPix = 64;
 
 using namespace lpdt;
 
+static size_t ren_rows(int N, int H, int W, int C, int groups) {
+    if (ren_fast(C)) return (size_t)N * ren_geom(N, H, W, C, groups).chunks;
+    return (size_t)N * (((size_t)H * W + kGenericPix - 1) / kGenericPix);
+}
+
 extern "C" size_t lpdt_range_evonorm_fwd_workspace_bytes(int N, int H, int W, int C, int groups) {
-    (void)H; (void)W; (void)C;
-    if (N <= 0 || groups <= 0) return 0;
-    return round_up((size_t)N * groups * 2 * sizeof(unsigned long long), 256);
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups) return 0;
+    const size_t blocks = ren_fast(C) ? (size_t)N * ren_geom(N, H, W, C, groups).chunks : (size_t)N;
+    return round_up(blocks * groups * 2 * sizeof(unsigned long long), 256);
 }
 
 extern "C" size_t lpdt_range_evonorm_bwd_workspace_bytes(int N, int H, int W, int C, int groups) {
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups) return 0;
-    size_t rows;
-    if (ren_fast(C)) rows = (size_t)N * ren_geom(N, H, W, C, groups).chunks;
-    else rows = (size_t)N * (((size_t)H * W + kGenericPix - 1) / kGenericPix);
-    return round_up(rows * 4 * C * sizeof(float), 256);
+    const size_t rows = ren_rows(N, H, W, C, groups);
+    return round_up(rows * 4 * C * sizeof(float), 256) + round_up(rows * sizeof(float), 256);
 }
 
 extern "C" int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
@@ -427,16 +478,14 @@ extern "C" int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C
     unsigned long long *stats = static_cast<unsigned long long *>(ws);
     const int count = N * groups, m = C / groups;
     const float cm = ren_cm(m);
-    hipLaunchKernelGGL(ren_clear_kernel, dim3((2 * count + 255) / 256), dim3(256), 0, st, stats, 2 * count, absmax_out);
     const size_t smem = (size_t)2 * groups * sizeof(unsigned long long);
     if (ren_fast(C)) {
         const RenGeom g = ren_geom(N, H, W, C, groups);
-        hipLaunchKernelGGL(ren_stats_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats);
-        hipLaunchKernelGGL(ren_finalize_kernel, dim3((count + 255) / 256), dim3(256), 0, st, stats, count, range_out,
-                           argmax_out, argmin_out);
-        hipLaunchKernelGGL(ren_apply_kernel, dim3(g.chunks, N), dim3(g.block), 0, st, x, g, v, gamma, beta, cm, eps,
-                           range_out, y, absmax_out);
+        hipLaunchKernelGGL(ren_stats_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, absmax_out);
+        hipLaunchKernelGGL(ren_apply_kernel, dim3(g.chunks, N), dim3(g.block), smem + groups * sizeof(float), st, x, g, v, gamma,
+                           beta, cm, eps, stats, y, range_out, argmax_out, argmin_out, absmax_out);
     } else {
+        hipLaunchKernelGGL(ren_clear_kernel, dim3((2 * count + 255) / 256), dim3(256), 0, st, stats, 2 * count, absmax_out);
         const long long total = (long long)H * W * C;
         const int blocks = (int)((total + kGenericElems - 1) / kGenericElems);
         hipLaunchKernelGGL(ren_stats_generic_kernel, dim3(blocks, N), dim3(kRThreads), smem, st, x, H * W, C, groups, m,
@@ -463,24 +512,24 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
     rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, groups));
     if (rc) return rc;
     hipStream_t st = as_stream(stream);
-    float *parts = static_cast<float *>(ws);
-    const int m = C / groups, count = N * groups;
+    const int m = C / groups;
     const float cm = ren_cm(m);
+    const size_t rows = ren_rows(N, H, W, C, groups);
+    float *parts = static_cast<float *>(ws);
+    float *pabs = reinterpret_cast<float *>(static_cast<char *>(ws) + round_up(rows * 4 * C * sizeof(float), 256));
     int chunks;
-    if (absmax_out) hipLaunchKernelGGL(ren_clear_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)nullptr, 0, absmax_out);
     if (ren_fast(C)) {
         const RenGeom g = ren_geom(N, H, W, C, groups);
         chunks = g.chunks;
         const size_t smem = (size_t)16 * g.threads * sizeof(float);
         hipLaunchKernelGGL(ren_bwd_main_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, dy, x, g, v, gamma, cm, eps,
-                           range, argmax, argmin, dx, parts, absmax_out);
+                           range, argmax, argmin, dx, parts, pabs);
     } else {
         chunks = (H * W + kGenericPix - 1) / kGenericPix;
         hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,
-                           kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, absmax_out);
+                           kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs);
     }
-    hipLaunchKernelGGL(ren_bwd_param_kernel, dim3((C + 31) / 32), dim3(256), 0, st, parts, N * chunks, C, dbeta, dgamma, dv);
-    hipLaunchKernelGGL(ren_bwd_range_kernel, dim3((count + 127) / 128), dim3(128), 0, st, parts, N, H * W, C, groups, m,
-                       chunks, cm, eps, range, argmax, argmin, dx, absmax_out);
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3((C + 31) / 32 + 1), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+                       groups, m, chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_bwd");
 }

@@ -10,6 +10,7 @@ Per quantized convolution (Section 3, "Low Precision Training"):
             Y = sX*sW * conv(Xq, Wq)
   backward: Gq = Q_stochastic(dY), quantized once and used by both products,
             dX (+)= sG*sW * conv_bwd_data(Gq, Wq)      (skipped for the network input)
+            (the scale products are applied in the convolution kernels' epilogues)
             dW   = sG*sX * conv_bwd_weight(Gq, Xq)      (fp32, never re-quantized)
 Range-EvoNorm hands the abs-max of its outputs to the quantizer that follows it, so that
 quantizer makes a single pass.
@@ -63,14 +64,6 @@ class TrainStep:
             for src in (op[2:4] if op[0] == "add" else ([op[1]] if op[0] == "loss" else [op[2]])):
                 consumers[src] = consumers.get(src, 0) + 1
         self.consumers = consumers
-        max_acc = 1
-        for op in net.ops:
-            if op[0] == "conv":
-                P, Q, K = net.shapes[op[1]]
-                H, W, C = net.shapes[op[2]]
-                a = op[3]
-                max_acc = max(max_acc, batch * P * Q * K, batch * H * W * C, K * a["R"] * a["R"] * C)
-        self.acc = i32(max_acc)          # int32 accumulators of the convolution in flight
         self._f32, self._i8, self._i32 = f32, i8, i32
         self._plan_forward(labels, upstream)
         self._plan_backward()
@@ -124,9 +117,9 @@ class TrainStep:
                     self._quantize(src, self.xq[inp], self.sx[inp], ROUND_NEAREST, self.absmax.get(inp))
                 y = self._f32(N, *net.shapes[out])
                 self.act[out] = y
-                self._need_ws(L.lpdt_qconv_fwd_workspace_bytes(ctypes.byref(d)))
-                self._emit(L.lpdt_qconv_fwd, [ctypes.byref(d), _p(self.xq[inp]), _p(self.wq[out]), _p(self.acc), "WS", "WSB"])
-                self._emit(L.lpdt_dequantize, [_p(self.acc), _sz(y.numel()), _p(self.sx[inp]), _p(self.sw[out]), _p(y), 0])
+                self._need_ws(L.lpdt_qconv_fwd_f32_workspace_bytes(ctypes.byref(d)))
+                self._emit(L.lpdt_qconv_fwd_f32, [ctypes.byref(d), _p(self.xq[inp]), _p(self.wq[out]), _p(self.sx[inp]),
+                                                  _p(self.sw[out]), _p(y), "WS", "WSB"])
             elif kind == "ren":
                 _, out, inp, a = op
                 H, W, C = net.shapes[inp]
@@ -205,13 +198,13 @@ class TrainStep:
                 if inp != "x":
                     buf, accumulate = self._grad_target(inp, pending)
                     self.gabsmax.pop(inp, None)
-                    self._need_ws(L.lpdt_qconv_bwd_data_workspace_bytes(ctypes.byref(d)))
-                    self._emit(L.lpdt_qconv_bwd_data, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(self.acc), "WS", "WSB"])
-                    self._emit(L.lpdt_dequantize, [_p(self.acc), _sz(buf.numel()), _p(sg), _p(self.sw[out]), _p(buf), accumulate])
+                    self._need_ws(L.lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
+                    self._emit(L.lpdt_qconv_bwd_data_f32, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(sg), _p(self.sw[out]),
+                                                           _p(buf), accumulate, "WS", "WSB"])
                 gw = self.gview[a["w"]]
-                self._need_ws(L.lpdt_qconv_bwd_weight_workspace_bytes(ctypes.byref(d)))
-                self._emit(L.lpdt_qconv_bwd_weight, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(self.acc), "WS", "WSB"])
-                self._emit(L.lpdt_dequantize, [_p(self.acc), _sz(gw.numel()), _p(sg), _p(self.sx[inp]), _p(gw), 0])
+                self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)))
+                self._emit(L.lpdt_qconv_bwd_weight_f32, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(sg), _p(self.sx[inp]),
+                                                         _p(gw), "WS", "WSB"])
             elif kind == "ren":
                 _, _, inp, a = op
                 H, W, C = net.shapes[inp]
@@ -295,7 +288,7 @@ class TrainStep:
         """[(entry point name, int8 multiply-adds)] for every convolution call of one step, in call order."""
         out = []
         for fn, args, _ in self.calls:
-            if fn.__name__ in ("lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight"):
+            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32"):
                 d = args[0]._obj
                 out.append((fn.__name__, d.N * d.P * d.Q * d.K * d.C * d.R * d.S))
         return out

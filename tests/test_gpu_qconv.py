@@ -71,3 +71,26 @@ def test_output_buffers_are_overwritten_and_deterministic():
     a = lpdt.qconv_bwd_weight(ld, dev(g), dev(x), dw=junk)
     b = lpdt.qconv_bwd_weight(ld, dev(g), dev(x))
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("shp", [CASES[0], CASES[2], CASES[3], CASES[4], CASES[7], CASES[9], CASES[10], CASES[12]])
+def test_fused_fp32_epilogue_equals_int32_then_dequantize(orc, shp):
+    """The *_f32 entry points must give exactly the bits of the int32 call followed by lpdt_dequantize,
+    and stay within 1e-5 of the oracle's real-valued result."""
+    x, w, g = _data(shp, 600, "gauss")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    sa, sb = np.float32(0.0123), np.float32(3.3e-3)
+    dsa, dsb = dev(np.array([sa])), dev(np.array([sb]))
+    y = lpdt.qconv_fwd_f32(ld, dev(x), dev(w), dsa, dsb)
+    assert torch.equal(y, lpdt.dequantize(lpdt.qconv_fwd(ld, dev(x), dev(w)), dsa, dsb))
+    ref = orc.dequantize(orc.qconv_fwd(od, x, w), sa, sb)
+    assert np.abs(host(y) - ref).max() <= 1e-5 * np.abs(ref).max()
+    dx = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), dsa, dsb)
+    assert torch.equal(dx, lpdt.dequantize(lpdt.qconv_bwd_data(ld, dev(g), dev(w)), dsa, dsb))
+    base = wl.images(601, *host(dx).shape)
+    acc = dev(base)
+    lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), dsa, dsb, dx=acc, accumulate=True)
+    ref = orc.dequantize(orc.qconv_bwd_data(od, g, w), sa, sb) + base
+    assert np.abs(host(acc) - ref).max() <= 1e-5 * max(np.abs(ref).max(), 1.0)
+    dw = lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), dsa, dsb)
+    assert torch.equal(dw, lpdt.dequantize(lpdt.qconv_bwd_weight(ld, dev(g), dev(x)), dsa, dsb))
