@@ -91,7 +91,13 @@ __device__ __forceinline__ unsigned long long make_key(float xv, float hv, unsig
     return ((unsigned long long)(__float_as_uint(v) & 0x7fffffffu) << 32) | (unsigned long long)(~idx_in_seg);
 }
 
-// Pass 1: histogram of key bits 62..51 (the top 12 bits of |v|).
+// Walks to the segment of element e; `end` caches off[s + 1] so the offsets are not re-read per element.
+__device__ __forceinline__ void seek_segment(const long long *__restrict__ off, long long e, int &s, long long &end) {
+    while (e >= end) { ++s; end = off[s + 1]; }
+}
+
+// Pass 1: histogram of key bits 62..51 (the top 12 bits of |v|).  VEC = 4: 16-byte loads (needs d % 4 == 0).
+template <int VEC>
 __global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
                                                                size_t d, const long long *__restrict__ off, int nseg,
                                                                unsigned int *__restrict__ hist) {
@@ -105,15 +111,28 @@ __global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__re
     __syncthreads();
     const int sfirst = s_first;
     int s = sfirst;
+    long long end = off[s + 1];
     const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
-    for (long long e = e0 + threadIdx.x; e < e1; e += kGThreads) {
-        while (e >= off[s + 1]) ++s;
-        const unsigned int bin = (__float_as_uint(__fsub_rn(xr[e], hr[e])) & 0x7fffffffu) >> 19;
-        if (s == sfirst) atomicAdd(&sh[bin], 1u);
-        else atomicAdd(&hist[((size_t)agent * nseg + s) * kBins + bin], 1u);
+    unsigned int *gh_all = hist + (size_t)agent * nseg * kBins;
+    for (long long e = e0 + (long long)threadIdx.x * VEC; e < e1; e += (long long)kGThreads * VEC) {
+        float xv[VEC], hv[VEC];
+        if (VEC == 4) {
+            const float4 a = *reinterpret_cast<const float4 *>(xr + e), b = *reinterpret_cast<const float4 *>(hr + e);
+            xv[0] = a.x; xv[1] = a.y; xv[2] = a.z; xv[3] = a.w;
+            hv[0] = b.x; hv[1] = b.y; hv[2] = b.z; hv[3] = b.w;
+        } else {
+            xv[0] = xr[e]; hv[0] = hr[e];
+        }
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            seek_segment(off, e + u, s, end);
+            const unsigned int bin = (__float_as_uint(__fsub_rn(xv[u], hv[u])) & 0x7fffffffu) >> 19;
+            if (s == sfirst) atomicAdd(&sh[bin], 1u);
+            else atomicAdd(&gh_all[(size_t)s * kBins + bin], 1u);
+        }
     }
     __syncthreads();
-    unsigned int *gh = hist + ((size_t)agent * nseg + sfirst) * kBins;
+    unsigned int *gh = gh_all + (size_t)sfirst * kBins;
     for (int i = threadIdx.x; i < 4096; i += kGThreads)
         if (sh[i]) atomicAdd(&gh[i], sh[i]);
 }
@@ -173,6 +192,7 @@ __global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__rest
 // Matches of the block's first segment are gathered in LDS and get their room in the list
 // with one global atomic per block; the (few) elements of later segments in the same tile
 // reserve their slots one by one.
+template <int VEC>
 __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
                                                                   size_t d, const long long *__restrict__ off, int nseg,
                                                                   PairState *__restrict__ st,
@@ -187,16 +207,28 @@ __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *_
     __syncthreads();
     const int sfirst = s_first;
     int s = sfirst;
+    long long end = off[s + 1], begin = off[s];
     const unsigned long long first_prefix = st[(size_t)agent * nseg + sfirst].prefix;
     const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
-    for (long long e = e0 + threadIdx.x; e < e1; e += kGThreads) {
-        while (e >= off[s + 1]) ++s;
-        const unsigned long long key = make_key(xr[e], hr[e], (unsigned int)(e - off[s]));
-        if (s == sfirst) {
-            if ((key >> 51) == first_prefix) stage[atomicAdd(&s_count, 1u)] = key;
+    for (long long e = e0 + (long long)threadIdx.x * VEC; e < e1; e += (long long)kGThreads * VEC) {
+        float xv[VEC], hv[VEC];
+        if (VEC == 4) {
+            const float4 a = *reinterpret_cast<const float4 *>(xr + e), b = *reinterpret_cast<const float4 *>(hr + e);
+            xv[0] = a.x; xv[1] = a.y; xv[2] = a.z; xv[3] = a.w;
+            hv[0] = b.x; hv[1] = b.y; hv[2] = b.z; hv[3] = b.w;
         } else {
-            PairState *ps = &st[(size_t)agent * nseg + s];
-            if ((key >> 51) == ps->prefix) cand[(size_t)agent * d + off[s] + atomicAdd(&ps->cand, 1u)] = key;
+            xv[0] = xr[e]; hv[0] = hr[e];
+        }
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            if (e + u >= end) { seek_segment(off, e + u, s, end); begin = off[s]; }
+            const unsigned long long key = make_key(xv[u], hv[u], (unsigned int)(e + u - begin));
+            if (s == sfirst) {
+                if ((key >> 51) == first_prefix) stage[atomicAdd(&s_count, 1u)] = key;
+            } else {
+                PairState *ps = &st[(size_t)agent * nseg + s];
+                if ((key >> 51) == ps->prefix) cand[(size_t)agent * d + begin + atomicAdd(&ps->cand, 1u)] = key;
+            }
         }
     }
     __syncthreads();
@@ -232,42 +264,73 @@ __global__ __launch_bounds__(kGThreads) void choco_cand_hist_kernel(const unsign
 }
 
 // Final pass: xhat += top-k(x - xhat) for every agent, then the gossip update of x.
-template <int NMAX>
+// A thread owns VEC adjacent parameter columns (VEC * 4-byte loads per agent row).
+template <int NMAX, int VEC>
 __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__restrict__ x, float *__restrict__ xhat, int n,
                                                                     size_t d, const long long *__restrict__ off, int nseg,
                                                                     const PairState *__restrict__ st, int select_all,
                                                                     MixGraph g, float rate) {
     __shared__ int s_first;
-    const long long e0 = (long long)blockIdx.x * kGThreads;
+    __shared__ unsigned long long sprefix[NMAX];        // thresholds of the block's first segment
+    __shared__ float sh[NMAX][VEC][kGThreads];          // this thread's columns of xhat (after the update)
+    const long long e0 = (long long)blockIdx.x * kGThreads * VEC;
     if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
     __syncthreads();
-    const long long e = e0 + threadIdx.x;
+    const int sfirst = s_first;
+    if ((int)threadIdx.x < n) sprefix[threadIdx.x] = select_all ? 0ull : st[(size_t)threadIdx.x * nseg + sfirst].prefix;
+    __syncthreads();
+    const long long e = e0 + (long long)threadIdx.x * VEC;
     if (e >= (long long)d) return;
-    int s = s_first;
-    while (e >= off[s + 1]) ++s;
-    const unsigned int idx = (unsigned int)(e - off[s]);
-    __shared__ float sh[NMAX][kGThreads];  // this thread's column of xhat (after the update)
-    float xv[NMAX];
+    int seg[VEC];
+    unsigned int idx[VEC];
+    {
+        int s = sfirst;
+        long long end = off[s + 1], begin = off[s];
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            if (e + u >= end && e + u < (long long)d) { seek_segment(off, e + u, s, end); begin = off[s]; }
+            seg[u] = s;
+            idx[u] = (unsigned int)(e + u - begin);
+        }
+    }
+    float xv[NMAX][VEC];
 #pragma unroll
     for (int i = 0; i < NMAX; ++i)
         if (i < n) {
-            xv[i] = x[(size_t)i * d + e];
-            float hv = xhat[(size_t)i * d + e];
-            const unsigned long long key = make_key(xv[i], hv, idx);
-            const bool sel = select_all || key >= st[(size_t)i * nseg + s].prefix;
-            if (sel) {
-                hv = __fadd_rn(hv, __fsub_rn(xv[i], hv));
-                xhat[(size_t)i * d + e] = hv;
+            float hv[VEC];
+            if (VEC == 2) {
+                const float2 a = *reinterpret_cast<const float2 *>(x + (size_t)i * d + e);
+                const float2 b = *reinterpret_cast<const float2 *>(xhat + (size_t)i * d + e);
+                xv[i][0] = a.x; xv[i][VEC - 1] = a.y; hv[0] = b.x; hv[VEC - 1] = b.y;
+            } else {
+                xv[i][0] = x[(size_t)i * d + e]; hv[0] = xhat[(size_t)i * d + e];
             }
-            sh[i][threadIdx.x] = hv;
+            bool any = false;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) {
+                const unsigned long long key = make_key(xv[i][u], hv[u], idx[u]);
+                const unsigned long long thr = seg[u] == sfirst ? sprefix[i] : (select_all ? 0ull : st[(size_t)i * nseg + seg[u]].prefix);
+                if (key >= thr) { hv[u] = __fadd_rn(hv[u], __fsub_rn(xv[i][u], hv[u])); any = true; }
+                sh[i][u][threadIdx.x] = hv[u];
+            }
+            if (any) {
+                if (VEC == 2) *reinterpret_cast<float2 *>(xhat + (size_t)i * d + e) = make_float2(hv[0], hv[VEC - 1]);
+                else xhat[(size_t)i * d + e] = hv[0];
+            }
         }
 #pragma unroll
     for (int i = 0; i < NMAX; ++i)
         if (i < n) {
-            const float hi = sh[i][threadIdx.x];
-            float sum = 0.0f;
-            for (int t = 0; t < g.deg[i]; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][threadIdx.x] - hi);
-            x[(size_t)i * d + e] = xv[i] + rate * sum;
+            float o[VEC];
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) {
+                const float hi = sh[i][u][threadIdx.x];
+                float sum = 0.0f;
+                for (int t = 0; t < g.deg[i]; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - hi);
+                o[u] = xv[i][u] + rate * sum;
+            }
+            if (VEC == 2) *reinterpret_cast<float2 *>(x + (size_t)i * d + e) = make_float2(o[0], o[VEC - 1]);
+            else x[(size_t)i * d + e] = o[0];
         }
 }
 
@@ -402,9 +465,12 @@ extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const flo
                            nseg, d_hist, hist_words);
         const dim3 tiles((unsigned int)((d + kTile - 1) / kTile), n);
         const dim3 ctiles((unsigned int)((d + kCandTile - 1) / kCandTile), n);
-        hipLaunchKernelGGL(choco_hist_kernel, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
+        const bool vec4 = d % 4 == 0 && aligned(x, 16) && aligned(xhat, 16);
+        if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
+        else hipLaunchKernelGGL(choco_hist_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
         hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12);
-        hipLaunchKernelGGL(choco_collect_kernel, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
+        if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
+        else hipLaunchKernelGGL(choco_collect_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
         const int shifts[4] = {38, 25, 12, 0}, widths[4] = {13, 13, 13, 12};
         for (int p = 0; p < 4; ++p) {
             hipLaunchKernelGGL(choco_cand_hist_kernel, ctiles, dim3(kGThreads), 0, st, d_cand, d, d_off, nseg, d_st, shifts[p],
@@ -412,10 +478,15 @@ extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const flo
             hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, widths[p]);
         }
     }
+    const bool vec2 = n <= 16 && d % 2 == 0 && aligned(x, 8) && aligned(xhat, 8);
     dispatch_nmax(n, [&](auto tag) {
         constexpr int NMAX = decltype(tag)::value;
-        hipLaunchKernelGGL(choco_apply_mix_kernel<NMAX>, dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg,
-                           d_st, select_all ? 1 : 0, g, rate);
+        if (NMAX <= 16 && vec2)
+            hipLaunchKernelGGL((choco_apply_mix_kernel<(NMAX <= 16 ? NMAX : 16), 2>), dim3((unsigned)((d / 2 + kGThreads - 1) / kGThreads)),
+                               dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st, select_all ? 1 : 0, g, rate);
+        else
+            hipLaunchKernelGGL((choco_apply_mix_kernel<NMAX, 1>), dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg,
+                               d_st, select_all ? 1 : 0, g, rate);
     });
     return launch_status("lpdt_gossip_mix");
 }

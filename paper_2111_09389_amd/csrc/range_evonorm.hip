@@ -262,10 +262,11 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
                                                                  const int32_t *__restrict__ argmax,
                                                                  const int32_t *__restrict__ argmin,
                                                                  float *__restrict__ dx, float *__restrict__ parts,
-                                                                 float *__restrict__ pabs) {
+                                                                 float *__restrict__ pabs, float *__restrict__ absmax_out) {
     extern __shared__ float sred[];  // [4][threads*4]
     __shared__ float lds[kRThreads / kWave];
     const int n = blockIdx.y;
+    if (absmax_out && blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *absmax_out = 0.0f;  // the second launch max-es into it
     const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
     const int p0 = blockIdx.x * g.pix_per_block;
     const int p1 = min(p0 + g.pix_per_block, g.HW);
@@ -339,10 +340,11 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float 
                                                                     const int32_t *__restrict__ argmax,
                                                                     const int32_t *__restrict__ argmin,
                                                                     float *__restrict__ dx, float *__restrict__ parts,
-                                                                    float *__restrict__ pabs) {
+                                                                    float *__restrict__ pabs, float *__restrict__ absmax_out) {
     // one thread per channel (strided), serial over the block's pixels: slow, any C
     __shared__ float lds[kRThreads / kWave];
     const int n = blockIdx.y;
+    if (absmax_out && blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *absmax_out = 0.0f;
     const int p0 = blockIdx.x * pix_per_block, p1 = min(p0 + pix_per_block, HW);
     const size_t row = (size_t)n * chunks + blockIdx.x;
     float am = 0.0f;
@@ -373,8 +375,10 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float 
 }
 
 // Second backward launch.  Blocks [0, ceil(C/32)): dbeta, dgamma, dv = column sums of parts over all rows in a fixed
-// order (32 channels x 8 row slices per block).  Last block: per (sample, group) the gradient through the range,
-// added at the saved extrema, and max|dx| = max(block partials, the elements just changed).
+// order (32 channels x 8 row slices per block).  The remaining blocks take 256 (sample, group) pairs each: the gradient
+// through the range, added at the saved extrema; they also fold max|dx| = max(block partials of the first launch, the
+// elements just changed) into absmax_out, which the first launch zeroed (a max is order-free, so this stays
+// deterministic).
 __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__restrict__ parts, const float *__restrict__ pabs,
                                                              int rows, int N, int HW, int C, int groups, int m, int chunks,
                                                              float cm, float eps, const float *__restrict__ range,
@@ -404,8 +408,10 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
         }
         return;
     }
+    const int rb = blockIdx.x - param_blocks, nrb = gridDim.x - param_blocks;
     float am = 0.0f;
-    for (int i = threadIdx.x; i < N * groups; i += blockDim.x) {
+    const int i = rb * 256 + threadIdx.x;
+    if (i < N * groups) {
         const int n = i / groups, grp = i % groups;
         float t = 0.0f;
         for (int ch = 0; ch < chunks; ++ch)
@@ -417,11 +423,11 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
         const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
         dx[pa] += dR;
         dx[pb] -= dR;
-        am = fmaxf(am, fmaxf(fabsf(dx[pa]), fabsf(dx[pb])));
+        am = fmaxf(fabsf(dx[pa]), fabsf(dx[pb]));
     }
     if (absmax_out) {
-        for (int r = threadIdx.x; r < rows; r += blockDim.x) am = fmaxf(am, pabs[r]);
-        block_absmax_store(am, absmax_out, lds);
+        for (int r = rb * 256 + threadIdx.x; r < rows; r += nrb * 256) am = fmaxf(am, pabs[r]);
+        block_absmax_commit(am, absmax_out, lds);
     }
 }
 
@@ -523,13 +529,13 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
         chunks = g.chunks;
         const size_t smem = (size_t)16 * g.threads * sizeof(float);
         hipLaunchKernelGGL(ren_bwd_main_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, dy, x, g, v, gamma, cm, eps,
-                           range, argmax, argmin, dx, parts, pabs);
+                           range, argmax, argmin, dx, parts, pabs, absmax_out);
     } else {
         chunks = (H * W + kGenericPix - 1) / kGenericPix;
         hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,
-                           kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs);
+                           kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out);
     }
-    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3((C + 31) / 32 + 1), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3((C + 31) / 32 + (N * groups + 255) / 256), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_bwd");
 }
