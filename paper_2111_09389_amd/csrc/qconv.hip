@@ -486,9 +486,7 @@ extern "C" size_t lpdt_qconv_bwd_data_workspace_bytes(const lpdt_conv_desc *d) {
     if (!d || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->C <= 0) return 0;
     return round_up((size_t)d->K * d->R * d->S * d->C, 256);
 }
-extern "C" size_t lpdt_qconv_bwd_weight_workspace_bytes(const lpdt_conv_desc *d) {
-    return narrow_ok(d) ? narrow_wgrad_workspace(d) : 0;
-}
+
 
 // Forward product.  out_mode 0: int32 sums to `out`; 1: fp32 sA*sB*sum.  When the kernel that runs cannot apply the
 // scale itself (split reduction, plain kernel) the sums go to the tail of the workspace and a dequantize pass follows.
@@ -631,18 +629,30 @@ extern "C" int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq
     return launch_status("lpdt_qconv_bwd_data_f32");
 }
 
-extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw, void *ws,
-                                     size_t ws_bytes, void *stream) {
-    int P, Q;
-    int rc = check_conv(d, &P, &Q);
-    if (rc) return rc;
-    LPDT_REQUIRE(gq && xq && dw, LPDT_EINVAL, "qconv_bwd_weight: NULL tensor");
-    LPDT_REQUIRE(aligned(dw, 4), LPDT_EINVAL, "qconv_bwd_weight: dw must be 4-byte aligned");
-    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_weight_workspace_bytes(d));
-    if (rc) return rc;
-    hipStream_t st = as_stream(stream);
+// Weight gradient.  Which kernel runs: first-layer path, rectangle-stepped kernel (partial tiles + reduction), the
+// flattened-pixel kernel (1x1 spatial maps, large halos) or the plain kernel.  Only the rectangle kernel can apply
+// the dequantizing scale itself; the others stage int32 sums in the workspace for the _f32 entry point.
+static bool wgrad_uses_rect(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
+    return !narrow_conv_supported(d, P, Q) && wgrad_rect_plan(d, P, Q, pl);
+}
+
+static size_t bwd_weight_base_ws(const lpdt_conv_desc *d, int P, int Q) {
+    WgradRectPlan pl;
+    if (narrow_conv_supported(d, P, Q)) return round_up(narrow_wgrad_workspace(d), 256);
+    if (wgrad_rect_plan(d, P, Q, &pl)) return pl.partial_bytes;
+    return 0;
+}
+
+static void conv_bwd_weight_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *xq, void *out, int out_mode,
+                                 const float *sA, const float *sB, void *ws, hipStream_t st) {
     const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
     const long long M = (long long)d->N * P * Q;
+    WgradRectPlan pl;
+    if (aligned(gq, 16) && aligned(xq, 16) && wgrad_uses_rect(d, P, Q, &pl)) {
+        launch_wgrad_rect(d, P, Q, pl, gq, xq, out, out_mode, sA, sB, ws, st);
+        return;
+    }
+    int32_t *dw = out_mode ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_weight_base_ws(d, P, Q)) : static_cast<int32_t *>(out);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(wlen, 1024)), dim3(kCThreads), 0, st, dw, wlen);
     if (narrow_conv_supported(d, P, Q) && aligned(gq, 16)) {
         launch_narrow_wgrad(d, P, Q, gq, xq, dw, ws, st);
@@ -674,18 +684,35 @@ extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, 
         hipLaunchKernelGGL(conv_bwd_weight_plain_kernel, dim3((unsigned)((wlen + kCThreads - 1) / kCThreads), (unsigned)slices),
                            dim3(kCThreads), 0, st, gq, xq, dw, *d, P, Q, pix);
     }
-    return launch_status("lpdt_qconv_bwd_weight");
+    if (out_mode) launch_dequant(dw, wlen, sA, sB, static_cast<float *>(out), false, st);
+}
+
+extern "C" size_t lpdt_qconv_bwd_weight_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
+    return bwd_weight_base_ws(d, P, Q);
 }
 
 extern "C" size_t lpdt_qconv_bwd_weight_f32_workspace_bytes(const lpdt_conv_desc *d) {
     int P, Q;
-    if (check_conv(d, &P, &Q)) return 0;
-    clear_error();
-    return round_up(lpdt_qconv_bwd_weight_workspace_bytes(d), 256) + round_up((size_t)d->K * d->R * d->S * d->C * 4, 256);
+    if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
+    // room for staged int32 sums as well, so that a misaligned operand (which rules out the fused kernel) still fits
+    return bwd_weight_base_ws(d, P, Q) + round_up((size_t)d->K * d->R * d->S * d->C * 4, 256);
 }
 
-// The weight-gradient reduction is split over blocks and combined with int32 atomics, so its sums are always staged
-// in the workspace; the filter-sized dequantize pass that follows is negligible.
+extern "C" int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw, void *ws,
+                                     size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && xq && dw, LPDT_EINVAL, "qconv_bwd_weight: NULL tensor");
+    LPDT_REQUIRE(aligned(dw, 4), LPDT_EINVAL, "qconv_bwd_weight: dw must be 4-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_weight_workspace_bytes(d));
+    if (rc) return rc;
+    conv_bwd_weight_impl(d, P, Q, gq, xq, dw, 0, nullptr, nullptr, ws, as_stream(stream));
+    return launch_status("lpdt_qconv_bwd_weight");
+}
+
 extern "C" int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, const float *sg,
                                          const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream) {
     int P, Q;
@@ -695,10 +722,6 @@ extern "C" int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *
     LPDT_REQUIRE(aligned(dw, 16), LPDT_EINVAL, "qconv_bwd_weight_f32: dw must be 16-byte aligned");
     rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_weight_f32_workspace_bytes(d));
     if (rc) return rc;
-    const size_t base = round_up(lpdt_qconv_bwd_weight_workspace_bytes(d), 256);
-    int32_t *acc = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + base);
-    rc = lpdt_qconv_bwd_weight(d, gq, xq, acc, ws, base, stream);
-    if (rc) return rc;
-    launch_dequant(acc, (size_t)d->K * d->R * d->S * d->C, sg, sx, dw, 0, as_stream(stream));
+    conv_bwd_weight_impl(d, P, Q, gq, xq, dw, 1, sg, sx, ws, as_stream(stream));
     return launch_status("lpdt_qconv_bwd_weight_f32");
 }

@@ -13,6 +13,17 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
 void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
                          hipStream_t st);
 
+// Weight gradient, rectangle-stepped kernel with partial tiles and a fixed-order reduction.
+struct WgradRectPlan {
+    int ch, cw, ncy, ncx, PHp, PWp, steps, steps_per_split, splits, tg, groups, tiles_k, tiles_c;
+    long long out_len;
+    size_t partial_bytes, lds;
+};
+bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *plan);  // false: shape not handled
+// out_mode 0: int32 sums; 1: fp32 sA*sB*sum.  `partial` needs plan.partial_bytes.
+void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPlan &plan, const int8_t *g, const int8_t *x,
+                       void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
+
 // y = (sA*sB) * acc (+ y when accumulate): the kernel behind lpdt_dequantize
 void launch_dequant(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y, bool accumulate, hipStream_t st);
 
