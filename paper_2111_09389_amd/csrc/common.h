@@ -39,4 +39,11 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// s*a (+ prev) as two separately rounded operations: what lpdt_dequantize computes, also in fused epilogues
+__device__ __forceinline__ float dequant_value(float s, int a, float prev, bool accumulate) {
+#pragma clang fp contract(off)
+    const float v = s * (float)a;
+    return accumulate ? prev + v : v;
+}
+
 }  // namespace lpdt

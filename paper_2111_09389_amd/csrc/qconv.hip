@@ -20,6 +20,8 @@
 //      with int32 atomic adds (exact, order-free).
 //  Shapes whose channel counts are not multiples of 16 take plain per-output kernels.
 #include "qconv_internal.h"
+#include <cstdlib>
+#include <type_traits>
 
 namespace lpdt {
 
@@ -28,172 +30,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kCThreads = 256;
-
-// ------------------------------------------------------------------ igemm
-struct IgemmParams {
-    const int8_t *in;   // [N][IH][IW][Cin]
-    const int8_t *wt;   // [Cout][R][S][Cin]
-    int32_t *out;       // [M][Cout], M = N*OH*OW; fp32 when out_mode != 0
-    int out_mode;       // 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32, added to what is there
-    const float *sA, *sB;
-    int M, Cin, Cout;
-    int IH, IW, OH, OW;
-    int R, S, stride, pad;
-    int gpt;            // granules per tap = Cin/16
-    int gtot;           // R*S*gpt
-    int nk;             // K-steps = ceil(gtot/4)
-    int k_per_split;    // K-steps per blockIdx.z
-    int atomic_out;     // combine splits with atomicAdd into a zeroed output
-    int tiles_n;
-};
-
-template <int BM, int BN, int WM, int WN, bool BWD>
-__global__ __launch_bounds__(kCThreads) void igemm_kernel(const IgemmParams p) {
-    constexpr int PLANE_A = BM * 16 + 64, PLANE_B = BN * 16 + 64;  // +64 B: the 4 planes start 16 banks apart
-    constexpr int BUF = 4 * (PLANE_A + PLANE_B);
-    constexpr int RA = BM / 64, RB = (BN + 63) / 64;               // 16-byte items per thread
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
-
-    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
-    const int g4 = t % 4, row0 = t / 4;
-    const int tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int ks_begin = blockIdx.z * p.k_per_split;
-    const int ks_end = min(p.nk, ks_begin + p.k_per_split);
-
-    // this thread's output pixels (rows of the A tile)
-    int rbase[RA], ry[RA], rx[RA];
-#pragma unroll
-    for (int j = 0; j < RA; ++j) {
-        const int m = m0 + row0 + 64 * j;
-        if (m < p.M) {
-            const int n = m / (p.OH * p.OW), rem = m % (p.OH * p.OW);
-            const int oy = rem / p.OW, ox = rem % p.OW;
-            rbase[j] = n * p.IH * p.IW;
-            ry[j] = BWD ? oy + p.pad : oy * p.stride - p.pad;
-            rx[j] = BWD ? ox + p.pad : ox * p.stride - p.pad;
-        } else {
-            rbase[j] = -1; ry[j] = 0; rx[j] = 0;
-        }
-    }
-    // this thread's granule: tap (tr, ts) and channel granule cg, advanced by 4 granules per K-step
-    int gi = ks_begin * 4 + g4;
-    int cg = gi % p.gpt, tap = gi / p.gpt;
-    int tr = tap / p.S, ts = tap % p.S;
-
-    v4i sa[RA], sb[RB];
-    auto load_tiles = [&]() {
-        const bool gvalid = tr < p.R;
-#pragma unroll
-        for (int j = 0; j < RA; ++j) {
-            int iy, ix;
-            bool ok = gvalid && rbase[j] >= 0;
-            if (BWD) {
-                const int ty = ry[j] - tr, tx = rx[j] - ts;
-                iy = ty / p.stride; ix = tx / p.stride;
-                ok = ok && ty >= 0 && tx >= 0 && iy * p.stride == ty && ix * p.stride == tx && iy < p.IH && ix < p.IW;
-            } else {
-                iy = ry[j] + tr; ix = rx[j] + ts;
-                ok = ok && iy >= 0 && iy < p.IH && ix >= 0 && ix < p.IW;
-            }
-            v4i v = {0, 0, 0, 0};
-            if (ok) v = *reinterpret_cast<const v4i *>(p.in + ((size_t)(rbase[j] + iy * p.IW + ix) * p.Cin + cg * 16));
-            sa[j] = v;
-        }
-#pragma unroll
-        for (int j = 0; j < RB; ++j) {
-            const int row = row0 + 64 * j;
-            v4i v = {0, 0, 0, 0};
-            if (gvalid && row < BN && n0 + row < p.Cout)
-                v = *reinterpret_cast<const v4i *>(p.wt + ((size_t)(n0 + row) * p.gtot + gi) * 16);
-            sb[j] = v;
-        }
-    };
-    auto advance = [&]() {
-        gi += 4;
-        cg += 4;
-        while (cg >= p.gpt) {
-            cg -= p.gpt;
-            if (++ts == p.S) { ts = 0; ++tr; }
-        }
-    };
-    auto store_tiles = [&](int buf) {
-        unsigned char *A = lds + buf * BUF, *B = A + 4 * PLANE_A;
-#pragma unroll
-        for (int j = 0; j < RA; ++j) *reinterpret_cast<v4i *>(A + g4 * PLANE_A + (row0 + 64 * j) * 16) = sa[j];
-#pragma unroll
-        for (int j = 0; j < RB; ++j) {
-            const int row = row0 + 64 * j;
-            if (row < BN) *reinterpret_cast<v4i *>(B + g4 * PLANE_B + row * 16) = sb[j];
-        }
-    };
-
-    v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
-    const int wm = wave / WN, wn = wave % WN;
-    const int a_row = wm * (BM / WM) + lane % 32, b_row = wn * (BN / WN) + lane % 32, half = lane / 32;
-
-    if (ks_begin < ks_end) {
-        load_tiles();
-        store_tiles(0);
-        advance();
-    }
-    __syncthreads();
-    for (int ks = ks_begin; ks < ks_end; ++ks) {
-        const int buf = (ks - ks_begin) & 1;
-        const bool more = ks + 1 < ks_end;
-        if (more) load_tiles();
-        const unsigned char *A = lds + buf * BUF, *B = A + 4 * PLANE_A;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            v4i a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                a[i] = *reinterpret_cast<const v4i *>(A + (2 * kk + half) * PLANE_A + (a_row + 32 * i) * 16);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                b[j] = *reinterpret_cast<const v4i *>(B + (2 * kk + half) * PLANE_B + (b_row + 32 * j) * 16);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) {
-            store_tiles(buf ^ 1);
-            advance();
-        }
-        __syncthreads();
-    }
-
-    // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
-    const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (BN / WN) + 32 * j + lane % 32;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * (BM / WM) + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
-                if (m < p.M && col < p.Cout) {
-                    int32_t *dst = p.out + (size_t)m * p.Cout + col;
-                    if (p.out_mode) {  // the dequantizing scale applied in the epilogue: same arithmetic as lpdt_dequantize
-                        float *fdst = reinterpret_cast<float *>(dst);
-                        const float v = scale * (float)acc[i][j][r];
-                        *fdst = p.out_mode == 2 ? *fdst + v : v;
-                    } else if (p.atomic_out) atomicAdd(dst, acc[i][j][r]);
-                    else *dst = acc[i][j][r];
-                }
-            }
-        }
-}
 
 // ------------------------------------------------------------------ wgrad
 struct WgradParams {
@@ -329,17 +165,6 @@ __global__ void fill_i32_kernel(int32_t *dst, size_t len) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < len; i += (size_t)gridDim.x * blockDim.x) dst[i] = 0;
 }
 
-// wt[c][r][s][k] = w[k][r][s][c]
-__global__ void transpose_filter_kernel(const int8_t *__restrict__ w, int K, int RS, int C, int8_t *__restrict__ wt) {
-    const size_t total = (size_t)K * RS * C;
-    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
-        const int k = (int)(o % K);
-        const int rs = (int)((o / K) % RS);
-        const int c = (int)(o / ((size_t)K * RS));
-        wt[o] = w[((size_t)k * RS + rs) * C + c];
-    }
-}
-
 // one thread per output element; any shape
 __global__ __launch_bounds__(kCThreads) void conv_fwd_plain_kernel(const int8_t *__restrict__ x, const int8_t *__restrict__ w,
                                                                    int32_t *__restrict__ acc, lpdt_conv_desc d, int P, int Q) {
@@ -426,46 +251,6 @@ static int blocks_for(size_t total, int cap = 65536) {
     return (int)b;
 }
 
-static int igemm_splits(int M, int Cout, int nk, int BM, int BN) {
-    const long long blocks = (long long)((M + BM - 1) / BM) * ((Cout + BN - 1) / BN);
-    int splits = 1;
-    if (blocks < 256 && nk >= 8) {  // too few tiles to fill 256 CUs: split the reduction
-        splits = (int)((512 + blocks - 1) / blocks);
-        if (splits > nk / 4) splits = nk / 4;
-        if (splits < 1) splits = 1;
-    }
-    const int per = (nk + splits - 1) / splits;
-    return (nk + per - 1) / per;
-}
-// tile shape by output channels: 128x64 tiles are small enough that every layer of the benchmark networks yields
-// several blocks per CU, which is what hides the gather latency (measured faster than 256-row tiles everywhere)
-static void igemm_tile(int Cout, int *BM, int *BN) { *BM = 128; *BN = Cout >= 48 ? 64 : 32; }
-static bool igemm_is_split(int M, int Cout, int nk) {
-    int BM, BN;
-    igemm_tile(Cout, &BM, &BN);
-    return igemm_splits(M, Cout, nk, BM, BN) > 1;
-}
-
-template <int BM, int BN, int WM, int WN, bool BWD>
-static void launch_igemm(IgemmParams p, hipStream_t st) {
-    const int tiles_m = (p.M + BM - 1) / BM;
-    p.tiles_n = (p.Cout + BN - 1) / BN;
-    const long long blocks = (long long)tiles_m * p.tiles_n;
-    const int splits = igemm_splits(p.M, p.Cout, p.nk, BM, BN);
-    p.k_per_split = (p.nk + splits - 1) / splits;
-    p.atomic_out = splits > 1;  // callers never combine a split reduction with a fused fp32 epilogue
-    if (p.atomic_out)
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for((size_t)p.M * p.Cout, 4096)), dim3(kCThreads), 0, st, p.out,
-                           (size_t)p.M * p.Cout);
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, BWD>), dim3((unsigned)blocks, 1, splits), dim3(kCThreads), 0, st, p);
-}
-
-template <bool BWD>
-static void dispatch_igemm(const IgemmParams &p, hipStream_t st) {
-    if (p.Cout >= 48) launch_igemm<128, 64, 2, 2, BWD>(p, st);
-    else launch_igemm<128, 32, 4, 1, BWD>(p, st);
-}
-
 static bool same_stride_pad(const lpdt_conv_desc *d) { return d->stride_h == d->stride_w && d->pad_h == d->pad_w; }
 
 }  // namespace lpdt
@@ -491,12 +276,10 @@ extern "C" size_t lpdt_qconv_bwd_data_workspace_bytes(const lpdt_conv_desc *d) {
 // Forward product.  out_mode 0: int32 sums to `out`; 1: fp32 sA*sB*sum.  When the kernel that runs cannot apply the
 // scale itself (split reduction, plain kernel) the sums go to the tail of the workspace and a dequantize pass follows.
 static size_t fwd_base_ws(const lpdt_conv_desc *d) { return narrow_ok(d) ? narrow_fwd_workspace(d) : 0; }
-static bool fwd_vec(const lpdt_conv_desc *d) { return d->C % 16 == 0 && same_stride_pad(d); }
+static bool fwd_vec(const lpdt_conv_desc *d, int P, int Q) { return igemm_fwd_supported(d, P, Q); }
 static bool fwd_fusable(const lpdt_conv_desc *d, int P, int Q) {
     if (narrow_conv_supported(d, P, Q)) return true;
-    if (!fwd_vec(d)) return false;
-    const int gtot = d->R * d->S * (d->C / 16);
-    return !igemm_is_split(d->N * P * Q, d->K, (gtot + 3) / 4);
+    return fwd_vec(d, P, Q) && !igemm_fwd_is_split(d, P, Q);
 }
 
 static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq, const int8_t *wq, void *out, int out_mode,
@@ -508,14 +291,8 @@ static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq
     const int mode = stage ? 0 : out_mode;
     if (narrow_conv_supported(d, P, Q)) {
         launch_narrow_fwd(d, P, Q, xq, wq, acc, mode, sA, sB, ws, st);
-    } else if (fwd_vec(d) && aligned(xq, 16) && aligned(wq, 16)) {
-        IgemmParams p = {};
-        p.in = xq; p.wt = wq; p.out = acc; p.out_mode = mode; p.sA = sA; p.sB = sB;
-        p.M = d->N * P * Q; p.Cin = d->C; p.Cout = d->K;
-        p.IH = d->H; p.IW = d->W; p.OH = P; p.OW = Q;
-        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
-        p.gpt = d->C / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
-        dispatch_igemm<false>(p, st);
+    } else if (fwd_vec(d, P, Q) && aligned(xq, 16) && aligned(wq, 16)) {
+        launch_igemm_fwd(d, P, Q, xq, wq, acc, mode, sA, sB, st);
     } else {
         hipLaunchKernelGGL(conv_fwd_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, xq, wq, acc, *d, P, Q);
     }
@@ -562,31 +339,19 @@ extern "C" int lpdt_qconv_fwd_f32(const lpdt_conv_desc *d, const int8_t *xq, con
 
 // Backward-data product; out_mode 2 adds to the gradient already in `out` (fan-out of a skip connection).
 static size_t bwd_data_base_ws(const lpdt_conv_desc *d) { return round_up((size_t)d->K * d->R * d->S * d->C, 256); }
-static bool bwd_data_vec(const lpdt_conv_desc *d) { return d->K % 16 == 0 && same_stride_pad(d); }
-static bool bwd_data_fusable(const lpdt_conv_desc *d) {
-    if (!bwd_data_vec(d)) return false;
-    const int gtot = d->R * d->S * (d->K / 16);
-    return !igemm_is_split(d->N * d->H * d->W, d->C, (gtot + 3) / 4);
+static bool bwd_data_vec(const lpdt_conv_desc *d, int P, int Q) { return igemm_bwd_data_supported(d, P, Q); }
+static bool bwd_data_fusable(const lpdt_conv_desc *d, int P, int Q) {
+    return bwd_data_vec(d, P, Q) && !igemm_bwd_data_is_split(d, P, Q);
 }
 
 static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *wq, void *out,
                               int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st) {
     const size_t out_len = (size_t)d->N * d->H * d->W * d->C;
-    const bool stage = out_mode != 0 && !(bwd_data_fusable(d) && aligned(gq, 16));
+    const bool stage = out_mode != 0 && !(bwd_data_fusable(d, P, Q) && aligned(gq, 16));
     int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_data_base_ws(d)) : static_cast<int32_t *>(out);
     const int mode = stage ? 0 : out_mode;
-    if (bwd_data_vec(d) && aligned(gq, 16)) {
-        int8_t *wt = static_cast<int8_t *>(ws);
-        const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
-        hipLaunchKernelGGL(transpose_filter_kernel, dim3(blocks_for(wlen, 2048)), dim3(kCThreads), 0, st, wq, d->K, d->R * d->S,
-                           d->C, wt);
-        IgemmParams p = {};
-        p.in = gq; p.wt = wt; p.out = acc; p.out_mode = mode; p.sA = sA; p.sB = sB;
-        p.M = d->N * d->H * d->W; p.Cin = d->K; p.Cout = d->C;
-        p.IH = P; p.IW = Q; p.OH = d->H; p.OW = d->W;
-        p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
-        p.gpt = d->K / 16; p.gtot = d->R * d->S * p.gpt; p.nk = (p.gtot + 3) / 4;
-        dispatch_igemm<true>(p, st);
+    if (bwd_data_vec(d, P, Q) && aligned(gq, 16)) {
+        launch_igemm_bwd_data(d, P, Q, gq, wq, acc, mode, sA, sB, ws, st);
     } else {
         hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, gq, wq, acc, *d, P, Q);
     }
@@ -598,7 +363,7 @@ extern "C" size_t lpdt_qconv_bwd_data_f32_workspace_bytes(const lpdt_conv_desc *
     int P, Q;
     if (check_conv(d, &P, &Q)) return 0;
     clear_error();
-    return bwd_data_base_ws(d) + (bwd_data_fusable(d) ? 0 : round_up((size_t)d->N * d->H * d->W * d->C * 4, 256));
+    return bwd_data_base_ws(d) + (bwd_data_fusable(d, P, Q) ? 0 : round_up((size_t)d->N * d->H * d->W * d->C * 4, 256));
 }
 
 extern "C" int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, int32_t *dx, void *ws,

@@ -1,0 +1,511 @@
+// int8 convolution forward and backward-data with exact int32 accumulation (Table
+// "hardware_training", row Conv) as an implicit GEMM on the gfx950 matrix cores
+// (v_mfma_i32_32x32x32_i8), im2col-free.
+//
+//   out[pix][j] = sum_{tap, c} in[pix + tap][c] * wt[j][tap][c]        j = output channel
+//
+// The reduction axis is cut into 16-byte granules (16 channels of one filter tap); a K-step is
+// 4 granules.  Both operands are fetched by 16-byte buffer loads in which 4 neighbouring lanes
+// read the 64 contiguous bytes of one row (the access shape the texture path serves at full
+// rate), staged through LDS in [granule][row][16 B] planes -- the operand order of the MFMA, so
+// every LDS read is a contiguous ds_read_b128 -- and double buffered.
+//
+// What keeps the inner loop short:
+//   * every row's image-border test is folded, once, into a bit mask over the filter taps; a
+//     masked-off or out-of-range row is read at an offset beyond the buffer's size, for which
+//     the hardware returns zeros: no branches, no selects on the data;
+//   * the tap-dependent part of the gather address comes from a small LDS table built once per
+//     block (one entry per granule of the block's K range);
+//   * the weights are the MFMA's row operand, so a lane ends up with 4 consecutive output
+//     channels of one pixel: 16-byte stores in the epilogue.
+//
+// Backward-data is the same kernel on the gradient tensor with the transposed filter.  With a
+// stride s > 1 an input pixel only meets the taps of its own residue class ((h + pad) mod s,
+// (w + pad) mod s); each class is a dense stride-1 problem over its sub-grid of pixels with its
+// own sub-filter, so the s*s classes run as grid.y of one launch and no product with a zero is
+// ever issued.
+#include "qconv_internal.h"
+#include <type_traits>
+
+namespace lpdt {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxClasses = 4;
+constexpr int kMaxTaps = 31;              // bits of the per-row tap mask; bit 31 is the always-clear "no granule" slot
+constexpr unsigned kBeyond = 0x80000000u; // a buffer offset no tensor reaches (sizes are checked to stay below it)
+constexpr int kMaxTableEntries = 4096;    // granules of one block's K range (32 KB of LDS)
+
+struct IgemmClass {
+    int M, OHs, OWs;        // rows of the class = N*OHs*OWs output pixels
+    int oy0, ox0;           // output pixel of sub-grid point (0,0); neighbours are `ostep` apart
+    int iy0, ix0;           // input pixel read by tap (0,0) at sub-grid point (0,0)
+    int Rc, Sc;             // tap grid of the class; tap (ty,tx) reads input pixel (+ty*dsign, +tx*dsign)
+    int gtot, nk, kps;      // granules, K-steps, K-steps per blockIdx.z
+    int wt_off;             // byte offset of the class's filter panel [Cout][Rc*Sc][Cin]
+    unsigned mul_hw, mul_w; // multipliers for x/(OHs*OWs) and x/OWs by umulhi; 0: divide
+};
+
+struct IgemmParams {
+    const int8_t *in;       // [N][IH][IW][Cin]
+    const int8_t *wt;       // filter panels, see IgemmClass::wt_off
+    void *out;              // [N][OH][OW][Cout]: int32 sums, or fp32 when out_mode != 0
+    unsigned in_bytes, wt_bytes;
+    int out_mode;           // 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32, added to what is there
+    const float *sA, *sB;
+    int Cin, Cout, gpt;     // gpt = granules per tap = Cin/16
+    int IH, IW, OH, OW;
+    int istep, ostep, dsign;
+    int tiles_n, atomic_out, vec_out;
+    int nclasses;
+    IgemmClass cls[kMaxClasses];
+};
+
+#ifdef LPDT_IGEMM_TIMING
+__device__ long long g_stamps[8 * 4096];
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && blockIdx.x < 4096) g_stamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#endif
+
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F f) {
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>());
+    }
+}
+
+__device__ __forceinline__ int fast_div(int x, int d, unsigned mul) {
+    return mul ? (int)__umulhi((unsigned)x, mul) : x / d;
+}
+
+// PF = K-steps whose global loads are in flight (held in registers) ahead of the one being multiplied.
+// SPLIT: the reduction is shared between the blocks of grid.z, which add their int32 sums into a zeroed output; the pixels
+// are then the MFMA's row operand, so that a lane's atomics of one instruction fall on consecutive addresses.
+template <int BM, int BN, int WM, int WN, int PF, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
+    constexpr int PLANE_A = BM * 16 + 64, PLANE_B = BN * 16 + 64;  // +64 B: the 4 planes start 16 banks apart
+    constexpr int BUF = 4 * (PLANE_A + PLANE_B);
+    constexpr int RA = BM / 64, RB = (BN + 63) / 64;               // 16-byte items per thread
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    int2 *tab = reinterpret_cast<int2 *>(lds + 2 * BUF);
+
+    STAMP(0);
+    const IgemmClass &c = p.cls[blockIdx.y];
+    // Blocks are dealt to the 8 XCDs round-robin; renumber so that each XCD (one L2) works on a contiguous run of tiles.
+    const int nb = gridDim.x, per = nb / 8, rem = nb % 8, xcd = blockIdx.x % 8;
+    const int tile = xcd * per + min(xcd, rem) + blockIdx.x / 8;
+    const int tile_n = tile % p.tiles_n, tile_m = tile / p.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    if (m0 >= c.M) return;
+    const int ks_begin = blockIdx.z * c.kps;
+    const int ks_end = min(c.nk, ks_begin + c.kps);
+    if (ks_begin >= ks_end && (blockIdx.z > 0)) return;
+
+    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
+    const int g4 = t % 4, row0 = t / 4;
+
+    // The K loop runs in rounds of PF steps with no conditions inside; steps past the block's range multiply zeros.
+    const int nsteps = (ks_end - ks_begin + PF - 1) / PF * PF;
+    // gather table: entry e = granule 4*ks_begin + e -> (byte offset of its tap and channels, tap slot); entries past
+    // the range (the padded steps and the PF steps of read-ahead) name the empty slot
+    for (int e = t; e < 4 * (nsteps + PF); e += kThreads) {
+        const int gi = 4 * ks_begin + e;
+        int2 v = {0, 31};
+        if (gi < min(c.gtot, 4 * ks_end)) {
+            const int slot = gi / p.gpt, cg = gi - slot * p.gpt;
+            const int ty = slot / c.Sc, tx = slot - ty * c.Sc;
+            v.x = (ty * p.IW + tx) * p.dsign * p.Cin + cg * 16;
+            v.y = slot;
+        }
+        tab[e] = v;
+    }
+
+    // this thread's rows of the pixel tile: byte offset of the pixel under tap (0,0), and which taps stay inside the image
+    int rowoff[RA];
+    unsigned mask[RA];
+    const int hw = c.OHs * c.OWs;
+#pragma unroll
+    for (int j = 0; j < RA; ++j) {
+        const int m = m0 + row0 + 64 * j;
+        rowoff[j] = 0;
+        mask[j] = 0;
+        if (m < c.M) {
+            const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
+            const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
+            const int iy = qy * p.istep + c.iy0, ix = qx * p.istep + c.ix0;
+            rowoff[j] = ((n * p.IH + iy) * p.IW + ix) * p.Cin;
+            unsigned xm = 0;
+            for (int tx = 0; tx < c.Sc; ++tx) xm |= (unsigned)((unsigned)(ix + tx * p.dsign) < (unsigned)p.IW) << tx;
+            for (int ty = 0; ty < c.Rc; ++ty)
+                if ((unsigned)(iy + ty * p.dsign) < (unsigned)p.IH) mask[j] |= xm << (ty * c.Sc);
+        }
+    }
+    // this thread's rows of the filter tile
+    unsigned boff[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        const int row = row0 + 64 * j;
+        boff[j] = (row < BN && n0 + row < p.Cout) ? (unsigned)(c.wt_off + ((n0 + row) * c.gtot + g4) * 16) : kBeyond;
+    }
+    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.in), 0, (int)p.in_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.wt), 0, (int)p.wt_bytes, 0x00020000);
+    __syncthreads();  // table complete
+    STAMP(1);
+
+    v4u sa[PF][RA], sb[PF][RB];
+    auto load_tiles = [&](auto slot_tag, int step) {  // step counts from the block's first K-step
+        constexpr int SL = decltype(slot_tag)::value;
+        const int2 e = tab[4 * step + g4];
+#pragma unroll
+        for (int j = 0; j < RA; ++j) {
+            const unsigned off = ((mask[j] >> e.y) & 1u) ? (unsigned)(rowoff[j] + e.x) : kBeyond;
+            sa[SL][j] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, off, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+            sb[SL][j] = __builtin_amdgcn_raw_buffer_load_b128(rs_wt, boff[j] + (unsigned)(ks_begin + step) * 64u, 0, 0);
+    };
+    unsigned char *const st_a = lds + g4 * PLANE_A + row0 * 16;
+    unsigned char *const st_b = lds + 4 * PLANE_A + g4 * PLANE_B + row0 * 16;
+    auto store_tiles = [&](auto slot_tag, int buf) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int j = 0; j < RA; ++j) *reinterpret_cast<v4u *>(st_a + buf * BUF + 64 * j * 16) = sa[SL][j];
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+            if (BN % 64 == 0 || row0 + 64 * j < BN) *reinterpret_cast<v4u *>(st_b + buf * BUF + 64 * j * 16) = sb[SL][j];
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int wm = wave / WN, wn = wave % WN, half = lane / 32;
+    const unsigned char *const rd_a = lds + half * PLANE_A + (wm * (BM / WM) + lane % 32) * 16;
+    const unsigned char *const rd_b = lds + 4 * PLANE_A + half * PLANE_B + (wn * (BN / WN) + lane % 32) * 16;
+
+    // prologue: the first PF K-steps' loads go out together; register slot s holds step s (mod PF afterwards)
+    static_for<PF>([&](auto s) { load_tiles(s, decltype(s)::value); });
+    store_tiles(std::integral_constant<int, 0>(), 0);
+    __syncthreads();
+    STAMP(2);
+    static_assert(PF % 2 == 0, "the LDS buffer of a step is a compile-time constant only for an even PF");
+    for (int base = 0; base < nsteps; base += PF) {
+        static_for<PF>([&](auto u) {
+            constexpr int U = decltype(u)::value;
+            constexpr int buf = U & 1;
+            load_tiles(u, base + U + PF);  // slot U went to LDS before this step: refill it
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                v4i a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    a[i] = *reinterpret_cast<const v4i *>(rd_a + buf * BUF + 2 * kk * PLANE_A + 32 * i * 16);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    b[j] = *reinterpret_cast<const v4i *>(rd_b + buf * BUF + 2 * kk * PLANE_B + 32 * j * 16);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {  // filter rows are the MFMA's row operand, except in a split reduction
+                        if (SPLIT) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+                        else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[j], a[i], acc[i][j], 0, 0, 0);
+                    }
+            }
+            store_tiles(std::integral_constant<int, (U + 1) % PF>(), buf ^ 1);
+            __syncthreads();
+        });
+    }
+
+    STAMP(3);
+    if constexpr (SPLIT) {  // lane: output channel lane%32 of the tile, pixels 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r16 = 0; r16 < 16; ++r16) {
+                const int m = m0 + wm * (BM / WM) + 32 * i + 8 * (r16 / 4) + 4 * half + (r16 % 4);
+                if (m >= c.M) continue;
+                const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
+                const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
+                const size_t pix = (size_t)(n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = n0 + wn * (BN / WN) + 32 * j + lane % 32;
+                    if (col < p.Cout && acc[i][j][r16] != 0) atomicAdd(static_cast<int32_t *>(p.out) + pix * p.Cout + col, acc[i][j][r16]);
+                }
+            }
+        STAMP(4);
+        return;
+    }
+    // Accumulator layout of the 32x32 MFMA: a lane holds column lane%32 (here: a pixel) and rows 8*(r/4) + 4*(lane/32) + r%4
+    // (here: output channels), i.e. four runs of 4 consecutive channels.
+    const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm * (BM / WM) + 32 * i + lane % 32;
+        if (m >= c.M) continue;
+        const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
+        const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
+        const size_t pix = (size_t)(n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = n0 + wn * (BN / WN) + 32 * j + 8 * q + 4 * half;
+                if (col >= p.Cout) continue;
+                const v4i s = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                int32_t *dst = static_cast<int32_t *>(p.out) + pix * p.Cout + col;
+                if (p.vec_out) {
+                    if (p.out_mode) {  // the dequantizing scale applied here: same arithmetic as lpdt_dequantize
+                        v4f *fdst = reinterpret_cast<v4f *>(dst);
+                        const bool add = p.out_mode == 2;
+                        v4f v = {0.f, 0.f, 0.f, 0.f};
+                        if (add) v = *fdst;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = dequant_value(scale, s[e], v[e], add);
+                        *fdst = v;
+                    } else *reinterpret_cast<v4i *>(dst) = s;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (col + e >= p.Cout) break;
+                        if (p.out_mode) {
+                            float *fdst = reinterpret_cast<float *>(dst + e);
+                            *fdst = dequant_value(scale, s[e], p.out_mode == 2 ? *fdst : 0.f, p.out_mode == 2);
+                        } else dst[e] = s[e];
+                    }
+                }
+            }
+        }
+    }
+    STAMP(4);
+}
+
+__global__ void fill_zero_kernel(int32_t *dst, size_t len) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < len; i += (size_t)gridDim.x * blockDim.x) dst[i] = 0;
+}
+
+// Filter panels for backward-data: class (cy,cx) holds wt[c][a][b][k] = w[k][cy + s*a][cx + s*b][c].
+struct PackParams {
+    int K, R, S, C, stride, nclasses;
+    int off[kMaxClasses + 1];  // element offsets of the panels
+    int Rc[kMaxClasses], Sc[kMaxClasses];
+};
+__global__ void pack_filter_bwd_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wt, const PackParams q) {
+    const int total = q.off[q.nclasses];
+    for (int o = blockIdx.x * blockDim.x + threadIdx.x; o < total; o += gridDim.x * blockDim.x) {
+        int cl = 0;
+        while (cl + 1 < q.nclasses && o >= q.off[cl + 1]) ++cl;
+        const int e = o - q.off[cl];
+        const int k = e % q.K;
+        const int slot = (e / q.K) % (q.Rc[cl] * q.Sc[cl]);
+        const int c = e / (q.K * q.Rc[cl] * q.Sc[cl]);
+        const int tr = cl / q.stride + q.stride * (slot / q.Sc[cl]), ts = cl % q.stride + q.stride * (slot % q.Sc[cl]);
+        wt[o] = w[((size_t)(k * q.R + tr) * q.S + ts) * q.C + c];
+    }
+}
+
+unsigned div_multiplier(int d, long long xmax) {
+    if (d <= 1 || xmax * d >= (1ll << 32)) return 0;
+    return (unsigned)((1ull << 32) / (unsigned)d + 1);
+}
+
+struct Tile { int BM, BN; };
+Tile pick_tile(int Cout) { return {128, Cout >= 48 ? 64 : 32}; }
+
+// Fills tile counts and the K split; returns the grid.
+dim3 finish_plan(IgemmParams *p, Tile tl, bool allow_split) {
+    p->tiles_n = (p->Cout + tl.BN - 1) / tl.BN;
+    long long blocks = 0;
+    int max_tiles_m = 0, max_nk = 0;
+    for (int i = 0; i < p->nclasses; ++i) {
+        const int tm = (p->cls[i].M + tl.BM - 1) / tl.BM;
+        blocks += (long long)tm * p->tiles_n;
+        if (tm > max_tiles_m) max_tiles_m = tm;
+        if (p->cls[i].nk > max_nk) max_nk = p->cls[i].nk;
+    }
+    int splits = 1;
+    if (allow_split && blocks < 256 && max_nk >= 8) {  // too few tiles to fill 256 CUs: split the reduction
+        splits = (int)((512 + blocks - 1) / blocks);
+        if (splits > max_nk / 4) splits = max_nk / 4;
+        if (splits < 1) splits = 1;
+    }
+    int zdim = 1;
+    for (int i = 0; i < p->nclasses; ++i) {
+        IgemmClass &c = p->cls[i];
+        c.kps = c.nk > 0 ? (c.nk + splits - 1) / splits : 1;
+        const int z = c.nk > 0 ? (c.nk + c.kps - 1) / c.kps : 1;
+        if (z > zdim) zdim = z;
+    }
+    p->atomic_out = zdim > 1;
+    return dim3((unsigned)(max_tiles_m * p->tiles_n), (unsigned)p->nclasses, (unsigned)zdim);
+}
+
+bool table_fits(const IgemmParams &p) {
+    for (int i = 0; i < p.nclasses; ++i)
+        if (4 * (p.cls[i].kps + 16) > kMaxTableEntries) return false;
+    return true;
+}
+
+template <int BM, int BN, int WM, int WN, int PF>
+void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
+    int max_kps = 1;
+    for (int i = 0; i < p.nclasses; ++i)
+        if (p.cls[i].kps > max_kps) max_kps = p.cls[i].kps;
+    const size_t lds = 2 * 4 * ((BM * 16 + 64) + (BN * 16 + 64)) + (size_t)((max_kps + PF - 1) / PF * PF + PF) * 4 * sizeof(int2);
+    if (p.atomic_out) hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, PF, true>), grid, dim3(kThreads), lds, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, PF, false>), grid, dim3(kThreads), lds, st, p);
+}
+
+void run(IgemmParams &p, size_t out_len, hipStream_t st) {
+    const Tile tl = pick_tile(p.Cout);
+    const dim3 grid = finish_plan(&p, tl, true);
+    if (p.atomic_out) {
+        const size_t len = out_len;
+        size_t b = (len + 1023) / 1024;
+        if (b > 4096) b = 4096;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)b), dim3(256), 0, st, static_cast<int32_t *>(p.out), len);
+    }
+    if (tl.BN == 64) launch<128, 64, 2, 2, 4>(p, grid, st);
+    else launch<128, 32, 4, 1, 4>(p, grid, st);
+}
+
+void fwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p) {
+    *p = IgemmParams{};
+    p->in_bytes = (unsigned)((size_t)d->N * d->H * d->W * d->C);
+    p->wt_bytes = (unsigned)((size_t)d->K * d->R * d->S * d->C);
+    p->Cin = d->C; p->Cout = d->K; p->gpt = d->C / 16;
+    p->IH = d->H; p->IW = d->W; p->OH = P; p->OW = Q;
+    p->istep = d->stride_h; p->ostep = 1; p->dsign = 1;
+    p->nclasses = 1;
+    IgemmClass &c = p->cls[0];
+    c.M = d->N * P * Q; c.OHs = P; c.OWs = Q;
+    c.oy0 = 0; c.ox0 = 0; c.iy0 = -d->pad_h; c.ix0 = -d->pad_w;
+    c.Rc = d->R; c.Sc = d->S;
+    c.gtot = d->R * d->S * p->gpt; c.nk = (c.gtot + 3) / 4;
+    c.wt_off = 0;
+    c.mul_hw = div_multiplier(P * Q, c.M);
+    c.mul_w = div_multiplier(Q, (long long)P * Q);
+}
+
+// Residue classes of backward-data.  Returns false when a class would be empty of pixels only (those are dropped).
+void bwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p, PackParams *pk) {
+    *p = IgemmParams{};
+    *pk = PackParams{};
+    const int s = d->stride_h, pad = d->pad_h;
+    p->in_bytes = (unsigned)((size_t)d->N * P * Q * d->K);
+    p->wt_bytes = (unsigned)((size_t)d->K * d->R * d->S * d->C);
+    p->Cin = d->K; p->Cout = d->C; p->gpt = d->K / 16;
+    p->IH = P; p->IW = Q; p->OH = d->H; p->OW = d->W;
+    p->istep = 1; p->ostep = s; p->dsign = -1;
+    pk->K = d->K; pk->R = d->R; pk->S = d->S; pk->C = d->C; pk->stride = s; pk->nclasses = s * s;
+    int n = 0, woff = 0;
+    for (int cy = 0; cy < s; ++cy)
+        for (int cx = 0; cx < s; ++cx) {
+            const int cl = cy * s + cx;
+            const int Rc = cy < d->R ? (d->R - 1 - cy) / s + 1 : 0, Sc = cx < d->S ? (d->S - 1 - cx) / s + 1 : 0;
+            pk->off[cl] = woff; pk->Rc[cl] = Rc; pk->Sc[cl] = Sc;
+            const int h0 = ((cy - pad) % s + s) % s, w0 = ((cx - pad) % s + s) % s;  // first pixel of the class
+            const int OHs = h0 < d->H ? (d->H - 1 - h0) / s + 1 : 0, OWs = w0 < d->W ? (d->W - 1 - w0) / s + 1 : 0;
+            if (OHs > 0 && OWs > 0) {
+                IgemmClass &c = p->cls[n++];
+                c.M = d->N * OHs * OWs; c.OHs = OHs; c.OWs = OWs;
+                c.oy0 = h0; c.ox0 = w0;
+                c.iy0 = (h0 + pad - cy) / s; c.ix0 = (w0 + pad - cx) / s;
+                c.Rc = Rc; c.Sc = Sc;
+                c.gtot = Rc * Sc * p->gpt; c.nk = (c.gtot + 3) / 4;
+                c.wt_off = woff;
+                c.mul_hw = div_multiplier(OHs * OWs, c.M);
+                c.mul_w = div_multiplier(OWs, (long long)OHs * OWs);
+            }
+            woff += Rc * Sc * d->K * d->C;
+        }
+    pk->off[s * s] = woff;
+    p->nclasses = n;
+}
+
+bool sizes_ok(const lpdt_conv_desc *d, int P, int Q) {
+    const size_t lim = (size_t)1 << 31;
+    return (size_t)d->N * d->H * d->W * d->C < lim - 4096 && (size_t)d->N * P * Q * d->K < lim - 4096 &&
+           (size_t)d->K * d->R * d->S * d->C < lim - 4096 && d->stride_h == d->stride_w && d->pad_h == d->pad_w;
+}
+
+}  // namespace
+
+bool igemm_fwd_supported(const lpdt_conv_desc *d, int P, int Q) {
+    if (!(d->C % 16 == 0 && sizes_ok(d, P, Q) && d->R <= 8 && d->S <= 8 && d->R * d->S <= kMaxTaps)) return false;
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    finish_plan(&p, pick_tile(p.Cout), true);
+    return table_fits(p);
+}
+
+bool igemm_bwd_data_supported(const lpdt_conv_desc *d, int P, int Q) {
+    if (!(d->K % 16 == 0 && sizes_ok(d, P, Q) && d->stride_h <= 2)) return false;
+    IgemmParams p;
+    PackParams pk;
+    bwd_params(d, P, Q, &p, &pk);
+    for (int i = 0; i < p.nclasses; ++i)  // the tap mask of a class has 31 bits
+        if (p.cls[i].Rc > 8 || p.cls[i].Sc > 8 || p.cls[i].Rc * p.cls[i].Sc > kMaxTaps) return false;
+    finish_plan(&p, pick_tile(p.Cout), true);
+    return table_fits(p);
+}
+
+bool igemm_fwd_is_split(const lpdt_conv_desc *d, int P, int Q) {
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    finish_plan(&p, pick_tile(p.Cout), true);
+    return p.atomic_out != 0;
+}
+
+bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q) {
+    IgemmParams p;
+    PackParams pk;
+    bwd_params(d, P, Q, &p, &pk);
+    finish_plan(&p, pick_tile(p.Cout), true);
+    return p.atomic_out != 0;
+}
+
+void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, void *out, int out_mode,
+                      const float *sA, const float *sB, hipStream_t st) {
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    p.in = x; p.wt = w; p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
+    p.vec_out = d->K % 4 == 0 && aligned(out, 16);
+    run(p, (size_t)d->N * P * Q * d->K, st);
+}
+
+void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *w, void *out, int out_mode,
+                           const float *sA, const float *sB, void *panel, hipStream_t st) {
+    IgemmParams p;
+    PackParams pk;
+    bwd_params(d, P, Q, &p, &pk);
+    const int total = pk.off[pk.nclasses];
+    int b = (total + 255) / 256;
+    if (b > 2048) b = 2048;
+    hipLaunchKernelGGL(pack_filter_bwd_kernel, dim3((unsigned)b), dim3(256), 0, st, w, static_cast<int8_t *>(panel), pk);
+    p.in = g; p.wt = static_cast<const int8_t *>(panel); p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
+    p.vec_out = d->C % 4 == 0 && aligned(out, 16);
+    run(p, (size_t)d->N * d->H * d->W * d->C, st);
+}
+
+}  // namespace lpdt
+
+#ifdef LPDT_IGEMM_TIMING
+extern "C" void lpdt_debug_stamps(long long *host, int n) {
+    (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(lpdt::g_stamps), sizeof(long long) * n);
+}
+#endif

@@ -13,6 +13,20 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
 void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
                          hipStream_t st);
 
+// Implicit-GEMM forward / backward-data on the matrix cores (channel counts of the reduction a multiple of 16).
+// `*_supported` is false for shapes that take the plain kernels; `*_is_split` tells that the reduction is split across
+// blocks and combined with int32 atomics, which rules out the fused fp32 epilogue (out_mode must be 0 then).
+bool igemm_fwd_supported(const lpdt_conv_desc *d, int P, int Q);
+bool igemm_bwd_data_supported(const lpdt_conv_desc *d, int P, int Q);
+bool igemm_fwd_is_split(const lpdt_conv_desc *d, int P, int Q);
+bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q);
+// out_mode 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32 added to `out`.  x, w, g 16-byte aligned.
+void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, void *out, int out_mode,
+                      const float *sA, const float *sB, hipStream_t st);
+// `panel`: K*R*S*C bytes of scratch for the transposed filter.
+void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *w, void *out, int out_mode,
+                           const float *sA, const float *sB, void *panel, hipStream_t st);
+
 // Weight gradient, rectangle-stepped kernel with partial tiles and a fixed-order reduction.
 struct WgradRectPlan {
     int ch, cw, ncy, ncx, PHp, PWp, steps, steps_per_split, splits, tg, groups, tiles_k, tiles_c;
