@@ -50,7 +50,13 @@ __global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict_
     __shared__ float sv[NMAX][kGThreads];
     const size_t e = (size_t)blockIdx.x * kGThreads + threadIdx.x;
     if (e >= d) return;
-    for (int i = 0; i < n; ++i) sv[i][threadIdx.x] = x[(size_t)i * d + e];
+    float v[NMAX];
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i)  // all rows' loads in flight together
+        if (i < n) v[i] = x[(size_t)i * d + e];
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i)
+        if (i < n) sv[i][threadIdx.x] = v[i];
     for (int i = 0; i < n; ++i) {
         const float vi = sv[i][threadIdx.x];
         float s = 0.0f;

@@ -50,6 +50,7 @@ struct IgemmClass {
     int gtot, nk, kps;      // granules, K-steps, K-steps per blockIdx.z
     int wt_off;             // byte offset of the class's filter panel [Cout][Rc*Sc][Cin]
     unsigned mul_hw, mul_w; // multipliers for x/(OHs*OWs) and x/OWs by umulhi; 0: divide
+    unsigned mul_sc;        // the same for x/Sc
 };
 
 struct IgemmParams {
@@ -60,19 +61,13 @@ struct IgemmParams {
     int out_mode;           // 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32, added to what is there
     const float *sA, *sB;
     int Cin, Cout, gpt;     // gpt = granules per tap = Cin/16
+    unsigned mul_gpt;       // multiplier for x/gpt
     int IH, IW, OH, OW;
     int istep, ostep, dsign;
     int tiles_n, atomic_out, vec_out;
     int nclasses;
     IgemmClass cls[kMaxClasses];
 };
-
-#ifdef LPDT_IGEMM_TIMING
-__device__ long long g_stamps[8 * 4096];
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && blockIdx.x < 4096) g_stamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do {} while (0)
-#endif
 
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F f) {
@@ -96,9 +91,9 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     constexpr int RA = BM / 64, RB = (BN + 63) / 64;               // 16-byte items per thread
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    int2 *tab = reinterpret_cast<int2 *>(lds + 2 * BUF);
+    int4 *rows = reinterpret_cast<int4 *>(lds + 2 * BUF);
+    int2 *tab = reinterpret_cast<int2 *>(lds + 2 * BUF + BM * sizeof(int4));
 
-    STAMP(0);
     const IgemmClass &c = p.cls[blockIdx.y];
     // Blocks are dealt to the 8 XCDs round-robin; renumber so that each XCD (one L2) works on a contiguous run of tiles.
     const int nb = gridDim.x, per = nb / 8, rem = nb % 8, xcd = blockIdx.x % 8;
@@ -121,33 +116,33 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
         const int gi = 4 * ks_begin + e;
         int2 v = {0, 31};
         if (gi < min(c.gtot, 4 * ks_end)) {
-            const int slot = gi / p.gpt, cg = gi - slot * p.gpt;
-            const int ty = slot / c.Sc, tx = slot - ty * c.Sc;
+            const int slot = fast_div(gi, p.gpt, p.mul_gpt), cg = gi - slot * p.gpt;
+            const int ty = fast_div(slot, c.Sc, c.mul_sc), tx = slot - ty * c.Sc;
             v.x = (ty * p.IW + tx) * p.dsign * p.Cin + cg * 16;
             v.y = slot;
         }
         tab[e] = v;
     }
 
-    // this thread's rows of the pixel tile: byte offset of the pixel under tap (0,0), and which taps stay inside the image
-    int rowoff[RA];
-    unsigned mask[RA];
+    // Row records, one per pixel of the tile, made by the first BM threads and shared through LDS: byte offset of the
+    // pixel under tap (0,0), which taps stay inside the image, and the output pixel (-1: past the end).
     const int hw = c.OHs * c.OWs;
-#pragma unroll
-    for (int j = 0; j < RA; ++j) {
-        const int m = m0 + row0 + 64 * j;
-        rowoff[j] = 0;
-        mask[j] = 0;
+    if (t < BM) {
+        const int m = m0 + t;
+        int4 rec = {0, 0, -1, 0};
         if (m < c.M) {
             const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
             const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
             const int iy = qy * p.istep + c.iy0, ix = qx * p.istep + c.ix0;
-            rowoff[j] = ((n * p.IH + iy) * p.IW + ix) * p.Cin;
-            unsigned xm = 0;
+            unsigned xm = 0, mk = 0;
             for (int tx = 0; tx < c.Sc; ++tx) xm |= (unsigned)((unsigned)(ix + tx * p.dsign) < (unsigned)p.IW) << tx;
             for (int ty = 0; ty < c.Rc; ++ty)
-                if ((unsigned)(iy + ty * p.dsign) < (unsigned)p.IH) mask[j] |= xm << (ty * c.Sc);
+                if ((unsigned)(iy + ty * p.dsign) < (unsigned)p.IH) mk |= xm << (ty * c.Sc);
+            rec.x = ((n * p.IH + iy) * p.IW + ix) * p.Cin;
+            rec.y = (int)mk;
+            rec.z = (n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
         }
+        rows[t] = rec;
     }
     // this thread's rows of the filter tile
     unsigned boff[RB];
@@ -158,8 +153,15 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     }
     const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.in), 0, (int)p.in_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.wt), 0, (int)p.wt_bytes, 0x00020000);
-    __syncthreads();  // table complete
-    STAMP(1);
+    __syncthreads();  // table and row records complete
+    int rowoff[RA];
+    unsigned mask[RA];
+#pragma unroll
+    for (int j = 0; j < RA; ++j) {
+        const int4 rec = rows[row0 + 64 * j];
+        rowoff[j] = rec.x;
+        mask[j] = (unsigned)rec.y;
+    }
 
     v4u sa[PF][RA], sb[PF][RB];
     auto load_tiles = [&](auto slot_tag, int step) {  // step counts from the block's first K-step
@@ -201,7 +203,6 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     static_for<PF>([&](auto s) { load_tiles(s, decltype(s)::value); });
     store_tiles(std::integral_constant<int, 0>(), 0);
     __syncthreads();
-    STAMP(2);
     static_assert(PF % 2 == 0, "the LDS buffer of a step is a compile-time constant only for an even PF");
     for (int base = 0; base < nsteps; base += PF) {
         static_for<PF>([&](auto u) {
@@ -230,24 +231,20 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
         });
     }
 
-    STAMP(3);
     if constexpr (SPLIT) {  // lane: output channel lane%32 of the tile, pixels 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r16 = 0; r16 < 16; ++r16) {
-                const int m = m0 + wm * (BM / WM) + 32 * i + 8 * (r16 / 4) + 4 * half + (r16 % 4);
-                if (m >= c.M) continue;
-                const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
-                const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
-                const size_t pix = (size_t)(n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
+                const int opix = rows[wm * (BM / WM) + 32 * i + 8 * (r16 / 4) + 4 * half + (r16 % 4)].z;
+                if (opix < 0) continue;
+                const size_t pix = (size_t)opix;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = n0 + wn * (BN / WN) + 32 * j + lane % 32;
                     if (col < p.Cout && acc[i][j][r16] != 0) atomicAdd(static_cast<int32_t *>(p.out) + pix * p.Cout + col, acc[i][j][r16]);
                 }
             }
-        STAMP(4);
         return;
     }
     // Accumulator layout of the 32x32 MFMA: a lane holds column lane%32 (here: a pixel) and rows 8*(r/4) + 4*(lane/32) + r%4
@@ -255,11 +252,9 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * (BM / WM) + 32 * i + lane % 32;
-        if (m >= c.M) continue;
-        const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
-        const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
-        const size_t pix = (size_t)(n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
+        const int opix = rows[wm * (BM / WM) + 32 * i + lane % 32].z;
+        if (opix < 0) continue;
+        const size_t pix = (size_t)opix;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -291,7 +286,6 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
             }
         }
     }
-    STAMP(4);
 }
 
 __global__ void fill_zero_kernel(int32_t *dst, size_t len) {
@@ -365,7 +359,8 @@ void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
     int max_kps = 1;
     for (int i = 0; i < p.nclasses; ++i)
         if (p.cls[i].kps > max_kps) max_kps = p.cls[i].kps;
-    const size_t lds = 2 * 4 * ((BM * 16 + 64) + (BN * 16 + 64)) + (size_t)((max_kps + PF - 1) / PF * PF + PF) * 4 * sizeof(int2);
+    const size_t lds = 2 * 4 * ((BM * 16 + 64) + (BN * 16 + 64)) + BM * sizeof(int4) +
+                       (size_t)((max_kps + PF - 1) / PF * PF + PF) * 4 * sizeof(int2);
     if (p.atomic_out) hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, PF, true>), grid, dim3(kThreads), lds, st, p);
     else hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, PF, false>), grid, dim3(kThreads), lds, st, p);
 }
@@ -399,6 +394,8 @@ void fwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p) {
     c.wt_off = 0;
     c.mul_hw = div_multiplier(P * Q, c.M);
     c.mul_w = div_multiplier(Q, (long long)P * Q);
+    c.mul_sc = div_multiplier(c.Sc, kMaxTaps + 1);
+    p->mul_gpt = div_multiplier(p->gpt, (long long)c.gtot + 64);
 }
 
 // Residue classes of backward-data.  Returns false when a class would be empty of pixels only (those are dropped).
@@ -430,11 +427,13 @@ void bwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p, PackParam
                 c.wt_off = woff;
                 c.mul_hw = div_multiplier(OHs * OWs, c.M);
                 c.mul_w = div_multiplier(OWs, (long long)OHs * OWs);
+                c.mul_sc = div_multiplier(Sc, kMaxTaps + 1);
             }
             woff += Rc * Sc * d->K * d->C;
         }
     pk->off[s * s] = woff;
     p->nclasses = n;
+    p->mul_gpt = div_multiplier(p->gpt, (long long)d->R * d->S * p->gpt + 64);
 }
 
 bool sizes_ok(const lpdt_conv_desc *d, int P, int Q) {
@@ -503,9 +502,3 @@ void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *
 }
 
 }  // namespace lpdt
-
-#ifdef LPDT_IGEMM_TIMING
-extern "C" void lpdt_debug_stamps(long long *host, int n) {
-    (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(lpdt::g_stamps), sizeof(long long) * n);
-}
-#endif
