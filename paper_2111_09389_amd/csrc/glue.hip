@@ -88,6 +88,64 @@ __global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const float *__restrict
     }
 }
 
+// 4 channels per thread (16-byte accesses), 32-bit index arithmetic: the form every benchmark shape takes
+__global__ __launch_bounds__(kT) void maxpool_fwd_vec_kernel(const float4 *__restrict__ x, int N, int H, int W, int C4, int k, int st,
+                                                             int pd, int P, int Q, float4 *__restrict__ y, int4 *__restrict__ idx) {
+    const unsigned total = (unsigned)N * P * Q * C4;
+    for (unsigned o = blockIdx.x * kT + threadIdx.x; o < total; o += gridDim.x * kT) {
+        const unsigned c = o % (unsigned)C4;
+        unsigned r = o / (unsigned)C4;
+        const int q = (int)(r % (unsigned)Q); r /= (unsigned)Q;
+        const int p = (int)(r % (unsigned)P);
+        const int n = (int)(r / (unsigned)P);
+        float best[4] = {0.f, 0.f, 0.f, 0.f};
+        int bi[4] = {-1, -1, -1, -1};
+        for (int i = 0; i < k; ++i) {
+            const int h = p * st + i - pd;
+            if (h < 0 || h >= H) continue;
+            for (int j = 0; j < k; ++j) {
+                const int w = q * st + j - pd;
+                if (w < 0 || w >= W) continue;
+                const float4 e4 = x[((unsigned)(n * H + h) * W + w) * (unsigned)C4 + c];
+                const float e[4] = {e4.x, e4.y, e4.z, e4.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (bi[u] < 0 || e[u] > best[u]) { best[u] = e[u]; bi[u] = h * W + w; }
+            }
+        }
+        y[o] = make_float4(best[0], best[1], best[2], best[3]);
+        idx[o] = make_int4(bi[0], bi[1], bi[2], bi[3]);
+    }
+}
+
+__global__ __launch_bounds__(kT) void maxpool_bwd_vec_kernel(const float4 *__restrict__ dy, const int4 *__restrict__ idx, int N,
+                                                             int H, int W, int C4, int k, int st, int pd, int P, int Q,
+                                                             float4 *__restrict__ dx) {
+    const unsigned total = (unsigned)N * H * W * C4;
+    for (unsigned o = blockIdx.x * kT + threadIdx.x; o < total; o += gridDim.x * kT) {
+        const unsigned c = o % (unsigned)C4;
+        unsigned r = o / (unsigned)C4;
+        const int w = (int)(r % (unsigned)W); r /= (unsigned)W;
+        const int h = (int)(r % (unsigned)H);
+        const int n = (int)(r / (unsigned)H);
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int p_lo = max(0, (h + pd - k + st) / st), p_hi = min(P - 1, (h + pd) / st);
+        const int q_lo = max(0, (w + pd - k + st) / st), q_hi = min(Q - 1, (w + pd) / st);
+        const int me = h * W + w;
+        for (int p = p_lo; p <= p_hi; ++p)
+            for (int q = q_lo; q <= q_hi; ++q) {
+                const unsigned at = ((unsigned)(n * P + p) * Q + q) * (unsigned)C4 + c;
+                const int4 id = idx[at];
+                const float4 g = dy[at];
+                if (id.x == me) s.x += g.x;
+                if (id.y == me) s.y += g.y;
+                if (id.z == me) s.z += g.z;
+                if (id.w == me) s.w += g.w;
+            }
+        dx[o] = s;
+    }
+}
+
 __global__ __launch_bounds__(kT) void avgpool_fwd_kernel(const float *__restrict__ x, int N, int HW, int C, float *__restrict__ y) {
     const int o = blockIdx.x * kT + threadIdx.x;
     if (o >= N * C) return;
@@ -151,6 +209,8 @@ extern "C" int lpdt_sgd(float *x, const float *g, size_t len, float lr, void *st
     return launch_status("lpdt_sgd");
 }
 
+static bool pool_vec_ok(int N, int H, int W, int C) { return C % 4 == 0 && (size_t)N * H * W * C < ((size_t)1 << 31); }
+
 static int check_pool(int N, int H, int W, int C, int k, int st, int pd) {
     LPDT_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, LPDT_EINVAL, "maxpool: sizes must be positive");
     LPDT_REQUIRE(k > 0 && st > 0 && pd >= 0 && pd < k, LPDT_EINVAL, "maxpool: need k > 0, stride > 0, 0 <= pad < k");
@@ -164,8 +224,13 @@ extern "C" int lpdt_maxpool_fwd(const float *x, int N, int H, int W, int C, int 
     if (rc) return rc;
     LPDT_REQUIRE(x && y && idx, LPDT_EINVAL, "maxpool_fwd: NULL argument");
     const int P = conv_out(H, pd, k, st), Q = conv_out(W, pd, k, st);
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid1d((size_t)N * P * Q * C)), dim3(kT), 0, as_stream(stream), x, N, H, W, C, k,
-                       st, pd, P, Q, y, idx);
+    if (pool_vec_ok(N, H, W, C) && aligned(x, 16) && aligned(y, 16) && aligned(idx, 16))
+        hipLaunchKernelGGL(maxpool_fwd_vec_kernel, dim3(grid1d((size_t)N * P * Q * (C / 4))), dim3(kT), 0, as_stream(stream),
+                           reinterpret_cast<const float4 *>(x), N, H, W, C / 4, k, st, pd, P, Q, reinterpret_cast<float4 *>(y),
+                           reinterpret_cast<int4 *>(idx));
+    else
+        hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid1d((size_t)N * P * Q * C)), dim3(kT), 0, as_stream(stream), x, N, H, W, C, k,
+                           st, pd, P, Q, y, idx);
     return launch_status("lpdt_maxpool_fwd");
 }
 
@@ -175,8 +240,13 @@ extern "C" int lpdt_maxpool_bwd(const float *dy, const int32_t *idx, int N, int 
     if (rc) return rc;
     LPDT_REQUIRE(dy && idx && dx, LPDT_EINVAL, "maxpool_bwd: NULL argument");
     const int P = conv_out(H, pd, k, st), Q = conv_out(W, pd, k, st);
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid1d((size_t)N * H * W * C)), dim3(kT), 0, as_stream(stream), dy, idx, N, H, W,
-                       C, k, st, pd, P, Q, dx);
+    if (pool_vec_ok(N, H, W, C) && aligned(dy, 16) && aligned(idx, 16) && aligned(dx, 16))
+        hipLaunchKernelGGL(maxpool_bwd_vec_kernel, dim3(grid1d((size_t)N * H * W * (C / 4))), dim3(kT), 0, as_stream(stream),
+                           reinterpret_cast<const float4 *>(dy), reinterpret_cast<const int4 *>(idx), N, H, W, C / 4, k, st, pd, P, Q,
+                           reinterpret_cast<float4 *>(dx));
+    else
+        hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid1d((size_t)N * H * W * C)), dim3(kT), 0, as_stream(stream), dy, idx, N, H, W,
+                           C, k, st, pd, P, Q, dx);
     return launch_status("lpdt_maxpool_bwd");
 }
 
