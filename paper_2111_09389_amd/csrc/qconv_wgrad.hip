@@ -6,15 +6,17 @@
 // and the gradient tile into LDS once per step, in their natural [pixel][channel] order, and every tap's MFMA operand
 // is read from it with the transposing LDS load (ds_read_b64_tr_b8): a tap is a constant LDS offset.  Compared with
 // staging one shifted copy per tap this moves ~2.4x fewer bytes through the global-load path for a 3x3 filter.
-// A block accumulates all taps (up to 9) of a 64 x 64 (output x input channel) tile over its share of the steps and
+// A block accumulates all taps (up to 9) of a 32 x 64 or 64 x 64 (output x input channel) tile over its share of the steps and
 // writes its sums as ONE plain partial tile; a second kernel adds the partial tiles (exact integers: order-free) and applies the
 // dequantizing scale when asked.  No atomics, no zero fill, bit-reproducible.
 #include "qconv_internal.h"
+#include <type_traits>
 
 namespace lpdt {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kRow = 96;        // LDS bytes per pixel: 64 channels + 32 pad (8 rows tile the 64 banks)
@@ -24,6 +26,7 @@ struct WgradRectParams {
     const int8_t *g;            // [N][P][Q][K]
     const int8_t *x;            // [N][H][W][C]
     int32_t *partial;           // [splits][K][R*S][C]
+    unsigned g_bytes, x_bytes;
     int N, K, C, H, W, P, Q, R, S, stride, pad;
     int ch, cw, ncy, ncx;       // rectangle and rectangles per image
     int PHp, PWp;               // halo patch size in pixels
@@ -32,74 +35,107 @@ struct WgradRectParams {
     long long out_len;
 };
 
-template <int TG>
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F f) {
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>());
+    }
+}
+
+constexpr unsigned kBeyond = 0x80000000u;  // a buffer offset no tensor reaches: such loads return zeros
+
+// KT x CT = the block's (output x input channel) tile, 32 or 64 each.  The 4 waves cover its 32 x 32 sub-tiles and, when
+// there are fewer than 4 of those, share out the taps: wave (ti, tj, tw) accumulates taps tw, tw + WT, ...
+// PF = steps whose loads are in flight (in registers) ahead of the step being multiplied; the loop runs in rounds of PF
+// steps without conditions, steps past the block's share load zeros.
+template <int KT, int CT, int TG, int PF>
 __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParams p) {
+    constexpr int WK = KT / 32, WC = CT / 32, WT = 4 / (WK * WC);
+    constexpr int NA = (TG + WT - 1) / WT;       // accumulators (taps) per wave
+    constexpr int GK = KT / 16, GC = CT / 16;    // 16-byte granules per pixel of the two tiles
+    static_assert(32 * GK % 64 == 0, "an item index is gradient or patch for a whole wave");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int patch_px = p.PHp * p.PWp;
     const int buf_bytes = (32 + patch_px) * kRow;
 
     const int t = threadIdx.x, lane = t % 64, wave = t / 64;
-    const int k0 = (blockIdx.x % p.tiles_k) * 64, c0 = (blockIdx.x / p.tiles_k) * 64;
+    const int k0 = (blockIdx.x % p.tiles_k) * KT, c0 = (blockIdx.x / p.tiles_k) * CT;
     const int tap0 = blockIdx.y * TG, ntaps = p.R * p.S;
     const int step_begin = blockIdx.z * p.steps_per_split;
     const int step_end = min(p.steps, step_begin + p.steps_per_split);
-    const int spi = p.ncy * p.ncx;
+    const int nsteps = (step_end - step_begin + PF - 1) / PF * PF;
 
-    // this thread's load items: id < 128: gradient (slot id/4, granule id%4); else patch pixel (id-128)/4
-    int kind[kItems], ia[kItems], ib[kItems], gran[kItems], dst[kItems];
+    // This thread's load items.  id < 32*GK: gradient (rectangle slot id/GK, granule id%GK); else patch pixel
+    // (id - 32*GK)/GC.  Per item: position (ia, ib) inside the rectangle / patch, the image limits its position is
+    // tested against, and the byte offset relative to the step's corner.  Whether an item is gradient or patch is the
+    // same for all lanes of a wave, so the choice of tensor is scalar.
+    const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.g), 0, (int)p.g_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x), 0, (int)p.x_bytes, 0x00020000);
+    bool is_g[kItems];
+    int ia[kItems], ib[kItems], soff[kItems], dst[kItems];
+    unsigned lim_y[kItems], lim_x[kItems];
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
         const int id = t + 256 * j;
-        gran[j] = (id % 4) * 16;
-        if (id < 128) {
-            const int slot = id / 4;
-            kind[j] = 0; ia[j] = slot / p.cw; ib[j] = slot % p.cw;          // row, column inside the rectangle
-            dst[j] = slot * kRow + gran[j];
-        } else if ((id - 128) / 4 < patch_px) {
-            const int pp = (id - 128) / 4;
-            kind[j] = 1; ia[j] = pp / p.PWp; ib[j] = pp % p.PWp;           // row, column inside the patch
-            dst[j] = (32 + pp) * kRow + gran[j];
+        is_g[j] = (wave * 64 + 256 * j) < 32 * GK;
+        if (is_g[j]) {
+            const int slot = id / GK, gran = (id % GK) * 16;
+            ia[j] = slot / p.cw; ib[j] = slot % p.cw;
+            const bool ok = ia[j] < p.ch && k0 + gran < p.K;
+            lim_y[j] = ok ? (unsigned)p.P : 0u; lim_x[j] = (unsigned)p.Q;
+            soff[j] = (ia[j] * p.Q + ib[j]) * p.K + k0 + gran;
+            dst[j] = slot * kRow + gran;
         } else {
-            kind[j] = 2; ia[j] = ib[j] = dst[j] = 0;
+            const int pp = (id - 32 * GK) / GC, gran = ((id - 32 * GK) % GC) * 16;
+            ia[j] = pp / p.PWp; ib[j] = pp % p.PWp;
+            const bool ok = pp < patch_px && c0 + gran < p.C;
+            lim_y[j] = ok ? (unsigned)p.H : 0u; lim_x[j] = (unsigned)p.W;
+            soff[j] = (ia[j] * p.W + ib[j]) * p.C + c0 + gran;
+            dst[j] = ok ? (32 + pp) * kRow + gran : -1;
         }
     }
 
-    v4i stage[kItems];
-    auto load_items = [&](int step) {
-        const int n = step / spi, rem = step - n * spi;
-        const int cy = rem / p.ncx, cx = rem - cy * p.ncx;
-        const int oy0 = cy * p.ch, ox0 = cx * p.cw;
+    // position of the next step to load: image n, rectangle (cy, cx)
+    const int spi = p.ncy * p.ncx;
+    int ld_n = step_begin / spi, ld_cy = (step_begin - ld_n * spi) / p.ncx, ld_cx = step_begin - ld_n * spi - ld_cy * p.ncx;
+    int ld_left = step_end - step_begin;  // real steps not yet loaded
+
+    v4u stage[PF][kItems];
+    auto load_items = [&](auto slot_tag) {
+        constexpr int SL = decltype(slot_tag)::value;
+        const bool live = ld_left > 0;
+        const int oy0 = ld_cy * p.ch, ox0 = ld_cx * p.cw;
+        const int iy0 = oy0 * p.stride - p.pad, ix0 = ox0 * p.stride - p.pad;
+        const int base_g = ((ld_n * p.P + oy0) * p.Q + ox0) * p.K;
+        const int base_x = ((ld_n * p.H + iy0) * p.W + ix0) * p.C;
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
-            v4i v = {0, 0, 0, 0};
-            if (kind[j] == 0) {
-                const int oy = oy0 + ia[j], ox = ox0 + ib[j];
-                if (ia[j] < p.ch && oy < p.P && ox < p.Q && k0 + gran[j] < p.K)
-                    v = *reinterpret_cast<const v4i *>(p.g + ((size_t)(n * p.P + oy) * p.Q + ox) * p.K + k0 + gran[j]);
-            } else if (kind[j] == 1) {
-                const int iy = oy0 * p.stride - p.pad + ia[j], ix = ox0 * p.stride - p.pad + ib[j];
-                if (iy >= 0 && iy < p.H && ix >= 0 && ix < p.W && c0 + gran[j] < p.C)
-                    v = *reinterpret_cast<const v4i *>(p.x + ((size_t)(n * p.H + iy) * p.W + ix) * p.C + c0 + gran[j]);
-            }
-            stage[j] = v;
+            const int y = (is_g[j] ? oy0 : iy0) + ia[j], x = (is_g[j] ? ox0 : ix0) + ib[j];
+            const bool ok = live && (unsigned)y < lim_y[j] && (unsigned)x < lim_x[j];
+            const unsigned off = ok ? (unsigned)((is_g[j] ? base_g : base_x) + soff[j]) : kBeyond;
+            stage[SL][j] = __builtin_amdgcn_raw_buffer_load_b128(is_g[j] ? rs_g : rs_x, off, 0, 0);
         }
+        --ld_left;
+        if (++ld_cx == p.ncx) { ld_cx = 0; if (++ld_cy == p.ncy) { ld_cy = 0; ++ld_n; } }
     };
-    auto store_items = [&](int buf) {
+    auto store_items = [&](auto slot_tag, int buf) {
+        constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
         for (int j = 0; j < kItems; ++j)
-            if (kind[j] != 2) *reinterpret_cast<v4i *>(lds + buf * buf_bytes + dst[j]) = stage[j];
+            if (dst[j] >= 0) *reinterpret_cast<v4u *>(lds + buf * buf_bytes + dst[j]) = stage[SL][j];
     };
 
-    v16i acc[TG];
+    v16i acc[NA];
 #pragma unroll
-    for (int i = 0; i < TG; ++i)
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0;
 
     // Transposing LDS read: in each block of 16 lanes, source lane j supplies 8 bytes and result lane i receives byte
     // (i%8) of source lanes i/8, i/8+2, ...  With source lane j reading pixel slot j/2 at channel offset 8*(j%2),
     // result lane i holds channel i of 8 pixel slots: the MFMA operand.  Slot -> patch pixel is this lane's business.
-    const int ti = wave / 2, tj = wave % 2;
+    const int ti = wave % WK, tj = (wave / WK) % WC, tw = wave / (WK * WC);
     const int blk = lane / 16, j16 = lane % 16;
     const int src_ch = 16 * (blk % 2) + 8 * (j16 % 2);
     int a_off[2], b_off[2];
@@ -111,46 +147,47 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
         const int pix = pr < p.ch ? (pr * p.stride) * p.PWp + pc * p.stride : 0;  // empty slots meet zero gradient rows
         b_off[h] = (32 + pix) * kRow + 32 * tj + src_ch;
     }
-    int tapoff[TG];
+    int tapoff[NA];
 #pragma unroll
-    for (int i = 0; i < TG; ++i) {
-        const int tap = min(tap0 + i, ntaps - 1);
+    for (int i = 0; i < NA; ++i) {
+        const int tap = min(tap0 + tw + WT * i, ntaps - 1);
         tapoff[i] = ((tap / p.S) * p.PWp + tap % p.S) * kRow;
     }
     typedef __attribute__((address_space(3))) v2i lds_v2i;
 
-    if (step_begin < step_end) {
-        load_items(step_begin);
-        store_items(0);
-    }
+    static_assert(PF % 2 == 0, "the LDS buffer of a step is a compile-time constant only for an even PF");
+    static_for<PF>([&](auto s) { load_items(s); });
+    store_items(std::integral_constant<int, 0>(), 0);
     __syncthreads();
-    for (int st = step_begin; st < step_end; ++st) {
-        const int buf = (st - step_begin) & 1;
-        const bool more = st + 1 < step_end;
-        if (more) load_items(st + 1);
-        unsigned char *base = lds + buf * buf_bytes;
-        const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0]));
-        const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1]));
-        const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+    for (int round = 0; round < nsteps; round += PF) {
+        static_for<PF>([&](auto u) {
+            constexpr int U = decltype(u)::value;
+            constexpr int buf = U & 1;
+            load_items(u);  // register slot U went to LDS before this step: refill it with the step PF ahead
+            unsigned char *base = lds + buf * buf_bytes;
+            const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0]));
+            const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1]));
+            const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
 #pragma unroll
-        for (int i = 0; i < TG; ++i) {
-            if (tap0 + i < ntaps) {
-                const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + tapoff[i]));
-                const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + tapoff[i]));
-                const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
-                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < NA; ++i) {
+                if (tw + WT * i < TG && tap0 + tw + WT * i < ntaps) {
+                    const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + tapoff[i]));
+                    const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + tapoff[i]));
+                    const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+                }
             }
-        }
-        if (more) store_items(buf ^ 1);
-        __syncthreads();
+            store_items(std::integral_constant<int, (U + 1) % PF>(), buf ^ 1);
+            __syncthreads();
+        });
     }
 
     int32_t *out = p.partial + (size_t)blockIdx.z * p.out_len;
     const int c = c0 + 32 * tj + lane % 32;
 #pragma unroll
-    for (int i = 0; i < TG; ++i) {
-        const int tap = tap0 + i;
-        if (tap < ntaps && c < p.C) {
+    for (int i = 0; i < NA; ++i) {
+        const int tap = tap0 + tw + WT * i;
+        if (tw + WT * i < TG && tap < ntaps && c < p.C) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = k0 + 32 * ti + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
@@ -192,6 +229,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const int32_t *__rest
 
 bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     if (d->K % 16 || d->C % 16 || d->stride_h != d->stride_w || d->pad_h != d->pad_w) return false;
+    const size_t lim = ((size_t)1 << 31) - 4096;  // 32-bit buffer offsets
+    if ((size_t)d->N * P * Q * d->K >= lim || (size_t)d->N * d->H * d->W * d->C >= lim) return false;
     if (P * Q < 16) return false;  // tiny maps: rectangles cannot be filled from one image
     const int st = d->stride_h;
     pl->cw = Q >= 32 ? 32 : Q;
@@ -209,8 +248,13 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     const int ntaps = d->R * d->S;
     pl->tg = ntaps == 1 ? 1 : 9;
     pl->groups = (ntaps + pl->tg - 1) / pl->tg;
-    pl->tiles_k = (d->K + 63) / 64;
-    pl->tiles_c = (d->C + 63) / 64;
+    // Every block writes its tile once per split and the second kernel reads all of that back, so a smaller tile means
+    // less traffic; it also means more steps per block.  Measured on the benchmark layers: 32 x 64 for multi-tap filters
+    // (the waves share out the 9 taps), 64 x 64 for 1x1 filters.
+    pl->kt = ntaps == 1 ? 64 : 32;
+    pl->ct = 64;
+    pl->tiles_k = (d->K + pl->kt - 1) / pl->kt;
+    pl->tiles_c = (d->C + pl->ct - 1) / pl->ct;
     const long long base = (long long)pl->tiles_k * pl->tiles_c * pl->groups;
     long long splits = (512 + base - 1) / base;
     if (splits > steps / 4) splits = steps / 4;
@@ -227,13 +271,20 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
                        void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st) {
     WgradRectParams p = {};
     p.g = g; p.x = x; p.partial = static_cast<int32_t *>(partial);
+    p.g_bytes = (unsigned)((size_t)d->N * P * Q * d->K); p.x_bytes = (unsigned)((size_t)d->N * d->H * d->W * d->C);
     p.N = d->N; p.K = d->K; p.C = d->C; p.H = d->H; p.W = d->W; p.P = P; p.Q = Q;
     p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
     p.ch = pl.ch; p.cw = pl.cw; p.ncy = pl.ncy; p.ncx = pl.ncx; p.PHp = pl.PHp; p.PWp = pl.PWp;
     p.steps = pl.steps; p.steps_per_split = pl.steps_per_split; p.tiles_k = pl.tiles_k; p.out_len = pl.out_len;
     const dim3 grid((unsigned)(pl.tiles_k * pl.tiles_c), (unsigned)pl.groups, (unsigned)pl.splits);
-    if (pl.tg == 1) hipLaunchKernelGGL(wgrad_rect_kernel<1>, grid, dim3(256), pl.lds, st, p);
-    else hipLaunchKernelGGL(wgrad_rect_kernel<9>, grid, dim3(256), pl.lds, st, p);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(256), pl.lds, st, p); };
+    if (pl.kt == 64 && pl.ct == 64) {
+        if (pl.tg == 1) go(wgrad_rect_kernel<64, 64, 1, 4>);
+        else go(wgrad_rect_kernel<64, 64, 9, 2>);  // 9 accumulators: no registers for a deeper read-ahead
+    } else {
+        if (pl.tg == 1) go(wgrad_rect_kernel<32, 64, 1, 4>);
+        else go(wgrad_rect_kernel<32, 64, 9, 2>);
+    }
     const long long rb = (pl.out_len + 31) / 32;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.splits,
                        static_cast<int32_t *>(out), out_mode, sA, sB);
