@@ -34,6 +34,17 @@ struct MixGraph {  // sparse rows of W, passed by value
     uint8_t deg[kMaxAgents];
 };
 
+// The same rows for graphs of at most 16 agents and 4 non-zeros per row (rings, tori), padded with zero weights on the
+// agent itself: every row has exactly 4 terms, so the kernels' loops over agents and terms unroll completely and the
+// compiler fetches the whole graph with a few scalar loads up front instead of a chain of dependent ones per term.
+struct MixGraph4 {
+    static constexpr int kFixedDeg = 4;
+    float w[16][4];
+    uint8_t nbr[16][4];
+};
+template <typename G> struct FixedDeg { static constexpr int value = 0; };
+template <> struct FixedDeg<MixGraph4> { static constexpr int value = 4; };
+
 struct UploadChunk { long long v[kUploadChunk]; };
 
 struct PairState {        // one per (agent, segment)
@@ -43,8 +54,8 @@ struct PairState {        // one per (agent, segment)
 };
 
 // ---- plain mix ---------------------------------------------------------------
-template <int NMAX>
-__global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict__ x, int n, size_t d, MixGraph g, float rate) {
+template <int NMAX, typename G>
+__global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict__ x, int n, size_t d, G g, float rate) {
     // column values staged in LDS: neighbour ids are run-time values, and LDS takes a
     // run-time row index where registers cannot.  Each thread touches its own column only.
     __shared__ float sv[NMAX][kGThreads];
@@ -57,11 +68,22 @@ __global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict_
 #pragma unroll
     for (int i = 0; i < NMAX; ++i)
         if (i < n) sv[i][threadIdx.x] = v[i];
-    for (int i = 0; i < n; ++i) {
-        const float vi = sv[i][threadIdx.x];
-        float s = 0.0f;
-        for (int t = 0; t < g.deg[i]; ++t) s += g.w[i][t] * sv[g.nbr[i][t]][threadIdx.x];
-        x[(size_t)i * d + e] = vi + rate * (s - vi);
+    if constexpr (FixedDeg<G>::value > 0) {
+#pragma unroll
+        for (int i = 0; i < NMAX; ++i)
+            if (i < n) {
+                float s = 0.0f;
+#pragma unroll
+                for (int t = 0; t < FixedDeg<G>::value; ++t) s += g.w[i][t] * sv[g.nbr[i][t]][threadIdx.x];
+                x[(size_t)i * d + e] = v[i] + rate * (s - v[i]);
+            }
+    } else {
+        for (int i = 0; i < n; ++i) {
+            const float vi = sv[i][threadIdx.x];
+            float s = 0.0f;
+            for (int t = 0; t < g.deg[i]; ++t) s += g.w[i][t] * sv[g.nbr[i][t]][threadIdx.x];
+            x[(size_t)i * d + e] = vi + rate * (s - vi);
+        }
     }
 }
 
@@ -271,11 +293,11 @@ __global__ __launch_bounds__(kGThreads) void choco_cand_hist_kernel(const unsign
 
 // Final pass: xhat += top-k(x - xhat) for every agent, then the gossip update of x.
 // A thread owns VEC adjacent parameter columns (VEC * 4-byte loads per agent row).
-template <int NMAX, int VEC>
+template <int NMAX, int VEC, typename G>
 __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__restrict__ x, float *__restrict__ xhat, int n,
                                                                     size_t d, const long long *__restrict__ off, int nseg,
                                                                     const PairState *__restrict__ st, int select_all,
-                                                                    MixGraph g, float rate) {
+                                                                    G g, float rate) {
     __shared__ int s_first;
     __shared__ unsigned long long sprefix[NMAX];        // thresholds of the block's first segment
     __shared__ float sh[NMAX][VEC][kGThreads];          // this thread's columns of xhat (after the update)
@@ -332,7 +354,12 @@ __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__res
             for (int u = 0; u < VEC; ++u) {
                 const float hi = sh[i][u][threadIdx.x];
                 float sum = 0.0f;
-                for (int t = 0; t < g.deg[i]; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - hi);
+                if constexpr (FixedDeg<G>::value > 0) {
+#pragma unroll
+                    for (int t = 0; t < FixedDeg<G>::value; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - hi);
+                } else {
+                    for (int t = 0; t < g.deg[i]; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - hi);
+                }
                 o[u] = xv[i][u] + rate * sum;
             }
             if (VEC == 2) *reinterpret_cast<float2 *>(x + (size_t)i * d + e) = make_float2(o[0], o[VEC - 1]);
@@ -382,6 +409,18 @@ static int build_graph(const float *W, int n, MixGraph *g) {
     return LPDT_OK;
 }
 
+// Fills the padded 4-term form; false when the graph does not fit it.
+static bool compact_graph(const MixGraph &g, int n, MixGraph4 *c) {
+    if (n > 16) return false;
+    for (int i = 0; i < 16; ++i)
+        for (int t = 0; t < 4; ++t) { c->w[i][t] = 0.0f; c->nbr[i][t] = (uint8_t)(i < n ? i : 0); }
+    for (int i = 0; i < n; ++i) {
+        if (g.deg[i] > 4) return false;
+        for (int t = 0; t < g.deg[i]; ++t) { c->w[i][t] = g.w[i][t]; c->nbr[i][t] = g.nbr[i][t]; }
+    }
+    return true;
+}
+
 template <typename F>
 static void dispatch_nmax(int n, F f) {
     if (n <= 8) f(std::integral_constant<int, 8>());
@@ -423,10 +462,16 @@ extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const flo
     hipStream_t st = as_stream(stream);
     const unsigned int col_blocks = (unsigned int)((d + kGThreads - 1) / kGThreads);
 
+    MixGraph4 g4;
+    const bool fixed4 = compact_graph(g, n, &g4);
     if (!xhat) {
         dispatch_nmax(n, [&](auto tag) {
             constexpr int NMAX = decltype(tag)::value;
-            hipLaunchKernelGGL(mix_plain_kernel<NMAX>, dim3(col_blocks), dim3(kGThreads), 0, st, x, n, d, g, rate);
+            if (NMAX <= 16 && fixed4)
+                hipLaunchKernelGGL((mix_plain_kernel<(NMAX <= 16 ? NMAX : 16), MixGraph4>), dim3(col_blocks), dim3(kGThreads), 0, st, x, n,
+                                   d, g4, rate);
+            else
+                hipLaunchKernelGGL((mix_plain_kernel<NMAX, MixGraph>), dim3(col_blocks), dim3(kGThreads), 0, st, x, n, d, g, rate);
         });
         return launch_status("lpdt_gossip_mix");
     }
@@ -487,12 +532,17 @@ extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const flo
     const bool vec2 = n <= 16 && d % 2 == 0 && aligned(x, 8) && aligned(xhat, 8);
     dispatch_nmax(n, [&](auto tag) {
         constexpr int NMAX = decltype(tag)::value;
-        if (NMAX <= 16 && vec2)
-            hipLaunchKernelGGL((choco_apply_mix_kernel<(NMAX <= 16 ? NMAX : 16), 2>), dim3((unsigned)((d / 2 + kGThreads - 1) / kGThreads)),
-                               dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st, select_all ? 1 : 0, g, rate);
+        constexpr int N16 = NMAX <= 16 ? NMAX : 16;
+        const dim3 grid2((unsigned)((d / 2 + kGThreads - 1) / kGThreads));
+        if (NMAX <= 16 && vec2 && fixed4)
+            hipLaunchKernelGGL((choco_apply_mix_kernel<N16, 2, MixGraph4>), grid2, dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st,
+                               select_all ? 1 : 0, g4, rate);
+        else if (NMAX <= 16 && vec2)
+            hipLaunchKernelGGL((choco_apply_mix_kernel<N16, 2, MixGraph>), grid2, dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st,
+                               select_all ? 1 : 0, g, rate);
         else
-            hipLaunchKernelGGL((choco_apply_mix_kernel<NMAX, 1>), dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg,
-                               d_st, select_all ? 1 : 0, g, rate);
+            hipLaunchKernelGGL((choco_apply_mix_kernel<NMAX, 1, MixGraph>), dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off,
+                               nseg, d_st, select_all ? 1 : 0, g, rate);
     });
     return launch_status("lpdt_gossip_mix");
 }
