@@ -24,8 +24,7 @@ constexpr int kMaxAgents = 64;
 constexpr int kMaxDeg = 8;
 constexpr int kGThreads = 256;
 constexpr int kTile = 4096;        // elements per block in the full-data passes
-constexpr int kCandTile = 65536;   // candidate slots per block in the candidate passes
-constexpr int kBins = 8192;        // histogram bins per (agent, segment)
+constexpr int kBins = 4096;        // histogram bins per (agent, segment): the 12-bit first pass
 constexpr int kUploadChunk = 384;  // int64 values per upload launch (kernel-argument space)
 
 struct MixGraph {  // sparse rows of W, passed by value
@@ -268,27 +267,95 @@ __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *_
     for (unsigned int i = threadIdx.x; i < count; i += kGThreads) dst[i] = stage[i];
 }
 
-// Candidate pass: histogram of key bits [shift, shift+bits) among candidates that match the prefix.
-__global__ __launch_bounds__(kGThreads) void choco_cand_hist_kernel(const unsigned long long *__restrict__ cand, size_t d,
-                                                                    const long long *__restrict__ off, int nseg,
-                                                                    const PairState *__restrict__ st, int shift, int bits,
-                                                                    unsigned int *__restrict__ hist) {
-    __shared__ int s_first;
-    const int agent = blockIdx.y;
-    const long long e0 = (long long)blockIdx.x * kCandTile;
-    const long long e1 = min(e0 + (long long)kCandTile, (long long)d);
-    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+// Refinement: one block per (agent, segment) finishes the selection among the pair's candidates (the keys sharing the
+// 12-bit prefix; a fraction of a per cent of the segment for bell-shaped data).  Four more radix rounds (13, 13, 13, 12
+// bits) each histogram the keys that still match the prefix in LDS and pick the bin holding the wanted rank.  After
+// the first round the survivors are normally a handful: they are copied to LDS and the remaining rounds never touch
+// memory; if they do not fit (massive ties) the rounds keep streaming the candidate list.  On exit prefix = the full
+// 63-bit key of the k-th largest element.
+constexpr int kRefThreads = 512;
+constexpr int kRefList = 2048;
+
+// Bin of the rank-th largest key in a histogram of nb bins (descending bin order), and how many keys lie above it.
+__device__ __forceinline__ void select_bin(const unsigned int *hist, int nb, unsigned int rank, unsigned int *wave_tot,
+                                           unsigned int *s_bin, unsigned int *s_above) {
+    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
+    const int per = nb / kRefThreads;  // thread t owns bins nb-1 - t*per - k, k = 0..per-1
+    unsigned int sum = 0;
+    for (int k = 0; k < per; ++k) sum += hist[nb - 1 - (t * per + k)];
+    unsigned int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
-    const unsigned long long mask = (1ull << bits) - 1ull;
-    for (int s = s_first; s < nseg && off[s] < e1; ++s) {
-        const PairState ps = st[(size_t)agent * nseg + s];
-        const long long lo = max(off[s], e0), hi = min(off[s] + (long long)ps.cand, e1);
-        unsigned int *h = hist + ((size_t)agent * nseg + s) * kBins;
-        for (long long e = lo + threadIdx.x; e < hi; e += kGThreads) {
-            const unsigned long long key = cand[(size_t)agent * d + e];
-            if ((key >> (shift + bits)) == ps.prefix) atomicAdd(&h[(key >> shift) & mask], 1u);
+    unsigned int before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    incl += before;
+    const unsigned int excl = incl - sum;
+    if (excl < rank && rank <= incl) {  // exactly one thread: the matching keys number at least rank
+        unsigned int run = excl;
+        for (int k = 0; k < per; ++k) {
+            const int b = nb - 1 - (t * per + k);
+            if (run + hist[b] >= rank) { *s_bin = (unsigned int)b; *s_above = run; break; }
+            run += hist[b];
         }
     }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigned long long *__restrict__ cand, size_t d,
+                                                                   const long long *__restrict__ off, int nseg,
+                                                                   PairState *__restrict__ st) {
+    __shared__ unsigned int hist[8192];
+    __shared__ unsigned long long list[kRefList];
+    __shared__ unsigned int wave_tot[kRefThreads / 64];
+    __shared__ unsigned int s_bin, s_above, s_cnt;
+    const int pair = blockIdx.x, agent = pair / nseg, seg = pair % nseg;
+    const PairState ps = st[pair];
+    if (ps.rank == 0u) return;  // empty segment: the scan has set the prefix that selects nothing
+    const unsigned long long *c = cand + (size_t)agent * d + off[seg];
+    const unsigned int count = ps.cand;
+    unsigned long long prefix = ps.prefix;
+    unsigned int rank = ps.rank, listed = 0;
+    bool in_lds = false;
+    const int shifts[4] = {38, 25, 12, 0}, widths[4] = {13, 13, 13, 12};
+    for (int r = 0; r < 4; ++r) {
+        const int shift = shifts[r], bits = widths[r], nb = 1 << bits;
+        const unsigned long long mask = (unsigned long long)(nb - 1);
+        for (int i = threadIdx.x; i < nb; i += kRefThreads) hist[i] = 0u;
+        __syncthreads();
+        if (in_lds) {
+            for (unsigned int i = threadIdx.x; i < listed; i += kRefThreads) {
+                const unsigned long long key = list[i];
+                if ((key >> (shift + bits)) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
+            }
+        } else {
+            for (unsigned int i = threadIdx.x; i < count; i += kRefThreads) {
+                const unsigned long long key = c[i];
+                if ((key >> (shift + bits)) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
+            }
+        }
+        __syncthreads();
+        select_bin(hist, nb, rank, wave_tot, &s_bin, &s_above);
+        prefix = (prefix << bits) | (unsigned long long)s_bin;
+        rank -= s_above;
+        if (r == 0 && hist[s_bin] <= (unsigned int)kRefList) {  // the same decision in every thread
+            if (threadIdx.x == 0) s_cnt = 0u;
+            __syncthreads();
+            for (unsigned int i = threadIdx.x; i < count; i += kRefThreads) {
+                const unsigned long long key = c[i];
+                if ((key >> shift) == prefix) list[atomicAdd(&s_cnt, 1u)] = key;
+            }
+            __syncthreads();
+            listed = s_cnt;
+            in_lds = true;
+        }
+        __syncthreads();  // everyone has read s_bin / hist before the next round clears them
+    }
+    if (threadIdx.x == 0) st[pair].prefix = prefix;
 }
 
 // Final pass: xhat += top-k(x - xhat) for every agent, then the gossip update of x.
@@ -515,19 +582,13 @@ extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const flo
         hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
                            nseg, d_hist, hist_words);
         const dim3 tiles((unsigned int)((d + kTile - 1) / kTile), n);
-        const dim3 ctiles((unsigned int)((d + kCandTile - 1) / kCandTile), n);
         const bool vec4 = d % 4 == 0 && aligned(x, 16) && aligned(xhat, 16);
         if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
         else hipLaunchKernelGGL(choco_hist_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
         hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12);
         if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
         else hipLaunchKernelGGL(choco_collect_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
-        const int shifts[4] = {38, 25, 12, 0}, widths[4] = {13, 13, 13, 12};
-        for (int p = 0; p < 4; ++p) {
-            hipLaunchKernelGGL(choco_cand_hist_kernel, ctiles, dim3(kGThreads), 0, st, d_cand, d, d_off, nseg, d_st, shifts[p],
-                               widths[p], d_hist);
-            hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, widths[p]);
-        }
+        hipLaunchKernelGGL(choco_refine_kernel, dim3(n * nseg), dim3(kRefThreads), 0, st, d_cand, d, d_off, nseg, d_st);
     }
     const bool vec2 = n <= 16 && d % 2 == 0 && aligned(x, 8) && aligned(xhat, 8);
     dispatch_nmax(n, [&](auto tag) {

@@ -50,6 +50,9 @@ def test_choco_global_topk_and_ties(orc):
     _choco_case(orc, 8, 100_003, None, 0.01, 0.2, 820)
     _choco_case(orc, 5, 9000, [0, 100, 4500, 9000], 0.05, 0.4, 822, ties=True)   # massive exact ties, zeros
     _choco_case(orc, 4, 3000, [0, 3000], 0.999, 1.0, 824, ties=True)
+    # thousands of equal magnitudes around the threshold: more survivors than the refinement keeps on chip
+    _choco_case(orc, 3, 60000, [0, 60000], 0.3, 0.5, 826, ties=True)
+    _choco_case(orc, 2, 50000, [0, 10, 50000], 0.5, 0.5, 828, ties=True)
 
 
 def test_choco_no_compression(orc):
