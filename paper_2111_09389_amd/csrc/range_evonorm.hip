@@ -386,44 +386,60 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
                                                              float *__restrict__ dx, float *__restrict__ dbeta,
                                                              float *__restrict__ dgamma, float *__restrict__ dv,
                                                              float *__restrict__ absmax_out) {
-    __shared__ float s[3][8][32];
+    __shared__ float s[3][32][8];
     __shared__ float lds[256 / kWave];
-    const int param_blocks = (C + 31) / 32;
-    if ((int)blockIdx.x < param_blocks) {
-        const int cl = threadIdx.x % 32, sl = threadIdx.x / 32;
-        const int c = blockIdx.x * 32 + cl;
-        float a0 = 0, a1 = 0, a2 = 0;
-        if (c < C)
-            for (int r = sl; r < rows; r += 8) {
+    const int param_blocks = (C + 7) / 8;
+    if ((int)blockIdx.x < param_blocks) {  // 8 channels x 32 row lanes: many short chains of loads instead of few long ones
+        const int cl = threadIdx.x % 8, sl = threadIdx.x / 8;
+        const int c = blockIdx.x * 8 + cl;
+        float a0 = 0, a1 = 0, a2 = 0, b0 = 0, b1 = 0, b2 = 0;
+        if (c < C) {
+            int r = sl;
+            for (; r + 32 < rows; r += 64) {
+                a0 += parts[((size_t)r * 4 + 0) * C + c];
+                a1 += parts[((size_t)r * 4 + 1) * C + c];
+                a2 += parts[((size_t)r * 4 + 2) * C + c];
+                b0 += parts[((size_t)(r + 32) * 4 + 0) * C + c];
+                b1 += parts[((size_t)(r + 32) * 4 + 1) * C + c];
+                b2 += parts[((size_t)(r + 32) * 4 + 2) * C + c];
+            }
+            if (r < rows) {
                 a0 += parts[((size_t)r * 4 + 0) * C + c];
                 a1 += parts[((size_t)r * 4 + 1) * C + c];
                 a2 += parts[((size_t)r * 4 + 2) * C + c];
             }
-        s[0][sl][cl] = a0; s[1][sl][cl] = a1; s[2][sl][cl] = a2;
+        }
+        s[0][sl][cl] = a0 + b0; s[1][sl][cl] = a1 + b1; s[2][sl][cl] = a2 + b2;
         __syncthreads();
-        if (sl == 0 && c < C) {
-            float b0 = 0, b1 = 0, b2 = 0;
-            for (int k = 0; k < 8; ++k) { b0 += s[0][k][cl]; b1 += s[1][k][cl]; b2 += s[2][k][cl]; }
-            dbeta[c] = b0; dgamma[c] = b1; dv[c] = b2;
+        if (sl < 3 && c < C) {  // row lane 0, 1, 2 finish dbeta, dgamma, dv
+            float t = 0;
+            for (int k = 0; k < 32; ++k) t += s[sl][k][cl];
+            (sl == 0 ? dbeta : sl == 1 ? dgamma : dv)[c] = t;
         }
         return;
     }
+    // range blocks: one wave per (sample, group) pair; its lanes share the pair's chunks x channels partial sums
     const int rb = blockIdx.x - param_blocks, nrb = gridDim.x - param_blocks;
     float am = 0.0f;
-    const int i = rb * 256 + threadIdx.x;
+    const int i = rb * (256 / kWave) + threadIdx.x / kWave, lane = threadIdx.x % kWave;
     if (i < N * groups) {
         const int n = i / groups, grp = i % groups;
         float t = 0.0f;
-        for (int ch = 0; ch < chunks; ++ch)
-            for (int cc = 0; cc < m; ++cc) t += parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc];
-        const float inv = inv_denominator(range[i], cm, eps);
-        const float dR = -cm * t * inv * inv;
-        const int ia = argmax[i], ib = argmin[i];
-        const size_t base = (size_t)n * HW * C + (size_t)grp * m;
-        const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
-        dx[pa] += dR;
-        dx[pb] -= dR;
-        am = fmaxf(fabsf(dx[pa]), fabsf(dx[pb]));
+        for (int k = lane; k < chunks * m; k += kWave) {
+            const int ch = k / m, cc = k - ch * m;
+            t += parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc];
+        }
+        t = wave_sum(t);
+        if (lane == 0) {
+            const float inv = inv_denominator(range[i], cm, eps);
+            const float dR = -cm * t * inv * inv;
+            const int ia = argmax[i], ib = argmin[i];
+            const size_t base = (size_t)n * HW * C + (size_t)grp * m;
+            const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
+            dx[pa] += dR;
+            dx[pb] -= dR;
+            am = fmaxf(fabsf(dx[pa]), fabsf(dx[pb]));
+        }
     }
     if (absmax_out) {
         for (int r = rb * 256 + threadIdx.x; r < rows; r += nrb * 256) am = fmaxf(am, pabs[r]);
@@ -535,7 +551,7 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
         hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,
                            kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out);
     }
-    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3((C + 31) / 32 + (N * groups + 255) / 256), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3((C + 7) / 8 + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_bwd");
 }
