@@ -76,6 +76,19 @@ int lpdt_quantize(const float *x, size_t len, int rounding, uint64_t seed, uint6
 int lpdt_quantize_with_absmax(const float *x, size_t len, const float *absmax, int rounding,
                               uint64_t seed, uint64_t offset, int8_t *q, float *scale, void *stream);
 
+/* Many tensors in one call (the weights of all layers of a model, Section 3: every layer's
+ * weights are quantized each iteration): slice s = x[seg_begin[s], seg_end[s]) gets its own
+ * scale, scales[s], and its codes go to q[seg_begin[s], seg_end[s]) -- exactly what
+ * lpdt_quantize(x + seg_begin[s], seg_end[s] - seg_begin[s], rounding, seed,
+ * offset + s*2^24, ...) would write, in three launches for any number of slices.
+ * seg_begin, seg_end: HOST arrays of nseg element indices (read before the call returns);
+ * slices must be non-empty, at most 2^26 elements each, and should not overlap.
+ * x, q, scales: device.  LPDT_EUNSUPPORTED for an empty slice or nseg <= 0. */
+size_t lpdt_quantize_segments_workspace_bytes(int nseg);
+int lpdt_quantize_segments(const float *x, const int64_t *seg_begin, const int64_t *seg_end, int nseg,
+                           int rounding, uint64_t seed, uint64_t offset, int8_t *q, float *scales,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* y_i = (sA*sB) * acc_i, the real value of an int32 accumulator of two quantized
  * tensors; sA, sB: device scalars.  If accumulate != 0, y_i += that value. */
 int lpdt_dequantize(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y,

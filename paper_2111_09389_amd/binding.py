@@ -6,7 +6,7 @@ import torch
 
 __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
-    "quantize", "quantize_with_absmax", "dequantize",
+    "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
@@ -20,7 +20,8 @@ _LIB_PATH = os.path.join(_HERE, "liblpdt.so")
 # every symbol include/lpdt.h declares
 EXPORTS = [
     "lpdt_last_error", "lpdt_version",
-    "lpdt_quantize_workspace_bytes", "lpdt_quantize", "lpdt_quantize_with_absmax", "lpdt_dequantize",
+    "lpdt_quantize_workspace_bytes", "lpdt_quantize", "lpdt_quantize_with_absmax",
+    "lpdt_quantize_segments_workspace_bytes", "lpdt_quantize_segments", "lpdt_dequantize",
     "lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes", "lpdt_qconv_bwd_weight_workspace_bytes",
     "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
     "lpdt_qconv_fwd_f32_workspace_bytes", "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
@@ -79,6 +80,7 @@ def lib():
             if name.endswith("_workspace_bytes"):
                 getattr(L, name).restype = _sz
         L.lpdt_quantize_workspace_bytes.argtypes = [_sz]
+        L.lpdt_quantize_segments_workspace_bytes.argtypes = [ctypes.c_int]
         for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
                      "lpdt_qconv_bwd_weight_workspace_bytes", "lpdt_qconv_fwd_f32_workspace_bytes",
                      "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes"):
@@ -159,6 +161,23 @@ def quantize_with_absmax(x, absmax, rounding=ROUND_NEAREST, seed=0, offset=0, q=
     _check(lib().lpdt_quantize_with_absmax(_ptr(x), _sz(x.numel()), _ptr(absmax), int(rounding), ctypes.c_uint64(seed),
                                            ctypes.c_uint64(offset), _ptr(q), _ptr(scale), _stream()))
     return q, scale
+
+
+def quantize_segments(x, seg_begin, seg_end, rounding=ROUND_NEAREST, seed=0, offset=0, q=None, scales=None, ws=None):
+    """Slices x.flat[seg_begin[s]:seg_end[s]] of one fp32 buffer, each with its own scale -> (int8 codes laid out like x,
+    fp32 scales[nseg])."""
+    _dev(x, torch.float32, "quantize_segments x")
+    nseg = len(seg_begin)
+    if len(seg_end) != nseg:
+        raise ValueError("seg_begin and seg_end differ in length")
+    q = torch.zeros(x.shape, dtype=torch.int8, device=x.device) if q is None else q
+    scales = torch.empty(max(nseg, 1), dtype=torch.float32, device=x.device) if scales is None else scales
+    b = (ctypes.c_int64 * max(nseg, 1))(*[int(v) for v in seg_begin])
+    e = (ctypes.c_int64 * max(nseg, 1))(*[int(v) for v in seg_end])
+    buf, nb = _ws(ws, lib().lpdt_quantize_segments_workspace_bytes(nseg))
+    _check(lib().lpdt_quantize_segments(_ptr(x), b, e, nseg, int(rounding), ctypes.c_uint64(seed), ctypes.c_uint64(offset),
+                                        _ptr(q), _ptr(scales), _ptr(buf), _sz(nb), _stream()))
+    return q, scales
 
 
 def dequantize(acc, sA, sB, y=None, accumulate=False):

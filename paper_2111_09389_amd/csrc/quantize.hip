@@ -113,6 +113,89 @@ __global__ __launch_bounds__(kQThreads) void round_kernel(const float *__restric
     }
 }
 
+// ---- many slices of one buffer in two launches --------------------------------
+// Slice table in device memory: begin[s], end[s] (element indices), written from kernel arguments so that the call
+// needs no host-to-device copy and can be captured in a graph.
+constexpr int kSegChunk = 128;
+constexpr int kSegTile = kQThreads * 16;  // elements per block
+struct SegChunk { long long v[2 * kSegChunk]; };
+
+__global__ void seg_upload_kernel(SegChunk c, long long *table, unsigned int *amax, int first, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 2 * count) table[2 * first + i] = c.v[i];
+    if (i < count) amax[first + i] = 0u;
+}
+
+// grid (tiles of the longest slice, slices); |x| >= 0, so its maximum is also the maximum of the bit patterns
+__global__ __launch_bounds__(kQThreads) void seg_absmax_kernel(const float *__restrict__ x, const long long *__restrict__ table,
+                                                               unsigned int *__restrict__ amax) {
+    __shared__ float lds[kQThreads / kWave];
+    const long long begin = table[2 * blockIdx.y], len = table[2 * blockIdx.y + 1] - begin;
+    const long long t0 = (long long)blockIdx.x * kSegTile;
+    if (t0 >= len) return;
+    const long long t1 = min(t0 + (long long)kSegTile, len);
+    const float *xs = x + begin;
+    float m = 0.0f;
+    if (((begin & 3) == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0)) {
+        const long long v1 = t1 / 4;
+        for (long long i = t0 / 4 + threadIdx.x; i < v1; i += kQThreads) {
+            const float4 a = reinterpret_cast<const float4 *>(xs)[i];
+            m = fmaxf(fmaxf(m, fmaxf(fabsf(a.x), fabsf(a.y))), fmaxf(fabsf(a.z), fabsf(a.w)));
+        }
+        for (long long i = v1 * 4 + threadIdx.x; i < t1; i += kQThreads) m = fmaxf(m, fabsf(xs[i]));
+    } else {
+        for (long long i = t0 + threadIdx.x; i < t1; i += kQThreads) m = fmaxf(m, fabsf(xs[i]));
+    }
+    m = block_max(m, lds);
+    if (threadIdx.x == 0) atomicMax(&amax[blockIdx.y], __float_as_uint(m));
+}
+
+template <bool kStochastic>
+__global__ __launch_bounds__(kQThreads) void seg_round_kernel(const float *__restrict__ x, const long long *__restrict__ table,
+                                                              const unsigned int *__restrict__ amax, uint64_t seed,
+                                                              uint64_t offset, int8_t *__restrict__ q,
+                                                              float *__restrict__ scales) {
+    const int s = blockIdx.y;
+    const long long begin = table[2 * s], len = table[2 * s + 1] - begin;
+    const float a = __uint_as_float(amax[s]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) scales[s] = __fdiv_rn(a, 127.0f);
+    const long long t0 = (long long)blockIdx.x * kSegTile;
+    if (t0 >= len) return;
+    const long long t1 = min(t0 + (long long)kSegTile, len);
+    const float inv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint64_t base = offset + ((uint64_t)s << 24);  // slice s has its own counter range
+    const float *xs = x + begin;
+    int8_t *qs = q + begin;
+    const bool vec = ((begin & 3) == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(q) & 3) == 0);
+    long long done = t0;
+    if (vec) {
+        const long long v1 = t1 / 4;
+        for (long long i = t0 / 4 + threadIdx.x; i < v1; i += kQThreads) {
+            const float4 v = reinterpret_cast<const float4 *>(xs)[i];
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            if (kStochastic) {
+                const uint64_t blk = base + (uint64_t)i;
+                philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
+            }
+            const uint32_t b0 = (uint32_t)round_code(v.x, inv, kStochastic, w[0]) & 0xffu;
+            const uint32_t b1 = (uint32_t)round_code(v.y, inv, kStochastic, w[1]) & 0xffu;
+            const uint32_t b2 = (uint32_t)round_code(v.z, inv, kStochastic, w[2]) & 0xffu;
+            const uint32_t b3 = (uint32_t)round_code(v.w, inv, kStochastic, w[3]) & 0xffu;
+            reinterpret_cast<uint32_t *>(qs)[i] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+        }
+        done = v1 * 4;
+    }
+    for (long long i = done + threadIdx.x; i < t1; i += kQThreads) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (kStochastic) {
+            const uint64_t blk = base + (uint64_t)(i / 4);
+            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
+        }
+        qs[i] = (int8_t)round_code(xs[i], inv, kStochastic, w[i & 3]);
+    }
+}
+
 template <bool kAccumulate>
 __global__ __launch_bounds__(kQThreads) void dequant_kernel(const int32_t *__restrict__ acc, size_t len,
                                                             const float *__restrict__ sA,
@@ -211,4 +294,46 @@ extern "C" int lpdt_dequantize(const int32_t *acc, size_t len, const float *sA, 
     LPDT_REQUIRE(aligned(acc, 16) && aligned(y, 16), LPDT_EINVAL, "dequantize: acc and y must be 16-byte aligned");
     launch_dequant(acc, len, sA, sB, y, accumulate != 0, as_stream(stream));
     return launch_status("lpdt_dequantize");
+}
+
+extern "C" size_t lpdt_quantize_segments_workspace_bytes(int nseg) {
+    if (nseg <= 0) return 0;
+    return round_up((size_t)nseg * 2 * sizeof(long long), 256) + round_up((size_t)nseg * sizeof(unsigned int), 256);
+}
+
+extern "C" int lpdt_quantize_segments(const float *x, const int64_t *seg_begin, const int64_t *seg_end, int nseg, int rounding,
+                                      uint64_t seed, uint64_t offset, int8_t *q, float *scales, void *ws, size_t ws_bytes,
+                                      void *stream) {
+    LPDT_REQUIRE(x && q && scales && seg_begin && seg_end, LPDT_EINVAL, "quantize_segments: NULL argument");
+    LPDT_REQUIRE(nseg > 0, LPDT_EUNSUPPORTED, "quantize_segments: nseg must be positive");
+    LPDT_REQUIRE(nseg <= 65535, LPDT_EUNSUPPORTED, "quantize_segments: at most 65535 slices");
+    LPDT_REQUIRE(rounding == LPDT_ROUND_NEAREST || rounding == LPDT_ROUND_STOCHASTIC, LPDT_EINVAL,
+                 "quantize_segments: rounding must be 0 (nearest) or 1 (stochastic)");
+    LPDT_REQUIRE(aligned(x, 4) && aligned(scales, 4), LPDT_EINVAL, "quantize_segments: x and scales must be 4-byte aligned");
+    long long longest = 0;
+    for (int s = 0; s < nseg; ++s) {
+        LPDT_REQUIRE(seg_begin[s] >= 0 && seg_end[s] > seg_begin[s], LPDT_EUNSUPPORTED,
+                     "quantize_segments: slice %d is empty or negative", s);
+        LPDT_REQUIRE(seg_end[s] - seg_begin[s] <= (1ll << 26), LPDT_EUNSUPPORTED,
+                     "quantize_segments: slice %d has more than 2^26 elements (its stochastic-rounding counters would overlap the next slice's)", s);
+        if (seg_end[s] - seg_begin[s] > longest) longest = seg_end[s] - seg_begin[s];
+    }
+    int rc = check_ws(ws, ws_bytes, lpdt_quantize_segments_workspace_bytes(nseg));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    long long *table = static_cast<long long *>(ws);
+    unsigned int *amax = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + round_up((size_t)nseg * 2 * sizeof(long long), 256));
+    for (int o = 0; o < nseg; o += kSegChunk) {
+        SegChunk c;
+        const int m = nseg - o < kSegChunk ? nseg - o : kSegChunk;
+        for (int i = 0; i < m; ++i) { c.v[2 * i] = seg_begin[o + i]; c.v[2 * i + 1] = seg_end[o + i]; }
+        hipLaunchKernelGGL(seg_upload_kernel, dim3(1), dim3(2 * kSegChunk), 0, st, c, table, amax, o, m);
+    }
+    const dim3 grid((unsigned)((longest + kSegTile - 1) / kSegTile), (unsigned)nseg);
+    hipLaunchKernelGGL(seg_absmax_kernel, grid, dim3(kQThreads), 0, st, x, table, amax);
+    if (rounding == LPDT_ROUND_STOCHASTIC)
+        hipLaunchKernelGGL(seg_round_kernel<true>, grid, dim3(kQThreads), 0, st, x, table, amax, seed, offset, q, scales);
+    else
+        hipLaunchKernelGGL(seg_round_kernel<false>, grid, dim3(kQThreads), 0, st, x, table, amax, seed, offset, q, scales);
+    return launch_status("lpdt_quantize_segments");
 }

@@ -42,7 +42,7 @@ class TrainStep:
         f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=self.dev)
         i8 = lambda *s: torch.empty(s, dtype=torch.int8, device=self.dev)
         i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=self.dev)
-        self.pview, self.gview = {}, {}
+        self.pview, self.gview, self._poff = {}, {}, {}
         at = 0
         for name, shp in net.params:
             k = 1
@@ -52,6 +52,7 @@ class TrainStep:
                 raise LpdtError(-1, "parameter tensors must start at multiples of 4 elements (16-byte alignment)")
             self.pview[name] = params[at:at + k].view(shp)
             self.gview[name] = grads[at:at + k].view(shp)
+            self._poff[name] = (at, at + k)
             at += k
         self.act = {"x": x}
         self.absmax = {}                 # tensor name -> device scalar max|t| (when its producer supplies it)
@@ -102,6 +103,22 @@ class TrainStep:
     def _plan_forward(self, labels, upstream):
         net, N, L = self.net, self.N, self.L
         self.xq, self.sx, self.wq, self.sw, self.desc, self.ren_saved, self.pool_idx = {}, {}, {}, {}, {}, {}, {}
+        # All filters are quantized by one call on the flat parameter vector (own scale each); their codes keep the
+        # vector's layout, so a filter's codes are a 16-byte aligned slice when its offset is a multiple of 16.
+        convs = [op for op in net.ops if op[0] == "conv"]
+        spans = [self._poff[op[3]["w"]] for op in convs]
+        batched = len(convs) > 1 and all(b % 16 == 0 for b, _ in spans)
+        if batched:
+            wq_flat, sw_all = self._i8(self.params.numel()), self._f32(len(convs))
+            self._seg_arrays = ((ctypes.c_int64 * len(spans))(*[b for b, _ in spans]),
+                                (ctypes.c_int64 * len(spans))(*[e for _, e in spans]))
+            self._need_ws(L.lpdt_quantize_segments_workspace_bytes(len(spans)))
+            self._emit(L.lpdt_quantize_segments,
+                       [_p(self.params), self._seg_arrays[0], self._seg_arrays[1], len(spans), ROUND_NEAREST, _u64(self.seed),
+                        _u64(0), _p(wq_flat), _p(sw_all), "WS", "WSB"])
+            for i, (op, (b, e)) in enumerate(zip(convs, spans)):
+                self.wq[op[1]] = wq_flat[b:e].view(self.pview[op[3]["w"]].shape)
+                self.sw[op[1]] = sw_all[i:i + 1]
         for op in net.ops:
             kind = op[0]
             if kind == "conv":
@@ -109,8 +126,9 @@ class TrainStep:
                 d = self._desc(inp, a)
                 self.desc[out] = d
                 w = self.pview[a["w"]]
-                self.wq[out], self.sw[out] = self._i8(*w.shape), self._f32(1)
-                self._quantize(w, self.wq[out], self.sw[out], ROUND_NEAREST)
+                if not batched:
+                    self.wq[out], self.sw[out] = self._i8(*w.shape), self._f32(1)
+                    self._quantize(w, self.wq[out], self.sw[out], ROUND_NEAREST)
                 if inp not in self.xq:       # one quantization per tensor, shared by its consumers
                     src = self.act[inp]
                     self.xq[inp], self.sx[inp] = self._i8(*src.shape), self._f32(1)

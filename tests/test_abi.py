@@ -54,6 +54,22 @@ def test_quantize_argument_errors(L):
     assert L.lpdt_quantize(FAKE, sz(4), 0, u64(0), u64(0), FAKE, FAKE, ctypes.c_void_p(0x10010), sz(8192), None) == -3
 
 
+def test_quantize_segments_argument_errors(L):
+    u64, i64 = ctypes.c_uint64, ctypes.c_int64
+    b, e = (i64 * 2)(0, 16), (i64 * 2)(16, 40)
+    need = L.lpdt_quantize_segments_workspace_bytes(2)
+    assert need >= 2 * 16 + 2 * 4
+    assert L.lpdt_quantize_segments(FAKE, b, e, 0, 0, u64(0), u64(0), FAKE, FAKE, FAKE, sz(need), None) == -2
+    assert L.lpdt_quantize_segments(None, b, e, 2, 0, u64(0), u64(0), FAKE, FAKE, FAKE, sz(need), None) == -1
+    assert L.lpdt_quantize_segments(FAKE, b, e, 2, 3, u64(0), u64(0), FAKE, FAKE, FAKE, sz(need), None) == -1
+    assert L.lpdt_quantize_segments(FAKE, b, e, 2, 0, u64(0), u64(0), FAKE, FAKE, FAKE, sz(8), None) == -3
+    empty = (i64 * 2)(16, 16)
+    assert L.lpdt_quantize_segments(FAKE, b, empty, 2, 0, u64(0), u64(0), FAKE, FAKE, FAKE, sz(need), None) == -2
+    assert "slice 1" in _err(L)
+    huge = (i64 * 2)(16, (1 << 26) + 1 + 16)
+    assert L.lpdt_quantize_segments(FAKE, b, huge, 2, 1, u64(0), u64(0), FAKE, FAKE, FAKE, sz(need), None) == -2
+
+
 def test_conv_argument_errors(L):
     good = lpdt.ConvDesc.make(2, 16, 8, 8, 16, 3, 3, 1, 1)
     assert L.lpdt_qconv_fwd(None, FAKE, FAKE, FAKE, None, sz(0), None) == -1

@@ -80,3 +80,22 @@ def test_determinism():
     a, _ = lpdt.quantize(x, 1, 5, 6)
     b, _ = lpdt.quantize(x, 1, 5, 6)
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quantize_segments_equals_per_slice_quantize(orc, rounding):
+    """Slices of one buffer, own scale each: the oracle's quantizer on every slice, with slice s at counter offset + s*2^24."""
+    g = wl.rng(77)
+    x = (g.standard_normal(40_000) * 0.1).astype(np.float32)
+    x[300:420] = 0.0                                         # an all-zero slice: scale 0, codes 0
+    begins = [0, 300, 420, 4096 + 4, 9001, 30_000]           # 9001: a slice that does not start on a 16-byte boundary
+    ends = [300, 420, 4100, 9001, 29_999, 40_000]            # 29_999..30_000: a gap that must stay untouched
+    seed, offset = wl.PHILOX_SEED, 12345
+    q0 = torch.full((40_000,), 77, dtype=torch.int8, device="cuda")
+    q, scales = lpdt.quantize_segments(dev(x), begins, ends, rounding, seed, offset, q=q0)
+    q, scales = host(q), host(scales)
+    for s, (b, e) in enumerate(zip(begins, ends)):
+        qr, sr = orc.quantize(x[b:e], rounding, seed, offset + (s << 24))
+        assert np.array_equal(q[b:e], qr), f"slice {s}"
+        assert scales[s] == np.float32(sr)
+    assert q[29_999] == 77
