@@ -22,6 +22,38 @@ sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "resnet18_b64_conv_kernels_hbm_traffic.txt")
+
+
+def measured_conv_traffic(cfg_id):
+    """HBM bytes all conv kernels of one config-5 step moved, from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a copy kernel of known size); None for other configs or when the summary is absent."""
+    if cfg_id != 5 or not os.path.exists(TRAFFIC_FILE):
+        return None
+    for line in open(TRAFFIC_FILE):
+        if line.startswith("conv_kernels_hbm_bytes_per_step:"):
+            return float(line.split(":")[1].split()[0])
+    return None
+
+
+def conv_algorithmic_bytes(net, batch):
+    """int8 operands once + result once (4 bytes per element) for each of the three products of every conv layer
+    (two for the first layer)."""
+    total = 0
+    first = True
+    for op in net.ops:
+        if op[0] != "conv":
+            continue
+        _, out, inp, a = op
+        H, W, C = net.shapes[inp]
+        P, Q, K = net.shapes[out]
+        x, y, w = batch * H * W * C, batch * P * Q * K, K * a["R"] * a["R"] * C
+        total += x + w + 4 * y                      # forward
+        total += y + x + 4 * w                      # backward-weight
+        if not first:
+            total += y + w + 4 * x                  # backward-data
+        first = False
+    return total
 
 CONFIGS = {
     1: dict(name="single 3x3 16->16 conv + Range-EvoNorm(g=8), batch 8, 32x32", net="single_layer", batch=8, agents=1, mix=None),
@@ -123,8 +155,8 @@ def cpu_baseline(cfg_id, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=sorted(CONFIGS))
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph (launch-bound configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -213,8 +245,11 @@ def main():
         "gossip_mix_ms": mix_ms,
         "conv_tops_by_kind": kind_tops,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": achieved / INT8_PEAK_TOPS, "traffic": None,
-                     "kernel": "igemm_kernel + wgrad_kernel (all conv launches of one step: ops / summed duration)"},
+                     "frac": achieved / INT8_PEAK_TOPS, "traffic": measured_conv_traffic(args.config),
+                     "algorithmic_bytes": conv_algorithmic_bytes(net, cfg["batch"]) * len(steps),
+                     "kernel": "all kernels behind the three conv entry points of one step (igemm_kernel, wgrad_rect_kernel + "
+                               "wgrad_reduce_kernel, narrow_*_kernel, filter packing): conv ops / summed duration; traffic and "
+                               "algorithmic_bytes are per step like achieved"},
     }
     if mix_ms:
         d, n = net.num_params(), cfg["agents"]
