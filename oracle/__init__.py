@@ -178,6 +178,33 @@ def gossip_mix(x, xhat, Wm, eta=1.0, keep_ratio=1.0, seg_offsets=None):
     return out, xh
 
 
+MIX_PLAIN, MIX_CHOCO, MIX_DEEPSQUEEZE = 0, 1, 2
+
+
+def gossip_mix_ex(x, state, Wm, eta=1.0, keep_ratio=1.0, seg_offsets=None, mode=MIX_PLAIN, u=None):
+    """One gossip step of the supplement's variants.  state: xhat (CHOCO) / delta (Deep-Squeeze) float32 [n,d] or None;
+    u: push-sum bias weights float32 [n] or None.
+    -> (x_new float64 [n,d], state_new float32 or None, u_new float64 [n] or None, z float64 [n,d] or None)."""
+    x = _c(x, np.float32)
+    n, d = x.shape
+    Wm = _c(Wm, np.float32)
+    assert Wm.shape == (n, n)
+    if seg_offsets is None:
+        seg_offsets = [0, d]
+    seg = _c(seg_offsets, np.int64)
+    out = np.empty((n, d), np.float64)
+    st = None if state is None else np.array(state, dtype=np.float32, order="C", copy=True)
+    uu = None if u is None else _c(u, np.float32)
+    u_out = None if u is None else np.empty(n, np.float64)
+    z_out = None if u is None else np.empty((n, d), np.float64)
+    rc = lib().orc_gossip_mix_ex(_p(x), None if st is None else _p(st), n, ctypes.c_size_t(d), _p(Wm), ctypes.c_float(eta),
+                                 ctypes.c_double(keep_ratio), _p(seg), len(seg) - 1, int(mode),
+                                 None if uu is None else _p(uu), _p(out), None if u_out is None else _p(u_out),
+                                 None if z_out is None else _p(z_out))
+    _chk(rc, "gossip_mix_ex")
+    return out, st, u_out, z_out
+
+
 def add(a, b):
     a = _c(a, np.float64)
     b = _c(b, np.float64)

@@ -359,6 +359,98 @@ int orc_gossip_mix(const float *x, float *xhat, int n, size_t d, const float *Wm
 }
 
 /* ------------------------------------------------------------------------- */
+/* The other gossip variants of the supplement (Algorithms "Deep-Squeeze", "Sparse-Push",
+ * "Quant-SGP"), one step each, after the local update.
+ *   mode 0: no compression    x_i+ = x_i + eta * sum_j (W_ij - I_ij) x_j
+ *   mode 1: CHOCO             state = xhat:  q = TopK(x_i - xhat_i); xhat_i += q;
+ *                             x_i+ = x_i + eta * sum_j (W_ij - I_ij)(xhat_j - xhat_i)
+ *   mode 2: Deep-Squeeze      state = delta (error memory):  v = x_i + delta_i (fp32);
+ *                             C[v] = v on the top-k |v| of each segment, 0 elsewhere;
+ *                             delta_i = v - C[v];  x_i+ = x_i + eta * sum_j (W_ij - I_ij) C[v_j]
+ *   u != NULL (push-sum, Algorithms "Sparse-Push" = mode 2 + u, "Quant-SGP" = mode 1 + u):
+ *                             u_i+ = u_i + eta * sum_j (W_ij - I_ij) u_j;   z_i = x_i+ / u_i+
+ *                             With u, mode 1 mixes xhat by the same operator as u and as modes 0 and 2,
+ *                             x_i+ = x_i + eta * sum_j (W_ij - I_ij) xhat_j.  For a W whose rows sum to 1 this is
+ *                             the printed (xhat_j - xhat_i) form; for a merely column-stochastic W the printed form
+ *                             would not conserve sum_i x_i, which the de-biasing by u relies on.
+ * Top-k as in orc_gossip_mix: k = max(1, ceil(keep_ratio*len)), larger |v| first (fp32 bit
+ * pattern), lower index on ties.  W only has to be column stochastic when u is given. */
+int orc_gossip_mix_ex(const float *x, float *state, int n, size_t d, const float *Wm, float eta, double keep_ratio,
+                      const int64_t *seg_offsets, int nseg, int mode, const float *u, double *x_out, double *u_out,
+                      double *z_out)
+{
+    if (mode < 0 || mode > 2 || (mode != 0 && !state)) return ORC_EINVAL;
+    float *cv = NULL; /* mode 2: the compressed vectors C[v_i] */
+    if (mode == 2) {
+        cv = (float *)calloc((size_t)n * d, sizeof(float));
+        if (!cv) return ORC_EINVAL;
+    }
+    if (mode != 0)
+        for (int i = 0; i < n; ++i)
+            for (int sgm = 0; sgm < nseg; ++sgm) {
+                size_t lo = (size_t)seg_offsets[sgm], hi = (size_t)seg_offsets[sgm + 1], len = hi - lo;
+                if (len == 0) continue;
+                int64_t k = (int64_t)ceil(keep_ratio * (double)len);
+                if (k < 1) k = 1;
+                if ((size_t)k > len) k = (int64_t)len;
+                orc_key *keys = (orc_key *)malloc(len * sizeof(orc_key));
+                float *vv = (float *)malloc(len * sizeof(float));
+                if (!keys || !vv) { free(keys); free(vv); free(cv); return ORC_EINVAL; }
+                for (size_t e = 0; e < len; ++e) {
+                    size_t at = (size_t)i * d + lo + e;
+                    volatile float v = (mode == 1) ? x[at] - state[at] : x[at] + state[at];
+                    vv[e] = v;
+                    float ab = fabsf(v);
+                    uint32_t bits;
+                    memcpy(&bits, &ab, 4);
+                    keys[e].mag = bits;
+                    keys[e].idx = (uint32_t)e;
+                }
+                qsort(keys, len, sizeof(orc_key), key_cmp);
+                if (mode == 1) {
+                    for (int64_t t = 0; t < k; ++t) {
+                        size_t at = (size_t)i * d + lo + keys[t].idx;
+                        volatile float s2 = state[at] + vv[keys[t].idx];
+                        state[at] = s2;
+                    }
+                } else {
+                    for (size_t e = 0; e < len; ++e) state[(size_t)i * d + lo + e] = vv[e]; /* delta = v ... */
+                    for (int64_t t = 0; t < k; ++t) {
+                        size_t at = (size_t)i * d + lo + keys[t].idx;
+                        cv[at] = vv[keys[t].idx];
+                        volatile float r = vv[keys[t].idx] - cv[at];                            /* ... minus C[v] */
+                        state[at] = r;
+                    }
+                }
+                free(keys);
+                free(vv);
+            }
+    const float *m = (mode == 0) ? x : (mode == 1) ? state : cv; /* what the neighbours exchange */
+    for (int i = 0; i < n; ++i)
+        for (size_t e = 0; e < d; ++e) {
+            double s = 0.0;
+            for (int j = 0; j < n; ++j) {
+                double wij = (double)Wm[(size_t)i * n + j] - (i == j ? 1.0 : 0.0);
+                double term = (double)m[(size_t)j * d + e];
+                if (mode == 1 && !u) term -= (double)m[(size_t)i * d + e];
+                s += wij * term;
+            }
+            x_out[(size_t)i * d + e] = (double)x[(size_t)i * d + e] + (double)eta * s;
+        }
+    if (u) {
+        for (int i = 0; i < n; ++i) {
+            double s = 0.0;
+            for (int j = 0; j < n; ++j) s += ((double)Wm[(size_t)i * n + j] - (i == j ? 1.0 : 0.0)) * (double)u[j];
+            u_out[i] = (double)u[i] + (double)eta * s;
+        }
+        for (int i = 0; i < n; ++i)
+            for (size_t e = 0; e < d; ++e) z_out[(size_t)i * d + e] = x_out[(size_t)i * d + e] / u_out[i];
+    }
+    free(cv);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Glue layers of the benchmark networks (Table "hardware_training": skip
  * connections, average pool; plus max-pool and the softmax cross-entropy
  * loss, standard definitions), all NHWC, fp64. */

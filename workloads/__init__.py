@@ -85,6 +85,18 @@ def torus_matrix(rows, cols):
     return Wm
 
 
+def directed_matrix(n):
+    """A strongly connected directed graph for push-sum: node j sends to itself, to j+1 and, when j is even, to j+3
+    (mod n), each with weight 1/out-degree(j).  Columns sum to 1, rows do not (in-degrees differ).
+    W[i, j] = weight node i gives what it receives from node j."""
+    Wm = np.zeros((n, n), np.float32)
+    for j in range(n):
+        outs = {j, (j + 1) % n} | ({(j + 3) % n} if j % 2 == 0 else set())
+        for i in outs:
+            Wm[i, j] = np.float32(1.0 / len(outs))
+    return Wm
+
+
 def agent_params(seed, n, d, spread=1e-2):
     """n agents' parameter vectors: a common model ~N(0, 0.05^2) plus a per-agent drift, fp32 [n,d]."""
     g = rng(seed)
