@@ -205,6 +205,31 @@ int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const float *W, floa
                     double keep_ratio, const int64_t *seg_offsets, int nseg, void *ws, size_t ws_bytes,
                     void *stream);
 
+/* The other gossip variants of the supplement, one step each (Algorithms "Deep-Squeeze",
+ * "Sparse-Push", "Quant-SGP"); arguments as for lpdt_gossip_mix, plus:
+ *   mode   LPDT_MIX_PLAIN (state must be NULL), LPDT_MIX_CHOCO (state = xhat, as above) or
+ *          LPDT_MIX_DEEPSQUEEZE: state = delta [n][d], the error memory (zeros at the start):
+ *              v = x_i + delta_i ;  C[v] = v on the top-k |v| of each segment (same rule as
+ *              above), 0 elsewhere ;  delta_i <- v - C[v] ;
+ *              x_i <- x_i + rate * ( sum_j W_ij C[v_j] - C[v_i] ).
+ *   u      NULL, or the push-sum bias weights: n fp32 in DEVICE memory (ones at the start),
+ *              u_i <- u_i + rate * ( sum_j W_ij u_j - u_i ),
+ *          updated in place.  With u, W only has to be column stochastic (directed graphs), and
+ *          LPDT_MIX_CHOCO mixes xhat by the same operator as u: x_i <- x_i + rate *
+ *          ( sum_j W_ij xhat_j - xhat_i ), which is the form above whenever the rows of W sum
+ *          to 1 (the printed difference form does not conserve sum_i x_i otherwise, and the
+ *          de-biasing relies on that).  mode DEEPSQUEEZE + u = Sparse-Push, CHOCO + u = Quant-SGP.
+ *   z      NULL, or [n][d] fp32 out (needs u): the de-biased models z_i = x_i / u_i after the step,
+ *          on which the next gradients are taken.
+ * Without u the rows of W must sum to 1 as well. */
+enum { LPDT_MIX_PLAIN = 0, LPDT_MIX_CHOCO = 1, LPDT_MIX_DEEPSQUEEZE = 2 };
+
+size_t lpdt_gossip_mix_ex_workspace_bytes(int n, size_t d, int nseg, int mode, int push_sum);
+
+int lpdt_gossip_mix_ex(float *x, float *state, int n, size_t d, const float *W, float rate,
+                       double keep_ratio, const int64_t *seg_offsets, int nseg, int mode, float *u,
+                       float *z, void *ws, size_t ws_bytes, void *stream);
+
 /* --------------------------------------------------------------------- glue
  * Table "hardware_training", rows Skip Connections and Average Pool, plus the
  * max-pool, loss and local SGD step (Algorithm 1 step 3) of the benchmark

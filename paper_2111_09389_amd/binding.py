@@ -8,12 +8,13 @@ __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
-    "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix",
+    "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
 
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+MIX_PLAIN, MIX_CHOCO, MIX_DEEPSQUEEZE = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liblpdt.so")
 
@@ -28,7 +29,7 @@ EXPORTS = [
     "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
-    "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix",
+    "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
     "lpdt_add", "lpdt_maxpool_fwd", "lpdt_maxpool_bwd", "lpdt_avgpool_fwd", "lpdt_avgpool_bwd",
     "lpdt_softmax_xent", "lpdt_sgd",
 ]
@@ -88,6 +89,7 @@ def lib():
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
         L.lpdt_gossip_mix_workspace_bytes.argtypes = [ctypes.c_int, _sz, ctypes.c_int, ctypes.c_int]
+        L.lpdt_gossip_mix_ex_workspace_bytes.argtypes = [ctypes.c_int, _sz, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -297,6 +299,32 @@ def gossip_mix(x, xhat, W, rate=1.0, keep_ratio=1.0, seg_offsets=None, ws=None):
     _check(lib().lpdt_gossip_mix(_ptr(x), _ptr(xhat), n, _sz(d), Wc, ctypes.c_float(rate), ctypes.c_double(keep_ratio),
                                  seg, nseg, _ptr(buf), _sz(nb), _stream()))
     return x, xhat
+
+
+def gossip_mix_ex(x, state, W, rate=1.0, keep_ratio=1.0, seg_offsets=None, mode=MIX_PLAIN, u=None, z=None, ws=None):
+    """In-place gossip step of the supplement's variants: state = xhat (MIX_CHOCO) / delta (MIX_DEEPSQUEEZE) / None;
+    u: device fp32 [n] push-sum weights or None; z: device fp32 [n,d] receiving x/u, or None."""
+    _dev(x, torch.float32, "gossip_mix_ex x")
+    n, d = x.shape
+    for t, what in ((state, "state"), (z, "z")):
+        if t is not None:
+            _dev(t, torch.float32, "gossip_mix_ex " + what)
+            assert tuple(t.shape) == (n, d)
+    if u is not None:
+        _dev(u, torch.float32, "gossip_mix_ex u")
+        assert u.numel() == n
+    Wh = torch.as_tensor(W, dtype=torch.float32, device="cpu").contiguous()
+    assert tuple(Wh.shape) == (n, n)
+    Wc = (ctypes.c_float * (n * n)).from_buffer_copy(Wh.numpy().tobytes())
+    if seg_offsets is None:
+        seg, nseg = None, 0
+    else:
+        so = [int(v) for v in seg_offsets]
+        seg, nseg = (ctypes.c_int64 * len(so))(*so), len(so) - 1
+    buf, nb = _ws(ws, lib().lpdt_gossip_mix_ex_workspace_bytes(n, _sz(d), nseg, int(mode), int(u is not None)))
+    _check(lib().lpdt_gossip_mix_ex(_ptr(x), _ptr(state), n, _sz(d), Wc, ctypes.c_float(rate), ctypes.c_double(keep_ratio),
+                                    seg, nseg, int(mode), _ptr(u), _ptr(z), _ptr(buf), _sz(nb), _stream()))
+    return x, state, u, z
 
 
 # ---------------------------------------------------------------- glue

@@ -54,7 +54,8 @@ struct PairState {        // one per (agent, segment)
 
 // ---- plain mix ---------------------------------------------------------------
 template <int NMAX, typename G>
-__global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict__ x, int n, size_t d, G g, float rate) {
+__global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict__ x, int n, size_t d, G g, float rate,
+                                                              const float *__restrict__ unew, float *__restrict__ z) {
     // column values staged in LDS: neighbour ids are run-time values, and LDS takes a
     // run-time row index where registers cannot.  Each thread touches its own column only.
     __shared__ float sv[NMAX][kGThreads];
@@ -74,14 +75,18 @@ __global__ __launch_bounds__(kGThreads) void mix_plain_kernel(float *__restrict_
                 float s = 0.0f;
 #pragma unroll
                 for (int t = 0; t < FixedDeg<G>::value; ++t) s += g.w[i][t] * sv[g.nbr[i][t]][threadIdx.x];
-                x[(size_t)i * d + e] = v[i] + rate * (s - v[i]);
+                const float o = v[i] + rate * (s - v[i]);
+                x[(size_t)i * d + e] = o;
+                if (z) z[(size_t)i * d + e] = __fdiv_rn(o, unew[i]);
             }
     } else {
         for (int i = 0; i < n; ++i) {
             const float vi = sv[i][threadIdx.x];
             float s = 0.0f;
             for (int t = 0; t < g.deg[i]; ++t) s += g.w[i][t] * sv[g.nbr[i][t]][threadIdx.x];
-            x[(size_t)i * d + e] = vi + rate * (s - vi);
+            const float o = vi + rate * (s - vi);
+            x[(size_t)i * d + e] = o;
+            if (z) z[(size_t)i * d + e] = __fdiv_rn(o, unew[i]);
         }
     }
 }
@@ -113,8 +118,11 @@ __device__ __forceinline__ int find_segment(const long long *off, int nseg, long
     return lo;
 }
 
-__device__ __forceinline__ unsigned long long make_key(float xv, float hv, unsigned int idx_in_seg) {
-    const float v = __fsub_rn(xv, hv);
+// what is compressed: x - xhat (CHOCO) or x + delta (Deep-Squeeze), one fp32 operation
+__device__ __forceinline__ float compress_input(float xv, float sv, int ds) { return ds ? __fadd_rn(xv, sv) : __fsub_rn(xv, sv); }
+
+__device__ __forceinline__ unsigned long long make_key(float xv, float hv, unsigned int idx_in_seg, int ds) {
+    const float v = compress_input(xv, hv, ds);
     return ((unsigned long long)(__float_as_uint(v) & 0x7fffffffu) << 32) | (unsigned long long)(~idx_in_seg);
 }
 
@@ -127,7 +135,7 @@ __device__ __forceinline__ void seek_segment(const long long *__restrict__ off, 
 template <int VEC>
 __global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
                                                                size_t d, const long long *__restrict__ off, int nseg,
-                                                               unsigned int *__restrict__ hist) {
+                                                               unsigned int *__restrict__ hist, int ds) {
     __shared__ unsigned int sh[4096];
     __shared__ int s_first;
     const int agent = blockIdx.y;
@@ -153,7 +161,7 @@ __global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__re
 #pragma unroll
         for (int u = 0; u < VEC; ++u) {
             seek_segment(off, e + u, s, end);
-            const unsigned int bin = (__float_as_uint(__fsub_rn(xv[u], hv[u])) & 0x7fffffffu) >> 19;
+            const unsigned int bin = (__float_as_uint(compress_input(xv[u], hv[u], ds)) & 0x7fffffffu) >> 19;
             if (s == sfirst) atomicAdd(&sh[bin], 1u);
             else atomicAdd(&gh_all[(size_t)s * kBins + bin], 1u);
         }
@@ -223,7 +231,7 @@ template <int VEC>
 __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
                                                                   size_t d, const long long *__restrict__ off, int nseg,
                                                                   PairState *__restrict__ st,
-                                                                  unsigned long long *__restrict__ cand) {
+                                                                  unsigned long long *__restrict__ cand, int ds) {
     __shared__ unsigned long long stage[kTile];
     __shared__ int s_first;
     __shared__ unsigned int s_count, s_base;
@@ -249,7 +257,7 @@ __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *_
 #pragma unroll
         for (int u = 0; u < VEC; ++u) {
             if (e + u >= end) { seek_segment(off, e + u, s, end); begin = off[s]; }
-            const unsigned long long key = make_key(xv[u], hv[u], (unsigned int)(e + u - begin));
+            const unsigned long long key = make_key(xv[u], hv[u], (unsigned int)(e + u - begin), ds);
             if (s == sfirst) {
                 if ((key >> 51) == first_prefix) stage[atomicAdd(&s_count, 1u)] = key;
             } else {
@@ -364,7 +372,8 @@ template <int NMAX, int VEC, typename G>
 __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__restrict__ x, float *__restrict__ xhat, int n,
                                                                     size_t d, const long long *__restrict__ off, int nseg,
                                                                     const PairState *__restrict__ st, int select_all,
-                                                                    G g, float rate) {
+                                                                    G g, float rate, int ds, const float *__restrict__ unew,
+                                                                    float *__restrict__ z) {
     __shared__ int s_first;
     __shared__ unsigned long long sprefix[NMAX];        // thresholds of the block's first segment
     __shared__ float sh[NMAX][VEC][kGThreads];          // this thread's columns of xhat (after the update)
@@ -403,16 +412,28 @@ __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__res
             bool any = false;
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
-                const unsigned long long key = make_key(xv[i][u], hv[u], idx[u]);
+                const unsigned long long key = make_key(xv[i][u], hv[u], idx[u], ds);
                 const unsigned long long thr = seg[u] == sfirst ? sprefix[i] : (select_all ? 0ull : st[(size_t)i * nseg + seg[u]].prefix);
-                if (key >= thr) { hv[u] = __fadd_rn(hv[u], __fsub_rn(xv[i][u], hv[u])); any = true; }
-                sh[i][u][threadIdx.x] = hv[u];
+                const bool sel = key >= thr;
+                if (ds) {  // Deep-Squeeze: sh = C[v] (what is sent), state = v - C[v] (what is kept back)
+                    const float v = __fadd_rn(xv[i][u], hv[u]);
+                    sh[i][u][threadIdx.x] = sel ? v : 0.0f;
+                    hv[u] = sel ? __fsub_rn(v, v) : v;
+                    any = true;
+                } else {   // CHOCO: sh = state = xhat + TopK(x - xhat)
+                    if (sel) { hv[u] = __fadd_rn(hv[u], __fsub_rn(xv[i][u], hv[u])); any = true; }
+                    sh[i][u][threadIdx.x] = hv[u];
+                }
             }
             if (any) {
                 if (VEC == 2) *reinterpret_cast<float2 *>(xhat + (size_t)i * d + e) = make_float2(hv[0], hv[VEC - 1]);
                 else xhat[(size_t)i * d + e] = hv[0];
             }
         }
+    // Mixing.  CHOCO with a row-stochastic W: sum_j W_ij (xhat_j - xhat_i), as printed.  With push-sum weights the rows
+    // of W need not sum to 1 and all variants mix by (W - I): sum_j W_ij m_j - m_i, written for CHOCO as the printed sum
+    // plus (rowsum_i - 1) * xhat_i so that the small differences are still formed first.
+    const bool push = unew != nullptr;
 #pragma unroll
     for (int i = 0; i < NMAX; ++i)
         if (i < n) {
@@ -420,18 +441,50 @@ __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__res
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
                 const float hi = sh[i][u][threadIdx.x];
-                float sum = 0.0f;
+                const float ref = ds ? 0.0f : hi;
+                float sum = 0.0f, rs = 0.0f;
                 if constexpr (FixedDeg<G>::value > 0) {
 #pragma unroll
-                    for (int t = 0; t < FixedDeg<G>::value; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - hi);
+                    for (int t = 0; t < FixedDeg<G>::value; ++t) {
+                        sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - ref);
+                        rs += g.w[i][t];
+                    }
                 } else {
-                    for (int t = 0; t < g.deg[i]; ++t) sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - hi);
+                    for (int t = 0; t < g.deg[i]; ++t) {
+                        sum += g.w[i][t] * (sh[g.nbr[i][t]][u][threadIdx.x] - ref);
+                        rs += g.w[i][t];
+                    }
                 }
+                if (ds) sum -= hi;
+                else if (push) sum += (rs - 1.0f) * hi;
                 o[u] = xv[i][u] + rate * sum;
             }
             if (VEC == 2) *reinterpret_cast<float2 *>(x + (size_t)i * d + e) = make_float2(o[0], o[VEC - 1]);
             else x[(size_t)i * d + e] = o[0];
+            if (z) {  // de-biased model z_i = x_i / u_i
+                const float ui = unew[i];
+                if (VEC == 2) *reinterpret_cast<float2 *>(z + (size_t)i * d + e) = make_float2(__fdiv_rn(o[0], ui), __fdiv_rn(o[VEC - 1], ui));
+                else z[(size_t)i * d + e] = __fdiv_rn(o[0], ui);
+            }
         }
+}
+
+// Push-sum bias weights: unew_i = u_i + rate * (sum_j W_ij u_j - u_i); a second launch copies them back once every
+// reader of the old values is done.
+template <typename G>
+__global__ void pushsum_weights_kernel(const float *__restrict__ u, int n, G g, float rate, float *__restrict__ unew) {
+    const int i = threadIdx.x;
+    if (i >= n) return;
+    float s = 0.0f;
+    if constexpr (FixedDeg<G>::value > 0) {
+        for (int t = 0; t < FixedDeg<G>::value; ++t) s += g.w[i][t] * u[g.nbr[i][t]];
+    } else {
+        for (int t = 0; t < g.deg[i]; ++t) s += g.w[i][t] * u[g.nbr[i][t]];
+    }
+    unew[i] = u[i] + rate * (s - u[i]);
+}
+__global__ void copy_small_kernel(const float *__restrict__ src, float *__restrict__ dst, int n) {
+    if ((int)threadIdx.x < n) dst[threadIdx.x] = src[threadIdx.x];
 }
 
 struct ChocoLayout {
@@ -448,7 +501,7 @@ static ChocoLayout choco_layout(int n, size_t d, int nseg) {
     return L;
 }
 
-static int build_graph(const float *W, int n, MixGraph *g) {
+static int build_graph(const float *W, int n, MixGraph *g, bool push_sum) {
     for (int i = 0; i < n; ++i) {
         int deg = 0;
         double row = 0.0;
@@ -464,14 +517,14 @@ static int build_graph(const float *W, int n, MixGraph *g) {
                 ++deg;
             }
         }
-        LPDT_REQUIRE(std::fabs(row - 1.0) <= 1e-5, LPDT_EINVAL, "gossip_mix: row %d of W sums to %.8f, not 1", i, row);
+        LPDT_REQUIRE(push_sum || std::fabs(row - 1.0) <= 1e-5, LPDT_EINVAL, "gossip_mix: row %d of W sums to %.8f, not 1", i, row);
         g->deg[i] = (uint8_t)deg;
     }
     for (int j = 0; j < n; ++j) {
         double col = 0.0;
         for (int i = 0; i < n; ++i) col += W[(size_t)i * n + j];
         LPDT_REQUIRE(std::fabs(col - 1.0) <= 1e-5, LPDT_EINVAL,
-                     "gossip_mix: column %d of W sums to %.8f, not 1 (W must be doubly stochastic)", j, col);
+                     "gossip_mix: column %d of W sums to %.8f, not 1 (W must be doubly stochastic; column stochastic with push-sum weights)", j, col);
     }
     return LPDT_OK;
 }
@@ -509,101 +562,137 @@ static void upload(const long long *src, int count, long long *dst, hipStream_t 
 
 using namespace lpdt;
 
-extern "C" size_t lpdt_gossip_mix_workspace_bytes(int n, size_t d, int nseg, int choco) {
-    if (!choco || n <= 0 || d == 0) return 0;
+static size_t mix_workspace(int n, size_t d, int nseg, bool compressed, bool push_sum) {
+    if (n <= 0 || d == 0) return 0;
     if (nseg <= 0) nseg = 1;
-    return choco_layout(n, d, nseg).total;
+    return (compressed ? choco_layout(n, d, nseg).total : 0) + (push_sum ? 256 : 0);
 }
 
-extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const float *W, float rate, double keep_ratio,
-                               const int64_t *seg_offsets, int nseg, void *ws, size_t ws_bytes, void *stream) {
+extern "C" size_t lpdt_gossip_mix_workspace_bytes(int n, size_t d, int nseg, int choco) {
+    return mix_workspace(n, d, nseg, choco != 0, false);
+}
+extern "C" size_t lpdt_gossip_mix_ex_workspace_bytes(int n, size_t d, int nseg, int mode, int push_sum) {
+    return mix_workspace(n, d, nseg, mode != LPDT_MIX_PLAIN, push_sum != 0);
+}
+
+// mode: LPDT_MIX_*; state: xhat (CHOCO) / delta (Deep-Squeeze); u, z: push-sum weights and de-biased models or NULL
+static int mix_impl(float *x, float *state, int n, size_t d, const float *W, float rate, double keep_ratio,
+                    const int64_t *seg_offsets, int nseg, int mode, float *u, float *z, void *ws, size_t ws_bytes, void *stream) {
     LPDT_REQUIRE(x && W, LPDT_EINVAL, "gossip_mix: x and W must be non-NULL");
     LPDT_REQUIRE(n > 0 && d > 0, LPDT_EINVAL, "gossip_mix: n and d must be positive");
     LPDT_REQUIRE(n <= kMaxAgents, LPDT_EUNSUPPORTED, "gossip_mix: at most %d agents", kMaxAgents);
     LPDT_REQUIRE(std::isfinite(rate), LPDT_EINVAL, "gossip_mix: rate must be finite");
     LPDT_REQUIRE((d + kGThreads - 1) / kGThreads <= 0x7fffffffull, LPDT_EUNSUPPORTED, "gossip_mix: d too large");
+    LPDT_REQUIRE(mode == LPDT_MIX_PLAIN || mode == LPDT_MIX_CHOCO || mode == LPDT_MIX_DEEPSQUEEZE, LPDT_EINVAL,
+                 "gossip_mix: unknown mode %d", mode);
+    LPDT_REQUIRE((mode == LPDT_MIX_PLAIN) == (state == nullptr), LPDT_EINVAL,
+                 "gossip_mix: a compressed mode needs its state matrix (xhat / delta), the plain mix takes none");
+    LPDT_REQUIRE(!z || u, LPDT_EINVAL, "gossip_mix: z (de-biased models) needs the push-sum weights u");
+    const bool push = u != nullptr, ds = mode == LPDT_MIX_DEEPSQUEEZE;
     MixGraph g;
     std::memset(&g, 0, sizeof(g));
-    int rc = build_graph(W, n, &g);
+    int rc = build_graph(W, n, &g, push);
     if (rc) return rc;
     hipStream_t st = as_stream(stream);
     const unsigned int col_blocks = (unsigned int)((d + kGThreads - 1) / kGThreads);
-
     MixGraph4 g4;
     const bool fixed4 = compact_graph(g, n, &g4);
-    if (!xhat) {
+
+    std::vector<long long> off, kk;
+    bool select_all = true;
+    if (state) {
+        LPDT_REQUIRE(keep_ratio > 0.0 && std::isfinite(keep_ratio), LPDT_EINVAL, "gossip_mix: keep_ratio must be positive");
+        if (!seg_offsets || nseg <= 0) {
+            nseg = 1;
+            off = {0, (long long)d};
+        } else {
+            off.assign(seg_offsets, seg_offsets + nseg + 1);
+            LPDT_REQUIRE(off[0] == 0 && off[nseg] == (long long)d, LPDT_EINVAL,
+                         "gossip_mix: seg_offsets must start at 0 and end at d");
+        }
+        for (int s = 0; s < nseg; ++s) {
+            const long long len = off[s + 1] - off[s];
+            LPDT_REQUIRE(len >= 0, LPDT_EINVAL, "gossip_mix: seg_offsets must be non-decreasing");
+            LPDT_REQUIRE(len < 0x7fffffffLL, LPDT_EUNSUPPORTED, "gossip_mix: segment %d has 2^31-1 or more elements", s);
+            long long k = (long long)std::ceil(keep_ratio * (double)len);
+            if (k < 1) k = 1;
+            if (k > len) k = len;
+            if (k < len) select_all = false;
+            kk.push_back(k);
+        }
+    }
+    rc = check_ws(ws, ws_bytes, mix_workspace(n, d, nseg, state != nullptr, push));
+    if (rc) return rc;
+    char *base = static_cast<char *>(ws);
+    float *unew = nullptr;
+    if (push) {  // the last 256 bytes of the workspace
+        unew = reinterpret_cast<float *>(base + mix_workspace(n, d, nseg, state != nullptr, false));
+        if (fixed4) hipLaunchKernelGGL(pushsum_weights_kernel<MixGraph4>, dim3(1), dim3(64), 0, st, u, n, g4, rate, unew);
+        else hipLaunchKernelGGL(pushsum_weights_kernel<MixGraph>, dim3(1), dim3(64), 0, st, u, n, g, rate, unew);
+    }
+
+    if (!state) {
         dispatch_nmax(n, [&](auto tag) {
             constexpr int NMAX = decltype(tag)::value;
             if (NMAX <= 16 && fixed4)
                 hipLaunchKernelGGL((mix_plain_kernel<(NMAX <= 16 ? NMAX : 16), MixGraph4>), dim3(col_blocks), dim3(kGThreads), 0, st, x, n,
-                                   d, g4, rate);
+                                   d, g4, rate, unew, z);
             else
-                hipLaunchKernelGGL((mix_plain_kernel<NMAX, MixGraph>), dim3(col_blocks), dim3(kGThreads), 0, st, x, n, d, g, rate);
+                hipLaunchKernelGGL((mix_plain_kernel<NMAX, MixGraph>), dim3(col_blocks), dim3(kGThreads), 0, st, x, n, d, g, rate, unew, z);
         });
-        return launch_status("lpdt_gossip_mix");
-    }
-
-    LPDT_REQUIRE(keep_ratio > 0.0 && std::isfinite(keep_ratio), LPDT_EINVAL, "gossip_mix: keep_ratio must be positive");
-    std::vector<long long> off, kk;
-    if (!seg_offsets || nseg <= 0) {
-        nseg = 1;
-        off = {0, (long long)d};
     } else {
-        off.assign(seg_offsets, seg_offsets + nseg + 1);
-        LPDT_REQUIRE(off[0] == 0 && off[nseg] == (long long)d, LPDT_EINVAL,
-                     "gossip_mix: seg_offsets must start at 0 and end at d");
+        const ChocoLayout L = choco_layout(n, d, nseg);
+        long long *d_off = reinterpret_cast<long long *>(base);
+        long long *d_k = reinterpret_cast<long long *>(base + L.off_bytes);
+        PairState *d_st = reinterpret_cast<PairState *>(base + L.off_bytes + L.k_bytes);
+        unsigned int *d_hist = reinterpret_cast<unsigned int *>(base + L.off_bytes + L.k_bytes + L.state_bytes);
+        unsigned long long *d_cand =
+            reinterpret_cast<unsigned long long *>(base + L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes);
+        float *xhat = state;
+        const int dsi = ds ? 1 : 0;
+        upload(off.data(), nseg + 1, d_off, st);
+        if (!select_all) {
+            upload(kk.data(), nseg, d_k, st);
+            const size_t hist_words = (size_t)n * nseg * kBins;
+            hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
+                               nseg, d_hist, hist_words);
+            const dim3 tiles((unsigned int)((d + kTile - 1) / kTile), n);
+            const bool vec4 = d % 4 == 0 && aligned(x, 16) && aligned(xhat, 16);
+            if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi);
+            else hipLaunchKernelGGL(choco_hist_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi);
+            hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12);
+            if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi);
+            else hipLaunchKernelGGL(choco_collect_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi);
+            hipLaunchKernelGGL(choco_refine_kernel, dim3(n * nseg), dim3(kRefThreads), 0, st, d_cand, d, d_off, nseg, d_st);
+        }
+        const bool vec2 = n <= 16 && d % 2 == 0 && aligned(x, 8) && aligned(xhat, 8) && (!z || aligned(z, 8));
+        dispatch_nmax(n, [&](auto tag) {
+            constexpr int NMAX = decltype(tag)::value;
+            constexpr int N16 = NMAX <= 16 ? NMAX : 16;
+            const dim3 grid2((unsigned)((d / 2 + kGThreads - 1) / kGThreads));
+            if (NMAX <= 16 && vec2 && fixed4)
+                hipLaunchKernelGGL((choco_apply_mix_kernel<N16, 2, MixGraph4>), grid2, dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st,
+                                   select_all ? 1 : 0, g4, rate, dsi, unew, z);
+            else if (NMAX <= 16 && vec2)
+                hipLaunchKernelGGL((choco_apply_mix_kernel<N16, 2, MixGraph>), grid2, dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st,
+                                   select_all ? 1 : 0, g, rate, dsi, unew, z);
+            else
+                hipLaunchKernelGGL((choco_apply_mix_kernel<NMAX, 1, MixGraph>), dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off,
+                                   nseg, d_st, select_all ? 1 : 0, g, rate, dsi, unew, z);
+        });
     }
-    bool select_all = true;
-    for (int s = 0; s < nseg; ++s) {
-        const long long len = off[s + 1] - off[s];
-        LPDT_REQUIRE(len >= 0, LPDT_EINVAL, "gossip_mix: seg_offsets must be non-decreasing");
-        LPDT_REQUIRE(len < 0x7fffffffLL, LPDT_EUNSUPPORTED, "gossip_mix: segment %d has 2^31-1 or more elements", s);
-        long long k = (long long)std::ceil(keep_ratio * (double)len);
-        if (k < 1) k = 1;
-        if (k > len) k = len;
-        if (k < len) select_all = false;
-        kk.push_back(k);
-    }
-    const ChocoLayout L = choco_layout(n, d, nseg);
-    rc = check_ws(ws, ws_bytes, L.total);
-    if (rc) return rc;
-    char *base = static_cast<char *>(ws);
-    long long *d_off = reinterpret_cast<long long *>(base);
-    long long *d_k = reinterpret_cast<long long *>(base + L.off_bytes);
-    PairState *d_st = reinterpret_cast<PairState *>(base + L.off_bytes + L.k_bytes);
-    unsigned int *d_hist = reinterpret_cast<unsigned int *>(base + L.off_bytes + L.k_bytes + L.state_bytes);
-    unsigned long long *d_cand =
-        reinterpret_cast<unsigned long long *>(base + L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes);
-
-    upload(off.data(), nseg + 1, d_off, st);
-    if (!select_all) {
-        upload(kk.data(), nseg, d_k, st);
-        const size_t hist_words = (size_t)n * nseg * kBins;
-        hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
-                           nseg, d_hist, hist_words);
-        const dim3 tiles((unsigned int)((d + kTile - 1) / kTile), n);
-        const bool vec4 = d % 4 == 0 && aligned(x, 16) && aligned(xhat, 16);
-        if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
-        else hipLaunchKernelGGL(choco_hist_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist);
-        hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12);
-        if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
-        else hipLaunchKernelGGL(choco_collect_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand);
-        hipLaunchKernelGGL(choco_refine_kernel, dim3(n * nseg), dim3(kRefThreads), 0, st, d_cand, d, d_off, nseg, d_st);
-    }
-    const bool vec2 = n <= 16 && d % 2 == 0 && aligned(x, 8) && aligned(xhat, 8);
-    dispatch_nmax(n, [&](auto tag) {
-        constexpr int NMAX = decltype(tag)::value;
-        constexpr int N16 = NMAX <= 16 ? NMAX : 16;
-        const dim3 grid2((unsigned)((d / 2 + kGThreads - 1) / kGThreads));
-        if (NMAX <= 16 && vec2 && fixed4)
-            hipLaunchKernelGGL((choco_apply_mix_kernel<N16, 2, MixGraph4>), grid2, dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st,
-                               select_all ? 1 : 0, g4, rate);
-        else if (NMAX <= 16 && vec2)
-            hipLaunchKernelGGL((choco_apply_mix_kernel<N16, 2, MixGraph>), grid2, dim3(kGThreads), 0, st, x, xhat, n, d, d_off, nseg, d_st,
-                               select_all ? 1 : 0, g, rate);
-        else
-            hipLaunchKernelGGL((choco_apply_mix_kernel<NMAX, 1, MixGraph>), dim3(col_blocks), dim3(kGThreads), 0, st, x, xhat, n, d, d_off,
-                               nseg, d_st, select_all ? 1 : 0, g, rate);
-    });
+    if (push) hipLaunchKernelGGL(copy_small_kernel, dim3(1), dim3(64), 0, st, unew, u, n);
     return launch_status("lpdt_gossip_mix");
+}
+
+extern "C" int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const float *W, float rate, double keep_ratio,
+                               const int64_t *seg_offsets, int nseg, void *ws, size_t ws_bytes, void *stream) {
+    return mix_impl(x, xhat, n, d, W, rate, keep_ratio, seg_offsets, nseg, xhat ? LPDT_MIX_CHOCO : LPDT_MIX_PLAIN, nullptr, nullptr,
+                    ws, ws_bytes, stream);
+}
+
+extern "C" int lpdt_gossip_mix_ex(float *x, float *state, int n, size_t d, const float *W, float rate, double keep_ratio,
+                                  const int64_t *seg_offsets, int nseg, int mode, float *u, float *z, void *ws, size_t ws_bytes,
+                                  void *stream) {
+    return mix_impl(x, state, n, d, W, rate, keep_ratio, seg_offsets, nseg, mode, u, z, ws, ws_bytes, stream);
 }

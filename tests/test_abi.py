@@ -131,6 +131,30 @@ def test_gossip_argument_errors(L):
     assert L.lpdt_gossip_mix_workspace_bytes(8, sz(1000), 1, 0) == 0
 
 
+def test_gossip_ex_argument_errors(L):
+    import numpy as np
+    import workloads as wl
+    f, dbl = ctypes.c_float, ctypes.c_double
+
+    def call(Wm, n, state=None, mode=0, u=None, z=None, ws=None, wsb=0, d=1000):
+        Wc = (ctypes.c_float * (n * n))(*np.asarray(Wm, np.float32).ravel().tolist())
+        return L.lpdt_gossip_mix_ex(FAKE, state, n, sz(d), Wc, f(1.0), dbl(0.1), None, 0, mode, u, z, ws, sz(wsb), None)
+
+    ring, dirg = wl.ring_matrix(8), wl.directed_matrix(8)
+    assert call(ring, 8, mode=7) == -1 and "mode" in _err(L)
+    assert call(ring, 8, state=None, mode=2) == -1 and "state" in _err(L)          # Deep-Squeeze without its error memory
+    assert call(ring, 8, state=FAKE, mode=0) == -1                                 # plain mix takes no state
+    assert call(ring, 8, z=FAKE) == -1 and "push-sum" in _err(L)                   # z without u
+    assert call(dirg, 8) == -1 and "row" in _err(L)                                # directed graph needs push-sum weights
+    assert call(dirg, 8, u=FAKE) == -3                                             # accepted with u; then the workspace is missing
+    bad = dirg.copy(); bad[0, 0] += 0.2
+    assert call(bad, 8, u=FAKE) == -1 and "column" in _err(L)
+    need = L.lpdt_gossip_mix_ex_workspace_bytes(8, sz(1000), 1, 2, 1)
+    assert need > L.lpdt_gossip_mix_ex_workspace_bytes(8, sz(1000), 1, 2, 0) > 0
+    assert L.lpdt_gossip_mix_ex_workspace_bytes(8, sz(1000), 1, 0, 0) == 0
+    assert call(ring, 8, state=FAKE, mode=2, ws=FAKE, wsb=16) == -3
+
+
 def test_glue_argument_errors(L):
     assert L.lpdt_add(None, FAKE, sz(4), FAKE, None) == -1
     assert L.lpdt_sgd(FAKE, FAKE, sz(0), ctypes.c_float(0.1), None) == -2
