@@ -112,7 +112,18 @@ def build_workload(cfg_id, device):
             gen.manual_seed(seed + 1)
             Xhat += 1e-3 * torch.randn((n_agents, d), generator=gen, device=device)
             seg = net.param_offsets()
-            mix = lambda: lpdt.gossip_mix(X, Xhat, Wm, rate=0.1, keep_ratio=0.01, seg_offsets=seg, ws=ws)
+            variant = cfg.get("variant", "choco")
+            if variant == "choco":
+                mix = lambda: lpdt.gossip_mix(X, Xhat, Wm, rate=0.1, keep_ratio=0.01, seg_offsets=seg, ws=ws)
+            else:   # the supplement's other algorithms on the same matrices; push-sum runs on a directed graph
+                push = variant in ("sparse_push", "quant_sgp")
+                mode = lpdt.MIX_CHOCO if variant == "quant_sgp" else lpdt.MIX_DEEPSQUEEZE
+                if mode == lpdt.MIX_DEEPSQUEEZE:
+                    Xhat.sub_(X).mul_(0.05)                     # an error memory: small next to the model
+                Wv = wl.directed_matrix(n_agents) if push else Wm
+                U = torch.ones(n_agents, device=device) if push else None
+                Z = torch.empty_like(X) if push else None
+                mix = lambda: lpdt.gossip_mix_ex(X, Xhat, Wv, rate=0.1, keep_ratio=0.01, seg_offsets=seg, mode=mode, u=U, z=Z, ws=ws)
             mix()                                               # sizes the workspace outside the timed region
     return cfg, net, steps, mix, X
 
@@ -160,6 +171,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=sorted(CONFIGS))
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph (launch-bound configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mix-variant", default="choco", choices=["choco", "deepsqueeze", "sparse_push", "quant_sgp"],
+                    help="gossip algorithm of the compressed configuration (config 5); the headline is choco")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (agents are simulated on one device); "
@@ -173,6 +186,8 @@ def main():
     import paper_2111_09389_amd as lpdt
     lpdt.lib()
     device = torch.device("cuda:0")
+    if CONFIGS[args.config]["mix"] == "choco":
+        CONFIGS[args.config] = dict(CONFIGS[args.config], variant=args.mix_variant)
     cfg, net, steps, mix, X = build_workload(args.config, device)
 
     def one_step(i):
@@ -253,7 +268,12 @@ def main():
     }
     if mix_ms:
         d, n = net.num_params(), cfg["agents"]
-        per_param = 28 if cfg["mix"] == "choco" else 8
+        # bytes per parameter and agent: threshold scan 8 + candidate scan 8 + apply (x and state read, x written: 12;
+        # Deep-Squeeze rewrites its whole error memory: +4; push-sum writes the de-biased models: +4)
+        per_param = {"choco": 28, "quant_sgp": 32, "deepsqueeze": 32, "sparse_push": 36}[cfg.get("variant", "choco")] \
+            if cfg["mix"] == "choco" else 8
+        out["gossip_mix_variant"] = cfg.get("variant", "plain")
+        out["gossip_mix_bytes_per_param"] = per_param
         out["gossip_mix_gbs"] = per_param * n * d / (mix_ms * 1e-3) / 1e9
         out["gossip_mix_frac_of_hbm_peak"] = out["gossip_mix_gbs"] / HBM_PEAK_GBS
     if not args.no_cpu_baseline:
