@@ -397,19 +397,34 @@ extern "C" int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq
 // Weight gradient.  Which kernel runs: first-layer path, rectangle-stepped kernel (partial tiles + reduction), the
 // flattened-pixel kernel (1x1 spatial maps, large halos) or the plain kernel.  Only the rectangle kernel can apply
 // the dequantizing scale itself; the others stage int32 sums in the workspace for the _f32 entry point.
+// A pointwise product (1x1 filter, stride 1, no padding: linear layers, transformer-shaped GEMMs) does not care which
+// image a pixel belongs to: seen as ONE image of 1 x (N*H*W) pixels it fills the rectangle-stepped kernel's 32-pixel steps
+// whatever the real spatial size (a linear layer has H = W = 1).
+static lpdt_conv_desc wgrad_view(const lpdt_conv_desc *d, int *P, int *Q) {
+    lpdt_conv_desc v = *d;
+    const long long pix = (long long)d->N * d->H * d->W;
+    if (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 && d->pad_w == 0 && pix <= 0x7fffffffLL) {
+        v.N = 1; v.H = 1; v.W = (int)pix;
+        *P = 1; *Q = (int)pix;
+    }
+    return v;
+}
+
 static bool wgrad_uses_rect(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     return !narrow_conv_supported(d, P, Q) && wgrad_rect_plan(d, P, Q, pl);
 }
 
-static size_t bwd_weight_base_ws(const lpdt_conv_desc *d, int P, int Q) {
+static size_t bwd_weight_base_ws(const lpdt_conv_desc *d0, int P, int Q) {
+    const lpdt_conv_desc view = wgrad_view(d0, &P, &Q), *d = &view;
     WgradRectPlan pl;
     if (narrow_conv_supported(d, P, Q)) return round_up(narrow_wgrad_workspace(d), 256);
     if (wgrad_rect_plan(d, P, Q, &pl)) return pl.partial_bytes;
     return 0;
 }
 
-static void conv_bwd_weight_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *xq, void *out, int out_mode,
+static void conv_bwd_weight_impl(const lpdt_conv_desc *d0, int P, int Q, const int8_t *gq, const int8_t *xq, void *out, int out_mode,
                                  const float *sA, const float *sB, void *ws, hipStream_t st) {
+    const lpdt_conv_desc view = wgrad_view(d0, &P, &Q), *d = &view;
     const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
     const long long M = (long long)d->N * P * Q;
     WgradRectPlan pl;

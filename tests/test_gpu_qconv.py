@@ -25,6 +25,8 @@ CASES = [
     (2, 16, 12, 12, 32, 7, 7, 2, 3),      # 49 taps with channel-multiple-of-16
     (1, 20, 6, 6, 24, 3, 3, 1, 1),        # channel counts that are not multiples of 16
     (1, 256, 4, 4, 512, 3, 3, 1, 1),
+    (257, 768, 1, 1, 768, 1, 1, 1, 0),    # transformer-shaped linear layers (tokens x 768 -> 768 / 3072 -> 768), ragged token count
+    (130, 3072, 1, 1, 768, 1, 1, 1, 0),
 ]
 
 
