@@ -62,6 +62,9 @@ CONFIGS = {
     4: dict(name="VGG-11 (REN g=32), batch 256, 32x32x3", net="vgg11", batch=256, agents=1, mix=None),
     5: dict(name="ResNet-18 (REN g=32), batch 64, 224x224x3, 100 classes + CHOCO gossip over 16 ring agents, "
                  "layer-wise top-1%", net="resnet18", batch=64, agents=16, mix="choco"),
+    # beyond the baseline's list: quantized linear layers at transformer shapes through the same int8 kernels
+    6: dict(name="DistilBERT-shaped linear layers (768 -> 3072 -> 768 -> 768), 16384 tokens",
+            net="transformer_ffn", batch=16384, agents=1, mix=None),
 }
 
 

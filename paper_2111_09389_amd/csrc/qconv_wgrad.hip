@@ -19,7 +19,9 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kRow = 96;        // LDS bytes per pixel: 64 channels + 32 pad (8 rows tile the 64 banks)
+// LDS bytes per pixel = channels of the wider tile + 32 bytes of padding: with 96 or 160 bytes the 8 pixel rows one
+// transposing read touches fall on 8 different groups of banks.
+static constexpr int lds_row_bytes(int kt, int ct) { return (kt > ct ? kt : ct) <= 64 ? 96 : 160; }
 constexpr int kItems = 4;       // 16-byte items per thread and step (256 threads: up to 1024 items)
 
 struct WgradRectParams {
@@ -45,14 +47,18 @@ __device__ __forceinline__ void static_for(F f) {
 
 constexpr unsigned kBeyond = 0x80000000u;  // a buffer offset no tensor reaches: such loads return zeros
 
-// KT x CT = the block's (output x input channel) tile, 32 or 64 each.  The 4 waves cover its 32 x 32 sub-tiles and, when
-// there are fewer than 4 of those, share out the taps: wave (ti, tj, tw) accumulates taps tw, tw + WT, ...
+// KT x CT = the block's (output x input channel) tile, 32, 64 or 128 each.  The 4 waves cover its 32 x 32 sub-tiles: with
+// fewer than 4 of those they share out the taps (wave (ti, tj, tw) accumulates taps tw, tw + WT, ...), with 16 of them
+// (128 x 128, single-tap filters only: GEMM-shaped linear layers) each wave owns SK x SC = 2 x 2 sub-tiles.
 // PF = steps whose loads are in flight (in registers) ahead of the step being multiplied; the loop runs in rounds of PF
 // steps without conditions, steps past the block's share load zeros.
 template <int KT, int CT, int TG, int PF>
 __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParams p) {
-    constexpr int WK = KT / 32, WC = CT / 32, WT = 4 / (WK * WC);
-    constexpr int NA = (TG + WT - 1) / WT;       // accumulators (taps) per wave
+    constexpr int WK = KT / 32 > 2 ? 2 : KT / 32, WC = CT / 32 > 2 ? 2 : CT / 32, WT = 4 / (WK * WC);
+    constexpr int SK = KT / 32 / WK, SC = CT / 32 / WC;   // sub-tiles per wave
+    static_assert(SK * SC == 1 || TG == 1, "several sub-tiles per wave only for single-tap filters");
+    constexpr int NA = SK * SC > 1 ? SK * SC : (TG + WT - 1) / WT;   // accumulators per wave: sub-tiles or taps
+    constexpr int kRow = lds_row_bytes(KT, CT);
     constexpr int GK = KT / 16, GC = CT / 16;    // 16-byte granules per pixel of the two tiles
     static_assert(32 * GK % 64 == 0, "an item index is gradient or patch for a whole wave");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -142,10 +148,10 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int slot = 16 * (blk / 2) + 8 * h + j16 / 2;
-        a_off[h] = slot * kRow + 32 * ti + src_ch;
+        a_off[h] = slot * kRow + 32 * ti * SK + src_ch;
         const int pr = slot / p.cw, pc = slot - pr * p.cw;
         const int pix = pr < p.ch ? (pr * p.stride) * p.PWp + pc * p.stride : 0;  // empty slots meet zero gradient rows
-        b_off[h] = (32 + pix) * kRow + 32 * tj + src_ch;
+        b_off[h] = (32 + pix) * kRow + 32 * tj * SC + src_ch;
     }
     int tapoff[NA];
 #pragma unroll
@@ -165,16 +171,37 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
             constexpr int buf = U & 1;
             load_items(u);  // register slot U went to LDS before this step: refill it with the step PF ahead
             unsigned char *base = lds + buf * buf_bytes;
-            const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0]));
-            const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1]));
-            const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+            if constexpr (SK * SC > 1) {
+                v4i a[SK], b[SC];
 #pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                if (tw + WT * i < TG && tap0 + tw + WT * i < ntaps) {
-                    const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + tapoff[i]));
-                    const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + tapoff[i]));
-                    const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
-                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+                for (int sk = 0; sk < SK; ++sk) {
+                    const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0] + 32 * sk));
+                    const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1] + 32 * sk));
+                    a[sk] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                }
+#pragma unroll
+                for (int sc = 0; sc < SC; ++sc) {
+                    const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + 32 * sc));
+                    const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + 32 * sc));
+                    b[sc] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                }
+#pragma unroll
+                for (int sk = 0; sk < SK; ++sk)
+#pragma unroll
+                    for (int sc = 0; sc < SC; ++sc)
+                        acc[sk * SC + sc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[sk], b[sc], acc[sk * SC + sc], 0, 0, 0);
+            } else {
+                const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0]));
+                const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1]));
+                const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    if (tw + WT * i < TG && tap0 + tw + WT * i < ntaps) {
+                        const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + tapoff[i]));
+                        const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + tapoff[i]));
+                        const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+                        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+                    }
                 }
             }
             store_items(std::integral_constant<int, (U + 1) % PF>(), buf ^ 1);
@@ -183,15 +210,31 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
     }
 
     int32_t *out = p.partial + (size_t)blockIdx.z * p.out_len;
-    const int c = c0 + 32 * tj + lane % 32;
+    if constexpr (SK * SC > 1) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int tap = tap0 + tw + WT * i;
-        if (tw + WT * i < TG && tap < ntaps && c < p.C) {
+        for (int sk = 0; sk < SK; ++sk)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int k = k0 + 32 * ti + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-                if (k < p.K) out[((size_t)k * ntaps + tap) * p.C + c] = acc[i][r];
+            for (int sc = 0; sc < SC; ++sc) {
+                const int c = c0 + 32 * (tj * SC + sc) + lane % 32;
+                if (tap0 < ntaps && c < p.C) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int k = k0 + 32 * (ti * SK + sk) + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+                        if (k < p.K) out[((size_t)k * ntaps + tap0) * p.C + c] = acc[sk * SC + sc][r];
+                    }
+                }
+            }
+    } else {
+        const int c = c0 + 32 * tj + lane % 32;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int tap = tap0 + tw + WT * i;
+            if (tw + WT * i < TG && tap < ntaps && c < p.C) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int k = k0 + 32 * ti + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+                    if (k < p.K) out[((size_t)k * ntaps + tap) * p.C + c] = acc[i][r];
+                }
             }
         }
     }
@@ -241,7 +284,6 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     pl->ncy = (P + pl->ch - 1) / pl->ch;
     pl->PHp = (pl->ch - 1) * st + d->R;
     pl->PWp = (pl->cw - 1) * st + d->S;
-    if (pl->PHp * pl->PWp * 4 + 128 > kItems * 256) return false;
     const long long steps = (long long)d->N * pl->ncy * pl->ncx;
     if (steps > 0x7fffffffLL || steps * 32 * 6 / 10 > (long long)d->N * P * Q) return false;  // < 60% of the slots used
     pl->steps = (int)steps;
@@ -253,6 +295,9 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     // (the waves share out the 9 taps), 64 x 64 for 1x1 filters.
     pl->kt = ntaps == 1 ? 64 : 32;
     pl->ct = 64;
+    // GEMM-shaped single-tap products (both channel counts large): 128 x 128 tiles, 4x the MFMAs per staged byte
+    if (ntaps == 1 && d->K >= 256 && d->C >= 256 && (long long)((d->K + 127) / 128) * ((d->C + 127) / 128) >= 32) pl->kt = pl->ct = 128;
+    if (pl->PHp * pl->PWp * (pl->ct / 16) + 32 * (pl->kt / 16) > kItems * 256) return false;
     pl->tiles_k = (d->K + pl->kt - 1) / pl->kt;
     pl->tiles_c = (d->C + pl->ct - 1) / pl->ct;
     const long long base = (long long)pl->tiles_k * pl->tiles_c * pl->groups;
@@ -263,7 +308,7 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     pl->splits = (int)((steps + pl->steps_per_split - 1) / pl->steps_per_split);
     pl->out_len = (long long)d->K * ntaps * d->C;
     pl->partial_bytes = round_up((size_t)pl->splits * pl->out_len * sizeof(int32_t), 256);
-    pl->lds = 2 * (size_t)(32 + pl->PHp * pl->PWp) * kRow;
+    pl->lds = 2 * (size_t)(32 + pl->PHp * pl->PWp) * lds_row_bytes(pl->kt, pl->ct);
     return pl->lds <= 64 * 1024;
 }
 
@@ -278,7 +323,9 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
     p.steps = pl.steps; p.steps_per_split = pl.steps_per_split; p.tiles_k = pl.tiles_k; p.out_len = pl.out_len;
     const dim3 grid((unsigned)(pl.tiles_k * pl.tiles_c), (unsigned)pl.groups, (unsigned)pl.splits);
     auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(256), pl.lds, st, p); };
-    if (pl.kt == 64 && pl.ct == 64) {
+    if (pl.kt == 128) {
+        go(wgrad_rect_kernel<128, 128, 1, 4>);
+    } else if (pl.kt == 64 && pl.ct == 64) {
         if (pl.tg == 1) go(wgrad_rect_kernel<64, 64, 1, 4>);
         else go(wgrad_rect_kernel<64, 64, 9, 2>);  // 9 accumulators: no registers for a deeper read-ahead
     } else {

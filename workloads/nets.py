@@ -111,6 +111,17 @@ def single_layer():
     return n
 
 
+def transformer_ffn():
+    """Quantized linear layers at the shapes of a DistilBERT feed-forward block (hidden 768, inner 3072) plus a
+    768 -> 768 projection, as 1x1 convolutions over tokens (the batch axis holds the tokens; H = W = 1).  Only the
+    int8 products and their quantizers: no normalisation between the layers."""
+    n = Net("transformer-ffn", (1, 1, 768), 0)
+    n.conv("fc1", "x", 3072, 1, 1, 0)
+    n.conv("fc2", "fc1", 768, 1, 1, 0)
+    n.conv("proj", "fc2", 768, 1, 1, 0)
+    return n
+
+
 def _basic_block(n, name, inp, K, stride, groups):
     a = n.conv(f"{name}.c1", inp, K, 3, stride, 1)
     a = n.ren(f"{name}.n1", a, groups)
