@@ -1,7 +1,7 @@
 // Weight gradient of a convolution on int8 codes, rectangle-stepped variant:
 //   dw[k][r][s][c] = sum over output pixels (n, oy, ox) of g[n,oy,ox,k] * x[n, oy*st + r - pad, ox*st + s - pad, c]
 //
-// One K-step of the reduction is a small RECTANGLE of <= 32 output pixels of one image (ch rows x cw columns), so
+// One K-step of the reduction is a small RECTANGLE of <= 32 or 64 output pixels of one image (ch rows x cw columns), so
 // the input pixels all R*S taps need form one halo patch ((ch-1)*st+R) x ((cw-1)*st+S).  The block copies that patch
 // and the gradient tile into LDS once per step, in their natural [pixel][channel] order, and every tap's MFMA operand
 // is read from it with the transposing LDS load (ds_read_b64_tr_b8): a tap is a constant LDS offset.  Compared with
@@ -52,18 +52,20 @@ constexpr unsigned kBeyond = 0x80000000u;  // a buffer offset no tensor reaches:
 // (128 x 128, single-tap filters only: GEMM-shaped linear layers) each wave owns SK x SC = 2 x 2 sub-tiles.
 // PF = steps whose loads are in flight (in registers) ahead of the step being multiplied; the loop runs in rounds of PF
 // steps without conditions, steps past the block's share load zeros.
-template <int KT, int CT, int TG, int PF>
+// KS = 32-pixel groups per step: the rectangle has 32*KS slots, one barrier serves KS MFMAs per accumulator.
+template <int KT, int CT, int TG, int PF, int KS>
 __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParams p) {
+    constexpr int SLOTS = 32 * KS;
     constexpr int WK = KT / 32 > 2 ? 2 : KT / 32, WC = CT / 32 > 2 ? 2 : CT / 32, WT = 4 / (WK * WC);
     constexpr int SK = KT / 32 / WK, SC = CT / 32 / WC;   // sub-tiles per wave
     static_assert(SK * SC == 1 || TG == 1, "several sub-tiles per wave only for single-tap filters");
     constexpr int NA = SK * SC > 1 ? SK * SC : (TG + WT - 1) / WT;   // accumulators per wave: sub-tiles or taps
     constexpr int kRow = lds_row_bytes(KT, CT);
     constexpr int GK = KT / 16, GC = CT / 16;    // 16-byte granules per pixel of the two tiles
-    static_assert(32 * GK % 64 == 0, "an item index is gradient or patch for a whole wave");
+    static_assert(SLOTS * GK % 64 == 0, "an item index is gradient or patch for a whole wave");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int patch_px = p.PHp * p.PWp;
-    const int buf_bytes = (32 + patch_px) * kRow;
+    const int buf_bytes = (SLOTS + patch_px) * kRow;
 
     const int t = threadIdx.x, lane = t % 64, wave = t / 64;
     const int k0 = (blockIdx.x % p.tiles_k) * KT, c0 = (blockIdx.x / p.tiles_k) * CT;
@@ -72,8 +74,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
     const int step_end = min(p.steps, step_begin + p.steps_per_split);
     const int nsteps = (step_end - step_begin + PF - 1) / PF * PF;
 
-    // This thread's load items.  id < 32*GK: gradient (rectangle slot id/GK, granule id%GK); else patch pixel
-    // (id - 32*GK)/GC.  Per item: position (ia, ib) inside the rectangle / patch, the image limits its position is
+    // This thread's load items.  id < SLOTS*GK: gradient (rectangle slot id/GK, granule id%GK); else patch pixel
+    // (id - SLOTS*GK)/GC.  Per item: position (ia, ib) inside the rectangle / patch, the image limits its position is
     // tested against, and the byte offset relative to the step's corner.  Whether an item is gradient or patch is the
     // same for all lanes of a wave, so the choice of tensor is scalar.
     const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.g), 0, (int)p.g_bytes, 0x00020000);
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
         const int id = t + 256 * j;
-        is_g[j] = (wave * 64 + 256 * j) < 32 * GK;
+        is_g[j] = (wave * 64 + 256 * j) < SLOTS * GK;
         if (is_g[j]) {
             const int slot = id / GK, gran = (id % GK) * 16;
             ia[j] = slot / p.cw; ib[j] = slot % p.cw;
@@ -93,12 +95,12 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
             soff[j] = (ia[j] * p.Q + ib[j]) * p.K + k0 + gran;
             dst[j] = slot * kRow + gran;
         } else {
-            const int pp = (id - 32 * GK) / GC, gran = ((id - 32 * GK) % GC) * 16;
+            const int pp = (id - SLOTS * GK) / GC, gran = ((id - SLOTS * GK) % GC) * 16;
             ia[j] = pp / p.PWp; ib[j] = pp % p.PWp;
             const bool ok = pp < patch_px && c0 + gran < p.C;
             lim_y[j] = ok ? (unsigned)p.H : 0u; lim_x[j] = (unsigned)p.W;
             soff[j] = (ia[j] * p.W + ib[j]) * p.C + c0 + gran;
-            dst[j] = ok ? (32 + pp) * kRow + gran : -1;
+            dst[j] = ok ? (SLOTS + pp) * kRow + gran : -1;
         }
     }
 
@@ -144,15 +146,17 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
     const int ti = wave % WK, tj = (wave / WK) % WC, tw = wave / (WK * WC);
     const int blk = lane / 16, j16 = lane % 16;
     const int src_ch = 16 * (blk % 2) + 8 * (j16 % 2);
-    int a_off[2], b_off[2];
+    int a_off[KS][2], b_off[KS][2];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int slot = 16 * (blk / 2) + 8 * h + j16 / 2;
-        a_off[h] = slot * kRow + 32 * ti * SK + src_ch;
-        const int pr = slot / p.cw, pc = slot - pr * p.cw;
-        const int pix = pr < p.ch ? (pr * p.stride) * p.PWp + pc * p.stride : 0;  // empty slots meet zero gradient rows
-        b_off[h] = (32 + pix) * kRow + 32 * tj * SC + src_ch;
-    }
+    for (int g32 = 0; g32 < KS; ++g32)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int slot = 32 * g32 + 16 * (blk / 2) + 8 * h + j16 / 2;
+            a_off[g32][h] = slot * kRow + 32 * ti * SK + src_ch;
+            const int pr = slot / p.cw, pc = slot - pr * p.cw;
+            const int pix = pr < p.ch ? (pr * p.stride) * p.PWp + pc * p.stride : 0;  // empty slots meet zero gradient rows
+            b_off[g32][h] = (SLOTS + pix) * kRow + 32 * tj * SC + src_ch;
+        }
     int tapoff[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
@@ -171,36 +175,39 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
             constexpr int buf = U & 1;
             load_items(u);  // register slot U went to LDS before this step: refill it with the step PF ahead
             unsigned char *base = lds + buf * buf_bytes;
-            if constexpr (SK * SC > 1) {
-                v4i a[SK], b[SC];
 #pragma unroll
-                for (int sk = 0; sk < SK; ++sk) {
-                    const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0] + 32 * sk));
-                    const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1] + 32 * sk));
-                    a[sk] = v4i{lo[0], lo[1], hi[0], hi[1]};
-                }
+            for (int g32 = 0; g32 < KS; ++g32) {
+                if constexpr (SK * SC > 1) {
+                    v4i a[SK], b[SC];
 #pragma unroll
-                for (int sc = 0; sc < SC; ++sc) {
-                    const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + 32 * sc));
-                    const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + 32 * sc));
-                    b[sc] = v4i{lo[0], lo[1], hi[0], hi[1]};
-                }
+                    for (int sk = 0; sk < SK; ++sk) {
+                        const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[g32][0] + 32 * sk));
+                        const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[g32][1] + 32 * sk));
+                        a[sk] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                    }
 #pragma unroll
-                for (int sk = 0; sk < SK; ++sk)
+                    for (int sc = 0; sc < SC; ++sc) {
+                        const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[g32][0] + 32 * sc));
+                        const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[g32][1] + 32 * sc));
+                        b[sc] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                    }
 #pragma unroll
-                    for (int sc = 0; sc < SC; ++sc)
-                        acc[sk * SC + sc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[sk], b[sc], acc[sk * SC + sc], 0, 0, 0);
-            } else {
-                const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[0]));
-                const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[1]));
-                const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+                    for (int sk = 0; sk < SK; ++sk)
 #pragma unroll
-                for (int i = 0; i < NA; ++i) {
-                    if (tw + WT * i < TG && tap0 + tw + WT * i < ntaps) {
-                        const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[0] + tapoff[i]));
-                        const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[1] + tapoff[i]));
-                        const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
-                        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+                        for (int sc = 0; sc < SC; ++sc)
+                            acc[sk * SC + sc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[sk], b[sc], acc[sk * SC + sc], 0, 0, 0);
+                } else {
+                    const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[g32][0]));
+                    const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off[g32][1]));
+                    const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+#pragma unroll
+                    for (int i = 0; i < NA; ++i) {
+                        if (tw + WT * i < TG && tap0 + tw + WT * i < ntaps) {
+                            const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[g32][0] + tapoff[i]));
+                            const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off[g32][1] + tapoff[i]));
+                            const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+                            acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -270,14 +277,25 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const int32_t *__rest
     }
 }
 
+static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradRectPlan *pl);
+
 bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
+    // 64-pixel steps (two MFMA k-groups per barrier) for multi-tap filters on maps that can fill them, when the halo
+    // patch of such a step still fits the per-step load budget (stride-2 patches are four times larger); else 32.
+    if (d->R * d->S > 1 && P * Q >= 64 && rect_plan_with(d, P, Q, 2, pl)) return true;
+    return rect_plan_with(d, P, Q, 1, pl);
+}
+
+static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradRectPlan *pl) {
     if (d->K % 16 || d->C % 16 || d->stride_h != d->stride_w || d->pad_h != d->pad_w) return false;
     const size_t lim = ((size_t)1 << 31) - 4096;  // 32-bit buffer offsets
     if ((size_t)d->N * P * Q * d->K >= lim || (size_t)d->N * d->H * d->W * d->C >= lim) return false;
     if (P * Q < 16) return false;  // tiny maps: rectangles cannot be filled from one image
     const int st = d->stride_h;
+    const int ntaps = d->R * d->S;
+    pl->ks = ks;
     pl->cw = Q >= 32 ? 32 : Q;
-    pl->ch = 32 / pl->cw;
+    pl->ch = 32 * pl->ks / pl->cw;
     if (pl->ch > P) pl->ch = P;
     if (pl->ch < 1) pl->ch = 1;
     pl->ncx = (Q + pl->cw - 1) / pl->cw;
@@ -285,9 +303,8 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     pl->PHp = (pl->ch - 1) * st + d->R;
     pl->PWp = (pl->cw - 1) * st + d->S;
     const long long steps = (long long)d->N * pl->ncy * pl->ncx;
-    if (steps > 0x7fffffffLL || steps * 32 * 6 / 10 > (long long)d->N * P * Q) return false;  // < 60% of the slots used
+    if (steps > 0x7fffffffLL || steps * 32 * pl->ks * 6 / 10 > (long long)d->N * P * Q) return false;  // < 60% of the slots used
     pl->steps = (int)steps;
-    const int ntaps = d->R * d->S;
     pl->tg = ntaps == 1 ? 1 : 9;
     pl->groups = (ntaps + pl->tg - 1) / pl->tg;
     // Every block writes its tile once per split and the second kernel reads all of that back, so a smaller tile means
@@ -297,7 +314,7 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     pl->ct = 64;
     // GEMM-shaped single-tap products (both channel counts large): 128 x 128 tiles, 4x the MFMAs per staged byte
     if (ntaps == 1 && d->K >= 256 && d->C >= 256 && (long long)((d->K + 127) / 128) * ((d->C + 127) / 128) >= 32) pl->kt = pl->ct = 128;
-    if (pl->PHp * pl->PWp * (pl->ct / 16) + 32 * (pl->kt / 16) > kItems * 256) return false;
+    if (pl->PHp * pl->PWp * (pl->ct / 16) + 32 * pl->ks * (pl->kt / 16) > kItems * 256) return false;
     pl->tiles_k = (d->K + pl->kt - 1) / pl->kt;
     pl->tiles_c = (d->C + pl->ct - 1) / pl->ct;
     const long long base = (long long)pl->tiles_k * pl->tiles_c * pl->groups;
@@ -308,7 +325,7 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
     pl->splits = (int)((steps + pl->steps_per_split - 1) / pl->steps_per_split);
     pl->out_len = (long long)d->K * ntaps * d->C;
     pl->partial_bytes = round_up((size_t)pl->splits * pl->out_len * sizeof(int32_t), 256);
-    pl->lds = 2 * (size_t)(32 + pl->PHp * pl->PWp) * lds_row_bytes(pl->kt, pl->ct);
+    pl->lds = 2 * (size_t)(32 * pl->ks + pl->PHp * pl->PWp) * lds_row_bytes(pl->kt, pl->ct);
     return pl->lds <= 64 * 1024;
 }
 
@@ -324,13 +341,15 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
     const dim3 grid((unsigned)(pl.tiles_k * pl.tiles_c), (unsigned)pl.groups, (unsigned)pl.splits);
     auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(256), pl.lds, st, p); };
     if (pl.kt == 128) {
-        go(wgrad_rect_kernel<128, 128, 1, 4>);
+        go(wgrad_rect_kernel<128, 128, 1, 4, 1>);
     } else if (pl.kt == 64 && pl.ct == 64) {
-        if (pl.tg == 1) go(wgrad_rect_kernel<64, 64, 1, 4>);
-        else go(wgrad_rect_kernel<64, 64, 9, 2>);  // 9 accumulators: no registers for a deeper read-ahead
+        if (pl.tg == 1) go(wgrad_rect_kernel<64, 64, 1, 4, 1>);
+        else if (pl.ks == 2) go(wgrad_rect_kernel<64, 64, 9, 2, 2>);
+        else go(wgrad_rect_kernel<64, 64, 9, 2, 1>);  // 9 accumulators: no registers for a deeper read-ahead
     } else {
-        if (pl.tg == 1) go(wgrad_rect_kernel<32, 64, 1, 4>);
-        else go(wgrad_rect_kernel<32, 64, 9, 2>);
+        if (pl.tg == 1) go(wgrad_rect_kernel<32, 64, 1, 4, 1>);
+        else if (pl.ks == 2) go(wgrad_rect_kernel<32, 64, 9, 2, 2>);
+        else go(wgrad_rect_kernel<32, 64, 9, 2, 1>);
     }
     const long long rb = (pl.out_len + 31) / 32;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.splits,
