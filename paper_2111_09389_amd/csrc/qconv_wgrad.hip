@@ -248,32 +248,39 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
 }
 
 // out[i] = sum over splits of partial[z][i] (exact integers: any order gives the same bits); as int32, or as fp32
-// times the scale product.  32 outputs x 8 split lanes per block so that the loads of one sum run in parallel.
+// times the scale product.  A block covers 128 outputs (4 per thread: 16-byte loads, 512 contiguous bytes per split)
+// with 8 split lanes, so that the loads of one sum run in parallel.  out_len is a multiple of 4 (K, C multiples of 16).
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const int32_t *__restrict__ partial, long long out_len, int splits,
                                                            int32_t *__restrict__ out, int out_mode, const float *sA,
                                                            const float *sB) {
-    __shared__ int sm[8][32];
+    __shared__ v4i sm[8][32];
     const int o = threadIdx.x % 32, zl = threadIdx.x / 32;
-    const long long i = (long long)blockIdx.x * 32 + o;
-    int s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+    const long long i = ((long long)blockIdx.x * 32 + o) * 4;
+    v4i s0 = {0, 0, 0, 0}, s1 = s0, s2 = s0, s3 = s0;
     if (i < out_len) {
         int z = zl;
         for (; z + 24 < splits; z += 32) {
-            s0 += partial[(size_t)z * out_len + i];
-            s1 += partial[(size_t)(z + 8) * out_len + i];
-            s2 += partial[(size_t)(z + 16) * out_len + i];
-            s3 += partial[(size_t)(z + 24) * out_len + i];
+            s0 += *reinterpret_cast<const v4i *>(partial + (size_t)z * out_len + i);
+            s1 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 8) * out_len + i);
+            s2 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 16) * out_len + i);
+            s3 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 24) * out_len + i);
         }
-        for (; z < splits; z += 8) s0 += partial[(size_t)z * out_len + i];
+        for (; z < splits; z += 8) s0 += *reinterpret_cast<const v4i *>(partial + (size_t)z * out_len + i);
     }
     sm[zl][o] = s0 + s1 + s2 + s3;
     __syncthreads();
     if (zl == 0 && i < out_len) {
-        int s = 0;
+        v4i s = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < 8; ++k) s += sm[k][o];
-        if (out_mode) reinterpret_cast<float *>(out)[i] = __fmul_rn(*sA, *sB) * (float)s;
-        else out[i] = s;
+        if (out_mode) {
+            const float sc = __fmul_rn(*sA, *sB);
+            float *f = reinterpret_cast<float *>(out) + i;
+            f[0] = dequant_value(sc, s[0], 0.f, false); f[1] = dequant_value(sc, s[1], 0.f, false);
+            f[2] = dequant_value(sc, s[2], 0.f, false); f[3] = dequant_value(sc, s[3], 0.f, false);
+        } else {
+            out[i] = s[0]; out[i + 1] = s[1]; out[i + 2] = s[2]; out[i + 3] = s[3];
+        }
     }
 }
 
@@ -351,7 +358,7 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
         else if (pl.ks == 2) go(wgrad_rect_kernel<32, 64, 9, 2, 2>);
         else go(wgrad_rect_kernel<32, 64, 9, 2, 1>);
     }
-    const long long rb = (pl.out_len + 31) / 32;
+    const long long rb = (pl.out_len / 4 + 31) / 32;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.splits,
                        static_cast<int32_t *>(out), out_mode, sA, sB);
 }
