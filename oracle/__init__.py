@@ -131,6 +131,26 @@ def qconv_bwd_weight(d, gq, xq):
     return dw
 
 
+def to_bf16(x):
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest even."""
+    x = _c(x, np.float32)
+    y = np.empty(x.shape, np.uint16)
+    lib().orc_to_bf16(_p(x), ctypes.c_size_t(x.size), _p(y))
+    return y
+
+
+def qconv_bwd_weight_bf16(d, g16, xq, sx):
+    """g16 uint16 bf16 patterns [N,P,Q,K], xq int8 [N,H,W,C], sx float -> (dw f64 [K,R,S,C], sum of |terms| f64)."""
+    g16 = _c(g16, np.uint16)
+    xq = _c(xq, np.int8)
+    assert g16.shape == (d.N, d.P, d.Q, d.K) and xq.shape == (d.N, d.H, d.W, d.C)
+    dw = np.empty((d.K, d.R, d.S, d.C), np.float64)
+    da = np.empty((d.K, d.R, d.S, d.C), np.float64)
+    _chk(lib().orc_qconv_bwd_weight_bf16(ctypes.byref(d), _p(g16), _p(xq), ctypes.c_float(sx), _p(dw), _p(da)),
+         "qconv_bwd_weight_bf16")
+    return dw, da
+
+
 def range_evonorm_fwd(x, groups, v, gamma, beta, eps=1e-5):
     """x float32 [N,H,W,C] -> (y f64, range f64 [N,groups], argmax i32, argmin i32)."""
     x = _c(x, np.float32)

@@ -197,6 +197,62 @@ int orc_qconv_bwd_weight(const orc_conv_desc *d, const int8_t *g, const int8_t *
 }
 
 /* ------------------------------------------------------------------------- */
+/* The weight-gradient product as the paper states it (Section 3, gradient bifurcation): the
+ * layer gradient enters in 16-bit floating point rather than as 8-bit codes; the saved 8-bit
+ * input codes are used as they are.  bfloat16 here: the upper 16 bits of the fp32 pattern
+ * after round-to-nearest-even.
+ *   dw[k,r,s,c] = sx * sum_{n,p,q} bf16(g)[n,p,q,k] * xq[n, p*st+r-pad, q*st+s-pad, c]
+ * in double; dwabs gets the same sum over |g*x| (the size against which a lower-precision
+ * accumulation is judged). */
+uint16_t orc_bf16_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u); /* nearest, ties to even; inputs are finite */
+    return (uint16_t)(u >> 16);
+}
+
+void orc_to_bf16(const float *x, size_t len, uint16_t *y)
+{
+    for (size_t i = 0; i < len; ++i) y[i] = orc_bf16_bits(x[i]);
+}
+
+static double bf16_value(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+int orc_qconv_bwd_weight_bf16(const orc_conv_desc *d, const uint16_t *g16, const int8_t *x, float sx, double *dw,
+                              double *dwabs)
+{
+    const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+#pragma omp parallel for collapse(2)
+    for (int k = 0; k < d->K; ++k)
+        for (int r = 0; r < d->R; ++r)
+            for (int t = 0; t < d->S; ++t)
+                for (int c = 0; c < d->C; ++c) {
+                    double s = 0.0, a = 0.0;
+                    for (int n = 0; n < d->N; ++n)
+                        for (int p = 0; p < P; ++p)
+                            for (int q = 0; q < Q; ++q) {
+                                int h = p * d->stride_h + r - d->pad_h, ww = q * d->stride_w + t - d->pad_w;
+                                if (h < 0 || h >= d->H || ww < 0 || ww >= d->W) continue;
+                                double term = bf16_value(g16[(((size_t)n * P + p) * Q + q) * d->K + k]) *
+                                              (double)x[(((size_t)n * d->H + h) * d->W + ww) * d->C + c];
+                                s += term;
+                                a += fabs(term);
+                            }
+                    size_t o = (((size_t)k * d->R + r) * d->S + t) * d->C + c;
+                    dw[o] = (double)sx * s;
+                    dwabs[o] = (double)sx * a;
+                }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Range-EvoNorm (Eq. "ren"): per sample and channel group, divide
  * x * hard_sigmoid(v x) by C(m) * (max - min) of the group's raw inputs,
  * m = channels per group, C(m) = 1/sqrt(2 ln m); then the affine gamma, beta.
