@@ -183,6 +183,21 @@ int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W,
                            float *dgamma, float *dbeta, float *absmax_out, void *ws, size_t ws_bytes,
                            void *stream);
 
+/* ------------------------------------------------- 16-bit weight gradient
+ * The weight-gradient product as Section 3 states it (gradient bifurcation): the layer
+ * gradient enters in 16-bit floating point, the saved input codes in 8 bits:
+ *   dw[k,r,s,c] = sx * sum_{n,p,q} g16[n,p,q,k] * xq[n, p*stride+r-pad, q*stride+s-pad, c]
+ * g16: bfloat16 bit patterns [N,P,Q,K] (lpdt_to_bf16 makes them from fp32: round to nearest
+ * even); xq int8 [N,H,W,C]; sx: device scalar, the scale of xq; dw fp32 [K,R,S,C], 16-byte
+ * aligned, overwritten.  fp32 accumulation on the matrix cores in a fixed order (run-to-run
+ * identical; within ~1e-6 of sum |g*x| of the exact sum).  This is an alternative to
+ * lpdt_qconv_bwd_weight(_f32), which takes the 8-bit codes of the gradient.
+ */
+int lpdt_to_bf16(const float *x, size_t len, uint16_t *y, void *stream);
+size_t lpdt_qconv_bwd_weight_bf16_workspace_bytes(const lpdt_conv_desc *d);
+int lpdt_qconv_bwd_weight_bf16(const lpdt_conv_desc *d, const uint16_t *g16, const int8_t *xq,
+                               const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------- gossip
  * Algorithm 1 step 7 for n agents whose parameter vectors are the rows of x.
  *   xhat == NULL (plain, D-PSGD / Algorithm 2 without compression):

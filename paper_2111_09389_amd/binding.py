@@ -8,6 +8,7 @@ __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
+    "to_bf16", "qconv_bwd_weight_bf16",
     "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
@@ -27,6 +28,7 @@ EXPORTS = [
     "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
     "lpdt_qconv_fwd_f32_workspace_bytes", "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
     "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
+    "lpdt_to_bf16", "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_bwd_weight_bf16",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
@@ -84,7 +86,8 @@ def lib():
         L.lpdt_quantize_segments_workspace_bytes.argtypes = [ctypes.c_int]
         for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
                      "lpdt_qconv_bwd_weight_workspace_bytes", "lpdt_qconv_fwd_f32_workspace_bytes",
-                     "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes"):
+                     "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
+                     "lpdt_qconv_bwd_weight_bf16_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
@@ -325,6 +328,24 @@ def gossip_mix_ex(x, state, W, rate=1.0, keep_ratio=1.0, seg_offsets=None, mode=
     _check(lib().lpdt_gossip_mix_ex(_ptr(x), _ptr(state), n, _sz(d), Wc, ctypes.c_float(rate), ctypes.c_double(keep_ratio),
                                     seg, nseg, int(mode), _ptr(u), _ptr(z), _ptr(buf), _sz(nb), _stream()))
     return x, state, u, z
+
+
+def to_bf16(x, y=None):
+    """fp32 tensor -> bfloat16 bit patterns (int16 tensor of the same shape), round to nearest even."""
+    _dev(x, torch.float32, "to_bf16 x")
+    y = torch.empty(x.shape, dtype=torch.int16, device=x.device) if y is None else y
+    _check(lib().lpdt_to_bf16(_ptr(x), _sz(x.numel()), _ptr(y), _stream()))
+    return y
+
+
+def qconv_bwd_weight_bf16(d, g16, xq, sx, dw=None, ws=None):
+    """Weight gradient from the bfloat16 copy of the layer gradient (int16 bit patterns [N,P,Q,K]) and int8 input codes."""
+    _dev(g16, torch.int16, "qconv_bwd_weight_bf16 g16"); _dev(xq, torch.int8, "qconv_bwd_weight_bf16 xq")
+    assert tuple(g16.shape) == (d.N, d.P, d.Q, d.K) and tuple(xq.shape) == (d.N, d.H, d.W, d.C)
+    dw = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.float32, device=xq.device) if dw is None else dw
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_weight_bf16_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_weight_bf16(ctypes.byref(d), _ptr(g16), _ptr(xq), _ptr(sx), _ptr(dw), _ptr(buf), _sz(nb), _stream()))
+    return dw
 
 
 # ---------------------------------------------------------------- glue
