@@ -101,7 +101,8 @@ def build_workload(cfg_id, device):
         else:
             labels, upstream = None, torch.from_numpy(wl.upstream_grad(seed + 300, (cfg["batch"], H, W, C))).to(device)
         grads = torch.zeros(d, dtype=torch.float32, device=device)
-        steps.append(TrainStep(net, cfg["batch"], X[a], grads, x, labels, upstream, lr=0.05, seed=wl.PHILOX_SEED + a))
+        steps.append(TrainStep(net, cfg["batch"], X[a], grads, x, labels, upstream, lr=0.05, seed=wl.PHILOX_SEED + a,
+                               wgrad_16bit=cfg.get("wgrad_16bit", False)))
     mix = None
     if cfg["mix"]:
         import paper_2111_09389_amd as lpdt
@@ -174,6 +175,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=sorted(CONFIGS))
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph (launch-bound configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wgrad-16bit", action="store_true",
+                    help="weight gradients from a bfloat16 copy of the layer gradient (the paper's gradient bifurcation) instead "
+                         "of its 8-bit codes; the headline runs the 8-bit product")
     ap.add_argument("--mix-variant", default="choco", choices=["choco", "deepsqueeze", "sparse_push", "quant_sgp"],
                     help="gossip algorithm of the compressed configuration (config 5); the headline is choco")
     args = ap.parse_args()
@@ -189,6 +193,8 @@ def main():
     import paper_2111_09389_amd as lpdt
     lpdt.lib()
     device = torch.device("cuda:0")
+    if args.wgrad_16bit:
+        CONFIGS[args.config] = dict(CONFIGS[args.config], wgrad_16bit=True)
     if CONFIGS[args.config]["mix"] == "choco":
         CONFIGS[args.config] = dict(CONFIGS[args.config], variant=args.mix_variant)
     cfg, net, steps, mix, X = build_workload(args.config, device)
@@ -241,7 +247,8 @@ def main():
         b.record()
         torch.cuda.synchronize()
         mix_ms = a.elapsed_time(b) / reps
-    conv_names = ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32")
+    wg_name = "lpdt_qconv_bwd_weight_bf16" if cfg.get("wgrad_16bit") else "lpdt_qconv_bwd_weight_f32"
+    conv_names = ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", wg_name)
     conv_ms = sum(per.get(n, 0.0) for n in conv_names)
     work = {}
     for ts in steps:

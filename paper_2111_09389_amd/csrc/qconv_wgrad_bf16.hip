@@ -220,29 +220,46 @@ __global__ __launch_bounds__(256, 2) void wgrad_bf16_kernel(const Params p) {
 }
 
 // dw[i] = sx * sum over splits of partial[z][i], the splits added in a fixed order (8 interleaved chains, then those)
+template <int V>
 __global__ __launch_bounds__(256) void wgrad_bf16_reduce_kernel(const float *__restrict__ partial, long long out_len, int splits,
                                                                 const float *__restrict__ sx, float *__restrict__ dw) {
-    __shared__ v4f sm[8][32];
+    typedef float vf __attribute__((ext_vector_type(V)));
+    __shared__ float sm[8][32][V];
     const int o = threadIdx.x % 32, zl = threadIdx.x / 32;
-    const long long i = ((long long)blockIdx.x * 32 + o) * 4;
-    v4f s = {0.f, 0.f, 0.f, 0.f};
+    const long long i = ((long long)blockIdx.x * 32 + o) * V;
+    float s[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) s[e] = 0.0f;
     if (i < out_len)
-        for (int z = zl; z < splits; z += 8) s += *reinterpret_cast<const v4f *>(partial + (size_t)z * out_len + i);
-    sm[zl][o] = s;
+        for (int z = zl; z < splits; z += 8) {
+            if constexpr (V == 4) {
+                const vf t = *reinterpret_cast<const vf *>(partial + (size_t)z * out_len + i);
+#pragma unroll
+                for (int e = 0; e < V; ++e) s[e] += t[e];
+            } else {
+                s[0] += partial[(size_t)z * out_len + i];
+            }
+        }
+#pragma unroll
+    for (int e = 0; e < V; ++e) sm[zl][o][e] = s[e];
     __syncthreads();
     if (zl == 0 && i < out_len) {
-        v4f tsum = sm[0][o];
-#pragma unroll
-        for (int k = 1; k < 8; ++k) tsum += sm[k][o];
         const float sc = *sx;
-        *reinterpret_cast<v4f *>(dw + i) = v4f{sc * tsum[0], sc * tsum[1], sc * tsum[2], sc * tsum[3]};
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float tsum = sm[0][o][e];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) tsum += sm[k][o][e];
+            dw[i + e] = sc * tsum;
+        }
     }
 }
 
-// any shape: one thread per filter element, pixels in order
+// any shape: one thread per filter element and pixel slice (pixels in order inside a slice); the slices are partial
+// tiles for the reduction kernel above
 __global__ __launch_bounds__(256) void wgrad_bf16_plain_kernel(const uint16_t *__restrict__ g, const int8_t *__restrict__ x,
-                                                               const float *__restrict__ sx, float *__restrict__ dw,
-                                                               lpdt_conv_desc d, int P, int Q) {
+                                                               float *__restrict__ partial, lpdt_conv_desc d, int P, int Q,
+                                                               int pix_per_slice) {
     const int total = d.K * d.R * d.S * d.C;
     const int o = blockIdx.x * 256 + threadIdx.x;
     if (o >= total) return;
@@ -250,19 +267,17 @@ __global__ __launch_bounds__(256) void wgrad_bf16_plain_kernel(const uint16_t *_
     const int s = (o / d.C) % d.S;
     const int r = (o / (d.C * d.S)) % d.R;
     const int k = o / (d.C * d.S * d.R);
+    const long long M = (long long)d.N * P * Q;
+    const long long m0 = (long long)blockIdx.y * pix_per_slice, m1 = min(M, m0 + pix_per_slice);
     float sum = 0.0f;
-    for (int n = 0; n < d.N; ++n)
-        for (int pp = 0; pp < P; ++pp) {
-            const int h = pp * d.stride_h + r - d.pad_h;
-            if (h < 0 || h >= d.H) continue;
-            for (int q = 0; q < Q; ++q) {
-                const int w = q * d.stride_w + s - d.pad_w;
-                if (w < 0 || w >= d.W) continue;
-                const float gv = __uint_as_float((unsigned)g[(((size_t)n * P + pp) * Q + q) * d.K + k] << 16);
-                sum += gv * (float)x[(((size_t)n * d.H + h) * d.W + w) * d.C + c];
-            }
-        }
-    dw[o] = *sx * sum;
+    for (long long m = m0; m < m1; ++m) {
+        const int q = (int)(m % Q), pp = (int)((m / Q) % P), n = (int)(m / ((long long)P * Q));
+        const int h = pp * d.stride_h + r - d.pad_h, w = q * d.stride_w + s - d.pad_w;
+        if (h < 0 || h >= d.H || w < 0 || w >= d.W) continue;
+        const float gv = __uint_as_float((unsigned)g[(size_t)m * d.K + k] << 16);
+        sum += gv * (float)x[(((size_t)n * d.H + h) * d.W + w) * d.C + c];
+    }
+    partial[(size_t)blockIdx.y * total + o] = sum;
 }
 
 __global__ __launch_bounds__(256) void to_bf16_kernel(const float *__restrict__ x, size_t len, uint16_t *__restrict__ y) {
@@ -320,6 +335,21 @@ bool make_plan(const lpdt_conv_desc *d0, int P, int Q, Plan *pl, lpdt_conv_desc 
     return pl->lds <= 96 * 1024;
 }
 
+// any-shape path: pixel slices of >= 256 pixels, at most 1024 of them, at most ~64 MB of partial tiles
+struct PlainPlan { int slices, pix; size_t bytes; };
+PlainPlan plain_plan(const lpdt_conv_desc *d, int P, int Q) {
+    const long long M = (long long)d->N * P * Q, total = (long long)d->K * d->R * d->S * d->C;
+    long long slices = (M + 255) / 256;
+    if (slices > 1024) slices = 1024;
+    const long long cap = (64ll << 20) / (total * 4) > 1 ? (64ll << 20) / (total * 4) : 1;
+    if (slices > cap) slices = cap;
+    PlainPlan pp;
+    pp.pix = (int)((M + slices - 1) / slices);
+    pp.slices = (int)((M + pp.pix - 1) / pp.pix);
+    pp.bytes = round_up((size_t)pp.slices * total * 4, 256);
+    return pp;
+}
+
 template <typename K>
 void launch_tiled(K kernel, const dim3 &grid, size_t lds, hipStream_t st, const Params &p) {
     if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -346,7 +376,8 @@ extern "C" size_t lpdt_qconv_bwd_weight_bf16_workspace_bytes(const lpdt_conv_des
     if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
     Plan pl;
     lpdt_conv_desc view;
-    return make_plan(d, P, Q, &pl, &view) ? pl.partial_bytes : 0;
+    const size_t plain = plain_plan(d, P, Q).bytes;  // also taken when an operand is not 16-byte aligned
+    return make_plan(d, P, Q, &pl, &view) && pl.partial_bytes > plain ? pl.partial_bytes : plain;
 }
 
 extern "C" int lpdt_qconv_bwd_weight_bf16(const lpdt_conv_desc *d, const uint16_t *g16, const int8_t *xq, const float *sx,
@@ -374,10 +405,17 @@ extern "C" int lpdt_qconv_bwd_weight_bf16(const lpdt_conv_desc *d, const uint16_
         if (pl.tg == 1) launch_tiled(wgrad_bf16_kernel<1, 2>, grid, pl.lds, st, p);
         else launch_tiled(wgrad_bf16_kernel<9, 2>, grid, pl.lds, st, p);
         const long long rb = (pl.out_len / 4 + 31) / 32;
-        hipLaunchKernelGGL(wgrad_bf16_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.splits, sx, dw);
+        hipLaunchKernelGGL(wgrad_bf16_reduce_kernel<4>, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.splits, sx, dw);
     } else {
         const int total = d->K * d->R * d->S * d->C;
-        hipLaunchKernelGGL(wgrad_bf16_plain_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g16, xq, sx, dw, *d, P, Q);
+        const PlainPlan pp = plain_plan(d, P, Q);
+        rc = check_ws(ws, ws_bytes, pp.bytes);
+        if (rc) return rc;
+        float *partial = static_cast<float *>(ws);
+        hipLaunchKernelGGL(wgrad_bf16_plain_kernel, dim3((unsigned)((total + 255) / 256), (unsigned)pp.slices), dim3(256), 0, st, g16, xq,
+                           partial, *d, P, Q, pp.pix);
+        hipLaunchKernelGGL(wgrad_bf16_reduce_kernel<1>, dim3((unsigned)((total + 31) / 32)), dim3(256), 0, st, partial, (long long)total,
+                           pp.slices, sx, dw);
     }
     return launch_status("lpdt_qconv_bwd_weight_bf16");
 }

@@ -34,9 +34,14 @@ class TrainStep:
     agents' matrix); x: [batch,H,W,C] fp32 device tensor; labels: int32 device tensor or None
     (then `upstream` must be the gradient of the last tensor)."""
 
-    def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5):
+    def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5,
+                 wgrad_16bit=False):
         self.L = lib()
         self.net, self.N, self.lr, self.seed, self.eps = net, batch, lr, seed, eps
+        # gradient bifurcation as the paper states it: weight gradients from a bfloat16 copy of the layer gradient
+        # (the 8-bit codes still feed backward-data), for every layer but the one that reads the image; default: both
+        # products from the 8-bit codes
+        self.wgrad_16bit = wgrad_16bit
         self.dev = params.device
         self.params, self.grads = params, grads
         f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=self.dev)
@@ -194,7 +199,7 @@ class TrainStep:
 
     def _plan_backward(self):
         net, N, L = self.net, self.N, self.L
-        self.gabsmax, self.gq, self.sg = {}, {}, {}
+        self.gabsmax, self.gq, self.sg, self._keep = {}, {}, {}, []
         pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
         conv_index = 0
         for op in reversed(net.ops):
@@ -220,9 +225,17 @@ class TrainStep:
                     self._emit(L.lpdt_qconv_bwd_data_f32, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(sg), _p(self.sw[out]),
                                                            _p(buf), accumulate, "WS", "WSB"])
                 gw = self.gview[a["w"]]
-                self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)))
-                self._emit(L.lpdt_qconv_bwd_weight_f32, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(sg), _p(self.sx[inp]),
-                                                         _p(gw), "WS", "WSB"])
+                if self.wgrad_16bit and inp != "x":   # the image layer (3 channels) has no tiled 16-bit kernel: 8-bit path
+                    g16 = torch.empty(dy.shape, dtype=torch.int16, device=self.dev)
+                    self._keep.append(g16)
+                    self._emit(L.lpdt_to_bf16, [_p(dy), _sz(dy.numel()), _p(g16)])
+                    self._need_ws(L.lpdt_qconv_bwd_weight_bf16_workspace_bytes(ctypes.byref(d)))
+                    self._emit(L.lpdt_qconv_bwd_weight_bf16, [ctypes.byref(d), _p(g16), _p(self.xq[inp]), _p(self.sx[inp]), _p(gw),
+                                                              "WS", "WSB"])
+                else:
+                    self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)))
+                    self._emit(L.lpdt_qconv_bwd_weight_f32, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(sg), _p(self.sx[inp]),
+                                                             _p(gw), "WS", "WSB"])
             elif kind == "ren":
                 _, _, inp, a = op
                 H, W, C = net.shapes[inp]
@@ -303,10 +316,11 @@ class TrainStep:
         return [(name, a.elapsed_time(b)) for name, a, b in marks]
 
     def conv_work(self):
-        """[(entry point name, int8 multiply-adds)] for every convolution call of one step, in call order."""
+        """[(entry point name, multiply-adds)] for every convolution call of one step, in call order."""
         out = []
         for fn, args, _ in self.calls:
-            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32"):
+            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
+                               "lpdt_qconv_bwd_weight_bf16"):
                 d = args[0]._obj
                 out.append((fn.__name__, d.N * d.P * d.Q * d.K * d.C * d.R * d.S))
         return out

@@ -227,3 +227,37 @@ def test_driver_under_graph_capture_matches_eager():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(g, g_eager) and torch.equal(ts.loss, loss_eager)
+
+
+def test_driver_with_16bit_weight_gradients():
+    """The step with weight gradients from the bfloat16 copy of the layer gradient: forward, layer gradients and the
+    first layer are the 8-bit step's bit for bit (same codes, same counters); the other weight gradients differ only
+    by the rounding of the gradient operand (8-bit stochastic vs bfloat16)."""
+    from paper_2111_09389_amd.step import TrainStep
+    net = nets.resnet20()
+    N = 16
+    params = nets.init_params(net, wl.BASE_SEED + 6)
+    flat = np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32)
+    x, lb = dev(wl.images(3, N, 32, 32, 3)), dev(wl.labels_uniform(4, N, 10))
+    out = []
+    for w16 in (False, True):
+        p = dev(flat)
+        g = torch.zeros_like(p)
+        ts = TrainStep(net, N, p, g, x, lb, lr=0.0, seed=9, wgrad_16bit=w16)
+        ts.run(1)
+        torch.cuda.synchronize()
+        out.append((ts, g))
+    (t8, g8), (t16, g16) = out
+    assert torch.equal(t8.loss, t16.loss)
+    convs = [op for op in net.ops if op[0] == "conv"]
+    for i, op in enumerate(convs):
+        name = op[3]["w"]
+        a, b = t8.gview[name].double().flatten(), t16.gview[name].double().flatten()
+        if op[2] == "x":
+            assert torch.equal(t8.gview[name], t16.gview[name])
+        else:
+            cos = float((a @ b) / (a.norm() * b.norm()))
+            assert cos > 0.97, (name, cos)
+    for nm, _ in net.params:            # Range-EvoNorm parameter gradients come from the same layer gradients
+        if not nm.endswith(".w"):
+            assert torch.equal(t8.gview[nm], t16.gview[nm]), nm
