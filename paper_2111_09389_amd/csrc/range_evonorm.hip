@@ -17,7 +17,9 @@
 namespace lpdt {
 
 constexpr int kRThreads = 256;
-constexpr int kPixIters = 16;    // least pixels per thread in the streaming passes
+constexpr int kPixIters = 2;     // least pixels per thread in the streaming passes
+constexpr int kBwdMinPix = 8;
+constexpr int kRU = 4;           // pixels a thread has in flight: the streaming loops load kRU pixels, then work on them
 constexpr int kMaxBlocks = 2048;  // the streaming grids are kept near this size: enough to fill the chip, few partial rows
 
 struct RenGeom {
@@ -30,7 +32,17 @@ struct RenGeom {
     int pix_per_block;
 };
 
-static RenGeom ren_geom(int N, int H, int W, int C, int groups) {
+// Grid size of a streaming pass: about one block per `elems_per_block` elements, between 256 and kMaxBlocks.  Small
+// tensors are latency-bound (every block first waits for its parameters and range), so they want few, longer blocks;
+// the stats pass has no such wait and takes more, shorter ones (measured on the ResNet-18 layer sizes).
+constexpr int kStatsElems = 8192, kApplyElems = 16384, kBwdElems = 16384;
+static int block_cap(int N, int H, int W, int C, int elems_per_block) {
+    const long long b = (long long)N * H * W * C / elems_per_block;
+    return (int)(b < 256 ? 256 : b > kMaxBlocks ? kMaxBlocks : b);
+}
+// min_pix: least pixels per block.  The forward passes leave a few keys per block and take 0; the backward pass leaves
+// 4 floats per channel and block, which must stay small beside the 3 floats per channel and pixel it streams.
+static RenGeom ren_geom(int N, int H, int W, int C, int groups, int min_pix, int max_blocks) {
     RenGeom g;
     g.N = N; g.HW = H * W; g.C = C; g.groups = groups; g.m = C / groups;
     g.cq = C / 4;
@@ -38,7 +50,7 @@ static RenGeom ren_geom(int N, int H, int W, int C, int groups) {
     g.block = (g.threads + kWave - 1) / kWave * kWave;
     g.ppi = g.threads / g.cq;
     int iters = kPixIters;
-    while ((long long)N * ((g.HW + g.ppi * iters - 1) / (g.ppi * iters)) > kMaxBlocks && iters < 4096) iters *= 2;
+    while (((long long)N * ((g.HW + g.ppi * iters - 1) / (g.ppi * iters)) > max_blocks || g.ppi * iters < min_pix) && iters < 4096) iters *= 2;
     g.pix_per_block = g.ppi * iters;
     g.chunks = (g.HW + g.pix_per_block - 1) / g.pix_per_block;
     return g;
@@ -79,13 +91,23 @@ __global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__res
 #pragma unroll
     for (int e = 0; e < 4; ++e) { imx[e] = -1; imn[e] = -1; mx[e] = 0.f; mn[e] = 0.f; }
     const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
-    for (int p = p0 + pl; p < p1 && (int)threadIdx.x < g.threads; p += g.ppi) {
-        const float4 a = xv[(size_t)p * g.cq + qd];
-        const float v[4] = {a.x, a.y, a.z, a.w};
+    for (int pb = p0 + pl; pb < p1 && (int)threadIdx.x < g.threads; pb += kRU * g.ppi) {
+        float4 a[kRU];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (imx[e] < 0 || v[e] > mx[e]) { mx[e] = v[e]; imx[e] = p; }
-            if (imn[e] < 0 || v[e] < mn[e]) { mn[e] = v[e]; imn[e] = p; }
+        for (int u = 0; u < kRU; ++u) {
+            const int p = pb + u * g.ppi;
+            a[u] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < kRU; ++u) {
+            const int p = pb + u * g.ppi;
+            if (p >= p1) break;
+            const float v[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (imx[e] < 0 || v[e] > mx[e]) { mx[e] = v[e]; imx[e] = p; }
+                if (imn[e] < 0 || v[e] < mn[e]) { mn[e] = v[e]; imn[e] = p; }
+            }
         }
     }
 #pragma unroll
@@ -170,7 +192,7 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__res
                                                               const float *__restrict__ v,
                                                               const float *__restrict__ gamma,
                                                               const float *__restrict__ beta, float cm, float eps,
-                                                              const unsigned long long *__restrict__ pstats,
+                                                              const unsigned long long *__restrict__ pstats, int stat_chunks,
                                                               float *__restrict__ y, float *__restrict__ range_out,
                                                               int32_t *__restrict__ argmax_out, int32_t *__restrict__ argmin_out,
                                                               float *__restrict__ absmax_out) {
@@ -179,13 +201,17 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__res
     float *srange = reinterpret_cast<float *>(skeys + 2 * g.groups);
     const int n = blockIdx.y;
     // fold the per-block keys of this sample (every block of the sample does it: a few KB out of L2)
-    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) {
-        unsigned long long k = 0ull;
-        const unsigned long long *src = pstats + (size_t)n * g.chunks * g.groups * 2 + i;
-        for (int ch = 0; ch < g.chunks; ++ch) k = max(k, src[(size_t)ch * g.groups * 2]);
-        skeys[i] = k;
+    {
+        const int nk = 2 * g.groups;
+        for (int i = threadIdx.x; i < nk; i += blockDim.x) skeys[i] = 0ull;
+        __syncthreads();
+        const unsigned long long *src = pstats + (size_t)n * stat_chunks * nk;  // [chunks][nk]: one contiguous run
+        for (int i = threadIdx.x; i < stat_chunks * nk; i += blockDim.x) {
+            const unsigned long long k = src[i];
+            if (k) atomicMax(&skeys[i % nk], k);
+        }
+        __syncthreads();
     }
-    __syncthreads();
     for (int grp = threadIdx.x; grp < g.groups; grp += blockDim.x) {
         const unsigned long long kmx = skeys[2 * grp], kmn = skeys[2 * grp + 1];
         const float r = __fsub_rn(from_ordered_bits((uint32_t)(kmx >> 32)), from_ordered_bits(~(uint32_t)(kmn >> 32)));
@@ -211,17 +237,27 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__res
     const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
     float4 *yv = reinterpret_cast<float4 *>(y + (size_t)n * g.HW * g.C);
     float am = 0.0f;
-    for (int p = p0 + pl; p < p1 && active; p += g.ppi) {
-        const float4 a = xv[(size_t)p * g.cq + qd];
-        const float xe[4] = {a.x, a.y, a.z, a.w};
-        float o[4];
+    for (int pb = p0 + pl; pb < p1 && active; pb += kRU * g.ppi) {
+        float4 a[kRU];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float u = xe[e] * hard_sigmoid(vv[e] * xe[e]);
-            o[e] = gg[e] * u * inv[e] + bb[e];
-            am = fmaxf(am, fabsf(o[e]));
+        for (int k = 0; k < kRU; ++k) {
+            const int p = pb + k * g.ppi;
+            a[k] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        yv[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
+#pragma unroll
+        for (int k = 0; k < kRU; ++k) {
+            const int p = pb + k * g.ppi;
+            if (p >= p1) break;
+            const float xe[4] = {a[k].x, a[k].y, a[k].z, a[k].w};
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float u = xe[e] * hard_sigmoid(vv[e] * xe[e]);
+                o[e] = gg[e] * u * inv[e] + bb[e];
+                am = fmaxf(am, fabsf(o[e]));
+            }
+            yv[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
+        }
     }
     if (absmax_out) block_absmax_commit(am, absmax_out, lds);
 }
@@ -288,27 +324,37 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
     float4 *ov = reinterpret_cast<float4 *>(dx + base);
     float am = 0.0f;
     const bool active = (int)threadIdx.x < g.threads;
-    for (int p = p0 + pl; p < p1 && active; p += g.ppi) {
-        const float4 a = xv[(size_t)p * g.cq + qd];
-        const float4 d = dv4[(size_t)p * g.cq + qd];
-        const float xe[4] = {a.x, a.y, a.z, a.w};
-        const float de[4] = {d.x, d.y, d.z, d.w};
-        float o[4];
+    for (int pb = p0 + pl; pb < p1 && active; pb += kRU * g.ppi) {
+        float4 a4[kRU], d4[kRU];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float z = vv[e] * xe[e];
-            const float s = hard_sigmoid(z);
-            const float sp = (z > -3.0f && z < 3.0f) ? (1.0f / 6.0f) : 0.0f;
-            const float u = xe[e] * s;
-            const float du = de[e] * gg[e] * inv[e];
-            o[e] = du * (s + xe[e] * vv[e] * sp);
-            sb[e] += de[e];
-            sg[e] += de[e] * u;
-            sv[e] += du * xe[e] * xe[e] * sp;
-            st[e] += de[e] * gg[e] * u;
-            if (p != skip_a[e] && p != skip_b[e]) am = fmaxf(am, fabsf(o[e]));
+        for (int k = 0; k < kRU; ++k) {
+            const int p = pb + k * g.ppi;
+            a4[k] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
+            d4[k] = p < p1 ? dv4[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        ov[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
+#pragma unroll
+        for (int k = 0; k < kRU; ++k) {
+            const int p = pb + k * g.ppi;
+            if (p >= p1) break;
+            const float xe[4] = {a4[k].x, a4[k].y, a4[k].z, a4[k].w};
+            const float de[4] = {d4[k].x, d4[k].y, d4[k].z, d4[k].w};
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float z = vv[e] * xe[e];
+                const float s = hard_sigmoid(z);
+                const float sp = (z > -3.0f && z < 3.0f) ? (1.0f / 6.0f) : 0.0f;
+                const float u = xe[e] * s;
+                const float du = de[e] * gg[e] * inv[e];
+                o[e] = du * (s + xe[e] * vv[e] * sp);
+                sb[e] += de[e];
+                sg[e] += de[e] * u;
+                sv[e] += du * xe[e] * xe[e] * sp;
+                st[e] += de[e] * gg[e] * u;
+                if (p != skip_a[e] && p != skip_b[e]) am = fmaxf(am, fabsf(o[e]));
+            }
+            ov[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
+        }
     }
     // fixed-order block reduction over the threads that share a channel quad
     const int T4 = g.threads * 4;
@@ -389,27 +435,26 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
     __shared__ float s[3][32][8];
     __shared__ float lds[256 / kWave];
     const int param_blocks = (C + 7) / 8;
-    if ((int)blockIdx.x < param_blocks) {  // 8 channels x 32 row lanes: many short chains of loads instead of few long ones
+    if ((int)blockIdx.x < param_blocks) {
+        // 8 channels x 32 row lanes; a lane's rows are summed four at a time (12 loads in flight) in a fixed order
         const int cl = threadIdx.x % 8, sl = threadIdx.x / 8;
         const int c = blockIdx.x * 8 + cl;
-        float a0 = 0, a1 = 0, a2 = 0, b0 = 0, b1 = 0, b2 = 0;
+        float acc[3] = {0.f, 0.f, 0.f};
         if (c < C) {
-            int r = sl;
-            for (; r + 32 < rows; r += 64) {
-                a0 += parts[((size_t)r * 4 + 0) * C + c];
-                a1 += parts[((size_t)r * 4 + 1) * C + c];
-                a2 += parts[((size_t)r * 4 + 2) * C + c];
-                b0 += parts[((size_t)(r + 32) * 4 + 0) * C + c];
-                b1 += parts[((size_t)(r + 32) * 4 + 1) * C + c];
-                b2 += parts[((size_t)(r + 32) * 4 + 2) * C + c];
-            }
-            if (r < rows) {
-                a0 += parts[((size_t)r * 4 + 0) * C + c];
-                a1 += parts[((size_t)r * 4 + 1) * C + c];
-                a2 += parts[((size_t)r * 4 + 2) * C + c];
+            for (int r = sl; r < rows; r += 128) {
+                float t[4][3];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) {
+                        const int rr = r + 32 * k;
+                        t[k][q] = rr < rows ? parts[((size_t)rr * 4 + q) * C + c] : 0.0f;
+                    }
+#pragma unroll
+                for (int q = 0; q < 3; ++q) acc[q] += (t[0][q] + t[1][q]) + (t[2][q] + t[3][q]);
             }
         }
-        s[0][sl][cl] = a0 + b0; s[1][sl][cl] = a1 + b1; s[2][sl][cl] = a2 + b2;
+        s[0][sl][cl] = acc[0]; s[1][sl][cl] = acc[1]; s[2][sl][cl] = acc[2];
         __syncthreads();
         if (sl < 3 && c < C) {  // row lane 0, 1, 2 finish dbeta, dgamma, dv
             float t = 0;
@@ -424,21 +469,35 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
     const int i = rb * (256 / kWave) + threadIdx.x / kWave, lane = threadIdx.x % kWave;
     if (i < N * groups) {
         const int n = i / groups, grp = i % groups;
+        // the two elements to change are fetched while the partial sums are still being added up
+        const int ia = argmax[i], ib = argmin[i];
+        const size_t base = (size_t)n * HW * C + (size_t)grp * m;
+        const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
+        const float da = dx[pa], db = dx[pb];
+        const float inv = inv_denominator(range[i], cm, eps);
         float t = 0.0f;
-        for (int k = lane; k < chunks * m; k += kWave) {
-            const int ch = k / m, cc = k - ch * m;
-            t += parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc];
+        for (int k0 = lane; k0 < chunks * m; k0 += 4 * kWave) {
+            float q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = k0 + j * kWave, ch = k / m, cc = k - ch * m;
+                q[j] = k < chunks * m ? parts[(((size_t)n * chunks + ch) * 4 + 3) * C + grp * m + cc] : 0.0f;
+            }
+            t += (q[0] + q[1]) + (q[2] + q[3]);
         }
         t = wave_sum(t);
         if (lane == 0) {
-            const float inv = inv_denominator(range[i], cm, eps);
             const float dR = -cm * t * inv * inv;
-            const int ia = argmax[i], ib = argmin[i];
-            const size_t base = (size_t)n * HW * C + (size_t)grp * m;
-            const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
-            dx[pa] += dR;
-            dx[pb] -= dR;
-            am = fmaxf(fabsf(dx[pa]), fabsf(dx[pb]));
+            if (pa != pb) {
+                const float na = da + dR, nb = db - dR;
+                dx[pa] = na;
+                dx[pb] = nb;
+                am = fmaxf(fabsf(na), fabsf(nb));
+            } else {  // a constant slab: both extrema are its first element
+                const float na = (da + dR) - dR;
+                dx[pa] = na;
+                am = fabsf(na);
+            }
         }
     }
     if (absmax_out) {
@@ -468,13 +527,13 @@ constexpr int kGenericPix = 64;
 using namespace lpdt;
 
 static size_t ren_rows(int N, int H, int W, int C, int groups) {
-    if (ren_fast(C)) return (size_t)N * ren_geom(N, H, W, C, groups).chunks;
+    if (ren_fast(C)) return (size_t)N * ren_geom(N, H, W, C, groups, kBwdMinPix, block_cap(N, H, W, C, kBwdElems)).chunks;
     return (size_t)N * (((size_t)H * W + kGenericPix - 1) / kGenericPix);
 }
 
 extern "C" size_t lpdt_range_evonorm_fwd_workspace_bytes(int N, int H, int W, int C, int groups) {
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups) return 0;
-    const size_t blocks = ren_fast(C) ? (size_t)N * ren_geom(N, H, W, C, groups).chunks : (size_t)N;
+    const size_t blocks = ren_fast(C) ? (size_t)N * ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems)).chunks : (size_t)N;
     return round_up(blocks * groups * 2 * sizeof(unsigned long long), 256);
 }
 
@@ -502,10 +561,11 @@ extern "C" int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C
     const float cm = ren_cm(m);
     const size_t smem = (size_t)2 * groups * sizeof(unsigned long long);
     if (ren_fast(C)) {
-        const RenGeom g = ren_geom(N, H, W, C, groups);
+        const RenGeom g = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems));
         hipLaunchKernelGGL(ren_stats_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, absmax_out);
-        hipLaunchKernelGGL(ren_apply_kernel, dim3(g.chunks, N), dim3(g.block), smem + groups * sizeof(float), st, x, g, v, gamma,
-                           beta, cm, eps, stats, y, range_out, argmax_out, argmin_out, absmax_out);
+        const RenGeom ga = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kApplyElems));
+        hipLaunchKernelGGL(ren_apply_kernel, dim3(ga.chunks, N), dim3(ga.block), smem + groups * sizeof(float), st, x, ga, v, gamma,
+                           beta, cm, eps, stats, g.chunks, y, range_out, argmax_out, argmin_out, absmax_out);
     } else {
         hipLaunchKernelGGL(ren_clear_kernel, dim3((2 * count + 255) / 256), dim3(256), 0, st, stats, 2 * count, absmax_out);
         const long long total = (long long)H * W * C;
@@ -541,7 +601,7 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
     float *pabs = reinterpret_cast<float *>(static_cast<char *>(ws) + round_up(rows * 4 * C * sizeof(float), 256));
     int chunks;
     if (ren_fast(C)) {
-        const RenGeom g = ren_geom(N, H, W, C, groups);
+        const RenGeom g = ren_geom(N, H, W, C, groups, kBwdMinPix, block_cap(N, H, W, C, kBwdElems));
         chunks = g.chunks;
         const size_t smem = (size_t)16 * g.threads * sizeof(float);
         hipLaunchKernelGGL(ren_bwd_main_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, dy, x, g, v, gamma, cm, eps,
