@@ -118,6 +118,7 @@ __global__ __launch_bounds__(kT) void maxpool_fwd_vec_kernel(const float4 *__res
     }
 }
 
+template <bool kTwoByTwo>
 __global__ __launch_bounds__(kT) void maxpool_bwd_vec_kernel(const float4 *__restrict__ dy, const int4 *__restrict__ idx, int N,
                                                              int H, int W, int C4, int k, int st, int pd, int P, int Q,
                                                              float4 *__restrict__ dx) {
@@ -132,16 +133,36 @@ __global__ __launch_bounds__(kT) void maxpool_bwd_vec_kernel(const float4 *__res
         const int p_lo = max(0, (h + pd - k + st) / st), p_hi = min(P - 1, (h + pd) / st);
         const int q_lo = max(0, (w + pd - k + st) / st), q_hi = min(Q - 1, (w + pd) / st);
         const int me = h * W + w;
-        for (int p = p_lo; p <= p_hi; ++p)
-            for (int q = q_lo; q <= q_hi; ++q) {
+        if (kTwoByTwo) {  // at most 2 x 2 windows hold this pixel: all their loads are issued before the first is used
+            int4 id[4];
+            float4 g[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int p = p_lo + j / 2, q = q_lo + j % 2;
+                const bool ok = p <= p_hi && q <= q_hi;
                 const unsigned at = ((unsigned)(n * P + p) * Q + q) * (unsigned)C4 + c;
-                const int4 id = idx[at];
-                const float4 g = dy[at];
-                if (id.x == me) s.x += g.x;
-                if (id.y == me) s.y += g.y;
-                if (id.z == me) s.z += g.z;
-                if (id.w == me) s.w += g.w;
+                id[j] = ok ? idx[at] : make_int4(-1, -1, -1, -1);
+                g[j] = ok ? dy[at] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {  // same order as the loops below; a window that is not there adds nothing
+                if (id[j].x == me) s.x += g[j].x;
+                if (id[j].y == me) s.y += g[j].y;
+                if (id[j].z == me) s.z += g[j].z;
+                if (id[j].w == me) s.w += g[j].w;
+            }
+        } else {
+            for (int p = p_lo; p <= p_hi; ++p)
+                for (int q = q_lo; q <= q_hi; ++q) {
+                    const unsigned at = ((unsigned)(n * P + p) * Q + q) * (unsigned)C4 + c;
+                    const int4 id = idx[at];
+                    const float4 g = dy[at];
+                    if (id.x == me) s.x += g.x;
+                    if (id.y == me) s.y += g.y;
+                    if (id.z == me) s.z += g.z;
+                    if (id.w == me) s.w += g.w;
+                }
+        }
         dx[o] = s;
     }
 }
@@ -240,11 +261,18 @@ extern "C" int lpdt_maxpool_bwd(const float *dy, const int32_t *idx, int N, int 
     if (rc) return rc;
     LPDT_REQUIRE(dy && idx && dx, LPDT_EINVAL, "maxpool_bwd: NULL argument");
     const int P = conv_out(H, pd, k, st), Q = conv_out(W, pd, k, st);
-    if (pool_vec_ok(N, H, W, C) && aligned(dy, 16) && aligned(idx, 16) && aligned(dx, 16))
-        hipLaunchKernelGGL(maxpool_bwd_vec_kernel, dim3(grid1d((size_t)N * H * W * (C / 4))), dim3(kT), 0, as_stream(stream),
-                           reinterpret_cast<const float4 *>(dy), reinterpret_cast<const int4 *>(idx), N, H, W, C / 4, k, st, pd, P, Q,
-                           reinterpret_cast<float4 *>(dx));
-    else
+    if (pool_vec_ok(N, H, W, C) && aligned(dy, 16) && aligned(idx, 16) && aligned(dx, 16)) {
+        const dim3 grid(grid1d((size_t)N * H * W * (C / 4)));
+        const float4 *dy4 = reinterpret_cast<const float4 *>(dy);
+        const int4 *idx4 = reinterpret_cast<const int4 *>(idx);
+        float4 *dx4 = reinterpret_cast<float4 *>(dx);
+        if ((k + st - 1) / st <= 2)  // a pixel lies in at most ceil(k / stride) windows per direction
+            hipLaunchKernelGGL(maxpool_bwd_vec_kernel<true>, grid, dim3(kT), 0, as_stream(stream), dy4, idx4, N, H, W, C / 4, k, st,
+                               pd, P, Q, dx4);
+        else
+            hipLaunchKernelGGL(maxpool_bwd_vec_kernel<false>, grid, dim3(kT), 0, as_stream(stream), dy4, idx4, N, H, W, C / 4, k, st,
+                               pd, P, Q, dx4);
+    } else
         hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid1d((size_t)N * H * W * C)), dim3(kT), 0, as_stream(stream), dy, idx, N, H, W,
                            C, k, st, pd, P, Q, dx);
     return launch_status("lpdt_maxpool_bwd");
