@@ -278,9 +278,10 @@ def main():
     }
     if mix_ms:
         d, n = net.num_params(), cfg["agents"]
-        # bytes per parameter and agent: threshold scan 8 + candidate scan 8 + apply (x and state read, x written: 12;
-        # Deep-Squeeze rewrites its whole error memory: +4; push-sum writes the de-biased models: +4)
-        per_param = {"choco": 28, "quant_sgp": 32, "deepsqueeze": 32, "sparse_push": 36}[cfg.get("variant", "choco")] \
+        # bytes per parameter and agent: the selection reads x and the state once (8) after a 1/16 sample of them (0.5);
+        # apply reads both and writes x (12; Deep-Squeeze rewrites its whole error memory: +4; push-sum writes the
+        # de-biased models: +4)
+        per_param = {"choco": 20.5, "quant_sgp": 24.5, "deepsqueeze": 24.5, "sparse_push": 28.5}[cfg.get("variant", "choco")] \
             if cfg["mix"] == "choco" else 8
         out["gossip_mix_variant"] = cfg.get("variant", "plain")
         out["gossip_mix_bytes_per_param"] = per_param

@@ -12,8 +12,13 @@
 // the top 12 key bits over the full data; pass 2 copies the keys that fall in the
 // threshold bin (a fraction of a percent of the data for smooth distributions) to
 // a candidate list; the remaining 51 bits are resolved on the candidates only.
+// Large problems take ONE pass over the full data instead: a histogram of a sample of
+// the tiles guesses a window of bins around each threshold bin, the full pass counts
+// the keys above the window and keeps the window's keys, and a pair whose window turns
+// out to have missed the threshold bin is redone in the two-pass form (exact either way).
 #include "common.h"
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <type_traits>
 #include <vector>
@@ -50,6 +55,9 @@ struct PairState {        // one per (agent, segment)
     unsigned long long prefix;  // key bits fixed so far (right aligned); finally the threshold key
     unsigned int rank;          // the wanted key is the rank-th largest among keys matching prefix
     unsigned int cand;          // candidates stored
+    unsigned int lo, hi;        // one-pass selection: the window of 12-bit bins whose keys the full pass keeps
+    unsigned int redo;          // one-pass selection: the window missed the threshold bin, select this pair in two passes
+    unsigned int above;         // one-pass selection: number of keys in bins above the window
 };
 
 // ---- plain mix ---------------------------------------------------------------
@@ -97,25 +105,27 @@ __global__ void upload_kernel(UploadChunk c, long long *dst, int count) {
     if (i < count) dst[i] = c.v[i];
 }
 
-__global__ void choco_init_kernel(PairState *st, const long long *kk, int n, int nseg, unsigned int *hist, size_t hist_words) {
+__global__ void choco_init_kernel(PairState *st, const long long *kk, int n, int nseg, unsigned int *hist, size_t hist_words,
+                                  unsigned int *any_redo) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < hist_words) hist[i] = 0u;
+    if (i == 0) *any_redo = 0u;
     if (i < (size_t)n * nseg) {
         PairState s;
         s.prefix = 0ull;
         s.rank = (unsigned int)kk[i % nseg];
         s.cand = 0u;
+        s.lo = 0u; s.hi = 0u; s.redo = 0u; s.above = 0u;
         st[i] = s;
     }
 }
 
-__device__ __forceinline__ int find_segment(const long long *off, int nseg, long long e) {
-    int lo = 0, hi = nseg - 1;  // largest s with off[s] <= e
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (off[mid] <= e) lo = mid; else hi = mid - 1;
-    }
-    return lo;
+// The (non-empty) segment holding element e < off[nseg], found by the whole block at once: every thread tests the
+// segments tid, tid + blockDim, ..., so the block waits for one round of loads instead of a binary search's chain.
+// The caller's next __syncthreads() publishes *s_first.
+__device__ __forceinline__ void find_segment_block(const long long *__restrict__ off, int nseg, long long e, int *s_first) {
+    for (int s = threadIdx.x; s < nseg; s += blockDim.x)
+        if (off[s] <= e && e < off[s + 1]) *s_first = s;
 }
 
 // what is compressed: x - xhat (CHOCO) or x + delta (Deep-Squeeze), one fp32 operation
@@ -132,53 +142,97 @@ __device__ __forceinline__ void seek_segment(const long long *__restrict__ off, 
 }
 
 // Pass 1: histogram of key bits 62..51 (the top 12 bits of |v|).  VEC = 4: 16-byte loads (needs d % 4 == 0).
+// Blocks walk over the tiles blockIdx.x, blockIdx.x + gridDim.x, ...; with a tile list (the sample of the one-pass
+// selection) over the listed tiles instead.
+// any_redo != NULL: only the pairs marked `redo` are counted (normally none: the block leaves at once).
 template <int VEC>
-__global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
-                                                               size_t d, const long long *__restrict__ off, int nseg,
-                                                               unsigned int *__restrict__ hist, int ds) {
-    __shared__ unsigned int sh[4096];
-    __shared__ int s_first;
+__device__ __forceinline__ void hist_tile(long long tile, const float *__restrict__ x, const float *__restrict__ xhat, size_t d,
+                                          const long long *__restrict__ off, int nseg, unsigned int *__restrict__ hist, int ds,
+                                          const PairState *__restrict__ st, bool only_redo, unsigned int *sh, int *s_first,
+                                          int *s_last) {
     const int agent = blockIdx.y;
-    const long long e0 = (long long)blockIdx.x * kTile;
+    const long long e0 = tile * kTile;
     const long long e1 = min(e0 + (long long)kTile, (long long)d);
     for (int i = threadIdx.x; i < 4096; i += kGThreads) sh[i] = 0u;
-    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    find_segment_block(off, nseg, e0, s_first);
+    find_segment_block(off, nseg, e1 - 1, s_last);
     __syncthreads();
-    const int sfirst = s_first;
-    int s = sfirst;
-    long long end = off[s + 1];
+    const int sfirst = *s_first, slast = *s_last;
     const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
     unsigned int *gh_all = hist + (size_t)agent * nseg * kBins;
-    for (long long e = e0 + (long long)threadIdx.x * VEC; e < e1; e += (long long)kGThreads * VEC) {
+    // the thread's 16 elements (e0 + (it * kGThreads + tid) * VEC + u) as bin numbers, two per register
+    constexpr int kIters = 16 / VEC;
+    unsigned int bins[8];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const long long e = e0 + ((long long)it * kGThreads + threadIdx.x) * VEC;
         float xv[VEC], hv[VEC];
         if (VEC == 4) {
-            const float4 a = *reinterpret_cast<const float4 *>(xr + e), b = *reinterpret_cast<const float4 *>(hr + e);
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (e < e1) { a = *reinterpret_cast<const float4 *>(xr + e); b = *reinterpret_cast<const float4 *>(hr + e); }
             xv[0] = a.x; xv[1] = a.y; xv[2] = a.z; xv[3] = a.w;
             hv[0] = b.x; hv[1] = b.y; hv[2] = b.z; hv[3] = b.w;
         } else {
-            xv[0] = xr[e]; hv[0] = hr[e];
+            xv[0] = e < e1 ? xr[e] : 0.f; hv[0] = e < e1 ? hr[e] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < VEC; ++u) {
-            seek_segment(off, e + u, s, end);
+            const int j = it * VEC + u;
             const unsigned int bin = (__float_as_uint(compress_input(xv[u], hv[u], ds)) & 0x7fffffffu) >> 19;
-            if (s == sfirst) atomicAdd(&sh[bin], 1u);
-            else atomicAdd(&gh_all[(size_t)s * kBins + bin], 1u);
+            if (j % 2 == 0) bins[j / 2] = bin; else bins[j / 2] |= bin << 16;
         }
     }
-    __syncthreads();
-    unsigned int *gh = gh_all + (size_t)sfirst * kBins;
-    for (int i = threadIdx.x; i < 4096; i += kGThreads)
-        if (sh[i]) atomicAdd(&gh[i], sh[i]);
+    // One round per segment of the tile (almost always one): its elements into the LDS histogram, then the non-empty
+    // bins into the pair's histogram, clearing the LDS copy for the next round.  No per-element global atomics.
+    for (int sg = sfirst; sg <= slast; ++sg) {
+        const long long lo = max(off[sg], e0), hi = min(off[sg + 1], e1);  // the segment's part of the tile
+        if (lo >= hi) continue;                                            // (the same in every thread)
+        if (only_redo && !st[(size_t)agent * nseg + sg].redo) continue;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const long long e = e0 + ((long long)(j / VEC) * kGThreads + threadIdx.x) * VEC + j % VEC;
+            if (e >= lo && e < hi) atomicAdd(&sh[(bins[j / 2] >> (16 * (j % 2))) & 0xffffu], 1u);
+        }
+        __syncthreads();
+        unsigned int *gh = gh_all + (size_t)sg * kBins;
+        for (int i = threadIdx.x; i < 4096; i += kGThreads) {
+            const unsigned int c = sh[i];
+            if (c) { atomicAdd(&gh[i], c); sh[i] = 0u; }
+        }
+        __syncthreads();
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
+                                                               size_t d, const long long *__restrict__ off, int nseg,
+                                                               unsigned int *__restrict__ hist, int ds,
+                                                               const long long *__restrict__ tile_list, int ntiles,
+                                                               const PairState *__restrict__ st,
+                                                               const unsigned int *__restrict__ any_redo) {
+    __shared__ unsigned int sh[4096];
+    __shared__ int s_first, s_last;
+    if (any_redo && *any_redo == 0u) return;
+    for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        hist_tile<VEC>(tile_list ? tile_list[t] : (long long)t, x, xhat, d, off, nseg, hist, ds, st, any_redo != nullptr, sh,
+                       &s_first, &s_last);
+        __syncthreads();
+    }
 }
 
 // Finds, per (agent, segment), the bin holding the rank-th largest key; extends the
 // prefix by `bits`, reduces the rank to the rank inside that bin, clears the histogram.
-__global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__restrict__ st, unsigned int *__restrict__ hist, int bits) {
+// mode 0: the histogram covers all keys matching the prefix.
+// mode 1 (one-pass selection): it covers the bins of the guessed window [lo, hi] only and `above` counts the keys in
+//   higher bins; a pair whose threshold bin is not in the window drops its candidates and is marked `redo`.
+// mode 2: the marked pairs again, now with their full histogram; the others are left alone.
+__global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__restrict__ st, unsigned int *__restrict__ hist, int bits,
+                                                               int mode, unsigned int *__restrict__ any_redo) {
     __shared__ unsigned int part[kGThreads];
     __shared__ unsigned int s_above;
     __shared__ int s_thread;
     const int pair = blockIdx.x;
+    if (mode == 2 && (*any_redo == 0u || st[pair].redo == 0u)) return;
     unsigned int *h = hist + (size_t)pair * kBins;
     const int nb = 1 << bits, per = kBins / kGThreads;  // thread t owns bins [hi - per*t - per + 1, hi - per*t], descending
     const unsigned int rank = st[pair].rank;
@@ -197,14 +251,20 @@ __global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__rest
     part[threadIdx.x] = sum;
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned int run = 0;
-        int t = 0;
-        for (; t < kGThreads; ++t) {
-            if (run + part[t] >= rank) break;
-            run += part[t];
-        }
+        unsigned int run = mode == 1 ? st[pair].above : 0u;
+        int t = kGThreads;  // stays there when the threshold bin is not among the counted ones (mode 1 only)
+        if (run < rank)
+            for (t = 0; t < kGThreads; ++t) {
+                if (run + part[t] >= rank) break;
+                run += part[t];
+            }
         s_above = run;
-        s_thread = t;  // t < kGThreads because the matching keys number at least rank
+        s_thread = t;
+        if (t == kGThreads) {  // the window missed
+            st[pair].cand = 0u;
+            st[pair].redo = 1u;
+            atomicOr(any_redo, 1u);
+        }
     }
     __syncthreads();
     if ((int)threadIdx.x == s_thread) {
@@ -222,28 +282,234 @@ __global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__rest
     for (int i = threadIdx.x; i < kBins; i += kGThreads) h[i] = 0u;
 }
 
+// One-pass selection, step 1 of 2 (after a histogram of every stride-th tile): per (agent, segment), the window of bins
+// that holds the threshold bin with near certainty.  With ns of the segment's len elements sampled, the wanted rank
+// scales to r = rank * ns / len; the window spans the bins where the sample's count from the top reaches r - margin
+// and r + margin, margin = 5 sqrt(r) + r / 16 + 4 (sampling noise is about sqrt(r); the rest covers tiles that differ).
+// A fully sampled segment gets the exact bin, a segment without samples the whole range.  Clears the histogram.
+__global__ __launch_bounds__(kGThreads) void choco_guess_kernel(PairState *__restrict__ st, unsigned int *__restrict__ hist,
+                                                                const long long *__restrict__ off, int nseg) {
+    __shared__ unsigned int part[kGThreads];
+    __shared__ unsigned int s_lo, s_hi;
+    const int pair = blockIdx.x, seg = pair % nseg;
+    unsigned int *h = hist + (size_t)pair * kBins;
+    constexpr int per = kBins / kGThreads;  // thread t owns bins kBins-1 - per*t - k, k = 0..per-1 (descending)
+    unsigned int mine[per];
+    unsigned int sum = 0;
+    for (int k = 0; k < per; ++k) {
+        const int b = kBins - 1 - (threadIdx.x * per + k);
+        mine[k] = h[b];
+        sum += mine[k];
+        h[b] = 0u;
+    }
+    part[threadIdx.x] = sum;
+    if (threadIdx.x == 0) { s_lo = 0u; s_hi = kBins - 1; }
+    __syncthreads();
+    unsigned int before = 0, ns = 0;
+    for (int t = 0; t < kGThreads; ++t) {
+        if (t < (int)threadIdx.x) before += part[t];
+        ns += part[t];
+    }
+    const long long len = off[seg + 1] - off[seg];
+    const unsigned int rank = st[pair].rank;
+    if (ns == 0u || rank == 0u) {  // nothing sampled: keep every bin (small segments); empty segment: nothing to do
+        if (threadIdx.x == 0) { st[pair].lo = 0u; st[pair].hi = kBins - 1; }
+        return;
+    }
+    double r = (double)rank, margin = 0.0;
+    if ((long long)ns < len) {
+        r = (double)rank * (double)ns / (double)len;
+        margin = 5.0 * sqrt(r) + r / 16.0 + 4.0;
+    }
+    const double top = r - margin < 1.0 ? 1.0 : floor(r - margin);  // count from the top at which the window opens
+    const double bot = ceil(r + margin);                             // ... and closes (past the sample: down to bin 0)
+    // the thread whose bins hold the top-th / bot-th largest sampled key writes that bin
+    unsigned int run = before;
+    for (int k = 0; k < per; ++k) {
+        const unsigned int b = (unsigned int)(kBins - 1 - (threadIdx.x * per + k));
+        const unsigned int next = run + mine[k];
+        if ((double)run < top && top <= (double)next) s_hi = b;
+        if ((double)run < bot && bot <= (double)next) s_lo = b;
+        run = next;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { st[pair].lo = s_lo; st[pair].hi = s_hi; }
+}
+
+// One-pass selection, step 2 of 2: the only pass over all the data.  Per pair it counts the keys in bins above the window
+// (`above`), histograms the window's bins and keeps the window's keys, which is all the scan needs to find the threshold
+// bin inside the window and the refinement to finish there.  The bulk of the elements (below the window) cost a
+// subtraction and two compares each: no atomics, so the pass runs at streaming speed.  A thread loads its 16 elements
+// up front and notes the window's elements in a bit mask; each wave then reserves room in the pair's list for all its
+// keys with one atomic and stores them from registers.  Elements of the tile that lie past its first segment (tiles
+// with a segment boundary) are handled afterwards, one by one, with the windows of up to kSegCache following segments
+// held in LDS.
+constexpr int kSegCache = 32;
+static_assert(kTile == kGThreads * 16, "one candidate bit per element of a thread: 16 elements per thread and tile");
+template <int VEC>
+__global__ __launch_bounds__(kGThreads) void choco_window_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
+                                                                 size_t d, const long long *__restrict__ off, int nseg,
+                                                                 unsigned int *__restrict__ hist, PairState *__restrict__ st,
+                                                                 unsigned long long *__restrict__ cand,
+                                                                 unsigned int *__restrict__ tile_count, int ds) {
+    __shared__ unsigned int sh[4096];
+    __shared__ unsigned int wave_keys[kGThreads / kWave];
+    __shared__ long long c_end[kSegCache];
+    __shared__ unsigned int c_lo[kSegCache], c_hi[kSegCache], c_above[kSegCache];
+    __shared__ int s_first, s_last;
+    __shared__ unsigned int s_above;
+    const int agent = blockIdx.y;
+    const long long e0 = (long long)blockIdx.x * kTile;
+    const long long e1 = min(e0 + (long long)kTile, (long long)d);
+    constexpr int kIters = 16 / VEC;
+    const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
+    float xv[16], hv[16];  // element j = it * VEC + u of this thread: e0 + (it * kGThreads + threadIdx.x) * VEC + u
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const long long e = e0 + ((long long)it * kGThreads + threadIdx.x) * VEC;
+        if (VEC == 4) {
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (e < e1) { a = *reinterpret_cast<const float4 *>(xr + e); b = *reinterpret_cast<const float4 *>(hr + e); }
+            xv[it * 4 + 0] = a.x; xv[it * 4 + 1] = a.y; xv[it * 4 + 2] = a.z; xv[it * 4 + 3] = a.w;
+            hv[it * 4 + 0] = b.x; hv[it * 4 + 1] = b.y; hv[it * 4 + 2] = b.z; hv[it * 4 + 3] = b.w;
+        } else {
+            xv[it] = e < e1 ? xr[e] : 0.f;
+            hv[it] = e < e1 ? hr[e] : 0.f;
+        }
+    }
+    find_segment_block(off, nseg, e0, &s_first);
+    find_segment_block(off, nseg, e1 - 1, &s_last);
+    if (threadIdx.x == 0) s_above = 0u;
+    __syncthreads();
+    const int sfirst = s_first;
+    const int nlater = s_last - sfirst;                       // segments of the tile after its first
+    const int ncached = nlater < kSegCache ? nlater : kSegCache;
+    PairState *pairs = st + (size_t)agent * nseg;
+    if ((int)threadIdx.x < ncached) {
+        const int sg = sfirst + 1 + threadIdx.x;
+        c_end[threadIdx.x] = off[sg + 1];
+        c_lo[threadIdx.x] = pairs[sg].lo;
+        c_hi[threadIdx.x] = pairs[sg].hi;
+        c_above[threadIdx.x] = 0u;
+    }
+    const long long first_begin = off[sfirst], first_end = off[sfirst + 1];
+    PairState *pfirst = &pairs[sfirst];
+    const unsigned int first_lo = pfirst->lo, first_hi = pfirst->hi, span = first_hi - first_lo;  // lo <= hi
+    for (unsigned int i = first_lo + threadIdx.x; i <= first_hi; i += kGThreads) sh[i] = 0u;
+    __syncthreads();
+    unsigned int *gh_all = hist + (size_t)agent * nseg * kBins;
+    unsigned long long *clist = cand + (size_t)agent * d;
+    unsigned int marks = 0u, later = 0u, above = 0u;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const long long e = e0 + ((long long)(j / VEC) * kGThreads + threadIdx.x) * VEC + j % VEC;
+        if (e >= e1) continue;
+        if (e >= first_end) { later |= 1u << j; continue; }
+        const unsigned int bin = (__float_as_uint(compress_input(xv[j], hv[j], ds)) & 0x7fffffffu) >> 19;
+        if (bin - first_lo <= span) {
+            atomicAdd(&sh[bin], 1u);
+            marks |= 1u << j;
+        }
+        above += bin > first_hi ? 1u : 0u;
+    }
+    // The keys of the tile's first segment go to the tile's own place in the pair's list, cand[e0 ...] (a tile has at
+    // most as many keys as elements, so tiles never collide and nothing has to be reserved), packed: exclusive prefix
+    // sum of the lanes' counts in the wave, then of the waves' totals.  tile_count tells the refinement how many.
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const unsigned int mine = (unsigned int)__popc(marks);
+    unsigned int incl = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const unsigned int v = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += v;
+    }
+    if (lane == kWave - 1) wave_keys[wave] = incl;
+    __syncthreads();
+    {
+        unsigned int before = 0u, total = 0u;
+#pragma unroll
+        for (int w = 0; w < kGThreads / kWave; ++w) {
+            if (w < wave) before += wave_keys[w];
+            total += wave_keys[w];
+        }
+        if (threadIdx.x == 0) tile_count[(size_t)agent * gridDim.x + blockIdx.x] = total;
+        unsigned long long *dst = clist + e0 + before + (incl - mine);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (marks & (1u << j)) {
+                const long long e = e0 + ((long long)(j / VEC) * kGThreads + threadIdx.x) * VEC + j % VEC;
+                *dst++ = make_key(xv[j], hv[j], (unsigned int)(e - first_begin), ds);
+            }
+        }
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) above += __shfl_xor(above, o, kWave);
+    if (lane == 0 && above) atomicAdd(&s_above, above);
+    // the tile's elements past its first segment (ascending e per thread, so the segment index only moves forward)
+    if (later) {
+        int k = 0;
+        int sg = sfirst + 1 + ncached;     // for segments beyond the cached ones
+        long long end_g = 0, begin_g = 0;
+        bool walking = false;
+        while (later) {
+            const int j = __ffs(later) - 1;
+            later &= later - 1u;
+            const long long e = e0 + ((long long)(j / VEC) * kGThreads + threadIdx.x) * VEC + j % VEC;
+            const float xe = xr[e], he = hr[e];
+            const unsigned int bin = (__float_as_uint(compress_input(xe, he, ds)) & 0x7fffffffu) >> 19;
+            while (k < ncached && e >= c_end[k]) ++k;
+            if (k < ncached) {
+                const long long begin = k ? c_end[k - 1] : first_end;
+                const int sk = sfirst + 1 + k;
+                if (bin > c_hi[k]) {
+                    atomicAdd(&c_above[k], 1u);
+                } else if (bin >= c_lo[k]) {
+                    atomicAdd(&gh_all[(size_t)sk * kBins + bin], 1u);
+                    clist[begin + atomicAdd(&pairs[sk].cand, 1u)] = make_key(xe, he, (unsigned int)(e - begin), ds);
+                }
+            } else {  // more segments in this tile than the cache holds: straight from memory
+                if (!walking) { walking = true; begin_g = off[sg]; end_g = off[sg + 1]; }
+                while (e >= end_g) { ++sg; begin_g = end_g; end_g = off[sg + 1]; }
+                PairState *ps = &pairs[sg];
+                if (bin > ps->hi) {
+                    atomicAdd(&ps->above, 1u);
+                } else if (bin >= ps->lo) {
+                    atomicAdd(&gh_all[(size_t)sg * kBins + bin], 1u);
+                    clist[begin_g + atomicAdd(&ps->cand, 1u)] = make_key(xe, he, (unsigned int)(e - begin_g), ds);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    unsigned int *gh = gh_all + (size_t)sfirst * kBins;
+    for (unsigned int i = first_lo + threadIdx.x; i <= first_hi; i += kGThreads)
+        if (sh[i]) atomicAdd(&gh[i], sh[i]);
+    if (threadIdx.x == 0 && s_above) atomicAdd(&pfirst->above, s_above);
+    if ((int)threadIdx.x < ncached && c_above[threadIdx.x]) atomicAdd(&pairs[sfirst + 1 + threadIdx.x].above, c_above[threadIdx.x]);
+}
+
 // Pass 2: copy the keys whose top 12 bits equal the prefix to the candidate list of
 // their (agent, segment); the list lives at the segment's own offset in `cand`.
 // Matches of the block's first segment are gathered in LDS and get their room in the list
 // with one global atomic per block; the (few) elements of later segments in the same tile
 // reserve their slots one by one.
 template <int VEC>
-__global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
-                                                                  size_t d, const long long *__restrict__ off, int nseg,
-                                                                  PairState *__restrict__ st,
-                                                                  unsigned long long *__restrict__ cand, int ds) {
-    __shared__ unsigned long long stage[kTile];
-    __shared__ int s_first;
-    __shared__ unsigned int s_count, s_base;
+__device__ __forceinline__ void collect_tile(long long tile, const float *__restrict__ x, const float *__restrict__ xhat, size_t d,
+                                             const long long *__restrict__ off, int nseg, PairState *__restrict__ st,
+                                             unsigned long long *__restrict__ cand, int ds, bool only_redo,
+                                             unsigned long long *stage, int *s_first, unsigned int *s_count, unsigned int *s_base) {
     const int agent = blockIdx.y;
-    const long long e0 = (long long)blockIdx.x * kTile;
+    const long long e0 = tile * kTile;
     const long long e1 = min(e0 + (long long)kTile, (long long)d);
-    if (threadIdx.x == 0) { s_first = find_segment(off, nseg, e0); s_count = 0u; }
+    find_segment_block(off, nseg, e0, s_first);
+    if (threadIdx.x == 0) *s_count = 0u;
     __syncthreads();
-    const int sfirst = s_first;
+    const int sfirst = *s_first;
     int s = sfirst;
     long long end = off[s + 1], begin = off[s];
-    const unsigned long long first_prefix = st[(size_t)agent * nseg + sfirst].prefix;
+    // a pair that is not to be collected gets a prefix no key has (keys >> 51 are below 2^12)
+    const PairState first = st[(size_t)agent * nseg + sfirst];
+    const unsigned long long first_prefix = (only_redo && !first.redo) ? ~0ull : first.prefix;
     const float *xr = x + (size_t)agent * d, *hr = xhat + (size_t)agent * d;
     for (long long e = e0 + (long long)threadIdx.x * VEC; e < e1; e += (long long)kGThreads * VEC) {
         float xv[VEC], hv[VEC];
@@ -259,20 +525,39 @@ __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *_
             if (e + u >= end) { seek_segment(off, e + u, s, end); begin = off[s]; }
             const unsigned long long key = make_key(xv[u], hv[u], (unsigned int)(e + u - begin), ds);
             if (s == sfirst) {
-                if ((key >> 51) == first_prefix) stage[atomicAdd(&s_count, 1u)] = key;
+                if ((key >> 51) == first_prefix) stage[atomicAdd(s_count, 1u)] = key;
             } else {
                 PairState *ps = &st[(size_t)agent * nseg + s];
-                if ((key >> 51) == ps->prefix) cand[(size_t)agent * d + begin + atomicAdd(&ps->cand, 1u)] = key;
+                if ((key >> 51) == ps->prefix && (!only_redo || ps->redo))
+                    cand[(size_t)agent * d + begin + atomicAdd(&ps->cand, 1u)] = key;
             }
         }
     }
     __syncthreads();
-    const unsigned int count = s_count;
+    const unsigned int count = *s_count;
     if (count == 0u) return;
-    if (threadIdx.x == 0) s_base = atomicAdd(&st[(size_t)agent * nseg + sfirst].cand, count);
+    if (threadIdx.x == 0) *s_base = atomicAdd(&st[(size_t)agent * nseg + sfirst].cand, count);
     __syncthreads();
-    unsigned long long *dst = cand + (size_t)agent * d + off[sfirst] + s_base;
+    unsigned long long *dst = cand + (size_t)agent * d + off[sfirst] + *s_base;
     for (unsigned int i = threadIdx.x; i < count; i += kGThreads) dst[i] = stage[i];
+}
+
+// Blocks walk over the tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+// any_redo != NULL: the second collection of the one-pass selection, only for the pairs marked `redo` (normally none).
+template <int VEC>
+__global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *__restrict__ x, const float *__restrict__ xhat,
+                                                                  size_t d, const long long *__restrict__ off, int nseg,
+                                                                  PairState *__restrict__ st,
+                                                                  unsigned long long *__restrict__ cand, int ds, int ntiles,
+                                                                  const unsigned int *__restrict__ any_redo) {
+    __shared__ unsigned long long stage[kTile];
+    __shared__ int s_first;
+    __shared__ unsigned int s_count, s_base;
+    if (any_redo && *any_redo == 0u) return;
+    for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        collect_tile<VEC>(t, x, xhat, d, off, nseg, st, cand, ds, any_redo != nullptr, stage, &s_first, &s_count, &s_base);
+        __syncthreads();
+    }
 }
 
 // Refinement: one block per (agent, segment) finishes the selection among the pair's candidates (the keys sharing the
@@ -281,7 +566,7 @@ __global__ __launch_bounds__(kGThreads) void choco_collect_kernel(const float *_
 // the first round the survivors are normally a handful: they are copied to LDS and the remaining rounds never touch
 // memory; if they do not fit (massive ties) the rounds keep streaming the candidate list.  On exit prefix = the full
 // 63-bit key of the k-th largest element.
-constexpr int kRefThreads = 512;
+constexpr int kRefThreads = 1024;
 constexpr int kRefList = 2048;
 
 // Bin of the rank-th largest key in a histogram of nb bins (descending bin order), and how many keys lie above it.
@@ -314,9 +599,13 @@ __device__ __forceinline__ void select_bin(const unsigned int *hist, int nb, uns
     __syncthreads();
 }
 
+// tile_count != NULL (one-pass selection): a pair's candidates are the list at its segment's offset (keys of the part of
+// the segment that shares a tile with earlier segments; `cand` of them) plus, for every tile that starts inside the
+// segment, tile_count keys at the tile's own offset.  A pair marked `redo` was collected again into the plain list.
 __global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigned long long *__restrict__ cand, size_t d,
                                                                    const long long *__restrict__ off, int nseg,
-                                                                   PairState *__restrict__ st) {
+                                                                   PairState *__restrict__ st,
+                                                                   const unsigned int *__restrict__ tile_count) {
     __shared__ unsigned int hist[8192];
     __shared__ unsigned long long list[kRefList];
     __shared__ unsigned int wave_tot[kRefThreads / 64];
@@ -324,8 +613,35 @@ __global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigne
     const int pair = blockIdx.x, agent = pair / nseg, seg = pair % nseg;
     const PairState ps = st[pair];
     if (ps.rank == 0u) return;  // empty segment: the scan has set the prefix that selects nothing
-    const unsigned long long *c = cand + (size_t)agent * d + off[seg];
+    const long long begin = off[seg], end = off[seg + 1];
+    const unsigned long long *ca = cand + (size_t)agent * d;
     const unsigned int count = ps.cand;
+    const bool tiled = tile_count != nullptr && ps.redo == 0u;
+    const long long t0 = (begin + kTile - 1) / kTile, t1 = (end + kTile - 1) / kTile;  // tiles starting in [begin, end)
+    const unsigned int ntiles_all = (unsigned int)((d + kTile - 1) / kTile);
+    const unsigned int *tc = tiled ? tile_count + (size_t)agent * ntiles_all : nullptr;
+    auto for_each_candidate = [&](auto f) {
+        for (unsigned int i = threadIdx.x; i < count; i += kRefThreads) f(ca[begin + i]);
+        if (tiled) {
+            // 64 threads share a tile (tiles hold some tens of keys for smooth data) and a wave has 4 tiles in flight:
+            // their counts are fetched together, then their first keys
+            constexpr long long kPerRound = (long long)(kRefThreads / 64) * 4;
+            const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+            for (long long tb = t0 + wave * 4; tb < t1; tb += kPerRound) {
+                unsigned int cnt[4];
+                unsigned long long first[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) cnt[q] = tb + q < t1 ? tc[tb + q] : 0u;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) first[q] = (unsigned int)lane < cnt[q] ? ca[(tb + q) * kTile + lane] : 0ull;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if ((unsigned int)lane < cnt[q]) f(first[q]);
+                    for (unsigned int slot = (unsigned int)lane + 64u; slot < cnt[q]; slot += 64u) f(ca[(tb + q) * kTile + slot]);
+                }
+            }
+        }
+    };
     unsigned long long prefix = ps.prefix;
     unsigned int rank = ps.rank, listed = 0;
     bool in_lds = false;
@@ -341,10 +657,9 @@ __global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigne
                 if ((key >> (shift + bits)) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
             }
         } else {
-            for (unsigned int i = threadIdx.x; i < count; i += kRefThreads) {
-                const unsigned long long key = c[i];
+            for_each_candidate([&](unsigned long long key) {
                 if ((key >> (shift + bits)) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
-            }
+            });
         }
         __syncthreads();
         select_bin(hist, nb, rank, wave_tot, &s_bin, &s_above);
@@ -353,10 +668,9 @@ __global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigne
         if (r == 0 && hist[s_bin] <= (unsigned int)kRefList) {  // the same decision in every thread
             if (threadIdx.x == 0) s_cnt = 0u;
             __syncthreads();
-            for (unsigned int i = threadIdx.x; i < count; i += kRefThreads) {
-                const unsigned long long key = c[i];
+            for_each_candidate([&](unsigned long long key) {
                 if ((key >> shift) == prefix) list[atomicAdd(&s_cnt, 1u)] = key;
-            }
+            });
             __syncthreads();
             listed = s_cnt;
             in_lds = true;
@@ -378,7 +692,7 @@ __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__res
     __shared__ unsigned long long sprefix[NMAX];        // thresholds of the block's first segment
     __shared__ float sh[NMAX][VEC][kGThreads];          // this thread's columns of xhat (after the update)
     const long long e0 = (long long)blockIdx.x * kGThreads * VEC;
-    if (threadIdx.x == 0) s_first = find_segment(off, nseg, e0);
+    find_segment_block(off, nseg, e0, &s_first);
     __syncthreads();
     const int sfirst = s_first;
     if ((int)threadIdx.x < n) sprefix[threadIdx.x] = select_all ? 0ull : st[(size_t)threadIdx.x * nseg + sfirst].prefix;
@@ -488,7 +802,7 @@ __global__ void copy_small_kernel(const float *__restrict__ src, float *__restri
 }
 
 struct ChocoLayout {
-    size_t off_bytes, k_bytes, state_bytes, hist_bytes, cand_bytes, total;
+    size_t off_bytes, k_bytes, state_bytes, hist_bytes, cand_bytes, flag_bytes, tile_bytes, list_bytes, total;
 };
 static ChocoLayout choco_layout(int n, size_t d, int nseg) {
     ChocoLayout L;
@@ -497,7 +811,10 @@ static ChocoLayout choco_layout(int n, size_t d, int nseg) {
     L.state_bytes = round_up((size_t)n * nseg * sizeof(PairState), 256);
     L.hist_bytes = round_up((size_t)n * nseg * kBins * sizeof(unsigned int), 256);
     L.cand_bytes = round_up((size_t)n * d * sizeof(unsigned long long), 256);
-    L.total = L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes + L.cand_bytes;
+    L.flag_bytes = 256;
+    L.tile_bytes = round_up((size_t)n * ((d + kTile - 1) / kTile) * sizeof(unsigned int), 256);
+    L.list_bytes = round_up(((d + kTile - 1) / kTile + 1) * sizeof(long long), 256);  // the sampled tiles
+    L.total = L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes + L.cand_bytes + L.flag_bytes + L.tile_bytes + L.list_bytes;
     return L;
 }
 
@@ -539,6 +856,17 @@ static bool compact_graph(const MixGraph &g, int n, MixGraph4 *c) {
         for (int t = 0; t < g.deg[i]; ++t) { c->w[i][t] = g.w[i][t]; c->nbr[i][t] = g.nbr[i][t]; }
     }
     return true;
+}
+
+// Tile stride of the sample for the one-pass selection, or 0 for the two-pass form.  Below some tens of millions of
+// elements the three extra (small) launches cost more than the saved pass.  LPDT_CHOCO_SAMPLE_STRIDE overrides the
+// choice (0: always two passes; s > 0: one pass with every s-th tile sampled, whatever the size): for tests and tuning.
+static int one_pass_stride(int n, size_t d) {
+    if (const char *e = std::getenv("LPDT_CHOCO_SAMPLE_STRIDE")) {
+        const int v = std::atoi(e);
+        return v < 0 ? 0 : v > 4096 ? 4096 : v;
+    }
+    return (size_t)n * d >= ((size_t)32 << 20) ? 16 : 0;
 }
 
 template <typename F>
@@ -654,16 +982,57 @@ static int mix_impl(float *x, float *state, int n, size_t d, const float *W, flo
         if (!select_all) {
             upload(kk.data(), nseg, d_k, st);
             const size_t hist_words = (size_t)n * nseg * kBins;
+            unsigned int *d_redo = reinterpret_cast<unsigned int *>(base + L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes + L.cand_bytes);
+            unsigned int *d_tiles = d_redo + L.flag_bytes / sizeof(unsigned int);
             hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
-                               nseg, d_hist, hist_words);
-            const dim3 tiles((unsigned int)((d + kTile - 1) / kTile), n);
+                               nseg, d_hist, hist_words, d_redo);
+            const unsigned int ntiles = (unsigned int)((d + kTile - 1) / kTile);
+            const dim3 tiles(ntiles, n);
             const bool vec4 = d % 4 == 0 && aligned(x, 16) && aligned(xhat, 16);
-            if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi);
-            else hipLaunchKernelGGL(choco_hist_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi);
-            hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12);
-            if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi);
-            else hipLaunchKernelGGL(choco_collect_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi);
-            hipLaunchKernelGGL(choco_refine_kernel, dim3(n * nseg), dim3(kRefThreads), 0, st, d_cand, d, d_off, nseg, d_st);
+            const int stride = one_pass_stride(n, d);
+            const long long *no_list = nullptr;
+            const unsigned int *none = nullptr;
+            if (stride > 0) {
+                // One pass over the data instead of two: a histogram of a sample of the tiles guesses, per pair, a window
+                // of bins around the threshold bin; the full pass counts the keys above the window, histograms the
+                // window and keeps its keys; the scan finds the threshold bin in the window.  A pair whose window
+                // missed (tiles that differ a lot from the sampled ones) goes through the two-pass form afterwards:
+                // three launches that end at once when there is none.  The result is exact either way.
+                // The sample: every stride-th tile, and every tile with a segment boundary in it, so that short
+                // segments are sampled completely and each longer one at least in the tiles of its two ends.
+                std::vector<char> mark(ntiles, 0);
+                for (unsigned int t = 0; t < ntiles; t += (unsigned int)stride) mark[t] = 1;
+                for (int sg = 1; sg < nseg; ++sg)
+                    if (off[sg] > 0 && off[sg] < (long long)d && off[sg] % kTile != 0) mark[(size_t)(off[sg] / kTile)] = 1;
+                std::vector<long long> list;
+                for (unsigned int t = 0; t < ntiles; ++t)
+                    if (mark[t]) list.push_back((long long)t);
+                long long *d_list = reinterpret_cast<long long *>(reinterpret_cast<char *>(d_tiles) + L.tile_bytes);
+                upload(list.data(), (int)list.size(), d_list, st);
+                const dim3 sampled((unsigned int)list.size(), n), few(ntiles < 128u ? ntiles : 128u, n);
+                const int nl = (int)list.size(), nt = (int)ntiles;
+                const unsigned int *redo = d_redo;
+                if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, sampled, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi, (const long long *)d_list, nl, d_st, none);
+                else hipLaunchKernelGGL(choco_hist_kernel<1>, sampled, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi, (const long long *)d_list, nl, d_st, none);
+                hipLaunchKernelGGL(choco_guess_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, d_off, nseg);
+                if (vec4) hipLaunchKernelGGL(choco_window_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, d_st, d_cand, d_tiles, dsi);
+                else hipLaunchKernelGGL(choco_window_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, d_st, d_cand, d_tiles, dsi);
+                hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12, 1, d_redo);
+                if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, few, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi, no_list, nt, d_st, redo);
+                else hipLaunchKernelGGL(choco_hist_kernel<1>, few, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi, no_list, nt, d_st, redo);
+                hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12, 2, d_redo);
+                if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, few, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi, nt, redo);
+                else hipLaunchKernelGGL(choco_collect_kernel<1>, few, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi, nt, redo);
+            } else {
+                const int nt = (int)ntiles;
+                if (vec4) hipLaunchKernelGGL(choco_hist_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi, no_list, nt, d_st, none);
+                else hipLaunchKernelGGL(choco_hist_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_hist, dsi, no_list, nt, d_st, none);
+                hipLaunchKernelGGL(choco_scan_kernel, dim3(n * nseg), dim3(kGThreads), 0, st, d_st, d_hist, 12, 0, d_redo);
+                if (vec4) hipLaunchKernelGGL(choco_collect_kernel<4>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi, nt, none);
+                else hipLaunchKernelGGL(choco_collect_kernel<1>, tiles, dim3(kGThreads), 0, st, x, xhat, d, d_off, nseg, d_st, d_cand, dsi, nt, none);
+            }
+            hipLaunchKernelGGL(choco_refine_kernel, dim3(n * nseg), dim3(kRefThreads), 0, st, d_cand, d, d_off, nseg, d_st,
+                               stride > 0 ? (const unsigned int *)d_tiles : (const unsigned int *)nullptr);
         }
         const bool vec2 = n <= 16 && d % 2 == 0 && aligned(x, 8) && aligned(xhat, 8) && (!z || aligned(z, 8));
         dispatch_nmax(n, [&](auto tag) {

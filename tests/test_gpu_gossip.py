@@ -55,6 +55,53 @@ def test_choco_global_topk_and_ties(orc):
     _choco_case(orc, 2, 50000, [0, 10, 50000], 0.5, 0.5, 828, ties=True)
 
 
+@pytest.fixture
+def sample_stride(monkeypatch):
+    """Forces the one-pass top-k (window of bins guessed from every s-th 4096-element tile) at any size."""
+    def set_stride(s):
+        monkeypatch.setenv("LPDT_CHOCO_SAMPLE_STRIDE", str(s))
+    return set_stride
+
+
+@pytest.mark.parametrize("stride", [1, 3, 16])
+def test_choco_one_pass_selection(orc, sample_stride, stride):
+    # the same cases as the two-pass form: the selection is exact whichever path finds it
+    sample_stride(stride)
+    seg = [0, 432, 448, 464, 480, 2784, 2800, 2816, 2832, 20000, 20001, 20001, 20010, 60000]
+    _choco_case(orc, 16, 60000, seg, 0.01, 0.3, 810)
+    _choco_case(orc, 8, 100_003, None, 0.01, 0.2, 820)
+    _choco_case(orc, 5, 9000, [0, 100, 4500, 9000], 0.05, 0.4, 822, ties=True)
+    _choco_case(orc, 3, 60000, [0, 60000], 0.3, 0.5, 826, ties=True)
+    _choco_case(orc, 2, 50000, [0, 10, 50000], 0.5, 0.5, 828, ties=True)
+    _choco_case(orc, 6, 300_000, [0, 150_000, 150_064, 300_000], 0.01, 0.7, 832)
+    _choco_case(orc, 4, 200_000, [0, 200_000], 0.002, 1.0, 834)
+
+
+@pytest.mark.parametrize("loud", ["unsampled", "sampled"])
+def test_choco_one_pass_window_misses(orc, sample_stride, loud):
+    """Sampled tiles that say nothing about the rest: the guessed window misses the threshold bin and the pair is
+    collected a second time; other pairs of the same call keep their first collection."""
+    sample_stride(4)
+    n, tile, ntiles = 3, 4096, 24
+    d = tile * ntiles + 1000
+    seg = [0, tile * 12, d]
+    g = wl.rng(840)
+    x = (g.standard_normal((n, d)) * 1e-3).astype(np.float32)
+    xhat = np.zeros((n, d), np.float32)
+    big = np.zeros(d, bool)
+    for t in range(12):   # first segment only: tiles 0, 4, 8 are the sampled ones
+        if (t % 4 == 0) == (loud == "sampled"):
+            big[t * tile:(t + 1) * tile] = True
+    x[:, big] *= 1000.0
+    Wm = wl.ring_matrix(n)
+    for rho in (0.01, 0.2, 0.6):
+        ref_x, ref_h = orc.gossip_mix(x, xhat, Wm, eta=0.5, keep_ratio=rho, seg_offsets=seg)
+        xd, hd = dev(x), dev(xhat)
+        lpdt.gossip_mix(xd, hd, Wm, rate=0.5, keep_ratio=rho, seg_offsets=seg)
+        assert np.array_equal(host(hd), ref_h), f"rho={rho}: xhat must be bit-exact"
+        assert_close(host(xd), ref_x, 1e-5, float(np.abs(x).max()), "choco mix")
+
+
 def test_choco_no_compression(orc):
     _choco_case(orc, 8, 5000, [0, 1200, 5000], 1.0, 1.0, 830)
 
