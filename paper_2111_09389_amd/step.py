@@ -14,6 +14,11 @@ Per quantized convolution (Section 3, "Low Precision Training"):
             dW   = sG*sX * conv_bwd_weight(Gq, Xq)      (fp32, never re-quantized)
 Range-EvoNorm hands the abs-max of its outputs to the quantizer that follows it, so that
 quantizer makes a single pass.
+
+The weight-gradient products have no consumer before the SGD update, so `run()` issues them
+on a second stream (default priority) behind an event recorded after the gradient quantizer,
+and the main stream waits for that stream once, before the update: they fill the gaps the
+chain of backward-data / normalisation kernels leaves on the chip.
 """
 import ctypes
 
@@ -35,8 +40,9 @@ class TrainStep:
     (then `upstream` must be the gradient of the last tensor)."""
 
     def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5,
-                 wgrad_16bit=False):
+                 wgrad_16bit=False, overlap_wgrad=True):
         self.L = lib()
+        self.overlap_wgrad = overlap_wgrad
         self.net, self.N, self.lr, self.seed, self.eps = net, batch, lr, seed, eps
         # gradient bifurcation as the paper states it: weight gradients from a bfloat16 copy of the layer gradient
         # (the 8-bit codes still feed backward-data), for every layer but the one that reads the image; default: both
@@ -64,6 +70,7 @@ class TrainStep:
         self.calls = []                  # (function, [args...], sr_layer or None)
         self.ws = torch.empty(1, dtype=torch.uint8, device=self.dev)
         self._ws_need = 256
+        self._ws_side_need = 256
         self.loss = None
         consumers = {}
         for op in net.ops:
@@ -76,19 +83,31 @@ class TrainStep:
         self.ws = torch.empty(self._ws_need + 256, dtype=torch.uint8, device=self.dev)
         off = (-self.ws.data_ptr()) % 256
         self._ws_ptr, self._ws_bytes = _vp(self.ws.data_ptr() + off), _sz(self._ws_need)
+        # the calls of the second stream have a workspace of their own
+        self.ws_side = torch.empty(self._ws_side_need + 256, dtype=torch.uint8, device=self.dev)
+        off = (-self.ws_side.data_ptr()) % 256
+        side_ptr, side_bytes = _vp(self.ws_side.data_ptr() + off), _sz(self._ws_side_need)
         for c in self.calls:             # workspace arguments were planned as placeholders
             for i, a in enumerate(c[1]):
                 if a == "WS":
-                    c[1][i] = self._ws_ptr
+                    c[1][i] = side_ptr if c[3] else self._ws_ptr
                 elif a == "WSB":
-                    c[1][i] = self._ws_bytes
+                    c[1][i] = side_bytes if c[3] else self._ws_bytes
+        self._side_stream = torch.cuda.Stream(device=self.dev) if self.dev.type == "cuda" else None   # default priority
+        self._fork_events = [torch.cuda.Event() for c in self.calls if c[3]] if self._side_stream else []
+        self._join_event = torch.cuda.Event() if self._side_stream else None
 
     # ------------------------------------------------------------------ planning helpers
-    def _need_ws(self, nbytes):
-        self._ws_need = max(self._ws_need, int(nbytes))
+    def _need_ws(self, nbytes, side=False):
+        if side:
+            self._ws_side_need = max(self._ws_side_need, int(nbytes))
+        else:
+            self._ws_need = max(self._ws_need, int(nbytes))
 
-    def _emit(self, fn, args, sr_layer=None):
-        self.calls.append((fn, list(args), sr_layer))
+    def _emit(self, fn, args, sr_layer=None, side=False):
+        """side: the call may run on the second stream (its inputs are final when it is issued and nothing
+        before the SGD update reads its output)."""
+        self.calls.append((fn, list(args), sr_layer, bool(side and self.overlap_wgrad)))
 
     def _quantize(self, src, q, scale, rounding, absmax=None, sr_layer=None):
         n = src.numel()
@@ -229,13 +248,13 @@ class TrainStep:
                     g16 = torch.empty(dy.shape, dtype=torch.int16, device=self.dev)
                     self._keep.append(g16)
                     self._emit(L.lpdt_to_bf16, [_p(dy), _sz(dy.numel()), _p(g16)])
-                    self._need_ws(L.lpdt_qconv_bwd_weight_bf16_workspace_bytes(ctypes.byref(d)))
+                    self._need_ws(L.lpdt_qconv_bwd_weight_bf16_workspace_bytes(ctypes.byref(d)), side=self.overlap_wgrad)
                     self._emit(L.lpdt_qconv_bwd_weight_bf16, [ctypes.byref(d), _p(g16), _p(self.xq[inp]), _p(self.sx[inp]), _p(gw),
-                                                              "WS", "WSB"])
+                                                              "WS", "WSB"], side=True)
                 else:
-                    self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)))
+                    self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)), side=self.overlap_wgrad)
                     self._emit(L.lpdt_qconv_bwd_weight_f32, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(sg), _p(self.sx[inp]),
-                                                             _p(gw), "WS", "WSB"])
+                                                             _p(gw), "WS", "WSB"], side=True)
             elif kind == "ren":
                 _, _, inp, a = op
                 H, W, C = net.shapes[inp]
@@ -284,24 +303,46 @@ class TrainStep:
 
     # ------------------------------------------------------------------ execution
     def run(self, step=0, upto=None):
-        """Enqueue the whole step on the current stream.  Stochastic-rounding counters are
-        offset = step * 2^32 + conv_index * 2^24 (in Philox blocks of 4 elements)."""
-        stream = _vp(torch.cuda.current_stream().cuda_stream)
+        """Enqueue the whole step on the current stream (the weight-gradient calls on the second stream, joined
+        before the SGD update).  Stochastic-rounding counters are offset = step * 2^32 + conv_index * 2^24 (in
+        Philox blocks of 4 elements)."""
+        main = torch.cuda.current_stream()
+        stream = _vp(main.cuda_stream)
+        side = self._side_stream
+        side_ptr = _vp(side.cuda_stream) if side is not None else stream
         last = self.L.lpdt_last_error
-        for fn, args, sr in (self.calls if upto is None else self.calls[:upto]):
+        forks, joined = 0, True
+        calls = self.calls if upto is None else self.calls[:upto]
+        n = len(calls)
+        for i, (fn, args, sr, on_side) in enumerate(calls):
             if sr is not None:
                 pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
                 args[pos] = _u64((int(step) << 32) + (sr << 24))
-            rc = fn(*args, stream)
+            if on_side:
+                ev = self._fork_events[forks]
+                forks += 1
+                ev.record(main)              # everything issued so far (the quantizer of this layer's gradient included)
+                side.wait_event(ev)
+                rc = fn(*args, side_ptr)
+                joined = False
+            else:
+                if not joined and (fn is self.L.lpdt_sgd or i == n - 1):
+                    self._join_event.record(side)
+                    main.wait_event(self._join_event)
+                    joined = True
+                rc = fn(*args, stream)
             if rc != 0:
                 raise LpdtError(rc, last().decode())
+        if not joined:
+            self._join_event.record(side)
+            main.wait_event(self._join_event)
 
     def run_timed(self, step=0):
-        """Like run(), but brackets every library call with events on the launch stream and returns
+        """Like run(), but everything on the current stream, every library call bracketed with events on it; returns
         [(entry point name, milliseconds)] in call order (one synchronisation at the end)."""
         stream = _vp(torch.cuda.current_stream().cuda_stream)
         marks = []
-        for fn, args, sr in self.calls:
+        for fn, args, sr, _ in self.calls:
             if sr is not None:
                 pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
                 args[pos] = _u64((int(step) << 32) + (sr << 24))
@@ -318,7 +359,7 @@ class TrainStep:
     def conv_work(self):
         """[(entry point name, multiply-adds)] for every convolution call of one step, in call order."""
         out = []
-        for fn, args, _ in self.calls:
+        for fn, args, _, _ in self.calls:
             if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
                                "lpdt_qconv_bwd_weight_bf16"):
                 d = args[0]._obj
