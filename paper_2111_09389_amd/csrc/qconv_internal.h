@@ -30,6 +30,7 @@ void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *
 // Weight gradient, rectangle-stepped kernel with partial tiles and a fixed-order reduction.
 struct WgradRectPlan {
     int ch, cw, ncy, ncx, PHp, PWp, steps, steps_per_split, splits, tg, groups, tiles_k, tiles_c, kt, ct, ks;
+    int ng, partials;   // wave groups per block (1 or 2); partial tiles written = ceil(splits / ng)
     long long out_len;
     size_t partial_bytes, lds;
 };

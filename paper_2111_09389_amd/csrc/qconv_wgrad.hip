@@ -53,8 +53,11 @@ constexpr unsigned kBeyond = 0x80000000u;  // a buffer offset no tensor reaches:
 // PF = steps whose loads are in flight (in registers) ahead of the step being multiplied; the loop runs in rounds of PF
 // steps without conditions, steps past the block's share load zeros.
 // KS = 32-pixel groups per step: the rectangle has 32*KS slots, one barrier serves KS MFMAs per accumulator.
-template <int KT, int CT, int TG, int PF, int KS>
-__global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParams p) {
+// NG = groups of 4 waves per block.  With NG = 2 the two groups work on two consecutive pixel splits, each with LDS
+// buffers of its own, and add their sums through LDS before one of them writes the partial tile: half the partial
+// tiles written and read back for the same number of waves on the chip.
+template <int KT, int CT, int TG, int PF, int KS, int NG = 1>
+__global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void wgrad_rect_kernel(const WgradRectParams p) {
     constexpr int SLOTS = 32 * KS;
     constexpr int WK = KT / 32 > 2 ? 2 : KT / 32, WC = CT / 32 > 2 ? 2 : CT / 32, WT = 4 / (WK * WC);
     constexpr int SK = KT / 32 / WK, SC = CT / 32 / WC;   // sub-tiles per wave
@@ -63,16 +66,18 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
     constexpr int kRow = lds_row_bytes(KT, CT);
     constexpr int GK = KT / 16, GC = CT / 16;    // 16-byte granules per pixel of the two tiles
     static_assert(SLOTS * GK % 64 == 0, "an item index is gradient or patch for a whole wave");
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
     const int patch_px = p.PHp * p.PWp;
     const int buf_bytes = (SLOTS + patch_px) * kRow;
 
-    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
+    const int grp = NG == 1 ? 0 : (int)threadIdx.x / 256;       // this thread's group of 4 waves
+    unsigned char *lds = lds_all + grp * 2 * buf_bytes;
+    const int t = threadIdx.x % 256, lane = t % 64, wave = t / 64;
     const int k0 = (blockIdx.x % p.tiles_k) * KT, c0 = (blockIdx.x / p.tiles_k) * CT;
     const int tap0 = blockIdx.y * TG, ntaps = p.R * p.S;
-    const int step_begin = blockIdx.z * p.steps_per_split;
+    const int step_begin = min(p.steps, (int)(blockIdx.z * NG + grp) * p.steps_per_split);
     const int step_end = min(p.steps, step_begin + p.steps_per_split);
-    const int nsteps = (step_end - step_begin + PF - 1) / PF * PF;
+    const int nsteps = (p.steps_per_split + PF - 1) / PF * PF;   // the same for every group: the barriers are shared
 
     // This thread's load items.  id < SLOTS*GK: gradient (rectangle slot id/GK, granule id%GK); else patch pixel
     // (id - SLOTS*GK)/GC.  Per item: position (ia, ib) inside the rectangle / patch, the image limits its position is
@@ -216,6 +221,22 @@ __global__ __launch_bounds__(256, 2) void wgrad_rect_kernel(const WgradRectParam
         });
     }
 
+    if constexpr (NG == 2) {
+        // group 1 hands its sums over through LDS (the staging buffers are free: the loop ended with a barrier)
+        int *dump = reinterpret_cast<int *>(lds_all);
+        if (grp == 1) {
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dump[((wave * NA + i) * 16 + r) * 64 + lane] = acc[i][r];
+        }
+        __syncthreads();
+        if (grp == 1) return;
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] += dump[((wave * NA + i) * 16 + r) * 64 + lane];
+    }
     int32_t *out = p.partial + (size_t)blockIdx.z * p.out_len;
     if constexpr (SK * SC > 1) {
 #pragma unroll
@@ -331,9 +352,19 @@ static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradR
     pl->steps_per_split = (int)((steps + splits - 1) / splits);
     pl->splits = (int)((steps + pl->steps_per_split - 1) / pl->steps_per_split);
     pl->out_len = (long long)d->K * ntaps * d->C;
-    pl->partial_bytes = round_up((size_t)pl->splits * pl->out_len * sizeof(int32_t), 256);
     pl->lds = 2 * (size_t)(32 * pl->ks + pl->PHp * pl->PWp) * lds_row_bytes(pl->kt, pl->ct);
-    return pl->lds <= 64 * 1024;
+    if (pl->lds > 64 * 1024) return false;
+    // Two wave groups per block (see the kernel) for the multi-tap 32 x 64 tiles when there are splits to pair up
+    pl->ng = (pl->tg == 9 && pl->kt == 32 && pl->ct == 64 && pl->splits >= 2) ? 2 : 1;
+    if (pl->ng == 2) {
+        const size_t dump = (size_t)4 * 5 * 16 * 64 * sizeof(int);   // 4 waves x 5 accumulators of 16 registers
+        pl->lds = 2 * pl->lds > dump ? 2 * pl->lds : dump;
+        pl->partials = (pl->splits + 1) / 2;
+    } else {
+        pl->partials = pl->splits;
+    }
+    pl->partial_bytes = round_up((size_t)pl->partials * pl->out_len * sizeof(int32_t), 256);
+    return true;
 }
 
 void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPlan &pl, const int8_t *g, const int8_t *x,
@@ -345,9 +376,17 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
     p.R = d->R; p.S = d->S; p.stride = d->stride_h; p.pad = d->pad_h;
     p.ch = pl.ch; p.cw = pl.cw; p.ncy = pl.ncy; p.ncx = pl.ncx; p.PHp = pl.PHp; p.PWp = pl.PWp;
     p.steps = pl.steps; p.steps_per_split = pl.steps_per_split; p.tiles_k = pl.tiles_k; p.out_len = pl.out_len;
-    const dim3 grid((unsigned)(pl.tiles_k * pl.tiles_c), (unsigned)pl.groups, (unsigned)pl.splits);
+    const dim3 grid((unsigned)(pl.tiles_k * pl.tiles_c), (unsigned)pl.groups, (unsigned)pl.partials);
     auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(256), pl.lds, st, p); };
-    if (pl.kt == 128) {
+    auto go2 = [&](auto kernel) {   // two wave groups: 512 threads, possibly more than 64 KB of LDS
+        if (pl.lds > 48 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+        hipLaunchKernelGGL(kernel, grid, dim3(512), pl.lds, st, p);
+    };
+    if (pl.ng == 2) {
+        if (pl.ks == 2) go2(wgrad_rect_kernel<32, 64, 9, 2, 2, 2>);
+        else go2(wgrad_rect_kernel<32, 64, 9, 2, 1, 2>);
+    } else if (pl.kt == 128) {
         go(wgrad_rect_kernel<128, 128, 1, 4, 1>);
     } else if (pl.kt == 64 && pl.ct == 64) {
         if (pl.tg == 1) go(wgrad_rect_kernel<64, 64, 1, 4, 1>);
@@ -359,7 +398,7 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
         else go(wgrad_rect_kernel<32, 64, 9, 2, 1>);
     }
     const long long rb = (pl.out_len / 4 + 31) / 32;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.splits,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.partials,
                        static_cast<int32_t *>(out), out_mode, sA, sB);
 }
 
