@@ -37,19 +37,29 @@ __device__ __forceinline__ int div24(int m, int d, float inv) {
     return q;
 }
 
-// xp[n][yy][xx][c] = x[n][yy-pad][xx-pad][c] inside the image, 0 in the border and in the slack after the last image
+// xp[n][yy][xx][c] = x[n][yy-pad][xx-pad][c] inside the image, 0 in the border and in the slack after the last image.
+// A thread builds 4 consecutive output bytes (one division chain, then carries) and stores them as one word; the
+// buffer is a multiple of 4 bytes long (total < 2^31).
 __global__ void pad_image_kernel(const int8_t *__restrict__ x, int N, int H, int W, int C, int pad, int PH, int PW,
-                                 int8_t *__restrict__ xp, size_t total) {
-    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
-        const int c = (int)(o % C);
-        size_t rest = o / C;
-        const int xx = (int)(rest % PW); rest /= PW;
-        const int yy = (int)(rest % PH);
-        const size_t n = rest / PH;
-        const int iy = yy - pad, ix = xx - pad;
-        int8_t v = 0;
-        if (n < (size_t)N && iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[((n * H + iy) * W + ix) * C + c];
-        xp[o] = v;
+                                 int8_t *__restrict__ xp, unsigned total) {
+    const unsigned nwords = (total + 3u) / 4u;
+    for (unsigned q = blockIdx.x * blockDim.x + threadIdx.x; q < nwords; q += gridDim.x * blockDim.x) {
+        const unsigned o = q * 4u;
+        int c = (int)(o % (unsigned)C);
+        unsigned rest = o / (unsigned)C;
+        int xx = (int)(rest % (unsigned)PW); rest /= (unsigned)PW;
+        int yy = (int)(rest % (unsigned)PH);
+        int n = (int)(rest / (unsigned)PH);
+        unsigned word = 0u;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int iy = yy - pad, ix = xx - pad;
+            int8_t v = 0;
+            if (n < N && iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((size_t)n * H + iy) * W + ix) * C + c];
+            word |= (unsigned)(uint8_t)v << (8 * b);
+            if (++c == C) { c = 0; if (++xx == PW) { xx = 0; if (++yy == PH) { yy = 0; ++n; } } }
+        }
+        reinterpret_cast<unsigned *>(xp)[q] = word;
     }
 }
 
@@ -289,10 +299,10 @@ static NarrowParams narrow_params(const lpdt_conv_desc *d, int P, int Q, const i
 
 static void launch_pad(const lpdt_conv_desc *d, const int8_t *x, int8_t *xp, hipStream_t st) {
     const size_t total = padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w);
-    size_t blocks = (total + 255) / 256;
+    size_t blocks = (total / 4 + 256) / 256;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(pad_image_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, d->N, d->H, d->W, d->C, d->pad_h,
-                       d->H + 2 * d->pad_h, d->W + 2 * d->pad_w, xp, total);
+                       d->H + 2 * d->pad_h, d->W + 2 * d->pad_w, xp, (unsigned)total);
 }
 
 void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, int out_mode,
