@@ -180,6 +180,60 @@ def range_evonorm_bwd(dy, x, groups, v, gamma, eps=1e-5):
     return dx, dv, dg, db
 
 
+def evonorm_s0_fwd(x, groups, v, gamma, beta, eps=1e-5):
+    """EvoNorm-S0 (Eq. "en").  x float32 [N,H,W,C] -> (y f64, mean f64 [N,groups], var f64 [N,groups])."""
+    x = _c(x, np.float32)
+    N, H, W, C = x.shape
+    v, gamma, beta = (_c(t, np.float32) for t in (v, gamma, beta))
+    y = np.empty(x.shape, np.float64)
+    mean, var = np.empty((N, groups), np.float64), np.empty((N, groups), np.float64)
+    rc = lib().orc_evonorm_s0_fwd(_p(x), N, H, W, C, int(groups), _p(v), _p(gamma), _p(beta), ctypes.c_double(eps),
+                                  _p(y), _p(mean), _p(var))
+    _chk(rc, "evonorm_s0_fwd")
+    return y, mean, var
+
+
+def evonorm_s0_bwd(dy, x, groups, v, gamma, eps=1e-5):
+    """-> (dx [N,H,W,C], dv [C], dgamma [C], dbeta [C]), float64."""
+    x = _c(x, np.float32)
+    dy = _c(dy, np.float64)
+    N, H, W, C = x.shape
+    v, gamma = (_c(t, np.float32) for t in (v, gamma))
+    dx = np.empty(x.shape, np.float64)
+    dv, dg, db = (np.empty(C, np.float64) for _ in range(3))
+    rc = lib().orc_evonorm_s0_bwd(_p(dy), _p(x), N, H, W, C, int(groups), _p(v), _p(gamma), ctypes.c_double(eps),
+                                  _p(dx), _p(dv), _p(dg), _p(db))
+    _chk(rc, "evonorm_s0_bwd")
+    return dx, dv, dg, db
+
+
+def range_bn_fwd(x, gamma, beta, eps=1e-5):
+    """Range batch-norm (Eq. "rbn").  x float32 [N,H,W,C] -> (y f64, mean f64 [C], range f64 [C], argmax i64 [C], argmin i64 [C])."""
+    x = _c(x, np.float32)
+    N, H, W, C = x.shape
+    gamma, beta = (_c(t, np.float32) for t in (gamma, beta))
+    y = np.empty(x.shape, np.float64)
+    mean, rng = np.empty(C, np.float64), np.empty(C, np.float64)
+    amx, amn = np.empty(C, np.int64), np.empty(C, np.int64)
+    rc = lib().orc_range_bn_fwd(_p(x), N, H, W, C, _p(gamma), _p(beta), ctypes.c_double(eps), _p(y), _p(mean), _p(rng),
+                                _p(amx), _p(amn))
+    _chk(rc, "range_bn_fwd")
+    return y, mean, rng, amx, amn
+
+
+def range_bn_bwd(dy, x, gamma, eps=1e-5):
+    """-> (dx [N,H,W,C], dgamma [C], dbeta [C]), float64."""
+    x = _c(x, np.float32)
+    dy = _c(dy, np.float64)
+    N, H, W, C = x.shape
+    gamma = _c(gamma, np.float32)
+    dx = np.empty(x.shape, np.float64)
+    dg, db = np.empty(C, np.float64), np.empty(C, np.float64)
+    rc = lib().orc_range_bn_bwd(_p(dy), _p(x), N, H, W, C, _p(gamma), ctypes.c_double(eps), _p(dx), _p(dg), _p(db))
+    _chk(rc, "range_bn_bwd")
+    return dx, dg, db
+
+
 def gossip_mix(x, xhat, Wm, eta=1.0, keep_ratio=1.0, seg_offsets=None):
     """x float32 [n,d]; xhat float32 [n,d] or None (plain mix).
     -> (x_new float64 [n,d], xhat_new float32 [n,d] or None)."""

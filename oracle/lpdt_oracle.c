@@ -350,6 +350,165 @@ int orc_range_evonorm_bwd(const double *dy, const float *x, int N, int H, int W,
 }
 
 /* ------------------------------------------------------------------------- */
+/* The two full-precision layers the paper compares Range-EvoNorm with.
+ *
+ * EvoNorm-S0 (Eq. "en"): per sample n and channel group G (m = C/groups channels),
+ *   var = variance of x over the group's (h, w, channel) slab (population form, 1/count),
+ *   y   = gamma_c * x * sigmoid(v_c x) / sqrt(var + eps) + beta_c.
+ * The paper writes no eps and does not say which variance; eps is an argument (0 allowed)
+ * and the population form is the reading taken. */
+int orc_evonorm_s0_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v, const float *gamma,
+                       const float *beta, double eps, double *y, double *mean_out, double *var_out)
+{
+    if (groups <= 0 || C % groups != 0) return ORC_EINVAL;
+    const int m = C / groups;
+    const double cnt = (double)H * W * m;
+#pragma omp parallel for collapse(2)
+    for (int n = 0; n < N; ++n)
+        for (int G = 0; G < groups; ++G) {
+            double sum = 0.0;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) sum += x[(((size_t)n * H + h) * W + w) * C + G * m + cc];
+            const double mu = sum / cnt;
+            double ss = 0.0;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        double e = x[(((size_t)n * H + h) * W + w) * C + G * m + cc] - mu;
+                        ss += e * e;
+                    }
+            const double var = ss / cnt, D = sqrt(var + eps);
+            mean_out[(size_t)n * groups + G] = mu;
+            var_out[(size_t)n * groups + G] = var;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        int c = G * m + cc;
+                        size_t at = (((size_t)n * H + h) * W + w) * C + c;
+                        double xe = x[at];
+                        double u = xe / (1.0 + exp(-(double)v[c] * xe));
+                        y[at] = (double)gamma[c] * u / D + (double)beta[c];
+                    }
+        }
+    return ORC_OK;
+}
+
+/* Chain rule of the forward above: u = x s, s = sigmoid(v x), s' = s (1 - s);
+ * dD = -sum dy gamma u / D^2 over the slab, and D depends on every x_j of the slab through the variance:
+ * dD/dx_j = (x_j - mean) / (count * D). */
+int orc_evonorm_s0_bwd(const double *dy, const float *x, int N, int H, int W, int C, int groups, const float *v,
+                       const float *gamma, double eps, double *dx, double *dv, double *dgamma, double *dbeta)
+{
+    if (groups <= 0 || C % groups != 0) return ORC_EINVAL;
+    const int m = C / groups;
+    const double cnt = (double)H * W * m;
+    for (int c = 0; c < C; ++c) dv[c] = dgamma[c] = dbeta[c] = 0.0;
+    for (int n = 0; n < N; ++n)
+        for (int G = 0; G < groups; ++G) {
+            double sum = 0.0, ss = 0.0;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) sum += x[(((size_t)n * H + h) * W + w) * C + G * m + cc];
+            const double mu = sum / cnt;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        double e = x[(((size_t)n * H + h) * W + w) * C + G * m + cc] - mu;
+                        ss += e * e;
+                    }
+            const double D = sqrt(ss / cnt + eps);
+            double dD = 0.0;
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        int c = G * m + cc;
+                        size_t at = (((size_t)n * H + h) * W + w) * C + c;
+                        double xe = x[at], s = 1.0 / (1.0 + exp(-(double)v[c] * xe)), sp = s * (1.0 - s);
+                        double u = xe * s, du = dy[at] * (double)gamma[c] / D;
+                        dbeta[c] += dy[at];
+                        dgamma[c] += dy[at] * u / D;
+                        dv[c] += du * xe * xe * sp;
+                        dx[at] = du * (s + xe * (double)v[c] * sp);
+                        dD -= dy[at] * (double)gamma[c] * u / (D * D);
+                    }
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int cc = 0; cc < m; ++cc) {
+                        size_t at = (((size_t)n * H + h) * W + w) * C + G * m + cc;
+                        dx[at] += dD * ((double)x[at] - mu) / (cnt * D);
+                    }
+        }
+    return ORC_OK;
+}
+
+/* Range batch-norm (Eq. "rbn"): per channel c, over all samples and pixels,
+ *   mu = mean of x,  R = max - min of (x - mu) = max - min of x,  D = C(b) * R + eps,  C(b) = 1/sqrt(2 ln b),
+ *   y = gamma_c * (x - mu) / D + beta_c,   b = batch size (needs b >= 2).
+ * argmax / argmin: first position (n, h, w order) of the extreme value, as flat index (n*H + h)*W + w. */
+int orc_range_bn_fwd(const float *x, int N, int H, int W, int C, const float *gamma, const float *beta, double eps,
+                     double *y, double *mean_out, double *range_out, int64_t *argmax_out, int64_t *argmin_out)
+{
+    if (N < 2) return ORC_EINVAL;
+    const double Cb = 1.0 / sqrt(2.0 * log((double)N));
+    const size_t pix = (size_t)N * H * W;
+#pragma omp parallel for
+    for (int c = 0; c < C; ++c) {
+        double sum = 0.0;
+        float mx = 0, mn = 0;
+        int64_t imx = -1, imn = -1;
+        for (size_t p = 0; p < pix; ++p) {
+            float e = x[p * C + c];
+            sum += e;
+            if (imx < 0 || e > mx) { mx = e; imx = (int64_t)p; }
+            if (imn < 0 || e < mn) { mn = e; imn = (int64_t)p; }
+        }
+        const double mu = sum / (double)pix, R = (double)mx - (double)mn, D = Cb * R + eps;
+        mean_out[c] = mu; range_out[c] = R; argmax_out[c] = imx; argmin_out[c] = imn;
+        for (size_t p = 0; p < pix; ++p) y[p * C + c] = (double)gamma[c] * ((double)x[p * C + c] - mu) / D + (double)beta[c];
+    }
+    return ORC_OK;
+}
+
+/* Chain rule: d(x_j - mu)/dx_i = [i == j] - 1/count, and the whole gradient of the range goes to the first arg-max (+)
+ * and the first arg-min (-). */
+int orc_range_bn_bwd(const double *dy, const float *x, int N, int H, int W, int C, const float *gamma, double eps,
+                     double *dx, double *dgamma, double *dbeta)
+{
+    if (N < 2) return ORC_EINVAL;
+    const double Cb = 1.0 / sqrt(2.0 * log((double)N));
+    const size_t pix = (size_t)N * H * W;
+#pragma omp parallel for
+    for (int c = 0; c < C; ++c) {
+        double sum = 0.0;
+        float mx = 0, mn = 0;
+        size_t imx = 0, imn = 0;
+        int first = 1;
+        for (size_t p = 0; p < pix; ++p) {
+            float e = x[p * C + c];
+            sum += e;
+            if (first || e > mx) { mx = e; imx = p; }
+            if (first || e < mn) { mn = e; imn = p; }
+            first = 0;
+        }
+        const double mu = sum / (double)pix, D = Cb * ((double)mx - (double)mn) + eps;
+        double sdy = 0.0, sdyx = 0.0;
+        for (size_t p = 0; p < pix; ++p) {
+            sdy += dy[p * C + c];
+            sdyx += dy[p * C + c] * ((double)x[p * C + c] - mu);
+        }
+        dbeta[c] = sdy;
+        dgamma[c] = sdyx / D;
+        const double g = (double)gamma[c];
+        for (size_t p = 0; p < pix; ++p) dx[p * C + c] = g / D * (dy[p * C + c] - sdy / (double)pix);
+        const double dR = Cb * (-g * sdyx / (D * D));
+        dx[imx * C + c] += dR;
+        dx[imn * C + c] -= dR;
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Gossip step (Algorithm 1 step 7; Algorithms 2 and 3 of the supplement).
  *   xhat == NULL : x_i+ = x_i + eta * (sum_j W_ij x_j - x_i)
  *   xhat != NULL : CHOCO.  v = x_i - xhat_i (fp32);  q = v on the top-k |v| of
