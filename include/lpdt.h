@@ -183,6 +183,47 @@ int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W,
                            float *dgamma, float *dbeta, float *absmax_out, void *ws, size_t ws_bytes,
                            void *stream);
 
+/* ------------------------------------------- full-precision comparison layers
+ * The two layers Section 3 sets Range-EvoNorm against, as fp32 reference layers with the same
+ * tensor conventions (x, y, dy, dx fp32 [N,H,W,C], 16-byte aligned; per-channel vectors fp32 [C];
+ * device pointers; eps >= 0).  C must be a multiple of 4 and at most 1024 (LPDT_EUNSUPPORTED
+ * otherwise).  Reductions run in a fixed order: results do not change from run to run.
+ *
+ * EvoNorm-S0 (Eq. "en"): for every sample n and channel group G (m = C/groups channels),
+ *   var = population variance (1/count) of x over the group's (h, w, channel) slab,
+ *   y   = gamma_c * x * sigmoid(v_c * x) / sqrt(var + eps) + beta_c.
+ * (The paper prints no eps and does not say which variance: eps is an argument and may be 0,
+ * the population form is the reading taken.)  mean_out, var_out: fp32 [N*groups], saved for
+ * the backward pass.  The backward pass returns dx and the parameter gradients dv, dgamma,
+ * dbeta (fp32 [C], overwritten). */
+size_t lpdt_evonorm_s0_fwd_workspace_bytes(int N, int H, int W, int C, int groups);
+size_t lpdt_evonorm_s0_bwd_workspace_bytes(int N, int H, int W, int C, int groups);
+int lpdt_evonorm_s0_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                        const float *gamma, const float *beta, float eps, float *y, float *mean_out,
+                        float *var_out, void *ws, size_t ws_bytes, void *stream);
+int lpdt_evonorm_s0_bwd(const float *dy, const float *x, int N, int H, int W, int C, int groups,
+                        const float *v, const float *gamma, float eps, const float *mean,
+                        const float *var, float *dx, float *dv, float *dgamma, float *dbeta, void *ws,
+                        size_t ws_bytes, void *stream);
+
+/* Range batch-norm (Eq. "rbn"): per channel c, over all samples and pixels of the batch,
+ *   mean  = mean of x,  range = max - min of x (= of x - mean),
+ *   y     = gamma_c * (x - mean) / (C(b) * range + eps) + beta_c,   C(b) = 1/sqrt(2 ln b),
+ * b = N, the batch size; N must be at least 2 (LPDT_EUNSUPPORTED otherwise).
+ * Saved for the backward pass, each [C]: mean_out, range_out (fp32) and argmax_out / argmin_out
+ * (int64): the first position of the maximum / minimum as flat pixel index (n*H + h)*W + w.
+ * The backward pass gives the range's whole gradient to those two positions and returns dx,
+ * dgamma, dbeta. */
+size_t lpdt_range_bn_fwd_workspace_bytes(int N, int H, int W, int C);
+size_t lpdt_range_bn_bwd_workspace_bytes(int N, int H, int W, int C);
+int lpdt_range_bn_fwd(const float *x, int N, int H, int W, int C, const float *gamma, const float *beta,
+                      float eps, float *y, float *mean_out, float *range_out, int64_t *argmax_out,
+                      int64_t *argmin_out, void *ws, size_t ws_bytes, void *stream);
+int lpdt_range_bn_bwd(const float *dy, const float *x, int N, int H, int W, int C, const float *gamma,
+                      float eps, const float *mean, const float *range, const int64_t *argmax,
+                      const int64_t *argmin, float *dx, float *dgamma, float *dbeta, void *ws,
+                      size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------- 16-bit weight gradient
  * The weight-gradient product as Section 3 states it (gradient bifurcation): the layer
  * gradient enters in 16-bit floating point, the saved input codes in 8 bits:

@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -31,6 +31,8 @@ EXPORTS = [
     "lpdt_to_bf16", "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_bwd_weight_bf16",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
+    "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
+    "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
     "lpdt_add", "lpdt_maxpool_fwd", "lpdt_maxpool_bwd", "lpdt_avgpool_fwd", "lpdt_avgpool_bwd",
     "lpdt_softmax_xent", "lpdt_sgd",
@@ -89,8 +91,11 @@ def lib():
                      "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
                      "lpdt_qconv_bwd_weight_bf16_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
-        for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes"):
+        for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
+                     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
+        for name in ("lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes"):
+            getattr(L, name).argtypes = [ctypes.c_int] * 4
         L.lpdt_gossip_mix_workspace_bytes.argtypes = [ctypes.c_int, _sz, ctypes.c_int, ctypes.c_int]
         L.lpdt_gossip_mix_ex_workspace_bytes.argtypes = [ctypes.c_int, _sz, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         _lib = L
@@ -280,6 +285,59 @@ def range_evonorm_bwd(dy, x, groups, v, gamma, rng, amx, amn, eps=1e-5, dx=None,
                                         ctypes.c_float(eps), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(dx), _ptr(dv), _ptr(dg),
                                         _ptr(db), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
     return (dx, dv, dg, db, absmax) if want_absmax else (dx, dv, dg, db)
+
+
+# ---------------------------------------------------------------- full-precision comparison layers
+def evonorm_s0_fwd(x, groups, v, gamma, beta, eps=1e-5, y=None, ws=None):
+    """EvoNorm-S0 -> (y, mean [N,groups], var [N,groups])."""
+    _dev(x, torch.float32, "evonorm_s0_fwd x")
+    N, H, W, C = x.shape
+    y = torch.empty_like(x) if y is None else y
+    mean = torch.empty((N, groups), dtype=torch.float32, device=x.device)
+    var = torch.empty((N, groups), dtype=torch.float32, device=x.device)
+    buf, nb = _ws(ws, lib().lpdt_evonorm_s0_fwd_workspace_bytes(N, H, W, C, int(groups)))
+    _check(lib().lpdt_evonorm_s0_fwd(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta), ctypes.c_float(eps),
+                                     _ptr(y), _ptr(mean), _ptr(var), _ptr(buf), _sz(nb), _stream()))
+    return y, mean, var
+
+
+def evonorm_s0_bwd(dy, x, groups, v, gamma, mean, var, eps=1e-5, dx=None, ws=None):
+    """-> (dx, dv, dgamma, dbeta)."""
+    _dev(x, torch.float32, "evonorm_s0_bwd x"); _dev(dy, torch.float32, "evonorm_s0_bwd dy")
+    N, H, W, C = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    dv, dg, db = (torch.empty(C, dtype=torch.float32, device=x.device) for _ in range(3))
+    buf, nb = _ws(ws, lib().lpdt_evonorm_s0_bwd_workspace_bytes(N, H, W, C, int(groups)))
+    _check(lib().lpdt_evonorm_s0_bwd(_ptr(dy), _ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), ctypes.c_float(eps),
+                                     _ptr(mean), _ptr(var), _ptr(dx), _ptr(dv), _ptr(dg), _ptr(db), _ptr(buf), _sz(nb), _stream()))
+    return dx, dv, dg, db
+
+
+def range_bn_fwd(x, gamma, beta, eps=1e-5, y=None, ws=None):
+    """Range batch-norm -> (y, mean [C], range [C], argmax int64 [C], argmin int64 [C])."""
+    _dev(x, torch.float32, "range_bn_fwd x")
+    N, H, W, C = x.shape
+    y = torch.empty_like(x) if y is None else y
+    mean = torch.empty(C, dtype=torch.float32, device=x.device)
+    rng = torch.empty(C, dtype=torch.float32, device=x.device)
+    amx = torch.empty(C, dtype=torch.int64, device=x.device)
+    amn = torch.empty(C, dtype=torch.int64, device=x.device)
+    buf, nb = _ws(ws, lib().lpdt_range_bn_fwd_workspace_bytes(N, H, W, C))
+    _check(lib().lpdt_range_bn_fwd(_ptr(x), N, H, W, C, _ptr(gamma), _ptr(beta), ctypes.c_float(eps), _ptr(y), _ptr(mean),
+                                   _ptr(rng), _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
+    return y, mean, rng, amx, amn
+
+
+def range_bn_bwd(dy, x, gamma, mean, rng, amx, amn, eps=1e-5, dx=None, ws=None):
+    """-> (dx, dgamma, dbeta)."""
+    _dev(x, torch.float32, "range_bn_bwd x"); _dev(dy, torch.float32, "range_bn_bwd dy")
+    N, H, W, C = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    dg, db = (torch.empty(C, dtype=torch.float32, device=x.device) for _ in range(2))
+    buf, nb = _ws(ws, lib().lpdt_range_bn_bwd_workspace_bytes(N, H, W, C))
+    _check(lib().lpdt_range_bn_bwd(_ptr(dy), _ptr(x), N, H, W, C, _ptr(gamma), ctypes.c_float(eps), _ptr(mean), _ptr(rng),
+                                   _ptr(amx), _ptr(amn), _ptr(dx), _ptr(dg), _ptr(db), _ptr(buf), _sz(nb), _stream()))
+    return dx, dg, db
 
 
 # ---------------------------------------------------------------- gossip

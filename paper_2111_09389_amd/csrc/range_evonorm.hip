@@ -12,58 +12,11 @@
 //             dbeta and, in its last block, adds the range gradient at the saved
 //             arg-max / arg-min and reduces max|dx|.  Two launches.
 #include "common.h"
+#include "norm_geom.h"
 #include <cmath>
 
 namespace lpdt {
 
-constexpr int kRThreads = 256;
-constexpr int kPixIters = 2;     // least pixels per thread in the streaming passes
-constexpr int kBwdMinPix = 8;
-constexpr int kRU = 4;           // pixels a thread has in flight: the streaming loops load kRU pixels, then work on them
-constexpr int kMaxBlocks = 2048;  // the streaming grids are kept near this size: enough to fill the chip, few partial rows
-
-struct RenGeom {
-    int N, HW, C, groups, m;
-    int cq;       // float4 quads per pixel (C/4)
-    int threads;  // working threads per block, multiple of cq
-    int block;    // launched block size: threads rounded up to whole waves (the extra threads only join reductions)
-    int ppi;      // pixels per block iteration
-    int chunks;   // blocks per sample
-    int pix_per_block;
-};
-
-// Grid size of a streaming pass: about one block per `elems_per_block` elements, between 256 and kMaxBlocks.  Small
-// tensors are latency-bound (every block first waits for its parameters and range), so they want few, longer blocks;
-// the stats pass has no such wait and takes more, shorter ones (measured on the ResNet-18 layer sizes).
-constexpr int kStatsElems = 8192, kApplyElems = 16384, kBwdElems = 16384;
-static int block_cap(int N, int H, int W, int C, int elems_per_block) {
-    const long long b = (long long)N * H * W * C / elems_per_block;
-    return (int)(b < 256 ? 256 : b > kMaxBlocks ? kMaxBlocks : b);
-}
-// min_pix: least pixels per block.  The forward passes leave a few keys per block and take 0; the backward pass leaves
-// 4 floats per channel and block, which must stay small beside the 3 floats per channel and pixel it streams.
-static RenGeom ren_geom(int N, int H, int W, int C, int groups, int min_pix, int max_blocks) {
-    RenGeom g;
-    g.N = N; g.HW = H * W; g.C = C; g.groups = groups; g.m = C / groups;
-    g.cq = C / 4;
-    g.threads = (kRThreads / g.cq) * g.cq;
-    g.block = (g.threads + kWave - 1) / kWave * kWave;
-    g.ppi = g.threads / g.cq;
-    int iters = kPixIters;
-    while (((long long)N * ((g.HW + g.ppi * iters - 1) / (g.ppi * iters)) > max_blocks || g.ppi * iters < min_pix) && iters < 4096) iters *= 2;
-    g.pix_per_block = g.ppi * iters;
-    g.chunks = (g.HW + g.pix_per_block - 1) / g.pix_per_block;
-    return g;
-}
-
-// monotone map float -> uint32 (larger float <=> larger key); -0 is folded onto +0
-__device__ __forceinline__ uint32_t ordered_bits(float x) {
-    const uint32_t b = __float_as_uint(x + 0.0f);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-__device__ __forceinline__ float from_ordered_bits(uint32_t k) {
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
-}
 __device__ __forceinline__ float hard_sigmoid(float z) { return fminf(1.0f, fmaxf(0.0f, (z + 3.0f) * (1.0f / 6.0f))); }
 
 __global__ void ren_clear_kernel(unsigned long long *stats, int count, float *absmax) {
