@@ -65,6 +65,9 @@ CONFIGS = {
     # beyond the baseline's list: quantized linear layers at transformer shapes through the same int8 kernels
     6: dict(name="DistilBERT-shaped linear layers (768 -> 3072 -> 768 -> 768), 16384 tokens",
             net="transformer_ffn", batch=16384, agents=1, mix=None),
+    # the normalisation layer next to the paper's two full-precision comparison layers, forward + backward on one tensor
+    7: dict(name="Range-EvoNorm / EvoNorm-S0 / range batch-norm, forward + backward, 64x56x56x64 fp32 (g=32)",
+            net=None, batch=64, agents=1, mix=None),
 }
 
 
@@ -167,6 +170,74 @@ def cpu_baseline(cfg_id, budget_s=20.0):
             "sample": f"{cfg['net']} training step(s) at batch <= {batch} ({used} images in {total_t:.1f} s), no gossip"}
 
 
+def bench_norm_layers(args, device):
+    """Config 7: the three normalisation layers on one ResNet-18 stage-1 tensor; a step = forward + backward of each."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2111_09389_amd as lpdt
+    N, H, W, C, groups = 64, 56, 56, 64, 32
+    g = wl.rng(wl.BASE_SEED + 7)
+    x = torch.from_numpy(wl.images(71, N, H, W, C)).to(device)
+    dy = torch.from_numpy(wl.upstream_grad(72, (N, H, W, C))).to(device)
+    v, gamma, beta = (torch.from_numpy((1.0 + 0.2 * g.standard_normal(C)).astype(np.float32)).to(device) for _ in range(3))
+    ws = lpdt.Workspace(device)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+
+    def ren():
+        _, r, a, b = lpdt.range_evonorm_fwd(x, groups, v, gamma, beta, 1e-5, y=y, ws=ws)
+        lpdt.range_evonorm_bwd(dy, x, groups, v, gamma, r, a, b, 1e-5, dx=dx, ws=ws)
+
+    def evo():
+        _, m, var = lpdt.evonorm_s0_fwd(x, groups, v, gamma, beta, 1e-5, y=y, ws=ws)
+        lpdt.evonorm_s0_bwd(dy, x, groups, v, gamma, m, var, 1e-5, dx=dx, ws=ws)
+
+    def rbn():
+        _, m, r, a, b = lpdt.range_bn_fwd(x, gamma, beta, 1e-5, y=y, ws=ws)
+        lpdt.range_bn_bwd(dy, x, gamma, m, r, a, b, 1e-5, dx=dx, ws=ws)
+
+    elems = x.numel()
+    # algorithmic bytes per element, forward + backward: x read for the statistics and again to apply them, y written;
+    # backward: dy and x read, dx written, and where a mean or variance feeds back into every dx, dy and x read twice
+    layers = {"range_evonorm": (ren, 12 + 12), "evonorm_s0": (evo, 12 + 20), "range_bn": (rbn, 12 + 16)}
+    out_layers, total_ms = {}, 0.0
+    for name, (fn, bpe) in layers.items():
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        total_ms += ms
+        out_layers[name] = {"ms_fwd_bwd": ms, "bytes_per_element": bpe, "gbs": bpe * elems / (ms * 1e-3) / 1e9}
+    ren_gbs = out_layers["range_evonorm"]["gbs"]
+    out = {
+        "metric": "Range-EvoNorm forward+backward GB/s (algorithmic bytes / time)", "value": ren_gbs, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 7: " + CONFIGS[7]["name"]}, "layers": out_layers,
+        "roofline": {"bound": "hbm", "achieved": ren_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ren_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "ren_stats + ren_apply + ren_bwd_main + ren_bwd_finish on one tensor"},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        n_small = 64
+        xs, dys = wl.images(71, n_small, H, W, C), wl.upstream_grad(72, (n_small, H, W, C)).astype(np.float64)
+        hv, hg, hb = (t.cpu().numpy() for t in (v, gamma, beta))
+        t0 = time.time()
+        oracle.range_evonorm_fwd(xs, groups, hv, hg, hb, 1e-5)
+        oracle.range_evonorm_bwd(dys, xs, groups, hv, hg, 1e-5)
+        dt = time.time() - t0
+        out["cpu_baseline"] = {"value": 24 * xs.size / dt / 1e9, "unit": "GB/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"Range-EvoNorm forward + backward on the same {n_small} x 56 x 56 x 64 tensor ({dt:.2f} s)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,6 +264,9 @@ def main():
     import paper_2111_09389_amd as lpdt
     lpdt.lib()
     device = torch.device("cuda:0")
+    if args.config == 7:
+        bench_norm_layers(args, device)
+        return
     if args.wgrad_16bit:
         CONFIGS[args.config] = dict(CONFIGS[args.config], wgrad_16bit=True)
     if CONFIGS[args.config]["mix"] == "choco":
