@@ -171,6 +171,18 @@ int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C, int group
                            float *range_out, int32_t *argmax_out, int32_t *argmin_out,
                            float *absmax_out, void *ws, size_t ws_bytes, void *stream);
 
+/* Range-EvoNorm forward whose output leaves as int8 codes (for layers whose only consumers are
+ * quantized convolutions): y as lpdt_range_evonorm_fwd computes it, then quantized as
+ * lpdt_quantize(y, LPDT_ROUND_NEAREST) would -- the same codes and scale, bit for bit -- without
+ * the fp32 tensor y making a round trip through HBM.  q int8 [N,H,W,C] (4-byte aligned), scale:
+ * fp32 device scalar; range_out / argmax_out / argmin_out as above.  C must be a multiple of 4,
+ * at most 1024 (LPDT_EUNSUPPORTED otherwise: use the two calls). */
+size_t lpdt_range_evonorm_fwd_q_workspace_bytes(int N, int H, int W, int C, int groups);
+int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                             const float *gamma, const float *beta, float eps, int8_t *q, float *scale,
+                             float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws,
+                             size_t ws_bytes, void *stream);
+
 /* Gradient of the forward above.  dy, x, dx fp32 [N,H,W,C]; range/argmax/argmin as
  * saved by the forward.  The hard-sigmoid slope is 1/6 strictly inside (-3,3), else 0;
  * the gradient through the range goes entirely to the saved arg-max (+) and arg-min (-).

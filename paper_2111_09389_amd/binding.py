@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -31,6 +31,7 @@ EXPORTS = [
     "lpdt_to_bf16", "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_bwd_weight_bf16",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
+    "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_fwd_q",
     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
     "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
@@ -92,7 +93,7 @@ def lib():
                      "lpdt_qconv_bwd_weight_bf16_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
-                     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
+                     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
         for name in ("lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 4
@@ -270,6 +271,22 @@ def range_evonorm_fwd(x, groups, v, gamma, beta, eps=1e-5, y=None, want_absmax=F
                                         ctypes.c_float(eps), _ptr(y), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(absmax),
                                         _ptr(buf), _sz(nb), _stream()))
     return (y, rng, amx, amn, absmax) if want_absmax else (y, rng, amx, amn)
+
+
+def range_evonorm_fwd_q(x, groups, v, gamma, beta, eps=1e-5, q=None, ws=None):
+    """Range-EvoNorm forward with int8 output -> (q int8, scale [1], range [N,groups], argmax, argmin)."""
+    _dev(x, torch.float32, "range_evonorm_fwd_q x")
+    N, H, W, C = x.shape
+    dev = x.device
+    q = torch.empty(x.shape, dtype=torch.int8, device=dev) if q is None else q
+    scale = torch.empty(1, dtype=torch.float32, device=dev)
+    rng = torch.empty((N, groups), dtype=torch.float32, device=dev)
+    amx = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    amn = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    buf, nb = _ws(ws, lib().lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, int(groups)))
+    _check(lib().lpdt_range_evonorm_fwd_q(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta), ctypes.c_float(eps),
+                                          _ptr(q), _ptr(scale), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
+    return q, scale, rng, amx, amn
 
 
 def range_evonorm_bwd(dy, x, groups, v, gamma, rng, amx, amn, eps=1e-5, dx=None, want_absmax=False, ws=None):

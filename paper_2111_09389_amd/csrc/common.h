@@ -46,4 +46,22 @@ __device__ __forceinline__ float dequant_value(float s, int a, float prev, bool 
     return accumulate ? prev + v : v;
 }
 
+// The quantizer's code for x with inv = 127 / max|x|: nearest (ties to even) or stochastic with the uniform number
+// u = (word >> 8) * 2^-24; clipped to [-127, 127].  Shared by every kernel that emits codes.
+__device__ __forceinline__ int round_code(float x, float inv, bool stochastic, uint32_t word) {
+#pragma clang fp contract(off)
+    const float t = __fmul_rn(x, inv);  // its own rounding: must not fuse with the subtraction below
+    float r;
+    if (stochastic) {
+        const float f = floorf(t);
+        const float frac = __fsub_rn(t, f);
+        const float u = __fmul_rn((float)(word >> 8), 0x1.0p-24f);
+        r = f + ((u < frac) ? 1.0f : 0.0f);
+    } else {
+        r = rintf(t);
+    }
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
 }  // namespace lpdt

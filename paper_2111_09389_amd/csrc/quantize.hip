@@ -57,22 +57,6 @@ __global__ __launch_bounds__(kQThreads) void absmax_kernel(const float *__restri
     if (threadIdx.x == 0) parts[blockIdx.x] = m;
 }
 
-__device__ __forceinline__ int round_code(float x, float inv, bool stochastic, uint32_t word) {
-#pragma clang fp contract(off)
-    const float t = __fmul_rn(x, inv);  // its own rounding: must not fuse with the subtraction below
-    float r;
-    if (stochastic) {
-        const float f = floorf(t);
-        const float frac = __fsub_rn(t, f);
-        const float u = __fmul_rn((float)(word >> 8), 0x1.0p-24f);
-        r = f + ((u < frac) ? 1.0f : 0.0f);
-    } else {
-        r = rintf(t);
-    }
-    r = fminf(fmaxf(r, -127.0f), 127.0f);
-    return (int)r;
-}
-
 template <bool kStochastic>
 __global__ __launch_bounds__(kQThreads) void round_kernel(const float *__restrict__ x, size_t len,
                                                           const float *__restrict__ parts, int nparts,

@@ -18,6 +18,14 @@
 namespace lpdt {
 
 __device__ __forceinline__ float hard_sigmoid(float z) { return fminf(1.0f, fmaxf(0.0f, (z + 3.0f) * (1.0f / 6.0f))); }
+// The forward value with every rounding pinned (no contraction left to the compiler): the plain and the int8-output
+// forward must produce the same bits, and the latter derives max|y| from extreme values of u, which relies on y being
+// a monotone function of u for fixed gamma, inv > 0, beta -- true of this sequence of correctly rounded operations.
+__device__ __forceinline__ float ren_u(float x, float v) {
+    const float z = __fmul_rn(v, x);
+    return __fmul_rn(x, fminf(1.0f, fmaxf(0.0f, __fmul_rn(__fadd_rn(z, 3.0f), 1.0f / 6.0f))));
+}
+__device__ __forceinline__ float ren_y(float u, float gamma, float inv, float beta) { return __fmaf_rn(__fmul_rn(gamma, u), inv, beta); }
 
 __global__ void ren_clear_kernel(unsigned long long *stats, int count, float *absmax) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -28,21 +36,32 @@ __global__ void ren_clear_kernel(unsigned long long *stats, int count, float *ab
 // Key = ordered value (inverted for the minimum) in the high word, ~slab_index in the low word: the
 // largest key is the extreme value at its lowest slab index.  pstats[((n*chunks + chunk)*groups + g)*2 + {0,1}]
 // = this block's max key / min key (0 = the block saw no element of the group).
+// kWithU: also the extreme values of u = x * hardsigmoid(v x) per block and channel, pu[((n*chunks + chunk)*C + c)*2 + {0,1}]
+// = max / min (the int8-output forward derives max|y| from them).
+template <bool kWithU>
 __global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__restrict__ x, RenGeom g,
                                                               unsigned long long *__restrict__ pstats,
-                                                              float *__restrict__ absmax_out) {
-    extern __shared__ unsigned long long skeys[];  // [groups][2]
+                                                              float *__restrict__ absmax_out, const float *__restrict__ vpar,
+                                                              float *__restrict__ pu) {
+    extern __shared__ unsigned long long skeys[];  // [groups][2]; with kWithU then unsigned su[C][2]
+    unsigned int *su = reinterpret_cast<unsigned int *>(skeys + 2 * g.groups);
     const int n = blockIdx.y;
-    if (absmax_out && blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *absmax_out = 0.0f;  // the apply pass max-es into it
+    if (absmax_out && blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *absmax_out = 0.0f;  // a later pass max-es into it
     for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) skeys[i] = 0ull;
+    if (kWithU)
+        for (int i = threadIdx.x; i < 2 * g.C; i += blockDim.x) su[i] = 0u;
     __syncthreads();
     const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
     const int p0 = blockIdx.x * g.pix_per_block;
     const int p1 = min(p0 + g.pix_per_block, g.HW);
     float mx[4], mn[4];
     int imx[4], imn[4];
+    float umx[4], umn[4], vv[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { imx[e] = -1; imn[e] = -1; mx[e] = 0.f; mn[e] = 0.f; }
+    for (int e = 0; e < 4; ++e) {
+        imx[e] = -1; imn[e] = -1; mx[e] = 0.f; mn[e] = 0.f;
+        umx[e] = -INFINITY; umn[e] = INFINITY; vv[e] = kWithU ? vpar[qd * 4 + e] : 0.f;
+    }
     const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
     for (int pb = p0 + pl; pb < p1 && (int)threadIdx.x < g.threads; pb += kRU * g.ppi) {
         float4 a[kRU];
@@ -60,6 +79,10 @@ __global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__res
             for (int e = 0; e < 4; ++e) {
                 if (imx[e] < 0 || v[e] > mx[e]) { mx[e] = v[e]; imx[e] = p; }
                 if (imn[e] < 0 || v[e] < mn[e]) { mn[e] = v[e]; imn[e] = p; }
+                if (kWithU) {
+                    const float u = ren_u(v[e], vv[e]);
+                    umx[e] = fmaxf(umx[e], u); umn[e] = fminf(umn[e], u);
+                }
             }
         }
     }
@@ -70,10 +93,18 @@ __global__ __launch_bounds__(kRThreads) void ren_stats_kernel(const float *__res
         const uint32_t lo_mx = ~(uint32_t)(imx[e] * g.m + cc), lo_mn = ~(uint32_t)(imn[e] * g.m + cc);
         atomicMax(&skeys[grp * 2 + 0], ((unsigned long long)ordered_bits(mx[e]) << 32) | lo_mx);
         atomicMax(&skeys[grp * 2 + 1], ((unsigned long long)(~ordered_bits(mn[e])) << 32) | lo_mn);
+        if (kWithU) {
+            atomicMax(&su[c * 2 + 0], ordered_bits(umx[e]));
+            atomicMax(&su[c * 2 + 1], ~ordered_bits(umn[e]));
+        }
     }
     __syncthreads();
     unsigned long long *dst = pstats + ((size_t)n * g.chunks + blockIdx.x) * g.groups * 2;
     for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) dst[i] = skeys[i];
+    if (kWithU) {  // every block holds at least one pixel, so every channel has been seen
+        float *du = pu + ((size_t)n * g.chunks + blockIdx.x) * g.C * 2;
+        for (int i = threadIdx.x; i < 2 * g.C; i += blockDim.x) du[i] = from_ordered_bits(i % 2 ? ~su[i] : su[i]);
+    }
 }
 
 // Any channel count: one element per thread step, keys straight into LDS atomics.
@@ -205,8 +236,7 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_kernel(const float *__res
             float o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float u = xe[e] * hard_sigmoid(vv[e] * xe[e]);
-                o[e] = gg[e] * u * inv[e] + bb[e];
+                o[e] = ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]);
                 am = fmaxf(am, fabsf(o[e]));
             }
             yv[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
@@ -232,11 +262,95 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_generic_kernel(const floa
         const int c = (int)(i % C);
         const float xe = x[(size_t)n * total + i];
         const float inv = inv_denominator(range[(size_t)n * groups + c / m], cm, eps);
-        const float o = gamma[c] * (xe * hard_sigmoid(v[c] * xe)) * inv + beta[c];
+        const float o = ren_y(ren_u(xe, v[c]), gamma[c], inv, beta[c]);
         y[(size_t)n * total + i] = o;
         am = fmaxf(am, fabsf(o));
     }
     if (absmax_out) block_absmax_commit(am, absmax_out, lds);
+}
+
+// ---- forward with int8 output -------------------------------------------------
+// Second launch of the int8-output forward, one block per sample: folds the sample's block keys (range and positions
+// for the backward pass) and the per-channel extremes of u, and from those the sample's max|y|: for fixed gamma,
+// inv > 0 and beta, y is a monotone function of u, so the extreme y of a channel sit at its extreme u.
+__global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsigned long long *__restrict__ pstats,
+                                                         const float *__restrict__ pu, const float *__restrict__ gamma,
+                                                         const float *__restrict__ beta, float cm, float eps,
+                                                         float *__restrict__ range_out, int32_t *__restrict__ argmax_out,
+                                                         int32_t *__restrict__ argmin_out, float *__restrict__ absmax) {
+    extern __shared__ unsigned long long skeys[];  // [groups][2], then float inv[groups]
+    __shared__ float lds[256 / kWave];
+    float *sinv = reinterpret_cast<float *>(skeys + 2 * g.groups);
+    const int n = blockIdx.x, nk = 2 * g.groups;
+    for (int i = threadIdx.x; i < nk; i += blockDim.x) skeys[i] = 0ull;
+    __syncthreads();
+    const unsigned long long *src = pstats + (size_t)n * g.chunks * nk;
+    for (int i = threadIdx.x; i < g.chunks * nk; i += blockDim.x) {
+        const unsigned long long k = src[i];
+        if (k) atomicMax(&skeys[i % nk], k);
+    }
+    __syncthreads();
+    for (int grp = threadIdx.x; grp < g.groups; grp += blockDim.x) {
+        const unsigned long long kmx = skeys[2 * grp], kmn = skeys[2 * grp + 1];
+        const float r = __fsub_rn(from_ordered_bits((uint32_t)(kmx >> 32)), from_ordered_bits(~(uint32_t)(kmn >> 32)));
+        sinv[grp] = inv_denominator(r, cm, eps);
+        range_out[(size_t)n * g.groups + grp] = r;
+        argmax_out[(size_t)n * g.groups + grp] = (int32_t)(~(uint32_t)kmx);
+        argmin_out[(size_t)n * g.groups + grp] = (int32_t)(~(uint32_t)kmn);
+    }
+    __syncthreads();
+    float am = 0.0f;
+    for (int c = threadIdx.x; c < g.C; c += blockDim.x) {
+        float hi = -INFINITY, lo = INFINITY;
+        const float *p = pu + (size_t)n * g.chunks * g.C * 2 + c * 2;
+        for (int ch = 0; ch < g.chunks; ++ch) { hi = fmaxf(hi, p[(size_t)ch * g.C * 2]); lo = fminf(lo, p[(size_t)ch * g.C * 2 + 1]); }
+        const float inv = sinv[c / g.m], gg = gamma[c], bb = beta[c];
+        am = fmaxf(am, fmaxf(fabsf(ren_y(hi, gg, inv, bb)), fabsf(ren_y(lo, gg, inv, bb))));
+    }
+    block_absmax_commit(am, absmax, lds);
+}
+
+// Third launch: y as the plain forward computes it, rounded to the nearest code with the scale max|y| / 127.
+__global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__restrict__ x, RenGeom g, const float *__restrict__ v,
+                                                                const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                                float cm, float eps, const float *__restrict__ range,
+                                                                const float *__restrict__ absmax, int8_t *__restrict__ q,
+                                                                float *__restrict__ scale) {
+    const int n = blockIdx.y;
+    const float a = *absmax;
+    if (blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *scale = __fdiv_rn(a, 127.0f);
+    if ((int)threadIdx.x >= g.threads) return;
+    const float qinv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
+    const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
+    const int p0 = blockIdx.x * g.pix_per_block, p1 = min(p0 + g.pix_per_block, g.HW);
+    float vv[4], gg[4], bb[4], inv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int c = qd * 4 + e;
+        vv[e] = v[c]; gg[e] = gamma[c]; bb[e] = beta[c];
+        inv[e] = inv_denominator(range[(size_t)n * g.groups + c / g.m], cm, eps);
+    }
+    const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
+    uint32_t *qv = reinterpret_cast<uint32_t *>(q + (size_t)n * g.HW * g.C);
+    for (int pb = p0 + pl; pb < p1; pb += kRU * g.ppi) {
+        float4 t[kRU];
+#pragma unroll
+        for (int k = 0; k < kRU; ++k) {
+            const int p = pb + k * g.ppi;
+            t[k] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < kRU; ++k) {
+            const int p = pb + k * g.ppi;
+            if (p >= p1) break;
+            const float xe[4] = {t[k].x, t[k].y, t[k].z, t[k].w};
+            uint32_t word = 0u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                word |= ((uint32_t)round_code(ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]), qinv, false, 0u) & 0xffu) << (8 * e);
+            qv[(size_t)p * g.cq + qd] = word;
+        }
+    }
 }
 
 // ---- backward ---------------------------------------------------------------
@@ -490,6 +604,47 @@ extern "C" size_t lpdt_range_evonorm_fwd_workspace_bytes(int N, int H, int W, in
     return round_up(blocks * groups * 2 * sizeof(unsigned long long), 256);
 }
 
+// int8-output forward: block keys, then the per-block channel extremes of u, then the scalar max|y|
+static size_t ren_q_key_bytes(const RenGeom &g) { return round_up((size_t)g.N * g.chunks * g.groups * 2 * sizeof(unsigned long long), 256); }
+static size_t ren_q_u_bytes(const RenGeom &g) { return round_up((size_t)g.N * g.chunks * g.C * 2 * sizeof(float), 256); }
+
+extern "C" size_t lpdt_range_evonorm_fwd_q_workspace_bytes(int N, int H, int W, int C, int groups) {
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups || !ren_fast(C)) return 0;
+    const RenGeom g = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems));
+    return ren_q_key_bytes(g) + ren_q_u_bytes(g) + 256;
+}
+
+extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                                        const float *gamma, const float *beta, float eps, int8_t *q, float *scale,
+                                        float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws, size_t ws_bytes,
+                                        void *stream) {
+    int rc = check_ren(x, N, H, W, C, groups);
+    if (rc) return rc;
+    LPDT_REQUIRE(v && gamma && beta && q && scale && range_out && argmax_out && argmin_out, LPDT_EINVAL,
+                 "range_evonorm_fwd_q: NULL argument");
+    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_fwd_q: eps must be >= 0");
+    LPDT_REQUIRE(ren_fast(C), LPDT_EUNSUPPORTED, "range_evonorm_fwd_q: C must be a multiple of 4, at most %d (got %d)", 4 * kRThreads, C);
+    LPDT_REQUIRE(aligned(x, 16) && aligned(q, 4) && aligned(scale, 4), LPDT_EINVAL,
+                 "range_evonorm_fwd_q: x must be 16-byte aligned, q and scale 4-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, groups));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    const float cm = ren_cm(C / groups);
+    const RenGeom g = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems));
+    const RenGeom ga = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kApplyElems));
+    unsigned long long *keys = static_cast<unsigned long long *>(ws);
+    float *pu = reinterpret_cast<float *>(static_cast<char *>(ws) + ren_q_key_bytes(g));
+    float *absmax = reinterpret_cast<float *>(static_cast<char *>(ws) + ren_q_key_bytes(g) + ren_q_u_bytes(g));
+    const size_t key_lds = (size_t)2 * groups * sizeof(unsigned long long);
+    hipLaunchKernelGGL(ren_stats_kernel<true>, dim3(g.chunks, N), dim3(g.block), key_lds + (size_t)2 * C * sizeof(unsigned int), st, x, g,
+                       keys, absmax, v, pu);
+    hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), key_lds + groups * sizeof(float), st, g, keys, pu, gamma, beta, cm, eps,
+                       range_out, argmax_out, argmin_out, absmax);
+    hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out,
+                       absmax, q, scale);
+    return launch_status("lpdt_range_evonorm_fwd_q");
+}
+
 extern "C" size_t lpdt_range_evonorm_bwd_workspace_bytes(int N, int H, int W, int C, int groups) {
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups) return 0;
     const size_t rows = ren_rows(N, H, W, C, groups);
@@ -515,7 +670,8 @@ extern "C" int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C
     const size_t smem = (size_t)2 * groups * sizeof(unsigned long long);
     if (ren_fast(C)) {
         const RenGeom g = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems));
-        hipLaunchKernelGGL(ren_stats_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, absmax_out);
+        hipLaunchKernelGGL(ren_stats_kernel<false>, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, absmax_out,
+                           (const float *)nullptr, (float *)nullptr);
         const RenGeom ga = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kApplyElems));
         hipLaunchKernelGGL(ren_apply_kernel, dim3(ga.chunks, N), dim3(ga.block), smem + groups * sizeof(float), st, x, ga, v, gamma,
                            beta, cm, eps, stats, g.chunks, y, range_out, argmax_out, argmin_out, absmax_out);

@@ -40,9 +40,10 @@ class TrainStep:
     (then `upstream` must be the gradient of the last tensor)."""
 
     def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5,
-                 wgrad_16bit=False, overlap_wgrad=True):
+                 wgrad_16bit=False, overlap_wgrad=True, fuse_ren_quant=True):
         self.L = lib()
         self.overlap_wgrad = overlap_wgrad
+        self.fuse_ren_quant = fuse_ren_quant   # Range-EvoNorm layers that feed only convolutions emit int8 codes directly
         self.net, self.N, self.lr, self.seed, self.eps = net, batch, lr, seed, eps
         # gradient bifurcation as the paper states it: weight gradients from a bfloat16 copy of the layer gradient
         # (the 8-bit codes still feed backward-data), for every layer but the one that reads the image; default: both
@@ -130,6 +131,12 @@ class TrainStep:
         # All filters are quantized by one call on the flat parameter vector (own scale each); their codes keep the
         # vector's layout, so a filter's codes are a 16-byte aligned slice when its offset is a multiple of 16.
         convs = [op for op in net.ops if op[0] == "conv"]
+        # tensors all of whose consumers are quantized convolutions (only their int8 codes are ever read)
+        readers = {}
+        for op in net.ops:
+            for src in (op[2:4] if op[0] == "add" else ([op[1]] if op[0] == "loss" else [op[2]])):
+                readers.setdefault(src, set()).add(op[0])
+        conv_only = {t for t, kinds in readers.items() if kinds == {"conv"}}
         spans = [self._poff[op[3]["w"]] for op in convs]
         batched = len(convs) > 1 and all(b % 16 == 0 for b, _ in spans)
         if batched:
@@ -166,13 +173,22 @@ class TrainStep:
                 _, out, inp, a = op
                 H, W, C = net.shapes[inp]
                 g = a["groups"]
-                y = self._f32(N, H, W, C)
-                self.act[out] = y
                 rng, amx, amn = self._f32(N, g), self._i32(N, g), self._i32(N, g)
                 self.ren_saved[out] = (rng, amx, amn)
+                pv = self.pview
+                if self.fuse_ren_quant and out in conv_only and L.lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, g) > 0:
+                    # every consumer is a quantized convolution: the layer emits the int8 codes itself, y is never stored
+                    self.xq[out], self.sx[out] = self._i8(N, H, W, C), self._f32(1)
+                    self._need_ws(L.lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, g))
+                    self._emit(L.lpdt_range_evonorm_fwd_q,
+                               [_p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
+                                _p(pv[a["p"] + ".beta"]), _f32(self.eps), _p(self.xq[out]), _p(self.sx[out]), _p(rng), _p(amx),
+                                _p(amn), "WS", "WSB"])
+                    continue
+                y = self._f32(N, H, W, C)
+                self.act[out] = y
                 self.absmax[out] = self._f32(1)
                 self._need_ws(L.lpdt_range_evonorm_fwd_workspace_bytes(N, H, W, C, g))
-                pv = self.pview
                 self._emit(L.lpdt_range_evonorm_fwd,
                            [_p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
                             _p(pv[a["p"] + ".beta"]), _f32(self.eps), _p(y), _p(rng), _p(amx), _p(amn),

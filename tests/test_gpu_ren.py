@@ -85,3 +85,34 @@ def test_negative_zero_and_determinism(orc):
     assert np.array_equal(host(out1[2]), amx_ref) and np.array_equal(host(out1[3]), amn_ref)
     for a, b in zip(out1, out2):
         assert np.array_equal(host(a), host(b))
+
+
+@pytest.mark.parametrize("shape", [c for c in CASES if c[3] % 4 == 0] + [(64, 14, 14, 256, 32)])
+def test_int8_output_forward_equals_forward_then_quantize(orc, shape):
+    """lpdt_range_evonorm_fwd_q: the codes and the scale of the plain forward followed by the round-to-nearest
+    quantizer, bit for bit; the saved range and positions of the plain forward; and, against the oracle's y, codes
+    within half a step plus the layer's tolerance."""
+    N, H, W, C, groups = shape
+    print("case", shape, flush=True)
+    x = wl.images(720, N, H, W, C) * np.float32(2.0)
+    v, gamma, beta = _params(721, C)
+    gamma[::3] *= np.float32(-1.0)                       # decreasing y(u) on some channels
+    xd, vd, gd, bd = dev(x), dev(v), dev(gamma), dev(beta)
+    y, r, amx, amn, absmax = lpdt.range_evonorm_fwd(xd, groups, vd, gd, bd, 1e-5, want_absmax=True)
+    q_ref, s_ref = lpdt.quantize_with_absmax(y, absmax, lpdt.ROUND_NEAREST)
+    q, s, r2, amx2, amn2 = lpdt.range_evonorm_fwd_q(xd, groups, vd, gd, bd, 1e-5)
+    import torch
+    assert torch.equal(s, s_ref) and torch.equal(q, q_ref)
+    assert torch.equal(r, r2) and torch.equal(amx, amx2) and torch.equal(amn, amn2)
+    y_ref, _, _, _ = orc.range_evonorm_fwd(x, groups, v, gamma, beta, 1e-5)
+    step = float(host(s)[0])
+    assert abs(step * 127 - np.abs(y_ref).max()) <= 1e-4 * np.abs(y_ref).max()
+    assert np.abs(host(q).astype(np.float64) * step - y_ref).max() <= 0.5 * step + 1e-4 * np.abs(y_ref).max()
+
+
+def test_int8_output_forward_rejects_odd_channel_counts():
+    import torch
+    x = torch.zeros((2, 5, 5, 6), device="cuda")
+    p = torch.ones(6, device="cuda")
+    with pytest.raises(lpdt.LpdtError):
+        lpdt.range_evonorm_fwd_q(x, 3, p, p, p)

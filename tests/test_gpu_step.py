@@ -261,3 +261,25 @@ def test_driver_with_16bit_weight_gradients():
     for nm, _ in net.params:            # Range-EvoNorm parameter gradients come from the same layer gradients
         if not nm.endswith(".w"):
             assert torch.equal(t8.gview[nm], t16.gview[nm]), nm
+
+
+def test_driver_int8_output_normalisation_changes_no_bit(orc):
+    """Range-EvoNorm layers that feed only convolutions emit their int8 codes directly (default); the step must give
+    exactly the gradients and the loss of the driver that stores y and quantizes it in a second call."""
+    from paper_2111_09389_amd.step import TrainStep
+    net = nets.resnet20()
+    N = 4
+    params = nets.init_params(net, wl.BASE_SEED + 12)
+    flat = np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32)
+    x = dev(wl.images(wl.BASE_SEED + 13, N, 32, 32, 3))
+    lb = dev(wl.labels_uniform(wl.BASE_SEED + 14, N, 10))
+    out = []
+    for fuse in (True, False):
+        p, g = dev(flat), torch.zeros(flat.size, dtype=torch.float32, device="cuda")
+        ts = TrainStep(net, N, p, g, x, lb, None, lr=0.05, seed=wl.PHILOX_SEED, fuse_ren_quant=fuse)
+        names = [c[0].__name__ for c in ts.calls if c[0] is not None]
+        assert ("lpdt_range_evonorm_fwd_q" in names) == fuse
+        ts.run(3)
+        torch.cuda.synchronize()
+        out.append((g.clone(), p.clone(), ts.loss.clone()))
+    assert all(torch.equal(a, b) for a, b in zip(*out))
