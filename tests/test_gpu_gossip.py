@@ -77,6 +77,22 @@ def test_choco_one_pass_selection(orc, sample_stride, stride):
     _choco_case(orc, 4, 200_000, [0, 200_000], 0.002, 1.0, 834)
 
 
+@pytest.mark.parametrize("stride", [0, 1, 8])
+def test_choco_many_tiny_segments_in_one_tile(orc, sample_stride, stride):
+    """More segment boundaries inside a 4096-element tile than the kernels keep at hand (32): the rest is walked from
+    memory; empty segments in between; then long segments again."""
+    sample_stride(stride)
+    g = wl.rng(850)
+    lens = [5000] + [int(v) for v in g.integers(1, 60, size=90)] + [0, 0, 7] + [int(v) for v in g.integers(1, 40, size=70)] + [9000, 3, 12000]
+    seg = [0]
+    for n_ in lens:
+        seg.append(seg[-1] + n_)
+    d = seg[-1]
+    _choco_case(orc, 5, d, seg, 0.1, 0.4, 852)
+    _choco_case(orc, 3, d, seg, 0.01, 0.9, 854)
+    _choco_case(orc, 2, d, seg, 0.5, 0.5, 856, ties=True)
+
+
 @pytest.mark.parametrize("loud", ["unsampled", "sampled"])
 def test_choco_one_pass_window_misses(orc, sample_stride, loud):
     """Sampled tiles that say nothing about the rest: the guessed window misses the threshold bin and the pair is
