@@ -241,11 +241,13 @@ __global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__rest
         if (threadIdx.x == 0) st[pair].prefix = ~0ull;
         return;
     }
+    // mode 1: only the window's bins were counted, the others are (still) zero and are neither read nor cleared
+    const unsigned int lo = mode == 1 ? st[pair].lo : 0u, hi = mode == 1 ? st[pair].hi : (unsigned int)(kBins - 1);
     unsigned int mine[kBins / kGThreads];
     unsigned int sum = 0;
     for (int k = 0; k < per; ++k) {
         const int b = kBins - 1 - (threadIdx.x * per + k);
-        mine[k] = (b < nb) ? h[b] : 0u;
+        mine[k] = (b < nb && (unsigned int)b >= lo && (unsigned int)b <= hi) ? h[b] : 0u;
         sum += mine[k];
     }
     part[threadIdx.x] = sum;
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(kGThreads) void choco_scan_kernel(PairState *__rest
             run += mine[k];
         }
     }
-    for (int i = threadIdx.x; i < kBins; i += kGThreads) h[i] = 0u;
+    for (unsigned int i = lo + threadIdx.x; i <= hi; i += kGThreads) h[i] = 0u;
 }
 
 // One-pass selection, step 1 of 2 (after a histogram of every stride-th tile): per (agent, segment), the window of bins
