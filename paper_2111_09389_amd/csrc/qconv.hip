@@ -347,10 +347,11 @@ static bool bwd_data_fusable(const lpdt_conv_desc *d, int P, int Q) {
 static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *wq, void *out,
                               int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st) {
     const size_t out_len = (size_t)d->N * d->H * d->W * d->C;
-    const bool stage = out_mode != 0 && !(bwd_data_fusable(d, P, Q) && aligned(gq, 16));
+    const bool al = aligned(gq, 16) && aligned(wq, 16);   // the matrix-core path loads both operands 16 bytes at a time
+    const bool stage = out_mode != 0 && !(bwd_data_fusable(d, P, Q) && al);
     int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_data_base_ws(d)) : static_cast<int32_t *>(out);
     const int mode = stage ? 0 : out_mode;
-    if (bwd_data_vec(d, P, Q) && aligned(gq, 16)) {
+    if (bwd_data_vec(d, P, Q) && al) {
         launch_igemm_bwd_data(d, P, Q, gq, wq, acc, mode, sA, sB, ws, st);
     } else {
         hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, gq, wq, acc, *d, P, Q);
@@ -386,7 +387,7 @@ extern "C" int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq
     if (rc) return rc;
     LPDT_REQUIRE(gq && wq && dx && sg && sw, LPDT_EINVAL, "qconv_bwd_data_f32: NULL argument");
     LPDT_REQUIRE(aligned(dx, 16), LPDT_EINVAL, "qconv_bwd_data_f32: dx must be 16-byte aligned");
-    const size_t need = aligned(gq, 16) ? lpdt_qconv_bwd_data_f32_workspace_bytes(d)
+    const size_t need = aligned(gq, 16) && aligned(wq, 16) ? lpdt_qconv_bwd_data_f32_workspace_bytes(d)
                                         : bwd_data_base_ws(d) + round_up((size_t)d->N * d->H * d->W * d->C * 4, 256);
     rc = check_ws(ws, ws_bytes, need);
     if (rc) return rc;

@@ -298,17 +298,30 @@ struct PackParams {
     int off[kMaxClasses + 1];  // element offsets of the panels
     int Rc[kMaxClasses], Sc[kMaxClasses];
 };
-__global__ void pack_filter_bwd_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wt, const PackParams q) {
-    const int total = q.off[q.nclasses];
-    for (int o = blockIdx.x * blockDim.x + threadIdx.x; o < total; o += gridDim.x * blockDim.x) {
-        int cl = 0;
-        while (cl + 1 < q.nclasses && o >= q.off[cl + 1]) ++cl;
-        const int e = o - q.off[cl];
-        const int k = e % q.K;
-        const int slot = (e / q.K) % (q.Rc[cl] * q.Sc[cl]);
-        const int c = e / (q.K * q.Rc[cl] * q.Sc[cl]);
-        const int tr = cl / q.stride + q.stride * (slot / q.Sc[cl]), ts = cl % q.stride + q.stride * (slot % q.Sc[cl]);
-        wt[o] = w[((size_t)(k * q.R + tr) * q.S + ts) * q.C + c];
+// A block transposes one 64 (c) x 64 (k) tile of one filter tap through LDS: 16-byte loads along c (contiguous in w),
+// 16-byte stores along k (contiguous in the panel).  grid = taps of all classes x c-tiles x k-tiles; C, K multiples of 16.
+__global__ __launch_bounds__(256) void pack_filter_bwd_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wt, const PackParams q) {
+    __shared__ unsigned char tile[64][64 + 16];  // [k][c], rows padded
+    const int tc = (q.C + 63) / 64, tk = (q.K + 63) / 64;
+    int b = blockIdx.x;
+    const int kt = b % tk; b /= tk;
+    const int ct = b % tc; b /= tc;   // b = tap index over all classes
+    int cl = 0;
+    while (cl + 1 < q.nclasses && b >= q.Rc[cl] * q.Sc[cl]) { b -= q.Rc[cl] * q.Sc[cl]; ++cl; }
+    const int slot = b, nslots = q.Rc[cl] * q.Sc[cl];
+    const int tr = cl / q.stride + q.stride * (slot / q.Sc[cl]), ts = cl % q.stride + q.stride * (slot % q.Sc[cl]);
+    const int k0 = kt * 64, c0 = ct * 64;
+    const int row = threadIdx.x / 4, chunk = (threadIdx.x % 4) * 16;
+    if (k0 + row < q.K && c0 + chunk < q.C)
+        *reinterpret_cast<int4 *>(&tile[row][chunk]) =
+            *reinterpret_cast<const int4 *>(w + ((size_t)((k0 + row) * q.R + tr) * q.S + ts) * q.C + c0 + chunk);
+    __syncthreads();
+    if (c0 + row < q.C && k0 + chunk < q.K) {   // this thread: channel c0 + row, 16 consecutive k
+        unsigned int o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[j / 4] |= (unsigned int)tile[chunk + j][row] << (8 * (j % 4));
+        *reinterpret_cast<int4 *>(wt + q.off[cl] + ((size_t)(c0 + row) * nslots + slot) * q.K + k0 + chunk) =
+            make_int4((int)o[0], (int)o[1], (int)o[2], (int)o[3]);
     }
 }
 
@@ -501,10 +514,10 @@ void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *
     IgemmParams p;
     PackParams pk;
     bwd_params(d, P, Q, &p, &pk);
-    const int total = pk.off[pk.nclasses];
-    int b = (total + 255) / 256;
-    if (b > 2048) b = 2048;
-    hipLaunchKernelGGL(pack_filter_bwd_kernel, dim3((unsigned)b), dim3(256), 0, st, w, static_cast<int8_t *>(panel), pk);
+    int taps = 0;
+    for (int cl = 0; cl < pk.nclasses; ++cl) taps += pk.Rc[cl] * pk.Sc[cl];
+    const int b = taps * ((pk.C + 63) / 64) * ((pk.K + 63) / 64);
+    if (b > 0) hipLaunchKernelGGL(pack_filter_bwd_kernel, dim3((unsigned)b), dim3(256), 0, st, w, static_cast<int8_t *>(panel), pk);
     p.in = g; p.wt = static_cast<const int8_t *>(panel); p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
     p.vec_out = d->C % 4 == 0 && aligned(out, 16);
     run(p, (size_t)d->N * d->H * d->W * d->C, st);
