@@ -184,6 +184,7 @@ __global__ __launch_bounds__(kCThreads) void conv_fwd_plain_kernel(const int8_t 
                 if (ww < 0 || ww >= d.W) continue;
                 const int8_t *xp = x + (((size_t)n * d.H + h) * d.W + ww) * d.C;
                 const int8_t *wp = w + (((size_t)k * d.R + r) * d.S + t) * d.C;
+#pragma unroll 8
                 for (int c = 0; c < d.C; ++c) s += (int)xp[c] * (int)wp[c];
             }
         }
@@ -212,6 +213,7 @@ __global__ __launch_bounds__(kCThreads) void conv_bwd_data_plain_kernel(const in
                 const int q = tx / d.stride_w;
                 if (q >= Q) continue;
                 const int8_t *gp = g + (((size_t)n * P + pp) * Q + q) * d.K;
+#pragma unroll 8
                 for (int k = 0; k < d.K; ++k) s += (int)gp[k] * (int)w[(((size_t)k * d.R + r) * d.S + t) * d.C + c];
             }
         }

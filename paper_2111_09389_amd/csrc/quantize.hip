@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kQThreads) void round_kernel(const float *__restric
 // Slice table in device memory: begin[s], end[s] (element indices), written from kernel arguments so that the call
 // needs no host-to-device copy and can be captured in a graph.
 constexpr int kSegChunk = 128;
-constexpr int kSegTile = kQThreads * 16;  // elements per block
+constexpr int kSegTile = kQThreads * 64;  // elements per block: few blocks (and few atomics) per slice, 16 quads per thread
 struct SegChunk { long long v[2 * kSegChunk]; };
 
 __global__ void seg_upload_kernel(SegChunk c, long long *table, unsigned int *amax, int first, int count) {
@@ -122,9 +122,16 @@ __global__ __launch_bounds__(kQThreads) void seg_absmax_kernel(const float *__re
     float m = 0.0f;
     if (((begin & 3) == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0)) {
         const long long v1 = t1 / 4;
-        for (long long i = t0 / 4 + threadIdx.x; i < v1; i += kQThreads) {
-            const float4 a = reinterpret_cast<const float4 *>(xs)[i];
-            m = fmaxf(fmaxf(m, fmaxf(fabsf(a.x), fabsf(a.y))), fmaxf(fabsf(a.z), fabsf(a.w)));
+        // four loads are issued before the first is used
+        for (long long i0 = t0 / 4 + threadIdx.x; i0 < v1; i0 += 4 * kQThreads) {
+            float4 a[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const long long i = i0 + (long long)k * kQThreads;
+                a[k] = i < v1 ? reinterpret_cast<const float4 *>(xs)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) m = fmaxf(fmaxf(m, fmaxf(fabsf(a[k].x), fabsf(a[k].y))), fmaxf(fabsf(a[k].z), fabsf(a[k].w)));
         }
         for (long long i = v1 * 4 + threadIdx.x; i < t1; i += kQThreads) m = fmaxf(m, fabsf(xs[i]));
     } else {
