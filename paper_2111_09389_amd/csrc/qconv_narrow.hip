@@ -77,6 +77,7 @@ struct NarrowParams {
     const int8_t *g;    // gradient codes [M][K]                     (weight gradient)
     int32_t *out;       // forward: [M][K] (fp32 when out_mode != 0) ; weight gradient: dw [K][R][S*C], zeroed before the launch
     int out_mode;       // forward only: 0 int32 sums, 1 fp32 sA*sB*sum
+    int vec_out;        // forward only: out is 16-byte aligned (16-byte stores)
     const float *sA, *sB;
     int M, K, C, R, SC, stride, PH, PW, P, Q;
     float inv_pq, inv_q;
@@ -116,22 +117,32 @@ __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
 #pragma unroll
         for (int r = 0; r < kNR; ++r)
             if (r < p.R) {
-                acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[r][0], acc[0], 0, 0, 0);
-                if (p.K > 32) acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[r][1], acc[1], 0, 0, 0);
+                // the filter is the row operand: a lane ends with 4 consecutive output channels of ONE pixel (16-byte stores)
+                acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[r][0], a[r], acc[0], 0, 0, 0);
+                if (p.K > 32) acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[r][1], a[r], acc[1], 0, 0, 0);
             }
+        const int mm = rb * 32 + lane % 32;
+        if (mm < p.M) {
 #pragma unroll
-        for (int tn = 0; tn < 2; ++tn) {
-            const int col = lane % 32 + 32 * tn;
-            if (col < p.K) {
+            for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int mm = rb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                    if (mm < p.M) {
-                        if (p.out_mode) reinterpret_cast<float *>(p.out)[(size_t)mm * p.K + col] = scale * (float)acc[tn][i];
-                        else p.out[(size_t)mm * p.K + col] = acc[tn][i];
+                for (int qd = 0; qd < 4; ++qd) {
+                    const int ch = 32 * tn + 8 * qd + 4 * half;   // K is a multiple of 16: a quad is inside or outside
+                    if (ch < p.K) {
+                        int32_t *dst = p.out + (size_t)mm * p.K + ch;
+                        if (!p.vec_out) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if (p.out_mode) reinterpret_cast<float *>(dst)[e] = scale * (float)acc[tn][4 * qd + e];
+                                else dst[e] = acc[tn][4 * qd + e];
+                            }
+                        } else if (p.out_mode)
+                            *reinterpret_cast<float4 *>(dst) = make_float4(scale * (float)acc[tn][4 * qd], scale * (float)acc[tn][4 * qd + 1],
+                                                                           scale * (float)acc[tn][4 * qd + 2], scale * (float)acc[tn][4 * qd + 3]);
+                        else
+                            *reinterpret_cast<int4 *>(dst) = make_int4(acc[tn][4 * qd], acc[tn][4 * qd + 1], acc[tn][4 * qd + 2], acc[tn][4 * qd + 3]);
                     }
                 }
-            }
         }
     }
 }
@@ -313,6 +324,7 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
     hipLaunchKernelGGL(pack_filter_rows_kernel, dim3((d->K * d->R * 32 + 255) / 256), dim3(256), 0, st, w, d->K, d->R, d->S * d->C, wr);
     NarrowParams p = narrow_params(d, P, Q, xp);
     p.wr = wr; p.out = acc; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
+    p.vec_out = aligned(acc, 16) ? 1 : 0;
     p.blocks_total = (p.M + 31) / 32;
     int grid = (p.blocks_total + 3) / 4;
     if (grid > 2048) grid = 2048;
