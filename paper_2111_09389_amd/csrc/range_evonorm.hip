@@ -487,8 +487,8 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float 
     block_absmax_store(am, pabs + row, lds);
 }
 
-// Second backward launch.  Blocks [0, ceil(C/32)): dbeta, dgamma, dv = column sums of parts over all rows in a fixed
-// order (32 channels x 8 row slices per block).  The remaining blocks take 256 (sample, group) pairs each: the gradient
+// Second backward launch.  Blocks [0, 3 ceil(C/8)): dbeta, dgamma, dv = column sums of parts over all rows in a fixed
+// order (one quantity, 8 channels x 32 row lanes per block).  The remaining blocks take 256 (sample, group) pairs each: the gradient
 // through the range, added at the saved extrema; they also fold max|dx| = max(block partials of the first launch, the
 // elements just changed) into absmax_out, which the first launch zeroed (a max is order-free, so this stays
 // deterministic).
@@ -499,34 +499,29 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
                                                              float *__restrict__ dx, float *__restrict__ dbeta,
                                                              float *__restrict__ dgamma, float *__restrict__ dv,
                                                              float *__restrict__ absmax_out) {
-    __shared__ float s[3][32][8];
+    __shared__ float s[32][8];
     __shared__ float lds[256 / kWave];
-    const int param_blocks = (C + 7) / 8;
+    const int param_blocks = 3 * ((C + 7) / 8);
     if ((int)blockIdx.x < param_blocks) {
-        // 8 channels x 32 row lanes; a lane's rows are summed four at a time (12 loads in flight) in a fixed order
-        const int cl = threadIdx.x % 8, sl = threadIdx.x / 8;
-        const int c = blockIdx.x * 8 + cl;
-        float acc[3] = {0.f, 0.f, 0.f};
+        // one of the three quantities, 8 channels x 32 row lanes; a lane's rows are summed eight at a time (8 loads in
+        // flight) in a fixed order
+        const int q = blockIdx.x % 3, cl = threadIdx.x % 8, sl = threadIdx.x / 8;
+        const int c = (blockIdx.x / 3) * 8 + cl;
+        float acc = 0.0f;
         if (c < C) {
-            for (int r = sl; r < rows; r += 128) {
-                float t[4][3];
+            for (int r = sl; r < rows; r += 256) {
+                float t[8];
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-#pragma unroll
-                    for (int q = 0; q < 3; ++q) {
-                        const int rr = r + 32 * k;
-                        t[k][q] = rr < rows ? parts[((size_t)rr * 4 + q) * C + c] : 0.0f;
-                    }
-#pragma unroll
-                for (int q = 0; q < 3; ++q) acc[q] += (t[0][q] + t[1][q]) + (t[2][q] + t[3][q]);
+                for (int k = 0; k < 8; ++k) t[k] = r + 32 * k < rows ? parts[((size_t)(r + 32 * k) * 4 + q) * C + c] : 0.0f;
+                acc += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
             }
         }
-        s[0][sl][cl] = acc[0]; s[1][sl][cl] = acc[1]; s[2][sl][cl] = acc[2];
+        s[sl][cl] = acc;
         __syncthreads();
-        if (sl < 3 && c < C) {  // row lane 0, 1, 2 finish dbeta, dgamma, dv
+        if (sl == 0 && c < C) {
             float t = 0;
-            for (int k = 0; k < 32; ++k) t += s[sl][k][cl];
-            (sl == 0 ? dbeta : sl == 1 ? dgamma : dv)[c] = t;
+            for (int k = 0; k < 32; ++k) t += s[k][cl];
+            (q == 0 ? dbeta : q == 1 ? dgamma : dv)[c] = t;
         }
         return;
     }
@@ -720,7 +715,7 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
         hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,
                            kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out);
     }
-    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3((C + 7) / 8 + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_bwd");
 }
