@@ -7,6 +7,10 @@
 //   forward : stats pass (per-block, per-group first arg-max / arg-min as packed 64-bit
 //             keys, no global atomics) -> apply pass (each block first folds the block
 //             keys of its sample, then does the elementwise work).  Two launches.
+//             With int8 output (for layers that feed only convolutions): the stats pass
+//             also takes per-channel extremes of u = x*hardsigmoid(v x), a one-block-per-
+//             sample fold turns them into the exact max|y|, and the apply pass writes the
+//             quantizer's codes instead of y.  Three launches, y never reaches memory.
 //   backward: one pass writes the elementwise part of dx and per-block channel
 //             partials; a second launch does the fixed-order reductions for dv, dgamma,
 //             dbeta and, in its last block, adds the range gradient at the saved
