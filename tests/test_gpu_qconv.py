@@ -96,3 +96,37 @@ def test_fused_fp32_epilogue_equals_int32_then_dequantize(orc, shp):
     assert np.abs(host(acc) - ref).max() <= 1e-5 * max(np.abs(ref).max(), 1.0)
     dw = lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), dsa, dsb)
     assert torch.equal(dw, lpdt.dequantize(lpdt.qconv_bwd_weight(ld, dev(g), dev(x)), dsa, dsb))
+
+
+def _random_shapes(seed, count):
+    """Seeded shapes across the kernels' decision boundaries: channel counts around multiples of 16, maps around the
+    tile and rectangle sizes, filters 1/3/5, strides 1/2, paddings 0..2, batch sizes that leave ragged tiles."""
+    g = wl.rng(seed)
+    out = []
+    while len(out) < count:
+        R = int(g.choice([1, 3, 3, 5]))
+        st, pd = int(g.choice([1, 1, 2])), int(g.integers(0, R // 2 + 2))
+        C = int(g.choice([16, 32, 48, 64, 80, 96, 128, 12, 40]))
+        K = int(g.choice([16, 32, 48, 64, 96, 128, 144, 24, 100]))
+        H, W = int(g.integers(R, 23)), int(g.integers(R, 23))
+        N = int(g.integers(1, 6))
+        if H + 2 * pd < R or W + 2 * pd < R or pd >= R:
+            continue
+        out.append((N, C, H, W, K, R, R, st, pd))
+    return out
+
+
+@pytest.mark.parametrize("shp", _random_shapes(4242, 28))
+def test_random_shapes_bit_exact_and_fused_epilogues(orc, shp):
+    print("case", shp, flush=True)
+    x, w, g = _data(shp, 900, "gauss")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    ref_f, ref_d, ref_w = orc.qconv_fwd(od, x, w), orc.qconv_bwd_data(od, g, w), orc.qconv_bwd_weight(od, g, x)
+    acc, dx, dw = lpdt.qconv_fwd(ld, dev(x), dev(w)), lpdt.qconv_bwd_data(ld, dev(g), dev(w)), lpdt.qconv_bwd_weight(ld, dev(g), dev(x))
+    assert np.array_equal(host(acc), ref_f), "forward"
+    assert np.array_equal(host(dx), ref_d), "backward-data"
+    assert np.array_equal(host(dw), ref_w), "backward-weight"
+    sa, sb = dev(np.array([0.0123], np.float32)), dev(np.array([3.3e-3], np.float32))
+    assert torch.equal(lpdt.qconv_fwd_f32(ld, dev(x), dev(w), sa, sb), lpdt.dequantize(acc, sa, sb))
+    assert torch.equal(lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), sa, sb), lpdt.dequantize(dx, sa, sb))
+    assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), lpdt.dequantize(dw, sa, sb))
