@@ -121,6 +121,13 @@ def test_range_evonorm_at_the_largest_activation(orc):
     for got, r, nm in ((dv, dv_ref, "dv"), (dg, dg_ref, "dgamma"), (db, db_ref, "dbeta")):
         # sums of 0.8 M terms of either sign per channel in fp32 (fixed order): a few 1e-6 of the sum of magnitudes
         assert_close(host(got), r, 1e-4, float(np.abs(r).max()), nm)
+    # the int8-output forward on the same 51 M elements: the codes and scale of forward + quantizer, bit for bit
+    import torch
+    z2, _, _, _, absmax = lpdt.range_evonorm_fwd(xd, groups, dev(v), dev(gamma), dev(beta), 1e-5, want_absmax=True)
+    q_ref, s_ref = lpdt.quantize_with_absmax(z2, absmax, lpdt.ROUND_NEAREST)
+    q, s, r2, amx2, amn2 = lpdt.range_evonorm_fwd_q(xd, groups, dev(v), dev(gamma), dev(beta), 1e-5)
+    assert torch.equal(s, s_ref) and torch.equal(q, q_ref)
+    assert torch.equal(r2, rng_d) and torch.equal(amx2, amx) and torch.equal(amn2, amn)
 
 
 def test_choco_mix_at_full_size():
