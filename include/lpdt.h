@@ -195,6 +195,25 @@ int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W,
                            float *dgamma, float *dbeta, float *absmax_out, void *ws, size_t ws_bytes,
                            void *stream);
 
+/* Range-EvoNorm directly followed by a max-pool (the stem of the residual networks), for a normalised tensor
+ * that nothing but the pool reads.  Forward: z [N,P,Q,C] and idx as lpdt_maxpool_fwd(lpdt_range_evonorm_fwd(x))
+ * would give them, bit for bit, and the layer's saved range / argmax / argmin; the normalised tensor itself is
+ * never stored.  Backward: from the pooled gradient dz [N,P,Q,C] and idx, everything
+ * lpdt_range_evonorm_bwd(lpdt_maxpool_bwd(dz, idx), x, ...) returns, bit for bit; needs k <= 2 * stride
+ * (LPDT_EUNSUPPORTED otherwise: use the two calls).  k, st, pd: window, stride, padding of the pool;
+ * C a multiple of 4, at most 1024; x, z, idx, dz, dx 16-byte aligned. */
+size_t lpdt_range_evonorm_maxpool_fwd_workspace_bytes(int N, int H, int W, int C, int groups);
+size_t lpdt_range_evonorm_maxpool_bwd_workspace_bytes(int N, int H, int W, int C, int groups);
+int lpdt_range_evonorm_maxpool_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                                   const float *gamma, const float *beta, float eps, int k, int st, int pd,
+                                   float *z, int32_t *idx, float *range_out, int32_t *argmax_out,
+                                   int32_t *argmin_out, void *ws, size_t ws_bytes, void *stream);
+int lpdt_range_evonorm_maxpool_bwd(const float *dz, const int32_t *idx, const float *x, int N, int H, int W,
+                                   int C, int groups, const float *v, const float *gamma, float eps, int k,
+                                   int st, int pd, const float *range, const int32_t *argmax,
+                                   const int32_t *argmin, float *dx, float *dv, float *dgamma, float *dbeta,
+                                   float *absmax_out, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------- full-precision comparison layers
  * The two layers Section 3 sets Range-EvoNorm against, as fp32 reference layers with the same
  * tensor conventions (x, y, dy, dx fp32 [N,H,W,C], 16-byte aligned; per-channel vectors fp32 [C];

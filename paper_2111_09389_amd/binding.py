@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -32,6 +32,8 @@ EXPORTS = [
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_fwd_q",
+    "lpdt_range_evonorm_maxpool_fwd_workspace_bytes", "lpdt_range_evonorm_maxpool_bwd_workspace_bytes",
+    "lpdt_range_evonorm_maxpool_fwd", "lpdt_range_evonorm_maxpool_bwd",
     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
     "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
@@ -93,7 +95,8 @@ def lib():
                      "lpdt_qconv_bwd_weight_bf16_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
-                     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
+                     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
+                     "lpdt_range_evonorm_maxpool_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
         for name in ("lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 4
@@ -287,6 +290,40 @@ def range_evonorm_fwd_q(x, groups, v, gamma, beta, eps=1e-5, q=None, ws=None):
     _check(lib().lpdt_range_evonorm_fwd_q(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta), ctypes.c_float(eps),
                                           _ptr(q), _ptr(scale), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
     return q, scale, rng, amx, amn
+
+
+def range_evonorm_maxpool_fwd(x, groups, v, gamma, beta, k, stride, pad, eps=1e-5, ws=None):
+    """maxpool(range_evonorm(x)) without storing the normalised tensor -> (z, idx, range, argmax, argmin)."""
+    _dev(x, torch.float32, "range_evonorm_maxpool_fwd x")
+    N, H, W, C = x.shape
+    dev = x.device
+    P, Q = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    z = torch.empty((N, P, Q, C), dtype=torch.float32, device=dev)
+    idx = torch.empty((N, P, Q, C), dtype=torch.int32, device=dev)
+    rng = torch.empty((N, groups), dtype=torch.float32, device=dev)
+    amx = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    amn = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    buf, nb = _ws(ws, lib().lpdt_range_evonorm_maxpool_fwd_workspace_bytes(N, H, W, C, int(groups)))
+    _check(lib().lpdt_range_evonorm_maxpool_fwd(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta),
+                                                ctypes.c_float(eps), int(k), int(stride), int(pad), _ptr(z), _ptr(idx), _ptr(rng),
+                                                _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
+    return z, idx, rng, amx, amn
+
+
+def range_evonorm_maxpool_bwd(dz, idx, x, groups, v, gamma, rng, amx, amn, k, stride, pad, eps=1e-5, want_absmax=False, ws=None):
+    """Backward of range_evonorm_maxpool_fwd -> (dx, dv, dgamma, dbeta[, absmax])."""
+    _dev(x, torch.float32, "range_evonorm_maxpool_bwd x"); _dev(dz, torch.float32, "range_evonorm_maxpool_bwd dz")
+    _dev(idx, torch.int32, "range_evonorm_maxpool_bwd idx")
+    N, H, W, C = x.shape
+    dev = x.device
+    dx = torch.empty_like(x)
+    dv, dg, db = (torch.empty(C, dtype=torch.float32, device=dev) for _ in range(3))
+    absmax = torch.empty(1, dtype=torch.float32, device=dev) if want_absmax else None
+    buf, nb = _ws(ws, lib().lpdt_range_evonorm_maxpool_bwd_workspace_bytes(N, H, W, C, int(groups)))
+    _check(lib().lpdt_range_evonorm_maxpool_bwd(_ptr(dz), _ptr(idx), _ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma),
+                                                ctypes.c_float(eps), int(k), int(stride), int(pad), _ptr(rng), _ptr(amx), _ptr(amn),
+                                                _ptr(dx), _ptr(dv), _ptr(dg), _ptr(db), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
+    return (dx, dv, dg, db, absmax) if want_absmax else (dx, dv, dg, db)
 
 
 def range_evonorm_bwd(dy, x, groups, v, gamma, rng, amx, amn, eps=1e-5, dx=None, want_absmax=False, ws=None):

@@ -357,11 +357,117 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
     }
 }
 
+// ---- forward followed by a max-pool --------------------------------------------
+struct PoolGeom { int W, P, Q, k, st, pd; };   // input width, pooled map, window, stride, padding
+// z = maxpool(y) and the winners' positions, with y evaluated at the window's pixels instead of being stored: the
+// arithmetic of the plain forward (ren_y) and the selection rule of the max-pool kernel (first in window scan order on
+// ties, padding never wins), so the results are the two calls' bit for bit.  g describes the POOLED map (HW = P*Q).
+__global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__restrict__ x, RenGeom g, int H, int W, PoolGeom pg,
+                                                             const float *__restrict__ v, const float *__restrict__ gamma,
+                                                             const float *__restrict__ beta, float cm, float eps,
+                                                             const unsigned long long *__restrict__ pstats, int stat_chunks,
+                                                             float *__restrict__ z, int32_t *__restrict__ idx,
+                                                             float *__restrict__ range_out, int32_t *__restrict__ argmax_out,
+                                                             int32_t *__restrict__ argmin_out) {
+    extern __shared__ unsigned long long skeys[];  // [groups][2], then float range[groups]
+    float *srange = reinterpret_cast<float *>(skeys + 2 * g.groups);
+    const int n = blockIdx.y;
+    {
+        const int nk = 2 * g.groups;
+        for (int i = threadIdx.x; i < nk; i += blockDim.x) skeys[i] = 0ull;
+        __syncthreads();
+        const unsigned long long *src = pstats + (size_t)n * stat_chunks * nk;
+        for (int i = threadIdx.x; i < stat_chunks * nk; i += blockDim.x) {
+            const unsigned long long k = src[i];
+            if (k) atomicMax(&skeys[i % nk], k);
+        }
+        __syncthreads();
+    }
+    for (int grp = threadIdx.x; grp < g.groups; grp += blockDim.x) {
+        const unsigned long long kmx = skeys[2 * grp], kmn = skeys[2 * grp + 1];
+        const float r = __fsub_rn(from_ordered_bits((uint32_t)(kmx >> 32)), from_ordered_bits(~(uint32_t)(kmn >> 32)));
+        srange[grp] = r;
+        if (blockIdx.x == 0) {
+            range_out[(size_t)n * g.groups + grp] = r;
+            argmax_out[(size_t)n * g.groups + grp] = (int32_t)(~(uint32_t)kmx);
+            argmin_out[(size_t)n * g.groups + grp] = (int32_t)(~(uint32_t)kmn);
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x >= g.threads) return;
+    const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
+    const int p0 = blockIdx.x * g.pix_per_block, p1 = min(p0 + g.pix_per_block, g.HW);
+    float vv[4], gg[4], bb[4], inv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int c = qd * 4 + e;
+        vv[e] = v[c]; gg[e] = gamma[c]; bb[e] = beta[c];
+        inv[e] = inv_denominator(srange[c / g.m], cm, eps);
+    }
+    const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * H * W * g.C);
+    float4 *zv = reinterpret_cast<float4 *>(z + (size_t)n * g.HW * g.C);
+    int4 *iv = reinterpret_cast<int4 *>(idx + (size_t)n * g.HW * g.C);
+    for (int pp = p0 + pl; pp < p1; pp += g.ppi) {
+        const int p = pp / pg.Q, q = pp - p * pg.Q;
+        float best[4] = {0.f, 0.f, 0.f, 0.f};
+        int bi[4] = {-1, -1, -1, -1};
+        for (int i = 0; i < pg.k; ++i) {
+            const int h = p * pg.st + i - pg.pd;
+            if (h < 0 || h >= H) continue;
+#pragma unroll 3
+            for (int j = 0; j < pg.k; ++j) {
+                const int w = q * pg.st + j - pg.pd;
+                if (w < 0 || w >= W) continue;
+                const float4 t = xv[(size_t)(h * W + w) * g.cq + qd];
+                const float xe[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float y = ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]);
+                    if (bi[e] < 0 || y > best[e]) { best[e] = y; bi[e] = h * W + w; }
+                }
+            }
+        }
+        zv[(size_t)pp * g.cq + qd] = make_float4(best[0], best[1], best[2], best[3]);
+        iv[(size_t)pp * g.cq + qd] = make_int4(bi[0], bi[1], bi[2], bi[3]);
+    }
+}
+
 // ---- backward ---------------------------------------------------------------
 // Per element: z = v x, s = hs(z), s' = 1/6 on (-3,3), u = x s, du = dy gamma / D,
 //   dx = du (s + x v s'),  dbeta += dy,  dgamma += dy u / D,  dv += du x^2 s',
 //   T += dy gamma u   (dD = -T / D^2, dRange = C(m) dD).
 // parts layout: [row = n*chunks + chunk][4 quantities][C]
+// The layer's output gradient at one pixel when the output went through a max-pool only: the sum, over the (at most
+// 2 x 2) windows holding the pixel, of the pooled gradients whose winner it was -- the arithmetic of the max-pool
+// backward kernel (same order of additions), evaluated where it is consumed.  dz, idx: this sample's pooled maps.
+__device__ __forceinline__ float4 pooled_grad(const float4 *__restrict__ dz, const int4 *__restrict__ idx, int p, const PoolGeom &pg,
+                                              int cq, int qd) {
+    const int h = p / pg.W, w = p - h * pg.W;
+    const int p_lo = max(0, (h + pg.pd - pg.k + pg.st) / pg.st), p_hi = min(pg.P - 1, (h + pg.pd) / pg.st);
+    const int q_lo = max(0, (w + pg.pd - pg.k + pg.st) / pg.st), q_hi = min(pg.Q - 1, (w + pg.pd) / pg.st);
+    int4 id[4];
+    float4 gq[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int pp = p_lo + j / 2, qq = q_lo + j % 2;
+        const bool ok = pp <= p_hi && qq <= q_hi;
+        const size_t at = (size_t)(pp * pg.Q + qq) * cq + qd;
+        id[j] = ok ? idx[at] : make_int4(-1, -1, -1, -1);
+        gq[j] = ok ? dz[at] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (id[j].x == p) s.x += gq[j].x;
+        if (id[j].y == p) s.y += gq[j].y;
+        if (id[j].z == p) s.z += gq[j].z;
+        if (id[j].w == p) s.w += gq[j].w;
+    }
+    return s;
+}
+
+// kPooled: dy is not read; it is gathered from the pooled gradient dz and the winners idx (see pooled_grad).
+template <bool kPooled>
 __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__restrict__ dy, const float *__restrict__ x,
                                                                  RenGeom g, const float *__restrict__ v,
                                                                  const float *__restrict__ gamma, float cm, float eps,
@@ -369,7 +475,9 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
                                                                  const int32_t *__restrict__ argmax,
                                                                  const int32_t *__restrict__ argmin,
                                                                  float *__restrict__ dx, float *__restrict__ parts,
-                                                                 float *__restrict__ pabs, float *__restrict__ absmax_out) {
+                                                                 float *__restrict__ pabs, float *__restrict__ absmax_out,
+                                                                 const float *__restrict__ dz, const int32_t *__restrict__ idx,
+                                                                 PoolGeom pg) {
     extern __shared__ float sred[];  // [4][threads*4]
     __shared__ float lds[kRThreads / kWave];
     const int n = blockIdx.y;
@@ -391,7 +499,10 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
     float sb[4] = {0, 0, 0, 0}, sg[4] = {0, 0, 0, 0}, sv[4] = {0, 0, 0, 0}, st[4] = {0, 0, 0, 0};
     const size_t base = (size_t)n * g.HW * g.C;
     const float4 *xv = reinterpret_cast<const float4 *>(x + base);
-    const float4 *dv4 = reinterpret_cast<const float4 *>(dy + base);
+    const float4 *dv4 = kPooled ? nullptr : reinterpret_cast<const float4 *>(dy + base);
+    const size_t pooled_base = kPooled ? (size_t)n * pg.P * pg.Q * g.C : 0;
+    const float4 *dz4 = kPooled ? reinterpret_cast<const float4 *>(dz + pooled_base) : nullptr;
+    const int4 *idx4 = kPooled ? reinterpret_cast<const int4 *>(idx + pooled_base) : nullptr;
     float4 *ov = reinterpret_cast<float4 *>(dx + base);
     float am = 0.0f;
     const bool active = (int)threadIdx.x < g.threads;
@@ -401,7 +512,8 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
         for (int k = 0; k < kRU; ++k) {
             const int p = pb + k * g.ppi;
             a4[k] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
-            d4[k] = p < p1 ? dv4[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (kPooled) d4[k] = p < p1 ? pooled_grad(dz4, idx4, p, pg, g.cq, qd) : make_float4(0.f, 0.f, 0.f, 0.f);
+            else d4[k] = p < p1 ? dv4[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int k = 0; k < kRU; ++k) {
@@ -688,6 +800,84 @@ extern "C" int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C
     return launch_status("lpdt_range_evonorm_fwd");
 }
 
+static int check_ren_pool(const char *what, int N, int H, int W, int C, int groups, int k, int st, int pd) {
+    LPDT_REQUIRE(ren_fast(C), LPDT_EUNSUPPORTED, "%s: C must be a multiple of 4, at most %d (got %d)", what, 4 * kRThreads, C);
+    LPDT_REQUIRE(k > 0 && st > 0 && pd >= 0 && pd < k, LPDT_EINVAL, "%s: need k > 0, stride > 0, 0 <= pad < k", what);
+    LPDT_REQUIRE(H + 2 * pd >= k && W + 2 * pd >= k, LPDT_EINVAL, "%s: window larger than the padded map", what);
+    LPDT_REQUIRE((size_t)N * H * W * C < ((size_t)1 << 31), LPDT_EUNSUPPORTED, "%s: tensor too large", what);
+    (void)groups;
+    return LPDT_OK;
+}
+
+extern "C" size_t lpdt_range_evonorm_maxpool_fwd_workspace_bytes(int N, int H, int W, int C, int groups) {
+    return ren_fast(C) ? lpdt_range_evonorm_fwd_workspace_bytes(N, H, W, C, groups) : 0;
+}
+extern "C" size_t lpdt_range_evonorm_maxpool_bwd_workspace_bytes(int N, int H, int W, int C, int groups) {
+    return ren_fast(C) ? lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, groups) : 0;
+}
+
+extern "C" int lpdt_range_evonorm_maxpool_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
+                                              const float *gamma, const float *beta, float eps, int k, int st_, int pd, float *z,
+                                              int32_t *idx, float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws,
+                                              size_t ws_bytes, void *stream) {
+    int rc = check_ren(x, N, H, W, C, groups);
+    if (rc) return rc;
+    rc = check_ren_pool("range_evonorm_maxpool_fwd", N, H, W, C, groups, k, st_, pd);
+    if (rc) return rc;
+    LPDT_REQUIRE(v && gamma && beta && z && idx && range_out && argmax_out && argmin_out, LPDT_EINVAL,
+                 "range_evonorm_maxpool_fwd: NULL argument");
+    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_maxpool_fwd: eps must be >= 0");
+    LPDT_REQUIRE(aligned(x, 16) && aligned(z, 16) && aligned(idx, 16), LPDT_EINVAL,
+                 "range_evonorm_maxpool_fwd: x, z and idx must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_maxpool_fwd_workspace_bytes(N, H, W, C, groups));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    const int P = conv_out(H, pd, k, st_), Q = conv_out(W, pd, k, st_);
+    const RenGeom g = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems));
+    const RenGeom gp = ren_geom(N, P, Q, C, groups, 0, block_cap(N, P, Q, C, kApplyElems / 4));
+    unsigned long long *stats = static_cast<unsigned long long *>(ws);
+    const size_t smem = (size_t)2 * groups * sizeof(unsigned long long);
+    hipLaunchKernelGGL(ren_stats_kernel<false>, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, (float *)nullptr,
+                       (const float *)nullptr, (float *)nullptr);
+    hipLaunchKernelGGL(ren_pool_kernel, dim3(gp.chunks, N), dim3(gp.block), smem + groups * sizeof(float), st, x, gp, H, W,
+                       PoolGeom{W, P, Q, k, st_, pd}, v, gamma, beta, ren_cm(C / groups), eps, stats, g.chunks, z, idx, range_out,
+                       argmax_out, argmin_out);
+    return launch_status("lpdt_range_evonorm_maxpool_fwd");
+}
+
+extern "C" int lpdt_range_evonorm_maxpool_bwd(const float *dz, const int32_t *idx, const float *x, int N, int H, int W, int C,
+                                              int groups, const float *v, const float *gamma, float eps, int k, int st_, int pd,
+                                              const float *range, const int32_t *argmax, const int32_t *argmin, float *dx,
+                                              float *dv, float *dgamma, float *dbeta, float *absmax_out, void *ws, size_t ws_bytes,
+                                              void *stream) {
+    int rc = check_ren(x, N, H, W, C, groups);
+    if (rc) return rc;
+    rc = check_ren_pool("range_evonorm_maxpool_bwd", N, H, W, C, groups, k, st_, pd);
+    if (rc) return rc;
+    LPDT_REQUIRE((k + st_ - 1) / st_ <= 2, LPDT_EUNSUPPORTED,
+                 "range_evonorm_maxpool_bwd: a pixel may lie in at most 2 x 2 windows (k <= 2 * stride)");
+    LPDT_REQUIRE(dz && idx && v && gamma && range && argmax && argmin && dx && dv && dgamma && dbeta, LPDT_EINVAL,
+                 "range_evonorm_maxpool_bwd: NULL argument");
+    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_maxpool_bwd: eps must be >= 0");
+    LPDT_REQUIRE(aligned(x, 16) && aligned(dz, 16) && aligned(idx, 16) && aligned(dx, 16), LPDT_EINVAL,
+                 "range_evonorm_maxpool_bwd: x, dz, idx and dx must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_maxpool_bwd_workspace_bytes(N, H, W, C, groups));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    const int m = C / groups, P = conv_out(H, pd, k, st_), Q = conv_out(W, pd, k, st_);
+    const float cm = ren_cm(m);
+    const size_t rows = ren_rows(N, H, W, C, groups);
+    float *parts = static_cast<float *>(ws);
+    float *pabs = reinterpret_cast<float *>(static_cast<char *>(ws) + round_up(rows * 4 * C * sizeof(float), 256));
+    const RenGeom g = ren_geom(N, H, W, C, groups, kBwdMinPix, block_cap(N, H, W, C, kBwdElems));
+    hipLaunchKernelGGL(ren_bwd_main_kernel<true>, dim3(g.chunks, N), dim3(g.block), (size_t)16 * g.threads * sizeof(float), st,
+                       (const float *)nullptr, x, g, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out, dz, idx,
+                       PoolGeom{W, P, Q, k, st_, pd});
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+                       groups, m, g.chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
+    return launch_status("lpdt_range_evonorm_maxpool_bwd");
+}
+
 extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W, int C, int groups,
                                       const float *v, const float *gamma, float eps, const float *range,
                                       const int32_t *argmax, const int32_t *argmin, float *dx, float *dv, float *dgamma,
@@ -712,8 +902,9 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
         const RenGeom g = ren_geom(N, H, W, C, groups, kBwdMinPix, block_cap(N, H, W, C, kBwdElems));
         chunks = g.chunks;
         const size_t smem = (size_t)16 * g.threads * sizeof(float);
-        hipLaunchKernelGGL(ren_bwd_main_kernel, dim3(g.chunks, N), dim3(g.block), smem, st, dy, x, g, v, gamma, cm, eps,
-                           range, argmax, argmin, dx, parts, pabs, absmax_out);
+        hipLaunchKernelGGL(ren_bwd_main_kernel<false>, dim3(g.chunks, N), dim3(g.block), smem, st, dy, x, g, v, gamma, cm, eps,
+                           range, argmax, argmin, dx, parts, pabs, absmax_out, (const float *)nullptr, (const int32_t *)nullptr,
+                           PoolGeom{});
     } else {
         chunks = (H * W + kGenericPix - 1) / kGenericPix;
         hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,

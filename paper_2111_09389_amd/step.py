@@ -137,6 +137,12 @@ class TrainStep:
             for src in (op[2:4] if op[0] == "add" else ([op[1]] if op[0] == "loss" else [op[2]])):
                 readers.setdefault(src, set()).add(op[0])
         conv_only = {t for t, kinds in readers.items() if kinds == {"conv"}}
+        # normalised tensors read by exactly one op, a max-pool: tensor -> that op
+        pooled_by = {}
+        for op in net.ops:
+            if op[0] == "maxpool" and self.consumers.get(op[2], 0) == 1:
+                pooled_by[op[2]] = op
+        self.fused_pool = {}             # pooled tensor -> the normalised tensor that is never stored
         spans = [self._poff[op[3]["w"]] for op in convs]
         batched = len(convs) > 1 and all(b % 16 == 0 for b, _ in spans)
         if batched:
@@ -176,6 +182,20 @@ class TrainStep:
                 rng, amx, amn = self._f32(N, g), self._i32(N, g), self._i32(N, g)
                 self.ren_saved[out] = (rng, amx, amn)
                 pv = self.pview
+                pool = pooled_by.get(out)
+                if (self.fuse_ren_quant and pool is not None and pool[3]["k"] <= 2 * pool[3]["stride"]
+                        and L.lpdt_range_evonorm_maxpool_fwd_workspace_bytes(N, H, W, C, g) > 0):
+                    # the only reader is a max-pool: one call gives the pooled tensor, y is never stored
+                    pa, pout = pool[3], pool[1]
+                    z, idx = self._f32(N, *net.shapes[pout]), self._i32(N, *net.shapes[pout])
+                    self.act[pout], self.pool_idx[pout] = z, idx
+                    self.fused_pool[pout] = out
+                    self._need_ws(L.lpdt_range_evonorm_maxpool_fwd_workspace_bytes(N, H, W, C, g))
+                    self._emit(L.lpdt_range_evonorm_maxpool_fwd,
+                               [_p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
+                                _p(pv[a["p"] + ".beta"]), _f32(self.eps), pa["k"], pa["stride"], pa["pad"], _p(z), _p(idx), _p(rng),
+                                _p(amx), _p(amn), "WS", "WSB"])
+                    continue
                 if self.fuse_ren_quant and out in conv_only and L.lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, g) > 0:
                     # every consumer is a quantized convolution: the layer emits the int8 codes itself, y is never stored
                     self.xq[out], self.sx[out] = self._i8(N, H, W, C), self._f32(1)
@@ -200,6 +220,8 @@ class TrainStep:
                 self._emit(L.lpdt_add, [_p(self.act[a_]), _p(self.act[b_]), _sz(y.numel()), _p(y)])
             elif kind == "maxpool":
                 _, out, inp, a = op
+                if out in self.fused_pool:       # produced together with the normalisation layer before it
+                    continue
                 H, W, C = net.shapes[inp]
                 y = self._f32(N, *net.shapes[out])
                 idx = self._i32(N, *net.shapes[out])
@@ -235,6 +257,7 @@ class TrainStep:
     def _plan_backward(self):
         net, N, L = self.net, self.N, self.L
         self.gabsmax, self.gq, self.sg, self._keep = {}, {}, {}, []
+        self.pooled_grad = {}            # normalised tensor -> (pooled gradient, winners, pool attributes) when fused
         pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
         conv_index = 0
         for op in reversed(net.ops):
@@ -244,7 +267,7 @@ class TrainStep:
             out = op[1]
             pending.discard(out)
             dy = self.grad.get(out)
-            if dy is None:
+            if dy is None and out not in self.pooled_grad:
                 raise LpdtError(-2, f"tensor {out} has no gradient (dead branch)")
             if kind == "conv":
                 _, _, inp, a = op
@@ -282,6 +305,15 @@ class TrainStep:
                 self.gabsmax[inp] = self._f32(1)
                 rng, amx, amn = self.ren_saved[out]
                 pv, gv = self.pview, self.gview
+                if out in self.pooled_grad:      # the layer's output went through a max-pool only: gather its gradient on the fly
+                    dz, idx, pa = self.pooled_grad[out]
+                    self._need_ws(L.lpdt_range_evonorm_maxpool_bwd_workspace_bytes(N, H, W, C, g))
+                    self._emit(L.lpdt_range_evonorm_maxpool_bwd,
+                               [_p(dz), _p(idx), _p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
+                                _f32(self.eps), pa["k"], pa["stride"], pa["pad"], _p(rng), _p(amx), _p(amn), _p(dx),
+                                _p(gv[a["p"] + ".v"]), _p(gv[a["p"] + ".gamma"]), _p(gv[a["p"] + ".beta"]), _p(self.gabsmax[inp]),
+                                "WS", "WSB"])
+                    continue
                 self._need_ws(L.lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, g))
                 self._emit(L.lpdt_range_evonorm_bwd,
                            [_p(dy), _p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
@@ -300,6 +332,9 @@ class TrainStep:
                         self._emit(L.lpdt_add, [_p(buf), _p(dy), _sz(buf.numel()), _p(buf)])
             elif kind == "maxpool":
                 _, _, inp, a = op
+                if out in self.fused_pool:       # its backward is part of the normalisation layer's
+                    self.pooled_grad[inp] = (dy, self.pool_idx[out], a)
+                    continue
                 H, W, C = net.shapes[inp]
                 if inp in self.grad:
                     raise LpdtError(-2, f"max-pool input {inp} has another consumer")

@@ -116,3 +116,39 @@ def test_int8_output_forward_rejects_odd_channel_counts():
     p = torch.ones(6, device="cuda")
     with pytest.raises(lpdt.LpdtError):
         lpdt.range_evonorm_fwd_q(x, 3, p, p, p)
+
+
+@pytest.mark.parametrize("shape,pool", [((2, 17, 19, 16, 8), (3, 2, 1)), ((3, 32, 32, 64, 32), (3, 2, 1)), ((2, 12, 12, 32, 8), (2, 2, 0)),
+                                        ((1, 9, 9, 48, 6), (3, 3, 0)), ((4, 56, 56, 64, 32), (3, 2, 1))])
+def test_normalisation_followed_by_max_pool_equals_the_two_calls(shape, pool):
+    """lpdt_range_evonorm_maxpool_fwd / _bwd: the pooled output, the winners, the saved statistics and every gradient of
+    the two separate calls, bit for bit (values on a coarse grid in one case, so that ties inside windows occur)."""
+    import torch
+    N, H, W, C, groups = shape
+    k, st, pd = pool
+    print("case", shape, pool, flush=True)
+    x = wl.images(740, N, H, W, C) * np.float32(2.0)
+    if H == 12:
+        x = (np.round(x * 2) / 2).astype(np.float32)
+    v, gamma, beta = _params(741, C)
+    xd, vd, gd, bd = dev(x), dev(v), dev(gamma), dev(beta)
+    y, r, amx, amn = lpdt.range_evonorm_fwd(xd, groups, vd, gd, bd, 1e-5)
+    z_ref, idx_ref = lpdt.maxpool_fwd(y, k, st, pd)
+    z, idx, r2, amx2, amn2 = lpdt.range_evonorm_maxpool_fwd(xd, groups, vd, gd, bd, k, st, pd, 1e-5)
+    assert torch.equal(z, z_ref) and torch.equal(idx, idx_ref)
+    assert torch.equal(r, r2) and torch.equal(amx, amx2) and torch.equal(amn, amn2)
+    dz = dev(wl.upstream_grad(742, tuple(z.shape)))
+    dy = lpdt.maxpool_bwd(dz, idx_ref, (N, H, W, C), k, st, pd)
+    ref = lpdt.range_evonorm_bwd(dy, xd, groups, vd, gd, r, amx, amn, 1e-5, want_absmax=True)
+    got = lpdt.range_evonorm_maxpool_bwd(dz, idx, xd, groups, vd, gd, r, amx, amn, k, st, pd, 1e-5, want_absmax=True)
+    for a, b, name in zip(got, ref, ("dx", "dv", "dgamma", "dbeta", "absmax")):
+        assert torch.equal(a, b), name
+
+
+def test_normalisation_followed_by_max_pool_rejects_wide_windows():
+    import torch
+    x = torch.zeros((1, 8, 8, 8), device="cuda")
+    p = torch.ones(8, device="cuda")
+    z, idx, r, a, b = lpdt.range_evonorm_maxpool_fwd(x, 2, p, p, p, 3, 1, 1)       # forward takes any window
+    with pytest.raises(lpdt.LpdtError):
+        lpdt.range_evonorm_maxpool_bwd(z, idx, x, 2, p, p, r, a, b, 3, 1, 1)       # a pixel in 3 x 3 windows: two calls

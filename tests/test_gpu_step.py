@@ -283,3 +283,27 @@ def test_driver_int8_output_normalisation_changes_no_bit(orc):
         torch.cuda.synchronize()
         out.append((g.clone(), p.clone(), ts.loss.clone()))
     assert all(torch.equal(a, b) for a, b in zip(*out))
+
+
+def test_driver_fused_stem_changes_no_bit(orc):
+    """ResNet-18's stem (conv -> Range-EvoNorm -> max-pool): the fused normalisation + pool calls (default) must give
+    exactly the step of the separate calls."""
+    from paper_2111_09389_amd.step import TrainStep
+    net = nets.resnet18()
+    N = 2
+    params = nets.init_params(net, wl.BASE_SEED + 22)
+    flat = np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32)
+    H, W, C = net.in_shape
+    x = dev(wl.images(wl.BASE_SEED + 23, N, H, W, C))
+    lb = dev(wl.labels_uniform(wl.BASE_SEED + 24, N, net.classes))
+    out = []
+    for fuse in (True, False):
+        p, g = dev(flat), torch.zeros(flat.size, dtype=torch.float32, device="cuda")
+        ts = TrainStep(net, N, p, g, x, lb, None, lr=0.05, seed=wl.PHILOX_SEED, fuse_ren_quant=fuse)
+        names = [c[0].__name__ for c in ts.calls if c[0] is not None]
+        assert ("lpdt_range_evonorm_maxpool_fwd" in names) == fuse and ("lpdt_range_evonorm_maxpool_bwd" in names) == fuse
+        assert ("lpdt_maxpool_fwd" in names) != fuse
+        ts.run(1)
+        torch.cuda.synchronize()
+        out.append((g.clone(), p.clone(), ts.loss.clone()))
+    assert all(torch.equal(a, b) for a, b in zip(*out))
