@@ -447,13 +447,18 @@ __device__ __forceinline__ float4 pooled_grad(const float4 *__restrict__ dz, con
     const int q_lo = max(0, (w + pg.pd - pg.k + pg.st) / pg.st), q_hi = min(pg.Q - 1, (w + pg.pd) / pg.st);
     int4 id[4];
     float4 gq[4];
+    size_t at[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int pp = p_lo + j / 2, qq = q_lo + j % 2;
         const bool ok = pp <= p_hi && qq <= q_hi;
-        const size_t at = (size_t)(pp * pg.Q + qq) * cq + qd;
-        id[j] = ok ? idx[at] : make_int4(-1, -1, -1, -1);
-        gq[j] = ok ? dz[at] : make_float4(0.f, 0.f, 0.f, 0.f);
+        at[j] = (size_t)(pp * pg.Q + qq) * cq + qd;
+        id[j] = ok ? idx[at[j]] : make_int4(-1, -1, -1, -1);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {  // a window's gradient is fetched only where the pixel won one of the 4 channels (~40% of the time)
+        const bool hit = id[j].x == p || id[j].y == p || id[j].z == p || id[j].w == p;
+        gq[j] = hit ? dz[at[j]] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
