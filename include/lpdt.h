@@ -148,6 +148,15 @@ int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq, const int
 int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, const float *sg,
                               const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream);
 
+/* The forward product added to what y already holds (Table "hardware_training", row Skip Connections, done in
+ * the convolution's epilogue): y += (sx*sw) * sum, the bits of lpdt_qconv_fwd_f32 into a temporary followed by
+ * lpdt_add(y, temporary).  y fp32 [N,P,Q,K], 16-byte aligned, read and overwritten.  A misaligned operand
+ * needs the staging room of the largest case: ask lpdt_qconv_fwd_f32_add_workspace_bytes and add
+ * 4*N*P*Q*K + 256 bytes. */
+size_t lpdt_qconv_fwd_f32_add_workspace_bytes(const lpdt_conv_desc *d);
+int lpdt_qconv_fwd_f32_add(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx,
+                           const float *sw, float *y, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------ Range-EvoNorm
  * Eq. "ren": for every sample n and channel group G (m = C/groups channels),
  *   range = max - min of x over the group's (h, w, channel) slab

@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
-    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
+    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
     "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
@@ -28,6 +28,7 @@ EXPORTS = [
     "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
     "lpdt_qconv_fwd_f32_workspace_bytes", "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
     "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
+    "lpdt_qconv_fwd_f32_add_workspace_bytes", "lpdt_qconv_fwd_f32_add",
     "lpdt_to_bf16", "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_bwd_weight_bf16",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
@@ -92,7 +93,7 @@ def lib():
         for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
                      "lpdt_qconv_bwd_weight_workspace_bytes", "lpdt_qconv_fwd_f32_workspace_bytes",
                      "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
-                     "lpdt_qconv_bwd_weight_bf16_workspace_bytes"):
+                     "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_fwd_f32_add_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
                      "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
@@ -235,6 +236,15 @@ def qconv_fwd_f32(d, xq, wq, sx, sw, y=None, ws=None):
     y = torch.empty((d.N, d.P, d.Q, d.K), dtype=torch.float32, device=xq.device) if y is None else y
     buf, nb = _ws(ws, lib().lpdt_qconv_fwd_f32_workspace_bytes(ctypes.byref(d)))
     _check(lib().lpdt_qconv_fwd_f32(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(sx), _ptr(sw), _ptr(y), _ptr(buf), _sz(nb), _stream()))
+    return y
+
+
+def qconv_fwd_f32_add(d, xq, wq, sx, sw, y, ws=None):
+    """y += sx*sw*conv(xq, wq), in place (the skip connection's addition in the convolution's epilogue)."""
+    _dev(xq, torch.int8, "qconv_fwd_f32_add xq"); _dev(wq, torch.int8, "qconv_fwd_f32_add wq"); _dev(y, torch.float32, "qconv_fwd_f32_add y")
+    assert tuple(xq.shape) == (d.N, d.H, d.W, d.C) and tuple(wq.shape) == (d.K, d.R, d.S, d.C) and tuple(y.shape) == (d.N, d.P, d.Q, d.K)
+    buf, nb = _ws(ws, lib().lpdt_qconv_fwd_f32_add_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_fwd_f32_add(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(sx), _ptr(sw), _ptr(y), _ptr(buf), _sz(nb), _stream()))
     return y
 
 

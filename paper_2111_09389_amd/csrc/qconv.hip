@@ -287,7 +287,9 @@ static bool fwd_fusable(const lpdt_conv_desc *d, int P, int Q) {
 static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq, const int8_t *wq, void *out, int out_mode,
                          const float *sA, const float *sB, void *ws, hipStream_t st) {
     const size_t out_len = (size_t)d->N * P * Q * d->K;
-    const bool stage = out_mode != 0 && !(fwd_fusable(d, P, Q) && aligned(xq, 16) && aligned(wq, 16));
+    // out_mode 2 (fp32, added to what is in `out`) is fused by the implicit-GEMM kernel only; the first-layer kernel stages
+    const bool fused = fwd_fusable(d, P, Q) && aligned(xq, 16) && aligned(wq, 16) && !(out_mode == 2 && narrow_conv_supported(d, P, Q));
+    const bool stage = out_mode != 0 && !fused;
     int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + round_up(fwd_base_ws(d), 256))
                          : static_cast<int32_t *>(out);
     const int mode = stage ? 0 : out_mode;
@@ -298,7 +300,7 @@ static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq
     } else {
         hipLaunchKernelGGL(conv_fwd_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, xq, wq, acc, *d, P, Q);
     }
-    if (stage) launch_dequant(acc, out_len, sA, sB, static_cast<float *>(out), 0, st);
+    if (stage) launch_dequant(acc, out_len, sA, sB, static_cast<float *>(out), out_mode == 2, st);
     return LPDT_OK;
 }
 
@@ -337,6 +339,31 @@ extern "C" int lpdt_qconv_fwd_f32(const lpdt_conv_desc *d, const int8_t *xq, con
     if (rc) return rc;
     conv_fwd_impl(d, P, Q, xq, wq, y, 1, sx, sw, ws, as_stream(stream));
     return launch_status("lpdt_qconv_fwd_f32");
+}
+
+extern "C" int lpdt_qconv_fwd_f32_add(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx, const float *sw,
+                                      float *y, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(xq && wq && y && sx && sw, LPDT_EINVAL, "qconv_fwd_f32_add: NULL argument");
+    LPDT_REQUIRE(aligned(y, 16), LPDT_EINVAL, "qconv_fwd_f32_add: y must be 16-byte aligned");
+    // every shape may have to stage its sums here (the first-layer kernel cannot add): ask for that room
+    const size_t need = round_up(fwd_base_ws(d), 256) + round_up((size_t)d->N * P * Q * d->K * 4, 256);
+    const bool al = aligned(xq, 16) && aligned(wq, 16);
+    const bool fused = al && fwd_fusable(d, P, Q) && !narrow_conv_supported(d, P, Q);
+    rc = check_ws(ws, ws_bytes, fused ? lpdt_qconv_fwd_f32_workspace_bytes(d) : need);
+    if (rc) return rc;
+    conv_fwd_impl(d, P, Q, xq, wq, y, 2, sx, sw, ws, as_stream(stream));
+    return launch_status("lpdt_qconv_fwd_f32_add");
+}
+
+extern "C" size_t lpdt_qconv_fwd_f32_add_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) return 0;
+    clear_error();
+    if (fwd_fusable(d, P, Q) && !narrow_conv_supported(d, P, Q)) return lpdt_qconv_fwd_f32_workspace_bytes(d);
+    return round_up(fwd_base_ws(d), 256) + round_up((size_t)d->N * P * Q * d->K * 4, 256);
 }
 
 // Backward-data product; out_mode 2 adds to the gradient already in `out` (fan-out of a skip connection).

@@ -143,6 +143,33 @@ class TrainStep:
             if op[0] == "maxpool" and self.consumers.get(op[2], 0) == 1:
                 pooled_by[op[2]] = op
         self.fused_pool = {}             # pooled tensor -> the normalised tensor that is never stored
+        # Skip connections done in a convolution's epilogue: of an add's two operands, the one produced later, when it
+        # is a convolution output nobody else reads, is accumulated straight into the other operand's buffer, provided
+        # that buffer may be overwritten: its other readers are convolutions (they read its int8 copy) and the first of
+        # them, which makes that copy, comes earlier.  conv output -> (sum tensor, buffer's tensor)
+        pos = {"x": -1}
+        for i, op in enumerate(net.ops):
+            if op[0] != "loss":
+                pos[op[1]] = i
+        producer = {op[1]: op for op in net.ops if op[0] != "loss"}
+        self.acc_conv, self.fused_add = {}, set()
+        if self.fuse_ren_quant:
+            for i, op in enumerate(net.ops):
+                if op[0] != "add":
+                    continue
+                _, out, a_, b_ = op
+                later, other = (a_, b_) if pos[a_] > pos[b_] else (b_, a_)
+                if later not in producer or producer[later][0] != "conv" or self.consumers.get(later, 0) != 1 or other == "x":
+                    continue
+                others = [o for o in net.ops if o is not op and o[0] != "loss" and other in (o[2:4] if o[0] == "add" else [o[2]])]
+                if any(o[0] != "conv" for o in others):
+                    continue
+                if others and min(pos[o[1]] for o in others) > pos[later]:
+                    continue
+                if other in conv_only or other in pooled_by:
+                    continue                     # never stored as fp32
+                self.acc_conv[later] = (out, other)
+                self.fused_add.add(out)
         spans = [self._poff[op[3]["w"]] for op in convs]
         batched = len(convs) > 1 and all(b % 16 == 0 for b, _ in spans)
         if batched:
@@ -170,6 +197,13 @@ class TrainStep:
                     src = self.act[inp]
                     self.xq[inp], self.sx[inp] = self._i8(*src.shape), self._f32(1)
                     self._quantize(src, self.xq[inp], self.sx[inp], ROUND_NEAREST, self.absmax.get(inp))
+                if out in self.acc_conv:     # y += conv: the sum of the skip connection, in the other operand's buffer
+                    sum_name, other = self.acc_conv[out]
+                    self.act[sum_name] = self.act[other]
+                    self._need_ws(L.lpdt_qconv_fwd_f32_add_workspace_bytes(ctypes.byref(d)))
+                    self._emit(L.lpdt_qconv_fwd_f32_add, [ctypes.byref(d), _p(self.xq[inp]), _p(self.wq[out]), _p(self.sx[inp]),
+                                                          _p(self.sw[out]), _p(self.act[other]), "WS", "WSB"])
+                    continue
                 y = self._f32(N, *net.shapes[out])
                 self.act[out] = y
                 self._need_ws(L.lpdt_qconv_fwd_f32_workspace_bytes(ctypes.byref(d)))
@@ -215,6 +249,8 @@ class TrainStep:
                             _p(self.absmax[out]), "WS", "WSB"])
             elif kind == "add":
                 _, out, a_, b_ = op
+                if out in self.fused_add:        # done in the epilogue of the convolution that produced one operand
+                    continue
                 y = self._f32(N, *net.shapes[out])
                 self.act[out] = y
                 self._emit(L.lpdt_add, [_p(self.act[a_]), _p(self.act[b_]), _sz(y.numel()), _p(y)])
@@ -411,7 +447,7 @@ class TrainStep:
         """[(entry point name, multiply-adds)] for every convolution call of one step, in call order."""
         out = []
         for fn, args, _, _ in self.calls:
-            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
+            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_fwd_f32_add", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
                                "lpdt_qconv_bwd_weight_bf16"):
                 d = args[0]._obj
                 out.append((fn.__name__, d.N * d.P * d.Q * d.K * d.C * d.R * d.S))

@@ -87,6 +87,11 @@ def test_fused_fp32_epilogue_equals_int32_then_dequantize(orc, shp):
     assert torch.equal(y, lpdt.dequantize(lpdt.qconv_fwd(ld, dev(x), dev(w)), dsa, dsb))
     ref = orc.dequantize(orc.qconv_fwd(od, x, w), sa, sb)
     assert np.abs(host(y) - ref).max() <= 1e-5 * np.abs(ref).max()
+    # the skip connection's addition in the epilogue: the bits of the product into a temporary + lpdt_add
+    addend = dev(wl.images(602, *host(y).shape))
+    want = lpdt.add(addend, y)
+    got = lpdt.qconv_fwd_f32_add(ld, dev(x), dev(w), dsa, dsb, addend.clone())
+    assert torch.equal(got, want)
     dx = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), dsa, dsb)
     assert torch.equal(dx, lpdt.dequantize(lpdt.qconv_bwd_data(ld, dev(g), dev(w)), dsa, dsb))
     base = wl.images(601, *host(dx).shape)

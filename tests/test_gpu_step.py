@@ -303,6 +303,7 @@ def test_driver_fused_stem_changes_no_bit(orc):
         names = [c[0].__name__ for c in ts.calls if c[0] is not None]
         assert ("lpdt_range_evonorm_maxpool_fwd" in names) == fuse and ("lpdt_range_evonorm_maxpool_bwd" in names) == fuse
         assert ("lpdt_maxpool_fwd" in names) != fuse
+        assert ("lpdt_qconv_fwd_f32_add" in names) == fuse and ("lpdt_add" in names or fuse)   # skip connections in conv epilogues
         ts.run(1)
         torch.cuda.synchronize()
         out.append((g.clone(), p.clone(), ts.loss.clone()))
