@@ -184,12 +184,14 @@ int lpdt_range_evonorm_fwd(const float *x, int N, int H, int W, int C, int group
  * quantized convolutions): y as lpdt_range_evonorm_fwd computes it, then quantized as
  * lpdt_quantize(y, LPDT_ROUND_NEAREST) would -- the same codes and scale, bit for bit -- without
  * the fp32 tensor y making a round trip through HBM.  q int8 [N,H,W,C] (4-byte aligned), scale:
- * fp32 device scalar; range_out / argmax_out / argmin_out as above.  C must be a multiple of 4,
+ * fp32 device scalar; y: NULL, or fp32 [N,H,W,C] (16-byte aligned) that also receives the
+ * unquantized output (for tensors with a full-precision reader besides the convolutions: then
+ * only the quantizer's read of y is saved); range_out / argmax_out / argmin_out as above.  C must be a multiple of 4,
  * at most 1024 (LPDT_EUNSUPPORTED otherwise: use the two calls). */
 size_t lpdt_range_evonorm_fwd_q_workspace_bytes(int N, int H, int W, int C, int groups);
 int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int C, int groups, const float *v,
                              const float *gamma, const float *beta, float eps, int8_t *q, float *scale,
-                             float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws,
+                             float *y, float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws,
                              size_t ws_bytes, void *stream);
 
 /* Gradient of the forward above.  dy, x, dx fp32 [N,H,W,C]; range/argmax/argmin as
@@ -207,7 +209,8 @@ int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W,
 /* Range-EvoNorm directly followed by a max-pool (the stem of the residual networks), for a normalised tensor
  * that nothing but the pool reads.  Forward: z [N,P,Q,C] and idx as lpdt_maxpool_fwd(lpdt_range_evonorm_fwd(x))
  * would give them, bit for bit, and the layer's saved range / argmax / argmin; the normalised tensor itself is
- * never stored.  Backward: from the pooled gradient dz [N,P,Q,C] and idx, everything
+ * never stored.  absmax_out: optional (may be NULL) fp32 scalar, set to max|z| for a following
+ * lpdt_quantize_with_absmax.  Backward: from the pooled gradient dz [N,P,Q,C] and idx, everything
  * lpdt_range_evonorm_bwd(lpdt_maxpool_bwd(dz, idx), x, ...) returns, bit for bit; needs k <= 2 * stride
  * (LPDT_EUNSUPPORTED otherwise: use the two calls).  k, st, pd: window, stride, padding of the pool;
  * C a multiple of 4, at most 1024; x, z, idx, dz, dx 16-byte aligned. */
@@ -216,7 +219,8 @@ size_t lpdt_range_evonorm_maxpool_bwd_workspace_bytes(int N, int H, int W, int C
 int lpdt_range_evonorm_maxpool_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
                                    const float *gamma, const float *beta, float eps, int k, int st, int pd,
                                    float *z, int32_t *idx, float *range_out, int32_t *argmax_out,
-                                   int32_t *argmin_out, void *ws, size_t ws_bytes, void *stream);
+                                   int32_t *argmin_out, float *absmax_out, void *ws, size_t ws_bytes,
+                                   void *stream);
 int lpdt_range_evonorm_maxpool_bwd(const float *dz, const int32_t *idx, const float *x, int N, int H, int W,
                                    int C, int groups, const float *v, const float *gamma, float eps, int k,
                                    int st, int pd, const float *range, const int32_t *argmax,

@@ -286,8 +286,9 @@ def range_evonorm_fwd(x, groups, v, gamma, beta, eps=1e-5, y=None, want_absmax=F
     return (y, rng, amx, amn, absmax) if want_absmax else (y, rng, amx, amn)
 
 
-def range_evonorm_fwd_q(x, groups, v, gamma, beta, eps=1e-5, q=None, ws=None):
-    """Range-EvoNorm forward with int8 output -> (q int8, scale [1], range [N,groups], argmax, argmin)."""
+def range_evonorm_fwd_q(x, groups, v, gamma, beta, eps=1e-5, q=None, y=None, ws=None):
+    """Range-EvoNorm forward with int8 output -> (q int8, scale [1], range [N,groups], argmax, argmin); y: optional fp32
+    tensor that also receives the unquantized output."""
     _dev(x, torch.float32, "range_evonorm_fwd_q x")
     N, H, W, C = x.shape
     dev = x.device
@@ -298,12 +299,12 @@ def range_evonorm_fwd_q(x, groups, v, gamma, beta, eps=1e-5, q=None, ws=None):
     amn = torch.empty((N, groups), dtype=torch.int32, device=dev)
     buf, nb = _ws(ws, lib().lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, int(groups)))
     _check(lib().lpdt_range_evonorm_fwd_q(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta), ctypes.c_float(eps),
-                                          _ptr(q), _ptr(scale), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
+                                          _ptr(q), _ptr(scale), _ptr(y), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
     return q, scale, rng, amx, amn
 
 
-def range_evonorm_maxpool_fwd(x, groups, v, gamma, beta, k, stride, pad, eps=1e-5, ws=None):
-    """maxpool(range_evonorm(x)) without storing the normalised tensor -> (z, idx, range, argmax, argmin)."""
+def range_evonorm_maxpool_fwd(x, groups, v, gamma, beta, k, stride, pad, eps=1e-5, want_absmax=False, ws=None):
+    """maxpool(range_evonorm(x)) without storing the normalised tensor -> (z, idx, range, argmax, argmin[, absmax])."""
     _dev(x, torch.float32, "range_evonorm_maxpool_fwd x")
     N, H, W, C = x.shape
     dev = x.device
@@ -313,11 +314,12 @@ def range_evonorm_maxpool_fwd(x, groups, v, gamma, beta, k, stride, pad, eps=1e-
     rng = torch.empty((N, groups), dtype=torch.float32, device=dev)
     amx = torch.empty((N, groups), dtype=torch.int32, device=dev)
     amn = torch.empty((N, groups), dtype=torch.int32, device=dev)
+    absmax = torch.empty(1, dtype=torch.float32, device=dev) if want_absmax else None
     buf, nb = _ws(ws, lib().lpdt_range_evonorm_maxpool_fwd_workspace_bytes(N, H, W, C, int(groups)))
     _check(lib().lpdt_range_evonorm_maxpool_fwd(_ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), _ptr(beta),
                                                 ctypes.c_float(eps), int(k), int(stride), int(pad), _ptr(z), _ptr(idx), _ptr(rng),
-                                                _ptr(amx), _ptr(amn), _ptr(buf), _sz(nb), _stream()))
-    return z, idx, rng, amx, amn
+                                                _ptr(amx), _ptr(amn), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
+    return (z, idx, rng, amx, amn, absmax) if want_absmax else (z, idx, rng, amx, amn)
 
 
 def range_evonorm_maxpool_bwd(dz, idx, x, groups, v, gamma, rng, amx, amn, k, stride, pad, eps=1e-5, want_absmax=False, ws=None):

@@ -319,7 +319,7 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
                                                                 const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                 float cm, float eps, const float *__restrict__ range,
                                                                 const float *__restrict__ absmax, int8_t *__restrict__ q,
-                                                                float *__restrict__ scale) {
+                                                                float *__restrict__ scale, float *__restrict__ y) {
     const int n = blockIdx.y;
     const float a = *absmax;
     if (blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *scale = __fdiv_rn(a, 127.0f);
@@ -348,11 +348,15 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
             const int p = pb + k * g.ppi;
             if (p >= p1) break;
             const float xe[4] = {t[k].x, t[k].y, t[k].z, t[k].w};
+            float o[4];
             uint32_t word = 0u;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                word |= ((uint32_t)round_code(ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]), qinv, false, 0u) & 0xffu) << (8 * e);
+            for (int e = 0; e < 4; ++e) {
+                o[e] = ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]);
+                word |= ((uint32_t)round_code(o[e], qinv, false, 0u) & 0xffu) << (8 * e);
+            }
             qv[(size_t)p * g.cq + qd] = word;
+            if (y) reinterpret_cast<float4 *>(y + (size_t)n * g.HW * g.C)[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
         }
     }
 }
@@ -368,8 +372,9 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
                                                              const unsigned long long *__restrict__ pstats, int stat_chunks,
                                                              float *__restrict__ z, int32_t *__restrict__ idx,
                                                              float *__restrict__ range_out, int32_t *__restrict__ argmax_out,
-                                                             int32_t *__restrict__ argmin_out) {
+                                                             int32_t *__restrict__ argmin_out, float *__restrict__ absmax_out) {
     extern __shared__ unsigned long long skeys[];  // [groups][2], then float range[groups]
+    __shared__ float lds[kRThreads / kWave];
     float *srange = reinterpret_cast<float *>(skeys + 2 * g.groups);
     const int n = blockIdx.y;
     {
@@ -394,7 +399,7 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
         }
     }
     __syncthreads();
-    if ((int)threadIdx.x >= g.threads) return;
+    const bool active = (int)threadIdx.x < g.threads;
     const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
     const int p0 = blockIdx.x * g.pix_per_block, p1 = min(p0 + g.pix_per_block, g.HW);
     float vv[4], gg[4], bb[4], inv[4];
@@ -407,7 +412,8 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
     const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * H * W * g.C);
     float4 *zv = reinterpret_cast<float4 *>(z + (size_t)n * g.HW * g.C);
     int4 *iv = reinterpret_cast<int4 *>(idx + (size_t)n * g.HW * g.C);
-    for (int pp = p0 + pl; pp < p1; pp += g.ppi) {
+    float am = 0.0f;
+    for (int pp = p0 + pl; pp < p1 && active; pp += g.ppi) {
         const int p = pp / pg.Q, q = pp - p * pg.Q;
         float best[4] = {0.f, 0.f, 0.f, 0.f};
         int bi[4] = {-1, -1, -1, -1};
@@ -429,7 +435,9 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
         }
         zv[(size_t)pp * g.cq + qd] = make_float4(best[0], best[1], best[2], best[3]);
         iv[(size_t)pp * g.cq + qd] = make_int4(bi[0], bi[1], bi[2], bi[3]);
+        am = fmaxf(fmaxf(am, fmaxf(fabsf(best[0]), fabsf(best[1]))), fmaxf(fabsf(best[2]), fabsf(best[3])));
     }
+    if (absmax_out) block_absmax_commit(am, absmax_out, lds);   // zeroed by the stats pass
 }
 
 // ---- backward ---------------------------------------------------------------
@@ -731,7 +739,7 @@ extern "C" size_t lpdt_range_evonorm_fwd_q_workspace_bytes(int N, int H, int W, 
 }
 
 extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int C, int groups, const float *v,
-                                        const float *gamma, const float *beta, float eps, int8_t *q, float *scale,
+                                        const float *gamma, const float *beta, float eps, int8_t *q, float *scale, float *y,
                                         float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws, size_t ws_bytes,
                                         void *stream) {
     int rc = check_ren(x, N, H, W, C, groups);
@@ -740,8 +748,8 @@ extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int
                  "range_evonorm_fwd_q: NULL argument");
     LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_fwd_q: eps must be >= 0");
     LPDT_REQUIRE(ren_fast(C), LPDT_EUNSUPPORTED, "range_evonorm_fwd_q: C must be a multiple of 4, at most %d (got %d)", 4 * kRThreads, C);
-    LPDT_REQUIRE(aligned(x, 16) && aligned(q, 4) && aligned(scale, 4), LPDT_EINVAL,
-                 "range_evonorm_fwd_q: x must be 16-byte aligned, q and scale 4-byte aligned");
+    LPDT_REQUIRE(aligned(x, 16) && aligned(q, 4) && aligned(scale, 4) && aligned(y, 16), LPDT_EINVAL,
+                 "range_evonorm_fwd_q: x and y must be 16-byte aligned, q and scale 4-byte aligned");
     rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, groups));
     if (rc) return rc;
     hipStream_t st = as_stream(stream);
@@ -757,7 +765,7 @@ extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int
     hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), key_lds + groups * sizeof(float), st, g, keys, pu, gamma, beta, cm, eps,
                        range_out, argmax_out, argmin_out, absmax);
     hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out,
-                       absmax, q, scale);
+                       absmax, q, scale, y);
     return launch_status("lpdt_range_evonorm_fwd_q");
 }
 
@@ -823,8 +831,8 @@ extern "C" size_t lpdt_range_evonorm_maxpool_bwd_workspace_bytes(int N, int H, i
 
 extern "C" int lpdt_range_evonorm_maxpool_fwd(const float *x, int N, int H, int W, int C, int groups, const float *v,
                                               const float *gamma, const float *beta, float eps, int k, int st_, int pd, float *z,
-                                              int32_t *idx, float *range_out, int32_t *argmax_out, int32_t *argmin_out, void *ws,
-                                              size_t ws_bytes, void *stream) {
+                                              int32_t *idx, float *range_out, int32_t *argmax_out, int32_t *argmin_out,
+                                              float *absmax_out, void *ws, size_t ws_bytes, void *stream) {
     int rc = check_ren(x, N, H, W, C, groups);
     if (rc) return rc;
     rc = check_ren_pool("range_evonorm_maxpool_fwd", N, H, W, C, groups, k, st_, pd);
@@ -842,11 +850,11 @@ extern "C" int lpdt_range_evonorm_maxpool_fwd(const float *x, int N, int H, int 
     const RenGeom gp = ren_geom(N, P, Q, C, groups, 0, block_cap(N, P, Q, C, kApplyElems / 4));
     unsigned long long *stats = static_cast<unsigned long long *>(ws);
     const size_t smem = (size_t)2 * groups * sizeof(unsigned long long);
-    hipLaunchKernelGGL(ren_stats_kernel<false>, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, (float *)nullptr,
+    hipLaunchKernelGGL(ren_stats_kernel<false>, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, absmax_out,
                        (const float *)nullptr, (float *)nullptr);
     hipLaunchKernelGGL(ren_pool_kernel, dim3(gp.chunks, N), dim3(gp.block), smem + groups * sizeof(float), st, x, gp, H, W,
                        PoolGeom{W, P, Q, k, st_, pd}, v, gamma, beta, ren_cm(C / groups), eps, stats, g.chunks, z, idx, range_out,
-                       argmax_out, argmin_out);
+                       argmax_out, argmin_out, absmax_out);
     return launch_status("lpdt_range_evonorm_maxpool_fwd");
 }
 

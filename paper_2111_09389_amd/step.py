@@ -224,19 +224,26 @@ class TrainStep:
                     z, idx = self._f32(N, *net.shapes[pout]), self._i32(N, *net.shapes[pout])
                     self.act[pout], self.pool_idx[pout] = z, idx
                     self.fused_pool[pout] = out
+                    self.absmax[pout] = self._f32(1)
                     self._need_ws(L.lpdt_range_evonorm_maxpool_fwd_workspace_bytes(N, H, W, C, g))
                     self._emit(L.lpdt_range_evonorm_maxpool_fwd,
                                [_p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
                                 _p(pv[a["p"] + ".beta"]), _f32(self.eps), pa["k"], pa["stride"], pa["pad"], _p(z), _p(idx), _p(rng),
-                                _p(amx), _p(amn), "WS", "WSB"])
+                                _p(amx), _p(amn), _p(self.absmax[pout]), "WS", "WSB"])
                     continue
-                if self.fuse_ren_quant and out in conv_only and L.lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, g) > 0:
-                    # every consumer is a quantized convolution: the layer emits the int8 codes itself, y is never stored
+                if (self.fuse_ren_quant and "conv" in readers.get(out, ())
+                        and L.lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, g) > 0):
+                    # a quantized convolution reads the output: the layer emits the int8 codes itself; y is stored as well only
+                    # when something else (a skip connection) reads it at full precision
                     self.xq[out], self.sx[out] = self._i8(N, H, W, C), self._f32(1)
+                    y = None
+                    if out not in conv_only:
+                        y = self._f32(N, H, W, C)
+                        self.act[out] = y
                     self._need_ws(L.lpdt_range_evonorm_fwd_q_workspace_bytes(N, H, W, C, g))
                     self._emit(L.lpdt_range_evonorm_fwd_q,
                                [_p(self.act[inp]), N, H, W, C, g, _p(pv[a["p"] + ".v"]), _p(pv[a["p"] + ".gamma"]),
-                                _p(pv[a["p"] + ".beta"]), _f32(self.eps), _p(self.xq[out]), _p(self.sx[out]), _p(rng), _p(amx),
+                                _p(pv[a["p"] + ".beta"]), _f32(self.eps), _p(self.xq[out]), _p(self.sx[out]), _p(y), _p(rng), _p(amx),
                                 _p(amn), "WS", "WSB"])
                     continue
                 y = self._f32(N, H, W, C)

@@ -103,6 +103,9 @@ def test_int8_output_forward_equals_forward_then_quantize(orc, shape):
     q, s, r2, amx2, amn2 = lpdt.range_evonorm_fwd_q(xd, groups, vd, gd, bd, 1e-5)
     import torch
     assert torch.equal(s, s_ref) and torch.equal(q, q_ref)
+    y2 = torch.empty_like(y)
+    q3, s3, _, _, _ = lpdt.range_evonorm_fwd_q(xd, groups, vd, gd, bd, 1e-5, y=y2)      # codes and the fp32 tensor in one call
+    assert torch.equal(q3, q_ref) and torch.equal(s3, s_ref) and torch.equal(y2, y)
     assert torch.equal(r, r2) and torch.equal(amx, amx2) and torch.equal(amn, amn2)
     y_ref, _, _, _ = orc.range_evonorm_fwd(x, groups, v, gamma, beta, 1e-5)
     step = float(host(s)[0])
@@ -134,8 +137,9 @@ def test_normalisation_followed_by_max_pool_equals_the_two_calls(shape, pool):
     xd, vd, gd, bd = dev(x), dev(v), dev(gamma), dev(beta)
     y, r, amx, amn = lpdt.range_evonorm_fwd(xd, groups, vd, gd, bd, 1e-5)
     z_ref, idx_ref = lpdt.maxpool_fwd(y, k, st, pd)
-    z, idx, r2, amx2, amn2 = lpdt.range_evonorm_maxpool_fwd(xd, groups, vd, gd, bd, k, st, pd, 1e-5)
+    z, idx, r2, amx2, amn2, zmax = lpdt.range_evonorm_maxpool_fwd(xd, groups, vd, gd, bd, k, st, pd, 1e-5, want_absmax=True)
     assert torch.equal(z, z_ref) and torch.equal(idx, idx_ref)
+    assert float(zmax[0]) == float(z_ref.abs().max())
     assert torch.equal(r, r2) and torch.equal(amx, amx2) and torch.equal(amn, amn2)
     dz = dev(wl.upstream_grad(742, tuple(z.shape)))
     dy = lpdt.maxpool_bwd(dz, idx_ref, (N, H, W, C), k, st, pd)
