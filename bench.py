@@ -306,12 +306,16 @@ def main():
     value = conv_ops / (ms_step * 1e-3) / 1e12
 
     # per-entry-point time of one more step (HIP events on the launch stream)
-    per = {}
-    reps = 3
+    # median over repetitions: the first bracket after an idle GPU now and then includes a host-side stall
+    reps = 5
+    runs = []
     for r in range(reps):
+        one = {}
         for ts in steps:
             for name, ms in ts.run_timed(args.warmup + args.steps + r):
-                per[name] = per.get(name, 0.0) + ms / reps
+                one[name] = one.get(name, 0.0) + ms
+        runs.append(one)
+    per = {name: sorted(one[name] for one in runs)[reps // 2] for name in runs[0]}
     mix_ms = None
     if mix:
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -65,6 +65,7 @@ struct IgemmParams {
     int IH, IW, OH, OW;
     int istep, ostep, dsign;
     int tiles_n, atomic_out, vec_out;
+    int kg;                 // granules per K-step
     int nclasses;
     IgemmClass cls[kMaxClasses];
 };
@@ -84,11 +85,14 @@ __device__ __forceinline__ int fast_div(int x, int d, unsigned mul) {
 // PF = K-steps whose global loads are in flight (held in registers) ahead of the one being multiplied.
 // SPLIT: the reduction is shared between the blocks of grid.z, which add their int32 sums into a zeroed output; the pixels
 // are then the MFMA's row operand, so that a lane's atomics of one instruction fall on consecutive addresses.
-template <int BM, int BN, int WM, int WN, int PF, bool SPLIT>
+// KG = granules of a K-step (4 or 8): with 8 a row's fetch is one whole 128-byte cache line.
+template <int BM, int BN, int WM, int WN, int PF, bool SPLIT, int KG>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
-    constexpr int PLANE_A = BM * 16 + 64, PLANE_B = BN * 16 + 64;  // +64 B: the 4 planes start 16 banks apart
-    constexpr int BUF = 4 * (PLANE_A + PLANE_B);
-    constexpr int RA = BM / 64, RB = (BN + 63) / 64;               // 16-byte items per thread
+    constexpr int PAD = 256 / KG;                                  // the KG planes start 64/KG banks apart
+    constexpr int PLANE_A = BM * 16 + PAD, PLANE_B = BN * 16 + PAD;
+    constexpr int BUF = KG * (PLANE_A + PLANE_B);
+    constexpr int RPP = kThreads / KG;                             // rows per pass of the block's loads
+    constexpr int RA = BM / RPP, RB = (BN + RPP - 1) / RPP;        // 16-byte items per thread
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     int4 *rows = reinterpret_cast<int4 *>(lds + 2 * BUF);
@@ -106,16 +110,16 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     if (ks_begin >= ks_end && (blockIdx.z > 0)) return;
 
     const int t = threadIdx.x, lane = t % 64, wave = t / 64;
-    const int g4 = t % 4, row0 = t / 4;
+    const int g4 = t % KG, row0 = t / KG;
 
     // The K loop runs in rounds of PF steps with no conditions inside; steps past the block's range multiply zeros.
     const int nsteps = (ks_end - ks_begin + PF - 1) / PF * PF;
     // gather table: entry e = granule 4*ks_begin + e -> (byte offset of its tap and channels, tap slot); entries past
     // the range (the padded steps and the PF steps of read-ahead) name the empty slot
-    for (int e = t; e < 4 * (nsteps + PF); e += kThreads) {
-        const int gi = 4 * ks_begin + e;
+    for (int e = t; e < KG * (nsteps + PF); e += kThreads) {
+        const int gi = KG * ks_begin + e;
         int2 v = {0, 31};
-        if (gi < min(c.gtot, 4 * ks_end)) {
+        if (gi < min(c.gtot, KG * ks_end)) {
             const int slot = fast_div(gi, p.gpt, p.mul_gpt), cg = gi - slot * p.gpt;
             const int ty = fast_div(slot, c.Sc, c.mul_sc), tx = slot - ty * c.Sc;
             v.x = (ty * p.IW + tx) * p.dsign * p.Cin + cg * 16;
@@ -148,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     unsigned boff[RB];
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
-        const int row = row0 + 64 * j;
+        const int row = row0 + RPP * j;
         boff[j] = (row < BN && n0 + row < p.Cout) ? (unsigned)(c.wt_off + ((n0 + row) * c.gtot + g4) * 16) : kBeyond;
     }
     const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.in), 0, (int)p.in_bytes, 0x00020000);
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     unsigned mask[RA];
 #pragma unroll
     for (int j = 0; j < RA; ++j) {
-        const int4 rec = rows[row0 + 64 * j];
+        const int4 rec = rows[row0 + RPP * j];
         rowoff[j] = rec.x;
         mask[j] = (unsigned)rec.y;
     }
@@ -166,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     v4u sa[PF][RA], sb[PF][RB];
     auto load_tiles = [&](auto slot_tag, int step) {  // step counts from the block's first K-step
         constexpr int SL = decltype(slot_tag)::value;
-        const int2 e = tab[4 * step + g4];
+        const int2 e = tab[KG * step + g4];
 #pragma unroll
         for (int j = 0; j < RA; ++j) {
             const unsigned off = ((mask[j] >> e.y) & 1u) ? (unsigned)(rowoff[j] + e.x) : kBeyond;
@@ -174,17 +178,17 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
         }
 #pragma unroll
         for (int j = 0; j < RB; ++j)
-            sb[SL][j] = __builtin_amdgcn_raw_buffer_load_b128(rs_wt, boff[j] + (unsigned)(ks_begin + step) * 64u, 0, 0);
+            sb[SL][j] = __builtin_amdgcn_raw_buffer_load_b128(rs_wt, boff[j] + (unsigned)(ks_begin + step) * (16u * KG), 0, 0);
     };
     unsigned char *const st_a = lds + g4 * PLANE_A + row0 * 16;
-    unsigned char *const st_b = lds + 4 * PLANE_A + g4 * PLANE_B + row0 * 16;
+    unsigned char *const st_b = lds + KG * PLANE_A + g4 * PLANE_B + row0 * 16;
     auto store_tiles = [&](auto slot_tag, int buf) {
         constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
-        for (int j = 0; j < RA; ++j) *reinterpret_cast<v4u *>(st_a + buf * BUF + 64 * j * 16) = sa[SL][j];
+        for (int j = 0; j < RA; ++j) *reinterpret_cast<v4u *>(st_a + buf * BUF + RPP * j * 16) = sa[SL][j];
 #pragma unroll
         for (int j = 0; j < RB; ++j)
-            if (BN % 64 == 0 || row0 + 64 * j < BN) *reinterpret_cast<v4u *>(st_b + buf * BUF + 64 * j * 16) = sb[SL][j];
+            if (BN % RPP == 0 || row0 + RPP * j < BN) *reinterpret_cast<v4u *>(st_b + buf * BUF + RPP * j * 16) = sb[SL][j];
     };
 
     v16i acc[TM][TN];
@@ -197,7 +201,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
 
     const int wm = wave / WN, wn = wave % WN, half = lane / 32;
     const unsigned char *const rd_a = lds + half * PLANE_A + (wm * (BM / WM) + lane % 32) * 16;
-    const unsigned char *const rd_b = lds + 4 * PLANE_A + half * PLANE_B + (wn * (BN / WN) + lane % 32) * 16;
+    const unsigned char *const rd_b = lds + KG * PLANE_A + half * PLANE_B + (wn * (BN / WN) + lane % 32) * 16;
 
     // prologue: the first PF K-steps' loads go out together; register slot s holds step s (mod PF afterwards)
     static_for<PF>([&](auto s) { load_tiles(s, decltype(s)::value); });
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
             constexpr int buf = U & 1;
             load_tiles(u, base + U + PF);  // slot U went to LDS before this step: refill it
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
+            for (int kk = 0; kk < KG / 2; ++kk) {
                 v4i a[TM], b[TN];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -330,20 +334,28 @@ unsigned div_multiplier(int d, long long xmax) {
     return (unsigned)((1ull << 32) / (unsigned)d + 1);
 }
 
-struct Tile { int BM, BN; };
+struct Tile { int BM, BN, KG; };
 // 128 x 64 tiles where they give at least one block per CU (measured faster than 64-row and than 256-row tiles on every
 // such layer of the benchmark networks); deeper layers with few pixels take 64 x 64 tiles, which still fill the chip
 // without splitting the reduction (so the scale can be applied in the epilogue).
 Tile pick_tile(const IgemmParams &p) {
-    if (p.Cout < 48) return {128, 32};
+    if (p.Cout < 48) return {128, 32, 4};
     long long blocks = 0;
-    for (int i = 0; i < p.nclasses; ++i) blocks += (long long)((p.cls[i].M + 127) / 128) * ((p.Cout + 63) / 64);
-    return {blocks >= 256 ? 128 : 64, 64};
+    int gmin = 1 << 30;
+    for (int i = 0; i < p.nclasses; ++i) {
+        blocks += (long long)((p.cls[i].M + 127) / 128) * ((p.Cout + 63) / 64);
+        if (p.cls[i].gtot < gmin) gmin = p.cls[i].gtot;
+    }
+    // K-steps of 8 granules fetch whole 128-byte lines of a row and halve the barriers; a short reduction would pay for
+    // them with padding (36 granules -> 5 steps of 8) and takes steps of 4
+    return {blocks >= 256 ? 128 : 64, 64, gmin >= 64 ? 8 : 4};
 }
 
 // Fills tile counts and the K split; returns the grid.
 dim3 finish_plan(IgemmParams *p, Tile tl, bool allow_split) {
     p->tiles_n = (p->Cout + tl.BN - 1) / tl.BN;
+    p->kg = tl.KG;
+    for (int i = 0; i < p->nclasses; ++i) p->cls[i].nk = (p->cls[i].gtot + tl.KG - 1) / tl.KG;
     long long blocks = 0;
     int max_tiles_m = 0, max_nk = 0;
     for (int i = 0; i < p->nclasses; ++i) {
@@ -353,9 +365,10 @@ dim3 finish_plan(IgemmParams *p, Tile tl, bool allow_split) {
         if (p->cls[i].nk > max_nk) max_nk = p->cls[i].nk;
     }
     int splits = 1;
-    if (allow_split && blocks < 256 && max_nk >= 8) {  // too few tiles to fill 256 CUs: split the reduction
+    const int min_steps = 16 / tl.KG;                  // a share of the reduction is at least 16 granules deep
+    if (allow_split && blocks < 256 && max_nk >= 2 * min_steps) {  // too few tiles to fill 256 CUs: split the reduction
         splits = (int)((512 + blocks - 1) / blocks);
-        if (splits > max_nk / 4) splits = max_nk / 4;
+        if (splits > max_nk / min_steps) splits = max_nk / min_steps;
         if (splits < 1) splits = 1;
     }
     int zdim = 1;
@@ -371,19 +384,23 @@ dim3 finish_plan(IgemmParams *p, Tile tl, bool allow_split) {
 
 bool table_fits(const IgemmParams &p) {
     for (int i = 0; i < p.nclasses; ++i)
-        if (4 * (p.cls[i].kps + 16) > kMaxTableEntries) return false;
+        if (p.kg * (p.cls[i].kps + 16) > kMaxTableEntries) return false;
     return true;
 }
 
-template <int BM, int BN, int WM, int WN, int PF>
+template <int BM, int BN, int WM, int WN, int PF, int KG>
 void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
     int max_kps = 1;
     for (int i = 0; i < p.nclasses; ++i)
         if (p.cls[i].kps > max_kps) max_kps = p.cls[i].kps;
-    const size_t lds = 2 * 4 * ((BM * 16 + 64) + (BN * 16 + 64)) + BM * sizeof(int4) +
-                       (size_t)((max_kps + PF - 1) / PF * PF + PF) * 4 * sizeof(int2);
-    if (p.atomic_out) hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, PF, true>), grid, dim3(kThreads), lds, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, PF, false>), grid, dim3(kThreads), lds, st, p);
+    const size_t lds = 2 * KG * ((BM * 16 + 256 / KG) + (BN * 16 + 256 / KG)) + BM * sizeof(int4) +
+                       (size_t)((max_kps + PF - 1) / PF * PF + PF) * KG * sizeof(int2);
+    auto go = [&](auto kernel) {
+        if (lds > 48 * 1024) hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, p);
+    };
+    if (p.atomic_out) go(igemm_kernel<BM, BN, WM, WN, PF, true, KG>);
+    else go(igemm_kernel<BM, BN, WM, WN, PF, false, KG>);
 }
 
 void run(IgemmParams &p, size_t out_len, hipStream_t st) {
@@ -395,9 +412,11 @@ void run(IgemmParams &p, size_t out_len, hipStream_t st) {
         if (b > 4096) b = 4096;
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)b), dim3(256), 0, st, static_cast<int32_t *>(p.out), len);
     }
-    if (tl.BM == 64) launch<64, 64, 2, 2, 4>(p, grid, st);
-    else if (tl.BN == 64) launch<128, 64, 2, 2, 4>(p, grid, st);
-    else launch<128, 32, 4, 1, 4>(p, grid, st);
+    if (tl.BN == 32) launch<128, 32, 4, 1, 4, 4>(p, grid, st);
+    else if (tl.BM == 64 && tl.KG == 8) launch<64, 64, 2, 2, 2, 8>(p, grid, st);
+    else if (tl.BM == 64) launch<64, 64, 2, 2, 4, 4>(p, grid, st);
+    else if (tl.KG == 8) launch<128, 64, 2, 2, 2, 8>(p, grid, st);
+    else launch<128, 64, 2, 2, 4, 4>(p, grid, st);
 }
 
 void fwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p) {
@@ -412,7 +431,7 @@ void fwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p) {
     c.M = d->N * P * Q; c.OHs = P; c.OWs = Q;
     c.oy0 = 0; c.ox0 = 0; c.iy0 = -d->pad_h; c.ix0 = -d->pad_w;
     c.Rc = d->R; c.Sc = d->S;
-    c.gtot = d->R * d->S * p->gpt; c.nk = (c.gtot + 3) / 4;
+    c.gtot = d->R * d->S * p->gpt;
     c.wt_off = 0;
     c.mul_hw = div_multiplier(P * Q, c.M);
     c.mul_w = div_multiplier(Q, (long long)P * Q);
@@ -445,7 +464,7 @@ void bwd_params(const lpdt_conv_desc *d, int P, int Q, IgemmParams *p, PackParam
                 c.oy0 = h0; c.ox0 = w0;
                 c.iy0 = (h0 + pad - cy) / s; c.ix0 = (w0 + pad - cx) / s;
                 c.Rc = Rc; c.Sc = Sc;
-                c.gtot = Rc * Sc * p->gpt; c.nk = (c.gtot + 3) / 4;
+                c.gtot = Rc * Sc * p->gpt;
                 c.wt_off = woff;
                 c.mul_hw = div_multiplier(OHs * OWs, c.M);
                 c.mul_w = div_multiplier(OWs, (long long)OHs * OWs);
