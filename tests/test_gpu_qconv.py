@@ -27,6 +27,8 @@ CASES = [
     (1, 256, 4, 4, 512, 3, 3, 1, 1),
     (257, 768, 1, 1, 768, 1, 1, 1, 0),    # transformer-shaped linear layers (tokens x 768 -> 768 / 3072 -> 768), ragged token count
     (130, 3072, 1, 1, 768, 1, 1, 1, 0),
+    (2, 144, 7, 7, 80, 3, 3, 1, 1),       # 81 granules of reduction: the forward's 8-granule steps end in a ragged one
+    (1, 80, 5, 5, 144, 3, 3, 1, 1),       # the same for backward-data (reduction over 144 output channels x 9 taps)
 ]
 
 
