@@ -462,11 +462,13 @@ static void conv_bwd_weight_impl(const lpdt_conv_desc *d0, int P, int Q, const i
         launch_wgrad_rect(d, P, Q, pl, gq, xq, out, out_mode, sA, sB, ws, st);
         return;
     }
+    if (narrow_conv_supported(d, P, Q) && aligned(gq, 16)) {
+        launch_narrow_wgrad(d, P, Q, gq, xq, out, out_mode, sA, sB, ws, st);
+        return;
+    }
     int32_t *dw = out_mode ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_weight_base_ws(d, P, Q)) : static_cast<int32_t *>(out);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(wlen, 1024)), dim3(kCThreads), 0, st, dw, wlen);
-    if (narrow_conv_supported(d, P, Q) && aligned(gq, 16)) {
-        launch_narrow_wgrad(d, P, Q, gq, xq, dw, ws, st);
-    } else if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d) && aligned(gq, 16) && aligned(xq, 16)) {
+    if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d) && aligned(gq, 16) && aligned(xq, 16)) {
         WgradParams p = {};
         p.g = gq; p.x = xq; p.dw = dw;
         p.M = (int)M; p.K = d->K; p.C = d->C; p.H = d->H; p.W = d->W; p.P = P; p.Q = Q;

@@ -10,8 +10,9 @@ size_t narrow_fwd_workspace(const lpdt_conv_desc *d);
 size_t narrow_wgrad_workspace(const lpdt_conv_desc *d);
 void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, int32_t *acc, int out_mode,
                        const float *sA, const float *sB, void *ws, hipStream_t st);
-void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
-                         hipStream_t st);
+// out_mode 0: int32 sums; 1: fp32 sA*sB*sum
+void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, void *out, int out_mode,
+                         const float *sA, const float *sB, void *ws, hipStream_t st);
 
 // Implicit-GEMM forward / backward-data on the matrix cores (channel counts of the reduction a multiple of 16).
 // `*_supported` is false for shapes that take the plain kernels; `*_is_split` tells that the reduction is split across
@@ -38,6 +39,10 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *plan)
 // out_mode 0: int32 sums; 1: fp32 sA*sB*sum.  `partial` needs plan.partial_bytes.
 void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPlan &plan, const int8_t *g, const int8_t *x,
                        void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
+
+// out[i] = sum over `splits` copies partial[z][i] (out_len a multiple of 4), as int32 or as fp32 times sA*sB
+void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
+                         const float *sB, hipStream_t st);
 
 // y = (sA*sB) * acc (+ y when accumulate): the kernel behind lpdt_dequantize
 void launch_dequant(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y, bool accumulate, hipStream_t st);

@@ -13,6 +13,7 @@
 //             transposing LDS load, exactly as in the general weight-gradient kernel; one
 //             filter row is one 32-column MFMA tile.
 #include "qconv_internal.h"
+#include <type_traits>
 
 namespace lpdt {
 
@@ -75,12 +76,13 @@ struct NarrowParams {
     const int8_t *xp;   // padded image [N][PH][PW][C] (+ slack)
     const int8_t *wr;   // packed filter rows [K][R][32]            (forward)
     const int8_t *g;    // gradient codes [M][K]                     (weight gradient)
-    int32_t *out;       // forward: [M][K] (fp32 when out_mode != 0) ; weight gradient: dw [K][R][S*C], zeroed before the launch
+    int32_t *out;       // forward: [M][K] (fp32 when out_mode != 0) ; weight gradient: one [K][R][S*C] partial per block
     int out_mode;       // forward only: 0 int32 sums, 1 fp32 sA*sB*sum
     int vec_out;        // forward only: out is 16-byte aligned (16-byte stores)
     const float *sA, *sB;
     int M, K, C, R, SC, stride, PH, PW, P, Q;
     float inv_pq, inv_q;
+    int zero_off;       // weight gradient: offset in xp of 16 zero bytes
     int blocks_total;   // row blocks (forward) / 32-pixel steps (weight gradient)
     int steps_per_block;
 };
@@ -149,6 +151,8 @@ __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
 
 constexpr int kGS = 96;  // LDS bytes per pixel of the gradient tile (64 channels + pad)
 
+// NI = filter rows per wave (rows r0, r0 + 2, ...): 2 for R <= 4, else 4
+template <int NI>
 __global__ __launch_bounds__(256) void narrow_wgrad_kernel(const NarrowParams p) {
     constexpr int ITEMS = 3;  // 16-byte items per thread and step: 128 gradient + 32*2R window items <= 768
     const int XS = p.R * 32 + 16;   // LDS bytes per pixel of the window tile
@@ -161,69 +165,63 @@ __global__ __launch_bounds__(256) void narrow_wgrad_kernel(const NarrowParams p)
     const int step_end = min(p.blocks_total, step_begin + p.steps_per_block);
     if (step_begin >= step_end) return;
 
-    // this thread's items: id < 128 -> gradient (pixel id/4, granule id%4); else window chunk
-    int kind[ITEMS], ipx[ITEMS], m_it[ITEMS], dst[ITEMS], aux[ITEMS];
-    int in_[ITEMS], oy_[ITEMS], ox_[ITEMS];
+    // this thread's items: id < 128 -> gradient (pixel id/4, granule id%4); else window chunk.  An item is a base
+    // pointer, a byte offset added to the pixel's own offset, and a validity flag; the loads themselves are unconditional
+    // (an invalid item reads 16 of the zero bytes that follow the last padded image), so the loop has no branches and
+    // nothing waits for a load before its data go to LDS.
+    int m_it[ITEMS], dst[ITEMS], aux[ITEMS];
+    bool win[ITEMS], ok[ITEMS];
+    const int8_t *src[ITEMS];
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         const int id = t + 256 * j;
+        int ipx = 0;
+        win[j] = false; ok[j] = false; aux[j] = 0; dst[j] = 0; src[j] = p.g;
         if (id < 128) {
-            kind[j] = 0; ipx[j] = id / 4; aux[j] = (id % 4) * 16;
-            dst[j] = ipx[j] * kGS + aux[j];
+            ipx = id / 4; aux[j] = (id % 4) * 16; ok[j] = aux[j] < p.K;
+            dst[j] = ipx * kGS + aux[j];
         } else if (id - 128 < 32 * 2 * p.R) {
             const int id2 = id - 128, chunk = id2 % (2 * p.R);
-            kind[j] = 1; ipx[j] = id2 / (2 * p.R);
+            ipx = id2 / (2 * p.R); win[j] = true; ok[j] = true; src[j] = p.xp;
             aux[j] = (chunk / 2) * row_bytes + (chunk % 2) * 16;             // byte offset from the pixel's window origin
-            dst[j] = 32 * kGS + ipx[j] * XS + (chunk / 2) * 32 + (chunk % 2) * 16;
-        } else {
-            kind[j] = 2; ipx[j] = 0; aux[j] = 0; dst[j] = 0;
+            dst[j] = 32 * kGS + ipx * XS + (chunk / 2) * 32 + (chunk % 2) * 16;
         }
-        m_it[j] = step_begin * 32 + ipx[j];
-        in_[j] = div24(min(m_it[j], p.M - 1), pq, p.inv_pq);
-        const int rem = min(m_it[j], p.M - 1) - in_[j] * pq;
-        oy_[j] = div24(rem, p.Q, p.inv_q);
-        ox_[j] = rem - oy_[j] * p.Q;
+        m_it[j] = step_begin * 32 + ipx;
     }
-    const int step_q = 32 / p.Q, step_r = 32 % p.Q;
 
-    v4i stage[ITEMS];
-    auto load_items = [&]() {
+    // two steps of loads are in flight in registers (slots 0 and 1) ahead of the step being multiplied from LDS
+    v4i stage[2][ITEMS];
+    auto load_items = [&](auto slot_tag) {
+        constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
-            v4i v = {0, 0, 0, 0};
-            if (m_it[j] < p.M) {
-                if (kind[j] == 0) {
-                    if (aux[j] < p.K) v = *reinterpret_cast<const v4i *>(p.g + (size_t)m_it[j] * p.K + aux[j]);
-                } else if (kind[j] == 1) {
-                    v = load16_any(p.xp + ((size_t)(in_[j] * p.PH + oy_[j] * p.stride) * p.PW + ox_[j] * p.stride) * p.C + aux[j]);
-                }
-            }
-            stage[j] = v;
+            const int m = min(m_it[j], p.M - 1);
+            const int n = div24(m, pq, p.inv_pq), rem = m - n * pq;
+            const int oy = div24(rem, p.Q, p.inv_q), ox = rem - oy * p.Q;
+            const int off_w = ((n * p.PH + oy * p.stride) * p.PW + ox * p.stride) * p.C;
+            const bool valid = ok[j] && m_it[j] < p.M;
+            const int off = valid ? (win[j] ? off_w : m * p.K) + aux[j] : p.zero_off;
+            stage[SL][j] = load16_any((valid ? src[j] : p.xp) + off);
+            m_it[j] += 32;   // on to the next step's pixels
         }
     };
-    auto advance = [&]() {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            m_it[j] += 32;
-            ox_[j] += step_r;
-            oy_[j] += step_q;
-            if (ox_[j] >= p.Q) { ox_[j] -= p.Q; ++oy_[j]; }
-            while (oy_[j] >= p.P) { oy_[j] -= p.P; ++in_[j]; }
-        }
-    };
-    auto store_items = [&](int buf) {
+    auto store_items = [&](auto slot_tag) {  // slot s goes to LDS buffer s
+        constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j)
-            if (kind[j] != 2) *reinterpret_cast<v4i *>(lds + buf * buf_bytes + dst[j]) = stage[j];
+            if (ok[j]) *reinterpret_cast<v4i *>(lds + SL * buf_bytes + dst[j]) = stage[SL][j];
     };
 
     // wave -> channel tile kt (32 gradient channels) and filter rows r = w/2, w/2+2, ...
     const int kt = wave % 2, r0 = wave / 2;
-    v16i acc[4];
+    v16i acc[NI];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][e] = 0;
+    int b_row[NI];   // a row past the filter reads the last row again; its sums are never stored
+#pragma unroll
+    for (int i = 0; i < NI; ++i) b_row[i] = min(r0 + 2 * i, p.R - 1) * 32;
 
     // transposing LDS read: source lane j of a 16-lane block reads pixel j/2, byte offset 8*(j%2);
     // result lane i then holds byte column i of 8 pixels (see the general weight-gradient kernel)
@@ -233,44 +231,47 @@ __global__ __launch_bounds__(256) void narrow_wgrad_kernel(const NarrowParams p)
     const int b_off = 32 * kGS + src_px * XS + src_ch;
     typedef __attribute__((address_space(3))) v2i lds_v2i;
 
-    load_items();
-    store_items(0);
-    advance();
-    __syncthreads();
-    for (int st = step_begin; st < step_end; ++st) {
-        const int buf = (st - step_begin) & 1;
-        const bool more = st + 1 < step_end;
-        if (more) load_items();
-        unsigned char *base = lds + buf * buf_bytes;
+    const std::integral_constant<int, 0> s0;
+    const std::integral_constant<int, 1> s1;
+    auto body = [&](auto slot_tag, int st) {  // step st sits in LDS buffer SL, step st + 1 in register slot 1 - SL
+        constexpr int SL = decltype(slot_tag)::value;
+        if (st + 2 < step_end) load_items(slot_tag);
+        unsigned char *base = lds + SL * buf_bytes;
         const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off));
         const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off + 8 * kGS));
         const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+        v4i b[NI];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = r0 + 2 * i;
-            if (r < p.R) {
-                const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + r * 32));
-                const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + r * 32 + 8 * XS));
-                const v4i b = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
-                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
-            }
+        for (int i = 0; i < NI; ++i) {
+            const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + b_row[i]));
+            const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + b_row[i] + 8 * XS));
+            b[i] = v4i{b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
         }
-        if (more) {
-            store_items(buf ^ 1);
-            advance();
-        }
+#pragma unroll
+        for (int i = 0; i < NI; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[i], acc[i], 0, 0, 0);
+        if (st + 1 < step_end) store_items(std::integral_constant<int, 1 - SL>());
         __syncthreads();
+    };
+    load_items(s0);
+    if (step_begin + 1 < step_end) load_items(s1);
+    store_items(s0);
+    __syncthreads();
+    for (int st = step_begin; st < step_end; st += 2) {
+        body(s0, st);
+        if (st + 1 < step_end) body(s1, st + 1);
     }
+    // every block writes its own copy of the whole filter gradient; a second launch adds the copies up
+    int32_t *part = p.out + (size_t)blockIdx.x * p.K * p.R * p.SC;
     const int j = lane % 32;
     if (j < p.SC) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int r = r0 + 2 * i;
             if (r < p.R) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int k = 32 * kt + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
-                    if (k < p.K && acc[i][e] != 0) atomicAdd(p.out + ((size_t)k * p.R + r) * p.SC + j, acc[i][e]);
+                    if (k < p.K) part[((size_t)k * p.R + r) * p.SC + j] = acc[i][e];
                 }
             }
         }
@@ -294,8 +295,20 @@ bool narrow_conv_supported(const lpdt_conv_desc *d, int P, int Q) {
 size_t narrow_fwd_workspace(const lpdt_conv_desc *d) {
     return round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256) + round_up((size_t)d->K * d->R * 32, 256);
 }
+// blocks of the weight-gradient launch and 32-pixel steps per block
+static void narrow_wgrad_grid(long long M, int *grid, int *steps_per_block) {
+    const int steps = (int)((M + 31) / 32);
+    int g = 512;   // 2 blocks per CU: more copies cost more in the second launch than they gain in the first
+    if (g > steps / 8) g = steps / 8 > 0 ? steps / 8 : 1;
+    *steps_per_block = (steps + g - 1) / g;
+    *grid = (steps + *steps_per_block - 1) / *steps_per_block;
+}
 size_t narrow_wgrad_workspace(const lpdt_conv_desc *d) {
-    return round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256);
+    const int P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1, Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    int grid, spb;
+    narrow_wgrad_grid((long long)d->N * P * Q, &grid, &spb);
+    return round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256) +
+           round_up((size_t)grid * d->K * d->R * d->S * d->C * sizeof(int32_t), 256);
 }
 
 static NarrowParams narrow_params(const lpdt_conv_desc *d, int P, int Q, const int8_t *xp) {
@@ -331,19 +344,21 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
     hipLaunchKernelGGL(narrow_fwd_kernel, dim3(grid), dim3(256), 0, st, p);
 }
 
-void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, int32_t *dw, void *ws,
-                         hipStream_t st) {
+void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, void *out, int out_mode,
+                         const float *sA, const float *sB, void *ws, hipStream_t st) {
     int8_t *xp = static_cast<int8_t *>(ws);
+    int32_t *partial = reinterpret_cast<int32_t *>(xp + round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256));
     launch_pad(d, x, xp, st);
     NarrowParams p = narrow_params(d, P, Q, xp);
-    p.g = g; p.out = dw;
+    p.g = g; p.out = partial;
     p.blocks_total = (p.M + 31) / 32;
-    int grid = 512;
-    if (grid > p.blocks_total / 8) grid = p.blocks_total / 8 > 0 ? p.blocks_total / 8 : 1;
-    p.steps_per_block = (p.blocks_total + grid - 1) / grid;
-    grid = (p.blocks_total + p.steps_per_block - 1) / p.steps_per_block;
+    int grid;
+    narrow_wgrad_grid(p.M, &grid, &p.steps_per_block);
     const size_t lds = 2 * (size_t)(32 * kGS + 32 * (d->R * 32 + 16));
-    hipLaunchKernelGGL(narrow_wgrad_kernel, dim3(grid), dim3(256), lds, st, p);
+    p.zero_off = (int)(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w) - 64);
+    if (d->R <= 4) hipLaunchKernelGGL(narrow_wgrad_kernel<2>, dim3(grid), dim3(256), lds, st, p);
+    else hipLaunchKernelGGL(narrow_wgrad_kernel<4>, dim3(grid), dim3(256), lds, st, p);
+    launch_wgrad_reduce(partial, (long long)d->K * d->R * d->S * d->C, grid, out, out_mode, sA, sB, st);
 }
 
 }  // namespace lpdt

@@ -397,8 +397,13 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
         else if (pl.ks == 2) go(wgrad_rect_kernel<32, 64, 9, 2, 2>);
         else go(wgrad_rect_kernel<32, 64, 9, 2, 1>);
     }
-    const long long rb = (pl.out_len / 4 + 31) / 32;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, p.partial, pl.out_len, pl.partials,
+    launch_wgrad_reduce(p.partial, pl.out_len, pl.partials, out, out_mode, sA, sB, st);
+}
+
+void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
+                         const float *sB, hipStream_t st) {
+    const long long rb = (out_len / 4 + 31) / 32;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, partial, out_len, splits,
                        static_cast<int32_t *>(out), out_mode, sA, sB);
 }
 
