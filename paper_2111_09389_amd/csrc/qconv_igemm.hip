@@ -396,7 +396,7 @@ void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
     const size_t lds = 2 * KG * ((BM * 16 + 256 / KG) + (BN * 16 + 256 / KG)) + BM * sizeof(int4) +
                        (size_t)((max_kps + PF - 1) / PF * PF + PF) * KG * sizeof(int2);
     auto go = [&](auto kernel) {
-        if (lds > 48 * 1024) hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, p);
     };
     if (p.atomic_out) go(igemm_kernel<BM, BN, WM, WN, PF, true, KG>);

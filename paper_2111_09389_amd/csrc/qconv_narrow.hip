@@ -87,13 +87,17 @@ struct NarrowParams {
     int steps_per_block;
 };
 
+// NR = filter rows multiplied (4 for R <= 4, else 8).  Nothing in the row sequence depends on R or K at run time, so the
+// accumulators stay in place between the MFMAs: rows past R hold zero weights and read row R-1 of the window again,
+// channels past K hold zero weights.
+template <int NR>
 __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
     const int lane = threadIdx.x % 64, half = lane / 32;
     const int gwave = blockIdx.x * 4 + threadIdx.x / 64, nwaves = gridDim.x * 4;
     const int pq = p.P * p.Q;
-    v4i b[kNR][2];
+    v4i b[NR][2];
 #pragma unroll
-    for (int r = 0; r < kNR; ++r)
+    for (int r = 0; r < NR; ++r)
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn) {
             const int n = lane % 32 + 32 * tn;
@@ -112,17 +116,15 @@ __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
         for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tn][i] = 0;
-        v4i a[kNR];
+        v4i a[NR];
 #pragma unroll
-        for (int r = 0; r < kNR; ++r)
-            if (r < p.R) a[r] = load16_any(src + (size_t)r * row_bytes);
+        for (int r = 0; r < NR; ++r) a[r] = load16_any(src + (size_t)min(r, p.R - 1) * row_bytes);
 #pragma unroll
-        for (int r = 0; r < kNR; ++r)
-            if (r < p.R) {
-                // the filter is the row operand: a lane ends with 4 consecutive output channels of ONE pixel (16-byte stores)
-                acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[r][0], a[r], acc[0], 0, 0, 0);
-                if (p.K > 32) acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[r][1], a[r], acc[1], 0, 0, 0);
-            }
+        for (int r = 0; r < NR; ++r) {
+            // the filter is the row operand: a lane ends with 4 consecutive output channels of ONE pixel (16-byte stores)
+            acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[r][0], a[r], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[r][1], a[r], acc[1], 0, 0, 0);
+        }
         const int mm = rb * 32 + lane % 32;
         if (mm < p.M) {
 #pragma unroll
@@ -341,7 +343,8 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
     p.blocks_total = (p.M + 31) / 32;
     int grid = (p.blocks_total + 3) / 4;
     if (grid > 2048) grid = 2048;
-    hipLaunchKernelGGL(narrow_fwd_kernel, dim3(grid), dim3(256), 0, st, p);
+    if (d->R <= 4) hipLaunchKernelGGL(narrow_fwd_kernel<4>, dim3(grid), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(narrow_fwd_kernel<8>, dim3(grid), dim3(256), 0, st, p);
 }
 
 void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *x, void *out, int out_mode,
