@@ -153,130 +153,122 @@ __global__ __launch_bounds__(256) void narrow_fwd_kernel(const NarrowParams p) {
 
 constexpr int kGS = 96;  // LDS bytes per pixel of the gradient tile (64 channels + pad)
 
-// NI = filter rows per wave (rows r0, r0 + 2, ...): 2 for R <= 4, else 4
-template <int NI>
-__global__ __launch_bounds__(256) void narrow_wgrad_kernel(const NarrowParams p) {
-    constexpr int ITEMS = 3;  // 16-byte items per thread and step: 128 gradient + 32*2R window items <= 768
-    const int XS = p.R * 32 + 16;   // LDS bytes per pixel of the window tile
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int buf_bytes = 32 * kGS + 32 * XS;
-
-    const int t = threadIdx.x, lane = t % 64, wave = t / 64;
-    const int pq = p.P * p.Q, row_bytes = p.PW * p.C;
-    const int step_begin = blockIdx.x * p.steps_per_block;
-    const int step_end = min(p.blocks_total, step_begin + p.steps_per_block);
-    if (step_begin >= step_end) return;
-
-    // this thread's items: id < 128 -> gradient (pixel id/4, granule id%4); else window chunk.  An item is a base
-    // pointer, a byte offset added to the pixel's own offset, and a validity flag; the loads themselves are unconditional
-    // (an invalid item reads 16 of the zero bytes that follow the last padded image), so the loop has no branches and
-    // nothing waits for a load before its data go to LDS.
-    int m_it[ITEMS], dst[ITEMS], aux[ITEMS];
-    bool win[ITEMS], ok[ITEMS];
-    const int8_t *src[ITEMS];
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const int id = t + 256 * j;
-        int ipx = 0;
-        win[j] = false; ok[j] = false; aux[j] = 0; dst[j] = 0; src[j] = p.g;
-        if (id < 128) {
-            ipx = id / 4; aux[j] = (id % 4) * 16; ok[j] = aux[j] < p.K;
-            dst[j] = ipx * kGS + aux[j];
-        } else if (id - 128 < 32 * 2 * p.R) {
-            const int id2 = id - 128, chunk = id2 % (2 * p.R);
-            ipx = id2 / (2 * p.R); win[j] = true; ok[j] = true; src[j] = p.xp;
-            aux[j] = (chunk / 2) * row_bytes + (chunk % 2) * 16;             // byte offset from the pixel's window origin
-            dst[j] = 32 * kGS + ipx * XS + (chunk / 2) * 32 + (chunk % 2) * 16;
-        }
-        m_it[j] = step_begin * 32 + ipx;
+template <int N, typename F>
+__device__ __forceinline__ void narrow_static_for(F f) {
+    if constexpr (N > 0) {
+        narrow_static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>());
     }
+}
 
-    // two steps of loads are in flight in registers (slots 0 and 1) ahead of the step being multiplied from LDS
-    v4i stage[2][ITEMS];
-    auto load_items = [&](auto slot_tag) {
+// Weight gradient of the first layer.  Every wave works alone on its own run of 32-pixel steps, for the whole filter
+// (2 channel tiles x NR filter rows = 2*NR MFMA tiles in its accumulators): it loads the step's gradient rows and window
+// rows, passes them through its private LDS area to read them back transposed (pixels become the MFMA's reduction
+// axis), and multiplies.  Nothing is shared between waves, so the loop has no barrier, and the next step's loads are in
+// flight while this step is multiplied.  At the end the block's four waves add their sums up in LDS and write one copy
+// of the filter gradient; a second launch sums the copies.  NR = 4 for R <= 4, else 8: rows past R read row R-1 again
+// and their sums are never stored.
+template <int NR>
+__global__ __launch_bounds__(256, 1) void narrow_wgrad_kernel(const NarrowParams p) {
+    constexpr int XS = NR * 32 + 32;              // LDS bytes per pixel of the window tile (8 banks from pixel to pixel: the transposing reads meet no conflict)
+    constexpr int WAVE_BYTES = 32 * kGS + 32 * XS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int t = threadIdx.x, lane = t % 64, wave = t / 64, half = lane / 32;
+    unsigned char *const base = lds + wave * WAVE_BYTES;
+    const int pq = p.P * p.Q, row_bytes = p.PW * p.C;
+    const int gw = blockIdx.x * 4 + wave;
+    const int step_begin = gw * p.steps_per_block, step_end = min(p.blocks_total, step_begin + p.steps_per_block);
+
+    v16i acc[2][NR];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[kt][r][e] = 0;
+
+    // loads of one step: 2 gradient items (pixel lane/4 + 16j, granule lane%4) and NR window items (pixel lane%32,
+    // bytes 16*half.. of filter row min(r, R-1)).  Past the last pixel and past the wave's last step the gradient items read
+    // zero bytes, so the loop below runs its steps in groups of D with no condition around the MFMAs.
+    const bool g_ok = (lane % 4) * 16 < p.K;
+    constexpr int D = 4;   // steps whose loads are in flight (in registers) ahead of the one being multiplied
+    v4i gs[D][2], ws[D][NR];
+    auto load_step = [&](auto slot_tag, int st) {
         constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int m = min(m_it[j], p.M - 1);
-            const int n = div24(m, pq, p.inv_pq), rem = m - n * pq;
-            const int oy = div24(rem, p.Q, p.inv_q), ox = rem - oy * p.Q;
-            const int off_w = ((n * p.PH + oy * p.stride) * p.PW + ox * p.stride) * p.C;
-            const bool valid = ok[j] && m_it[j] < p.M;
-            const int off = valid ? (win[j] ? off_w : m * p.K) + aux[j] : p.zero_off;
-            stage[SL][j] = load16_any((valid ? src[j] : p.xp) + off);
-            m_it[j] += 32;   // on to the next step's pixels
+        for (int j = 0; j < 2; ++j) {
+            const int m = st * 32 + lane / 4 + 16 * j;
+            const bool valid = g_ok && m < p.M && st < step_end;
+            gs[SL][j] = load16_any(valid ? p.g + (size_t)m * p.K + (lane % 4) * 16 : p.xp + p.zero_off);
         }
+        const int m = min(st * 32 + lane % 32, p.M - 1);
+        const int n = div24(m, pq, p.inv_pq), rem = m - n * pq;
+        const int oy = div24(rem, p.Q, p.inv_q), ox = rem - oy * p.Q;
+        const int8_t *src = p.xp + ((size_t)(n * p.PH + oy * p.stride) * p.PW + ox * p.stride) * p.C + 16 * half;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) ws[SL][r] = load16_any(src + (size_t)min(r, p.R - 1) * row_bytes);
     };
-    auto store_items = [&](auto slot_tag) {  // slot s goes to LDS buffer s
+    auto store_step = [&](auto slot_tag) {
         constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-            if (ok[j]) *reinterpret_cast<v4i *>(lds + SL * buf_bytes + dst[j]) = stage[SL][j];
+        for (int j = 0; j < 2; ++j) *reinterpret_cast<v4i *>(base + (lane / 4 + 16 * j) * kGS + (lane % 4) * 16) = gs[SL][j];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) *reinterpret_cast<v4i *>(base + 32 * kGS + (lane % 32) * XS + r * 32 + 16 * half) = ws[SL][r];
     };
-
-    // wave -> channel tile kt (32 gradient channels) and filter rows r = w/2, w/2+2, ...
-    const int kt = wave % 2, r0 = wave / 2;
-    v16i acc[NI];
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][e] = 0;
-    int b_row[NI];   // a row past the filter reads the last row again; its sums are never stored
-#pragma unroll
-    for (int i = 0; i < NI; ++i) b_row[i] = min(r0 + 2 * i, p.R - 1) * 32;
-
     // transposing LDS read: source lane j of a 16-lane block reads pixel j/2, byte offset 8*(j%2);
     // result lane i then holds byte column i of 8 pixels (see the general weight-gradient kernel)
     const int blk = lane / 16, j16 = lane % 16;
     const int src_px = 16 * (blk / 2) + j16 / 2, src_ch = 16 * (blk % 2) + 8 * (j16 % 2);
-    const int a_off = src_px * kGS + 32 * kt + src_ch;
+    const int a_off = src_px * kGS + src_ch;
     const int b_off = 32 * kGS + src_px * XS + src_ch;
     typedef __attribute__((address_space(3))) v2i lds_v2i;
-
-    const std::integral_constant<int, 0> s0;
-    const std::integral_constant<int, 1> s1;
-    auto body = [&](auto slot_tag, int st) {  // step st sits in LDS buffer SL, step st + 1 in register slot 1 - SL
-        constexpr int SL = decltype(slot_tag)::value;
-        if (st + 2 < step_end) load_items(slot_tag);
-        unsigned char *base = lds + SL * buf_bytes;
-        const v2i a_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off));
-        const v2i a_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off + 8 * kGS));
-        const v4i a = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
-        v4i b[NI];
+    auto multiply = [&]() {
+        v4i a[2];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const v2i b_lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + b_row[i]));
-            const v2i b_hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + b_row[i] + 8 * XS));
-            b[i] = v4i{b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+        for (int kt = 0; kt < 2; ++kt) {
+            const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off + 32 * kt));
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + a_off + 32 * kt + 8 * kGS));
+            a[kt] = v4i{lo[0], lo[1], hi[0], hi[1]};
         }
 #pragma unroll
-        for (int i = 0; i < NI; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[i], acc[i], 0, 0, 0);
-        if (st + 1 < step_end) store_items(std::integral_constant<int, 1 - SL>());
-        __syncthreads();
+        for (int r = 0; r < NR; ++r) {
+            const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + r * 32));
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(base + b_off + r * 32 + 8 * XS));
+            const v4i b = {lo[0], lo[1], hi[0], hi[1]};
+            acc[0][r] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[0], b, acc[0][r], 0, 0, 0);
+            acc[1][r] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[1], b, acc[1][r], 0, 0, 0);
+        }
     };
-    load_items(s0);
-    if (step_begin + 1 < step_end) load_items(s1);
-    store_items(s0);
-    __syncthreads();
-    for (int st = step_begin; st < step_end; st += 2) {
-        body(s0, st);
-        if (st + 1 < step_end) body(s1, st + 1);
+    // slot (st - step_begin) % D holds step st; the loop body covers D steps so that the slots are compile-time names
+    narrow_static_for<D - 1>([&](auto u) { load_step(u, step_begin + decltype(u)::value); });
+    for (int st = step_begin; st < step_end; st += D) {
+        narrow_static_for<D>([&](auto u) {
+            constexpr int U = decltype(u)::value;
+            load_step(std::integral_constant<int, (U + D - 1) % D>(), st + U + D - 1);
+            store_step(u);
+            multiply();
+        });
     }
-    // every block writes its own copy of the whole filter gradient; a second launch adds the copies up
-    int32_t *part = p.out + (size_t)blockIdx.x * p.K * p.R * p.SC;
-    const int j = lane % 32;
-    if (j < p.SC) {
+    // the block's sum: every wave adds its tiles into one [K][NR][32] array in LDS (over the staging areas)
+    __syncthreads();
+    int32_t *sum = reinterpret_cast<int32_t *>(lds);
+    for (int i = t; i < 64 * NR * 32; i += 256) sum[i] = 0;
+    __syncthreads();
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int r = r0 + 2 * i;
-            if (r < p.R) {
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int k = 32 * kt + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
-                    if (k < p.K) part[((size_t)k * p.R + r) * p.SC + j] = acc[i][e];
-                }
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int k = 32 * kt + 8 * (e / 4) + 4 * half + (e % 4);
+                atomicAdd(&sum[(k * NR + r) * 32 + lane % 32], acc[kt][r][e]);
             }
-        }
+    __syncthreads();
+    int32_t *part = p.out + (size_t)blockIdx.x * p.K * p.R * p.SC;
+    const int per_k = p.R * p.SC;
+    for (int i = t; i < p.K * per_k; i += 256) {
+        const int k = i / per_k, rj = i - k * per_k, r = rj / p.SC, j = rj - r * p.SC;
+        part[i] = sum[(k * NR + r) * 32 + j];
     }
 }
 
@@ -297,13 +289,14 @@ bool narrow_conv_supported(const lpdt_conv_desc *d, int P, int Q) {
 size_t narrow_fwd_workspace(const lpdt_conv_desc *d) {
     return round_up(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w), 256) + round_up((size_t)d->K * d->R * 32, 256);
 }
-// blocks of the weight-gradient launch and 32-pixel steps per block
-static void narrow_wgrad_grid(long long M, int *grid, int *steps_per_block) {
+// blocks of the weight-gradient launch (4 waves each) and 32-pixel steps per wave
+static void narrow_wgrad_grid(long long M, int *grid, int *steps_per_wave) {
     const int steps = (int)((M + 31) / 32);
-    int g = 512;   // 2 blocks per CU: more copies cost more in the second launch than they gain in the first
-    if (g > steps / 8) g = steps / 8 > 0 ? steps / 8 : 1;
-    *steps_per_block = (steps + g - 1) / g;
-    *grid = (steps + *steps_per_block - 1) / *steps_per_block;
+    int waves = 1024;                          // one wave per SIMD: the filter's sums fill a wave's accumulators
+    if (waves > steps / 4) waves = steps / 4 > 0 ? steps / 4 : 1;
+    waves = (waves + 3) / 4 * 4;
+    *steps_per_wave = (steps + waves - 1) / waves;
+    *grid = ((steps + *steps_per_wave - 1) / *steps_per_wave + 3) / 4;
 }
 size_t narrow_wgrad_workspace(const lpdt_conv_desc *d) {
     const int P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1, Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
@@ -357,10 +350,16 @@ void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g,
     p.blocks_total = (p.M + 31) / 32;
     int grid;
     narrow_wgrad_grid(p.M, &grid, &p.steps_per_block);
-    const size_t lds = 2 * (size_t)(32 * kGS + 32 * (d->R * 32 + 16));
+    const int NR = d->R <= 4 ? 4 : 8;
+    size_t lds = 4 * (size_t)(32 * kGS + 32 * (NR * 32 + 32));
+    if (lds < (size_t)64 * NR * 32 * 4) lds = (size_t)64 * NR * 32 * 4;
     p.zero_off = (int)(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w) - 64);
-    if (d->R <= 4) hipLaunchKernelGGL(narrow_wgrad_kernel<2>, dim3(grid), dim3(256), lds, st, p);
-    else hipLaunchKernelGGL(narrow_wgrad_kernel<4>, dim3(grid), dim3(256), lds, st, p);
+    auto go = [&](auto kernel) {
+        if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, st, p);
+    };
+    if (NR == 4) go(narrow_wgrad_kernel<4>);
+    else go(narrow_wgrad_kernel<8>);
     launch_wgrad_reduce(partial, (long long)d->K * d->R * d->S * d->C, grid, out, out_mode, sA, sB, st);
 }
 
