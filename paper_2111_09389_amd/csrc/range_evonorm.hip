@@ -282,12 +282,31 @@ __global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsign
                                                          const float *__restrict__ beta, float cm, float eps,
                                                          float *__restrict__ range_out, int32_t *__restrict__ argmax_out,
                                                          int32_t *__restrict__ argmin_out, float *__restrict__ absmax) {
-    extern __shared__ unsigned long long skeys[];  // [groups][2], then float inv[groups]
+    extern __shared__ unsigned long long skeys[];  // [groups][2], then float inv[groups], then unsigned su[C][2]
     __shared__ float lds[256 / kWave];
     float *sinv = reinterpret_cast<float *>(skeys + 2 * g.groups);
+    unsigned int *su = reinterpret_cast<unsigned int *>(sinv + g.groups);
     const int n = blockIdx.x, nk = 2 * g.groups;
     for (int i = threadIdx.x; i < nk; i += blockDim.x) skeys[i] = 0ull;
+    for (int i = threadIdx.x; i < 2 * g.C; i += blockDim.x) su[i] = 0u;
     __syncthreads();
+    // per-channel extremes of u over the sample's blocks: the threads of a channel split the blocks between them
+    {
+        const int parts = g.C < 256 ? 256 / g.C : 1;
+        const float2 *p2 = reinterpret_cast<const float2 *>(pu + (size_t)n * g.chunks * g.C * 2);
+        for (int i = threadIdx.x; i < g.C * parts; i += blockDim.x) {
+            const int c = i % g.C, part = i / g.C;
+            float hi = -INFINITY, lo = INFINITY;
+            for (int ch = part; ch < g.chunks; ch += parts) {
+                const float2 v = p2[(size_t)ch * g.C + c];
+                hi = fmaxf(hi, v.x); lo = fminf(lo, v.y);
+            }
+            if (part < g.chunks) {
+                atomicMax(&su[c * 2 + 0], ordered_bits(hi));
+                atomicMax(&su[c * 2 + 1], ~ordered_bits(lo));
+            }
+        }
+    }
     const unsigned long long *src = pstats + (size_t)n * g.chunks * nk;
     for (int i = threadIdx.x; i < g.chunks * nk; i += blockDim.x) {
         const unsigned long long k = src[i];
@@ -305,9 +324,7 @@ __global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsign
     __syncthreads();
     float am = 0.0f;
     for (int c = threadIdx.x; c < g.C; c += blockDim.x) {
-        float hi = -INFINITY, lo = INFINITY;
-        const float *p = pu + (size_t)n * g.chunks * g.C * 2 + c * 2;
-        for (int ch = 0; ch < g.chunks; ++ch) { hi = fmaxf(hi, p[(size_t)ch * g.C * 2]); lo = fminf(lo, p[(size_t)ch * g.C * 2 + 1]); }
+        const float hi = from_ordered_bits(su[c * 2 + 0]), lo = from_ordered_bits(~su[c * 2 + 1]);
         const float inv = sinv[c / g.m], gg = gamma[c], bb = beta[c];
         am = fmaxf(am, fmaxf(fabsf(ren_y(hi, gg, inv, bb)), fabsf(ren_y(lo, gg, inv, bb))));
     }
@@ -762,7 +779,7 @@ extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int
     const size_t key_lds = (size_t)2 * groups * sizeof(unsigned long long);
     hipLaunchKernelGGL(ren_stats_kernel<true>, dim3(g.chunks, N), dim3(g.block), key_lds + (size_t)2 * C * sizeof(unsigned int), st, x, g,
                        keys, absmax, v, pu);
-    hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), key_lds + groups * sizeof(float), st, g, keys, pu, gamma, beta, cm, eps,
+    hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), key_lds + groups * sizeof(float) + (size_t)2 * C * sizeof(unsigned int), st, g, keys, pu, gamma, beta, cm, eps,
                        range_out, argmax_out, argmin_out, absmax);
     hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out,
                        absmax, q, scale, y);
