@@ -145,8 +145,22 @@ int lpdt_qconv_fwd_f32(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *
 int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, const float *sg,
                             const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes,
                             void *stream);
+
 int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, const float *sg,
                               const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream);
+
+/* The same product with the filter prepared ahead of time.  Backward-data reads the filter transposed; the call above
+ * transposes it on every call, although the weights change only once per step (Algorithm 1, line 3).  A training step
+ * can make the transposed copy when the weights' codes are final (for instance beside the forward pass, on another
+ * stream) and hand it over here.  lpdt_qconv_bwd_data_packed_filter_bytes: size of the copy, 0 when the shape has no
+ * prepared form (then only lpdt_qconv_bwd_data_f32 applies).  packed: device, 16-byte aligned, owned by the caller,
+ * valid until the weights change.  Results are those of lpdt_qconv_bwd_data_f32, bit for bit. */
+size_t lpdt_qconv_bwd_data_packed_filter_bytes(const lpdt_conv_desc *d);
+int lpdt_qconv_bwd_data_pack_filter(const lpdt_conv_desc *d, const int8_t *wq, void *packed, size_t packed_bytes,
+                                    void *stream);
+int lpdt_qconv_bwd_data_f32_packed(const lpdt_conv_desc *d, const int8_t *gq, const void *packed, const float *sg,
+                                   const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes,
+                                   void *stream);
 
 /* The forward product added to what y already holds (Table "hardware_training", row Skip Connections, done in
  * the convolution's epilogue): y += (sx*sw) * sum, the bits of lpdt_qconv_fwd_f32 into a temporary followed by

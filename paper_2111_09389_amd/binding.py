@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -35,6 +35,7 @@ EXPORTS = [
     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_fwd_q",
     "lpdt_range_evonorm_maxpool_fwd_workspace_bytes", "lpdt_range_evonorm_maxpool_bwd_workspace_bytes",
     "lpdt_range_evonorm_maxpool_fwd", "lpdt_range_evonorm_maxpool_bwd",
+    "lpdt_qconv_bwd_data_packed_filter_bytes", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_f32_packed",
     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
     "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
@@ -99,6 +100,8 @@ def lib():
                      "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
                      "lpdt_range_evonorm_maxpool_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
+        L.lpdt_qconv_bwd_data_packed_filter_bytes.restype = _sz
+        L.lpdt_qconv_bwd_data_packed_filter_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 4
         L.lpdt_gossip_mix_workspace_bytes.argtypes = [ctypes.c_int, _sz, ctypes.c_int, ctypes.c_int]
@@ -255,6 +258,29 @@ def qconv_bwd_data_f32(d, gq, wq, sg, sw, dx=None, accumulate=False, ws=None):
     buf, nb = _ws(ws, lib().lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
     _check(lib().lpdt_qconv_bwd_data_f32(ctypes.byref(d), _ptr(gq), _ptr(wq), _ptr(sg), _ptr(sw), _ptr(dx), int(bool(accumulate)),
                                          _ptr(buf), _sz(nb), _stream()))
+    return dx
+
+
+def qconv_bwd_data_pack_filter(d, wq):
+    """The filter as backward-data reads it (transposed panels), for qconv_bwd_data_f32_packed; None when the shape has no
+    prepared form."""
+    _dev(wq, torch.int8, "qconv_bwd_data_pack_filter wq")
+    assert tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    nb = int(lib().lpdt_qconv_bwd_data_packed_filter_bytes(ctypes.byref(d)))
+    if nb == 0:
+        return None
+    packed = torch.empty(nb, dtype=torch.uint8, device=wq.device)
+    _check(lib().lpdt_qconv_bwd_data_pack_filter(ctypes.byref(d), _ptr(wq), _ptr(packed), _sz(nb), _stream()))
+    return packed
+
+
+def qconv_bwd_data_f32_packed(d, gq, packed, sg, sw, dx=None, accumulate=False, ws=None):
+    _dev(gq, torch.int8, "qconv_bwd_data_f32_packed gq")
+    assert tuple(gq.shape) == (d.N, d.P, d.Q, d.K)
+    dx = torch.empty((d.N, d.H, d.W, d.C), dtype=torch.float32, device=gq.device) if dx is None else dx
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_data_f32_packed(ctypes.byref(d), _ptr(gq), _ptr(packed), _ptr(sg), _ptr(sw), _ptr(dx),
+                                                int(bool(accumulate)), _ptr(buf), _sz(nb), _stream()))
     return dx
 
 

@@ -373,15 +373,17 @@ static bool bwd_data_fusable(const lpdt_conv_desc *d, int P, int Q) {
     return bwd_data_vec(d, P, Q) && !igemm_bwd_data_is_split(d, P, Q);
 }
 
-static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *wq, void *out,
-                              int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st) {
+// packed: the filter's transposed panels made earlier by lpdt_qconv_bwd_data_pack_filter (then wq is not read), else NULL
+static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *wq, const void *packed,
+                              void *out, int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st) {
     const size_t out_len = (size_t)d->N * d->H * d->W * d->C;
-    const bool al = aligned(gq, 16) && aligned(wq, 16);   // the matrix-core path loads both operands 16 bytes at a time
+    const bool al = aligned(gq, 16) && (packed || aligned(wq, 16));   // the matrix-core path loads both operands 16 bytes at a time
     const bool stage = out_mode != 0 && !(bwd_data_fusable(d, P, Q) && al);
     int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_data_base_ws(d)) : static_cast<int32_t *>(out);
     const int mode = stage ? 0 : out_mode;
     if (bwd_data_vec(d, P, Q) && al) {
-        launch_igemm_bwd_data(d, P, Q, gq, wq, acc, mode, sA, sB, ws, st);
+        if (!packed) launch_igemm_pack_bwd_filter(d, P, Q, wq, ws, st);
+        launch_igemm_bwd_data(d, P, Q, gq, packed ? packed : ws, acc, mode, sA, sB, st);
     } else {
         hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, gq, wq, acc, *d, P, Q);
     }
@@ -405,7 +407,7 @@ extern "C" int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, co
     LPDT_REQUIRE(aligned(dx, 4), LPDT_EINVAL, "qconv_bwd_data: dx must be 4-byte aligned");
     rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_data_workspace_bytes(d));
     if (rc) return rc;
-    conv_bwd_data_impl(d, P, Q, gq, wq, dx, 0, nullptr, nullptr, ws, as_stream(stream));
+    conv_bwd_data_impl(d, P, Q, gq, wq, nullptr, dx, 0, nullptr, nullptr, ws, as_stream(stream));
     return launch_status("lpdt_qconv_bwd_data");
 }
 
@@ -420,8 +422,43 @@ extern "C" int lpdt_qconv_bwd_data_f32(const lpdt_conv_desc *d, const int8_t *gq
                                         : bwd_data_base_ws(d) + round_up((size_t)d->N * d->H * d->W * d->C * 4, 256);
     rc = check_ws(ws, ws_bytes, need);
     if (rc) return rc;
-    conv_bwd_data_impl(d, P, Q, gq, wq, dx, accumulate ? 2 : 1, sg, sw, ws, as_stream(stream));
+    conv_bwd_data_impl(d, P, Q, gq, wq, nullptr, dx, accumulate ? 2 : 1, sg, sw, ws, as_stream(stream));
     return launch_status("lpdt_qconv_bwd_data_f32");
+}
+
+extern "C" size_t lpdt_qconv_bwd_data_packed_filter_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
+    return bwd_data_vec(d, P, Q) ? round_up(igemm_bwd_filter_panel_bytes(d), 256) : 0;
+}
+
+extern "C" int lpdt_qconv_bwd_data_pack_filter(const lpdt_conv_desc *d, const int8_t *wq, void *packed, size_t packed_bytes,
+                                               void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(wq && packed, LPDT_EINVAL, "qconv_bwd_data_pack_filter: NULL argument");
+    LPDT_REQUIRE(bwd_data_vec(d, P, Q), LPDT_EUNSUPPORTED, "qconv_bwd_data_pack_filter: this shape has no packed filter");
+    LPDT_REQUIRE(aligned(wq, 16) && aligned(packed, 16), LPDT_EINVAL, "qconv_bwd_data_pack_filter: wq and packed must be 16-byte aligned");
+    LPDT_REQUIRE(packed_bytes >= lpdt_qconv_bwd_data_packed_filter_bytes(d), LPDT_EWORKSPACE,
+                 "qconv_bwd_data_pack_filter: packed needs %zu bytes, got %zu", lpdt_qconv_bwd_data_packed_filter_bytes(d), packed_bytes);
+    launch_igemm_pack_bwd_filter(d, P, Q, wq, packed, as_stream(stream));
+    return launch_status("lpdt_qconv_bwd_data_pack_filter");
+}
+
+extern "C" int lpdt_qconv_bwd_data_f32_packed(const lpdt_conv_desc *d, const int8_t *gq, const void *packed, const float *sg,
+                                              const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && packed && dx && sg && sw, LPDT_EINVAL, "qconv_bwd_data_f32_packed: NULL argument");
+    LPDT_REQUIRE(bwd_data_vec(d, P, Q), LPDT_EUNSUPPORTED, "qconv_bwd_data_f32_packed: this shape has no packed filter");
+    LPDT_REQUIRE(aligned(dx, 16) && aligned(gq, 16) && aligned(packed, 16), LPDT_EINVAL,
+                 "qconv_bwd_data_f32_packed: gq, packed and dx must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_data_f32_workspace_bytes(d));
+    if (rc) return rc;
+    conv_bwd_data_impl(d, P, Q, gq, nullptr, packed, dx, accumulate ? 2 : 1, sg, sw, ws, as_stream(stream));
+    return launch_status("lpdt_qconv_bwd_data_f32_packed");
 }
 
 // Weight gradient.  Which kernel runs: first-layer path, rectangle-stepped kernel (partial tiles + reduction), the

@@ -528,8 +528,9 @@ void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, co
     run(p, (size_t)d->N * P * Q * d->K, st);
 }
 
-void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *w, void *out, int out_mode,
-                           const float *sA, const float *sB, void *panel, hipStream_t st) {
+size_t igemm_bwd_filter_panel_bytes(const lpdt_conv_desc *d) { return (size_t)d->K * d->R * d->S * d->C; }
+
+void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const int8_t *w, void *panel, hipStream_t st) {
     IgemmParams p;
     PackParams pk;
     bwd_params(d, P, Q, &p, &pk);
@@ -537,6 +538,13 @@ void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *
     for (int cl = 0; cl < pk.nclasses; ++cl) taps += pk.Rc[cl] * pk.Sc[cl];
     const int b = taps * ((pk.C + 63) / 64) * ((pk.K + 63) / 64);
     if (b > 0) hipLaunchKernelGGL(pack_filter_bwd_kernel, dim3((unsigned)b), dim3(256), 0, st, w, static_cast<int8_t *>(panel), pk);
+}
+
+void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const void *panel, void *out, int out_mode,
+                           const float *sA, const float *sB, hipStream_t st) {
+    IgemmParams p;
+    PackParams pk;
+    bwd_params(d, P, Q, &p, &pk);
     p.in = g; p.wt = static_cast<const int8_t *>(panel); p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
     p.vec_out = d->C % 4 == 0 && aligned(out, 16);
     run(p, (size_t)d->N * d->H * d->W * d->C, st);

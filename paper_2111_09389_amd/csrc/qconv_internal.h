@@ -24,9 +24,12 @@ bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q);
 // out_mode 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32 added to `out`.  x, w, g 16-byte aligned.
 void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, void *out, int out_mode,
                       const float *sA, const float *sB, hipStream_t st);
-// `panel`: K*R*S*C bytes of scratch for the transposed filter.
-void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const int8_t *w, void *out, int out_mode,
-                           const float *sA, const float *sB, void *panel, hipStream_t st);
+// Backward-data reads the filter as transposed panels (one per stride residue class), K*R*S*C bytes in all, 16-byte
+// aligned: made by the first call, consumed by the second (g and panel 16-byte aligned).
+size_t igemm_bwd_filter_panel_bytes(const lpdt_conv_desc *d);
+void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const int8_t *w, void *panel, hipStream_t st);
+void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const void *panel, void *out, int out_mode,
+                           const float *sA, const float *sB, hipStream_t st);
 
 // Weight gradient, rectangle-stepped kernel with partial tiles and a fixed-order reduction.
 struct WgradRectPlan {

@@ -40,10 +40,12 @@ class TrainStep:
     (then `upstream` must be the gradient of the last tensor)."""
 
     def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5,
-                 wgrad_16bit=False, overlap_wgrad=True, fuse_ren_quant=True):
+                 wgrad_16bit=False, overlap_wgrad=True, fuse_ren_quant=True, prepack_filters=True):
         self.L = lib()
         self.overlap_wgrad = overlap_wgrad
         self.fuse_ren_quant = fuse_ren_quant   # Range-EvoNorm layers that feed only convolutions emit int8 codes directly
+        # backward-data's transposed filters are made once per step, on the second stream beside the forward pass
+        self.prepack_filters = prepack_filters and overlap_wgrad
         self.net, self.N, self.lr, self.seed, self.eps = net, batch, lr, seed, eps
         # gradient bifurcation as the paper states it: weight gradients from a bfloat16 copy of the layer gradient
         # (the 8-bit codes still feed backward-data), for every layer but the one that reads the image; default: both
@@ -128,6 +130,7 @@ class TrainStep:
     def _plan_forward(self, labels, upstream):
         net, N, L = self.net, self.N, self.L
         self.xq, self.sx, self.wq, self.sw, self.desc, self.ren_saved, self.pool_idx = {}, {}, {}, {}, {}, {}, {}
+        self.wpacked = {}                # conv output -> its filter as backward-data reads it
         # All filters are quantized by one call on the flat parameter vector (own scale each); their codes keep the
         # vector's layout, so a filter's codes are a 16-byte aligned slice when its offset is a multiple of 16.
         convs = [op for op in net.ops if op[0] == "conv"]
@@ -183,6 +186,17 @@ class TrainStep:
             for i, (op, (b, e)) in enumerate(zip(convs, spans)):
                 self.wq[op[1]] = wq_flat[b:e].view(self.pview[op[3]["w"]].shape)
                 self.sw[op[1]] = sw_all[i:i + 1]
+            if self.prepack_filters:     # the codes of every filter are final here
+                for op in convs:
+                    if op[2] == "x":
+                        continue         # no backward-data for the image layer
+                    d = self._desc(op[2], op[3])
+                    nb = int(L.lpdt_qconv_bwd_data_packed_filter_bytes(ctypes.byref(d)))
+                    if nb == 0 or self.wq[op[1]].data_ptr() % 16:
+                        continue
+                    packed = torch.empty(nb, dtype=torch.uint8, device=self.dev)
+                    self.wpacked[op[1]] = packed
+                    self._emit(L.lpdt_qconv_bwd_data_pack_filter, [ctypes.byref(d), _p(self.wq[op[1]]), _p(packed), _sz(nb)], side=True)
         for op in net.ops:
             kind = op[0]
             if kind == "conv":
@@ -303,6 +317,8 @@ class TrainStep:
         self.pooled_grad = {}            # normalised tensor -> (pooled gradient, winners, pool attributes) when fused
         pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
         conv_index = 0
+        if self.wpacked:
+            self.calls.append((None, [], None, False))   # the main stream waits here for the second stream's filter copies
         for op in reversed(net.ops):
             kind = op[0]
             if kind == "loss":
@@ -323,8 +339,12 @@ class TrainStep:
                     buf, accumulate = self._grad_target(inp, pending)
                     self.gabsmax.pop(inp, None)
                     self._need_ws(L.lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
-                    self._emit(L.lpdt_qconv_bwd_data_f32, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(sg), _p(self.sw[out]),
-                                                           _p(buf), accumulate, "WS", "WSB"])
+                    if out in self.wpacked:
+                        self._emit(L.lpdt_qconv_bwd_data_f32_packed, [ctypes.byref(d), _p(gq), _p(self.wpacked[out]), _p(sg),
+                                                                      _p(self.sw[out]), _p(buf), accumulate, "WS", "WSB"])
+                    else:
+                        self._emit(L.lpdt_qconv_bwd_data_f32, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(sg), _p(self.sw[out]),
+                                                               _p(buf), accumulate, "WS", "WSB"])
                 gw = self.gview[a["w"]]
                 if self.wgrad_16bit and inp != "x":   # the image layer (3 channels) has no tiled 16-bit kernel: 8-bit path
                     g16 = torch.empty(dy.shape, dtype=torch.int16, device=self.dev)
@@ -405,7 +425,7 @@ class TrainStep:
         side = self._side_stream
         side_ptr = _vp(side.cuda_stream) if side is not None else stream
         last = self.L.lpdt_last_error
-        forks, joined = 0, True
+        forks, joined, prev_side = 0, True, False
         calls = self.calls if upto is None else self.calls[:upto]
         n = len(calls)
         for i, (fn, args, sr, on_side) in enumerate(calls):
@@ -413,18 +433,28 @@ class TrainStep:
                 pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
                 args[pos] = _u64((int(step) << 32) + (sr << 24))
             if on_side:
-                ev = self._fork_events[forks]
-                forks += 1
-                ev.record(main)              # everything issued so far (the quantizer of this layer's gradient included)
-                side.wait_event(ev)
+                if not prev_side:            # consecutive calls of the second stream share one fork
+                    ev = self._fork_events[forks]
+                    forks += 1
+                    ev.record(main)          # everything issued so far (the quantizer of this layer's gradient included)
+                    side.wait_event(ev)
                 rc = fn(*args, side_ptr)
                 joined = False
+                prev_side = True
+            elif fn is None:
+                prev_side = False
+                if not joined:
+                    self._join_event.record(side)
+                    main.wait_event(self._join_event)
+                    joined = True
+                continue
             else:
                 if not joined and (fn is self.L.lpdt_sgd or i == n - 1):
                     self._join_event.record(side)
                     main.wait_event(self._join_event)
                     joined = True
                 rc = fn(*args, stream)
+                prev_side = False
             if rc != 0:
                 raise LpdtError(rc, last().decode())
         if not joined:
@@ -437,6 +467,8 @@ class TrainStep:
         stream = _vp(torch.cuda.current_stream().cuda_stream)
         marks = []
         for fn, args, sr, _ in self.calls:
+            if fn is None:
+                continue
             if sr is not None:
                 pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
                 args[pos] = _u64((int(step) << 32) + (sr << 24))
@@ -454,8 +486,10 @@ class TrainStep:
         """[(entry point name, multiply-adds)] for every convolution call of one step, in call order."""
         out = []
         for fn, args, _, _ in self.calls:
-            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_fwd_f32_add", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
-                               "lpdt_qconv_bwd_weight_bf16"):
+            if fn is None:
+                continue
+            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_fwd_f32_add", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_data_f32_packed",
+                               "lpdt_qconv_bwd_weight_f32", "lpdt_qconv_bwd_weight_bf16"):
                 d = args[0]._obj
                 out.append((fn.__name__, d.N * d.P * d.Q * d.K * d.C * d.R * d.S))
         return out

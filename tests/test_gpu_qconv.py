@@ -137,3 +137,28 @@ def test_random_shapes_bit_exact_and_fused_epilogues(orc, shp):
     assert torch.equal(lpdt.qconv_fwd_f32(ld, dev(x), dev(w), sa, sb), lpdt.dequantize(acc, sa, sb))
     assert torch.equal(lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), sa, sb), lpdt.dequantize(dx, sa, sb))
     assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), lpdt.dequantize(dw, sa, sb))
+
+
+@pytest.mark.parametrize("shp", [CASES[1], CASES[3], CASES[4], CASES[5], CASES[13], CASES[15]])
+def test_backward_data_with_prepacked_filter_equals_the_plain_call(shp):
+    """lpdt_qconv_bwd_data_pack_filter + lpdt_qconv_bwd_data_f32_packed: the bits of lpdt_qconv_bwd_data_f32, overwrite and
+    accumulate; the packed copy stays valid over several calls."""
+    x, w, g = _data(shp, 900, "gauss")
+    ld = lpdt.ConvDesc.make(*shp)
+    sg = torch.tensor([0.031], dtype=torch.float32, device="cuda")
+    sw = torch.tensor([0.0042], dtype=torch.float32, device="cuda")
+    packed = lpdt.qconv_bwd_data_pack_filter(ld, dev(w))
+    assert packed is not None
+    ref = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), sg, sw)
+    got = lpdt.qconv_bwd_data_f32_packed(ld, dev(g), packed, sg, sw)
+    assert torch.equal(got, ref)
+    base = dev(wl.upstream_grad(901, tuple(ref.shape)))
+    ref2 = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), sg, sw, dx=base.clone(), accumulate=True)
+    got2 = lpdt.qconv_bwd_data_f32_packed(ld, dev(g), packed, sg, sw, dx=base.clone(), accumulate=True)
+    assert torch.equal(got2, ref2)
+
+
+def test_prepacked_filter_is_refused_where_backward_data_has_no_packed_form():
+    ld = lpdt.ConvDesc.make(1, 20, 6, 6, 24, 3, 3, 1, 1)     # channel counts that are not multiples of 16
+    w = torch.zeros((24, 3, 3, 20), dtype=torch.int8, device="cuda")
+    assert lpdt.qconv_bwd_data_pack_filter(ld, w) is None

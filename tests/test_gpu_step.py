@@ -308,3 +308,26 @@ def test_driver_fused_stem_changes_no_bit(orc):
         torch.cuda.synchronize()
         out.append((g.clone(), p.clone(), ts.loss.clone()))
     assert all(torch.equal(a, b) for a, b in zip(*out))
+
+
+def test_driver_prepacked_filters_change_no_bit(orc):
+    """Backward-data's transposed filters made once per step on the second stream (default) against the driver that lets
+    every backward-data call transpose its own: identical gradients, parameters and loss, over two steps."""
+    from paper_2111_09389_amd.step import TrainStep
+    net = nets.resnet20()
+    N = 4
+    params = nets.init_params(net, wl.BASE_SEED + 42)
+    flat = np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32)
+    x = dev(wl.images(wl.BASE_SEED + 43, N, 32, 32, 3))
+    lb = dev(wl.labels_uniform(wl.BASE_SEED + 44, N, 10))
+    out = []
+    for pre in (True, False):
+        p, g = dev(flat), torch.zeros(flat.size, dtype=torch.float32, device="cuda")
+        ts = TrainStep(net, N, p, g, x, lb, None, lr=0.05, seed=wl.PHILOX_SEED, prepack_filters=pre)
+        names = [c[0].__name__ for c in ts.calls if c[0] is not None]
+        assert ("lpdt_qconv_bwd_data_pack_filter" in names) == pre and ("lpdt_qconv_bwd_data_f32_packed" in names) == pre
+        ts.run(1)
+        ts.run(2)          # the second step must see the filters of the updated weights
+        torch.cuda.synchronize()
+        out.append((g.clone(), p.clone(), ts.loss.clone()))
+    assert all(torch.equal(a, b) for a, b in zip(*out))
