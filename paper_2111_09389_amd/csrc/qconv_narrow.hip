@@ -39,26 +39,36 @@ __device__ __forceinline__ int div24(int m, int d, float inv) {
 }
 
 // xp[n][yy][xx][c] = x[n][yy-pad][xx-pad][c] inside the image, 0 in the border and in the slack after the last image.
-// A thread builds 4 consecutive output bytes (one division chain, then carries) and stores them as one word; the
-// buffer is a multiple of 4 bytes long (total < 2^31).
+// A padded row is the image row shifted by pad*C bytes between two runs of zeros, so a thread finds its 4 consecutive
+// output bytes with one division (which padded row) and carries from there, and stores them as one word; the buffer is
+// a multiple of 4 bytes long (total < 2^31).  Four bytes from inside one image row come from two aligned word loads.
 __global__ void pad_image_kernel(const int8_t *__restrict__ x, int N, int H, int W, int C, int pad, int PH, int PW,
                                  int8_t *__restrict__ xp, unsigned total) {
     const unsigned nwords = (total + 3u) / 4u;
+    const unsigned row_bytes = (unsigned)(PW * C), src_row = (unsigned)(W * C), shift = (unsigned)(pad * C);
+    const size_t src_total = (size_t)N * H * src_row;
     for (unsigned q = blockIdx.x * blockDim.x + threadIdx.x; q < nwords; q += gridDim.x * blockDim.x) {
         const unsigned o = q * 4u;
-        int c = (int)(o % (unsigned)C);
-        unsigned rest = o / (unsigned)C;
-        int xx = (int)(rest % (unsigned)PW); rest /= (unsigned)PW;
-        int yy = (int)(rest % (unsigned)PH);
-        int n = (int)(rest / (unsigned)PH);
+        unsigned row = o / row_bytes, b = o - row * row_bytes;
+        unsigned n = row / (unsigned)PH, yy = row - n * (unsigned)PH;
+        {   // the common case, 4 bytes from inside one image row: two aligned word loads and a byte shift
+            const unsigned iy = yy - (unsigned)pad, sb = b - shift;   // wrap to huge values outside the image
+            const size_t at = ((size_t)n * H + iy) * src_row + sb;
+            if (n < (unsigned)N && iy < (unsigned)H && b >= shift && sb + 3u < src_row && at + 8 <= src_total) {
+                const uintptr_t addr = reinterpret_cast<uintptr_t>(x) + at;
+                const unsigned *w = reinterpret_cast<const unsigned *>(addr & ~(uintptr_t)3);
+                reinterpret_cast<unsigned *>(xp)[q] = __builtin_amdgcn_alignbyte(w[1], w[0], (unsigned)(addr & 3u));
+                continue;
+            }
+        }
         unsigned word = 0u;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int iy = yy - pad, ix = xx - pad;
+        for (int k = 0; k < 4; ++k) {
+            const unsigned iy = yy - (unsigned)pad, sb = b - shift;
             int8_t v = 0;
-            if (n < N && iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((size_t)n * H + iy) * W + ix) * C + c];
-            word |= (unsigned)(uint8_t)v << (8 * b);
-            if (++c == C) { c = 0; if (++xx == PW) { xx = 0; if (++yy == PH) { yy = 0; ++n; } } }
+            if (n < (unsigned)N && iy < (unsigned)H && sb < src_row) v = x[((size_t)n * H + iy) * src_row + sb];
+            word |= (unsigned)(uint8_t)v << (8 * k);
+            if (++b == row_bytes) { b = 0; if (++yy == (unsigned)PH) { yy = 0; ++n; } }
         }
         reinterpret_cast<unsigned *>(xp)[q] = word;
     }
