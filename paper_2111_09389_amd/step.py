@@ -317,6 +317,7 @@ class TrainStep:
         self.pooled_grad = {}            # normalised tensor -> (pooled gradient, winners, pool attributes) when fused
         pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
         conv_index = 0
+        deferred = {}                    # tensor -> backward-data calls waiting for another writer of its gradient
         if self.wpacked:
             self.calls.append((None, [], None, False))   # the main stream waits here for the second stream's filter copies
         for op in reversed(net.ops):
@@ -325,6 +326,8 @@ class TrainStep:
                 continue
             out = op[1]
             pending.discard(out)
+            for f in deferred.pop(out, []):      # (never left over in the benchmark networks)
+                f()
             dy = self.grad.get(out)
             if dy is None and out not in self.pooled_grad:
                 raise LpdtError(-2, f"tensor {out} has no gradient (dead branch)")
@@ -336,15 +339,26 @@ class TrainStep:
                 self.gq[out], self.sg[out] = gq, sg
                 self._quantize(dy, gq, sg, ROUND_STOCHASTIC, self.gabsmax.get(out), sr_layer=conv_index)
                 if inp != "x":
-                    buf, accumulate = self._grad_target(inp, pending)
-                    self.gabsmax.pop(inp, None)
-                    self._need_ws(L.lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
-                    if out in self.wpacked:
-                        self._emit(L.lpdt_qconv_bwd_data_f32_packed, [ctypes.byref(d), _p(gq), _p(self.wpacked[out]), _p(sg),
-                                                                      _p(self.sw[out]), _p(buf), accumulate, "WS", "WSB"])
+                    def bwd_data(out=out, d=d, gq=gq, sg=sg, inp=inp):
+                        buf, accumulate = self._grad_target(inp, pending)
+                        self.gabsmax.pop(inp, None)
+                        self._need_ws(L.lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
+                        if out in self.wpacked:
+                            self._emit(L.lpdt_qconv_bwd_data_f32_packed, [ctypes.byref(d), _p(gq), _p(self.wpacked[out]), _p(sg),
+                                                                          _p(self.sw[out]), _p(buf), accumulate, "WS", "WSB"])
+                        else:
+                            self._emit(L.lpdt_qconv_bwd_data_f32, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(sg),
+                                                                   _p(self.sw[out]), _p(buf), accumulate, "WS", "WSB"])
+                    # A strided 1x1 projection reaches only every stride-th pixel of its input.  As the first writer of that
+                    # gradient it would have to fill the rest with zeros, and the block's other convolution would then read
+                    # everything back to add to it; after that convolution it adds into a quarter of the pixels instead.
+                    later = [o for o in net.ops if o[0] == "conv" and o[2] == inp and o[1] in pending]
+                    if a["R"] == 1 and a["stride"] > 1 and inp not in self.grad and later:
+                        deferred.setdefault(inp, []).append(bwd_data)
                     else:
-                        self._emit(L.lpdt_qconv_bwd_data_f32, [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(sg), _p(self.sw[out]),
-                                                               _p(buf), accumulate, "WS", "WSB"])
+                        bwd_data()
+                        for f in deferred.pop(inp, []):
+                            f()
                 gw = self.gview[a["w"]]
                 if self.wgrad_16bit and inp != "x":   # the image layer (3 channels) has no tiled 16-bit kernel: 8-bit path
                     g16 = torch.empty(dy.shape, dtype=torch.int16, device=self.dev)
