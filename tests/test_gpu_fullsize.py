@@ -81,6 +81,9 @@ def test_conv_products_at_full_size_on_sampled_outputs(name):
     assert np.array_equal(np.array([dx[c] for c in ci], np.int64), ref), name + " backward-data"
     dxf = host(lpdt.qconv_bwd_data_f32(ld, gd, wd, sa, sb))
     assert_close(np.array([dxf[c] for c in ci]), scale * ref.astype(np.float64), 1e-5, 0.0, name + " backward-data, fused scale")
+    packed = lpdt.qconv_bwd_data_pack_filter(ld, wd)       # the filter transposed ahead of time: the same bits
+    if packed is not None:
+        assert np.array_equal(host(lpdt.qconv_bwd_data_f32_packed(ld, gd, packed, sa, sb)), dxf), name + " backward-data, packed filter"
     del dx, dxf
 
     cw = _coords(rng, (K, R, S, C), 60)
