@@ -328,15 +328,20 @@ def main():
     wg_name = "lpdt_qconv_bwd_weight_bf16" if cfg.get("wgrad_16bit") else "lpdt_qconv_bwd_weight_f32"
     if "lpdt_qconv_fwd_f32_add" in per:      # the forward product with the skip connection's addition in its epilogue
         per["lpdt_qconv_fwd_f32"] = per.get("lpdt_qconv_fwd_f32", 0.0) + per.pop("lpdt_qconv_fwd_f32_add")
-    for alias in ("lpdt_qconv_bwd_data_f32_packed", "lpdt_qconv_bwd_data_pack_filter"):   # backward-data with the filter transposed ahead of time
+    # variants of the same products: the filter transposed ahead of time, max|result| as a by-product
+    for alias in ("lpdt_qconv_bwd_data_f32_packed", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_f32_absmax"):
         if alias in per:
             per["lpdt_qconv_bwd_data_f32"] = per.get("lpdt_qconv_bwd_data_f32", 0.0) + per.pop(alias)
+    if "lpdt_qconv_fwd_f32_absmax" in per:
+        per["lpdt_qconv_fwd_f32"] = per.get("lpdt_qconv_fwd_f32", 0.0) + per.pop("lpdt_qconv_fwd_f32_absmax")
     conv_names = ("lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", wg_name)
     conv_ms = sum(per.get(n, 0.0) for n in conv_names)
     work = {}
     for ts in steps:
         for name, macs in ts.conv_work():
-            name = {"lpdt_qconv_fwd_f32_add": "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32_packed": "lpdt_qconv_bwd_data_f32"}.get(name, name)
+            name = {"lpdt_qconv_fwd_f32_add": "lpdt_qconv_fwd_f32", "lpdt_qconv_fwd_f32_absmax": "lpdt_qconv_fwd_f32",
+                    "lpdt_qconv_bwd_data_f32_packed": "lpdt_qconv_bwd_data_f32",
+                    "lpdt_qconv_bwd_data_f32_absmax": "lpdt_qconv_bwd_data_f32"}.get(name, name)
             work[name] = work.get(name, 0) + 2 * macs
     kind_tops = {n: (work.get(n, 0) / (per[n] * 1e-3) / 1e12 if per.get(n) else None) for n in conv_names}
     achieved = sum(work.values()) / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else 0.0

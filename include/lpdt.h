@@ -162,6 +162,21 @@ int lpdt_qconv_bwd_data_f32_packed(const lpdt_conv_desc *d, const int8_t *gq, co
                                    const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes,
                                    void *stream);
 
+/* The two products with max |result| as a by-product: absmax_out (device fp32 scalar) = max over all elements of |y|
+ * resp. |dx| as stored (after the addition when accumulate != 0), exactly, for an lpdt_quantize_with_absmax that follows
+ * with no normalisation layer in between (linear layers, Table "hardware_training" row Linear; the quantizer's first
+ * pass over the tensor then falls away).  Where the matrix-core kernel writes the result itself the maximum is taken in
+ * its epilogue; elsewhere (first layer, split reductions, misaligned operands) in a pass over the result.  y, dx and
+ * the operands as in lpdt_qconv_fwd_f32 / lpdt_qconv_bwd_data_f32; the backward call takes the filter either as wq or
+ * prepared (packed != NULL, see lpdt_qconv_bwd_data_pack_filter; wq may then be NULL). */
+size_t lpdt_qconv_fwd_f32_absmax_workspace_bytes(const lpdt_conv_desc *d);
+size_t lpdt_qconv_bwd_data_f32_absmax_workspace_bytes(const lpdt_conv_desc *d);
+int lpdt_qconv_fwd_f32_absmax(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx,
+                              const float *sw, float *y, float *absmax_out, void *ws, size_t ws_bytes, void *stream);
+int lpdt_qconv_bwd_data_f32_absmax(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, const void *packed,
+                                   const float *sg, const float *sw, float *dx, int accumulate, float *absmax_out,
+                                   void *ws, size_t ws_bytes, void *stream);
+
 /* The forward product added to what y already holds (Table "hardware_training", row Skip Connections, done in
  * the convolution's epilogue): y += (sx*sw) * sum, the bits of lpdt_qconv_fwd_f32 into a temporary followed by
  * lpdt_add(y, temporary).  y fp32 [N,P,Q,K], 16-byte aligned, read and overwritten.  A misaligned operand

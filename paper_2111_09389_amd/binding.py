@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -36,6 +36,8 @@ EXPORTS = [
     "lpdt_range_evonorm_maxpool_fwd_workspace_bytes", "lpdt_range_evonorm_maxpool_bwd_workspace_bytes",
     "lpdt_range_evonorm_maxpool_fwd", "lpdt_range_evonorm_maxpool_bwd",
     "lpdt_qconv_bwd_data_packed_filter_bytes", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_f32_packed",
+    "lpdt_qconv_fwd_f32_absmax_workspace_bytes", "lpdt_qconv_bwd_data_f32_absmax_workspace_bytes",
+    "lpdt_qconv_fwd_f32_absmax", "lpdt_qconv_bwd_data_f32_absmax",
     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
     "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
@@ -94,7 +96,8 @@ def lib():
         for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
                      "lpdt_qconv_bwd_weight_workspace_bytes", "lpdt_qconv_fwd_f32_workspace_bytes",
                      "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
-                     "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_fwd_f32_add_workspace_bytes"):
+                     "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_fwd_f32_add_workspace_bytes",
+                     "lpdt_qconv_fwd_f32_absmax_workspace_bytes", "lpdt_qconv_bwd_data_f32_absmax_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
                      "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
@@ -259,6 +262,30 @@ def qconv_bwd_data_f32(d, gq, wq, sg, sw, dx=None, accumulate=False, ws=None):
     _check(lib().lpdt_qconv_bwd_data_f32(ctypes.byref(d), _ptr(gq), _ptr(wq), _ptr(sg), _ptr(sw), _ptr(dx), int(bool(accumulate)),
                                          _ptr(buf), _sz(nb), _stream()))
     return dx
+
+
+def qconv_fwd_f32_absmax(d, xq, wq, sx, sw, y=None, ws=None):
+    """-> (y, absmax): lpdt_qconv_fwd_f32 plus max|y| as a device scalar."""
+    _dev(xq, torch.int8, "qconv_fwd_f32_absmax xq"); _dev(wq, torch.int8, "qconv_fwd_f32_absmax wq")
+    assert tuple(xq.shape) == (d.N, d.H, d.W, d.C) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    y = torch.empty((d.N, d.P, d.Q, d.K), dtype=torch.float32, device=xq.device) if y is None else y
+    absmax = torch.empty(1, dtype=torch.float32, device=xq.device)
+    buf, nb = _ws(ws, lib().lpdt_qconv_fwd_f32_absmax_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_fwd_f32_absmax(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(sx), _ptr(sw), _ptr(y), _ptr(absmax), _ptr(buf),
+                                           _sz(nb), _stream()))
+    return y, absmax
+
+
+def qconv_bwd_data_f32_absmax(d, gq, wq, sg, sw, packed=None, dx=None, accumulate=False, ws=None):
+    """-> (dx, absmax): lpdt_qconv_bwd_data_f32 (filter as wq or packed) plus max|dx| as a device scalar."""
+    _dev(gq, torch.int8, "qconv_bwd_data_f32_absmax gq")
+    assert tuple(gq.shape) == (d.N, d.P, d.Q, d.K)
+    dx = torch.empty((d.N, d.H, d.W, d.C), dtype=torch.float32, device=gq.device) if dx is None else dx
+    absmax = torch.empty(1, dtype=torch.float32, device=gq.device)
+    buf, nb = _ws(ws, lib().lpdt_qconv_bwd_data_f32_absmax_workspace_bytes(ctypes.byref(d)))
+    _check(lib().lpdt_qconv_bwd_data_f32_absmax(ctypes.byref(d), _ptr(gq), _ptr(wq), _ptr(packed), _ptr(sg), _ptr(sw), _ptr(dx),
+                                                int(bool(accumulate)), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
+    return dx, absmax
 
 
 def qconv_bwd_data_pack_filter(d, wq):

@@ -284,8 +284,11 @@ static bool fwd_fusable(const lpdt_conv_desc *d, int P, int Q) {
     return fwd_vec(d, P, Q) && !igemm_fwd_is_split(d, P, Q);
 }
 
+// pabs: room for the abs-max partials of the fused implicit-GEMM epilogue; returns how many were written (0: none, the
+// caller takes the abs-max of `out` in a pass of its own)
 static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq, const int8_t *wq, void *out, int out_mode,
-                         const float *sA, const float *sB, void *ws, hipStream_t st) {
+                         const float *sA, const float *sB, void *ws, hipStream_t st, float *pabs = nullptr) {
+    int nparts = 0;
     const size_t out_len = (size_t)d->N * P * Q * d->K;
     // out_mode 2 (fp32, added to what is in `out`) is fused by the implicit-GEMM kernel only; the first-layer kernel stages
     const bool fused = fwd_fusable(d, P, Q) && aligned(xq, 16) && aligned(wq, 16) && !(out_mode == 2 && narrow_conv_supported(d, P, Q));
@@ -296,12 +299,13 @@ static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq
     if (narrow_conv_supported(d, P, Q)) {
         launch_narrow_fwd(d, P, Q, xq, wq, acc, mode, sA, sB, ws, st);
     } else if (fwd_vec(d, P, Q) && aligned(xq, 16) && aligned(wq, 16)) {
-        launch_igemm_fwd(d, P, Q, xq, wq, acc, mode, sA, sB, st);
+        if (pabs && mode != 0) nparts = igemm_fwd_absmax_parts(d, P, Q);
+        launch_igemm_fwd(d, P, Q, xq, wq, acc, mode, sA, sB, st, nparts > 0 ? pabs : nullptr);
     } else {
         hipLaunchKernelGGL(conv_fwd_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, xq, wq, acc, *d, P, Q);
     }
     if (stage) launch_dequant(acc, out_len, sA, sB, static_cast<float *>(out), out_mode == 2, st);
-    return LPDT_OK;
+    return nparts;
 }
 
 extern "C" size_t lpdt_qconv_fwd_f32_workspace_bytes(const lpdt_conv_desc *d) {
@@ -375,7 +379,9 @@ static bool bwd_data_fusable(const lpdt_conv_desc *d, int P, int Q) {
 
 // packed: the filter's transposed panels made earlier by lpdt_qconv_bwd_data_pack_filter (then wq is not read), else NULL
 static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *gq, const int8_t *wq, const void *packed,
-                              void *out, int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st) {
+                              void *out, int out_mode, const float *sA, const float *sB, void *ws, hipStream_t st,
+                              float *pabs = nullptr) {
+    int nparts = 0;
     const size_t out_len = (size_t)d->N * d->H * d->W * d->C;
     const bool al = aligned(gq, 16) && (packed || aligned(wq, 16));   // the matrix-core path loads both operands 16 bytes at a time
     const bool stage = out_mode != 0 && !(bwd_data_fusable(d, P, Q) && al);
@@ -383,12 +389,13 @@ static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_
     const int mode = stage ? 0 : out_mode;
     if (bwd_data_vec(d, P, Q) && al) {
         if (!packed) launch_igemm_pack_bwd_filter(d, P, Q, wq, ws, st);
-        launch_igemm_bwd_data(d, P, Q, gq, packed ? packed : ws, acc, mode, sA, sB, st);
+        if (pabs && mode != 0) nparts = igemm_bwd_data_absmax_parts(d, P, Q);
+        launch_igemm_bwd_data(d, P, Q, gq, packed ? packed : ws, acc, mode, sA, sB, st, nparts > 0 ? pabs : nullptr);
     } else {
         hipLaunchKernelGGL(conv_bwd_data_plain_kernel, dim3(blocks_for(out_len)), dim3(kCThreads), 0, st, gq, wq, acc, *d, P, Q);
     }
     if (stage) launch_dequant(acc, out_len, sA, sB, static_cast<float *>(out), out_mode == 2, st);
-    return LPDT_OK;
+    return nparts;
 }
 
 extern "C" size_t lpdt_qconv_bwd_data_f32_workspace_bytes(const lpdt_conv_desc *d) {
@@ -459,6 +466,70 @@ extern "C" int lpdt_qconv_bwd_data_f32_packed(const lpdt_conv_desc *d, const int
     if (rc) return rc;
     conv_bwd_data_impl(d, P, Q, gq, nullptr, packed, dx, accumulate ? 2 : 1, sg, sw, ws, as_stream(stream));
     return launch_status("lpdt_qconv_bwd_data_f32_packed");
+}
+
+// ---- products that also hand over max |result| (for a quantizer that follows with no normalisation layer between) ----
+static size_t absmax_tail_bytes(int parts) {
+    const int scratch = absmax_scratch_floats();
+    return round_up((size_t)(parts > scratch ? parts : scratch) * sizeof(float), 256);
+}
+static size_t fwd_f32_any_ws(const lpdt_conv_desc *d, int P, int Q) {   // room lpdt_qconv_fwd_f32 may need, aligned operands or not
+    return round_up(fwd_base_ws(d), 256) + round_up((size_t)d->N * P * Q * d->K * 4, 256);
+}
+static size_t bwd_data_f32_any_ws(const lpdt_conv_desc *d) {
+    return bwd_data_base_ws(d) + round_up((size_t)d->N * d->H * d->W * d->C * 4, 256);
+}
+
+extern "C" size_t lpdt_qconv_fwd_f32_absmax_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
+    const int parts = fwd_vec(d, P, Q) ? igemm_fwd_absmax_parts(d, P, Q) : 0;
+    return fwd_f32_any_ws(d, P, Q) + absmax_tail_bytes(parts);
+}
+
+extern "C" int lpdt_qconv_fwd_f32_absmax(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx,
+                                         const float *sw, float *y, float *absmax_out, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(xq && wq && y && sx && sw && absmax_out, LPDT_EINVAL, "qconv_fwd_f32_absmax: NULL argument");
+    LPDT_REQUIRE(aligned(y, 16) && aligned(absmax_out, 4), LPDT_EINVAL, "qconv_fwd_f32_absmax: y must be 16-byte aligned");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_fwd_f32_absmax_workspace_bytes(d));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    float *tail = reinterpret_cast<float *>(static_cast<char *>(ws) + fwd_f32_any_ws(d, P, Q));
+    const int nparts = conv_fwd_impl(d, P, Q, xq, wq, y, 1, sx, sw, ws, st, tail);
+    if (nparts > 0) launch_absmax_fold(tail, nparts, absmax_out, st);
+    else launch_absmax(y, (size_t)d->N * P * Q * d->K, tail, absmax_out, st);
+    return launch_status("lpdt_qconv_fwd_f32_absmax");
+}
+
+extern "C" size_t lpdt_qconv_bwd_data_f32_absmax_workspace_bytes(const lpdt_conv_desc *d) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
+    const int parts = bwd_data_vec(d, P, Q) ? igemm_bwd_data_absmax_parts(d, P, Q) : 0;
+    return bwd_data_f32_any_ws(d) + absmax_tail_bytes(parts);
+}
+
+extern "C" int lpdt_qconv_bwd_data_f32_absmax(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *wq, const void *packed,
+                                              const float *sg, const float *sw, float *dx, int accumulate, float *absmax_out,
+                                              void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(gq && (wq || packed) && dx && sg && sw && absmax_out, LPDT_EINVAL, "qconv_bwd_data_f32_absmax: NULL argument");
+    LPDT_REQUIRE(aligned(dx, 16) && aligned(absmax_out, 4), LPDT_EINVAL, "qconv_bwd_data_f32_absmax: dx must be 16-byte aligned");
+    if (packed)
+        LPDT_REQUIRE(bwd_data_vec(d, P, Q) && aligned(packed, 16) && aligned(gq, 16), LPDT_EINVAL,
+                     "qconv_bwd_data_f32_absmax: a packed filter needs a shape that has one and 16-byte aligned gq, packed");
+    rc = check_ws(ws, ws_bytes, lpdt_qconv_bwd_data_f32_absmax_workspace_bytes(d));
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    float *tail = reinterpret_cast<float *>(static_cast<char *>(ws) + bwd_data_f32_any_ws(d));
+    const int nparts = conv_bwd_data_impl(d, P, Q, gq, packed ? nullptr : wq, packed, dx, accumulate ? 2 : 1, sg, sw, ws, st, tail);
+    if (nparts > 0) launch_absmax_fold(tail, nparts, absmax_out, st);
+    else launch_absmax(dx, (size_t)d->N * d->H * d->W * d->C, tail, absmax_out, st);
+    return launch_status("lpdt_qconv_bwd_data_f32_absmax");
 }
 
 // Weight gradient.  Which kernel runs: first-layer path, rectangle-stepped kernel (partial tiles + reduction), the

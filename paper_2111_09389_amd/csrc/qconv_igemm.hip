@@ -66,6 +66,7 @@ struct IgemmParams {
     int istep, ostep, dsign;
     int tiles_n, atomic_out, vec_out;
     int kg;                 // granules per K-step
+    float *pabs;            // ABSMAX kernels: max |out| per wave, [grid.y][grid.x][4]
     int nclasses;
     IgemmClass cls[kMaxClasses];
 };
@@ -86,7 +87,9 @@ __device__ __forceinline__ int fast_div(int x, int d, unsigned mul) {
 // SPLIT: the reduction is shared between the blocks of grid.z, which add their int32 sums into a zeroed output; the pixels
 // are then the MFMA's row operand, so that a lane's atomics of one instruction fall on consecutive addresses.
 // KG = granules of a K-step (4 or 8): with 8 a row's fetch is one whole 128-byte cache line.
-template <int BM, int BN, int WM, int WN, int PF, bool SPLIT, int KG>
+// ABSMAX (fp32 output, no split): every wave also leaves the largest |value| it stored in p.pabs, for a quantizer that
+// follows without a normalisation layer in between.
+template <int BM, int BN, int WM, int WN, int PF, bool SPLIT, int KG, bool ABSMAX = false>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     constexpr int PAD = 256 / KG;                                  // the KG planes start 64/KG banks apart
     constexpr int PLANE_A = BM * 16 + PAD, PLANE_B = BN * 16 + PAD;
@@ -104,7 +107,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     const int tile = xcd * per + min(xcd, rem) + blockIdx.x / 8;
     const int tile_n = tile % p.tiles_n, tile_m = tile / p.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    if (m0 >= c.M) return;
+    if (m0 >= c.M) {
+        if (ABSMAX && threadIdx.x % 64 == 0) p.pabs[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 4 + threadIdx.x / 64] = 0.0f;
+        return;
+    }
     const int ks_begin = blockIdx.z * c.kps;
     const int ks_end = min(c.nk, ks_begin + c.kps);
     if (ks_begin >= ks_end && (blockIdx.z > 0)) return;
@@ -254,6 +260,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
     // Accumulator layout of the 32x32 MFMA: a lane holds column lane%32 (here: a pixel) and rows 8*(r/4) + 4*(lane/32) + r%4
     // (here: output channels), i.e. four runs of 4 consecutive channels.
     const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
+    float am = 0.0f;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int opix = rows[wm * (BM / WM) + 32 * i + lane % 32].z;
@@ -276,6 +283,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] = dequant_value(scale, s[e], v[e], add);
                         *fdst = v;
+                        if (ABSMAX) am = fmaxf(fmaxf(am, fmaxf(fabsf(v[0]), fabsf(v[1]))), fmaxf(fabsf(v[2]), fabsf(v[3])));
                     } else *reinterpret_cast<v4i *>(dst) = s;
                 } else {
 #pragma unroll
@@ -283,12 +291,18 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const IgemmParams p) {
                         if (col + e >= p.Cout) break;
                         if (p.out_mode) {
                             float *fdst = reinterpret_cast<float *>(dst + e);
-                            *fdst = dequant_value(scale, s[e], p.out_mode == 2 ? *fdst : 0.f, p.out_mode == 2);
+                            const float v = dequant_value(scale, s[e], p.out_mode == 2 ? *fdst : 0.f, p.out_mode == 2);
+                            *fdst = v;
+                            if (ABSMAX) am = fmaxf(am, fabsf(v));
                         } else dst[e] = s[e];
                     }
                 }
             }
         }
+    }
+    if (ABSMAX) {
+        am = wave_max(am);
+        if (lane == 0) p.pabs[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = am;
     }
 }
 
@@ -400,6 +414,7 @@ void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, p);
     };
     if (p.atomic_out) go(igemm_kernel<BM, BN, WM, WN, PF, true, KG>);
+    else if (p.pabs) go(igemm_kernel<BM, BN, WM, WN, PF, false, KG, true>);
     else go(igemm_kernel<BM, BN, WM, WN, PF, false, KG>);
 }
 
@@ -504,6 +519,23 @@ bool igemm_bwd_data_supported(const lpdt_conv_desc *d, int P, int Q) {
     return table_fits(p);
 }
 
+// Waves of the launch (= abs-max partials an ABSMAX kernel writes); 0 when the reduction is split
+static int plan_waves(IgemmParams &p) {
+    const dim3 grid = finish_plan(&p, pick_tile(p), true);
+    return p.atomic_out ? 0 : (int)(grid.x * grid.y * 4);
+}
+int igemm_fwd_absmax_parts(const lpdt_conv_desc *d, int P, int Q) {
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    return plan_waves(p);
+}
+int igemm_bwd_data_absmax_parts(const lpdt_conv_desc *d, int P, int Q) {
+    IgemmParams p;
+    PackParams pk;
+    bwd_params(d, P, Q, &p, &pk);
+    return plan_waves(p);
+}
+
 bool igemm_fwd_is_split(const lpdt_conv_desc *d, int P, int Q) {
     IgemmParams p;
     fwd_params(d, P, Q, &p);
@@ -520,10 +552,10 @@ bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q) {
 }
 
 void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, void *out, int out_mode,
-                      const float *sA, const float *sB, hipStream_t st) {
+                      const float *sA, const float *sB, hipStream_t st, float *pabs) {
     IgemmParams p;
     fwd_params(d, P, Q, &p);
-    p.in = x; p.wt = w; p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
+    p.in = x; p.wt = w; p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB; p.pabs = pabs;
     p.vec_out = d->K % 4 == 0 && aligned(out, 16);
     run(p, (size_t)d->N * P * Q * d->K, st);
 }
@@ -541,11 +573,11 @@ void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const i
 }
 
 void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const void *panel, void *out, int out_mode,
-                           const float *sA, const float *sB, hipStream_t st) {
+                           const float *sA, const float *sB, hipStream_t st, float *pabs) {
     IgemmParams p;
     PackParams pk;
     bwd_params(d, P, Q, &p, &pk);
-    p.in = g; p.wt = static_cast<const int8_t *>(panel); p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
+    p.in = g; p.wt = static_cast<const int8_t *>(panel); p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB; p.pabs = pabs;
     p.vec_out = d->C % 4 == 0 && aligned(out, 16);
     run(p, (size_t)d->N * d->H * d->W * d->C, st);
 }

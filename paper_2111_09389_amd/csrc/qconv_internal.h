@@ -22,14 +22,18 @@ bool igemm_bwd_data_supported(const lpdt_conv_desc *d, int P, int Q);
 bool igemm_fwd_is_split(const lpdt_conv_desc *d, int P, int Q);
 bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q);
 // out_mode 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32 added to `out`.  x, w, g 16-byte aligned.
+// pabs (fp32 output, reduction not split): every wave writes the largest |value| it stored, `*_absmax_parts` floats in all
+// (0: the reduction is split, no such output).
+int igemm_fwd_absmax_parts(const lpdt_conv_desc *d, int P, int Q);
+int igemm_bwd_data_absmax_parts(const lpdt_conv_desc *d, int P, int Q);
 void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, void *out, int out_mode,
-                      const float *sA, const float *sB, hipStream_t st);
+                      const float *sA, const float *sB, hipStream_t st, float *pabs = nullptr);
 // Backward-data reads the filter as transposed panels (one per stride residue class), K*R*S*C bytes in all, 16-byte
 // aligned: made by the first call, consumed by the second (g and panel 16-byte aligned).
 size_t igemm_bwd_filter_panel_bytes(const lpdt_conv_desc *d);
 void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const int8_t *w, void *panel, hipStream_t st);
 void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const void *panel, void *out, int out_mode,
-                           const float *sA, const float *sB, hipStream_t st);
+                           const float *sA, const float *sB, hipStream_t st, float *pabs = nullptr);
 
 // Weight gradient, rectangle-stepped kernel with partial tiles and a fixed-order reduction.
 struct WgradRectPlan {
@@ -46,6 +50,11 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
 // out[i] = sum over `splits` copies partial[z][i] (out_len a multiple of 4), as int32 or as fp32 times sA*sB
 void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
                          const float *sB, hipStream_t st);
+
+// *out = max |x[i]| (x 16-byte aligned; scratch: absmax_scratch_floats() floats), and the fold of n ready partials alone
+int absmax_scratch_floats();
+void launch_absmax(const float *x, size_t len, float *scratch, float *out, hipStream_t st);
+void launch_absmax_fold(const float *parts, int n, float *out, hipStream_t st);
 
 // y = (sA*sB) * acc (+ y when accumulate): the kernel behind lpdt_dequantize
 void launch_dequant(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y, bool accumulate, hipStream_t st);

@@ -228,6 +228,34 @@ static int check_quant_args(const float *x, size_t len, int rounding, const int8
     return LPDT_OK;
 }
 
+// out = max of n non-negative partials (one block)
+__global__ __launch_bounds__(1024) void absmax_fold_kernel(const float *__restrict__ parts, int n, float *__restrict__ out) {
+    __shared__ float lds[1024 / kWave];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, parts[i]);
+    m = wave_max(m);
+    if (threadIdx.x % kWave == 0) lds[threadIdx.x / kWave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = lds[0];
+        for (int w = 1; w < 1024 / kWave; ++w) r = fmaxf(r, lds[w]);
+        *out = r;
+    }
+}
+
+void launch_absmax_fold(const float *parts, int n, float *out, hipStream_t st) {
+    hipLaunchKernelGGL(absmax_fold_kernel, dim3(1), dim3(1024), 0, st, parts, n, out);
+}
+
+int absmax_scratch_floats() { return kMaxParts; }
+
+void launch_absmax(const float *x, size_t len, float *scratch, float *out, hipStream_t st) {
+    int g1 = grid_for(len, 16);
+    if (g1 > kMaxParts) g1 = kMaxParts;
+    hipLaunchKernelGGL(absmax_kernel, dim3(g1), dim3(kQThreads), 0, st, x, len, scratch);
+    launch_absmax_fold(scratch, g1, out, st);
+}
+
 void launch_dequant(const int32_t *acc, size_t len, const float *sA, const float *sB, float *y, bool accumulate, hipStream_t st) {
     const int g = grid_for(len, 16);
     if (accumulate) hipLaunchKernelGGL(dequant_kernel<true>, dim3(g), dim3(kQThreads), 0, st, acc, len, sA, sB, y);

@@ -40,12 +40,13 @@ class TrainStep:
     (then `upstream` must be the gradient of the last tensor)."""
 
     def __init__(self, net, batch, params, grads, x, labels=None, upstream=None, lr=0.1, seed=0, eps=1e-5,
-                 wgrad_16bit=False, overlap_wgrad=True, fuse_ren_quant=True, prepack_filters=True):
+                 wgrad_16bit=False, overlap_wgrad=True, fuse_ren_quant=True, prepack_filters=True, conv_absmax=True):
         self.L = lib()
         self.overlap_wgrad = overlap_wgrad
         self.fuse_ren_quant = fuse_ren_quant   # Range-EvoNorm layers that feed only convolutions emit int8 codes directly
         # backward-data's transposed filters are made once per step, on the second stream beside the forward pass
         self.prepack_filters = prepack_filters and overlap_wgrad
+        self.conv_absmax = conv_absmax   # products followed directly by a quantizer hand max|result| over
         self.net, self.N, self.lr, self.seed, self.eps = net, batch, lr, seed, eps
         # gradient bifurcation as the paper states it: weight gradients from a bfloat16 copy of the layer gradient
         # (the 8-bit codes still feed backward-data), for every layer but the one that reads the image; default: both
@@ -220,6 +221,12 @@ class TrainStep:
                     continue
                 y = self._f32(N, *net.shapes[out])
                 self.act[out] = y
+                if self.conv_absmax and out in conv_only:         # quantized next, with no normalisation layer between: the product hands max|y| over
+                    self.absmax[out] = self._f32(1)
+                    self._need_ws(L.lpdt_qconv_fwd_f32_absmax_workspace_bytes(ctypes.byref(d)))
+                    self._emit(L.lpdt_qconv_fwd_f32_absmax, [ctypes.byref(d), _p(self.xq[inp]), _p(self.wq[out]), _p(self.sx[inp]),
+                                                             _p(self.sw[out]), _p(y), _p(self.absmax[out]), "WS", "WSB"])
+                    continue
                 self._need_ws(L.lpdt_qconv_fwd_f32_workspace_bytes(ctypes.byref(d)))
                 self._emit(L.lpdt_qconv_fwd_f32, [ctypes.byref(d), _p(self.xq[inp]), _p(self.wq[out]), _p(self.sx[inp]),
                                                   _p(self.sw[out]), _p(y), "WS", "WSB"])
@@ -318,6 +325,7 @@ class TrainStep:
         pending = {op[1] for op in net.ops if op[0] != "loss"}      # tensors whose producer's backward has not run
         conv_index = 0
         deferred = {}                    # tensor -> backward-data calls waiting for another writer of its gradient
+        producer_kind = {op[1]: op[0] for op in net.ops if op[0] != "loss"}
         if self.wpacked:
             self.calls.append((None, [], None, False))   # the main stream waits here for the second stream's filter copies
         for op in reversed(net.ops):
@@ -342,6 +350,14 @@ class TrainStep:
                     def bwd_data(out=out, d=d, gq=gq, sg=sg, inp=inp):
                         buf, accumulate = self._grad_target(inp, pending)
                         self.gabsmax.pop(inp, None)
+                        if self.conv_absmax and producer_kind.get(inp) == "conv" and self.consumers.get(inp, 0) == 1:
+                            # the whole gradient of a convolution's output, quantized next: the product hands max|dx| over
+                            self.gabsmax[inp] = self._f32(1)
+                            self._need_ws(L.lpdt_qconv_bwd_data_f32_absmax_workspace_bytes(ctypes.byref(d)))
+                            self._emit(L.lpdt_qconv_bwd_data_f32_absmax,
+                                       [ctypes.byref(d), _p(gq), _p(self.wq[out]), _p(self.wpacked.get(out)), _p(sg), _p(self.sw[out]),
+                                        _p(buf), accumulate, _p(self.gabsmax[inp]), "WS", "WSB"])
+                            return
                         self._need_ws(L.lpdt_qconv_bwd_data_f32_workspace_bytes(ctypes.byref(d)))
                         if out in self.wpacked:
                             self._emit(L.lpdt_qconv_bwd_data_f32_packed, [ctypes.byref(d), _p(gq), _p(self.wpacked[out]), _p(sg),
@@ -502,8 +518,9 @@ class TrainStep:
         for fn, args, _, _ in self.calls:
             if fn is None:
                 continue
-            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_fwd_f32_add", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_data_f32_packed",
-                               "lpdt_qconv_bwd_weight_f32", "lpdt_qconv_bwd_weight_bf16"):
+            if fn.__name__ in ("lpdt_qconv_fwd_f32", "lpdt_qconv_fwd_f32_add", "lpdt_qconv_fwd_f32_absmax", "lpdt_qconv_bwd_data_f32",
+                               "lpdt_qconv_bwd_data_f32_packed", "lpdt_qconv_bwd_data_f32_absmax", "lpdt_qconv_bwd_weight_f32",
+                               "lpdt_qconv_bwd_weight_bf16"):
                 d = args[0]._obj
                 out.append((fn.__name__, d.N * d.P * d.Q * d.K * d.C * d.R * d.S))
         return out

@@ -162,3 +162,25 @@ def test_prepacked_filter_is_refused_where_backward_data_has_no_packed_form():
     ld = lpdt.ConvDesc.make(1, 20, 6, 6, 24, 3, 3, 1, 1)     # channel counts that are not multiples of 16
     w = torch.zeros((24, 3, 3, 20), dtype=torch.int8, device="cuda")
     assert lpdt.qconv_bwd_data_pack_filter(ld, w) is None
+
+
+@pytest.mark.parametrize("shp", [CASES[1], CASES[2], CASES[3], CASES[4], CASES[9], CASES[12], CASES[14], CASES[15]])
+def test_products_with_absmax_output(shp):
+    """lpdt_qconv_fwd_f32_absmax / lpdt_qconv_bwd_data_f32_absmax: the results of the plain calls, bit for bit, and the exact
+    largest magnitude of what was stored (epilogue path, split reductions, first layer, odd channel counts)."""
+    x, w, g = _data(shp, 950, "gauss")
+    ld = lpdt.ConvDesc.make(*shp)
+    s1 = torch.tensor([0.027], dtype=torch.float32, device="cuda")
+    s2 = torch.tensor([0.0031], dtype=torch.float32, device="cuda")
+    ref = lpdt.qconv_fwd_f32(ld, dev(x), dev(w), s1, s2)
+    y, am = lpdt.qconv_fwd_f32_absmax(ld, dev(x), dev(w), s1, s2)
+    assert torch.equal(y, ref) and float(am[0]) == float(ref.abs().max())
+    ref = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), s1, s2)
+    dx, am = lpdt.qconv_bwd_data_f32_absmax(ld, dev(g), dev(w), s1, s2)
+    assert torch.equal(dx, ref) and float(am[0]) == float(ref.abs().max())
+    base = dev(wl.upstream_grad(951, tuple(ref.shape)))
+    ref2 = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), s1, s2, dx=base.clone(), accumulate=True)
+    packed = lpdt.qconv_bwd_data_pack_filter(ld, dev(w))
+    dx2, am2 = lpdt.qconv_bwd_data_f32_absmax(ld, dev(g), None if packed is not None else dev(w), s1, s2, packed=packed, dx=base.clone(),
+                                              accumulate=True)
+    assert torch.equal(dx2, ref2) and float(am2[0]) == float(ref2.abs().max())

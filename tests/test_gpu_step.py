@@ -331,3 +331,27 @@ def test_driver_prepacked_filters_change_no_bit(orc):
         torch.cuda.synchronize()
         out.append((g.clone(), p.clone(), ts.loss.clone()))
     assert all(torch.equal(a, b) for a, b in zip(*out))
+
+
+def test_driver_linear_layers_with_absmax_products_change_no_bit():
+    """Linear layers with nothing between them (transformer-shaped net): the products that hand max|result| to the next
+    quantizer (default) against products followed by the two-pass quantizer: identical gradients and parameters."""
+    from paper_2111_09389_amd.step import TrainStep
+    net = nets.transformer_ffn()
+    N = 200                      # tokens: a ragged tile count
+    params = nets.init_params(net, wl.BASE_SEED + 52)
+    flat = np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32)
+    H, W, C = net.in_shape
+    x = dev(wl.images(wl.BASE_SEED + 53, N, H, W, C))
+    last = net.ops[-1][1]
+    up = dev(wl.upstream_grad(wl.BASE_SEED + 54, (N,) + tuple(net.shapes[last])))
+    out = []
+    for fuse in (True, False):
+        p, g = dev(flat), torch.zeros(flat.size, dtype=torch.float32, device="cuda")
+        ts = TrainStep(net, N, p, g, x, None, up, lr=0.05, seed=wl.PHILOX_SEED, conv_absmax=fuse)
+        names = [c[0].__name__ for c in ts.calls if c[0] is not None]
+        assert ("lpdt_qconv_fwd_f32_absmax" in names) == fuse and ("lpdt_qconv_bwd_data_f32_absmax" in names) == fuse
+        ts.run(1)
+        torch.cuda.synchronize()
+        out.append((g.clone(), p.clone()))
+    assert all(torch.equal(a, b) for a, b in zip(*out))
