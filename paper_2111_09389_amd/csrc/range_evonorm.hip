@@ -379,7 +379,12 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
 }
 
 // ---- forward followed by a max-pool --------------------------------------------
-struct PoolGeom { int W, P, Q, k, st, pd; };   // input width, pooled map, window, stride, padding
+struct PoolGeom {   // input width, pooled map, window, stride, padding
+    int W, P, Q, k, st, pd;
+    unsigned mul_w, mul_q, mul_st;   // multipliers for x/W, x/Q, x/st by a high multiply (0: divide), see pool_geom()
+};
+// x / d for 0 <= x below the bound its multiplier was made for
+__device__ __forceinline__ int pool_div(int x, int d, unsigned mul) { return mul ? (int)__umulhi((unsigned)x, mul) : x / d; }
 // z = maxpool(y) and the winners' positions, with y evaluated at the window's pixels instead of being stored: the
 // arithmetic of the plain forward (ren_y) and the selection rule of the max-pool kernel (first in window scan order on
 // ties, padding never wins), so the results are the two calls' bit for bit.  g describes the POOLED map (HW = P*Q).
@@ -431,7 +436,7 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
     int4 *iv = reinterpret_cast<int4 *>(idx + (size_t)n * g.HW * g.C);
     float am = 0.0f;
     for (int pp = p0 + pl; pp < p1 && active; pp += g.ppi) {
-        const int p = pp / pg.Q, q = pp - p * pg.Q;
+        const int p = pool_div(pp, pg.Q, pg.mul_q), q = pp - p * pg.Q;
         float best[4] = {0.f, 0.f, 0.f, 0.f};
         int bi[4] = {-1, -1, -1, -1};
         for (int i = 0; i < pg.k; ++i) {
@@ -467,9 +472,10 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
 // backward kernel (same order of additions), evaluated where it is consumed.  dz, idx: this sample's pooled maps.
 __device__ __forceinline__ float4 pooled_grad(const float4 *__restrict__ dz, const int4 *__restrict__ idx, int p, const PoolGeom &pg,
                                               int cq, int qd) {
-    const int h = p / pg.W, w = p - h * pg.W;
-    const int p_lo = max(0, (h + pg.pd - pg.k + pg.st) / pg.st), p_hi = min(pg.P - 1, (h + pg.pd) / pg.st);
-    const int q_lo = max(0, (w + pg.pd - pg.k + pg.st) / pg.st), q_hi = min(pg.Q - 1, (w + pg.pd) / pg.st);
+    // (a negative numerator means no window that far up or left: the first window is 0 either way)
+    const int h = pool_div(p, pg.W, pg.mul_w), w = p - h * pg.W;
+    const int p_lo = pool_div(max(0, h + pg.pd - pg.k + pg.st), pg.st, pg.mul_st), p_hi = min(pg.P - 1, pool_div(h + pg.pd, pg.st, pg.mul_st));
+    const int q_lo = pool_div(max(0, w + pg.pd - pg.k + pg.st), pg.st, pg.mul_st), q_hi = min(pg.Q - 1, pool_div(w + pg.pd, pg.st, pg.mul_st));
     int4 id[4];
     float4 gq[4];
     size_t at[4];
@@ -726,6 +732,20 @@ static int check_ren(const void *x, int N, int H, int W, int C, int groups) {
     return LPDT_OK;
 }
 static bool ren_fast(int C) { return C % 4 == 0 && C / 4 <= kRThreads; }
+// floor(x / d) == umulhi(x, 2^32/d + 1) for every 0 <= x <= xmax when xmax * d < 2^32 (the error term x / 2^32 stays
+// below 1/d); 0 asks for a plain division
+static unsigned pool_mul(int d, long long xmax) {
+    if (d <= 1 || xmax * d >= (1ll << 32)) return 0u;
+    return (unsigned)((1ull << 32) / (unsigned)d + 1);
+}
+static PoolGeom pool_geom(int H, int W, int P, int Q, int k, int st, int pd) {
+    PoolGeom pg;
+    pg.W = W; pg.P = P; pg.Q = Q; pg.k = k; pg.st = st; pg.pd = pd;
+    pg.mul_w = pool_mul(W, (long long)H * W);
+    pg.mul_q = pool_mul(Q, (long long)P * Q);
+    pg.mul_st = pool_mul(st, (long long)(H > W ? H : W) + pd + st);
+    return pg;
+}
 static float ren_cm(int m) { return (float)(1.0 / std::sqrt(2.0 * std::log((double)m))); }
 constexpr int kGenericElems = 8192;
 constexpr int kGenericPix = 64;
@@ -870,7 +890,7 @@ extern "C" int lpdt_range_evonorm_maxpool_fwd(const float *x, int N, int H, int 
     hipLaunchKernelGGL(ren_stats_kernel<false>, dim3(g.chunks, N), dim3(g.block), smem, st, x, g, stats, absmax_out,
                        (const float *)nullptr, (float *)nullptr);
     hipLaunchKernelGGL(ren_pool_kernel, dim3(gp.chunks, N), dim3(gp.block), smem + groups * sizeof(float), st, x, gp, H, W,
-                       PoolGeom{W, P, Q, k, st_, pd}, v, gamma, beta, ren_cm(C / groups), eps, stats, g.chunks, z, idx, range_out,
+                       pool_geom(H, W, P, Q, k, st_, pd), v, gamma, beta, ren_cm(C / groups), eps, stats, g.chunks, z, idx, range_out,
                        argmax_out, argmin_out, absmax_out);
     return launch_status("lpdt_range_evonorm_maxpool_fwd");
 }
@@ -902,7 +922,7 @@ extern "C" int lpdt_range_evonorm_maxpool_bwd(const float *dz, const int32_t *id
     const RenGeom g = ren_geom(N, H, W, C, groups, kBwdMinPix, block_cap(N, H, W, C, kBwdElems));
     hipLaunchKernelGGL(ren_bwd_main_kernel<true>, dim3(g.chunks, N), dim3(g.block), (size_t)16 * g.threads * sizeof(float), st,
                        (const float *)nullptr, x, g, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out, dz, idx,
-                       PoolGeom{W, P, Q, k, st_, pd});
+                       pool_geom(H, W, P, Q, k, st_, pd));
     hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, g.chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_maxpool_bwd");
