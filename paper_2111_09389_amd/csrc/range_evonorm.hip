@@ -542,17 +542,19 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
     float4 *ov = reinterpret_cast<float4 *>(dx + base);
     float am = 0.0f;
     const bool active = (int)threadIdx.x < g.threads;
-    for (int pb = p0 + pl; pb < p1 && active; pb += kRU * g.ppi) {
-        float4 a4[kRU], d4[kRU];
+    // pixels in flight per thread: the pooled variant holds 4 winner quads and up to 4 gradient quads per pixel as well
+    constexpr int RU = kPooled ? 2 : kRU;
+    for (int pb = p0 + pl; pb < p1 && active; pb += RU * g.ppi) {
+        float4 a4[RU], d4[RU];
 #pragma unroll
-        for (int k = 0; k < kRU; ++k) {
+        for (int k = 0; k < RU; ++k) {
             const int p = pb + k * g.ppi;
             a4[k] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
             if (kPooled) d4[k] = p < p1 ? pooled_grad(dz4, idx4, p, pg, g.cq, qd) : make_float4(0.f, 0.f, 0.f, 0.f);
             else d4[k] = p < p1 ? dv4[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int k = 0; k < kRU; ++k) {
+        for (int k = 0; k < RU; ++k) {
             const int p = pb + k * g.ppi;
             if (p >= p1) break;
             const float xe[4] = {a4[k].x, a4[k].y, a4[k].z, a4[k].w};
