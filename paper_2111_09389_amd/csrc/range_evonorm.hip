@@ -439,19 +439,40 @@ __global__ __launch_bounds__(kRThreads) void ren_pool_kernel(const float *__rest
         const int p = pool_div(pp, pg.Q, pg.mul_q), q = pp - p * pg.Q;
         float best[4] = {0.f, 0.f, 0.f, 0.f};
         int bi[4] = {-1, -1, -1, -1};
-        for (int i = 0; i < pg.k; ++i) {
-            const int h = p * pg.st + i - pg.pd;
-            if (h < 0 || h >= H) continue;
-#pragma unroll 3
-            for (int j = 0; j < pg.k; ++j) {
-                const int w = q * pg.st + j - pg.pd;
-                if (w < 0 || w >= W) continue;
-                const float4 t = xv[(size_t)(h * W + w) * g.cq + qd];
-                const float xe[4] = {t.x, t.y, t.z, t.w};
+        auto take = [&](const float4 &t, int pos) {   // window scan order: a later pixel wins only if strictly larger
+            const float xe[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float y = ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]);
-                    if (bi[e] < 0 || y > best[e]) { best[e] = y; bi[e] = h * W + w; }
+            for (int e = 0; e < 4; ++e) {
+                const float y = ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]);
+                if (bi[e] < 0 || y > best[e]) { best[e] = y; bi[e] = pos; }
+            }
+        };
+        if (pg.k <= 3) {
+            // windows of up to 3 x 3: all loads of the window go out together (a pixel outside the window or the map
+            // is fetched from a clamped position and skipped)
+            float4 t[9];
+            int pos[9];
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    const int h = p * pg.st + i - pg.pd, w = q * pg.st + j - pg.pd;
+                    const bool ok = i < pg.k && j < pg.k && h >= 0 && h < H && w >= 0 && w < W;
+                    const int hc = min(max(h, 0), H - 1), wc = min(max(w, 0), W - 1);
+                    pos[i * 3 + j] = ok ? h * W + w : -1;
+                    t[i * 3 + j] = xv[(size_t)(hc * W + wc) * g.cq + qd];
+                }
+#pragma unroll
+            for (int s = 0; s < 9; ++s)
+                if (pos[s] >= 0) take(t[s], pos[s]);
+        } else {
+            for (int i = 0; i < pg.k; ++i) {
+                const int h = p * pg.st + i - pg.pd;
+                if (h < 0 || h >= H) continue;
+                for (int j = 0; j < pg.k; ++j) {
+                    const int w = q * pg.st + j - pg.pd;
+                    if (w < 0 || w >= W) continue;
+                    take(xv[(size_t)(h * W + w) * g.cq + qd], h * W + w);
                 }
             }
         }
