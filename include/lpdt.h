@@ -76,6 +76,17 @@ int lpdt_quantize(const float *x, size_t len, int rounding, uint64_t seed, uint6
 int lpdt_quantize_with_absmax(const float *x, size_t len, const float *absmax, int rounding,
                               uint64_t seed, uint64_t offset, int8_t *q, float *scale, void *stream);
 
+/* For callers that cannot allocate or hand over a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): lpdt_quantize with the abs-max partials
+ * kept in a fixed 4 KiB device array inside the library (one copy per GPU, held until the process
+ * ends) instead of a caller workspace.  Same codes and scale as lpdt_quantize, bit for bit.
+ * Calls no allocating routine.  len must not exceed lpdt_quantize_static_max_len() (2^30 elements),
+ * else LPDT_EUNSUPPORTED.  All calls on one GPU share the array: two calls that overlap in time
+ * on the same GPU (different streams or host threads) race; serialise them. */
+size_t lpdt_quantize_static_max_len(void);
+int lpdt_quantize_static(const float *x, size_t len, int rounding, uint64_t seed, uint64_t offset,
+                         int8_t *q, float *scale, void *stream);
+
 /* Many tensors in one call (the weights of all layers of a model, Section 3: every layer's
  * weights are quantized each iteration): slice s = x[seg_begin[s], seg_end[s]) gets its own
  * scale, scales[s], and its codes go to q[seg_begin[s], seg_end[s]) -- exactly what

@@ -6,7 +6,7 @@ import torch
 
 __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
-    "quantize", "quantize_with_absmax", "quantize_segments", "dequantize",
+    "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
     "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
@@ -23,6 +23,7 @@ _LIB_PATH = os.path.join(_HERE, "liblpdt.so")
 EXPORTS = [
     "lpdt_last_error", "lpdt_version",
     "lpdt_quantize_workspace_bytes", "lpdt_quantize", "lpdt_quantize_with_absmax",
+    "lpdt_quantize_static_max_len", "lpdt_quantize_static",
     "lpdt_quantize_segments_workspace_bytes", "lpdt_quantize_segments", "lpdt_dequantize",
     "lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes", "lpdt_qconv_bwd_weight_workspace_bytes",
     "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
@@ -92,6 +93,7 @@ def lib():
             if name.endswith("_workspace_bytes"):
                 getattr(L, name).restype = _sz
         L.lpdt_quantize_workspace_bytes.argtypes = [_sz]
+        L.lpdt_quantize_static_max_len.restype = _sz
         L.lpdt_quantize_segments_workspace_bytes.argtypes = [ctypes.c_int]
         for name in ("lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes",
                      "lpdt_qconv_bwd_weight_workspace_bytes", "lpdt_qconv_fwd_f32_workspace_bytes",
@@ -171,6 +173,16 @@ def quantize(x, rounding=ROUND_NEAREST, seed=0, offset=0, q=None, scale=None, ws
     buf, nb = _ws(ws, lib().lpdt_quantize_workspace_bytes(n))
     _check(lib().lpdt_quantize(_ptr(x), _sz(n), int(rounding), ctypes.c_uint64(seed), ctypes.c_uint64(offset),
                                _ptr(q), _ptr(scale), _ptr(buf), _sz(nb), _stream()))
+    return q, scale
+
+
+def quantize_static(x, rounding=ROUND_NEAREST, seed=0, offset=0, q=None, scale=None):
+    """lpdt_quantize_static: the quantizer that takes no workspace (q and scale must be given by callers that may not allocate)."""
+    _dev(x, torch.float32, "quantize x")
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device) if q is None else q
+    scale = torch.empty(1, dtype=torch.float32, device=x.device) if scale is None else scale
+    _check(lib().lpdt_quantize_static(_ptr(x), _sz(x.numel()), int(rounding), ctypes.c_uint64(seed), ctypes.c_uint64(offset),
+                                      _ptr(q), _ptr(scale), _stream()))
     return q, scale
 
 

@@ -4,6 +4,7 @@
 // 4-byte packed code stores, no atomics (abs-max goes through per-block
 // partials that every block of the rounding pass re-reduces from L2).
 #include "qconv_internal.h"
+#include <mutex>
 
 namespace lpdt {
 
@@ -355,4 +356,58 @@ extern "C" int lpdt_quantize_segments(const float *x, const int64_t *seg_begin, 
     else
         hipLaunchKernelGGL(seg_round_kernel<false>, grid, dim3(kQThreads), 0, st, x, table, amax, seed, offset, q, scales);
     return launch_status("lpdt_quantize_segments");
+}
+
+// ---- the quantizer for callers that cannot hand over a workspace ----------------------------------------------------
+// Same two kernels as lpdt_quantize; the abs-max partials live in a file-scope device array instead of the caller's
+// workspace.  Every GPU holds its own copy of the array; its address there is looked up once per device (the array's
+// name is only a host-side handle and is never passed to a kernel) and kept.
+static __device__ __align__(256) float scratch[kMaxParts];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU; written once, under the mutex
+std::mutex g_scratch_mutex;
+
+int static_scratch(float **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(LPDT_EHIP, "quantize_static: hipGetDevice: %s", hipGetErrorString(e));
+    LPDT_REQUIRE(dev >= 0 && dev < kMaxDevices, LPDT_EUNSUPPORTED, "quantize_static: device ordinal %d is beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));  // for the device that is current
+        if (e != hipSuccess || !ptr) return fail(LPDT_EHIP, "quantize_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = static_cast<float *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return LPDT_OK;
+}
+}  // namespace
+
+extern "C" size_t lpdt_quantize_static_max_len(void) { return (size_t)1 << 30; }
+
+extern "C" int lpdt_quantize_static(const float *x, size_t len, int rounding, uint64_t seed, uint64_t offset, int8_t *q,
+                                    float *scale, void *stream) {
+    int rc = check_quant_args(x, len, rounding, q, scale);
+    if (rc) return rc;
+    LPDT_REQUIRE(len <= lpdt_quantize_static_max_len(), LPDT_EUNSUPPORTED,
+                 "quantize_static: len %zu exceeds the maximum of %zu elements (use lpdt_quantize with a workspace)", len,
+                 lpdt_quantize_static_max_len());
+    float *parts = nullptr;
+    rc = static_scratch(&parts);
+    if (rc) return rc;
+    // every partial the second kernel reads is written by the first: nothing of the previous call's contents is used
+    int g1 = grid_for(len, 16);
+    if (g1 > kMaxParts) g1 = kMaxParts;
+    hipLaunchKernelGGL(absmax_kernel, dim3(g1), dim3(kQThreads), 0, as_stream(stream), x, len, parts);
+    const int g2 = grid_for(len, 16);
+    if (rounding == LPDT_ROUND_STOCHASTIC)
+        hipLaunchKernelGGL(round_kernel<true>, dim3(g2), dim3(kQThreads), 0, as_stream(stream), x, len, parts, g1,
+                           seed, offset, q, scale);
+    else
+        hipLaunchKernelGGL(round_kernel<false>, dim3(g2), dim3(kQThreads), 0, as_stream(stream), x, len, parts, g1,
+                           seed, offset, q, scale);
+    return launch_status("lpdt_quantize_static");
 }
