@@ -141,6 +141,20 @@ int lpdt_qconv_bwd_data(const lpdt_conv_desc *d, const int8_t *gq, const int8_t 
 int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_t *xq, int32_t *dw,
                           void *ws, size_t ws_bytes, void *stream);
 
+/* Which kernel a product of this shape takes when its operands are 16-byte aligned, for tests and profiles that
+ * must know which code they exercise (the result never affects the arithmetic).  product: 0 forward, 1 backward-data,
+ * 2 backward-weight.  Returns a negative lpdt_status for a bad descriptor, else
+ *   0   the any-shape kernel (one thread per output; the sliced weight-gradient kernel)
+ *   1   the first-layer matrix-core kernel (few input channels)
+ *   2   backward-weight only: the per-tap matrix-core kernel with atomic adds
+ *   10 + v (+ 100 when the reduction is split over blocks)  register-staged implicit GEMM, v = 0: 128 x 32 tile,
+ *       1 / 2: 64 x 64 with 64- / 128-byte steps, 3 / 4: 128 x 64 with 64- / 128-byte steps
+ *   20 + t  implicit GEMM with operands loaded straight into LDS, t = 0: 256 x 256, 1: 128 x 128 with 8 waves,
+ *       2: 128 x 128 with 4 waves, 3: 64 x 128
+ *   30 + t + 4*[64-pixel steps] + 8*[two wave groups per block]  rectangle-stepped backward-weight, t = 0: 32 x 64,
+ *       1: 64 x 64, 2: 128 x 128 channel tile */
+int lpdt_qconv_kernel_id(const lpdt_conv_desc *d, int product);
+
 /* The same three products with the dequantizing scale applied in the kernel epilogue: the result
  * is the fp32 tensor (s_a*s_b)*sum, bit-identical to the int32 call followed by lpdt_dequantize,
  * without the int32 tensor making a round trip through HBM.  s_*: fp32 device scalars (the scales

@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
     "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
-    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
+    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
     "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
@@ -26,7 +26,7 @@ EXPORTS = [
     "lpdt_quantize_static_max_len", "lpdt_quantize_static",
     "lpdt_quantize_segments_workspace_bytes", "lpdt_quantize_segments", "lpdt_dequantize",
     "lpdt_qconv_fwd_workspace_bytes", "lpdt_qconv_bwd_data_workspace_bytes", "lpdt_qconv_bwd_weight_workspace_bytes",
-    "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight",
+    "lpdt_qconv_fwd", "lpdt_qconv_bwd_data", "lpdt_qconv_bwd_weight", "lpdt_qconv_kernel_id",
     "lpdt_qconv_fwd_f32_workspace_bytes", "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
     "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
     "lpdt_qconv_fwd_f32_add_workspace_bytes", "lpdt_qconv_fwd_f32_add",
@@ -221,6 +221,14 @@ def dequantize(acc, sA, sB, y=None, accumulate=False):
 
 
 # ---------------------------------------------------------------- convolutions
+def qconv_kernel_id(d, product):
+    """lpdt_qconv_kernel_id: which kernel / tile the product (0 forward, 1 backward-data, 2 backward-weight) takes."""
+    rc = lib().lpdt_qconv_kernel_id(ctypes.byref(d), int(product))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
 def qconv_fwd(d, xq, wq, acc=None, ws=None):
     _dev(xq, torch.int8, "qconv_fwd xq"); _dev(wq, torch.int8, "qconv_fwd wq")
     assert tuple(xq.shape) == (d.N, d.H, d.W, d.C) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)

@@ -645,3 +645,25 @@ extern "C" int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *
     conv_bwd_weight_impl(d, P, Q, gq, xq, dw, 1, sg, sx, ws, as_stream(stream));
     return launch_status("lpdt_qconv_bwd_weight_f32");
 }
+
+// ---------------------------------------------------------------- which kernel a call takes
+extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
+    int P, Q;
+    int rc = check_conv(d0, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(product >= 0 && product <= 2, LPDT_EINVAL, "qconv_kernel_id: product must be 0 (forward), 1 (backward-data) or 2 (backward-weight)");
+    if (product == 0) {
+        if (narrow_conv_supported(d0, P, Q)) return 1;
+        return fwd_vec(d0, P, Q) ? igemm_fwd_kernel_id(d0, P, Q) : 0;
+    }
+    if (product == 1) return bwd_data_vec(d0, P, Q) ? igemm_bwd_data_kernel_id(d0, P, Q) : 0;
+    const lpdt_conv_desc view = wgrad_view(d0, &P, &Q), *d = &view;
+    WgradRectPlan pl;
+    if (wgrad_uses_rect(d, P, Q, &pl)) {
+        // 30 + tile (0: 32 x 64, 1: 64 x 64, 2: 128 x 128) + 4 for 64-pixel steps + 8 for two wave groups per block
+        return 30 + (pl.kt == 128 ? 2 : pl.kt == 64 ? 1 : 0) + (pl.ks == 2 ? 4 : 0) + (pl.ng == 2 ? 8 : 0);
+    }
+    if (narrow_conv_supported(d, P, Q)) return 1;
+    if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d)) return 2;
+    return 0;
+}

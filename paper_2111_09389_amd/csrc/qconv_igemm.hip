@@ -24,53 +24,14 @@
 // (w + pad) mod s); each class is a dense stride-1 problem over its sub-grid of pixels with its
 // own sub-filter, so the s*s classes run as grid.y of one launch and no product with a zero is
 // ever issued.
-#include "qconv_internal.h"
+#include "qconv_igemm_plan.h"
 #include <type_traits>
 
 namespace lpdt {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxClasses = 4;
-constexpr int kMaxTaps = 31;              // bits of the per-row tap mask; bit 31 is the always-clear "no granule" slot
-constexpr unsigned kBeyond = 0x80000000u; // a buffer offset no tensor reaches (sizes are checked to stay below it)
-constexpr int kMaxTableEntries = 4096;    // granules of one block's K range (32 KB of LDS)
-
-struct IgemmClass {
-    int M, OHs, OWs;        // rows of the class = N*OHs*OWs output pixels
-    int oy0, ox0;           // output pixel of sub-grid point (0,0); neighbours are `ostep` apart
-    int iy0, ix0;           // input pixel read by tap (0,0) at sub-grid point (0,0)
-    int Rc, Sc;             // tap grid of the class; tap (ty,tx) reads input pixel (+ty*dsign, +tx*dsign)
-    int gtot, nk, kps;      // granules, K-steps, K-steps per blockIdx.z
-    int wt_off;             // byte offset of the class's filter panel [Cout][Rc*Sc][Cin]
-    unsigned mul_hw, mul_w; // multipliers for x/(OHs*OWs) and x/OWs by umulhi; 0: divide
-    unsigned mul_sc;        // the same for x/Sc
-};
-
-struct IgemmParams {
-    const int8_t *in;       // [N][IH][IW][Cin]
-    const int8_t *wt;       // filter panels, see IgemmClass::wt_off
-    void *out;              // [N][OH][OW][Cout]: int32 sums, or fp32 when out_mode != 0
-    unsigned in_bytes, wt_bytes;
-    int out_mode;           // 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32, added to what is there
-    const float *sA, *sB;
-    int Cin, Cout, gpt;     // gpt = granules per tap = Cin/16
-    unsigned mul_gpt;       // multiplier for x/gpt
-    int IH, IW, OH, OW;
-    int istep, ostep, dsign;
-    int tiles_n, atomic_out, vec_out;
-    int kg;                 // granules per K-step
-    float *pabs;            // ABSMAX kernels: max |out| per wave, [grid.y][grid.x][4]
-    int nclasses;
-    IgemmClass cls[kMaxClasses];
-};
-
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F f) {
     if constexpr (N > 0) {
@@ -419,6 +380,12 @@ void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
 }
 
 void run(IgemmParams &p, size_t out_len, hipStream_t st) {
+    int cfg;
+    dim3 dgrid;
+    if (dma_plan(&p, &cfg, &dgrid)) {
+        dma_launch(p, cfg, dgrid, st);
+        return;
+    }
     const Tile tl = pick_tile(p);
     const dim3 grid = finish_plan(&p, tl, true);
     if (p.atomic_out) {
@@ -521,6 +488,10 @@ bool igemm_bwd_data_supported(const lpdt_conv_desc *d, int P, int Q) {
 
 // Waves of the launch (= abs-max partials an ABSMAX kernel writes); 0 when the reduction is split
 static int plan_waves(IgemmParams &p) {
+    int cfg;
+    dim3 dgrid;
+    p.vec_out = p.Cout % 4 == 0;   // the fp32 entry points, the only ones with this output, take 16-byte aligned results
+    if (dma_plan(&p, &cfg, &dgrid)) return dma_absmax_parts(cfg, dgrid);
     const dim3 grid = finish_plan(&p, pick_tile(p), true);
     return p.atomic_out ? 0 : (int)(grid.x * grid.y * 4);
 }
@@ -536,19 +507,51 @@ int igemm_bwd_data_absmax_parts(const lpdt_conv_desc *d, int P, int Q) {
     return plan_waves(p);
 }
 
+// whether a launch with a 16-byte aligned result splits its reduction
+static bool plan_is_split(IgemmParams &p) {
+    int cfg;
+    dim3 dgrid;
+    p.vec_out = p.Cout % 4 == 0;
+    if (dma_plan(&p, &cfg, &dgrid)) return false;
+    finish_plan(&p, pick_tile(p), true);
+    return p.atomic_out != 0;
+}
+
+// 20 + tile of the direct-to-LDS kernel, or 10 + variant of the register-staged one (0: 128 x 32, 1: 64 x 64 with 4-granule
+// steps, 2: 64 x 64 with 8, 3: 128 x 64 with 4, 4: 128 x 64 with 8), + 100 when the reduction is split over blocks
+static int plan_kernel_id(IgemmParams &p) {
+    int cfg;
+    dim3 dgrid;
+    p.vec_out = p.Cout % 4 == 0;
+    if (dma_plan(&p, &cfg, &dgrid)) return 20 + cfg;
+    const Tile tl = pick_tile(p);
+    finish_plan(&p, tl, true);
+    const int v = tl.BN == 32 ? 0 : (tl.BM == 64 ? 1 : 3) + (tl.KG == 8 ? 1 : 0);
+    return 10 + v + (p.atomic_out ? 100 : 0);
+}
+int igemm_fwd_kernel_id(const lpdt_conv_desc *d, int P, int Q) {
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    return plan_kernel_id(p);
+}
+int igemm_bwd_data_kernel_id(const lpdt_conv_desc *d, int P, int Q) {
+    IgemmParams p;
+    PackParams pk;
+    bwd_params(d, P, Q, &p, &pk);
+    return plan_kernel_id(p);
+}
+
 bool igemm_fwd_is_split(const lpdt_conv_desc *d, int P, int Q) {
     IgemmParams p;
     fwd_params(d, P, Q, &p);
-    finish_plan(&p, pick_tile(p), true);
-    return p.atomic_out != 0;
+    return plan_is_split(p);
 }
 
 bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q) {
     IgemmParams p;
     PackParams pk;
     bwd_params(d, P, Q, &p, &pk);
-    finish_plan(&p, pick_tile(p), true);
-    return p.atomic_out != 0;
+    return plan_is_split(p);
 }
 
 void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, void *out, int out_mode,

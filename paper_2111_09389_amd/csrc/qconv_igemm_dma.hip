@@ -1,0 +1,312 @@
+// int8 convolution forward / backward-data (Table "hardware_training", row Conv) as an implicit GEMM whose operand
+// tiles go from global memory straight into LDS (buffer loads with the LDS bit: no staging registers, no LDS store
+// instructions), for reductions whose channel count is a multiple of 64.
+//
+//   out[pix][j] = sum_{tap, c} in[pix + tap][c] * wt[j][tap][c]
+//
+// The reduction is cut into 64-byte units (64 channels of one filter tap); a K-step is KB = 64 or 128 bytes, i.e. one
+// or two units, so the tap of a unit (hence its border test and gather offset) is the same for the whole block and
+// lives in scalar registers.  LDS holds S stages of [BM pixel rows][KB] + [BN filter rows][KB].  A wave's load
+// instruction fills 1 KiB: 1024/KB rows, lane -> (row, 16-byte slot); the lane fetches the granule slot ^ swz(row) of
+// its row, swz = the bit-reversed row bits just above the bank period, which makes the MFMA operand reads (lane = row,
+// 16 bytes) free of bank conflicts whichever way the hardware groups the lanes of a ds_read_b128 (counters: none).
+// Masked rows (image border, past the end) fetch at an offset beyond the buffer, for which the hardware delivers zeros.
+//
+// Pipeline per step: wait until this wave's loads of the step have landed (vmcnt counts exactly: every step issues the
+// same number of loads, the steps past the end fetch nothing), barrier, issue the loads of step + S-1 into the stage
+// that was multiplied last, multiply the current stage.  One barrier per step; S-1 steps of loads in flight.
+//
+// What bounds it (counters and timing-only builds on a 16384 x 768 x 3072 product): the matrix cores run at their
+// full rate when fed from registers (at the ~1.9 GHz the chip sustains under this load), the LDS reads are free of
+// conflicts, and the L2 cache delivers about 0.6 requests of 64 bytes per cycle and channel: 10-15 TB/s for the whole
+// chip, only 2-3 times the HBM rate, so the bytes a tile re-reads through L2 decide the speed.  A variant in which the
+// two waves of a SIMD alternate between loading and multiplying was slower than this loop and was dropped.
+#include "qconv_igemm_plan.h"
+#include <type_traits>
+
+namespace lpdt {
+
+namespace {
+
+__device__ __forceinline__ int fast_div(int x, int d, unsigned mul) {
+    return mul ? (int)__umulhi((unsigned)x, mul) : x / d;
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+// added to a filter offset (a valid one below 2^30, or kBeyond) it gives an offset no filter reaches, without wrapping
+constexpr unsigned kBeyondStep = 0x40000000u;
+
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    // vmcnt(N): at most N of this wave's loads still in flight; lgkmcnt(0): its LDS reads of the previous stage are done
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F f) {
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>());
+    }
+}
+
+template <int KB> __device__ __forceinline__ int row_swz(int row) {
+    if (KB == 64) return ((row >> 3) & 1) | ((row >> 1) & 2);                         // bits 2..3 reversed
+    return ((row >> 3) & 1) | ((row >> 1) & 2) | ((row << 1) & 4);                    // bits 1..3 reversed
+}
+
+// TM x TN MFMA tiles (32 x 32) per wave, WGM x WGN waves per block, S LDS stages of KB (64 or 128) bytes of the reduction.
+template <int TM, int TN, int WGM, int WGN, int S, int KB, bool ABSMAX>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmParams p) {
+    constexpr int NW = WGM * WGN;
+    constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
+    constexpr int STAGE = (BM + BN) * KB;
+    constexpr int RPI = 1024 / KB, LPR = KB / 16, UPS = KB / 64, NKK = KB / 32;   // rows per load instruction, lanes per row, 64-byte units and MFMA K-chunks per step
+    constexpr int LA = BM / RPI / NW, LB = BN / RPI / NW;
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "every wave issues the same number of loads");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    int *const opix_tab = reinterpret_cast<int *>(lds + S * STAGE);
+
+    const IgemmClass &c = p.cls[blockIdx.y];
+    const int nb = gridDim.x, per = nb / 8, rem = nb % 8, xcd = blockIdx.x % 8;
+    const int tile = xcd * per + min(xcd, rem) + blockIdx.x / 8;
+    const int tile_n = tile % p.tiles_n, tile_m = tile / p.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int t = threadIdx.x, lane = t % 64, wave = __builtin_amdgcn_readfirstlane(t / 64);
+    if (m0 >= c.M) {
+        if (ABSMAX && lane == 0) p.pabs[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * NW + wave] = 0.0f;
+        return;
+    }
+    const int nunits = c.gtot >> 2;                       // 64-byte units of the reduction
+    const int nsteps = (nunits + UPS - 1) / UPS;
+    const int cpt = p.Cin >> 6;                           // units per filter tap
+
+    const int lrow = lane / LPR, lslot = lane % LPR;
+    // the 16-byte granule of the step this lane fetches for a row: slot ^ swz(row); the swizzle's top bit comes from the
+    // instruction's number, the rest from the lane
+    const bool lhi = ((lslot ^ row_swz<KB>(lrow)) >> 2) != 0;   // KB = 128: this lane fetches from the step's second unit
+    const int hw = c.OHs * c.OWs;
+    int aoff[LA];
+    unsigned amask[LA];
+#pragma unroll
+    for (int j = 0; j < LA; ++j) {
+        const int row = (wave * LA + j) * RPI + lrow, m = m0 + row;
+        int off = 0, opix = -1;
+        unsigned mk = 0;
+        if (m < c.M) {
+            const int n = fast_div(m, hw, c.mul_hw), r = m - n * hw;
+            const int qy = fast_div(r, c.OWs, c.mul_w), qx = r - qy * c.OWs;
+            const int iy = qy * p.istep + c.iy0, ix = qx * p.istep + c.ix0;
+            unsigned xm = 0;
+            for (int tx = 0; tx < c.Sc; ++tx) xm |= (unsigned)((unsigned)(ix + tx * p.dsign) < (unsigned)p.IW) << tx;
+            for (int ty = 0; ty < c.Rc; ++ty)
+                if ((unsigned)(iy + ty * p.dsign) < (unsigned)p.IH) mk |= xm << (ty * c.Sc);
+            off = ((n * p.IH + iy) * p.IW + ix) * p.Cin + ((lslot ^ row_swz<KB>(row)) & 3) * 16;
+            opix = (n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
+        }
+        aoff[j] = off;
+        amask[j] = mk;
+        if (lslot == 0) opix_tab[row] = opix;
+    }
+    unsigned boff[LB];
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+        const int brow = (wave * LB + j) * RPI + lrow, col = n0 + brow;
+        boff[j] = col < p.Cout ? (unsigned)(c.wt_off + (col * c.gtot + (lslot ^ row_swz<KB>(brow))) * 16) : kBeyond;
+    }
+    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.in), 0, (int)p.in_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.wt), 0, (int)p.wt_bytes, 0x00020000);
+
+    // the 64-byte unit whose loads go out next (all uniform): its tap slot (31 past the end) and the tap's byte offset
+    int l_unit = 0, l_cc = 0, l_tx = 0, l_ty = 0, l_tapbase = 0, l_step = 0, l_stage = 0;
+    auto next_unit = [&](unsigned &slot, int &tapoff) {
+        slot = l_unit < nunits ? (unsigned)(l_ty * c.Sc + l_tx) : 31u;
+        tapoff = l_tapbase + l_cc * 64;
+        ++l_unit;
+        if (++l_cc == cpt) {
+            l_cc = 0;
+            if (++l_tx == c.Sc) { l_tx = 0; ++l_ty; }
+            l_tapbase = (l_ty * p.IW + l_tx) * p.dsign * p.Cin;
+        }
+    };
+    auto issue_loads = [&]() {
+        const unsigned bstep = l_step < nsteps ? (unsigned)l_step * KB : kBeyondStep;
+        unsigned slot0, slot1 = 31u;
+        int tap0, tap1 = 0;
+        next_unit(slot0, tap0);
+        if (UPS == 2) next_unit(slot1, tap1);
+        const unsigned slot = (UPS == 2 && lhi) ? slot1 : slot0;
+        const int tapoff = (UPS == 2 && lhi) ? tap1 : tap0;
+        unsigned char *const base = lds + l_stage * STAGE;
+        {
+#pragma unroll
+            for (int j = 0; j < LA; ++j) {
+                const unsigned off = ((amask[j] >> slot) & 1u) ? (unsigned)(aoff[j] + tapoff) : kBeyond;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void *)(base + (wave * LA + j) * 1024), 16, off, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < LB; ++j) {
+                const unsigned off = boff[j] + bstep;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void *)(base + BM * KB + (wave * LB + j) * 1024), 16, off, 0, 0, 0);
+            }
+        }
+        ++l_step;
+        l_stage = l_stage + 1 == S ? 0 : l_stage + 1;
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int wm = wave / WGN, wn = wave % WGN, half = lane >> 5, r32 = lane & 31;
+    const int g0 = half ^ row_swz<KB>(r32);               // K-chunk kk reads the 16-byte slot g0 ^ 2*kk of its row
+    const int rd_a = (wm * TM * 32 + r32) * KB, rd_b = BM * KB + (wn * TN * 32 + r32) * KB;
+
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) issue_loads();
+    int stage = 0;
+    for (int step = 0; step < nsteps; ++step) {
+        wait_loads_and_barrier<(LA + LB) * (S - 2)>();
+        issue_loads();
+        const unsigned char *const sb = lds + stage * STAGE;
+        stage = stage + 1 == S ? 0 : stage + 1;
+        static_for<NKK>([&](auto kkc) {
+            constexpr int kk = decltype(kkc)::value;
+            const int g = (g0 ^ (2 * kk)) * 16;
+            v4i a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const v4i *>(sb + rd_a + i * 32 * KB + g);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const v4i *>(sb + rd_b + j * 32 * KB + g);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)  // filter rows are the MFMA's row operand: a lane ends with 4 consecutive channels
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[j], a[i], acc[i][j], 0, 0, 0);
+        });
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the empty loads of the last S-1 steps
+
+    // Accumulator layout of the 32x32 MFMA: a lane holds column lane%32 (a pixel) and rows 8*q + 4*(lane/32) + 0..3
+    // (output channels), q = 0..3.
+    const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
+    float am = 0.0f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int opix = opix_tab[wm * TM * 32 + 32 * i + r32];
+        if (opix < 0) continue;
+        const size_t pix = (size_t)opix;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * half;
+                if (col >= p.Cout) continue;
+                const v4i s = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                int32_t *dst = static_cast<int32_t *>(p.out) + pix * p.Cout + col;
+                if (p.out_mode) {
+                    v4f *fdst = reinterpret_cast<v4f *>(dst);
+                    const bool add = p.out_mode == 2;
+                    v4f v = {0.f, 0.f, 0.f, 0.f};
+                    if (add) v = *fdst;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = dequant_value(scale, s[e], v[e], add);
+                    *fdst = v;
+                    if (ABSMAX) am = fmaxf(fmaxf(am, fmaxf(fabsf(v[0]), fabsf(v[1]))), fmaxf(fabsf(v[2]), fabsf(v[3])));
+                } else *reinterpret_cast<v4i *>(dst) = s;
+            }
+        }
+    }
+    if (ABSMAX) {
+        am = wave_max(am);
+        if (lane == 0) p.pabs[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * NW + wave] = am;
+    }
+}
+
+struct DmaTile { int TM, TN, WGM, WGN, S, KB; };
+// 0: 256 x 256, 64-byte steps   1: 128 x 128, 128-byte steps, 8 waves   2: 128 x 128, 64-byte steps, 4 waves (two blocks per CU)
+// 3: 64 x 128, 128-byte steps
+constexpr DmaTile kTiles[] = {{4, 2, 2, 4, 4, 64}, {2, 1, 2, 4, 4, 128}, {2, 2, 2, 2, 4, 64}, {1, 1, 2, 4, 4, 128}};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+inline int tile_bm(int cfg) { return 32 * kTiles[cfg].TM * kTiles[cfg].WGM; }
+inline int tile_bn(int cfg) { return 32 * kTiles[cfg].TN * kTiles[cfg].WGN; }
+inline int tile_waves(int cfg) { return kTiles[cfg].WGM * kTiles[cfg].WGN; }
+inline size_t tile_lds(int cfg) { return (size_t)kTiles[cfg].S * (tile_bm(cfg) + tile_bn(cfg)) * kTiles[cfg].KB + (size_t)tile_bm(cfg) * 4; }
+
+long long tiles_of(const IgemmParams &p, int cfg) {
+    long long blocks = 0;
+    const int tn = (p.Cout + tile_bn(cfg) - 1) / tile_bn(cfg);
+    for (int i = 0; i < p.nclasses; ++i) blocks += (long long)((p.cls[i].M + tile_bm(cfg) - 1) / tile_bm(cfg)) * tn;
+    return blocks;
+}
+
+template <int TM, int TN, int WGM, int WGN, int S, int KB>
+void launch_cfg(const IgemmParams &p, dim3 grid, size_t lds, hipStream_t st) {
+    auto go = [&](auto kernel) {
+        static bool raised = false;  // the limit is a property of the kernel: raised once
+        if (!raised && lds > 48 * 1024) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            raised = true;
+        }
+        hipLaunchKernelGGL(kernel, grid, dim3(64 * WGM * WGN), lds, st, p);
+    };
+    if (p.pabs) go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, true>);
+    else go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, false>);
+}
+
+}  // namespace
+
+// Tile choice, from timings of the benchmark networks' layers and of 16384-token linear layers: the L2 cache delivers
+// only about 2.5 times the HBM rate, so the largest tile that still gives most CUs a block wins; 128 x 128 runs as two
+// 4-wave blocks per CU where there are enough tiles for that and as one 8-wave block otherwise.  Outputs narrower than
+// 96 channels and launches with too few tiles (they split the reduction) stay with the register-staged kernel.
+int dma_pick_tile(const IgemmParams &p) {
+    if (p.Cin % 64 != 0 || !p.vec_out || p.nclasses < 1 || p.wt_bytes >= kBeyondStep || p.Cout < 96) return -1;
+#ifdef LPDT_TUNE
+    if (const char *e = getenv("LPDT_DMA_TILE")) return atoi(e) < kNumTiles ? atoi(e) : -1;
+#endif
+    if (p.Cout >= 192 && tiles_of(p, 0) >= 160) return 0;
+    const long long t128 = tiles_of(p, 1);
+    if (t128 >= 320) return 2;
+    if (t128 >= 160) return 1;
+    if (tiles_of(p, 3) >= 128) return 3;
+    return -1;
+}
+
+bool dma_plan(IgemmParams *p, int *cfg_out, dim3 *grid) {
+    const int cfg = dma_pick_tile(*p);
+    if (cfg < 0) return false;
+    p->tiles_n = (p->Cout + tile_bn(cfg) - 1) / tile_bn(cfg);
+    p->kg = 4;
+    p->atomic_out = 0;
+    int max_tiles_m = 0;
+    for (int i = 0; i < p->nclasses; ++i) {
+        IgemmClass &c = p->cls[i];
+        c.nk = c.gtot / 4;
+        c.kps = c.nk;
+        const int tm = (c.M + tile_bm(cfg) - 1) / tile_bm(cfg);
+        if (tm > max_tiles_m) max_tiles_m = tm;
+    }
+    *cfg_out = cfg;
+    *grid = dim3((unsigned)(max_tiles_m * p->tiles_n), (unsigned)p->nclasses, 1);
+    return true;
+}
+
+int dma_absmax_parts(int cfg, dim3 grid) { return (int)(grid.x * grid.y) * tile_waves(cfg); }
+
+void dma_launch(const IgemmParams &p, int cfg, dim3 grid, hipStream_t st) {
+    const size_t lds = tile_lds(cfg);
+    switch (cfg) {
+        case 0: launch_cfg<4, 2, 2, 4, 4, 64>(p, grid, lds, st); break;
+        case 1: launch_cfg<2, 1, 2, 4, 4, 128>(p, grid, lds, st); break;
+        case 2: launch_cfg<2, 2, 2, 2, 4, 64>(p, grid, lds, st); break;
+        default: launch_cfg<1, 1, 2, 4, 4, 128>(p, grid, lds, st); break;
+    }
+}
+
+}  // namespace lpdt

@@ -21,6 +21,9 @@ bool igemm_fwd_supported(const lpdt_conv_desc *d, int P, int Q);
 bool igemm_bwd_data_supported(const lpdt_conv_desc *d, int P, int Q);
 bool igemm_fwd_is_split(const lpdt_conv_desc *d, int P, int Q);
 bool igemm_bwd_data_is_split(const lpdt_conv_desc *d, int P, int Q);
+// Which kernel and tile a launch with aligned operands takes (see lpdt_qconv_kernel_id).
+int igemm_fwd_kernel_id(const lpdt_conv_desc *d, int P, int Q);
+int igemm_bwd_data_kernel_id(const lpdt_conv_desc *d, int P, int Q);
 // out_mode 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32 added to `out`.  x, w, g 16-byte aligned.
 // pabs (fp32 output, reduction not split): every wave writes the largest |value| it stored, `*_absmax_parts` floats in all
 // (0: the reduction is split, no such output).

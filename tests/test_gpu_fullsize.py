@@ -1,7 +1,10 @@
 """Parity at the benchmark's full sizes (config 5: ResNet-18 shapes at batch 64 and 224x224, 16 agents x 11.2 M
-parameters), in the launch configurations bench.py times.  Inputs are seeded and synthetic; conv outputs are compared
-on sampled coordinates that the oracle computes one by one from the same inputs (oracle/sampled.py); the O(n) parts
-(quantizer, Range-EvoNorm) against the full C oracle; the CHOCO mix against the top-k rule written out in numpy."""
+parameters), in the launch configurations bench.py times.  Inputs are seeded and synthetic.  The three convolution
+products of every layer are compared with the C oracle element by element over the WHOLE result
+(test_conv_products_at_full_size_whole_tensors, which also pins the kernel and tile each product takes), and, as a
+quick check that also covers the fused-scale and packed-filter entry points, on sampled coordinates that the oracle
+computes one by one (oracle/sampled.py); the O(n) parts (quantizer, Range-EvoNorm) against the full C oracle; the CHOCO
+mix against the top-k rule written out in numpy."""
 import math
 
 import numpy as np
@@ -14,7 +17,7 @@ from gpu_util import assert_close, dev, host
 from oracle import sampled
 
 pytestmark = pytest.mark.gpu
-lpdt = pytest.importorskip("paper_2111_09389_amd")
+import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
 B = 64
 LAYERS = {   # N C H W K R S stride pad
@@ -41,6 +44,44 @@ LAYERS = {   # N C H W K R S stride pad
 }
 
 
+# lpdt_qconv_kernel_id of (forward, backward-data, backward-weight) at these sizes: the kernels and tiles bench.py times.
+# 1: first-layer kernels (narrow_fwd_kernel / narrow_wgrad_kernel); 10..14 (+100: split reduction): igemm_kernel
+# <128,32,4>, <64,64,4>, <64,64,8>, <128,64,4>, <128,64,8>; 20..23: igemm_dma_kernel 256x256, 128x128 (8 waves), 128x128
+# (4 waves), 64x128; 30 + t + 4*[64-pixel steps] + 8*[two wave groups]: wgrad_rect_kernel with tile t (0: 32x64, 1: 64x64);
+# 2: wgrad_kernel; 0: the any-shape kernels.
+KERNELS = {
+    "stem 7x7 s2": (1, 10, 1), "layer1 3x3": (13, 13, 42), "layer2 3x3 s2": (22, 13, 38), "layer2 1x1 s2": (22, 13, 31),
+    "layer2 3x3": (22, 22, 42), "layer3 3x3 s2": (21, 22, 38), "layer3 1x1 s2": (21, 22, 31), "layer3 3x3": (21, 21, 42),
+    "layer4 3x3 s2": (23, 21, 38), "layer4 1x1 s2": (23, 21, 31), "layer4 3x3": (23, 23, 38), "classifier": (111, 0, 0),
+    "resnet20 first": (1, 10, 1), "resnet20 16": (10, 10, 42), "resnet20 64": (111, 111, 42), "vgg11 first": (1, 10, 1),
+    "vgg11 128": (22, 14, 42), "vgg11 512": (112, 112, 2),
+    "gemm 256x256 tile": (20, 12, 42),
+}
+LAYERS["gemm 256x256 tile"] = (8, 64, 56, 56, 512, 3, 3, 1, 1)   # the one direct-to-LDS tile no benchmark layer takes at batch 64
+
+
+@pytest.mark.parametrize("name", list(LAYERS))
+def test_conv_products_at_full_size_whole_tensors(orc, name):
+    shp = LAYERS[name]
+    N, C, H, W, K, R, S, st, pd = shp
+    P, Q = wl.conv_out(H, pd, R, st), wl.conv_out(W, pd, S, st)
+    seed = 9000 + sum(shp)
+    x, w, g = wl.int8_codes(seed, (N, H, W, C)), wl.int8_codes(seed + 1, (K, R, S, C)), wl.int8_codes(seed + 2, (N, P, Q, K))
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert tuple(lpdt.qconv_kernel_id(ld, i) for i in range(3)) == KERNELS[name], "the planner changed: update KERNELS"
+    print(name, "forward", flush=True)
+    got = host(lpdt.qconv_fwd(ld, xd, wd))
+    assert np.array_equal(got, orc.qconv_fwd(od, x, w)), name + " forward"
+    if name != "stem 7x7 s2":   # nothing upstream of the image; its backward-data is covered at small sizes
+        print(name, "backward-data", flush=True)
+        got = host(lpdt.qconv_bwd_data(ld, gd, wd))
+        assert np.array_equal(got, orc.qconv_bwd_data(od, g, w)), name + " backward-data"
+    print(name, "backward-weight", flush=True)
+    got = host(lpdt.qconv_bwd_weight(ld, gd, xd))
+    assert np.array_equal(got, orc.qconv_bwd_weight(od, g, x)), name + " backward-weight"
+
+
 def _coords(rng, dims, count):
     pts = {tuple(0 for _ in dims), tuple(d - 1 for d in dims)}
     for axis in range(len(dims)):          # one point on every face
@@ -55,6 +96,7 @@ def _coords(rng, dims, count):
 
 @pytest.mark.parametrize("name", list(LAYERS))
 def test_conv_products_at_full_size_on_sampled_outputs(name):
+    # the fused-scale (fp32) and packed-filter entry points on top of the int32 ones, on sampled coordinates
     shp = LAYERS[name]
     N, C, H, W, K, R, S, st, pd = shp
     P, Q = wl.conv_out(H, pd, R, st), wl.conv_out(W, pd, S, st)

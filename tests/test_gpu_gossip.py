@@ -6,7 +6,7 @@ import workloads as wl
 from gpu_util import assert_close, dev, host
 
 pytestmark = pytest.mark.gpu
-lpdt = pytest.importorskip("paper_2111_09389_amd")
+import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
 
 @pytest.mark.parametrize("n,d,topo", [(16, 272_474, "ring"), (8, 1000, "ring"), (16, 5003, "torus"), (3, 17, "ring"),

@@ -7,7 +7,7 @@ import workloads as wl
 from gpu_util import dev, host
 
 pytestmark = pytest.mark.gpu
-lpdt = pytest.importorskip("paper_2111_09389_amd")
+import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
 # N C H W K R S stride pad -- sizes the oracle finishes in seconds, spanning several tiles with ragged tails
 CASES = [

@@ -8,7 +8,7 @@ import workloads as wl
 from gpu_util import assert_close, dev, host
 
 pytestmark = pytest.mark.gpu
-lpdt = pytest.importorskip("paper_2111_09389_amd")
+import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
 SIZES = [1, 3, 4, 5, 255, 1024, 4099, 131072, 1 << 20, (1 << 20) + 7, 5_000_003]
 

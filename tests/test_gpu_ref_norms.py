@@ -8,7 +8,7 @@ import workloads as wl
 from gpu_util import assert_close, dev, host
 
 pytestmark = pytest.mark.gpu
-lpdt = pytest.importorskip("paper_2111_09389_amd")
+import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
 # N H W C groups
 CASES = [

@@ -9,7 +9,7 @@ import workloads as wl
 from gpu_util import dev, host
 
 pytestmark = pytest.mark.gpu
-lpdt = pytest.importorskip("paper_2111_09389_amd")
+import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
 CASES = [
     (8, 16, 32, 32, 16, 3, 3, 1, 1),
