@@ -147,6 +147,7 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
  *   0   the any-shape kernel (one thread per output; the sliced weight-gradient kernel)
  *   1   the first-layer matrix-core kernel (few input channels)
  *   2   backward-weight only: the per-tap matrix-core kernel with atomic adds
+ *   3   the one-launch kernel for small linear layers (1x1, stride 1, at most 4 Mi multiply-adds)
  *   10 + v (+ 100 when the reduction is split over blocks)  register-staged implicit GEMM, v = 0: 128 x 32 tile,
  *       1 / 2: 64 x 64 with 64- / 128-byte steps, 3 / 4: 128 x 64 with 64- / 128-byte steps
  *   20 + t  implicit GEMM with operands loaded straight into LDS, t = 0: 256 x 256, 1: 128 x 128 with 8 waves,
@@ -160,7 +161,10 @@ int lpdt_qconv_kernel_id(const lpdt_conv_desc *d, int product);
  * without the int32 tensor making a round trip through HBM.  s_*: fp32 device scalars (the scales
  * lpdt_quantize wrote).  accumulate != 0 (backward-data only) adds to the gradient already in dx,
  * for tensors that fan out to several consumers.  Shapes whose reduction is split over blocks
- * stage their int32 sums in the workspace, which the *_f32_workspace_bytes queries include. */
+ * stage their int32 sums in the workspace, which the *_f32_workspace_bytes queries include.
+ * The forward and backward-data queries assume 16-byte aligned operands (xq, wq, gq): a call with a
+ * misaligned one takes the any-shape kernel, which stages its sums too, and needs 4*N*P*Q*K + 256
+ * (forward) or 4*N*H*W*C + 256 (backward-data) bytes on top, else it returns LPDT_EWORKSPACE. */
 size_t lpdt_qconv_fwd_f32_workspace_bytes(const lpdt_conv_desc *d);
 size_t lpdt_qconv_bwd_data_f32_workspace_bytes(const lpdt_conv_desc *d);
 size_t lpdt_qconv_bwd_weight_f32_workspace_bytes(const lpdt_conv_desc *d);
@@ -358,6 +362,13 @@ size_t lpdt_gossip_mix_workspace_bytes(int n, size_t d, int nseg, int choco);
 int lpdt_gossip_mix(float *x, float *xhat, int n, size_t d, const float *W, float rate,
                     double keep_ratio, const int64_t *seg_offsets, int nseg, void *ws, size_t ws_bytes,
                     void *stream);
+
+/* How the top-k selection of lpdt_gossip_mix / lpdt_gossip_mix_ex finds its threshold (the selected set is the same
+ * either way, exactly): -1 (the default) lets the library choose by problem size; 0 forces the two-pass form (one pass
+ * to histogram every key, one to collect); s > 0 forces the one-pass form that guesses the threshold's neighbourhood
+ * from a sample of every s-th 4096-element tile and falls back to two passes for a segment whose guess missed.
+ * Process-wide, takes effect at the next call; for tests and tuning.  LPDT_EINVAL for stride < -1. */
+int lpdt_gossip_set_sample_stride(int stride);
 
 /* The other gossip variants of the supplement, one step each (Algorithms "Deep-Squeeze",
  * "Sparse-Push", "Quant-SGP"); arguments as for lpdt_gossip_mix, plus:

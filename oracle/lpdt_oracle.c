@@ -92,6 +92,9 @@ int orc_quantize(const float *x, size_t len, int rounding, uint64_t seed, uint64
         if (m > a) a = m;
     }
     volatile float inv = (a > 0.0f) ? 127.0f / a : 0.0f; /* one fp32 divide */
+    /* An abs-max so small that 127/a is not a finite float (below about 3.7e-37) cannot carry a grid with
+     * |x - q*scale| <= scale/2: such a tensor counts as zero, like a == 0 (codes 0, scale 0). */
+    if (!(inv <= 3.4028234663852886e38f)) { inv = 0.0f; a = 0.0f; }
     *scale = a / 127.0f;
     for (size_t i = 0; i < len; ++i) {
         volatile float t = x[i] * inv; /* one fp32 multiply, never fused */

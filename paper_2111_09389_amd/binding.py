@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -41,7 +41,7 @@ EXPORTS = [
     "lpdt_qconv_fwd_f32_absmax", "lpdt_qconv_bwd_data_f32_absmax",
     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
     "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
-    "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
+    "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_set_sample_stride", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
     "lpdt_add", "lpdt_maxpool_fwd", "lpdt_maxpool_bwd", "lpdt_avgpool_fwd", "lpdt_avgpool_bwd",
     "lpdt_softmax_xent", "lpdt_sgd",
 ]
@@ -480,6 +480,11 @@ def range_bn_bwd(dy, x, gamma, mean, rng, amx, amn, eps=1e-5, dx=None, ws=None):
 
 
 # ---------------------------------------------------------------- gossip
+def gossip_set_sample_stride(stride):
+    """lpdt_gossip_set_sample_stride: -1 automatic, 0 two-pass selection, s > 0 one pass with every s-th tile sampled."""
+    _check(lib().lpdt_gossip_set_sample_stride(int(stride)))
+
+
 def gossip_mix(x, xhat, W, rate=1.0, keep_ratio=1.0, seg_offsets=None, ws=None):
     """In-place gossip step on x [n,d] (and xhat for CHOCO).  W: host matrix (numpy / nested list / CPU tensor)."""
     _dev(x, torch.float32, "gossip_mix x")

@@ -46,6 +46,15 @@ __device__ __forceinline__ float dequant_value(float s, int a, float prev, bool 
     return accumulate ? prev + v : v;
 }
 
+// 127 / a, the factor that maps a tensor of abs-max a onto the code grid: one fp32 division; 0 for a == 0 and for an
+// abs-max so small (below about 3.7e-37) that the quotient is not a finite float -- such a tensor counts as zero.
+__device__ __forceinline__ float quant_inv(float a) {
+    const float inv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
+    return inv <= 3.4028234663852886e38f ? inv : 0.0f;
+}
+// the scale that goes with it: a / 127, or 0 where quant_inv is 0
+__device__ __forceinline__ float quant_scale(float a) { return quant_inv(a) > 0.0f ? __fdiv_rn(a, 127.0f) : 0.0f; }
+
 // The quantizer's code for x with inv = 127 / max|x|: nearest (ties to even) or stochastic with the uniform number
 // u = (word >> 8) * 2^-24; clipped to [-127, 127].  Shared by every kernel that emits codes.
 __device__ __forceinline__ int round_code(float x, float inv, bool stochastic, uint32_t word) {

@@ -18,6 +18,7 @@
 // out to have missed the threshold bin is redone in the two-pass form (exact either way).
 #include "common.h"
 #include <cmath>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -861,13 +862,12 @@ static bool compact_graph(const MixGraph &g, int n, MixGraph4 *c) {
 }
 
 // Tile stride of the sample for the one-pass selection, or 0 for the two-pass form.  Below some tens of millions of
-// elements the three extra (small) launches cost more than the saved pass.  LPDT_CHOCO_SAMPLE_STRIDE overrides the
+// elements the three extra (small) launches cost more than the saved pass.  lpdt_gossip_set_sample_stride overrides the
 // choice (0: always two passes; s > 0: one pass with every s-th tile sampled, whatever the size): for tests and tuning.
+static std::atomic<int> g_sample_stride{-1};
 static int one_pass_stride(int n, size_t d) {
-    if (const char *e = std::getenv("LPDT_CHOCO_SAMPLE_STRIDE")) {
-        const int v = std::atoi(e);
-        return v < 0 ? 0 : v > 4096 ? 4096 : v;
-    }
+    const int v = g_sample_stride.load(std::memory_order_relaxed);
+    if (v >= 0) return v > 4096 ? 4096 : v;
     return (size_t)n * d >= ((size_t)32 << 20) ? 16 : 0;
 }
 
@@ -1066,4 +1066,10 @@ extern "C" int lpdt_gossip_mix_ex(float *x, float *state, int n, size_t d, const
                                   const int64_t *seg_offsets, int nseg, int mode, float *u, float *z, void *ws, size_t ws_bytes,
                                   void *stream) {
     return mix_impl(x, state, n, d, W, rate, keep_ratio, seg_offsets, nseg, mode, u, z, ws, ws_bytes, stream);
+}
+
+extern "C" int lpdt_gossip_set_sample_stride(int stride) {
+    LPDT_REQUIRE(stride >= -1, LPDT_EINVAL, "gossip_set_sample_stride: stride must be -1 (automatic), 0 (two passes) or positive");
+    lpdt::g_sample_stride.store(stride, std::memory_order_relaxed);
+    return LPDT_OK;
 }

@@ -1,24 +1,18 @@
-// int8 convolution forward, backward-data and backward-weight with exact int32
-// accumulation (Table "hardware_training", row Conv) as implicit GEMMs on the
-// gfx950 matrix cores (v_mfma_i32_32x32x32_i8), im2col-free.
+// Entry points of the three int8 convolution products with exact int32 accumulation (Table "hardware_training", row
+// Conv), and the kernels that take the shapes the matrix-core kernels do not.
 //
-//  forward / backward-data ("igemm"): out[m][j] = sum_{tap,c} in[pix(m,tap)][c] * wt[j][tap][c]
-//      m = output pixel, j = output channel.  The reduction axis is cut into 16-byte
-//      granules (16 channels of one filter tap); a K-step is 4 granules.  Both operands
-//      are gathered by 16-byte loads (zero for padding), staged through LDS in
-//      [granule][row][16 B] planes -- exactly the operand order of the MFMA, so every
-//      LDS read is a contiguous, conflict-free ds_read_b128 -- and double buffered.
-//      backward-data is the same kernel reading the gradient tensor with the
-//      transposed filter (built once per call in the workspace).
-//  backward-weight ("wgrad"): dw[k][tap][c] = sum_m g[m][k] * x[pix(m,tap)][c]
-//      the reduction runs over pixels, which is the strided axis of both NHWC operands.
-//      Tiles are staged in LDS in their natural [pixel][channel] order and read with
-//      the transposing LDS load (ds_read_b64_tr_b8), which hands each lane 8 pixels of
-//      one channel: the MFMA operand, with no transposed copy in memory.  One block
-//      accumulates all taps of a 3x3 filter for a 64x64 channel tile, so the gradient
-//      tile is loaded once for 9 products; blocks split the pixel range and combine
-//      with int32 atomic adds (exact, order-free).
-//  Shapes whose channel counts are not multiples of 16 take plain per-output kernels.
+//  forward / backward-data: out[m][j] = sum_{tap,c} in[pix(m,tap)][c] * wt[j][tap][c], an implicit GEMM (no im2col
+//      copy).  The kernels live in qconv_igemm_dma.hip (operands loaded straight into LDS; reductions over a multiple of
+//      64 channels), qconv_igemm.hip (register-staged loads, any multiple of 16 channels; splits the reduction over
+//      blocks with int32 atomics where there are too few tiles; also the filter transposition backward-data reads) and
+//      qconv_narrow.hip (first layer: 3 input channels).  This file chooses between them, stages the int32 sums in the
+//      workspace where the chosen kernel cannot apply the dequantizing scale itself, and holds the one-thread-per-output
+//      kernels for every other shape.
+//  backward-weight: dw[k][tap][c] = sum_m g[m][k] * x[pix(m,tap)][c]; the reduction runs over pixels, the strided
+//      axis of both NHWC operands.  qconv_wgrad.hip (rectangle steps, partial tiles, fixed-order reduce) takes the
+//      layers of the benchmark networks; wgrad_kernel below is the older per-tap form (one shifted copy of the input
+//      tile per tap in LDS, transposing LDS reads, int32 atomic combine) kept for shapes the rectangle plan rejects,
+//      and conv_bwd_weight_plain_kernel takes channel counts that are not multiples of 16.
 #include "qconv_internal.h"
 #include <cstdlib>
 #include <type_traits>
@@ -246,6 +240,56 @@ __global__ __launch_bounds__(kCThreads) void conv_bwd_weight_plain_kernel(const 
     if (s) atomicAdd(dw + o, s);
 }
 
+
+// ---- small linear layers (a network's classifier): 1x1 filters, stride 1, no padding, at most a few million
+// multiply-adds.  One thread per result element, any channel counts and alignments, the dequantizing scale (and, for
+// forward and backward-data, the addition to what the result holds) applied on the spot: one short launch instead of
+// the zero fill, split reduction and dequantizing pass the tiled kernels would need at this size.
+// mode 0: int32 sums; 1: fp32 sA*sB*sum; 2: fp32 added to out.  rows = N*H*W.
+template <int KIND>  // 0: out[m][k] = sum_c x[m][c] w[k][c]; 1: dx[m][c] = sum_k g[m][k] w[k][c]; 2: dw[k][c] = sum_m g[m][k] x[m][c]
+__global__ __launch_bounds__(kCThreads) void linear_small_kernel(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
+                                                                 void *__restrict__ out, int rows, int C, int K, int mode,
+                                                                 const float *__restrict__ sA, const float *__restrict__ sB) {
+    const int total = KIND == 0 ? rows * K : KIND == 1 ? rows * C : K * C;
+    const int o = blockIdx.x * kCThreads + threadIdx.x;
+    if (o >= total) return;
+    int s = 0;
+    if (KIND == 0) {
+        const int m = o / K, k = o - m * K;
+        const int8_t *xp = a + (size_t)m * C, *wp = b + (size_t)k * C;
+        int c = 0;
+        if (C % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 3) == 0)
+            for (; c < C; c += 4)
+                s = __builtin_amdgcn_sdot4(*reinterpret_cast<const int *>(xp + c), *reinterpret_cast<const int *>(wp + c), s, false);
+        for (; c < C; ++c) s += (int)xp[c] * (int)wp[c];
+    } else if (KIND == 1) {
+        const int m = o / C, c = o - m * C;
+        const int8_t *gp = a + (size_t)m * K;
+        for (int k = 0; k < K; ++k) s += (int)gp[k] * (int)b[(size_t)k * C + c];
+    } else {
+        const int k = o / C, c = o - k * C;
+        for (int m = 0; m < rows; ++m) s += (int)a[(size_t)m * K + k] * (int)b[(size_t)m * C + c];
+    }
+    if (mode == 0) static_cast<int32_t *>(out)[o] = s;
+    else {
+        float *f = static_cast<float *>(out) + o;
+        *f = dequant_value(__fmul_rn(*sA, *sB), s, mode == 2 ? *f : 0.0f, mode == 2);
+    }
+}
+
+static bool small_linear(const lpdt_conv_desc *d) {
+    return d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 && d->pad_w == 0 &&
+           (long long)d->N * d->H * d->W * d->C * d->K <= (4ll << 20);
+}
+template <int KIND>
+static void launch_linear_small(const lpdt_conv_desc *d, const int8_t *a, const int8_t *b, void *out, int mode, const float *sA,
+                                const float *sB, hipStream_t st) {
+    const int rows = d->N * d->H * d->W;
+    const int total = KIND == 0 ? rows * d->K : KIND == 1 ? rows * d->C : d->K * d->C;
+    hipLaunchKernelGGL(linear_small_kernel<KIND>, dim3((unsigned)((total + kCThreads - 1) / kCThreads)), dim3(kCThreads), 0, st, a, b, out,
+                       rows, d->C, d->K, mode, sA, sB);
+}
+
 static int blocks_for(size_t total, int cap = 65536) {
     size_t b = (total + kCThreads - 1) / kCThreads;
     if (b < 1) b = 1;
@@ -290,6 +334,10 @@ static int conv_fwd_impl(const lpdt_conv_desc *d, int P, int Q, const int8_t *xq
                          const float *sA, const float *sB, void *ws, hipStream_t st, float *pabs = nullptr) {
     int nparts = 0;
     const size_t out_len = (size_t)d->N * P * Q * d->K;
+    if (small_linear(d)) {
+        launch_linear_small<0>(d, xq, wq, out, out_mode, sA, sB, st);
+        return 0;
+    }
     // out_mode 2 (fp32, added to what is in `out`) is fused by the implicit-GEMM kernel only; the first-layer kernel stages
     const bool fused = fwd_fusable(d, P, Q) && aligned(xq, 16) && aligned(wq, 16) && !(out_mode == 2 && narrow_conv_supported(d, P, Q));
     const bool stage = out_mode != 0 && !fused;
@@ -383,6 +431,10 @@ static int conv_bwd_data_impl(const lpdt_conv_desc *d, int P, int Q, const int8_
                               float *pabs = nullptr) {
     int nparts = 0;
     const size_t out_len = (size_t)d->N * d->H * d->W * d->C;
+    if (small_linear(d) && wq) {
+        launch_linear_small<1>(d, gq, wq, out, out_mode, sA, sB, st);
+        return 0;
+    }
     const bool al = aligned(gq, 16) && (packed || aligned(wq, 16));   // the matrix-core path loads both operands 16 bytes at a time
     const bool stage = out_mode != 0 && !(bwd_data_fusable(d, P, Q) && al);
     int32_t *acc = stage ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + bwd_data_base_ws(d)) : static_cast<int32_t *>(out);
@@ -562,6 +614,10 @@ static size_t bwd_weight_base_ws(const lpdt_conv_desc *d0, int P, int Q) {
 
 static void conv_bwd_weight_impl(const lpdt_conv_desc *d0, int P, int Q, const int8_t *gq, const int8_t *xq, void *out, int out_mode,
                                  const float *sA, const float *sB, void *ws, hipStream_t st) {
+    if (small_linear(d0)) {
+        launch_linear_small<2>(d0, gq, xq, out, out_mode, sA, sB, st);
+        return;
+    }
     const lpdt_conv_desc view = wgrad_view(d0, &P, &Q), *d = &view;
     const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
     const long long M = (long long)d->N * P * Q;
@@ -652,6 +708,7 @@ extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
     int rc = check_conv(d0, &P, &Q);
     if (rc) return rc;
     LPDT_REQUIRE(product >= 0 && product <= 2, LPDT_EINVAL, "qconv_kernel_id: product must be 0 (forward), 1 (backward-data) or 2 (backward-weight)");
+    if (small_linear(d0)) return 3;
     if (product == 0) {
         if (narrow_conv_supported(d0, P, Q)) return 1;
         return fwd_vec(d0, P, Q) ? igemm_fwd_kernel_id(d0, P, Q) : 0;

@@ -379,20 +379,37 @@ void launch(const IgemmParams &p, dim3 grid, hipStream_t st) {
     else go(igemm_kernel<BM, BN, WM, WN, PF, false, KG>);
 }
 
+// When the result is ADDED to what the output holds (out_mode 2), pixels of a residue class without taps (a 1x1 stride-2
+// filter reaches one pixel in four) stay as they are: their blocks are dropped from the launch, after the tile has been
+// chosen for the whole problem.  Not when the maximum of the result is wanted, which has to visit every element.
+dim3 drop_empty_classes(IgemmParams &p, dim3 grid) {
+    if (p.out_mode != 2 || p.pabs) return grid;
+    int n = 0;
+    for (int i = 0; i < p.nclasses; ++i)
+        if (p.cls[i].gtot > 0) p.cls[n++] = p.cls[i];
+    p.nclasses = n;
+    grid.y = (unsigned)n;
+    return grid;
+}
+
 void run(IgemmParams &p, size_t out_len, hipStream_t st) {
     int cfg;
     dim3 dgrid;
     if (dma_plan(&p, &cfg, &dgrid)) {
-        dma_launch(p, cfg, dgrid, st);
+        dgrid = drop_empty_classes(p, dgrid);
+        if (dgrid.y > 0) dma_launch(p, cfg, dgrid, st);
         return;
     }
     const Tile tl = pick_tile(p);
-    const dim3 grid = finish_plan(&p, tl, true);
+    dim3 grid = finish_plan(&p, tl, true);
     if (p.atomic_out) {
         const size_t len = out_len;
         size_t b = (len + 1023) / 1024;
         if (b > 4096) b = 4096;
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)b), dim3(256), 0, st, static_cast<int32_t *>(p.out), len);
+    } else {
+        grid = drop_empty_classes(p, grid);
+        if (grid.y == 0) return;
     }
     if (tl.BN == 32) launch<128, 32, 4, 1, 4, 4>(p, grid, st);
     else if (tl.BM == 64 && tl.KG == 8) launch<64, 64, 2, 2, 2, 8>(p, grid, st);

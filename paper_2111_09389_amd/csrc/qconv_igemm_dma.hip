@@ -4,9 +4,9 @@
 //
 //   out[pix][j] = sum_{tap, c} in[pix + tap][c] * wt[j][tap][c]
 //
-// The reduction is cut into 64-byte units (64 channels of one filter tap); a K-step is KB = 64 or 128 bytes, i.e. one
-// or two units, so the tap of a unit (hence its border test and gather offset) is the same for the whole block and
-// lives in scalar registers.  LDS holds S stages of [BM pixel rows][KB] + [BN filter rows][KB].  A wave's load
+// A K-step is KB = 64 or 128 channels of one filter tap (KB divides the channel count), so the tap (hence the border
+// test and the gather offset) is the same for the whole block and lives in scalar registers; the steps visit all taps
+// of a channel chunk before the next chunk, which keeps the input lines of a tile in the CU's vector cache.  LDS holds S stages of [BM pixel rows][KB] + [BN filter rows][KB].  A wave's load
 // instruction fills 1 KiB: 1024/KB rows, lane -> (row, 16-byte slot); the lane fetches the granule slot ^ swz(row) of
 // its row, swz = the bit-reversed row bits just above the bank period, which makes the MFMA operand reads (lane = row,
 // 16 bytes) free of bank conflicts whichever way the hardware groups the lanes of a ds_read_b128 (counters: none).
@@ -23,6 +23,9 @@
 // two waves of a SIMD alternate between loading and multiplying was slower than this loop and was dropped.
 #include "qconv_igemm_plan.h"
 #include <type_traits>
+#ifdef LPDT_TUNE
+#include <cstdlib>
+#endif
 
 namespace lpdt {
 
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
     constexpr int NW = WGM * WGN;
     constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
     constexpr int STAGE = (BM + BN) * KB;
-    constexpr int RPI = 1024 / KB, LPR = KB / 16, UPS = KB / 64, NKK = KB / 32;   // rows per load instruction, lanes per row, 64-byte units and MFMA K-chunks per step
+    constexpr int RPI = 1024 / KB, LPR = KB / 16, NKK = KB / 32;   // rows per load instruction, lanes per row, MFMA K-chunks per step
     constexpr int LA = BM / RPI / NW, LB = BN / RPI / NW;
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "every wave issues the same number of loads");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -77,14 +80,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
         if (ABSMAX && lane == 0) p.pabs[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * NW + wave] = 0.0f;
         return;
     }
-    const int nunits = c.gtot >> 2;                       // 64-byte units of the reduction
-    const int nsteps = (nunits + UPS - 1) / UPS;
-    const int cpt = p.Cin >> 6;                           // units per filter tap
+    // A step is KB channels of one filter tap (the channel count is a multiple of KB).  Steps run over the taps first and
+    // the channel chunks second: consecutive steps then read nearly the same input lines (one pixel or one image row
+    // further), which the CU's vector cache still holds, instead of fetching every input line once per tap from L2.
+    const int ntaps = c.Rc * c.Sc;
+    const int nsteps = ntaps * (p.Cin / KB);
 
     const int lrow = lane / LPR, lslot = lane % LPR;
     // the 16-byte granule of the step this lane fetches for a row: slot ^ swz(row); the swizzle's top bit comes from the
     // instruction's number, the rest from the lane
-    const bool lhi = ((lslot ^ row_swz<KB>(lrow)) >> 2) != 0;   // KB = 128: this lane fetches from the step's second unit
     const int hw = c.OHs * c.OWs;
     int aoff[LA];
     unsigned amask[LA];
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
             for (int tx = 0; tx < c.Sc; ++tx) xm |= (unsigned)((unsigned)(ix + tx * p.dsign) < (unsigned)p.IW) << tx;
             for (int ty = 0; ty < c.Rc; ++ty)
                 if ((unsigned)(iy + ty * p.dsign) < (unsigned)p.IH) mk |= xm << (ty * c.Sc);
-            off = ((n * p.IH + iy) * p.IW + ix) * p.Cin + ((lslot ^ row_swz<KB>(row)) & 3) * 16;
+            off = ((n * p.IH + iy) * p.IW + ix) * p.Cin + (lslot ^ row_swz<KB>(row)) * 16;
             opix = (n * p.OH + qy * p.ostep + c.oy0) * p.OW + (qx * p.ostep + c.ox0);
         }
         aoff[j] = off;
@@ -117,26 +121,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
     const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.in), 0, (int)p.in_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.wt), 0, (int)p.wt_bytes, 0x00020000);
 
-    // the 64-byte unit whose loads go out next (all uniform): its tap slot (31 past the end) and the tap's byte offset
-    int l_unit = 0, l_cc = 0, l_tx = 0, l_ty = 0, l_tapbase = 0, l_step = 0, l_stage = 0;
-    auto next_unit = [&](unsigned &slot, int &tapoff) {
-        slot = l_unit < nunits ? (unsigned)(l_ty * c.Sc + l_tx) : 31u;
-        tapoff = l_tapbase + l_cc * 64;
-        ++l_unit;
-        if (++l_cc == cpt) {
-            l_cc = 0;
-            if (++l_tx == c.Sc) { l_tx = 0; ++l_ty; }
-            l_tapbase = (l_ty * p.IW + l_tx) * p.dsign * p.Cin;
-        }
-    };
+    // the step whose loads go out next (all uniform): its tap (slot 31, never set in a row's mask, past the end), the
+    // tap's byte offset in the input and the step's byte offset inside a filter row
+    int l_step = 0, l_tx = 0, l_ty = 0, l_chunk = 0, l_stage = 0;
     auto issue_loads = [&]() {
-        const unsigned bstep = l_step < nsteps ? (unsigned)l_step * KB : kBeyondStep;
-        unsigned slot0, slot1 = 31u;
-        int tap0, tap1 = 0;
-        next_unit(slot0, tap0);
-        if (UPS == 2) next_unit(slot1, tap1);
-        const unsigned slot = (UPS == 2 && lhi) ? slot1 : slot0;
-        const int tapoff = (UPS == 2 && lhi) ? tap1 : tap0;
+        const bool live = l_step < nsteps;
+        const unsigned slot = live ? (unsigned)(l_ty * c.Sc + l_tx) : 31u;
+        const int tapoff = (l_ty * p.IW + l_tx) * p.dsign * p.Cin + l_chunk;
+        const unsigned bstep = live ? (unsigned)((l_ty * c.Sc + l_tx) * p.Cin + l_chunk) : kBeyondStep;
+        ++l_step;
+        if (++l_tx == c.Sc) {
+            l_tx = 0;
+            if (++l_ty == c.Rc) { l_ty = 0; l_chunk += KB; }
+        }
         unsigned char *const base = lds + l_stage * STAGE;
         {
 #pragma unroll
@@ -150,7 +147,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void *)(base + BM * KB + (wave * LB + j) * 1024), 16, off, 0, 0, 0);
             }
         }
-        ++l_step;
         l_stage = l_stage + 1 == S ? 0 : l_stage + 1;
     };
 
@@ -268,13 +264,17 @@ void launch_cfg(const IgemmParams &p, dim3 grid, size_t lds, hipStream_t st) {
 int dma_pick_tile(const IgemmParams &p) {
     if (p.Cin % 64 != 0 || !p.vec_out || p.nclasses < 1 || p.wt_bytes >= kBeyondStep || p.Cout < 96) return -1;
 #ifdef LPDT_TUNE
-    if (const char *e = getenv("LPDT_DMA_TILE")) return atoi(e) < kNumTiles ? atoi(e) : -1;
+    if (const char *e = getenv("LPDT_DMA_TILE")) {
+        const int t = atoi(e);
+        return t >= 0 && t < kNumTiles && p.Cin % kTiles[t].KB == 0 ? t : -1;
+    }
 #endif
+    const bool wide = p.Cin % 128 == 0;   // tiles with 128-byte steps
     if (p.Cout >= 192 && tiles_of(p, 0) >= 160) return 0;
     const long long t128 = tiles_of(p, 1);
-    if (t128 >= 320) return 2;
+    if (t128 >= 320 || (t128 >= 160 && !wide)) return 2;
     if (t128 >= 160) return 1;
-    if (tiles_of(p, 3) >= 128) return 3;
+    if (wide && tiles_of(p, 3) >= 128) return 3;
     return -1;
 }
 

@@ -67,8 +67,8 @@ __global__ __launch_bounds__(kQThreads) void round_kernel(const float *__restric
     float a = 0.0f;
     for (int i = threadIdx.x; i < nparts; i += kQThreads) a = fmaxf(a, parts[i]);
     a = block_max(a, lds);
-    const float inv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *scale = __fdiv_rn(a, 127.0f);
+    const float inv = quant_inv(a);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale = quant_scale(a);
 
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const size_t nvec = len / 4;
@@ -150,11 +150,11 @@ __global__ __launch_bounds__(kQThreads) void seg_round_kernel(const float *__res
     const int s = blockIdx.y;
     const long long begin = table[2 * s], len = table[2 * s + 1] - begin;
     const float a = __uint_as_float(amax[s]);
-    if (blockIdx.x == 0 && threadIdx.x == 0) scales[s] = __fdiv_rn(a, 127.0f);
+    if (blockIdx.x == 0 && threadIdx.x == 0) scales[s] = quant_scale(a);
     const long long t0 = (long long)blockIdx.x * kSegTile;
     if (t0 >= len) return;
     const long long t1 = min(t0 + (long long)kSegTile, len);
-    const float inv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
+    const float inv = quant_inv(a);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint64_t base = offset + ((uint64_t)s << 24);  // slice s has its own counter range
     const float *xs = x + begin;

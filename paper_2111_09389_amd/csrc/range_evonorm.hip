@@ -339,9 +339,9 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
                                                                 float *__restrict__ scale, float *__restrict__ y) {
     const int n = blockIdx.y;
     const float a = *absmax;
-    if (blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *scale = __fdiv_rn(a, 127.0f);
+    if (blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *scale = quant_scale(a);
     if ((int)threadIdx.x >= g.threads) return;
-    const float qinv = (a > 0.0f) ? __fdiv_rn(127.0f, a) : 0.0f;
+    const float qinv = quant_inv(a);
     const int qd = threadIdx.x % g.cq, pl = threadIdx.x / g.cq;
     const int p0 = blockIdx.x * g.pix_per_block, p1 = min(p0 + g.pix_per_block, g.HW);
     float vv[4], gg[4], bb[4], inv[4];

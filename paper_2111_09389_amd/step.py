@@ -115,6 +115,14 @@ class TrainStep:
 
     def _quantize(self, src, q, scale, rounding, absmax=None, sr_layer=None):
         n = src.numel()
+        if sr_layer is not None:
+            # the counter ranges of run(): 2^24 Philox blocks (2^26 elements) per layer, 2^8 layers per step; beyond them
+            # two tensors would share random numbers, against the independent stochastic rounding of Section 3
+            if n > (1 << 26):
+                raise LpdtError(-2, f"a stochastically rounded tensor of {n} elements exceeds the 2^26 elements a layer's "
+                                    "Philox counter range holds")
+            if sr_layer >= 256:
+                raise LpdtError(-2, f"layer index {sr_layer} exceeds the 256 stochastic-rounding ranges of a step")
         if absmax is not None:
             self._emit(self.L.lpdt_quantize_with_absmax,
                        [_p(src), _sz(n), _p(absmax), rounding, _u64(self.seed), _u64(0), _p(q), _p(scale)], sr_layer)
@@ -491,9 +499,10 @@ class TrainStep:
             self._join_event.record(side)
             main.wait_event(self._join_event)
 
-    def run_timed(self, step=0):
+    def run_timed(self, step=0, with_desc=False):
         """Like run(), but everything on the current stream, every library call bracketed with events on it; returns
-        [(entry point name, milliseconds)] in call order (one synchronisation at the end)."""
+        [(entry point name, milliseconds)] in call order (one synchronisation at the end); with_desc adds the
+        convolution descriptor of the call as a third item (None for other calls)."""
         stream = _vp(torch.cuda.current_stream().cuda_stream)
         marks = []
         for fn, args, sr, _ in self.calls:
@@ -508,9 +517,12 @@ class TrainStep:
             b.record()
             if rc != 0:
                 raise LpdtError(rc, self.L.lpdt_last_error().decode())
-            marks.append((fn.__name__, a, b))
+            desc = args[0]._obj if fn.__name__.startswith("lpdt_qconv_") else None
+            marks.append((fn.__name__, a, b, desc))
         torch.cuda.synchronize()
-        return [(name, a.elapsed_time(b)) for name, a, b in marks]
+        if with_desc:
+            return [(name, a.elapsed_time(b), desc) for name, a, b, desc in marks]
+        return [(name, a.elapsed_time(b)) for name, a, b, _ in marks]
 
     def conv_work(self):
         """[(entry point name, multiply-adds)] for every convolution call of one step, in call order."""

@@ -171,3 +171,15 @@ def test_product_package_does_not_import_the_oracle():
     for fn in os.listdir(os.path.join(ROOT, "paper_2111_09389_amd")):
         if fn.endswith(".py"):
             assert "oracle" not in open(os.path.join(ROOT, "paper_2111_09389_amd", fn)).read().lower().replace("no cpu fallback", "")
+
+
+def test_gossip_sample_stride_setter(L):
+    assert L.lpdt_gossip_set_sample_stride(-2) == -1 and "stride" in _err(L)
+    assert L.lpdt_gossip_set_sample_stride(3) == 0 and L.lpdt_gossip_set_sample_stride(-1) == 0
+
+
+def test_qconv_kernel_id_argument_errors(L):
+    d = lpdt.ConvDesc.make(2, 64, 8, 8, 64, 3, 3, 1, 1)
+    assert L.lpdt_qconv_kernel_id(ctypes.byref(d), 5) == -1
+    assert L.lpdt_qconv_kernel_id(None, 0) == -1
+    assert L.lpdt_qconv_kernel_id(ctypes.byref(d), 0) >= 10

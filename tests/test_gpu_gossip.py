@@ -56,11 +56,11 @@ def test_choco_global_topk_and_ties(orc):
 
 
 @pytest.fixture
-def sample_stride(monkeypatch):
-    """Forces the one-pass top-k (window of bins guessed from every s-th 4096-element tile) at any size."""
-    def set_stride(s):
-        monkeypatch.setenv("LPDT_CHOCO_SAMPLE_STRIDE", str(s))
-    return set_stride
+def sample_stride():
+    """Forces the one-pass top-k (window of bins guessed from every s-th 4096-element tile) at any size; back to the
+    library's own choice afterwards."""
+    yield lpdt.gossip_set_sample_stride
+    lpdt.gossip_set_sample_stride(-1)
 
 
 @pytest.mark.parametrize("stride", [1, 3, 16])

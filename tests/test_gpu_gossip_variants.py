@@ -52,12 +52,15 @@ def test_deepsqueeze(orc, n, topo):
 
 
 @pytest.mark.parametrize("stride", [1, 2])
-def test_deepsqueeze_one_pass_selection(orc, monkeypatch, stride):
+def test_deepsqueeze_one_pass_selection(orc, stride):
     # the top-k window guessed from a sample of the tiles (forced here at a small size); exact like the two-pass form
-    monkeypatch.setenv("LPDT_CHOCO_SAMPLE_STRIDE", str(stride))
-    _case(orc, orc.MIX_DEEPSQUEEZE, 16, 30000, SEG, 0.01, 0.3, 916, wl.ring_matrix(16), False)
-    _case(orc, orc.MIX_DEEPSQUEEZE, 9, 30000, SEG, 0.1, 0.5, 919, wl.directed_matrix(9), True)
-    _case(orc, orc.MIX_DEEPSQUEEZE, 5, 9000, [0, 100, 4500, 9000], 0.05, 0.4, 935, wl.ring_matrix(5), False, ties=True)
+    lpdt.gossip_set_sample_stride(stride)
+    try:
+        _case(orc, orc.MIX_DEEPSQUEEZE, 16, 30000, SEG, 0.01, 0.3, 916, wl.ring_matrix(16), False)
+        _case(orc, orc.MIX_DEEPSQUEEZE, 9, 30000, SEG, 0.1, 0.5, 919, wl.directed_matrix(9), True)
+        _case(orc, orc.MIX_DEEPSQUEEZE, 5, 9000, [0, 100, 4500, 9000], 0.05, 0.4, 935, wl.ring_matrix(5), False, ties=True)
+    finally:
+        lpdt.gossip_set_sample_stride(-1)
 
 
 @pytest.mark.parametrize("n", [7, 16])

@@ -77,7 +77,9 @@ def test_output_buffers_are_overwritten_and_deterministic():
     assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("shp", [CASES[0], CASES[2], CASES[3], CASES[4], CASES[7], CASES[9], CASES[10], CASES[12]])
+# CASES[5]: three of the four residue classes of a 1x1 stride-2 filter have no taps (accumulating calls leave their pixels
+# alone); CASES[6], CASES[7]: small linear layers (the one-launch kernel with every output mode)
+@pytest.mark.parametrize("shp", [CASES[0], CASES[2], CASES[3], CASES[4], CASES[5], CASES[6], CASES[7], CASES[9], CASES[10], CASES[12]])
 def test_fused_fp32_epilogue_equals_int32_then_dequantize(orc, shp):
     """The *_f32 entry points must give exactly the bits of the int32 call followed by lpdt_dequantize,
     and stay within 1e-5 of the oracle's real-valued result."""

@@ -55,7 +55,9 @@ def test_quantize_edge_values(orc):
               np.array([-1, 0.5, 0.25, 1], np.float32),
               np.array([127, 62.5, 61.5, -62.5, -0.5, 0.5, 1.5], np.float32),
               (wl.int8_codes(3, (4096,), "uniform").astype(np.float32) * np.float32(0.0173)),
-              np.array([1e-30, -3e-30, 2e-30], np.float32), np.array([3e38, -1e38, 5e37], np.float32)):
+              np.array([1e-30, -3e-30, 2e-30], np.float32), np.array([3e38, -1e38, 5e37], np.float32),
+              np.array([1e-45, -5e-46, 0.0], np.float32), np.array([3.6e-37, -1e-37, 0.0, 2e-38], np.float32),   # 127/absmax overflows: zero
+              np.array([4e-37, -2e-37, 0.0, 1e-37], np.float32)):
         for rounding in (0, 1):
             q_ref, s_ref = orc.quantize(x, rounding, 11, 0)
             q, s = lpdt.quantize(dev(x), rounding, 11, 0)

@@ -86,6 +86,19 @@ def test_zero_and_tiny(orc):
     assert q.tolist() == [127]
 
 
+def test_abs_max_too_small_for_a_grid_counts_as_zero(orc):
+    # 127/absmax overflows fp32 below about 3.7e-37 (subnormals included): codes 0, scale 0, for both roundings;
+    # just above the limit the grid still holds
+    for a in (1e-45, 1.2e-38, 3.6e-37):
+        x = np.array([a, -a / 2, 0.0, a / 4], np.float32)
+        for rounding in (0, 1):
+            q, s = orc.quantize(x, rounding, 5, 0)
+            assert s == 0.0 and not q.any()
+    x = np.array([4e-37, -2e-37, 0.0, 1e-37], np.float32)
+    q, s = orc.quantize(x, 0, 5, 0)
+    assert s > 0 and list(q) == [127, -64, 0, 32] and np.all(np.abs(x - q.astype(np.float32) * s) <= s / 2 * (1 + 2 ** -20))
+
+
 def test_sr_floor_ceil_and_determinism(orc):
     x = wl.upstream_grad(3, (8, 32, 32, 16))
     q, s = orc.quantize(x, rounding=1, seed=wl.PHILOX_SEED, offset=11)
