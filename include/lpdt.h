@@ -143,7 +143,8 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
 
 /* Which kernel a product of this shape takes when its operands are 16-byte aligned, for tests and profiles that
  * must know which code they exercise (the result never affects the arithmetic).  product: 0 forward, 1 backward-data,
- * 2 backward-weight.  Returns a negative lpdt_status for a bad descriptor, else
+ * 2 backward-weight, 3 the forward product inside lpdt_qconv_ren_fwd_q (40 + t when it takes the normalisation's
+ * statistics in its epilogue, t as for 20 + t below; else the value for product 0).  Returns a negative lpdt_status for a bad descriptor, else
  *   0   the any-shape kernel (one thread per output; the sliced weight-gradient kernel)
  *   1   the first-layer matrix-core kernel (few input channels)
  *   2   backward-weight only: the per-tap matrix-core kernel with atomic adds
@@ -214,6 +215,21 @@ int lpdt_qconv_bwd_data_f32_absmax(const lpdt_conv_desc *d, const int8_t *gq, co
 size_t lpdt_qconv_fwd_f32_add_workspace_bytes(const lpdt_conv_desc *d);
 int lpdt_qconv_fwd_f32_add(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx,
                            const float *sw, float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* The chain convolution -> Range-EvoNorm -> quantizer of a layer whose normalised output only feeds convolutions
+ * (Section 3: every layer's input is quantized; Eq. "ren"), as one call: y = (sx*sw) * conv(xq, wq) (added to what y holds
+ * when accumulate != 0: a skip connection), then the codes q and scale of Range-EvoNorm(y) and the layer's saved range /
+ * argmax / argmin -- the bits of lpdt_qconv_fwd_f32 (or lpdt_qconv_fwd_f32_add) followed by lpdt_range_evonorm_fwd_q;
+ * z: NULL, or fp32 [N,P,Q,K] that also receives the normalised output (a skip connection reads it).  Where the matrix-core kernel writes y through LDS it takes the per-sample, per-channel extremes
+ * of y and of y*hardsigmoid(v y) on the way out, so the normalisation's statistics pass over y falls away and the
+ * positions of the extremes are found by the pass that emits the codes; other shapes run the two calls.
+ * y fp32 [N,P,Q,K] (kept: the backward pass reads it), q int8 [N,P,Q,K]; v, gamma, beta fp32 [K]; groups as in
+ * lpdt_range_evonorm_fwd (K % groups == 0, K/groups >= 2); K a multiple of 4, at most 1024. */
+size_t lpdt_qconv_ren_fwd_q_workspace_bytes(const lpdt_conv_desc *d, int groups);
+int lpdt_qconv_ren_fwd_q(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx, const float *sw,
+                         int accumulate, int groups, const float *v, const float *gamma, const float *beta, float eps,
+                         float *y, float *z, int8_t *q, float *scale, float *range_out, int32_t *argmax_out,
+                         int32_t *argmin_out, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------ Range-EvoNorm
  * Eq. "ren": for every sample n and channel group G (m = C/groups channels),

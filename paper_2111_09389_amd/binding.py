@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "LpdtError", "ConvDesc", "lib", "library_path", "ROUND_NEAREST", "ROUND_STOCHASTIC",
     "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
-    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
+    "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_ren_fwd_q", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
     "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
@@ -30,6 +30,7 @@ EXPORTS = [
     "lpdt_qconv_fwd_f32_workspace_bytes", "lpdt_qconv_bwd_data_f32_workspace_bytes", "lpdt_qconv_bwd_weight_f32_workspace_bytes",
     "lpdt_qconv_fwd_f32", "lpdt_qconv_bwd_data_f32", "lpdt_qconv_bwd_weight_f32",
     "lpdt_qconv_fwd_f32_add_workspace_bytes", "lpdt_qconv_fwd_f32_add",
+    "lpdt_qconv_ren_fwd_q_workspace_bytes", "lpdt_qconv_ren_fwd_q",
     "lpdt_to_bf16", "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_bwd_weight_bf16",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
     "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
@@ -105,6 +106,7 @@ def lib():
                      "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
                      "lpdt_range_evonorm_maxpool_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
+        L.lpdt_qconv_ren_fwd_q_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.c_int]
         L.lpdt_qconv_bwd_data_packed_filter_bytes.restype = _sz
         L.lpdt_qconv_bwd_data_packed_filter_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes"):
@@ -272,6 +274,27 @@ def qconv_fwd_f32_add(d, xq, wq, sx, sw, y, ws=None):
     buf, nb = _ws(ws, lib().lpdt_qconv_fwd_f32_add_workspace_bytes(ctypes.byref(d)))
     _check(lib().lpdt_qconv_fwd_f32_add(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(sx), _ptr(sw), _ptr(y), _ptr(buf), _sz(nb), _stream()))
     return y
+
+
+def qconv_ren_fwd_q(d, xq, wq, sx, sw, groups, v, gamma, beta, eps=1e-5, y=None, accumulate=False, z=None, ws=None):
+    """lpdt_qconv_ren_fwd_q: conv -> Range-EvoNorm -> quantizer in one call -> (y, q, scale, range, argmax, argmin);
+    accumulate: y (given) += product before the normalisation."""
+    _dev(xq, torch.int8, "qconv_ren_fwd_q xq"); _dev(wq, torch.int8, "qconv_ren_fwd_q wq")
+    assert tuple(xq.shape) == (d.N, d.H, d.W, d.C) and tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    dev = xq.device
+    if y is None:
+        assert not accumulate
+        y = torch.empty((d.N, d.P, d.Q, d.K), dtype=torch.float32, device=dev)
+    q = torch.empty((d.N, d.P, d.Q, d.K), dtype=torch.int8, device=dev)
+    scale = torch.empty(1, dtype=torch.float32, device=dev)
+    rng = torch.empty((d.N, groups), dtype=torch.float32, device=dev)
+    amx = torch.empty((d.N, groups), dtype=torch.int32, device=dev)
+    amn = torch.empty((d.N, groups), dtype=torch.int32, device=dev)
+    buf, nb = _ws(ws, lib().lpdt_qconv_ren_fwd_q_workspace_bytes(ctypes.byref(d), int(groups)))
+    _check(lib().lpdt_qconv_ren_fwd_q(ctypes.byref(d), _ptr(xq), _ptr(wq), _ptr(sx), _ptr(sw), int(bool(accumulate)), int(groups), _ptr(v),
+                                      _ptr(gamma), _ptr(beta), ctypes.c_float(eps), _ptr(y), _ptr(z), _ptr(q), _ptr(scale), _ptr(rng), _ptr(amx),
+                                      _ptr(amn), _ptr(buf), _sz(nb), _stream()))
+    return y, q, scale, rng, amx, amn
 
 
 def qconv_bwd_data_f32(d, gq, wq, sg, sw, dx=None, accumulate=False, ws=None):

@@ -46,6 +46,14 @@ static inline RenGeom ren_geom(int N, int H, int W, int C, int groups, int min_p
     return g;
 }
 
+// u = x * hardsigmoid(v x) of Eq. "ren" with every rounding pinned (no contraction left to the compiler): every kernel
+// that evaluates it -- the forward passes and the convolution epilogue that takes the layer's statistics on the way
+// out -- must produce the same bits.
+__device__ __forceinline__ float ren_u(float x, float v) {
+    const float z = __fmul_rn(v, x);
+    return __fmul_rn(x, fminf(1.0f, fmaxf(0.0f, __fmul_rn(__fadd_rn(z, 3.0f), 1.0f / 6.0f))));
+}
+
 // monotone map float -> uint32 (larger float <=> larger key); -0 is folded onto +0
 __device__ __forceinline__ uint32_t ordered_bits(float x) {
     const uint32_t b = __float_as_uint(x + 0.0f);

@@ -702,13 +702,61 @@ extern "C" int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *
     return launch_status("lpdt_qconv_bwd_weight_f32");
 }
 
+// ---------------------------------------------------------------- convolution -> Range-EvoNorm -> quantizer
+static bool chain_fused(const lpdt_conv_desc *d, int P, int Q, int groups) {
+    return !small_linear(d) && ren_chain_supported(d->K, groups) && igemm_fwd_stats_supported(d, P, Q);
+}
+
+extern "C" size_t lpdt_qconv_ren_fwd_q_workspace_bytes(const lpdt_conv_desc *d, int groups) {
+    int P, Q;
+    if (check_conv(d, &P, &Q)) { clear_error(); return 0; }
+    if (chain_fused(d, P, Q, groups)) return ren_chain_ws_bytes(d->N, d->K, groups);
+    const size_t conv = lpdt_qconv_fwd_f32_add_workspace_bytes(d), ren = lpdt_range_evonorm_fwd_q_workspace_bytes(d->N, P, Q, d->K, groups);
+    return conv > ren ? conv : ren;
+}
+
+extern "C" int lpdt_qconv_ren_fwd_q(const lpdt_conv_desc *d, const int8_t *xq, const int8_t *wq, const float *sx, const float *sw,
+                                    int accumulate, int groups, const float *v, const float *gamma, const float *beta, float eps,
+                                    float *y, float *z, int8_t *q, float *scale, float *range_out, int32_t *argmax_out,
+                                    int32_t *argmin_out, void *ws, size_t ws_bytes, void *stream) {
+    int P, Q;
+    int rc = check_conv(d, &P, &Q);
+    if (rc) return rc;
+    LPDT_REQUIRE(xq && wq && sx && sw && v && gamma && beta && y && q && scale && range_out && argmax_out && argmin_out, LPDT_EINVAL,
+                 "qconv_ren_fwd_q: NULL argument");
+    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "qconv_ren_fwd_q: eps must be >= 0");
+    LPDT_REQUIRE(groups > 0 && d->K % groups == 0 && d->K / groups >= 2, LPDT_EUNSUPPORTED,
+                 "qconv_ren_fwd_q: groups must divide K with at least 2 channels per group");
+    LPDT_REQUIRE(aligned(y, 16) && aligned(z, 16) && aligned(q, 4) && aligned(scale, 4), LPDT_EINVAL,
+                 "qconv_ren_fwd_q: y and z must be 16-byte aligned, q and scale 4-byte aligned");
+    hipStream_t st = as_stream(stream);
+    if (chain_fused(d, P, Q, groups) && aligned(xq, 16) && aligned(wq, 16)) {
+        rc = check_ws(ws, ws_bytes, ren_chain_ws_bytes(d->N, d->K, groups));
+        if (rc) return rc;
+        unsigned *cstats = ren_chain_begin(d->N, d->K, groups, ws, st);
+        launch_igemm_fwd_stats(d, P, Q, xq, wq, y, accumulate ? 2 : 1, sx, sw, cstats, v, st);
+        ren_chain_finish(y, d->N, P, Q, d->K, groups, v, gamma, beta, eps, q, scale, z, range_out, argmax_out, argmin_out, ws, st);
+        return launch_status("lpdt_qconv_ren_fwd_q");
+    }
+    // any other shape: the two calls this one stands for
+    rc = accumulate ? lpdt_qconv_fwd_f32_add(d, xq, wq, sx, sw, y, ws, ws_bytes, stream) : lpdt_qconv_fwd_f32(d, xq, wq, sx, sw, y, ws, ws_bytes, stream);
+    if (rc) return rc;
+    return lpdt_range_evonorm_fwd_q(y, d->N, P, Q, d->K, groups, v, gamma, beta, eps, q, scale, z, range_out, argmax_out, argmin_out,
+                                    ws, ws_bytes, stream);
+}
+
 // ---------------------------------------------------------------- which kernel a call takes
 extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
     int P, Q;
     int rc = check_conv(d0, &P, &Q);
     if (rc) return rc;
-    LPDT_REQUIRE(product >= 0 && product <= 2, LPDT_EINVAL, "qconv_kernel_id: product must be 0 (forward), 1 (backward-data) or 2 (backward-weight)");
+    LPDT_REQUIRE(product >= 0 && product <= 3, LPDT_EINVAL,
+                 "qconv_kernel_id: product must be 0 (forward), 1 (backward-data), 2 (backward-weight) or 3 (forward inside lpdt_qconv_ren_fwd_q)");
     if (small_linear(d0)) return 3;
+    if (product == 3) {   // the statistics ride in the epilogue wherever the shape allows (two channels per group assumed)
+        if (chain_fused(d0, P, Q, d0->K / 2)) return 20 + igemm_fwd_kernel_id(d0, P, Q);
+        product = 0;
+    }
     if (product == 0) {
         if (narrow_conv_supported(d0, P, Q)) return 1;
         return fwd_vec(d0, P, Q) ? igemm_fwd_kernel_id(d0, P, Q) : 0;

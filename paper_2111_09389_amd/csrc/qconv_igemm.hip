@@ -580,6 +580,30 @@ void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, co
     run(p, (size_t)d->N * P * Q * d->K, st);
 }
 
+bool igemm_fwd_stats_supported(const lpdt_conv_desc *d, int P, int Q) {
+    if (!igemm_fwd_supported(d, P, Q)) return false;
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    p.vec_out = d->K % 4 == 0;
+    p.out_mode = 1;
+    p.pix_per_sample = P * Q;
+    int cfg;
+    dim3 grid;
+    return dma_plan(&p, &cfg, &grid) && dma_stats_supported(p, cfg);
+}
+
+void launch_igemm_fwd_stats(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, float *out, int out_mode,
+                            const float *sA, const float *sB, unsigned *cstats, const float *vpar, hipStream_t st) {
+    IgemmParams p;
+    fwd_params(d, P, Q, &p);
+    p.in = x; p.wt = w; p.out = out; p.out_mode = out_mode; p.sA = sA; p.sB = sB;
+    p.vec_out = 1;
+    p.cstats = cstats; p.vpar = vpar; p.pix_per_sample = P * Q;
+    int cfg;
+    dim3 grid;
+    if (dma_plan(&p, &cfg, &grid)) dma_launch(p, cfg, grid, st);   // igemm_fwd_stats_supported said so
+}
+
 size_t igemm_bwd_filter_panel_bytes(const lpdt_conv_desc *d) { return (size_t)d->K * d->R * d->S * d->C; }
 
 void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const int8_t *w, void *panel, hipStream_t st) {

@@ -22,6 +22,7 @@
 // chip, only 2-3 times the HBM rate, so the bytes a tile re-reads through L2 decide the speed.  A variant in which the
 // two waves of a SIMD alternate between loading and multiplying was slower than this loop and was dropped.
 #include "qconv_igemm_plan.h"
+#include "norm_geom.h"
 #include <type_traits>
 #ifdef LPDT_TUNE
 #include <cstdlib>
@@ -59,7 +60,17 @@ template <int KB> __device__ __forceinline__ int row_swz(int row) {
 }
 
 // TM x TN MFMA tiles (32 x 32) per wave, WGM x WGN waves per block, S LDS stages of KB (64 or 128) bytes of the reduction.
-template <int TM, int TN, int WGM, int WGN, int S, int KB, bool ABSMAX>
+// Passes of the staged epilogue: the tile goes through LDS in 1, 2 or 4 runs of whole wave rows so that a run ([rows][BN + 4]
+// words, plus the statistics array when one is taken) fits the operand stages; 0: it does not fit (direct epilogue).
+constexpr int staged_passes(int BM, int BN, int WGM, int stage_bytes, int extra) {
+    for (int ps = 1; ps <= 4; ps *= 2)
+        if (WGM % ps == 0 && (BM / ps) * (BN + 4) * 4 + extra <= stage_bytes) return ps;
+    return 0;
+}
+
+// ABSMAX: every wave leaves the largest |value| it stored.  STATS: the per-sample, per-channel extremes of the stored
+// values x and of u = x * hardsigmoid(v x) go to p.cstats (needs the staged epilogue).
+template <int TM, int TN, int WGM, int WGN, int S, int KB, bool ABSMAX, bool STAGED, bool STATS>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmParams p) {
     constexpr int NW = WGM * WGN;
     constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
@@ -68,7 +79,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
     constexpr int LA = BM / RPI / NW, LB = BN / RPI / NW;
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "every wave issues the same number of loads");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    int *const opix_tab = reinterpret_cast<int *>(lds + S * STAGE);
+    int *const opix_tab = reinterpret_cast<int *>(lds + S * STAGE);   // output pixel of every tile row (-1: none)
+    int *const slot_tab = opix_tab + BM;                              // STATS: the row's sample, counted from the tile's first
 
     const IgemmClass &c = p.cls[blockIdx.y];
     const int nb = gridDim.x, per = nb / 8, rem = nb % 8, xcd = blockIdx.x % 8;
@@ -110,7 +122,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
         }
         aoff[j] = off;
         amask[j] = mk;
-        if (lslot == 0) opix_tab[row] = opix;
+        if (lslot == 0) {
+            opix_tab[row] = opix;
+            if (STATS) slot_tab[row] = opix >= 0 ? opix / p.pix_per_sample - m0 / p.pix_per_sample : 0;
+        }
     }
     unsigned boff[LB];
 #pragma unroll
@@ -189,6 +204,107 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
 
     // Accumulator layout of the 32x32 MFMA: a lane holds column lane%32 (a pixel) and rows 8*q + 4*(lane/32) + 0..3
     // (output channels), q = 0..3.
+    if constexpr (STAGED) {
+        // The tile goes through LDS (the operand stages are free now) as [pixel][BN + 4 words], so that the stores to
+        // global memory run along the channels: a pixel's BN results are one contiguous run instead of 16-byte pieces
+        // BN*4 bytes apart.  The scale (and the addition, out_mode 2) is applied on the way out, with the arithmetic of
+        // lpdt_dequantize.  A thread keeps one quad of channels for all its pixels, which is what lets it carry the
+        // running extremes of its four channels in registers when the layer's statistics are taken.
+        constexpr int RS = BN + 4, NT = 64 * NW, QPR = BN / 4;   // row stride in words, threads, 16-byte pieces per pixel
+        constexpr int SB = STATS ? kStatSlots * BN * 16 : 0;
+        constexpr int PASSES = staged_passes(BM, BN, WGM, S * STAGE, SB), RP = BM / PASSES;
+        static_assert(PASSES > 0, "the staged tile fits the operand stages");
+        int *const stg = reinterpret_cast<int *>(lds);
+        unsigned *const sst = reinterpret_cast<unsigned *>(lds + RP * RS * 4);   // [slot][channel of the tile][4]
+        const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
+        const int cq = t % QPR, col = n0 + cq * 4;
+        float am = 0.0f;
+        // running extremes of this thread's channels over its pixels of the current sample: x max, x min, u max, u min
+        float ex[4][4], vv[4];
+        int cur = -1;
+        if constexpr (STATS) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vv[e] = col + e < p.Cout ? p.vpar[col + e] : 0.0f;
+        }
+        auto flush = [&]() {
+            if (cur < 0) return;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                unsigned *d = sst + ((cur * BN + cq * 4 + e) << 2);
+                atomicMax(d + 0, ordered_bits(ex[e][0]));
+                atomicMax(d + 1, ~ordered_bits(ex[e][1]));
+                atomicMax(d + 2, ordered_bits(ex[e][2]));
+                atomicMax(d + 3, ~ordered_bits(ex[e][3]));
+            }
+        };
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // main loop (or the previous run's reads) done everywhere
+            if (STATS && ps == 0)
+                for (int i = t; i < kStatSlots * BN * 4; i += NT) sst[i] = 0u;
+            if (wm / (WGM / PASSES) == ps) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            *reinterpret_cast<v4i *>(stg + ((wm % (WGM / PASSES)) * TM * 32 + 32 * i + r32) * RS + (wn * TN + j) * 32 + 8 * q + 4 * half) =
+                                v4i{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (col < p.Cout) {
+#pragma unroll 4
+                for (int pr = t / QPR; pr < RP; pr += NT / QPR) {
+                    const int opix = opix_tab[ps * RP + pr];
+                    if (opix < 0) continue;
+                    const v4i sv = *reinterpret_cast<const v4i *>(stg + pr * RS + cq * 4);
+                    int32_t *dst = static_cast<int32_t *>(p.out) + (size_t)opix * p.Cout + col;
+                    if (p.out_mode) {
+                        v4f *fdst = reinterpret_cast<v4f *>(dst);
+                        const bool add = p.out_mode == 2;
+                        v4f v = {0.f, 0.f, 0.f, 0.f};
+                        if (add) v = *fdst;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = dequant_value(scale, sv[e], v[e], add);
+                        *fdst = v;
+                        if (ABSMAX) am = fmaxf(fmaxf(am, fmaxf(fabsf(v[0]), fabsf(v[1]))), fmaxf(fabsf(v[2]), fabsf(v[3])));
+                        if constexpr (STATS) {
+                            const int slot = slot_tab[ps * RP + pr];
+                            if (slot != cur) {
+                                flush();
+                                cur = slot;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) { ex[e][0] = -INFINITY; ex[e][1] = INFINITY; ex[e][2] = -INFINITY; ex[e][3] = INFINITY; }
+                            }
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float u = ren_u(v[e], vv[e]);
+                                ex[e][0] = fmaxf(ex[e][0], v[e]); ex[e][1] = fminf(ex[e][1], v[e]);
+                                ex[e][2] = fmaxf(ex[e][2], u); ex[e][3] = fminf(ex[e][3], u);
+                            }
+                        }
+                    } else *reinterpret_cast<v4i *>(dst) = sv;
+                }
+            }
+        }
+        if (ABSMAX) {
+            am = wave_max(am);
+            if (lane == 0) p.pabs[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * NW + wave] = am;
+        }
+        if constexpr (STATS) {
+            flush();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const int n_first = m0 / p.pix_per_sample;
+            const int n_last = (min(m0 + BM, c.M) - 1) / p.pix_per_sample;
+            for (int i = t; i < (n_last - n_first + 1) * BN * 4; i += NT) {
+                const unsigned k = sst[i];
+                const int ch = n0 + (i >> 2) % BN;
+                if (k && ch < p.Cout) atomicMax(p.cstats + (((size_t)(n_first + (i >> 2) / BN) * p.Cout + ch) << 2) + (i & 3), k);
+            }
+        }
+        return;
+    }
     const float scale = p.out_mode ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
     float am = 0.0f;
 #pragma unroll
@@ -232,7 +348,7 @@ constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 inline int tile_bm(int cfg) { return 32 * kTiles[cfg].TM * kTiles[cfg].WGM; }
 inline int tile_bn(int cfg) { return 32 * kTiles[cfg].TN * kTiles[cfg].WGN; }
 inline int tile_waves(int cfg) { return kTiles[cfg].WGM * kTiles[cfg].WGN; }
-inline size_t tile_lds(int cfg) { return (size_t)kTiles[cfg].S * (tile_bm(cfg) + tile_bn(cfg)) * kTiles[cfg].KB + (size_t)tile_bm(cfg) * 4; }
+inline size_t tile_lds(int cfg) { return (size_t)kTiles[cfg].S * (tile_bm(cfg) + tile_bn(cfg)) * kTiles[cfg].KB + (size_t)tile_bm(cfg) * 8; }
 
 long long tiles_of(const IgemmParams &p, int cfg) {
     long long blocks = 0;
@@ -251,8 +367,28 @@ void launch_cfg(const IgemmParams &p, dim3 grid, size_t lds, hipStream_t st) {
         }
         hipLaunchKernelGGL(kernel, grid, dim3(64 * WGM * WGN), lds, st, p);
     };
-    if (p.pabs) go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, true>);
-    else go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, false>);
+    constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN, STAGES = S * (BM + BN) * KB;
+    constexpr bool FITS = staged_passes(BM, BN, WGM, STAGES, 0) > 0;                      // the result tile can go through LDS
+    constexpr bool FITS_STATS = staged_passes(BM, BN, WGM, STAGES, kStatSlots * BN * 16) > 0;
+    bool staged = FITS;
+#ifdef LPDT_TUNE
+    if (const char *e = getenv("LPDT_DMA_EPI")) staged = FITS && atoi(e) != 0;
+#endif
+    if constexpr (FITS_STATS) {
+        if (p.cstats) {
+            go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, false, true, true>);
+            return;
+        }
+    }
+    if constexpr (FITS) {
+        if (staged) {
+            if (p.pabs) go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, true, true, false>);
+            else go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, false, true, false>);
+            return;
+        }
+    }
+    if (p.pabs) go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, true, false, false>);
+    else go(igemm_dma_kernel<TM, TN, WGM, WGN, S, KB, false, false, false>);
 }
 
 }  // namespace
@@ -295,6 +431,14 @@ bool dma_plan(IgemmParams *p, int *cfg_out, dim3 *grid) {
     *cfg_out = cfg;
     *grid = dim3((unsigned)(max_tiles_m * p->tiles_n), (unsigned)p->nclasses, 1);
     return true;
+}
+
+bool dma_stats_supported(const IgemmParams &p, int cfg) {
+    if (cfg < 0 || cfg >= kNumTiles || p.nclasses != 1 || p.out_mode == 0 || p.pix_per_sample <= 0) return false;
+    const DmaTile &tl = kTiles[cfg];
+    const int bm = tile_bm(cfg), bn = tile_bn(cfg);
+    if (staged_passes(bm, bn, tl.WGM, tl.S * (bm + bn) * tl.KB, kStatSlots * bn * 16) == 0) return false;
+    return (bm - 1) / p.pix_per_sample + 2 <= kStatSlots;   // samples a tile can touch
 }
 
 int dma_absmax_parts(int cfg, dim3 grid) { return (int)(grid.x * grid.y) * tile_waves(cfg); }

@@ -39,6 +39,12 @@ struct IgemmParams {
     int tiles_n, atomic_out, vec_out;
     int kg;                 // granules per K-step
     float *pabs;            // ABSMAX kernels: max |out| per wave, [grid.y][grid.x][4]
+    // forward products that also take the statistics of a Range-EvoNorm layer reading the result (fp32 output, one class,
+    // direct-to-LDS kernel with a staged epilogue): cstats[n][Cout][4] receives, by atomic max on ordered bit patterns,
+    // max x, ~min x, max u, ~min u per sample and channel (u = x * hardsigmoid(v x)); zero-filled before the launch
+    unsigned *cstats;
+    const float *vpar;      // the layer's v, [Cout]
+    int pix_per_sample;     // OH * OW
     int nclasses;
     IgemmClass cls[kMaxClasses];
 };
@@ -49,6 +55,9 @@ struct IgemmParams {
 // fills tiles_n and the per-class step counts and names the tile in *cfg.  dma_absmax_parts: abs-max partials that launch
 // writes (one per wave).
 bool dma_plan(IgemmParams *p, int *cfg, dim3 *grid);
+// whether the launch dma_plan chose can take the statistics (p->pix_per_sample set)
+bool dma_stats_supported(const IgemmParams &p, int cfg);
+constexpr int kStatSlots = 8;   // samples one tile may touch in a statistics launch
 int dma_absmax_parts(int cfg, dim3 grid);
 void dma_launch(const IgemmParams &p, int cfg, dim3 grid, hipStream_t st);
 

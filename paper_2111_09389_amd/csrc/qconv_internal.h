@@ -54,6 +54,22 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
 void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
                          const float *sB, hipStream_t st);
 
+// Range-EvoNorm with int8 output behind a convolution whose epilogue took the layer's statistics (range_evonorm.hip):
+// ren_chain_begin zero-fills the statistics array at the head of `ws` (ren_chain_ws_bytes, 256-byte aligned) and returns
+// it for the convolution launch; ren_chain_finish folds it and writes codes, scale, range and first arg-max / arg-min of
+// x [N,H,W,C] -- the bits of lpdt_range_evonorm_fwd_q.
+bool ren_chain_supported(int C, int groups);
+size_t ren_chain_ws_bytes(int N, int C, int groups);
+unsigned *ren_chain_begin(int N, int C, int groups, void *ws, hipStream_t st);
+void ren_chain_finish(const float *x, int N, int H, int W, int C, int groups, const float *v, const float *gamma, const float *beta,
+                      float eps, int8_t *q, float *scale, float *z, float *range_out, int32_t *argmax_out, int32_t *argmin_out,
+                      void *ws, hipStream_t st);
+// Forward product (fp32 result, out_mode 1 or 2) that also fills the statistics array; false (nothing launched) when the
+// shape does not take the kernel that can.
+bool igemm_fwd_stats_supported(const lpdt_conv_desc *d, int P, int Q);
+void launch_igemm_fwd_stats(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, const int8_t *w, float *out, int out_mode,
+                            const float *sA, const float *sB, unsigned *cstats, const float *vpar, hipStream_t st);
+
 // *out = max |x[i]| (x 16-byte aligned; scratch: absmax_scratch_floats() floats), and the fold of n ready partials alone
 int absmax_scratch_floats();
 void launch_absmax(const float *x, size_t len, float *scratch, float *out, hipStream_t st);

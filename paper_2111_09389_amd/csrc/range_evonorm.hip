@@ -25,10 +25,6 @@ __device__ __forceinline__ float hard_sigmoid(float z) { return fminf(1.0f, fmax
 // The forward value with every rounding pinned (no contraction left to the compiler): the plain and the int8-output
 // forward must produce the same bits, and the latter derives max|y| from extreme values of u, which relies on y being
 // a monotone function of u for fixed gamma, inv > 0, beta -- true of this sequence of correctly rounded operations.
-__device__ __forceinline__ float ren_u(float x, float v) {
-    const float z = __fmul_rn(v, x);
-    return __fmul_rn(x, fminf(1.0f, fmaxf(0.0f, __fmul_rn(__fadd_rn(z, 3.0f), 1.0f / 6.0f))));
-}
 __device__ __forceinline__ float ren_y(float u, float gamma, float inv, float beta) { return __fmaf_rn(__fmul_rn(gamma, u), inv, beta); }
 
 __global__ void ren_clear_kernel(unsigned long long *stats, int count, float *absmax) {
@@ -331,12 +327,63 @@ __global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsign
     block_absmax_commit(am, absmax, lds);
 }
 
+// The int8-output forward behind a convolution that took the statistics in its epilogue: cstats[n][C][4] holds, as
+// ordered bit patterns, max x, ~min x, max u, ~min u of every sample and channel.  One block per sample folds the
+// channels of a group into the group's extremes (range for the backward pass, extremes for the position search of the
+// apply pass, positions preset to INT_MAX) and evaluates y at the channels' extreme u for the exact max|y|.
+__global__ __launch_bounds__(256) void ren_cfold_kernel(RenGeom g, const unsigned *__restrict__ cstats, const float *__restrict__ gamma,
+                                                        const float *__restrict__ beta, float cm, float eps,
+                                                        float *__restrict__ range_out, float *__restrict__ gext,
+                                                        int32_t *__restrict__ argmax_out, int32_t *__restrict__ argmin_out,
+                                                        float *__restrict__ absmax) {
+    extern __shared__ unsigned sgk[];   // [groups][2] ordered max x, ~ordered min x; then float inv[groups]
+    __shared__ float lds[256 / kWave];
+    float *sinv = reinterpret_cast<float *>(sgk + 2 * g.groups);
+    const int n = blockIdx.x;
+    for (int i = threadIdx.x; i < 2 * g.groups; i += blockDim.x) sgk[i] = 0u;
+    __syncthreads();
+    const unsigned *src = cstats + (size_t)n * g.C * 4;
+    for (int c = threadIdx.x; c < g.C; c += blockDim.x) {
+        atomicMax(&sgk[(c / g.m) * 2 + 0], src[c * 4 + 0]);
+        atomicMax(&sgk[(c / g.m) * 2 + 1], src[c * 4 + 1]);
+    }
+    __syncthreads();
+    for (int grp = threadIdx.x; grp < g.groups; grp += blockDim.x) {
+        const float hi = from_ordered_bits(sgk[2 * grp]), lo = from_ordered_bits(~sgk[2 * grp + 1]);
+        const float r = __fsub_rn(hi, lo);
+        sinv[grp] = inv_denominator(r, cm, eps);
+        range_out[(size_t)n * g.groups + grp] = r;
+        gext[((size_t)n * g.groups + grp) * 2 + 0] = hi;
+        gext[((size_t)n * g.groups + grp) * 2 + 1] = lo;
+        argmax_out[(size_t)n * g.groups + grp] = 0x7fffffff;
+        argmin_out[(size_t)n * g.groups + grp] = 0x7fffffff;
+    }
+    __syncthreads();
+    float am = 0.0f;
+    for (int c = threadIdx.x; c < g.C; c += blockDim.x) {
+        const float hi = from_ordered_bits(src[c * 4 + 2]), lo = from_ordered_bits(~src[c * 4 + 3]);
+        const float inv = sinv[c / g.m], gg = gamma[c], bb = beta[c];
+        am = fmaxf(am, fmaxf(fabsf(ren_y(hi, gg, inv, bb)), fabsf(ren_y(lo, gg, inv, bb))));
+    }
+    block_absmax_commit(am, absmax, lds);
+}
+
+__global__ void ren_cstats_clear_kernel(unsigned *cstats, size_t count, float *absmax) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) cstats[i] = 0u;
+    if (i == 0) *absmax = 0.0f;
+}
+
 // Third launch: y as the plain forward computes it, rounded to the nearest code with the scale max|y| / 127.
 __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__restrict__ x, RenGeom g, const float *__restrict__ v,
                                                                 const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                 float cm, float eps, const float *__restrict__ range,
                                                                 const float *__restrict__ absmax, int8_t *__restrict__ q,
-                                                                float *__restrict__ scale, float *__restrict__ y) {
+                                                                float *__restrict__ scale, float *__restrict__ y,
+                                                                const float *__restrict__ gext, int32_t *__restrict__ argmax,
+                                                                int32_t *__restrict__ argmin) {
+    // gext != NULL: the extremes of every (sample, group) are known ([n][group][max, min]) but not where they sit: every
+    // element equal to one reports its position, the lowest wins (argmax / argmin start at INT_MAX)
     const int n = blockIdx.y;
     const float a = *absmax;
     if (blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *scale = quant_scale(a);
@@ -350,6 +397,14 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
         const int c = qd * 4 + e;
         vv[e] = v[c]; gg[e] = gamma[c]; bb[e] = beta[c];
         inv[e] = inv_denominator(range[(size_t)n * g.groups + c / g.m], cm, eps);
+    }
+    float hi[4] = {0.f, 0.f, 0.f, 0.f}, lo[4] = {0.f, 0.f, 0.f, 0.f};
+    if (gext) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            hi[e] = gext[((size_t)n * g.groups + (qd * 4 + e) / g.m) * 2 + 0];
+            lo[e] = gext[((size_t)n * g.groups + (qd * 4 + e) / g.m) * 2 + 1];
+        }
     }
     const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * g.HW * g.C);
     uint32_t *qv = reinterpret_cast<uint32_t *>(q + (size_t)n * g.HW * g.C);
@@ -371,6 +426,11 @@ __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__r
             for (int e = 0; e < 4; ++e) {
                 o[e] = ren_y(ren_u(xe[e], vv[e]), gg[e], inv[e], bb[e]);
                 word |= ((uint32_t)round_code(o[e], qinv, false, 0u) & 0xffu) << (8 * e);
+                if (gext) {
+                    const int c = qd * 4 + e;
+                    if (xe[e] == hi[e]) atomicMin(&argmax[(size_t)n * g.groups + c / g.m], p * g.m + c % g.m);
+                    if (xe[e] == lo[e]) atomicMin(&argmin[(size_t)n * g.groups + c / g.m], p * g.m + c % g.m);
+                }
             }
             qv[(size_t)p * g.cq + qd] = word;
             if (y) reinterpret_cast<float4 *>(y + (size_t)n * g.HW * g.C)[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
@@ -773,6 +833,34 @@ static float ren_cm(int m) { return (float)(1.0 / std::sqrt(2.0 * std::log((doub
 constexpr int kGenericElems = 8192;
 constexpr int kGenericPix = 64;
 
+
+// ---- the normalisation behind a convolution that took its statistics (see qconv_internal.h) ----
+bool ren_chain_supported(int C, int groups) { return groups > 0 && C % groups == 0 && C / groups >= 2 && C % 4 == 0 && C / 4 <= kRThreads; }
+size_t ren_chain_ws_bytes(int N, int C, int groups) {
+    return round_up((size_t)N * C * 4 * sizeof(unsigned), 256) + round_up((size_t)N * groups * 2 * sizeof(float), 256) + 256;
+}
+static float ren_cm_of(int m) { return (float)(1.0 / std::sqrt(2.0 * std::log((double)m))); }
+unsigned *ren_chain_begin(int N, int C, int groups, void *ws, hipStream_t st) {
+    unsigned *cstats = static_cast<unsigned *>(ws);
+    float *absmax = reinterpret_cast<float *>(static_cast<char *>(ws) + ren_chain_ws_bytes(N, C, groups) - 256);
+    const size_t count = (size_t)N * C * 4;
+    hipLaunchKernelGGL(ren_cstats_clear_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, cstats, count, absmax);
+    return cstats;
+}
+void ren_chain_finish(const float *x, int N, int H, int W, int C, int groups, const float *v, const float *gamma, const float *beta,
+                      float eps, int8_t *q, float *scale, float *z, float *range_out, int32_t *argmax_out, int32_t *argmin_out,
+                      void *ws, hipStream_t st) {
+    const unsigned *cstats = static_cast<const unsigned *>(ws);
+    float *gext = reinterpret_cast<float *>(static_cast<char *>(ws) + round_up((size_t)N * C * 4 * sizeof(unsigned), 256));
+    float *absmax = reinterpret_cast<float *>(static_cast<char *>(ws) + ren_chain_ws_bytes(N, C, groups) - 256);
+    const float cm = ren_cm_of(C / groups);
+    const RenGeom ga = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kApplyElems));
+    hipLaunchKernelGGL(ren_cfold_kernel, dim3(N), dim3(256), (size_t)2 * groups * sizeof(unsigned) + groups * sizeof(float), st, ga, cstats,
+                       gamma, beta, cm, eps, range_out, gext, argmax_out, argmin_out, absmax);
+    hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out, absmax, q,
+                       scale, z, gext, argmax_out, argmin_out);
+}
+
 }  // namespace lpdt
 
 using namespace lpdt;
@@ -825,7 +913,7 @@ extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int
     hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), key_lds + groups * sizeof(float) + (size_t)2 * C * sizeof(unsigned int), st, g, keys, pu, gamma, beta, cm, eps,
                        range_out, argmax_out, argmin_out, absmax);
     hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out,
-                       absmax, q, scale, y);
+                       absmax, q, scale, y, nullptr, nullptr, nullptr);
     return launch_status("lpdt_range_evonorm_fwd_q");
 }
 

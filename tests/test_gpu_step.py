@@ -310,6 +310,32 @@ def test_driver_fused_stem_changes_no_bit(orc):
     assert all(torch.equal(a, b) for a, b in zip(*out))
 
 
+def test_driver_conv_norm_chain_changes_no_bit():
+    """ResNet-18 at a batch where the 128-channel stage takes lpdt_qconv_ren_fwd_q's fused form: the step planned with the
+    chain calls against the default plan of separate calls -- identical gradients, parameters and loss."""
+    from paper_2111_09389_amd.step import TrainStep
+    net = nets.resnet18()
+    N = 16
+    params = nets.init_params(net, wl.BASE_SEED + 62)
+    flat = np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32)
+    H, W, C = net.in_shape
+    x = dev(wl.images(wl.BASE_SEED + 63, N, H, W, C))
+    lb = dev(wl.labels_uniform(wl.BASE_SEED + 64, N, net.classes))
+    out = []
+    for chain in (True, False):
+        p, g = dev(flat), torch.zeros(flat.size, dtype=torch.float32, device="cuda")
+        ts = TrainStep(net, N, p, g, x, lb, None, lr=0.05, seed=wl.PHILOX_SEED, fuse_conv_ren=chain)
+        calls = [c for c in ts.calls if c[0] is not None and c[0].__name__ == "lpdt_qconv_ren_fwd_q"]
+        assert (len(calls) > 0) == chain
+        if chain:   # with and without the skip connection in the epilogue, with and without the fp32 normalised output
+            assert {c[1][5] for c in calls} == {0, 1} and len({c[1][12].value is None for c in calls}) == 2
+        ts.run(1)
+        torch.cuda.synchronize()
+        out.append((g.clone(), p.clone(), ts.loss.clone()))
+        del ts
+    assert all(torch.equal(a, b) for a, b in zip(*out))
+
+
 def test_driver_prepacked_filters_change_no_bit(orc):
     """Backward-data's transposed filters made once per step on the second stream (default) against the driver that lets
     every backward-data call transpose its own: identical gradients, parameters and loss, over two steps."""
