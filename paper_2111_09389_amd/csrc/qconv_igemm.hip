@@ -395,6 +395,10 @@ dim3 drop_empty_classes(IgemmParams &p, dim3 grid) {
 void run(IgemmParams &p, size_t out_len, hipStream_t st) {
     int cfg;
     dim3 dgrid;
+    if (patch_plan(p)) {
+        patch_launch(p, st);
+        return;
+    }
     if (dma_plan(&p, &cfg, &dgrid)) {
         dgrid = drop_empty_classes(p, dgrid);
         if (dgrid.y > 0) dma_launch(p, cfg, dgrid, st);
@@ -529,17 +533,18 @@ static bool plan_is_split(IgemmParams &p) {
     int cfg;
     dim3 dgrid;
     p.vec_out = p.Cout % 4 == 0;
-    if (dma_plan(&p, &cfg, &dgrid)) return false;
+    if (patch_plan(p) || dma_plan(&p, &cfg, &dgrid)) return false;
     finish_plan(&p, pick_tile(p), true);
     return p.atomic_out != 0;
 }
 
-// 20 + tile of the direct-to-LDS kernel, or 10 + variant of the register-staged one (0: 128 x 32, 1: 64 x 64 with 4-granule
+// 50: the filter-resident row-tile kernel; 20 + tile of the direct-to-LDS kernel, or 10 + variant of the register-staged one (0: 128 x 32, 1: 64 x 64 with 4-granule
 // steps, 2: 64 x 64 with 8, 3: 128 x 64 with 4, 4: 128 x 64 with 8), + 100 when the reduction is split over blocks
 static int plan_kernel_id(IgemmParams &p) {
     int cfg;
     dim3 dgrid;
     p.vec_out = p.Cout % 4 == 0;
+    if (patch_plan(p)) return 50;
     if (dma_plan(&p, &cfg, &dgrid)) return 20 + cfg;
     const Tile tl = pick_tile(p);
     finish_plan(&p, tl, true);

@@ -61,4 +61,9 @@ constexpr int kStatSlots = 8;   // samples one tile may touch in a statistics la
 int dma_absmax_parts(int cfg, dim3 grid);
 void dma_launch(const IgemmParams &p, int cfg, dim3 grid, hipStream_t st);
 
+// The kernel that keeps the whole filter in LDS and walks over row tiles (qconv_patch.hip): stride-1 layers with 64
+// reduction channels and at most 64 result channels.  patch_plan: whether the launch (out_mode, pabs, cstats set) takes it.
+bool patch_plan(const IgemmParams &p);
+void patch_launch(const IgemmParams &p, hipStream_t st);
+
 }  // namespace lpdt

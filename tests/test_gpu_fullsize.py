@@ -47,10 +47,10 @@ LAYERS = {   # N C H W K R S stride pad
 # lpdt_qconv_kernel_id of (forward, backward-data, backward-weight) at these sizes: the kernels and tiles bench.py times.
 # 1: first-layer kernels (narrow_fwd_kernel / narrow_wgrad_kernel); 10..14 (+100: split reduction): igemm_kernel
 # <128,32,4>, <64,64,4>, <64,64,8>, <128,64,4>, <128,64,8>; 20..23: igemm_dma_kernel 256x256, 128x128 (8 waves), 128x128
-# (4 waves), 64x128; 30 + t + 4*[64-pixel steps] + 8*[two wave groups]: wgrad_rect_kernel with tile t (0: 32x64, 1: 64x64);
+# (4 waves), 64x128; 50: patch_conv_kernel (filter resident in LDS, row tiles); 30 + t + 4*[64-pixel steps] + 8*[two wave groups]: wgrad_rect_kernel with tile t (0: 32x64, 1: 64x64);
 # 2: wgrad_kernel; 3: linear_small_kernel; 0: the any-shape kernels.
 KERNELS = {
-    "stem 7x7 s2": (1, 10, 1), "layer1 3x3": (13, 13, 42), "layer2 3x3 s2": (22, 13, 38), "layer2 1x1 s2": (22, 13, 31),
+    "stem 7x7 s2": (1, 10, 1), "layer1 3x3": (50, 50, 42), "layer2 3x3 s2": (22, 13, 38), "layer2 1x1 s2": (22, 13, 31),
     "layer2 3x3": (22, 22, 42), "layer3 3x3 s2": (21, 22, 38), "layer3 1x1 s2": (21, 22, 31), "layer3 3x3": (21, 21, 42),
     "layer4 3x3 s2": (23, 21, 38), "layer4 1x1 s2": (23, 21, 31), "layer4 3x3": (23, 23, 38), "classifier": (3, 3, 3),
     "resnet20 first": (1, 10, 1), "resnet20 16": (10, 10, 42), "resnet20 64": (111, 111, 42), "vgg11 first": (1, 10, 1),

@@ -53,6 +53,33 @@ def test_three_convs_bit_exact(orc, shp, kind):
     assert np.array_equal(host(dw), orc.qconv_bwd_weight(od, g, x)), "backward-weight"
 
 
+# stride-1 layers with 64 reduction channels and at most 64 result channels, enough row tiles to fill the chip: the
+# filter-resident row-tile kernel (lpdt_qconv_kernel_id 50) -- paddings 0/1/2, ragged last tiles, maps from 14 to 120 wide,
+# 2x2 / 3x1 / 3x3 filters, fewer than 64 result channels
+ROW_TILE_CASES = [(10, 64, 56, 56, 64, 3, 3, 1, 1), (40, 64, 30, 30, 64, 3, 3, 1, 0), (14, 64, 57, 41, 48, 3, 3, 1, 1),
+                  (40, 64, 28, 28, 64, 3, 3, 1, 1), (130, 64, 14, 14, 64, 3, 3, 1, 1), (9, 64, 64, 64, 32, 3, 1, 1, 0),
+                  (3, 64, 100, 120, 64, 2, 2, 1, 0), (11, 64, 50, 50, 64, 3, 3, 1, 2)]
+
+
+@pytest.mark.parametrize("shp", ROW_TILE_CASES)
+def test_row_tile_kernel_bit_exact(orc, shp):
+    x, w, g = _data(shp, 700, "uniform")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert lpdt.qconv_kernel_id(ld, 0) == 50, "the planner changed: pick shapes that reach the row-tile kernel"
+    print("row tiles", shp, flush=True)
+    assert np.array_equal(host(lpdt.qconv_fwd(ld, dev(x), dev(w))), orc.qconv_fwd(od, x, w)), "forward"
+    if shp[4] == 64:
+        assert lpdt.qconv_kernel_id(ld, 1) == 50
+        ref = orc.qconv_bwd_data(od, g, w)
+        assert np.array_equal(host(lpdt.qconv_bwd_data(ld, dev(g), dev(w))), ref), "backward-data"
+        # fused scale and accumulation into an existing gradient
+        sa, sb = dev(np.array([0.017], np.float32)), dev(np.array([0.0021], np.float32))
+        base = dev(wl.images(701, *ref.shape))
+        want = lpdt.dequantize(dev(ref.astype(np.int32)), sa, sb, y=base.clone(), accumulate=True)
+        got = lpdt.qconv_bwd_data_f32(ld, dev(g), dev(w), sa, sb, dx=base.clone(), accumulate=True)
+        assert torch.equal(got, want), "backward-data, fused scale, accumulated"
+
+
 def test_extreme_codes_no_overflow_in_range(orc):
     # all +-127 with reduction length 4608 (fwd) / 1152 (wgrad): the largest magnitudes the path can see here
     shp = (2, 512, 6, 6, 64, 3, 3, 1, 1)
