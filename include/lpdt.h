@@ -156,7 +156,10 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
  *   50  forward / backward-data of stride-1 layers with 64 reduction channels and at most 64 result channels: the
  *       whole filter stays in LDS, tiles of whole output rows, each input patch loaded once for all taps
  *   30 + t + 4*[64-pixel steps] + 8*[two wave groups per block]  rectangle-stepped backward-weight, t = 0: 32 x 64,
- *       1: 64 x 64, 2: 128 x 128 channel tile */
+ *       1: 64 x 64, 2: 128 x 128 channel tile
+ *   60  backward-weight of stride-1 layers with filters of up to 3 x 3 taps (output channels a multiple of 32, input
+ *       channels of 64): tiles of whole output rows, gradient and input patch loaded straight into LDS, all taps
+ *       read out of the one patch */
 int lpdt_qconv_kernel_id(const lpdt_conv_desc *d, int product);
 
 /* The same three products with the dequantizing scale applied in the kernel epilogue: the result

@@ -607,7 +607,9 @@ static bool wgrad_uses_rect(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan
 static size_t bwd_weight_base_ws(const lpdt_conv_desc *d0, int P, int Q) {
     const lpdt_conv_desc view = wgrad_view(d0, &P, &Q), *d = &view;
     WgradRectPlan pl;
+    WgradRowsPlan rows;
     if (narrow_conv_supported(d, P, Q)) return round_up(narrow_wgrad_workspace(d), 256);
+    if (wgrad_rows_plan(d, P, Q, &rows)) return rows.partial_bytes;
     if (wgrad_rect_plan(d, P, Q, &pl)) return pl.partial_bytes;
     return 0;
 }
@@ -622,6 +624,11 @@ static void conv_bwd_weight_impl(const lpdt_conv_desc *d0, int P, int Q, const i
     const size_t wlen = (size_t)d->K * d->R * d->S * d->C;
     const long long M = (long long)d->N * P * Q;
     WgradRectPlan pl;
+    WgradRowsPlan rows;
+    if (aligned(gq, 16) && aligned(xq, 16) && !narrow_conv_supported(d, P, Q) && wgrad_rows_plan(d, P, Q, &rows)) {
+        launch_wgrad_rows(d, P, Q, rows, gq, xq, out, out_mode, sA, sB, ws, st);
+        return;
+    }
     if (aligned(gq, 16) && aligned(xq, 16) && wgrad_uses_rect(d, P, Q, &pl)) {
         launch_wgrad_rect(d, P, Q, pl, gq, xq, out, out_mode, sA, sB, ws, st);
         return;
@@ -764,6 +771,8 @@ extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
     if (product == 1) return bwd_data_vec(d0, P, Q) ? igemm_bwd_data_kernel_id(d0, P, Q) : 0;
     const lpdt_conv_desc view = wgrad_view(d0, &P, &Q), *d = &view;
     WgradRectPlan pl;
+    WgradRowsPlan rows;
+    if (!narrow_conv_supported(d, P, Q) && wgrad_rows_plan(d, P, Q, &rows)) return 60;  // row-tile kernel
     if (wgrad_uses_rect(d, P, Q, &pl)) {
         // 30 + tile (0: 32 x 64, 1: 64 x 64, 2: 128 x 128) + 4 for 64-pixel steps + 8 for two wave groups per block
         return 30 + (pl.kt == 128 ? 2 : pl.kt == 64 ? 1 : 0) + (pl.ks == 2 ? 4 : 0) + (pl.ng == 2 ? 8 : 0);

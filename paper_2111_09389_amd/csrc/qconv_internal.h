@@ -50,6 +50,16 @@ bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *plan)
 void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPlan &plan, const int8_t *g, const int8_t *x,
                        void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
 
+// Row-tile variant for stride-1 filters of up to 3 x 3 taps (qconv_wgrad_rows.hip): same contract, same reduction kernel
+struct WgradRowsPlan {
+    int kt, stages, TR, PR, PW, ni, nkg, tiles_per_image, ntiles, tiles_per_split, splits, tiles_k, tiles_kc;
+    long long out_len;
+    size_t partial_bytes, lds;
+};
+bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *plan);
+void launch_wgrad_rows(const lpdt_conv_desc *d, int P, int Q, const WgradRowsPlan &plan, const int8_t *g, const int8_t *x,
+                       void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
+
 // out[i] = sum over `splits` copies partial[z][i] (out_len a multiple of 4), as int32 or as fp32 times sA*sB
 void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
                          const float *sB, hipStream_t st);

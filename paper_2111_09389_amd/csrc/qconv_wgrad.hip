@@ -11,6 +11,9 @@
 // dequantizing scale when asked.  No atomics, no zero fill, bit-reproducible.
 #include "qconv_internal.h"
 #include <type_traits>
+#ifdef LPDT_TUNE
+#include <cstdlib>
+#endif
 
 namespace lpdt {
 
@@ -269,31 +272,38 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void wgrad_rect_kernel(c
 }
 
 // out[i] = sum over splits of partial[z][i] (exact integers: any order gives the same bits); as int32, or as fp32
-// times the scale product.  A block covers 128 outputs (4 per thread: 16-byte loads, 512 contiguous bytes per split)
-// with 8 split lanes, so that the loads of one sum run in parallel.  out_len is a multiple of 4 (K, C multiples of 16).
+// times the scale product.  A block covers 256/ZL groups of 4 outputs (16-byte loads) with ZL split lanes each, so that
+// the loads of one sum run in parallel; ZL follows the number of splits (few splits: every thread walks them all and a
+// block covers 4 KiB of every partial tile; hundreds: 32 lanes, each with a handful of loads in flight).
+// out_len is a multiple of 4 (K, C multiples of 16).
+template <int ZL>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const int32_t *__restrict__ partial, long long out_len, int splits,
                                                            int32_t *__restrict__ out, int out_mode, const float *sA,
                                                            const float *sB) {
-    __shared__ v4i sm[8][32];
-    const int o = threadIdx.x % 32, zl = threadIdx.x / 32;
-    const long long i = ((long long)blockIdx.x * 32 + o) * 4;
+    constexpr int QB = 256 / ZL;
+    __shared__ v4i sm[ZL][QB];
+    const int o = threadIdx.x % QB, zl = threadIdx.x / QB;
+    const long long i = ((long long)blockIdx.x * QB + o) * 4;
     v4i s0 = {0, 0, 0, 0}, s1 = s0, s2 = s0, s3 = s0;
     if (i < out_len) {
         int z = zl;
-        for (; z + 24 < splits; z += 32) {
+        for (; z + 3 * ZL < splits; z += 4 * ZL) {
             s0 += *reinterpret_cast<const v4i *>(partial + (size_t)z * out_len + i);
-            s1 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 8) * out_len + i);
-            s2 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 16) * out_len + i);
-            s3 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 24) * out_len + i);
+            s1 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + ZL) * out_len + i);
+            s2 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 2 * ZL) * out_len + i);
+            s3 += *reinterpret_cast<const v4i *>(partial + (size_t)(z + 3 * ZL) * out_len + i);
         }
-        for (; z < splits; z += 8) s0 += *reinterpret_cast<const v4i *>(partial + (size_t)z * out_len + i);
+        for (; z < splits; z += ZL) s0 += *reinterpret_cast<const v4i *>(partial + (size_t)z * out_len + i);
     }
-    sm[zl][o] = s0 + s1 + s2 + s3;
-    __syncthreads();
-    if (zl == 0 && i < out_len) {
-        v4i s = {0, 0, 0, 0};
+    v4i s = s0 + s1 + s2 + s3;
+    if constexpr (ZL > 1) {
+        sm[zl][o] = s;
+        __syncthreads();
+        if (zl != 0) return;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) s += sm[k][o];
+        for (int k = 1; k < ZL; ++k) s += sm[k][o];
+    }
+    if (i < out_len) {
         if (out_mode) {
             const float sc = __fmul_rn(*sA, *sB);
             float *f = reinterpret_cast<float *>(out) + i;
@@ -346,7 +356,11 @@ static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradR
     pl->tiles_k = (d->K + pl->kt - 1) / pl->kt;
     pl->tiles_c = (d->C + pl->ct - 1) / pl->ct;
     const long long base = (long long)pl->tiles_k * pl->tiles_c * pl->groups;
-    long long splits = (512 + base - 1) / base;
+    long long target = 512;
+#ifdef LPDT_TUNE
+    if (const char *e = getenv("LPDT_WGRAD_BLOCKS")) target = atoi(e);
+#endif
+    long long splits = (target + base - 1) / base;
     if (splits > steps / 4) splits = steps / 4;
     if (splits < 1) splits = 1;
     pl->steps_per_split = (int)((steps + splits - 1) / splits);
@@ -402,9 +416,19 @@ void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPla
 
 void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
                          const float *sB, hipStream_t st) {
-    const long long rb = (out_len / 4 + 31) / 32;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)rb), dim3(256), 0, st, partial, out_len, splits,
-                       static_cast<int32_t *>(out), out_mode, sA, sB);
+    int zl = splits >= 64 ? 32 : splits >= 16 ? 8 : splits >= 8 ? 4 : 1;
+#ifdef LPDT_TUNE
+    if (const char *e = getenv("LPDT_REDUCE_ZL")) zl = atoi(e);
+#endif
+    const long long quads = out_len / 4;
+    auto go = [&](auto kernel, int z) {
+        const long long rb = (quads + 256 / z - 1) / (256 / z);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)rb), dim3(256), 0, st, partial, out_len, splits, static_cast<int32_t *>(out), out_mode, sA, sB);
+    };
+    if (zl >= 32) go(wgrad_reduce_kernel<32>, 32);
+    else if (zl >= 8) go(wgrad_reduce_kernel<8>, 8);
+    else if (zl >= 4) go(wgrad_reduce_kernel<4>, 4);
+    else go(wgrad_reduce_kernel<1>, 1);
 }
 
 }  // namespace lpdt
