@@ -316,8 +316,9 @@ def measure(cfg_id, nsteps, warmup, use_graph, device, detail=True, entry_points
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": achieved / INT8_PEAK_TOPS, "traffic": measured_conv_traffic(cfg_id),
                      "algorithmic_bytes": conv_algorithmic_bytes(net, cfg["batch"]) * len(steps),
-                     "kernel": "all kernels behind the three conv entry points of one step (igemm_dma_kernel, igemm_kernel, "
-                               "wgrad_rect_kernel + wgrad_reduce_kernel, narrow_*_kernel, filter packing): conv ops / summed duration; "
+                     "kernel": "all kernels behind the three conv entry points of one step (patch_conv_kernel, igemm_dma_kernel, "
+                               "igemm_kernel, wgrad_rows_kernel / wgrad_rect_kernel + wgrad_reduce_kernel, narrow_*_kernel, "
+                               "linear_small_kernel, filter packing): conv ops / summed duration; "
                                "traffic and algorithmic_bytes are per step like achieved"},
     }
     if detail:
