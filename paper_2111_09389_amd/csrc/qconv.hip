@@ -257,17 +257,31 @@ __global__ __launch_bounds__(kCThreads) void linear_small_kernel(const int8_t *_
     if (KIND == 0) {
         const int m = o / K, k = o - m * K;
         const int8_t *xp = a + (size_t)m * C, *wp = b + (size_t)k * C;
+        // the loops are chains of dependent-free loads: unrolled so that several are in flight (a thread's whole time is
+        // load latency), 16 bytes per load where the rows allow it
         int c = 0;
-        if (C % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 3) == 0)
+        if (C % 16 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0) {
+            typedef int v4i_t __attribute__((ext_vector_type(4)));
+#pragma unroll 4
+            for (; c < C; c += 16) {
+                const v4i_t xv = *reinterpret_cast<const v4i_t *>(xp + c), wv = *reinterpret_cast<const v4i_t *>(wp + c);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s = __builtin_amdgcn_sdot4(xv[e], wv[e], s, false);
+            }
+        } else if (C % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 3) == 0) {
+#pragma unroll 8
             for (; c < C; c += 4)
                 s = __builtin_amdgcn_sdot4(*reinterpret_cast<const int *>(xp + c), *reinterpret_cast<const int *>(wp + c), s, false);
+        }
         for (; c < C; ++c) s += (int)xp[c] * (int)wp[c];
     } else if (KIND == 1) {
         const int m = o / C, c = o - m * C;
         const int8_t *gp = a + (size_t)m * K;
+#pragma unroll 8
         for (int k = 0; k < K; ++k) s += (int)gp[k] * (int)b[(size_t)k * C + c];
     } else {
         const int k = o / C, c = o - k * C;
+#pragma unroll 8
         for (int m = 0; m < rows; ++m) s += (int)a[(size_t)m * K + k] * (int)b[(size_t)m * C + c];
     }
     if (mode == 0) static_cast<int32_t *>(out)[o] = s;

@@ -18,6 +18,9 @@
 #include "common.h"
 #include "norm_geom.h"
 #include <cmath>
+#ifdef LPDT_TUNE
+#include <cstdlib>
+#endif
 
 namespace lpdt {
 
@@ -327,6 +330,88 @@ __global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsign
     block_absmax_commit(am, absmax, lds);
 }
 
+// First and second launch in one for small samples (the late layers: a sample of 25-100 K elements): one block of
+// kSampleThreads threads walks its whole sample, so the sample's fold needs no second launch.  The three launches of
+// such a layer are bound by launch latency, not by bytes.  The sample's max|y| goes to sample_abs[n] (a plain store: no
+// array to clear first); the pass that emits the codes takes the maximum over the samples.  Same arithmetic and the same
+// order-free reductions (maxima of keys) as ren_stats_kernel<true> + ren_q_fold_kernel: same bits.
+constexpr int kSampleThreads = 1024;
+constexpr int kSampleRU = 8;      // pixels a thread has in flight
+__global__ __launch_bounds__(kSampleThreads) void ren_sample_kernel(const float *__restrict__ x, int HW, int C, int groups, int m,
+                                                                     const float *__restrict__ vpar, const float *__restrict__ gamma,
+                                                                     const float *__restrict__ beta, float cm, float eps,
+                                                                     float *__restrict__ range_out, int32_t *__restrict__ argmax_out,
+                                                                     int32_t *__restrict__ argmin_out, float *__restrict__ sample_abs) {
+    extern __shared__ unsigned long long skeys[];  // [groups][2], then float inv[groups], then unsigned su[C][2]
+    __shared__ float lds[kSampleThreads / kWave];
+    float *sinv = reinterpret_cast<float *>(skeys + 2 * groups);
+    unsigned int *su = reinterpret_cast<unsigned int *>(sinv + groups);
+    const int n = blockIdx.x, cq = C / 4;
+    for (int i = threadIdx.x; i < 2 * groups; i += blockDim.x) skeys[i] = 0ull;
+    for (int i = threadIdx.x; i < 2 * C; i += blockDim.x) su[i] = 0u;
+    __syncthreads();
+    const int ppi = kSampleThreads / cq;            // pixels per round of the block; threads past ppi * cq only join the barriers
+    const int qd = threadIdx.x % cq, pl = threadIdx.x / cq;
+    if (pl < ppi) {
+        float mx[4], mn[4], umx[4], umn[4], vv[4];
+        int imx[4], imn[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            imx[e] = -1; imn[e] = -1; mx[e] = 0.f; mn[e] = 0.f;
+            umx[e] = -INFINITY; umn[e] = INFINITY; vv[e] = vpar[qd * 4 + e];
+        }
+        const float4 *xv = reinterpret_cast<const float4 *>(x + (size_t)n * HW * C);
+        for (int pb = pl; pb < HW; pb += kSampleRU * ppi) {
+            float4 a[kSampleRU];
+#pragma unroll
+            for (int u = 0; u < kSampleRU; ++u) {
+                const int p = pb + u * ppi;
+                a[u] = p < HW ? xv[(size_t)p * cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < kSampleRU; ++u) {
+                const int p = pb + u * ppi;
+                if (p >= HW) break;
+                const float v[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (imx[e] < 0 || v[e] > mx[e]) { mx[e] = v[e]; imx[e] = p; }
+                    if (imn[e] < 0 || v[e] < mn[e]) { mn[e] = v[e]; imn[e] = p; }
+                    const float uu = ren_u(v[e], vv[e]);
+                    umx[e] = fmaxf(umx[e], uu); umn[e] = fminf(umn[e], uu);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (imx[e] < 0) continue;
+            const int c = qd * 4 + e, grp = c / m, cc = c % m;
+            const uint32_t lo_mx = ~(uint32_t)(imx[e] * m + cc), lo_mn = ~(uint32_t)(imn[e] * m + cc);
+            atomicMax(&skeys[grp * 2 + 0], ((unsigned long long)ordered_bits(mx[e]) << 32) | lo_mx);
+            atomicMax(&skeys[grp * 2 + 1], ((unsigned long long)(~ordered_bits(mn[e])) << 32) | lo_mn);
+            atomicMax(&su[c * 2 + 0], ordered_bits(umx[e]));
+            atomicMax(&su[c * 2 + 1], ~ordered_bits(umn[e]));
+        }
+    }
+    __syncthreads();
+    for (int grp = threadIdx.x; grp < groups; grp += blockDim.x) {
+        const unsigned long long kmx = skeys[2 * grp], kmn = skeys[2 * grp + 1];
+        const float r = __fsub_rn(from_ordered_bits((uint32_t)(kmx >> 32)), from_ordered_bits(~(uint32_t)(kmn >> 32)));
+        sinv[grp] = inv_denominator(r, cm, eps);
+        range_out[(size_t)n * groups + grp] = r;
+        argmax_out[(size_t)n * groups + grp] = (int32_t)(~(uint32_t)kmx);
+        argmin_out[(size_t)n * groups + grp] = (int32_t)(~(uint32_t)kmn);
+    }
+    __syncthreads();
+    float am = 0.0f;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        const float hi = from_ordered_bits(su[c * 2 + 0]), lo = from_ordered_bits(~su[c * 2 + 1]);
+        const float inv = sinv[c / m], gg = gamma[c], bb = beta[c];
+        am = fmaxf(am, fmaxf(fabsf(ren_y(hi, gg, inv, bb)), fabsf(ren_y(lo, gg, inv, bb))));
+    }
+    block_absmax_store(am, sample_abs + n, lds);
+}
+
 // The int8-output forward behind a convolution that took the statistics in its epilogue: cstats[n][C][4] holds, as
 // ordered bit patterns, max x, ~min x, max u, ~min u of every sample and channel.  One block per sample folds the
 // channels of a group into the group's extremes (range for the backward pass, extremes for the position search of the
@@ -378,14 +463,17 @@ __global__ void ren_cstats_clear_kernel(unsigned *cstats, size_t count, float *a
 __global__ __launch_bounds__(kRThreads) void ren_apply_q_kernel(const float *__restrict__ x, RenGeom g, const float *__restrict__ v,
                                                                 const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                 float cm, float eps, const float *__restrict__ range,
-                                                                const float *__restrict__ absmax, int8_t *__restrict__ q,
+                                                                const float *__restrict__ absmax, int nabs, int8_t *__restrict__ q,
                                                                 float *__restrict__ scale, float *__restrict__ y,
                                                                 const float *__restrict__ gext, int32_t *__restrict__ argmax,
                                                                 int32_t *__restrict__ argmin) {
     // gext != NULL: the extremes of every (sample, group) are known ([n][group][max, min]) but not where they sit: every
     // element equal to one reports its position, the lowest wins (argmax / argmin start at INT_MAX)
+    // absmax: max|y| of the tensor, or (nabs > 1) of every sample: the same addresses for all threads, loads in flight together
     const int n = blockIdx.y;
-    const float a = *absmax;
+    float a = absmax[0];
+#pragma unroll 8
+    for (int i = 1; i < nabs; ++i) a = fmaxf(a, absmax[i]);
     if (blockIdx.x == 0 && n == 0 && threadIdx.x == 0) *scale = quant_scale(a);
     if ((int)threadIdx.x >= g.threads) return;
     const float qinv = quant_inv(a);
@@ -857,7 +945,7 @@ void ren_chain_finish(const float *x, int N, int H, int W, int C, int groups, co
     const RenGeom ga = ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kApplyElems));
     hipLaunchKernelGGL(ren_cfold_kernel, dim3(N), dim3(256), (size_t)2 * groups * sizeof(unsigned) + groups * sizeof(float), st, ga, cstats,
                        gamma, beta, cm, eps, range_out, gext, argmax_out, argmin_out, absmax);
-    hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out, absmax, q,
+    hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out, absmax, 1, q,
                        scale, z, gext, argmax_out, argmin_out);
 }
 
@@ -874,6 +962,16 @@ extern "C" size_t lpdt_range_evonorm_fwd_workspace_bytes(int N, int H, int W, in
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || groups <= 0 || C % groups) return 0;
     const size_t blocks = ren_fast(C) ? (size_t)N * ren_geom(N, H, W, C, groups, 0, block_cap(N, H, W, C, kStatsElems)).chunks : (size_t)N;
     return round_up(blocks * groups * 2 * sizeof(unsigned long long), 256);
+}
+
+// Samples small enough for the one-block-per-sample statistics (ren_sample_kernel); the keys' room (at least 256 bytes
+// per sample: 2 keys per group and block) also holds its N floats.
+static bool ren_sample_path(int N, int H, int W, int C) {
+    long long limit = 64 * 1024;
+#ifdef LPDT_TUNE
+    if (const char *e = getenv("LPDT_REN_SAMPLE_ELEMS")) limit = atoll(e);
+#endif
+    return (long long)H * W * C <= limit && C / 4 <= kSampleThreads && N <= 4096;
 }
 
 // int8-output forward: block keys, then the per-block channel extremes of u, then the scalar max|y|
@@ -908,12 +1006,21 @@ extern "C" int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int
     float *pu = reinterpret_cast<float *>(static_cast<char *>(ws) + ren_q_key_bytes(g));
     float *absmax = reinterpret_cast<float *>(static_cast<char *>(ws) + ren_q_key_bytes(g) + ren_q_u_bytes(g));
     const size_t key_lds = (size_t)2 * groups * sizeof(unsigned long long);
+    const size_t fold_lds = key_lds + groups * sizeof(float) + (size_t)2 * C * sizeof(unsigned int);
+    if (ren_sample_path(N, H, W, C)) {
+        float *sample_abs = static_cast<float *>(ws);     // [N]: fits the room of the block keys it replaces
+        hipLaunchKernelGGL(ren_sample_kernel, dim3(N), dim3(kSampleThreads), fold_lds, st, x, H * W, C, groups, C / groups, v, gamma, beta,
+                           cm, eps, range_out, argmax_out, argmin_out, sample_abs);
+        hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out,
+                           sample_abs, N, q, scale, y, nullptr, nullptr, nullptr);
+        return launch_status("lpdt_range_evonorm_fwd_q");
+    }
     hipLaunchKernelGGL(ren_stats_kernel<true>, dim3(g.chunks, N), dim3(g.block), key_lds + (size_t)2 * C * sizeof(unsigned int), st, x, g,
                        keys, absmax, v, pu);
-    hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), key_lds + groups * sizeof(float) + (size_t)2 * C * sizeof(unsigned int), st, g, keys, pu, gamma, beta, cm, eps,
+    hipLaunchKernelGGL(ren_q_fold_kernel, dim3(N), dim3(256), fold_lds, st, g, keys, pu, gamma, beta, cm, eps,
                        range_out, argmax_out, argmin_out, absmax);
     hipLaunchKernelGGL(ren_apply_q_kernel, dim3(ga.chunks, N), dim3(ga.block), 0, st, x, ga, v, gamma, beta, cm, eps, range_out,
-                       absmax, q, scale, y, nullptr, nullptr, nullptr);
+                       absmax, 1, q, scale, y, nullptr, nullptr, nullptr);
     return launch_status("lpdt_range_evonorm_fwd_q");
 }
 
