@@ -80,6 +80,28 @@ def test_row_tile_kernel_bit_exact(orc, shp):
         assert torch.equal(got, want), "backward-data, fused scale, accumulated"
 
 
+# backward-weight through wgrad_rows_kernel (kernel id 60): ragged last row tile of an image (57 rows in tiles of 2),
+# a single row per tile (80 columns), tiles that span the whole image (7x7, 8x8: 2 and 2 reduction groups), no padding,
+# padding 2, 2x2 / 3x1 / 1x3 / 2x3 filters, one and several channel tiles, a pixel share that ends inside an image
+WGRAD_ROWS_CASES = [(5, 64, 57, 41, 32, 3, 3, 1, 1), (3, 64, 6, 80, 64, 3, 3, 1, 1), (37, 128, 7, 7, 96, 3, 3, 1, 1),
+                    (9, 64, 8, 8, 32, 3, 3, 1, 1), (6, 64, 30, 30, 64, 3, 3, 1, 0), (4, 64, 20, 22, 32, 3, 3, 1, 2),
+                    (3, 64, 33, 17, 32, 2, 2, 1, 0), (5, 128, 14, 14, 64, 3, 1, 1, 0), (5, 64, 14, 16, 160, 1, 3, 1, 0),
+                    (2, 192, 12, 28, 64, 2, 3, 1, 1), (67, 64, 28, 28, 32, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("shp", WGRAD_ROWS_CASES)
+def test_wgrad_rows_kernel_bit_exact(orc, shp):
+    x, w, g = _data(shp, 800, "uniform")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert lpdt.qconv_kernel_id(ld, 2) == 60, "the planner changed: pick shapes that reach the row-tile weight-gradient kernel"
+    print("wgrad rows", shp, flush=True)
+    ref = orc.qconv_bwd_weight(od, g, x)
+    assert np.array_equal(host(lpdt.qconv_bwd_weight(ld, dev(g), dev(x))), ref), "backward-weight"
+    sa, sb = dev(np.array([0.013], np.float32)), dev(np.array([0.0037], np.float32))
+    want = lpdt.dequantize(dev(ref.astype(np.int32)), sa, sb)
+    assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
+
+
 def test_extreme_codes_no_overflow_in_range(orc):
     # all +-127 with reduction length 4608 (fwd) / 1152 (wgrad): the largest magnitudes the path can see here
     shp = (2, 512, 6, 6, 64, 3, 3, 1, 1)
