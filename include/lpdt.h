@@ -159,7 +159,9 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
  *       1: 64 x 64, 2: 128 x 128 channel tile
  *   60  backward-weight of stride-1 layers with filters of up to 3 x 3 taps (output channels a multiple of 32, input
  *       channels of 64): tiles of whole output rows, gradient and input patch loaded straight into LDS, all taps
- *       read out of the one patch */
+ *       read out of the one patch
+ *   62  backward-weight of pointwise products with both channel counts multiples of 256 (linear layers at transformer
+ *       shapes): 256 x 256 tiles, both operands loaded straight into LDS and read back transposed */
 int lpdt_qconv_kernel_id(const lpdt_conv_desc *d, int product);
 
 /* The same three products with the dequantizing scale applied in the kernel epilogue: the result

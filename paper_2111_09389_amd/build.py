@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblpdt.so")
-SOURCES = ["common.cpp", "quantize.hip", "range_evonorm.hip", "ref_norms.hip", "gossip.hip", "glue.hip", "qconv.hip", "qconv_igemm.hip", "qconv_igemm_dma.hip", "qconv_patch.hip", "qconv_narrow.hip", "qconv_wgrad.hip", "qconv_wgrad_rows.hip", "qconv_wgrad_bf16.hip"]
+SOURCES = ["common.cpp", "quantize.hip", "range_evonorm.hip", "ref_norms.hip", "gossip.hip", "glue.hip", "qconv.hip", "qconv_igemm.hip", "qconv_igemm_dma.hip", "qconv_patch.hip", "qconv_narrow.hip", "qconv_wgrad.hip", "qconv_wgrad_rows.hip", "qconv_wgrad_gemm.hip", "qconv_wgrad_bf16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

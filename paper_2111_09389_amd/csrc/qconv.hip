@@ -624,6 +624,8 @@ static size_t bwd_weight_base_ws(const lpdt_conv_desc *d0, int P, int Q) {
     WgradRowsPlan rows;
     if (narrow_conv_supported(d, P, Q)) return round_up(narrow_wgrad_workspace(d), 256);
     if (wgrad_rows_plan(d, P, Q, &rows)) return rows.partial_bytes;
+    WgradGemmPlan gemm;
+    if (wgrad_gemm_plan(d, P, Q, &gemm)) return gemm.partial_bytes;
     if (wgrad_rect_plan(d, P, Q, &pl)) return pl.partial_bytes;
     return 0;
 }
@@ -641,6 +643,11 @@ static void conv_bwd_weight_impl(const lpdt_conv_desc *d0, int P, int Q, const i
     WgradRowsPlan rows;
     if (aligned(gq, 16) && aligned(xq, 16) && !narrow_conv_supported(d, P, Q) && wgrad_rows_plan(d, P, Q, &rows)) {
         launch_wgrad_rows(d, P, Q, rows, gq, xq, out, out_mode, sA, sB, ws, st);
+        return;
+    }
+    WgradGemmPlan gemm;
+    if (aligned(gq, 16) && aligned(xq, 16) && wgrad_gemm_plan(d, P, Q, &gemm)) {
+        launch_wgrad_gemm(d, gemm, gq, xq, out, out_mode, sA, sB, ws, st);
         return;
     }
     if (aligned(gq, 16) && aligned(xq, 16) && wgrad_uses_rect(d, P, Q, &pl)) {
@@ -787,6 +794,8 @@ extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
     WgradRectPlan pl;
     WgradRowsPlan rows;
     if (!narrow_conv_supported(d, P, Q) && wgrad_rows_plan(d, P, Q, &rows)) return 60;  // row-tile kernel
+    WgradGemmPlan gemm;
+    if (wgrad_gemm_plan(d, P, Q, &gemm)) return 62;                                       // 256 x 256 GEMM tiles
     if (wgrad_uses_rect(d, P, Q, &pl)) {
         // 30 + tile (0: 32 x 64, 1: 64 x 64, 2: 128 x 128) + 4 for 64-pixel steps + 8 for two wave groups per block
         return 30 + (pl.kt == 128 ? 2 : pl.kt == 64 ? 1 : 0) + (pl.ks == 2 ? 4 : 0) + (pl.ng == 2 ? 8 : 0);

@@ -60,6 +60,16 @@ bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *plan)
 void launch_wgrad_rows(const lpdt_conv_desc *d, int P, int Q, const WgradRowsPlan &plan, const int8_t *g, const int8_t *x,
                        void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
 
+// GEMM-shaped variant for pointwise products with both channel counts multiples of 256 (qconv_wgrad_gemm.hip)
+struct WgradGemmPlan {
+    int T, steps, steps_per_split, splits, tiles_k, tiles_kc;
+    long long out_len;
+    size_t partial_bytes;
+};
+bool wgrad_gemm_plan(const lpdt_conv_desc *d, int P, int Q, WgradGemmPlan *plan);
+void launch_wgrad_gemm(const lpdt_conv_desc *d, const WgradGemmPlan &plan, const int8_t *g, const int8_t *x, void *out, int out_mode,
+                       const float *sA, const float *sB, void *partial, hipStream_t st);
+
 // out[i] = sum over `splits` copies partial[z][i] (out_len a multiple of 4), as int32 or as fp32 times sA*sB
 void launch_wgrad_reduce(const int32_t *partial, long long out_len, int splits, void *out, int out_mode, const float *sA,
                          const float *sB, hipStream_t st);

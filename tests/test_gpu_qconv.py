@@ -102,6 +102,25 @@ def test_wgrad_rows_kernel_bit_exact(orc, shp):
     assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
 
 
+# backward-weight of pointwise products through wgrad_gemm_kernel (kernel id 62): token counts that are no multiple of the
+# 64-token step or of a block's share, 3 x 3 / 3 x 12 / 12 x 3 / 4 x 4 tiles, a spatial 1x1 layer
+WGRAD_GEMM_CASES = [(8200, 768, 1, 1, 768, 1, 1, 1, 0), (3001, 768, 1, 1, 3072, 1, 1, 1, 0), (2987, 3072, 1, 1, 768, 1, 1, 1, 0),
+                    (9, 1024, 24, 25, 1024, 1, 1, 1, 0)]
+
+
+@pytest.mark.parametrize("shp", WGRAD_GEMM_CASES)
+def test_wgrad_gemm_kernel_bit_exact(orc, shp):
+    x, w, g = _data(shp, 900, "uniform")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert lpdt.qconv_kernel_id(ld, 2) == 62, "the planner changed: pick shapes that reach the GEMM-shaped weight-gradient kernel"
+    print("wgrad gemm", shp, flush=True)
+    ref = orc.qconv_bwd_weight(od, g, x)
+    assert np.array_equal(host(lpdt.qconv_bwd_weight(ld, dev(g), dev(x))), ref), "backward-weight"
+    sa, sb = dev(np.array([0.013], np.float32)), dev(np.array([0.0037], np.float32))
+    want = lpdt.dequantize(dev(ref.astype(np.int32)), sa, sb)
+    assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
+
+
 def test_extreme_codes_no_overflow_in_range(orc):
     # all +-127 with reduction length 4608 (fwd) / 1152 (wgrad): the largest magnitudes the path can see here
     shp = (2, 512, 6, 6, 64, 3, 3, 1, 1)
