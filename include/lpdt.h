@@ -152,7 +152,7 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
  *   10 + v (+ 100 when the reduction is split over blocks)  register-staged implicit GEMM, v = 0: 128 x 32 tile,
  *       1 / 2: 64 x 64 with 64- / 128-byte steps, 3 / 4: 128 x 64 with 64- / 128-byte steps
  *   20 + t  implicit GEMM with operands loaded straight into LDS, t = 0: 256 x 256, 1: 128 x 128 with 8 waves,
- *       2: 128 x 128 with 4 waves, 3: 64 x 128
+ *       2: 128 x 128 with 4 waves, 3: 64 x 128, 4: 256 x 128 on three stages (two blocks per CU)
  *   50  forward / backward-data of stride-1 layers with 64 reduction channels and at most 64 result channels: the
  *       whole filter stays in LDS, tiles of whole output rows, each input patch loaded once for all taps
  *   30 + t + 4*[64-pixel steps] + 8*[two wave groups per block]  rectangle-stepped backward-weight, t = 0: 32 x 64,

@@ -342,7 +342,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
 struct DmaTile { int TM, TN, WGM, WGN, S, KB; };
 // 0: 256 x 256, 64-byte steps   1: 128 x 128, 128-byte steps, 8 waves   2: 128 x 128, 64-byte steps, 4 waves (two blocks per CU)
 // 3: 64 x 128, 128-byte steps
-constexpr DmaTile kTiles[] = {{4, 2, 2, 4, 4, 64}, {2, 1, 2, 4, 4, 128}, {2, 2, 2, 2, 4, 64}, {1, 1, 2, 4, 4, 128}};
+constexpr DmaTile kTiles[] = {{4, 2, 2, 4, 4, 64}, {2, 1, 2, 4, 4, 128}, {2, 2, 2, 2, 4, 64}, {1, 1, 2, 4, 4, 128}, {2, 2, 4, 2, 3, 64}};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 inline int tile_bm(int cfg) { return 32 * kTiles[cfg].TM * kTiles[cfg].WGM; }
@@ -406,7 +406,13 @@ int dma_pick_tile(const IgemmParams &p) {
     }
 #endif
     const bool wide = p.Cin % 128 == 0;   // tiles with 128-byte steps
-    if (p.Cout >= 192 && tiles_of(p, 0) >= 160) return 0;
+    if (p.Cout >= 192 && tiles_of(p, 0) >= 160) {
+        // GEMM-like launches.  With a short reduction the fp32 result is most of the traffic: 256 x 128 tiles on three
+        // stages leave room for two blocks per CU, so that one block's stores run under the other's products
+        // (16384 x 768 -> 3072: 77 -> 66 us).  With a long one (3072) the two are even and the larger tile re-reads less.
+        const long long reduction = (long long)p.cls[0].Rc * p.cls[0].Sc * p.Cin;
+        return reduction <= 2048 && p.nclasses == 1 ? 4 : 0;
+    }
     const long long t128 = tiles_of(p, 1);
     if (t128 >= 320 || (t128 >= 160 && !wide)) return 2;
     if (t128 >= 160) return 1;
@@ -449,7 +455,8 @@ void dma_launch(const IgemmParams &p, int cfg, dim3 grid, hipStream_t st) {
         case 0: launch_cfg<4, 2, 2, 4, 4, 64>(p, grid, lds, st); break;
         case 1: launch_cfg<2, 1, 2, 4, 4, 128>(p, grid, lds, st); break;
         case 2: launch_cfg<2, 2, 2, 2, 4, 64>(p, grid, lds, st); break;
-        default: launch_cfg<1, 1, 2, 4, 4, 128>(p, grid, lds, st); break;
+        case 3: launch_cfg<1, 1, 2, 4, 4, 128>(p, grid, lds, st); break;
+        default: launch_cfg<2, 2, 4, 2, 3, 64>(p, grid, lds, st); break;
     }
 }
 

@@ -46,9 +46,9 @@ LAYERS = {   # N C H W K R S stride pad
 
 # lpdt_qconv_kernel_id of (forward, backward-data, backward-weight) at these sizes: the kernels and tiles bench.py times.
 # 1: first-layer kernels (narrow_fwd_kernel / narrow_wgrad_kernel); 10..14 (+100: split reduction): igemm_kernel
-# <128,32,4>, <64,64,4>, <64,64,8>, <128,64,4>, <128,64,8>; 20..23: igemm_dma_kernel 256x256, 128x128 (8 waves), 128x128
-# (4 waves), 64x128; 50: patch_conv_kernel (filter resident in LDS, row tiles); 30 + t + 4*[64-pixel steps] + 8*[two wave groups]: wgrad_rect_kernel with tile t (0: 32x64, 1: 64x64);
-# 60: wgrad_rows_kernel (row tiles of a stride-1 layer, operands straight into LDS);
+# <128,32,4>, <64,64,4>, <64,64,8>, <128,64,4>, <128,64,8>; 20..24: igemm_dma_kernel 256x256, 128x128 (8 waves), 128x128
+# (4 waves), 64x128, 256x128 (3 stages); 50: patch_conv_kernel (filter resident in LDS, row tiles); 30 + t + 4*[64-pixel steps] + 8*[two wave groups]: wgrad_rect_kernel with tile t (0: 32x64, 1: 64x64);
+# 60: wgrad_rows_kernel (row tiles of a stride-1 layer, operands straight into LDS); 62: wgrad_gemm_kernel (pointwise, 256x256 tiles);
 # 2: wgrad_kernel; 3: linear_small_kernel; 0: the any-shape kernels.
 KERNELS = {
     "stem 7x7 s2": (1, 10, 1), "layer1 3x3": (50, 50, 60), "layer2 3x3 s2": (22, 13, 38), "layer2 1x1 s2": (22, 13, 31),
@@ -56,9 +56,11 @@ KERNELS = {
     "layer4 3x3 s2": (23, 21, 38), "layer4 1x1 s2": (23, 21, 31), "layer4 3x3": (23, 23, 60), "classifier": (3, 3, 3),
     "resnet20 first": (1, 10, 1), "resnet20 16": (10, 10, 42), "resnet20 64": (111, 111, 60), "vgg11 first": (1, 10, 1),
     "vgg11 128": (22, 14, 60), "vgg11 512": (112, 112, 2),
-    "gemm 256x256 tile": (20, 12, 60),
+    "gemm 256x128 tile": (24, 12, 60), "gemm 256x256 tile": (20, 24, 62),
 }
-LAYERS["gemm 256x256 tile"] = (8, 64, 56, 56, 512, 3, 3, 1, 1)   # the one direct-to-LDS tile no benchmark layer takes at batch 64
+# the two direct-to-LDS tiles no benchmark layer takes at batch 64, and the GEMM-shaped weight gradient
+LAYERS["gemm 256x128 tile"] = (8, 64, 56, 56, 512, 3, 3, 1, 1)
+LAYERS["gemm 256x256 tile"] = (10240, 2304, 1, 1, 1024, 1, 1, 1, 0)
 
 
 @pytest.mark.parametrize("name", list(LAYERS))
