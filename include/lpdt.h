@@ -187,7 +187,7 @@ int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const i
                               const float *sx, float *dw, void *ws, size_t ws_bytes, void *stream);
 
 /* The same product with the filter prepared ahead of time.  Backward-data reads the filter transposed; the call above
- * transposes it on every call, although the weights change only once per step (Algorithm 1, line 3).  A training step
+ * transposes it on every call, although the weights change only once per step (the local update of Algorithm 1).  A training step
  * can make the transposed copy when the weights' codes are final (for instance beside the forward pass, on another
  * stream) and hand it over here.  lpdt_qconv_bwd_data_packed_filter_bytes: size of the copy, 0 when the shape has no
  * prepared form (then only lpdt_qconv_bwd_data_f32 applies).  packed: device, 16-byte aligned, owned by the caller,

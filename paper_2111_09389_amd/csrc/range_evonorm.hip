@@ -971,7 +971,7 @@ static bool ren_sample_path(int N, int H, int W, int C) {
 #ifdef LPDT_TUNE
     if (const char *e = getenv("LPDT_REN_SAMPLE_ELEMS")) limit = atoll(e);
 #endif
-    return (long long)H * W * C <= limit && C / 4 <= kSampleThreads && N <= 4096;
+    return (long long)H * W * C <= limit && C / 4 <= kSampleThreads && N <= 256;   // every apply thread reads the N maxima
 }
 
 // int8-output forward: block keys, then the per-block channel extremes of u, then the scalar max|y|

@@ -39,7 +39,7 @@ def test_deepsqueeze_selection_error_memory_and_update(orc):
             k = max(1, math.ceil(rho * (hi - lo)))
             for e in _brute_topk(v[i, lo:hi], k):
                 C[i, lo + e] = v[i, lo + e]
-    # error memory: delta + C[v] = v, bit for bit (line 7 of the algorithm)
+    # error memory: delta + C[v] = v, bit for bit (the error-update step of the algorithm)
     assert np.array_equal(dnew + C, v) and np.array_equal(dnew, v - C)
     assert np.array_equal(dnew[C != 0], np.zeros_like(dnew[C != 0]))
     # gossip update: x + eta * (W - I) C[v]
