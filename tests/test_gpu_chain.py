@@ -10,14 +10,17 @@ from gpu_util import dev, host
 pytestmark = pytest.mark.gpu
 import paper_2111_09389_amd as lpdt  # noqa: E402  (a broken import must fail the run, not skip it)
 
-# shape, groups, expected lpdt_qconv_kernel_id(d, 3): 41 / 42 / 43 = the statistics ride in the epilogue of the 128x128
-# (8 waves), 128x128 (4 waves, tile staged in two runs) and 64x128 tiles; anything else runs the two calls
+# shape, groups, expected lpdt_qconv_kernel_id(d, 3): 41 / 42 / 43 / 44 = the statistics ride in the epilogue of the 128x128
+# (8 waves), 128x128 (4 waves, tile staged in two runs), 64x128 and 256x128 (staged in four runs) tiles; anything else runs
+# the two calls
 CASES = [
     ((16, 128, 28, 28, 256, 3, 3, 1, 1), 32, 41),    # 784 pixels per sample: a tile touches up to 2 samples
     ((16, 64, 56, 56, 128, 3, 3, 1, 1), 32, 42),
     ((16, 256, 14, 14, 512, 3, 3, 1, 1), 32, 43),    # 196 pixels per sample, 64-pixel tiles
     ((64, 512, 7, 7, 512, 3, 3, 1, 1), 32, 43),      # 49 pixels per sample: up to 3 samples per tile
     ((64, 512, 7, 7, 512, 3, 3, 1, 1), 256, 43),     # two channels per group
+    ((8, 64, 56, 56, 512, 3, 3, 1, 1), 32, 44),      # GEMM-like launch with a short reduction
+    ((40, 128, 28, 28, 512, 1, 1, 1, 0), 64, 44),    # 784 pixels per sample on 256-pixel tiles: up to 2 samples per tile
     ((16, 128, 28, 28, 256, 3, 3, 2, 1), 32, 112),    # too few tiles for the fused form at this batch: the two calls
     ((2, 64, 14, 14, 64, 3, 3, 1, 1), 8, 111),
     ((3, 3, 20, 20, 16, 3, 3, 1, 1), 4, 1),          # first-layer kernel
