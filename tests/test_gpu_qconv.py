@@ -234,7 +234,9 @@ def test_prepacked_filter_is_refused_where_backward_data_has_no_packed_form():
     assert lpdt.qconv_bwd_data_pack_filter(ld, w) is None
 
 
-@pytest.mark.parametrize("shp", [CASES[1], CASES[2], CASES[3], CASES[4], CASES[9], CASES[12], CASES[14], CASES[15]])
+# the last three: launches on the 256x256, 256x128 and 128x128 tiles of the direct-to-LDS kernel (kernel ids 20, 24, 22)
+@pytest.mark.parametrize("shp", [CASES[1], CASES[2], CASES[3], CASES[4], CASES[9], CASES[12], CASES[14], CASES[15],
+                                 (16384, 768, 1, 1, 3072, 1, 1, 1, 0), (8, 64, 56, 56, 512, 3, 3, 1, 1), (8200, 768, 1, 1, 768, 1, 1, 1, 0)])
 def test_products_with_absmax_output(shp):
     """lpdt_qconv_fwd_f32_absmax / lpdt_qconv_bwd_data_f32_absmax: the results of the plain calls, bit for bit, and the exact
     largest magnitude of what was stored (epilogue path, split reductions, first layer, odd channel counts)."""
