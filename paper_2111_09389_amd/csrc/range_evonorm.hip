@@ -810,28 +810,33 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_generic_kernel(const float 
     block_absmax_store(am, pabs + row, lds);
 }
 
-// Second backward launch.  Blocks [0, 3 ceil(C/8)): dbeta, dgamma, dv = column sums of parts over all rows in a fixed
-// order (one quantity, 8 channels x 32 row lanes per block).  The remaining blocks take 256 (sample, group) pairs each: the gradient
+// Second backward launch, blocks of kFinishThreads threads.  Blocks [0, 3 ceil(C/8)): dbeta, dgamma, dv = column sums of
+// parts over all rows in a fixed order (one quantity, 8 channels x 32 row lanes per block: the first 256 threads; the
+// others only meet the barrier).  The remaining blocks take 16 (sample, group) pairs each, one per wave: the gradient
 // through the range, added at the saved extrema; they also fold max|dx| = max(block partials of the first launch, the
 // elements just changed) into absmax_out, which the first launch zeroed (a max is order-free, so this stays
-// deterministic).
-__global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__restrict__ parts, const float *__restrict__ pabs,
-                                                             int rows, int N, int HW, int C, int groups, int m, int chunks,
-                                                             float cm, float eps, const float *__restrict__ range,
-                                                             const int32_t *__restrict__ argmax, const int32_t *__restrict__ argmin,
-                                                             float *__restrict__ dx, float *__restrict__ dbeta,
-                                                             float *__restrict__ dgamma, float *__restrict__ dv,
-                                                             float *__restrict__ absmax_out) {
+// deterministic).  16 pairs per block, not 4: every block ends with an atomic on that one address, those are served one
+// after the other (~10 ns each), and with 512 of them they were half of this kernel's 8 us.
+constexpr int kFinishThreads = 1024;
+constexpr int kFinishPairs = kFinishThreads / kWave;
+__global__ __launch_bounds__(kFinishThreads) void ren_bwd_finish_kernel(const float *__restrict__ parts, const float *__restrict__ pabs,
+                                                                        int rows, int N, int HW, int C, int groups, int m, int chunks,
+                                                                        float cm, float eps, const float *__restrict__ range,
+                                                                        const int32_t *__restrict__ argmax, const int32_t *__restrict__ argmin,
+                                                                        float *__restrict__ dx, float *__restrict__ dbeta,
+                                                                        float *__restrict__ dgamma, float *__restrict__ dv,
+                                                                        float *__restrict__ absmax_out) {
     __shared__ float s[32][8];
-    __shared__ float lds[256 / kWave];
+    __shared__ float lds[kFinishPairs];
     const int param_blocks = 3 * ((C + 7) / 8);
     if ((int)blockIdx.x < param_blocks) {
         // one of the three quantities, 8 channels x 32 row lanes; a lane's rows are summed eight at a time (8 loads in
         // flight) in a fixed order
-        const int q = blockIdx.x % 3, cl = threadIdx.x % 8, sl = threadIdx.x / 8;
+        const bool worker = threadIdx.x < 256;
+        const int q = blockIdx.x % 3, cl = threadIdx.x % 8, sl = (threadIdx.x / 8) % 32;
         const int c = (blockIdx.x / 3) * 8 + cl;
         float acc = 0.0f;
-        if (c < C) {
+        if (worker && c < C) {
             for (int r = sl; r < rows; r += 256) {
                 float t[8];
 #pragma unroll
@@ -839,9 +844,9 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
                 acc += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
             }
         }
-        s[sl][cl] = acc;
+        if (worker) s[sl][cl] = acc;
         __syncthreads();
-        if (sl == 0 && c < C) {
+        if (worker && sl == 0 && c < C) {
             float t = 0;
             for (int k = 0; k < 32; ++k) t += s[k][cl];
             (q == 0 ? dbeta : q == 1 ? dgamma : dv)[c] = t;
@@ -851,7 +856,7 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
     // range blocks: one wave per (sample, group) pair; its lanes share the pair's chunks x channels partial sums
     const int rb = blockIdx.x - param_blocks, nrb = gridDim.x - param_blocks;
     float am = 0.0f;
-    const int i = rb * (256 / kWave) + threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int i = rb * kFinishPairs + threadIdx.x / kWave, lane = threadIdx.x % kWave;
     if (i < N * groups) {
         const int n = i / groups, grp = i % groups;
         // the two elements to change are fetched while the partial sums are still being added up
@@ -886,7 +891,7 @@ __global__ __launch_bounds__(256) void ren_bwd_finish_kernel(const float *__rest
         }
     }
     if (absmax_out) {
-        for (int r = rb * 256 + threadIdx.x; r < rows; r += nrb * 256) am = fmaxf(am, pabs[r]);
+        for (int r = rb * kFinishThreads + threadIdx.x; r < rows; r += nrb * kFinishThreads) am = fmaxf(am, pabs[r]);
         block_absmax_commit(am, absmax_out, lds);
     }
 }
@@ -1141,7 +1146,7 @@ extern "C" int lpdt_range_evonorm_maxpool_bwd(const float *dz, const int32_t *id
     hipLaunchKernelGGL(ren_bwd_main_kernel<true>, dim3(g.chunks, N), dim3(g.block), (size_t)16 * g.threads * sizeof(float), st,
                        (const float *)nullptr, x, g, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out, dz, idx,
                        pool_geom(H, W, P, Q, k, st_, pd));
-    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + kFinishPairs - 1) / kFinishPairs), dim3(kFinishThreads), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, g.chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_maxpool_bwd");
 }
@@ -1178,7 +1183,7 @@ extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, in
         hipLaunchKernelGGL(ren_bwd_generic_kernel, dim3(chunks, N), dim3(kRThreads), 0, st, dy, x, H * W, C, groups, m,
                            kGenericPix, chunks, v, gamma, cm, eps, range, argmax, argmin, dx, parts, pabs, absmax_out);
     }
-    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + 3) / 4), dim3(256), 0, st, parts, pabs, (int)rows, N, H * W, C,
+    hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + kFinishPairs - 1) / kFinishPairs), dim3(kFinishThreads), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_bwd");
 }
