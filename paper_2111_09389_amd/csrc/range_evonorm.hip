@@ -296,9 +296,13 @@ __global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsign
         for (int i = threadIdx.x; i < g.C * parts; i += blockDim.x) {
             const int c = i % g.C, part = i / g.C;
             float hi = -INFINITY, lo = INFINITY;
-            for (int ch = part; ch < g.chunks; ch += parts) {
-                const float2 v = p2[(size_t)ch * g.C + c];
-                hi = fmaxf(hi, v.x); lo = fminf(lo, v.y);
+            for (int ch0 = part; ch0 < g.chunks; ch0 += 4 * parts) {   // 4 loads in flight
+                float2 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    v[k] = ch0 + k * parts < g.chunks ? p2[(size_t)(ch0 + k * parts) * g.C + c] : make_float2(-INFINITY, INFINITY);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { hi = fmaxf(hi, v[k].x); lo = fminf(lo, v[k].y); }
             }
             if (part < g.chunks) {
                 atomicMax(&su[c * 2 + 0], ordered_bits(hi));
@@ -307,9 +311,13 @@ __global__ __launch_bounds__(256) void ren_q_fold_kernel(RenGeom g, const unsign
         }
     }
     const unsigned long long *src = pstats + (size_t)n * g.chunks * nk;
-    for (int i = threadIdx.x; i < g.chunks * nk; i += blockDim.x) {
-        const unsigned long long k = src[i];
-        if (k) atomicMax(&skeys[i % nk], k);
+    for (int i0 = threadIdx.x; i0 < g.chunks * nk; i0 += 4 * blockDim.x) {   // 4 loads in flight
+        unsigned long long k[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) k[j] = i0 + j * (int)blockDim.x < g.chunks * nk ? src[i0 + j * blockDim.x] : 0ull;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (k[j]) atomicMax(&skeys[(i0 + j * blockDim.x) % nk], k[j]);
     }
     __syncthreads();
     for (int grp = threadIdx.x; grp < g.groups; grp += blockDim.x) {
