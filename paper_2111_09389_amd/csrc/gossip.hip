@@ -372,7 +372,12 @@ __global__ __launch_bounds__(kGThreads) void choco_window_kernel(const float *__
         const long long e = e0 + ((long long)it * kGThreads + threadIdx.x) * VEC;
         if (VEC == 4) {
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-            if (e < e1) { a = *reinterpret_cast<const float4 *>(xr + e); b = *reinterpret_cast<const float4 *>(hr + e); }
+            if (e < e1) {
+                typedef float nt4 __attribute__((ext_vector_type(4)));
+                const nt4 na = __builtin_nontemporal_load(reinterpret_cast<const nt4 *>(xr + e));
+                const nt4 nb = __builtin_nontemporal_load(reinterpret_cast<const nt4 *>(hr + e));
+                a = make_float4(na[0], na[1], na[2], na[3]); b = make_float4(nb[0], nb[1], nb[2], nb[3]);
+            }
             xv[it * 4 + 0] = a.x; xv[it * 4 + 1] = a.y; xv[it * 4 + 2] = a.z; xv[it * 4 + 3] = a.w;
             hv[it * 4 + 0] = b.x; hv[it * 4 + 1] = b.y; hv[it * 4 + 2] = b.z; hv[it * 4 + 3] = b.w;
         } else {
@@ -683,6 +688,8 @@ __global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigne
     if (threadIdx.x == 0) st[pair].prefix = prefix;
 }
 
+typedef float nt2 __attribute__((ext_vector_type(2)));   // the type of the streaming (nontemporal) 8-byte accesses
+
 // Final pass: xhat += top-k(x - xhat) for every agent, then the gossip update of x.
 // A thread owns VEC adjacent parameter columns (VEC * 4-byte loads per agent row).
 template <int NMAX, int VEC, typename G>
@@ -720,9 +727,9 @@ __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__res
         if (i < n) {
             float hv[VEC];
             if (VEC == 2) {
-                const float2 a = *reinterpret_cast<const float2 *>(x + (size_t)i * d + e);
-                const float2 b = *reinterpret_cast<const float2 *>(xhat + (size_t)i * d + e);
-                xv[i][0] = a.x; xv[i][VEC - 1] = a.y; hv[0] = b.x; hv[VEC - 1] = b.y;
+                const nt2 a = __builtin_nontemporal_load(reinterpret_cast<const nt2 *>(x + (size_t)i * d + e));
+                const nt2 b = __builtin_nontemporal_load(reinterpret_cast<const nt2 *>(xhat + (size_t)i * d + e));
+                xv[i][0] = a[0]; xv[i][VEC - 1] = a[1]; hv[0] = b[0]; hv[VEC - 1] = b[1];
             } else {
                 xv[i][0] = x[(size_t)i * d + e]; hv[0] = xhat[(size_t)i * d + e];
             }
@@ -776,7 +783,7 @@ __global__ __launch_bounds__(kGThreads) void choco_apply_mix_kernel(float *__res
                 else if (push) sum += (rs - 1.0f) * hi;
                 o[u] = xv[i][u] + rate * sum;
             }
-            if (VEC == 2) *reinterpret_cast<float2 *>(x + (size_t)i * d + e) = make_float2(o[0], o[VEC - 1]);
+            if (VEC == 2) __builtin_nontemporal_store(nt2{o[0], o[VEC - 1]}, reinterpret_cast<nt2 *>(x + (size_t)i * d + e));
             else x[(size_t)i * d + e] = o[0];
             if (z) {  // de-biased model z_i = x_i / u_i
                 const float ui = unew[i];
