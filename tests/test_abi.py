@@ -183,3 +183,12 @@ def test_qconv_kernel_id_argument_errors(L):
     assert L.lpdt_qconv_kernel_id(ctypes.byref(d), 5) == -1
     assert L.lpdt_qconv_kernel_id(None, 0) == -1
     assert L.lpdt_qconv_kernel_id(ctypes.byref(d), 0) >= 10
+
+
+def test_planner_gives_the_benchmark_layers_their_kernels():
+    """lpdt_qconv_kernel_id does no GPU work: the table of test_gpu_fullsize (which kernel family and tile each benchmark
+    layer's three products take) is checked here too, so a planner change shows up without a GPU."""
+    import test_gpu_fullsize as full
+    for name, shp in full.LAYERS.items():
+        ld = lpdt.ConvDesc.make(*shp)
+        assert tuple(lpdt.qconv_kernel_id(ld, i) for i in range(3)) == full.KERNELS[name], name
