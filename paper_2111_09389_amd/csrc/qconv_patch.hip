@@ -108,6 +108,24 @@ __global__ __launch_bounds__(kPatchThreads, 2) void patch_conv_kernel(const Patc
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+        // a call that adds to what the result tensor holds fetches those values now, under the products
+        const int n = tile / q.tiles_per_image, r0 = (tile - n * q.tiles_per_image) * q.TR;
+        const int rows = min(q.TR, c.OHs - r0);
+        const size_t pix0 = ((size_t)n * p.OH + r0) * p.OW;
+        v4f held[2][4];
+        if (p.out_mode == 2) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int pix = wm * 64 + 32 * i + r32;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int col = wn * 32 + 8 * k + 4 * half;
+                    held[i][k] = pix < rows * c.OWs && col < p.Cout
+                                     ? *reinterpret_cast<const v4f *>(static_cast<const float *>(p.out) + (pix0 + pix) * p.Cout + col)
+                                     : v4f{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
         int ty = 0, tx = 0;
         for (int tap = 0; tap < ntaps; ++tap) {
             const int toff = (c.iy0 + ty * p.dsign - q.rmin) * q.PW + (c.ix0 + tx * p.dsign - q.cmin);
@@ -126,9 +144,6 @@ __global__ __launch_bounds__(kPatchThreads, 2) void patch_conv_kernel(const Patc
             }
         }
         // a lane holds pixel lane%32 of sub-tile i and channels wn*32 + 8*k + 4*(lane/32) + 0..3, k = 0..3
-        const int n = tile / q.tiles_per_image, r0 = (tile - n * q.tiles_per_image) * q.TR;
-        const int rows = min(q.TR, c.OHs - r0);
-        const size_t pix0 = ((size_t)n * p.OH + r0) * p.OW;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int pix = wm * 64 + 32 * i + r32;
@@ -143,7 +158,7 @@ __global__ __launch_bounds__(kPatchThreads, 2) void patch_conv_kernel(const Patc
                     v4f *fdst = reinterpret_cast<v4f *>(dst);
                     const bool add = p.out_mode == 2;
                     v4f v = {0.f, 0.f, 0.f, 0.f};
-                    if (add) v = *fdst;
+                    if (add) v = held[i][k];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = dequant_value(scale, s[e], v[e], add);
                     *fdst = v;
