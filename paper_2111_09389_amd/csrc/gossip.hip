@@ -650,6 +650,21 @@ __global__ __launch_bounds__(kRefThreads) void choco_refine_kernel(const unsigne
             }
         }
     };
+    if (count <= (unsigned int)kRefThreads && (!tiled || t0 >= t1)) {
+        // A handful of candidates in one plain list (the small tensors: two thirds of a network's segments): one key per
+        // thread, and the key with exactly rank - 1 matching keys above it is the answer (keys are unique: they carry
+        // the element's index).  The four radix rounds below cost such a block 15 us, mostly barriers.
+        const unsigned long long key = threadIdx.x < count ? ca[begin + threadIdx.x] : 0ull;
+        const bool match = threadIdx.x < count && (key >> 51) == ps.prefix;
+        list[threadIdx.x] = match ? key : 0ull;      // 0 is never counted as larger than anything
+        __syncthreads();
+        if (match) {
+            unsigned int greater = 0;
+            for (unsigned int j = 0; j < count; ++j) greater += list[j] > key ? 1u : 0u;
+            if (greater + 1u == ps.rank) st[pair].prefix = key;
+        }
+        return;
+    }
     unsigned long long prefix = ps.prefix;
     unsigned int rank = ps.rank, listed = 0;
     bool in_lds = false;
