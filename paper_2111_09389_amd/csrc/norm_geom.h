@@ -22,10 +22,11 @@ struct RenGeom {
     int pix_per_block;
 };
 
-// Grid size of a streaming pass: about one block per `elems_per_block` elements, between 256 and kMaxBlocks.  Small
-// tensors are latency-bound (every block first waits for its parameters and range), so they want few, longer blocks;
-// the stats pass has no such wait and takes more, shorter ones (measured on the ResNet-18 layer sizes).
-constexpr int kStatsElems = 8192, kApplyElems = 16384, kBwdElems = 16384;
+// Grid size of a streaming pass: about one block per `elems_per_block` elements, between 256 and kMaxBlocks.  Measured
+// on the ResNet-18 layer sizes inside the training step (4 K against 8 K and 16 K elements per block in the apply and
+// backward passes: 9.6 against 10.0 and 11.2 us, 18.8 against 19.6 and 20.1 us per layer on average; 2 K is no better
+// and lengthens the backward pass's second launch, which adds up one row of partial sums per block).
+constexpr int kStatsElems = 8192, kApplyElems = 4096, kBwdElems = 4096;
 static inline int block_cap(int N, int H, int W, int C, int elems_per_block) {
     const long long b = (long long)N * H * W * C / elems_per_block;
     return (int)(b < 256 ? 256 : b > kMaxBlocks ? kMaxBlocks : b);
