@@ -150,11 +150,12 @@ template <int VEC>
 __device__ __forceinline__ void hist_tile(long long tile, const float *__restrict__ x, const float *__restrict__ xhat, size_t d,
                                           const long long *__restrict__ off, int nseg, unsigned int *__restrict__ hist, int ds,
                                           const PairState *__restrict__ st, bool only_redo, unsigned int *sh, int *s_first,
-                                          int *s_last) {
+                                          int *s_last, unsigned int *range) {
     const int agent = blockIdx.y;
     const long long e0 = tile * kTile;
     const long long e1 = min(e0 + (long long)kTile, (long long)d);
     for (int i = threadIdx.x; i < 4096; i += kGThreads) sh[i] = 0u;
+    if (threadIdx.x == 0) { range[0] = 4095u; range[1] = 0u; }   // bins touched by a round: [min, max], two pairs in turn
     find_segment_block(off, nseg, e0, s_first);
     find_segment_block(off, nseg, e1 - 1, s_last);
     __syncthreads();
@@ -184,19 +185,39 @@ __device__ __forceinline__ void hist_tile(long long tile, const float *__restric
         }
     }
     // One round per segment of the tile (almost always one): its elements into the LDS histogram, then the non-empty
-    // bins into the pair's histogram, clearing the LDS copy for the next round.  No per-element global atomics.
+    // bins into the pair's histogram, clearing the LDS copy for the next round.  No per-element global atomics.  Only
+    // the range of bins the round touched is walked: a tile in a run of small tensors (a network's normalisation
+    // parameters) has a dozen rounds, and walking all 4096 bins in each made those few tiles the whole launch's time.
+    int round = 0;   // rounds done: they alternate between the two [min, max] pairs of `range`
     for (int sg = sfirst; sg <= slast; ++sg) {
         const long long lo = max(off[sg], e0), hi = min(off[sg + 1], e1);  // the segment's part of the tile
         if (lo >= hi) continue;                                            // (the same in every thread)
         if (only_redo && !st[(size_t)agent * nseg + sg].redo) continue;
+        unsigned int *const rng = range + 2 * (round & 1), *const rng_next = range + 2 * (~round & 1);
+        ++round;
+        unsigned int bmin = 4095u, bmax = 0u;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const long long e = e0 + ((long long)(j / VEC) * kGThreads + threadIdx.x) * VEC + j % VEC;
-            if (e >= lo && e < hi) atomicAdd(&sh[(bins[j / 2] >> (16 * (j % 2))) & 0xffffu], 1u);
+            if (e >= lo && e < hi) {
+                const unsigned int b = (bins[j / 2] >> (16 * (j % 2))) & 0xffffu;
+                atomicAdd(&sh[b], 1u);
+                bmin = min(bmin, b); bmax = max(bmax, b);
+            }
         }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            bmin = min(bmin, (unsigned int)__shfl_xor((int)bmin, o, 64));
+            bmax = max(bmax, (unsigned int)__shfl_xor((int)bmax, o, 64));
+        }
+        if (threadIdx.x % 64 == 0 && bmin <= bmax) { atomicMin(&rng[0], bmin); atomicMax(&rng[1], bmax); }
         __syncthreads();
+        // the other pair was last read before the previous round's closing barrier and is next written after this
+        // round's: now is the time to reset it
+        if (threadIdx.x == 0) { rng_next[0] = 4095u; rng_next[1] = 0u; }
         unsigned int *gh = gh_all + (size_t)sg * kBins;
-        for (int i = threadIdx.x; i < 4096; i += kGThreads) {
+        const unsigned int r_lo = rng[0], r_hi = rng[1];   // nothing touched: 4095 > 0, nothing to walk
+        for (unsigned int i = r_lo + threadIdx.x; i <= r_hi && r_lo <= r_hi; i += kGThreads) {
             const unsigned int c = sh[i];
             if (c) { atomicAdd(&gh[i], c); sh[i] = 0u; }
         }
@@ -212,11 +233,12 @@ __global__ __launch_bounds__(kGThreads) void choco_hist_kernel(const float *__re
                                                                const PairState *__restrict__ st,
                                                                const unsigned int *__restrict__ any_redo) {
     __shared__ unsigned int sh[4096];
+    __shared__ unsigned int range[4];
     __shared__ int s_first, s_last;
     if (any_redo && *any_redo == 0u) return;
     for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
         hist_tile<VEC>(tile_list ? tile_list[t] : (long long)t, x, xhat, d, off, nseg, hist, ds, st, any_redo != nullptr, sh,
-                       &s_first, &s_last);
+                       &s_first, &s_last, range);
         __syncthreads();
     }
 }
