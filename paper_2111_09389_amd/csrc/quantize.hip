@@ -98,6 +98,62 @@ __global__ __launch_bounds__(kQThreads) void round_kernel(const float *__restric
     }
 }
 
+// Small tensors (a classifier's input, the loss gradient): one block finds the abs-max and emits the codes, one launch
+// instead of two -- at this size a launch costs more than the work.  Same arithmetic as absmax_kernel + round_kernel.
+constexpr int kSmallThreads = 1024, kSmallVecs = 16;                  // up to 16 float4 per thread: 64 Ki elements
+constexpr size_t kSmallLen = (size_t)kSmallThreads * kSmallVecs * 4;
+template <bool kStochastic>
+__global__ __launch_bounds__(kSmallThreads) void quantize_small_kernel(const float *__restrict__ x, size_t len, uint64_t seed,
+                                                                       uint64_t offset, int8_t *__restrict__ q,
+                                                                       float *__restrict__ scale) {
+    __shared__ float lds[kSmallThreads / kWave];
+    const size_t nvec = len / 4;
+    const int tail = (int)(len & 3);
+    const float4 *xv = reinterpret_cast<const float4 *>(x);
+    float4 v[kSmallVecs];
+    float m = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kSmallVecs; ++k) {
+        const size_t i = threadIdx.x + (size_t)kSmallThreads * k;
+        v[k] = i < nvec ? xv[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        m = fmaxf(fmaxf(m, fmaxf(fabsf(v[k].x), fabsf(v[k].y))), fmaxf(fabsf(v[k].z), fabsf(v[k].w)));
+    }
+    const float t = (int)threadIdx.x < tail ? x[nvec * 4 + threadIdx.x] : 0.0f;
+    m = wave_max(fmaxf(m, fabsf(t)));
+    if (threadIdx.x % kWave == 0) lds[threadIdx.x / kWave] = m;
+    __syncthreads();
+    float a = lds[0];
+#pragma unroll
+    for (int w = 1; w < kSmallThreads / kWave; ++w) a = fmaxf(a, lds[w]);
+    const float inv = quant_inv(a);
+    if (threadIdx.x == 0) *scale = quant_scale(a);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t *qv = reinterpret_cast<uint32_t *>(q);
+#pragma unroll
+    for (int k = 0; k < kSmallVecs; ++k) {
+        const size_t i = threadIdx.x + (size_t)kSmallThreads * k;
+        if (i >= nvec) break;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (kStochastic) {
+            const uint64_t blk = offset + i;
+            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
+        }
+        const uint32_t b0 = (uint32_t)round_code(v[k].x, inv, kStochastic, w[0]) & 0xffu;
+        const uint32_t b1 = (uint32_t)round_code(v[k].y, inv, kStochastic, w[1]) & 0xffu;
+        const uint32_t b2 = (uint32_t)round_code(v[k].z, inv, kStochastic, w[2]) & 0xffu;
+        const uint32_t b3 = (uint32_t)round_code(v[k].w, inv, kStochastic, w[3]) & 0xffu;
+        qv[i] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+    }
+    if ((int)threadIdx.x < tail) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (kStochastic) {
+            const uint64_t blk = offset + nvec;
+            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
+        }
+        q[nvec * 4 + threadIdx.x] = (int8_t)round_code(t, inv, kStochastic, w[threadIdx.x]);
+    }
+}
+
 // ---- many slices of one buffer in two launches --------------------------------
 // Slice table in device memory: begin[s], end[s] (element indices), written from kernel arguments so that the call
 // needs no host-to-device copy and can be captured in a graph.
@@ -278,6 +334,13 @@ extern "C" int lpdt_quantize(const float *x, size_t len, int rounding, uint64_t 
     if (rc) return rc;
     rc = check_ws(ws, ws_bytes, lpdt_quantize_workspace_bytes(len));
     if (rc) return rc;
+    if (len <= kSmallLen) {
+        if (rounding == LPDT_ROUND_STOCHASTIC)
+            hipLaunchKernelGGL(quantize_small_kernel<true>, dim3(1), dim3(kSmallThreads), 0, as_stream(stream), x, len, seed, offset, q, scale);
+        else
+            hipLaunchKernelGGL(quantize_small_kernel<false>, dim3(1), dim3(kSmallThreads), 0, as_stream(stream), x, len, seed, offset, q, scale);
+        return launch_status("lpdt_quantize");
+    }
     float *parts = static_cast<float *>(ws);
     int g1 = grid_for(len, 16);
     if (g1 > kMaxParts) g1 = kMaxParts;
