@@ -44,6 +44,7 @@ class TrainStep:
                  fuse_conv_ren=False):
         self.L = lib()
         self.overlap_wgrad = overlap_wgrad
+        self.fork_batch = 2              # second-stream calls issued behind one fork event (measured: 1 and 3 are slower)
         self.fuse_ren_quant = fuse_ren_quant   # Range-EvoNorm layers that feed only convolutions emit int8 codes directly
         # backward-data's transposed filters are made once per step, on the second stream beside the forward pass
         self.prepack_filters = prepack_filters and overlap_wgrad
@@ -514,41 +515,52 @@ class TrainStep:
         side = self._side_stream
         side_ptr = _vp(side.cuda_stream) if side is not None else stream
         last = self.L.lpdt_last_error
-        forks, joined, prev_side = 0, True, False
+        forks, joined = 0, True
         calls = self.calls if upto is None else self.calls[:upto]
         n = len(calls)
+        pending = []                         # calls of the second stream not yet issued: they go out in batches behind one fork
+
+        def flush():
+            nonlocal forks, joined
+            if not pending:
+                return
+            ev = self._fork_events[forks]
+            forks += 1
+            ev.record(main)                  # everything issued so far (the quantizers of these layers' gradients included)
+            side.wait_event(ev)
+            for f, a in pending:
+                rc_ = f(*a, side_ptr)
+                if rc_ != 0:
+                    raise LpdtError(rc_, last().decode())
+            pending.clear()
+            joined = False
+
+        def join():
+            nonlocal joined
+            flush()
+            if not joined:
+                self._join_event.record(side)
+                main.wait_event(self._join_event)
+                joined = True
+
         for i, (fn, args, sr, on_side) in enumerate(calls):
             if sr is not None:
                 pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4
                 args[pos] = _u64((int(step) << 32) + (sr << 24))
             if on_side:
-                if not prev_side:            # consecutive calls of the second stream share one fork
-                    ev = self._fork_events[forks]
-                    forks += 1
-                    ev.record(main)          # everything issued so far (the quantizer of this layer's gradient included)
-                    side.wait_event(ev)
-                rc = fn(*args, side_ptr)
-                joined = False
-                prev_side = True
-            elif fn is None:
-                prev_side = False
-                if not joined:
-                    self._join_event.record(side)
-                    main.wait_event(self._join_event)
-                    joined = True
+                pending.append((fn, args))
+                if len(pending) >= self.fork_batch and not (i + 1 < n and calls[i + 1][3]):
+                    flush()                  # (a run of consecutive second-stream calls is never split)
                 continue
-            else:
-                if not joined and (fn is self.L.lpdt_sgd or i == n - 1):
-                    self._join_event.record(side)
-                    main.wait_event(self._join_event)
-                    joined = True
-                rc = fn(*args, stream)
-                prev_side = False
+            if fn is None:
+                join()
+                continue
+            if fn is self.L.lpdt_sgd or i == n - 1:
+                join()
+            rc = fn(*args, stream)
             if rc != 0:
                 raise LpdtError(rc, last().decode())
-        if not joined:
-            self._join_event.record(side)
-            main.wait_event(self._join_event)
+        join()
 
     def run_timed(self, step=0, with_desc=False):
         """Like run(), but everything on the current stream, every library call bracketed with events on it; returns
