@@ -282,7 +282,8 @@ def measure(cfg_id, nsteps, warmup, use_graph, device, detail=True, entry_points
     if "lpdt_qconv_fwd_f32_add" in per:      # the forward product with the skip connection's addition in its epilogue
         per["lpdt_qconv_fwd_f32"] = per.get("lpdt_qconv_fwd_f32", 0.0) + per.pop("lpdt_qconv_fwd_f32_add")
     # variants of the same products: the filter transposed ahead of time, max|result| as a by-product
-    for alias in ("lpdt_qconv_bwd_data_f32_packed", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_f32_absmax"):
+    for alias in ("lpdt_qconv_bwd_data_f32_packed", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_pack_filters",
+                  "lpdt_qconv_bwd_data_f32_absmax"):
         if alias in per:
             per["lpdt_qconv_bwd_data_f32"] = per.get("lpdt_qconv_bwd_data_f32", 0.0) + per.pop(alias)
     if "lpdt_qconv_fwd_f32_absmax" in per:

@@ -191,10 +191,16 @@ int lpdt_qconv_bwd_weight_f32(const lpdt_conv_desc *d, const int8_t *gq, const i
  * can make the transposed copy when the weights' codes are final (for instance beside the forward pass, on another
  * stream) and hand it over here.  lpdt_qconv_bwd_data_packed_filter_bytes: size of the copy, 0 when the shape has no
  * prepared form (then only lpdt_qconv_bwd_data_f32 applies).  packed: device, 16-byte aligned, owned by the caller,
- * valid until the weights change.  Results are those of lpdt_qconv_bwd_data_f32, bit for bit. */
+ * valid until the weights change.  Results are those of lpdt_qconv_bwd_data_f32, bit for bit.
+ * lpdt_qconv_bwd_data_pack_filters prepares `count` filters in one launch (per 24 filters): descs, wq, packed and
+ * packed_bytes are HOST arrays of `count` entries (wq[i], packed[i]: device pointers as above); every entry is checked
+ * before anything is launched, and an entry whose shape has no prepared form is an error (LPDT_EUNSUPPORTED).  Each
+ * packed[i] holds exactly what lpdt_qconv_bwd_data_pack_filter would have written. */
 size_t lpdt_qconv_bwd_data_packed_filter_bytes(const lpdt_conv_desc *d);
 int lpdt_qconv_bwd_data_pack_filter(const lpdt_conv_desc *d, const int8_t *wq, void *packed, size_t packed_bytes,
                                     void *stream);
+int lpdt_qconv_bwd_data_pack_filters(const lpdt_conv_desc *descs, int count, const int8_t *const *wq, void *const *packed,
+                                     const size_t *packed_bytes, void *stream);
 int lpdt_qconv_bwd_data_f32_packed(const lpdt_conv_desc *d, const int8_t *gq, const void *packed, const float *sg,
                                    const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes,
                                    void *stream);

@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_ren_fwd_q", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_pack_filters", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -37,7 +37,8 @@ EXPORTS = [
     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_fwd_q",
     "lpdt_range_evonorm_maxpool_fwd_workspace_bytes", "lpdt_range_evonorm_maxpool_bwd_workspace_bytes",
     "lpdt_range_evonorm_maxpool_fwd", "lpdt_range_evonorm_maxpool_bwd",
-    "lpdt_qconv_bwd_data_packed_filter_bytes", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_f32_packed",
+    "lpdt_qconv_bwd_data_packed_filter_bytes", "lpdt_qconv_bwd_data_pack_filter", "lpdt_qconv_bwd_data_pack_filters",
+    "lpdt_qconv_bwd_data_f32_packed",
     "lpdt_qconv_fwd_f32_absmax_workspace_bytes", "lpdt_qconv_bwd_data_f32_absmax_workspace_bytes",
     "lpdt_qconv_fwd_f32_absmax", "lpdt_qconv_bwd_data_f32_absmax",
     "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd", "lpdt_evonorm_s0_bwd",
@@ -341,6 +342,22 @@ def qconv_bwd_data_pack_filter(d, wq):
         return None
     packed = torch.empty(nb, dtype=torch.uint8, device=wq.device)
     _check(lib().lpdt_qconv_bwd_data_pack_filter(ctypes.byref(d), _ptr(wq), _ptr(packed), _sz(nb), _stream()))
+    return packed
+
+
+def qconv_bwd_data_pack_filters(descs, wqs):
+    """qconv_bwd_data_pack_filter for several filters in one launch; every shape must have a prepared form."""
+    n = len(descs)
+    assert n == len(wqs)
+    for d, wq in zip(descs, wqs):
+        _dev(wq, torch.int8, "qconv_bwd_data_pack_filters wq")
+        assert tuple(wq.shape) == (d.K, d.R, d.S, d.C)
+    darr = (ConvDesc * n)(*descs)
+    sizes = [int(lib().lpdt_qconv_bwd_data_packed_filter_bytes(ctypes.byref(darr[i]))) for i in range(n)]
+    packed = [torch.empty(max(nb, 16), dtype=torch.uint8, device=wq.device) for nb, wq in zip(sizes, wqs)]
+    _check(lib().lpdt_qconv_bwd_data_pack_filters(darr, n, (ctypes.c_void_p * n)(*[w.data_ptr() for w in wqs]),
+                                                  (ctypes.c_void_p * n)(*[t.data_ptr() for t in packed]),
+                                                  (_sz * n)(*sizes), _stream()))
     return packed
 
 

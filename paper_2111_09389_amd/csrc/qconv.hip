@@ -519,6 +519,28 @@ extern "C" int lpdt_qconv_bwd_data_pack_filter(const lpdt_conv_desc *d, const in
     return launch_status("lpdt_qconv_bwd_data_pack_filter");
 }
 
+extern "C" int lpdt_qconv_bwd_data_pack_filters(const lpdt_conv_desc *descs, int count, const int8_t *const *wq, void *const *packed,
+                                                const size_t *packed_bytes, void *stream) {
+    LPDT_REQUIRE(count >= 0, LPDT_EINVAL, "qconv_bwd_data_pack_filters: negative count");
+    if (count == 0) return LPDT_OK;
+    LPDT_REQUIRE(descs && wq && packed && packed_bytes, LPDT_EINVAL, "qconv_bwd_data_pack_filters: NULL argument");
+    for (int i = 0; i < count; ++i) {     // every filter is checked before anything is launched
+        const lpdt_conv_desc *d = descs + i;
+        int P, Q;
+        int rc = check_conv(d, &P, &Q);
+        if (rc) return rc;
+        LPDT_REQUIRE(wq[i] && packed[i], LPDT_EINVAL, "qconv_bwd_data_pack_filters: NULL filter %d", i);
+        LPDT_REQUIRE(bwd_data_vec(d, P, Q), LPDT_EUNSUPPORTED, "qconv_bwd_data_pack_filters: filter %d's shape has no packed filter", i);
+        LPDT_REQUIRE(aligned(wq[i], 16) && aligned(packed[i], 16), LPDT_EINVAL,
+                     "qconv_bwd_data_pack_filters: wq and packed must be 16-byte aligned (filter %d)", i);
+        LPDT_REQUIRE(packed_bytes[i] >= lpdt_qconv_bwd_data_packed_filter_bytes(d), LPDT_EWORKSPACE,
+                     "qconv_bwd_data_pack_filters: packed[%d] needs %zu bytes, got %zu", i, lpdt_qconv_bwd_data_packed_filter_bytes(d),
+                     packed_bytes[i]);
+    }
+    launch_igemm_pack_bwd_filters(descs, count, wq, packed, as_stream(stream));
+    return launch_status("lpdt_qconv_bwd_data_pack_filters");
+}
+
 extern "C" int lpdt_qconv_bwd_data_f32_packed(const lpdt_conv_desc *d, const int8_t *gq, const void *packed, const float *sg,
                                               const float *sw, float *dx, int accumulate, void *ws, size_t ws_bytes, void *stream) {
     int P, Q;

@@ -278,11 +278,10 @@ struct PackParams {
     int Rc[kMaxClasses], Sc[kMaxClasses];
 };
 // A block transposes one 64 (c) x 64 (k) tile of one filter tap through LDS: 16-byte loads along c (contiguous in w),
-// 16-byte stores along k (contiguous in the panel).  grid = taps of all classes x c-tiles x k-tiles; C, K multiples of 16.
-__global__ __launch_bounds__(256) void pack_filter_bwd_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wt, const PackParams q) {
-    __shared__ unsigned char tile[64][64 + 16];  // [k][c], rows padded
+// 16-byte stores along k (contiguous in the panel).  b = taps of all classes x c-tiles x k-tiles; C, K multiples of 16.
+__device__ __forceinline__ void pack_filter_tile(const int8_t *__restrict__ w, int8_t *__restrict__ wt, const PackParams &q, int b,
+                                                 unsigned char (*tile)[64 + 16]) {
     const int tc = (q.C + 63) / 64, tk = (q.K + 63) / 64;
-    int b = blockIdx.x;
     const int kt = b % tk; b /= tk;
     const int ct = b % tc; b /= tc;   // b = tap index over all classes
     int cl = 0;
@@ -302,6 +301,26 @@ __global__ __launch_bounds__(256) void pack_filter_bwd_kernel(const int8_t *__re
         *reinterpret_cast<int4 *>(wt + q.off[cl] + ((size_t)(c0 + row) * nslots + slot) * q.K + k0 + chunk) =
             make_int4((int)o[0], (int)o[1], (int)o[2], (int)o[3]);
     }
+}
+__global__ __launch_bounds__(256) void pack_filter_bwd_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wt, const PackParams q) {
+    __shared__ unsigned char tile[64][64 + 16];  // [k][c], rows padded
+    pack_filter_tile(w, wt, q, blockIdx.x, tile);
+}
+// The same for several filters in one launch (a network's filters are all final at the same moment, and a launch per
+// filter is mostly launch latency): the table travels in the kernel arguments; a block finds its filter by its number.
+constexpr int kPackBatch = 24;
+struct PackBatch {
+    int count;
+    int first[kPackBatch + 1];   // first block of each filter
+    PackParams pk[kPackBatch];
+    const int8_t *w[kPackBatch];
+    int8_t *wt[kPackBatch];
+};
+__global__ __launch_bounds__(256) void pack_filter_bwd_batch_kernel(const PackBatch t) {
+    __shared__ unsigned char tile[64][64 + 16];
+    int f = 0;
+    while (f + 1 < t.count && (int)blockIdx.x >= t.first[f + 1]) ++f;
+    pack_filter_tile(t.w[f], t.wt[f], t.pk[f], (int)blockIdx.x - t.first[f], tile);
 }
 
 unsigned div_multiplier(int d, long long xmax) {
@@ -611,14 +630,39 @@ void launch_igemm_fwd_stats(const lpdt_conv_desc *d, int P, int Q, const int8_t 
 
 size_t igemm_bwd_filter_panel_bytes(const lpdt_conv_desc *d) { return (size_t)d->K * d->R * d->S * d->C; }
 
+static int pack_blocks(const PackParams &pk) {
+    int taps = 0;
+    for (int cl = 0; cl < pk.nclasses; ++cl) taps += pk.Rc[cl] * pk.Sc[cl];
+    return taps * ((pk.C + 63) / 64) * ((pk.K + 63) / 64);
+}
+
 void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const int8_t *w, void *panel, hipStream_t st) {
     IgemmParams p;
     PackParams pk;
     bwd_params(d, P, Q, &p, &pk);
-    int taps = 0;
-    for (int cl = 0; cl < pk.nclasses; ++cl) taps += pk.Rc[cl] * pk.Sc[cl];
-    const int b = taps * ((pk.C + 63) / 64) * ((pk.K + 63) / 64);
+    const int b = pack_blocks(pk);
     if (b > 0) hipLaunchKernelGGL(pack_filter_bwd_kernel, dim3((unsigned)b), dim3(256), 0, st, w, static_cast<int8_t *>(panel), pk);
+}
+
+void launch_igemm_pack_bwd_filters(const lpdt_conv_desc *descs, int count, const int8_t *const *w, void *const *panels, hipStream_t st) {
+    for (int i0 = 0; i0 < count; i0 += kPackBatch) {
+        PackBatch t;
+        t.count = 0;
+        t.first[0] = 0;
+        for (int i = i0; i < count && i < i0 + kPackBatch; ++i) {
+            const lpdt_conv_desc *d = descs + i;
+            IgemmParams p;
+            PackParams pk;
+            bwd_params(d, (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1, (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1, &p, &pk);
+            const int b = pack_blocks(pk);
+            if (b == 0) continue;
+            const int k = t.count++;
+            t.pk[k] = pk; t.w[k] = w[i]; t.wt[k] = static_cast<int8_t *>(panels[i]);
+            t.first[k + 1] = t.first[k] + b;
+        }
+        if (t.count > 0)
+            hipLaunchKernelGGL(pack_filter_bwd_batch_kernel, dim3((unsigned)t.first[t.count]), dim3(256), 0, st, t);
+    }
 }
 
 void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const void *panel, void *out, int out_mode,

@@ -35,6 +35,7 @@ void launch_igemm_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, co
 // aligned: made by the first call, consumed by the second (g and panel 16-byte aligned).
 size_t igemm_bwd_filter_panel_bytes(const lpdt_conv_desc *d);
 void launch_igemm_pack_bwd_filter(const lpdt_conv_desc *d, int P, int Q, const int8_t *w, void *panel, hipStream_t st);
+void launch_igemm_pack_bwd_filters(const lpdt_conv_desc *descs, int count, const int8_t *const *w, void *const *panels, hipStream_t st);
 void launch_igemm_bwd_data(const lpdt_conv_desc *d, int P, int Q, const int8_t *g, const void *panel, void *out, int out_mode,
                            const float *sA, const float *sB, hipStream_t st, float *pabs = nullptr);
 

@@ -246,11 +246,13 @@ bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *pl) {
     if (pl->lds > 80 * 1024) return false;
     pl->tiles_k = d->K / pl->kt;
     pl->tiles_kc = pl->tiles_k * (d->C / 64);
-    // One block of 8 waves per CU.  Twice as many finish this product 5 % sooner on an idle chip, but in the training
-    // step it runs beside the backward-data product of the same layer, which then loses more than this one gains.
-    long long target = 256;
+    // Fewer blocks than CUs.  On an idle chip 256 blocks (one per CU) finish this product ~10 % sooner and 512 another 5 %,
+    // but in the training step it runs beside the main chain's kernels on the other stream, and what counts there is how much
+    // of the chip it takes from them and the bytes of partial tiles it moves: measured in the ResNet-18 step, 192 blocks
+    // give the shortest step (128: +50 us, 256: +45 us, 512: +130 us).
+    long long target = 192;
 #ifdef LPDT_TUNE
-    if (const char *e = getenv("LPDT_WGRAD_BLOCKS")) target = atoi(e);
+    if (const char *e = getenv("LPDT_WGRAD_ROWS_BLOCKS")) target = atoi(e);
 #endif
     long long splits = target / pl->tiles_kc;
     if (splits > nt / 2) splits = nt / 2;             // at least two tiles per block: one to hide the other's loads

@@ -219,7 +219,8 @@ class TrainStep:
             for i, (op, (b, e)) in enumerate(zip(convs, spans)):
                 self.wq[op[1]] = wq_flat[b:e].view(self.pview[op[3]["w"]].shape)
                 self.sw[op[1]] = sw_all[i:i + 1]
-            if self.prepack_filters:     # the codes of every filter are final here
+            if self.prepack_filters:     # the codes of every filter are final here: one launch prepares them all
+                todo = []
                 for op in convs:
                     if op[2] == "x":
                         continue         # no backward-data for the image layer
@@ -227,9 +228,13 @@ class TrainStep:
                     nb = int(L.lpdt_qconv_bwd_data_packed_filter_bytes(ctypes.byref(d)))
                     if nb == 0 or self.wq[op[1]].data_ptr() % 16:
                         continue
-                    packed = torch.empty(nb, dtype=torch.uint8, device=self.dev)
-                    self.wpacked[op[1]] = packed
-                    self._emit(L.lpdt_qconv_bwd_data_pack_filter, [ctypes.byref(d), _p(self.wq[op[1]]), _p(packed), _sz(nb)], side=True)
+                    self.wpacked[op[1]] = torch.empty(nb, dtype=torch.uint8, device=self.dev)
+                    todo.append((d, self.wq[op[1]], self.wpacked[op[1]], nb))
+                if todo:
+                    n = len(todo)
+                    self._pack_arrays = ((ConvDesc * n)(*[t[0] for t in todo]), (ctypes.c_void_p * n)(*[t[1].data_ptr() for t in todo]),
+                                         (ctypes.c_void_p * n)(*[t[2].data_ptr() for t in todo]), (ctypes.c_size_t * n)(*[t[3] for t in todo]))
+                    self._emit(L.lpdt_qconv_bwd_data_pack_filters, [self._pack_arrays[0], n, *self._pack_arrays[1:]], side=True)
         for op in net.ops:
             kind = op[0]
             if kind == "conv":
@@ -580,7 +585,7 @@ class TrainStep:
             b.record()
             if rc != 0:
                 raise LpdtError(rc, self.L.lpdt_last_error().decode())
-            desc = args[0]._obj if fn.__name__.startswith("lpdt_qconv_") else None
+            desc = getattr(args[0], "_obj", None) if fn.__name__.startswith("lpdt_qconv_") else None
             marks.append((fn.__name__, a, b, desc))
         torch.cuda.synchronize()
         if with_desc:

@@ -228,6 +228,21 @@ def test_backward_data_with_prepacked_filter_equals_the_plain_call(shp):
     assert torch.equal(got2, ref2)
 
 
+def test_filters_prepacked_in_one_launch_equal_the_single_calls():
+    """lpdt_qconv_bwd_data_pack_filters: the bytes of lpdt_qconv_bwd_data_pack_filter for every filter, with more filters
+    than one launch's table holds (24), stride 1 and 2, 1x1 and 3x3; a shape without a prepared form is refused."""
+    shapes = [CASES[1], CASES[3], CASES[4], CASES[5], CASES[13], CASES[15]] * 5
+    descs = [lpdt.ConvDesc.make(*shp) for shp in shapes]
+    ws = [dev(_data(shp, 1200 + i, "gauss")[1]) for i, shp in enumerate(shapes)]
+    got = lpdt.qconv_bwd_data_pack_filters(descs, ws)
+    for d, w, t in zip(descs, ws, got):
+        ref = lpdt.qconv_bwd_data_pack_filter(d, w)
+        assert torch.equal(t[:ref.numel()], ref)
+    bad = lpdt.ConvDesc.make(1, 20, 6, 6, 24, 3, 3, 1, 1)
+    with pytest.raises(lpdt.LpdtError):
+        lpdt.qconv_bwd_data_pack_filters([descs[0], bad], [ws[0], torch.zeros((24, 3, 3, 20), dtype=torch.int8, device="cuda")])
+
+
 def test_prepacked_filter_is_refused_where_backward_data_has_no_packed_form():
     ld = lpdt.ConvDesc.make(1, 20, 6, 6, 24, 3, 3, 1, 1)     # channel counts that are not multiples of 16
     w = torch.zeros((24, 3, 3, 20), dtype=torch.int8, device="cuda")

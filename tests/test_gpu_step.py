@@ -351,7 +351,7 @@ def test_driver_prepacked_filters_change_no_bit(orc):
         p, g = dev(flat), torch.zeros(flat.size, dtype=torch.float32, device="cuda")
         ts = TrainStep(net, N, p, g, x, lb, None, lr=0.05, seed=wl.PHILOX_SEED, prepack_filters=pre)
         names = [c[0].__name__ for c in ts.calls if c[0] is not None]
-        assert ("lpdt_qconv_bwd_data_pack_filter" in names) == pre and ("lpdt_qconv_bwd_data_f32_packed" in names) == pre
+        assert ("lpdt_qconv_bwd_data_pack_filters" in names) == pre and ("lpdt_qconv_bwd_data_f32_packed" in names) == pre
         ts.run(1)
         ts.run(2)          # the second step must see the filters of the updated weights
         torch.cuda.synchronize()
