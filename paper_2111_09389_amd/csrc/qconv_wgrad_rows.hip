@@ -49,6 +49,11 @@ struct WgradRowsParams {
     int tiles_k, tiles_kc;
     float inv_Q, inv_PW;        // reciprocals for the set-up's divisions
     long long out_len;
+    // one share only (a block holds the complete sums of its tile): the results go straight to their place, no partial
+    // tiles and no second launch.  direct_mode: 0 int32 sums, 1 fp32 sA*sB*sum (the reduction kernel's arithmetic).
+    void *direct;
+    int direct_mode;
+    const float *sA, *sB;
 };
 
 // LDS layouts.  Gradient tile: [slot][32 B]; the 8 consecutive slots one transposing read touches are 256 contiguous
@@ -199,7 +204,9 @@ __global__ __launch_bounds__(64 * kRowsWaves, 2) void wgrad_rows_kernel(const Wg
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the zero loads past the last tile
 
     // a lane holds input channel lane%32 of its sub-tile and output channels 8*(r/4) + 4*(lane/32) + r%4
-    int32_t *out = p.partial + (size_t)z * p.out_len;
+    const bool as_float = p.direct && p.direct_mode;
+    int32_t *out = p.direct ? static_cast<int32_t *>(p.direct) : p.partial + (size_t)z * p.out_len;
+    const float sc = as_float ? __fmul_rn(*p.sA, *p.sB) : 0.0f;
     const int c = c0 + 32 * tj + (lane & 31);
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
@@ -208,7 +215,9 @@ __global__ __launch_bounds__(64 * kRowsWaves, 2) void wgrad_rows_kernel(const Wg
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = k0 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                out[((size_t)k * p.ntaps + tap) * p.C + c] = acc[i][r];
+                const size_t at = ((size_t)k * p.ntaps + tap) * p.C + c;
+                if (as_float) reinterpret_cast<float *>(out)[at] = dequant_value(sc, acc[i][r], 0.f, false);
+                else out[at] = acc[i][r];
             }
         }
     }
@@ -284,6 +293,11 @@ void launch_wgrad_rows(const lpdt_conv_desc *d, int P, int Q, const WgradRowsPla
         }
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(64 * kRowsWaves), pl.lds, st, p);
     };
+    if (pl.splits == 1) {
+        p.direct = out; p.direct_mode = out_mode; p.sA = sA; p.sB = sB;
+        go(wgrad_rows_kernel<3>);
+        return;
+    }
     go(wgrad_rows_kernel<3>);
     launch_wgrad_reduce(p.partial, pl.out_len, pl.splits, out, out_mode, sA, sB, st);
 }

@@ -86,7 +86,8 @@ def test_row_tile_kernel_bit_exact(orc, shp):
 WGRAD_ROWS_CASES = [(5, 64, 57, 41, 32, 3, 3, 1, 1), (3, 64, 6, 80, 64, 3, 3, 1, 1), (37, 128, 7, 7, 96, 3, 3, 1, 1),
                     (9, 64, 8, 8, 32, 3, 3, 1, 1), (6, 64, 30, 30, 64, 3, 3, 1, 0), (4, 64, 20, 22, 32, 3, 3, 1, 2),
                     (3, 64, 33, 17, 32, 2, 2, 1, 0), (5, 128, 14, 14, 64, 3, 1, 1, 0), (5, 64, 14, 16, 160, 1, 3, 1, 0),
-                    (2, 192, 12, 28, 64, 2, 3, 1, 1), (67, 64, 28, 28, 32, 3, 3, 1, 1)]
+                    (2, 192, 12, 28, 64, 2, 3, 1, 1), (67, 64, 28, 28, 32, 3, 3, 1, 1),
+                    (3, 512, 7, 7, 512, 3, 3, 1, 1)]   # the last: 128 output tiles, one pixel share -> results stored by the product kernel itself
 
 
 @pytest.mark.parametrize("shp", WGRAD_ROWS_CASES)
