@@ -44,7 +44,8 @@ class TrainStep:
                  fuse_conv_ren=False):
         self.L = lib()
         self.overlap_wgrad = overlap_wgrad
-        self.fork_batch = 2              # second-stream calls issued behind one fork event (measured: 1 and 3 are slower)
+        self.fork_batch = 2              # second-stream calls issued behind one fork event (measured: 1 and 3 are slower, and so is
+                                         # 2 with the pairs shifted by one call: +30 us)
         self.fuse_ren_quant = fuse_ren_quant   # Range-EvoNorm layers that feed only convolutions emit int8 codes directly
         # backward-data's transposed filters are made once per step, on the second stream beside the forward pass
         self.prepack_filters = prepack_filters and overlap_wgrad
@@ -554,8 +555,19 @@ class TrainStep:
                 args[pos] = _u64((int(step) << 32) + (sr << 24))
             if on_side:
                 pending.append((fn, args))
-                if len(pending) >= self.fork_batch and not (i + 1 < n and calls[i + 1][3]):
-                    flush()                  # (a run of consecutive second-stream calls is never split)
+                if i + 1 < n and calls[i + 1][3]:
+                    continue                 # a run of consecutive second-stream calls is never split
+                # a call goes out at once when no partner follows before the next join (the filter preparation at the
+                # start of the step would otherwise wait for the first weight gradient and be joined right after it)
+                partner = False
+                for j in range(i + 1, n):
+                    if calls[j][0] is None or calls[j][0] is self.L.lpdt_sgd:
+                        break
+                    if calls[j][3]:
+                        partner = True
+                        break
+                if len(pending) >= self.fork_batch or not partner:
+                    flush()
                 continue
             if fn is None:
                 join()

@@ -103,6 +103,27 @@ def test_wgrad_rows_kernel_bit_exact(orc, shp):
     assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
 
 
+# backward-weight of first-layer shapes (few input channels; kernel id 1): 1, 3, 4, 5 and 6 input channels, windows of exactly
+# 32 bytes, strides 1 and 2, 4- and 8-row filters, fewer than 64 output channels, pixel counts that leave ragged last steps
+# and idle waves
+NARROW_WGRAD_CASES = [((3, 3, 37, 41, 64, 7, 7, 2, 3), 1), ((5, 3, 32, 32, 16, 3, 3, 1, 1), 1), ((2, 1, 28, 28, 32, 5, 5, 1, 2), 1),
+                      ((2, 5, 20, 20, 48, 3, 3, 2, 1), 1), ((70, 3, 24, 24, 64, 7, 7, 2, 3), 1), ((2, 4, 18, 18, 64, 8, 8, 1, 0), 1),
+                      ((16, 3, 224, 224, 64, 7, 7, 2, 3), 1), ((2, 6, 12, 12, 32, 5, 5, 1, 2), 1), ((2, 3, 20, 24, 32, 3, 9, 1, 1), 1)]
+
+
+@pytest.mark.parametrize("shp,kid", NARROW_WGRAD_CASES)
+def test_first_layer_weight_gradient_bit_exact(orc, shp, kid):
+    x, w, g = _data(shp, 1300, "uniform")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert lpdt.qconv_kernel_id(ld, 2) == kid, "the planner changed: pick shapes that reach the first-layer weight-gradient kernel"
+    print("first-layer wgrad", shp, flush=True)
+    ref = orc.qconv_bwd_weight(od, g, x)
+    assert np.array_equal(host(lpdt.qconv_bwd_weight(ld, dev(g), dev(x))), ref), "backward-weight"
+    sa, sb = dev(np.array([0.013], np.float32)), dev(np.array([0.0037], np.float32))
+    want = lpdt.dequantize(dev(ref.astype(np.int32)), sa, sb)
+    assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
+
+
 # backward-weight of pointwise products through wgrad_gemm_kernel (kernel id 62): token counts that are no multiple of the
 # 64-token step or of a block's share, 3 x 3 / 3 x 12 / 12 x 3 / 4 x 4 tiles, a spatial 1x1 layer
 WGRAD_GEMM_CASES = [(8200, 768, 1, 1, 768, 1, 1, 1, 0), (3001, 768, 1, 1, 3072, 1, 1, 1, 0), (2987, 3072, 1, 1, 768, 1, 1, 1, 0),
