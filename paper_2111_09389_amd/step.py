@@ -450,9 +450,12 @@ class TrainStep:
                     self._emit(L.lpdt_qconv_bwd_weight_bf16, [ctypes.byref(d), _p(g16), _p(self.xq[inp]), _p(self.sx[inp]), _p(gw),
                                                               "WS", "WSB"], side=True)
                 else:
-                    self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)), side=self.overlap_wgrad)
+                    # the image layer's product is the last of the backward pass and nothing is left to run beside it: on
+                    # the main stream it saves the fork and join around it
+                    beside = inp != "x"
+                    self._need_ws(L.lpdt_qconv_bwd_weight_f32_workspace_bytes(ctypes.byref(d)), side=self.overlap_wgrad and beside)
                     self._emit(L.lpdt_qconv_bwd_weight_f32, [ctypes.byref(d), _p(gq), _p(self.xq[inp]), _p(sg), _p(self.sx[inp]),
-                                                             _p(gw), "WS", "WSB"], side=True)
+                                                             _p(gw), "WS", "WSB"], side=beside)
             elif kind == "ren":
                 _, _, inp, a = op
                 H, W, C = net.shapes[inp]
