@@ -121,6 +121,26 @@ __global__ void choco_init_kernel(PairState *st, const long long *kk, int n, int
     }
 }
 
+// The set-up in one launch when its three tables (segment offsets, per-segment k, sampled tiles) fit one kernel-argument
+// chunk together: what three upload_kernel launches and choco_init_kernel do (four dependent launches of ~4 us each).
+__global__ void choco_setup_kernel(UploadChunk c, int n_off, int n_k, int n_list, long long *d_off, long long *d_k, long long *d_list,
+                                   PairState *st, int n, int nseg, unsigned int *hist, size_t hist_words, unsigned int *any_redo) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (size_t)n_off) d_off[i] = c.v[i];
+    if (i < (size_t)n_k) d_k[i] = c.v[n_off + i];
+    if (i < (size_t)n_list) d_list[i] = c.v[n_off + n_k + i];
+    if (i < hist_words) hist[i] = 0u;
+    if (i == 0) *any_redo = 0u;
+    if (i < (size_t)n * nseg) {
+        PairState s;
+        s.prefix = 0ull;
+        s.rank = (unsigned int)c.v[n_off + i % nseg];
+        s.cand = 0u;
+        s.lo = 0u; s.hi = 0u; s.redo = 0u; s.above = 0u;
+        st[i] = s;
+    }
+}
+
 // The (non-empty) segment holding element e < off[nseg], found by the whole block at once: every thread tests the
 // segments tid, tid + blockDim, ..., so the block waits for one round of loads instead of a binary search's chain.
 // The caller's next __syncthreads() publishes *s_first.
@@ -1024,37 +1044,51 @@ static int mix_impl(float *x, float *state, int n, size_t d, const float *W, flo
             reinterpret_cast<unsigned long long *>(base + L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes);
         float *xhat = state;
         const int dsi = ds ? 1 : 0;
-        upload(off.data(), nseg + 1, d_off, st);
+        if (select_all) upload(off.data(), nseg + 1, d_off, st);
         if (!select_all) {
-            upload(kk.data(), nseg, d_k, st);
             const size_t hist_words = (size_t)n * nseg * kBins;
             unsigned int *d_redo = reinterpret_cast<unsigned int *>(base + L.off_bytes + L.k_bytes + L.state_bytes + L.hist_bytes + L.cand_bytes);
             unsigned int *d_tiles = d_redo + L.flag_bytes / sizeof(unsigned int);
-            hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
-                               nseg, d_hist, hist_words, d_redo);
             const unsigned int ntiles = (unsigned int)((d + kTile - 1) / kTile);
             const dim3 tiles(ntiles, n);
             const bool vec4 = d % 4 == 0 && aligned(x, 16) && aligned(xhat, 16);
             const int stride = one_pass_stride(n, d);
             const long long *no_list = nullptr;
             const unsigned int *none = nullptr;
+            // The sample of the one-pass selection (see below): every stride-th tile, and every tile with a segment boundary
+            // in it, so that short segments are sampled completely and each longer one at least in the tiles of its two ends.
+            std::vector<long long> list;
+            long long *d_list = reinterpret_cast<long long *>(reinterpret_cast<char *>(d_tiles) + L.tile_bytes);
+            if (stride > 0) {
+                std::vector<char> mark(ntiles, 0);
+                for (unsigned int t = 0; t < ntiles; t += (unsigned int)stride) mark[t] = 1;
+                for (int sg = 1; sg < nseg; ++sg)
+                    if (off[sg] > 0 && off[sg] < (long long)d && off[sg] % kTile != 0) mark[(size_t)(off[sg] / kTile)] = 1;
+                for (unsigned int t = 0; t < ntiles; ++t)
+                    if (mark[t]) list.push_back((long long)t);
+            }
+            if ((size_t)(nseg + 1) + (size_t)nseg + list.size() <= (size_t)kUploadChunk) {
+                UploadChunk c;
+                for (int i = 0; i <= nseg; ++i) c.v[i] = off[i];
+                for (int i = 0; i < nseg; ++i) c.v[nseg + 1 + i] = kk[i];
+                for (size_t i = 0; i < list.size(); ++i) c.v[2 * nseg + 1 + i] = list[i];
+                size_t threads = hist_words > (size_t)kUploadChunk ? hist_words : (size_t)kUploadChunk;
+                if (threads < (size_t)n * nseg) threads = (size_t)n * nseg;
+                hipLaunchKernelGGL(choco_setup_kernel, dim3((unsigned int)((threads + 255) / 256)), dim3(256), 0, st, c, nseg + 1, nseg,
+                                   (int)list.size(), d_off, d_k, d_list, d_st, n, nseg, d_hist, hist_words, d_redo);
+            } else {
+                upload(off.data(), nseg + 1, d_off, st);
+                upload(kk.data(), nseg, d_k, st);
+                hipLaunchKernelGGL(choco_init_kernel, dim3((unsigned int)((hist_words + 255) / 256)), dim3(256), 0, st, d_st, d_k, n,
+                                   nseg, d_hist, hist_words, d_redo);
+                if (!list.empty()) upload(list.data(), (int)list.size(), d_list, st);
+            }
             if (stride > 0) {
                 // One pass over the data instead of two: a histogram of a sample of the tiles guesses, per pair, a window
                 // of bins around the threshold bin; the full pass counts the keys above the window, histograms the
                 // window and keeps its keys; the scan finds the threshold bin in the window.  A pair whose window
                 // missed (tiles that differ a lot from the sampled ones) goes through the two-pass form afterwards:
                 // three launches that end at once when there is none.  The result is exact either way.
-                // The sample: every stride-th tile, and every tile with a segment boundary in it, so that short
-                // segments are sampled completely and each longer one at least in the tiles of its two ends.
-                std::vector<char> mark(ntiles, 0);
-                for (unsigned int t = 0; t < ntiles; t += (unsigned int)stride) mark[t] = 1;
-                for (int sg = 1; sg < nseg; ++sg)
-                    if (off[sg] > 0 && off[sg] < (long long)d && off[sg] % kTile != 0) mark[(size_t)(off[sg] / kTile)] = 1;
-                std::vector<long long> list;
-                for (unsigned int t = 0; t < ntiles; ++t)
-                    if (mark[t]) list.push_back((long long)t);
-                long long *d_list = reinterpret_cast<long long *>(reinterpret_cast<char *>(d_tiles) + L.tile_bytes);
-                upload(list.data(), (int)list.size(), d_list, st);
                 const dim3 sampled((unsigned int)list.size(), n), few(ntiles < 128u ? ntiles : 128u, n);
                 const int nl = (int)list.size(), nt = (int)ntiles;
                 const unsigned int *redo = d_redo;
