@@ -164,6 +164,14 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
  *       shapes): 256 x 256 tiles, both operands loaded straight into LDS and read back transposed */
 int lpdt_qconv_kernel_id(const lpdt_conv_desc *d, int product);
 
+/* How the backward-weight products size their launches.  beside == 0 (the default): for a product that has the chip to
+ * itself (one block per compute unit or more).  beside != 0: for a product issued beside other kernels, as a training
+ * step does on a second stream -- fewer blocks, which leaves compute units to the other stream and writes fewer partial
+ * tiles; alone such a launch is up to 40 % slower, beside the backward chain of a ResNet-18 step it makes the step ~2 %
+ * shorter.  Results are identical, bit for bit (integer sums).  Process-wide, takes effect at the next call; the
+ * workspace queries cover both settings.  Always returns LPDT_OK. */
+int lpdt_qconv_set_wgrad_beside(int beside);
+
 /* The same three products with the dequantizing scale applied in the kernel epilogue: the result
  * is the fp32 tensor (s_a*s_b)*sum, bit-identical to the int32 call followed by lpdt_dequantize,
  * without the int32 tensor making a round trip through HBM.  s_*: fp32 device scalars (the scales

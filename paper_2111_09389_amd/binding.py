@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_ren_fwd_q", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_pack_filters", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_pack_filters", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "qconv_set_wgrad_beside", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -45,7 +45,7 @@ EXPORTS = [
     "lpdt_range_bn_fwd_workspace_bytes", "lpdt_range_bn_bwd_workspace_bytes", "lpdt_range_bn_fwd", "lpdt_range_bn_bwd",
     "lpdt_gossip_mix_workspace_bytes", "lpdt_gossip_mix", "lpdt_gossip_set_sample_stride", "lpdt_gossip_mix_ex_workspace_bytes", "lpdt_gossip_mix_ex",
     "lpdt_add", "lpdt_maxpool_fwd", "lpdt_maxpool_bwd", "lpdt_avgpool_fwd", "lpdt_avgpool_bwd",
-    "lpdt_softmax_xent", "lpdt_sgd",
+    "lpdt_softmax_xent", "lpdt_sgd", "lpdt_qconv_set_wgrad_beside",
 ]
 
 
@@ -330,6 +330,11 @@ def qconv_bwd_data_f32_absmax(d, gq, wq, sg, sw, packed=None, dx=None, accumulat
     _check(lib().lpdt_qconv_bwd_data_f32_absmax(ctypes.byref(d), _ptr(gq), _ptr(wq), _ptr(packed), _ptr(sg), _ptr(sw), _ptr(dx),
                                                 int(bool(accumulate)), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
     return dx, absmax
+
+
+def qconv_set_wgrad_beside(beside):
+    """Size the backward-weight launches for running beside other kernels (True) or alone (False, the default)."""
+    _check(lib().lpdt_qconv_set_wgrad_beside(int(bool(beside))))
 
 
 def qconv_bwd_data_pack_filter(d, wq):

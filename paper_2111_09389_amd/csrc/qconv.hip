@@ -645,10 +645,19 @@ static size_t bwd_weight_base_ws(const lpdt_conv_desc *d0, int P, int Q) {
     WgradRectPlan pl;
     WgradRowsPlan rows;
     if (narrow_conv_supported(d, P, Q)) return round_up(narrow_wgrad_workspace(d), 256);
-    if (wgrad_rows_plan(d, P, Q, &rows)) return rows.partial_bytes;
+    // (partial tiles: the mode with more blocks needs more room, and the mode may change between query and call)
+    if (wgrad_rows_plan(d, P, Q, &rows, 0)) {
+        const size_t alone = rows.partial_bytes;
+        wgrad_rows_plan(d, P, Q, &rows, 1);
+        return alone > rows.partial_bytes ? alone : rows.partial_bytes;
+    }
     WgradGemmPlan gemm;
     if (wgrad_gemm_plan(d, P, Q, &gemm)) return gemm.partial_bytes;
-    if (wgrad_rect_plan(d, P, Q, &pl)) return pl.partial_bytes;
+    if (wgrad_rect_plan(d, P, Q, &pl, 0)) {
+        const size_t alone = pl.partial_bytes;
+        wgrad_rect_plan(d, P, Q, &pl, 1);
+        return alone > pl.partial_bytes ? alone : pl.partial_bytes;
+    }
     return 0;
 }
 
@@ -796,6 +805,11 @@ extern "C" int lpdt_qconv_ren_fwd_q(const lpdt_conv_desc *d, const int8_t *xq, c
 }
 
 // ---------------------------------------------------------------- which kernel a call takes
+extern "C" int lpdt_qconv_set_wgrad_beside(int beside) {
+    set_wgrad_beside(beside);
+    return LPDT_OK;
+}
+
 extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
     int P, Q;
     int rc = check_conv(d0, &P, &Q);

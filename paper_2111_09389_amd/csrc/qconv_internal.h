@@ -46,7 +46,11 @@ struct WgradRectPlan {
     long long out_len;
     size_t partial_bytes, lds;
 };
-bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *plan);  // false: shape not handled
+// beside: 1 the product runs beside other kernels (fewer blocks), 0 it has the chip to itself, -1 what the caller set
+// with lpdt_qconv_set_wgrad_beside
+int wgrad_beside();
+void set_wgrad_beside(int v);
+bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *plan, int beside = -1);  // false: shape not handled
 // out_mode 0: int32 sums; 1: fp32 sA*sB*sum.  `partial` needs plan.partial_bytes.
 void launch_wgrad_rect(const lpdt_conv_desc *d, int P, int Q, const WgradRectPlan &plan, const int8_t *g, const int8_t *x,
                        void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
@@ -57,7 +61,7 @@ struct WgradRowsPlan {
     long long out_len;
     size_t partial_bytes, lds;
 };
-bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *plan);
+bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *plan, int beside = -1);
 void launch_wgrad_rows(const lpdt_conv_desc *d, int P, int Q, const WgradRowsPlan &plan, const int8_t *g, const int8_t *x,
                        void *out, int out_mode, const float *sA, const float *sB, void *partial, hipStream_t st);
 

@@ -10,6 +10,7 @@
 // writes its sums as ONE plain partial tile; a second kernel adds the partial tiles (exact integers: order-free) and applies the
 // dequantizing scale when asked.  No atomics, no zero fill, bit-reproducible.
 #include "qconv_internal.h"
+#include <atomic>
 #include <type_traits>
 #ifdef LPDT_TUNE
 #include <cstdlib>
@@ -315,16 +316,21 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const int32_t *__rest
     }
 }
 
-static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradRectPlan *pl);
+static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradRectPlan *pl, int beside);
 
-bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl) {
+static std::atomic<int> g_wgrad_beside{0};
+int wgrad_beside() { return g_wgrad_beside.load(std::memory_order_relaxed); }
+void set_wgrad_beside(int v) { g_wgrad_beside.store(v ? 1 : 0, std::memory_order_relaxed); }
+
+bool wgrad_rect_plan(const lpdt_conv_desc *d, int P, int Q, WgradRectPlan *pl, int beside) {
+    if (beside < 0) beside = wgrad_beside();
     // 64-pixel steps (two MFMA k-groups per barrier) for multi-tap filters on maps that can fill them, when the halo
     // patch of such a step still fits the per-step load budget (stride-2 patches are four times larger); else 32.
-    if (d->R * d->S > 1 && P * Q >= 64 && rect_plan_with(d, P, Q, 2, pl)) return true;
-    return rect_plan_with(d, P, Q, 1, pl);
+    if (d->R * d->S > 1 && P * Q >= 64 && rect_plan_with(d, P, Q, 2, pl, beside)) return true;
+    return rect_plan_with(d, P, Q, 1, pl, beside);
 }
 
-static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradRectPlan *pl) {
+static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradRectPlan *pl, int beside) {
     if (d->K % 16 || d->C % 16 || d->stride_h != d->stride_w || d->pad_h != d->pad_w) return false;
     const size_t lim = ((size_t)1 << 31) - 4096;  // 32-bit buffer offsets
     if ((size_t)d->N * P * Q * d->K >= lim || (size_t)d->N * d->H * d->W * d->C >= lim) return false;
@@ -356,9 +362,10 @@ static bool rect_plan_with(const lpdt_conv_desc *d, int P, int Q, int ks, WgradR
     pl->tiles_k = (d->K + pl->kt - 1) / pl->kt;
     pl->tiles_c = (d->C + pl->ct - 1) / pl->ct;
     const long long base = (long long)pl->tiles_k * pl->tiles_c * pl->groups;
-    // blocks wanted: 512 is the fastest on an idle chip, 256 gives the shortest training step (this product runs beside the
-    // main chain's kernels there; measured in the ResNet-18 step: 128 +15 us, 512 +20 us, 768 +27 us)
-    long long target = 256;
+    // blocks wanted: 512 is the fastest on an idle chip; 256 when the caller has said that the product runs beside other
+    // kernels (lpdt_qconv_set_wgrad_beside; measured in the ResNet-18 step, where it runs on a second stream: 128 +15 us,
+    // 512 +20 us, 768 +27 us)
+    long long target = beside ? 256 : 512;
 #ifdef LPDT_TUNE
     if (const char *e = getenv("LPDT_WGRAD_BLOCKS")) target = atoi(e);
 #endif

@@ -225,7 +225,8 @@ __global__ __launch_bounds__(64 * kRowsWaves, 2) void wgrad_rows_kernel(const Wg
 
 }  // namespace
 
-bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *pl) {
+bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *pl, int beside) {
+    if (beside < 0) beside = wgrad_beside();
     const int ntaps = d->R * d->S;
     if (d->stride_h != 1 || d->stride_w != 1 || d->R > 3 || d->S > 3 || ntaps < 2) return false;
     if (d->K % kRowsKT || d->C % 64 || Q > 128 || P < 1 || Q < 1) return false;
@@ -255,11 +256,11 @@ bool wgrad_rows_plan(const lpdt_conv_desc *d, int P, int Q, WgradRowsPlan *pl) {
     if (pl->lds > 80 * 1024) return false;
     pl->tiles_k = d->K / pl->kt;
     pl->tiles_kc = pl->tiles_k * (d->C / 64);
-    // Fewer blocks than CUs.  On an idle chip 256 blocks (one per CU) finish this product ~10 % sooner and 512 another 5 %,
-    // but in the training step it runs beside the main chain's kernels on the other stream, and what counts there is how much
+    // One block of 8 waves per CU when the product has the chip to itself.  When the caller has said that it runs beside
+    // other kernels (lpdt_qconv_set_wgrad_beside: the training step issues it on a second stream), what counts is how much
     // of the chip it takes from them and the bytes of partial tiles it moves: measured in the ResNet-18 step, 192 blocks
-    // give the shortest step (128: +50 us, 256: +45 us, 512: +130 us).
-    long long target = 192;
+    // give the shortest step (128: +50 us, 256: +45 us, 512: +130 us), although alone they take 40 % longer than 256.
+    long long target = beside ? 192 : 256;
 #ifdef LPDT_TUNE
     if (const char *e = getenv("LPDT_WGRAD_ROWS_BLOCKS")) target = atoi(e);
 #endif

@@ -552,6 +552,15 @@ class TrainStep:
                 main.wait_event(self._join_event)
                 joined = True
 
+        # the weight-gradient products are sized at launch: tell the library that they run beside the main chain
+        self.L.lpdt_qconv_set_wgrad_beside(1 if side is not None else 0)
+        try:
+            self._issue(calls, n, step, stream, pending, flush, join)
+        finally:
+            self.L.lpdt_qconv_set_wgrad_beside(0)
+
+    def _issue(self, calls, n, step, stream, pending, flush, join):
+        last = self.L.lpdt_last_error
         for i, (fn, args, sr, on_side) in enumerate(calls):
             if sr is not None:
                 pos = 5 if fn is self.L.lpdt_quantize_with_absmax else 4

@@ -124,6 +124,22 @@ def test_first_layer_weight_gradient_bit_exact(orc, shp, kid):
     assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
 
 
+@pytest.mark.parametrize("shp", [(67, 64, 28, 28, 32, 3, 3, 1, 1), (37, 128, 7, 7, 96, 3, 3, 1, 1), (40, 64, 28, 28, 128, 3, 3, 2, 1),
+                                 (40, 64, 28, 28, 128, 1, 1, 2, 0)])
+def test_weight_gradient_sized_for_running_beside_other_kernels(orc, shp):
+    """lpdt_qconv_set_wgrad_beside: fewer blocks (other pixel shares, other partial tiles), the same sums bit for bit -- row-tile
+    and rectangle kernels; the workspace query covers both settings."""
+    x, w, g = _data(shp, 1400, "uniform")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    ref = orc.qconv_bwd_weight(od, g, x)
+    try:
+        for beside in (True, False, True):
+            lpdt.qconv_set_wgrad_beside(beside)
+            assert np.array_equal(host(lpdt.qconv_bwd_weight(ld, dev(g), dev(x))), ref), f"beside={beside}"
+    finally:
+        lpdt.qconv_set_wgrad_beside(False)
+
+
 # backward-weight of pointwise products through wgrad_gemm_kernel (kernel id 62): token counts that are no multiple of the
 # 64-token step or of a block's share, 3 x 3 / 3 x 12 / 12 x 3 / 4 x 4 tiles, a spatial 1x1 layer
 WGRAD_GEMM_CASES = [(8200, 768, 1, 1, 768, 1, 1, 1, 0), (3001, 768, 1, 1, 3072, 1, 1, 1, 0), (2987, 3072, 1, 1, 768, 1, 1, 1, 0),
