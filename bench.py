@@ -319,7 +319,9 @@ def measure(cfg_id, nsteps, warmup, use_graph, device, detail=True, entry_points
                      "algorithmic_bytes": conv_algorithmic_bytes(net, cfg["batch"]) * len(steps),
                      "kernel": "all kernels behind the three conv entry points of one step (patch_conv_kernel, igemm_dma_kernel, "
                                "igemm_kernel, wgrad_rows_kernel / wgrad_rect_kernel + wgrad_reduce_kernel, narrow_*_kernel, "
-                               "linear_small_kernel, filter packing): conv ops / summed duration; "
+                               "linear_small_kernel, filter packing): conv ops / summed duration, every call timed with HIP events "
+                               "in separate steps on one stream (each product alone on the chip; the timed steps behind `value` run "
+                               "the weight gradients on a second stream, sized for that with lpdt_qconv_set_wgrad_beside); "
                                "traffic and algorithmic_bytes are per step like achieved"},
     }
     if detail:
