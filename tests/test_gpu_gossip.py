@@ -93,6 +93,21 @@ def test_choco_many_tiny_segments_in_one_tile(orc, sample_stride, stride):
     _choco_case(orc, 2, d, seg, 0.5, 0.5, 856, ties=True)
 
 
+@pytest.mark.parametrize("stride", [0, 2])
+def test_choco_more_segments_than_one_set_up_launch_carries(orc, sample_stride, stride):
+    """The segment table, the per-segment k and the sampled tiles normally travel in one kernel-argument chunk (384 values)
+    with the set-up launch; 260 segments do not fit, and the tables go up in launches of their own."""
+    sample_stride(stride)
+    g = wl.rng(860)
+    lens = [int(v) for v in g.integers(1, 400, size=257)] + [9000, 0, 6000]
+    seg = [0]
+    for n_ in lens:
+        seg.append(seg[-1] + n_)
+    d = seg[-1]
+    _choco_case(orc, 4, d, seg, 0.05, 0.4, 862)
+    _choco_case(orc, 2, d, seg, 0.3, 0.8, 864, ties=True)
+
+
 @pytest.mark.parametrize("loud", ["unsampled", "sampled"])
 def test_choco_one_pass_window_misses(orc, sample_stride, loud):
     """Sampled tiles that say nothing about the rest: the guessed window misses the threshold bin and the pair is
