@@ -161,7 +161,9 @@ int lpdt_qconv_bwd_weight(const lpdt_conv_desc *d, const int8_t *gq, const int8_
  *       channels of 64): tiles of whole output rows, gradient and input patch loaded straight into LDS, all taps
  *       read out of the one patch
  *   62  backward-weight of pointwise products with both channel counts multiples of 256 (linear layers at transformer
- *       shapes): 256 x 256 tiles, both operands loaded straight into LDS and read back transposed */
+ *       shapes): 256 x 256 tiles, both operands loaded straight into LDS and read back transposed
+ *   63  the same kernel with one filter tap per block, for stride-1 filters of up to 3 x 3 taps that the row-tile and
+ *       rectangle kernels decline (maps of a few pixels at channel counts that are multiples of 256) */
 int lpdt_qconv_kernel_id(const lpdt_conv_desc *d, int product);
 
 /* How the backward-weight products size their launches.  beside == 0 (the default): for a product that has the chip to

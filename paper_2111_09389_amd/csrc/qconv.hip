@@ -658,6 +658,7 @@ static size_t bwd_weight_base_ws(const lpdt_conv_desc *d0, int P, int Q) {
         wgrad_rect_plan(d, P, Q, &pl, 1);
         return alone > pl.partial_bytes ? alone : pl.partial_bytes;
     }
+    if (wgrad_gemm_taps_plan(d, P, Q, &gemm)) return gemm.partial_bytes;
     return 0;
 }
 
@@ -683,6 +684,10 @@ static void conv_bwd_weight_impl(const lpdt_conv_desc *d0, int P, int Q, const i
     }
     if (aligned(gq, 16) && aligned(xq, 16) && wgrad_uses_rect(d, P, Q, &pl)) {
         launch_wgrad_rect(d, P, Q, pl, gq, xq, out, out_mode, sA, sB, ws, st);
+        return;
+    }
+    if (aligned(gq, 16) && aligned(xq, 16) && !narrow_conv_supported(d, P, Q) && wgrad_gemm_taps_plan(d, P, Q, &gemm)) {
+        launch_wgrad_gemm(d, gemm, gq, xq, out, out_mode, sA, sB, ws, st);
         return;
     }
     if (narrow_conv_supported(d, P, Q) && aligned(gq, 16)) {
@@ -836,6 +841,7 @@ extern "C" int lpdt_qconv_kernel_id(const lpdt_conv_desc *d0, int product) {
         // 30 + tile (0: 32 x 64, 1: 64 x 64, 2: 128 x 128) + 4 for 64-pixel steps + 8 for two wave groups per block
         return 30 + (pl.kt == 128 ? 2 : pl.kt == 64 ? 1 : 0) + (pl.ks == 2 ? 4 : 0) + (pl.ng == 2 ? 8 : 0);
     }
+    if (!narrow_conv_supported(d, P, Q) && wgrad_gemm_taps_plan(d, P, Q, &gemm)) return 63;   // the same, one tap per block
     if (narrow_conv_supported(d, P, Q)) return 1;
     if (d->K % 16 == 0 && d->C % 16 == 0 && same_stride_pad(d)) return 2;
     return 0;

@@ -72,6 +72,7 @@ struct WgradGemmPlan {
     size_t partial_bytes;
 };
 bool wgrad_gemm_plan(const lpdt_conv_desc *d, int P, int Q, WgradGemmPlan *plan);
+bool wgrad_gemm_taps_plan(const lpdt_conv_desc *d, int P, int Q, WgradGemmPlan *plan);   // stride-1 filters of up to 3 x 3 taps
 void launch_wgrad_gemm(const lpdt_conv_desc *d, const WgradGemmPlan &plan, const int8_t *g, const int8_t *x, void *out, int out_mode,
                        const float *sA, const float *sB, void *partial, hipStream_t st);
 

@@ -12,7 +12,15 @@
 // LDS rows are 256 bytes = the bank period, so the 8 tokens of a transposing read would all hit the same banks: the
 // 16-byte granule q of token t sits at position q ^ 2*(t % 8).  The two 16-lane halves that are served together read
 // granules q and q + 1 (q even) of 8 consecutive tokens: 16 different positions.
+//
+// kTaps: the same for stride-1 filters of up to 3 x 3 taps on maps too small for the row-tile kernel (VGG's 4 x 4 and 2 x 2
+// maps at 512 channels): a block owns ONE tap of a 256 x 256 channel tile, dw[k][tap][c] = sum over output pixels t of
+// g[t][k] * x[t + tap][c]; the loader finds each token's input pixel (a pixel outside the image is fetched from beyond
+// the buffer: zeros), everything after the loads is the pointwise kernel.
 #include "qconv_internal.h"
+#ifdef LPDT_TUNE
+#include <cstdlib>
+#endif
 
 namespace lpdt {
 
@@ -40,7 +48,19 @@ struct WgradGemmParams {
     int steps, steps_per_split;
     int tiles_k, tiles_kc;
     long long out_len;
+    // kTaps only: the maps and the filter (stride 1); T = N * P * Q output pixels, x = [N][H][W][C]
+    int ntaps, S, pad_h, pad_w, H, W, P, Q;
+    float inv_pq, inv_q;
 };
+
+// q = m / d for 0 <= m < 2^24 through one float multiply and a correction step
+__device__ __forceinline__ int gemm_div24(int m, int d, float inv) {
+    int q = (int)((float)m * inv);
+    int r = m - q * d;
+    if (r < 0) { --q; r += d; }
+    if (r >= d) ++q;
+    return q;
+}
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
@@ -48,6 +68,7 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+template <bool kTaps>
 __global__ __launch_bounds__(64 * kGemmWaves, 1) void wgrad_gemm_kernel(const WgradGemmParams p) {
     constexpr int ST = kGemmStages, NL = kGemmLoads;
     constexpr int kOperand = kGemmStep * kGemmTile;      // bytes of one operand tile
@@ -58,7 +79,11 @@ __global__ __launch_bounds__(64 * kGemmWaves, 1) void wgrad_gemm_kernel(const Wg
     // the tiles of one token share sit next to each other on one XCD (blocks go round the 8 XCDs): they read the same tokens
     const int nb = gridDim.x;
     const int lid = nb % 8 == 0 ? (int)(blockIdx.x % 8) * (nb / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
-    const int z = lid / p.tiles_kc, kc = lid - z * p.tiles_kc;
+    // (with taps: the taps of a channel tile are neighbours too)
+    const int per_share = kTaps ? p.tiles_kc * p.ntaps : p.tiles_kc;
+    const int z = lid / per_share, rest = lid - z * per_share;
+    const int tap = kTaps ? rest / p.tiles_kc : 0, kc = rest - tap * p.tiles_kc;
+    const int ty = kTaps ? tap / p.S : 0, tx = tap - ty * p.S;
     const int k0 = (kc % p.tiles_k) * kGemmTile, c0 = (kc / p.tiles_k) * kGemmTile;
     const int step_begin = min(p.steps, z * p.steps_per_split), step_end = min(p.steps, step_begin + p.steps_per_split);
 
@@ -86,8 +111,17 @@ __global__ __launch_bounds__(64 * kGemmWaves, 1) void wgrad_gemm_kernel(const Wg
             if (i < 16) {
                 const unsigned off = ok ? (unsigned)(tok0 * p.K + loff[j]) : kBeyond;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_g, (lds_void *)(lds + buf * kStage + i * 1024), 16, off, 0, 0, 0);
-            } else {
+            } else if (!kTaps) {
                 const unsigned off = ok ? (unsigned)(tok0 * p.C + loff[j]) : kBeyond;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(lds + buf * kStage + i * 1024), 16, off, 0, 0, 0);
+            } else {
+                // output pixel (n, oy, ox) of this lane's token meets input pixel (n, oy + ty - pad, ox + tx - pad)
+                const int tk = min(tok0 + ltok[j], p.T - 1);
+                const int n = gemm_div24(tk, p.P * p.Q, p.inv_pq), rem = tk - n * p.P * p.Q;
+                const int oy = gemm_div24(rem, p.Q, p.inv_q), ox = rem - oy * p.Q;
+                const int iy = oy + ty - p.pad_h, ix = ox + tx - p.pad_w;
+                const bool in = ok && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+                const unsigned off = in ? (unsigned)(((n * p.H + iy) * p.W + ix) * p.C + (loff[j] - ltok[j] * p.C)) : kBeyond;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(lds + buf * kStage + i * 1024), 16, off, 0, 0, 0);
             }
         }
@@ -160,7 +194,7 @@ __global__ __launch_bounds__(64 * kGemmWaves, 1) void wgrad_gemm_kernel(const Wg
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = k0 + 128 * wk + 32 * i + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                out[(size_t)k * p.C + c] = acc[i][s][r];
+                out[kTaps ? ((size_t)k * p.ntaps + tap) * p.C + c : (size_t)k * p.C + c] = acc[i][s][r];
             }
         }
 }
@@ -188,6 +222,37 @@ bool wgrad_gemm_plan(const lpdt_conv_desc *d, int P, int Q, WgradGemmPlan *pl) {
     return true;
 }
 
+// Multi-tap form: for what the row-tile and rectangle kernels decline (the caller asks them first).
+bool wgrad_gemm_taps_plan(const lpdt_conv_desc *d, int P, int Q, WgradGemmPlan *pl) {
+    const int ntaps = d->R * d->S;
+    if (ntaps < 2 || d->R > 3 || d->S > 3 || d->stride_h != 1 || d->stride_w != 1) return false;
+    if (d->K % kGemmTile || d->C % kGemmTile) return false;
+    const long long T = (long long)d->N * P * Q;
+    const size_t lim = ((size_t)1 << 31) - 4096;  // 32-bit buffer offsets
+    if (T >= (1 << 24) || (size_t)T * d->K >= lim || (size_t)d->N * d->H * d->W * d->C >= lim) return false;
+    pl->T = (int)T;
+    pl->steps = (int)((T + kGemmStep - 1) / kGemmStep);
+    pl->tiles_k = d->K / kGemmTile;
+    pl->tiles_kc = pl->tiles_k * (d->C / kGemmTile);
+    const long long tiles = (long long)pl->tiles_kc * ntaps;
+    // blocks wanted: a few less than CUs, since a share more can push the launch just past one block per CU and into a
+    // second round (512 -> 512 on 4 x 4 maps, 36 tiles: 8 shares = 288 blocks 52 us, 5-7 shares 37-39 us, 4 shares 42 us)
+    long long target = 192, min_steps = 4;
+#ifdef LPDT_TUNE
+    if (const char *e = getenv("LPDT_WGRAD_GEMM_BLOCKS")) target = atoi(e);
+    if (const char *e = getenv("LPDT_WGRAD_GEMM_MINSTEPS")) min_steps = atoi(e);
+#endif
+    long long splits = (target + tiles - 1) / tiles;
+    if (splits > pl->steps / min_steps) splits = pl->steps / min_steps;  // each share's partial tile is written and read back: no shorter shares
+    if (splits < 1) return false;
+    pl->steps_per_split = (int)((pl->steps + splits - 1) / splits);
+    pl->splits = (pl->steps + pl->steps_per_split - 1) / pl->steps_per_split;
+    if (tiles * pl->splits < 64) return false;
+    pl->out_len = (long long)d->K * ntaps * d->C;
+    pl->partial_bytes = round_up((size_t)pl->splits * pl->out_len * sizeof(int32_t), 256);
+    return true;
+}
+
 void launch_wgrad_gemm(const lpdt_conv_desc *d, const WgradGemmPlan &pl, const int8_t *g, const int8_t *x, void *out, int out_mode,
                        const float *sA, const float *sB, void *partial, hipStream_t st) {
     WgradGemmParams p = {};
@@ -197,12 +262,27 @@ void launch_wgrad_gemm(const lpdt_conv_desc *d, const WgradGemmPlan &pl, const i
     p.steps = pl.steps; p.steps_per_split = pl.steps_per_split; p.tiles_k = pl.tiles_k; p.tiles_kc = pl.tiles_kc;
     p.out_len = pl.out_len;
     const size_t lds = (size_t)kGemmStages * 2 * kGemmStep * kGemmTile;
+    const int ntaps = d->R * d->S;
+    if (ntaps > 1) {
+        const int P = d->H + 2 * d->pad_h - d->R + 1, Q = d->W + 2 * d->pad_w - d->S + 1;   // stride 1
+        p.x_bytes = (unsigned)((size_t)d->N * d->H * d->W * d->C);
+        p.ntaps = ntaps; p.S = d->S; p.pad_h = d->pad_h; p.pad_w = d->pad_w; p.H = d->H; p.W = d->W; p.P = P; p.Q = Q;
+        p.inv_pq = 1.0f / (float)(P * Q); p.inv_q = 1.0f / (float)Q;
+        static bool raised_taps = false;
+        if (!raised_taps) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_gemm_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            raised_taps = true;
+        }
+        hipLaunchKernelGGL(wgrad_gemm_kernel<true>, dim3((unsigned)(pl.tiles_kc * ntaps * pl.splits)), dim3(64 * kGemmWaves), lds, st, p);
+        launch_wgrad_reduce(p.partial, pl.out_len, pl.splits, out, out_mode, sA, sB, st);
+        return;
+    }
     static bool raised = false;
     if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_gemm_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         raised = true;
     }
-    hipLaunchKernelGGL(wgrad_gemm_kernel, dim3((unsigned)(pl.tiles_kc * pl.splits)), dim3(64 * kGemmWaves), lds, st, p);
+    hipLaunchKernelGGL(wgrad_gemm_kernel<false>, dim3((unsigned)(pl.tiles_kc * pl.splits)), dim3(64 * kGemmWaves), lds, st, p);
     launch_wgrad_reduce(p.partial, pl.out_len, pl.splits, out, out_mode, sA, sB, st);
 }
 

@@ -146,6 +146,25 @@ WGRAD_GEMM_CASES = [(8200, 768, 1, 1, 768, 1, 1, 1, 0), (3001, 768, 1, 1, 3072, 
                     (9, 1024, 24, 25, 1024, 1, 1, 1, 0)]
 
 
+# the same kernel with one filter tap per block (kernel id 63): VGG's 4 x 4 and 2 x 2 maps at 512 channels, a ragged last
+# 64-pixel step on a 5 x 3 map, a 2 x 3 filter without padding, 512 -> 256 and 256 -> 512 channels
+WGRAD_GEMM_TAPS_CASES = [(64, 512, 4, 4, 512, 3, 3, 1, 1), (256, 512, 2, 2, 512, 3, 3, 1, 1), (100, 256, 5, 3, 512, 3, 3, 1, 1),
+                         (120, 512, 4, 4, 512, 2, 3, 1, 0), (77, 512, 4, 4, 256, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("shp", WGRAD_GEMM_TAPS_CASES)
+def test_wgrad_gemm_kernel_with_taps_bit_exact(orc, shp):
+    x, w, g = _data(shp, 950, "uniform")
+    od, ld = orc.conv_desc(*shp), lpdt.ConvDesc.make(*shp)
+    assert lpdt.qconv_kernel_id(ld, 2) == 63, "the planner changed: pick shapes that reach the one-tap-per-block GEMM weight gradient"
+    print("wgrad gemm taps", shp, flush=True)
+    ref = orc.qconv_bwd_weight(od, g, x)
+    assert np.array_equal(host(lpdt.qconv_bwd_weight(ld, dev(g), dev(x))), ref), "backward-weight"
+    sa, sb = dev(np.array([0.013], np.float32)), dev(np.array([0.0037], np.float32))
+    want = lpdt.dequantize(dev(ref.astype(np.int32)), sa, sb)
+    assert torch.equal(lpdt.qconv_bwd_weight_f32(ld, dev(g), dev(x), sa, sb), want), "backward-weight, fused scale"
+
+
 @pytest.mark.parametrize("shp", WGRAD_GEMM_CASES)
 def test_wgrad_gemm_kernel_bit_exact(orc, shp):
     x, w, g = _data(shp, 900, "uniform")
