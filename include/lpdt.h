@@ -303,19 +303,6 @@ int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W,
                            float *dgamma, float *dbeta, float *absmax_out, void *ws, size_t ws_bytes,
                            void *stream);
 
-/* The same gradient together with the int8 codes of dx (Section 3: the gradient a convolution's backward products read is
- * quantized with stochastic rounding): lpdt_range_evonorm_bwd(..., absmax_out) followed by
- * lpdt_quantize_with_absmax(dx, N*H*W*C, absmax_out, rounding, seed, offset, q, scale), bit for bit, in two launches
- * instead of three when a sample holds at most 64 Ki elements (the late layers, whose launches cost more than their
- * bytes); larger samples run the two calls' own launches.  q: int8 [N,H,W,C], 4-byte aligned; scale: fp32 device scalar;
- * absmax_out: optional, as above (for other readers of dx); dx is still written. */
-size_t lpdt_range_evonorm_bwd_q_workspace_bytes(int N, int H, int W, int C, int groups);
-int lpdt_range_evonorm_bwd_q(const float *dy, const float *x, int N, int H, int W, int C, int groups, const float *v,
-                             const float *gamma, float eps, const float *range, const int32_t *argmax,
-                             const int32_t *argmin, float *dx, float *dv, float *dgamma, float *dbeta, int rounding,
-                             uint64_t seed, uint64_t offset, int8_t *q, float *scale, float *absmax_out, void *ws,
-                             size_t ws_bytes, void *stream);
-
 /* Range-EvoNorm directly followed by a max-pool (the stem of the residual networks), for a normalised tensor
  * that nothing but the pool reads.  Forward: z [N,P,Q,C] and idx as lpdt_maxpool_fwd(lpdt_range_evonorm_fwd(x))
  * would give them, bit for bit, and the layer's saved range / argmax / argmin; the normalised tensor itself is

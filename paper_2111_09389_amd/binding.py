@@ -9,7 +9,7 @@ __all__ = [
     "quantize", "quantize_static", "quantize_with_absmax", "quantize_segments", "dequantize",
     "qconv_fwd", "qconv_bwd_data", "qconv_bwd_weight", "qconv_kernel_id", "qconv_fwd_f32", "qconv_fwd_f32_add", "qconv_ren_fwd_q", "qconv_bwd_data_f32", "qconv_bwd_weight_f32",
     "to_bf16", "qconv_bwd_weight_bf16",
-    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_bwd_q", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_pack_filters", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "qconv_set_wgrad_beside", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
+    "range_evonorm_fwd", "range_evonorm_fwd_q", "range_evonorm_bwd", "range_evonorm_maxpool_fwd", "range_evonorm_maxpool_bwd", "qconv_bwd_data_pack_filter", "qconv_bwd_data_pack_filters", "qconv_bwd_data_f32_packed", "qconv_fwd_f32_absmax", "qconv_bwd_data_f32_absmax", "evonorm_s0_fwd", "evonorm_s0_bwd", "range_bn_fwd", "range_bn_bwd", "gossip_mix", "gossip_mix_ex", "gossip_set_sample_stride", "qconv_set_wgrad_beside", "MIX_PLAIN", "MIX_CHOCO", "MIX_DEEPSQUEEZE",
     "add", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd",
     "Workspace", "EXPORTS",
 ]
@@ -33,7 +33,7 @@ EXPORTS = [
     "lpdt_qconv_ren_fwd_q_workspace_bytes", "lpdt_qconv_ren_fwd_q",
     "lpdt_to_bf16", "lpdt_qconv_bwd_weight_bf16_workspace_bytes", "lpdt_qconv_bwd_weight_bf16",
     "lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
-    "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd", "lpdt_range_evonorm_bwd_q_workspace_bytes", "lpdt_range_evonorm_bwd_q",
+    "lpdt_range_evonorm_fwd", "lpdt_range_evonorm_bwd",
     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_fwd_q",
     "lpdt_range_evonorm_maxpool_fwd_workspace_bytes", "lpdt_range_evonorm_maxpool_bwd_workspace_bytes",
     "lpdt_range_evonorm_maxpool_fwd", "lpdt_range_evonorm_maxpool_bwd",
@@ -104,8 +104,7 @@ def lib():
                      "lpdt_qconv_fwd_f32_absmax_workspace_bytes", "lpdt_qconv_bwd_data_f32_absmax_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.POINTER(ConvDesc)]
         for name in ("lpdt_range_evonorm_fwd_workspace_bytes", "lpdt_range_evonorm_bwd_workspace_bytes",
-                     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_bwd_q_workspace_bytes",
-                     "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
+                     "lpdt_range_evonorm_fwd_q_workspace_bytes", "lpdt_range_evonorm_maxpool_fwd_workspace_bytes",
                      "lpdt_range_evonorm_maxpool_bwd_workspace_bytes", "lpdt_evonorm_s0_fwd_workspace_bytes", "lpdt_evonorm_s0_bwd_workspace_bytes"):
             getattr(L, name).argtypes = [ctypes.c_int] * 5
         L.lpdt_qconv_ren_fwd_q_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.c_int]
@@ -470,23 +469,6 @@ def range_evonorm_bwd(dy, x, groups, v, gamma, rng, amx, amn, eps=1e-5, dx=None,
                                         ctypes.c_float(eps), _ptr(rng), _ptr(amx), _ptr(amn), _ptr(dx), _ptr(dv), _ptr(dg),
                                         _ptr(db), _ptr(absmax), _ptr(buf), _sz(nb), _stream()))
     return (dx, dv, dg, db, absmax) if want_absmax else (dx, dv, dg, db)
-
-
-def range_evonorm_bwd_q(dy, x, groups, v, gamma, rng, amx, amn, eps=1e-5, rounding=ROUND_STOCHASTIC, seed=0, offset=0, ws=None):
-    """The backward pass and the int8 codes of dx in one call -> (dx, dv, dgamma, dbeta, q, scale, absmax)."""
-    _dev(x, torch.float32, "range_evonorm_bwd_q x"); _dev(dy, torch.float32, "range_evonorm_bwd_q dy")
-    N, H, W, C = x.shape
-    dev = x.device
-    dx = torch.empty_like(x)
-    dv, dg, db = (torch.empty(C, dtype=torch.float32, device=dev) for _ in range(3))
-    q = torch.empty(x.shape, dtype=torch.int8, device=dev)
-    scale, absmax = (torch.empty(1, dtype=torch.float32, device=dev) for _ in range(2))
-    buf, nb = _ws(ws, lib().lpdt_range_evonorm_bwd_q_workspace_bytes(N, H, W, C, groups))
-    _check(lib().lpdt_range_evonorm_bwd_q(_ptr(dy), _ptr(x), N, H, W, C, int(groups), _ptr(v), _ptr(gamma), ctypes.c_float(eps),
-                                          _ptr(rng), _ptr(amx), _ptr(amn), _ptr(dx), _ptr(dv), _ptr(dg), _ptr(db), int(rounding),
-                                          ctypes.c_uint64(seed), ctypes.c_uint64(offset), _ptr(q), _ptr(scale), _ptr(absmax),
-                                          _ptr(buf), _sz(nb), _stream()))
-    return dx, dv, dg, db, q, scale, absmax
 
 
 # ---------------------------------------------------------------- full-precision comparison layers

@@ -81,28 +81,4 @@ __device__ __forceinline__ int round_code(float x, float inv, bool stochastic, u
     return (int)r;
 }
 
-// ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------
-// One call yields the four 32-bit words used by four consecutive elements.
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t out[4]) {
-    uint32_t c2 = 0u, c3 = 0u;
-#pragma unroll
-    for (int i = 0; i < 10; ++i) {
-        const uint64_t lo = (uint64_t)c0 * 0xD2511F53ull;
-        const uint64_t hi = (uint64_t)c2 * 0xCD9E8D57ull;
-        const uint32_t t0 = (uint32_t)(hi >> 32) ^ c1 ^ k0;
-        const uint32_t t2 = (uint32_t)(lo >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)hi;
-        c3 = (uint32_t)lo;
-        c0 = t0;
-        c2 = t2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
-
-// the quantizer's rounding pass over x with max|x| = the largest of parts[0..nparts) (quantize.hip)
-void launch_round_pass(const float *x, size_t len, const float *parts, int nparts, int rounding, uint64_t seed, uint64_t offset,
-                       int8_t *q, float *scale, hipStream_t st);
-
 }  // namespace lpdt

@@ -679,32 +679,6 @@ __device__ __forceinline__ float4 pooled_grad(const float4 *__restrict__ dz, con
     return s;
 }
 
-// One pixel of a thread's channel quad: dx, and the pixel's terms of the four per-channel sums and of max|dx| (the two
-// elements that the range's gradient will still change stay out of the maximum).  One function for every kernel that
-// walks the tensor, so that they round alike.
-__device__ __forceinline__ float4 ren_bwd_pixel(const float4 &x4, const float4 &d4, const float (&vv)[4], const float (&gg)[4],
-                                                const float (&inv)[4], int p, const int (&skip_a)[4], const int (&skip_b)[4],
-                                                float (&sb)[4], float (&sg)[4], float (&sv)[4], float (&st)[4], float &am) {
-    const float xe[4] = {x4.x, x4.y, x4.z, x4.w};
-    const float de[4] = {d4.x, d4.y, d4.z, d4.w};
-    float o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float z = vv[e] * xe[e];
-        const float s = hard_sigmoid(z);
-        const float sp = (z > -3.0f && z < 3.0f) ? (1.0f / 6.0f) : 0.0f;
-        const float u = xe[e] * s;
-        const float du = de[e] * gg[e] * inv[e];
-        o[e] = du * (s + xe[e] * vv[e] * sp);
-        sb[e] += de[e];
-        sg[e] += de[e] * u;
-        sv[e] += du * xe[e] * xe[e] * sp;
-        st[e] += de[e] * gg[e] * u;
-        if (p != skip_a[e] && p != skip_b[e]) am = fmaxf(am, fabsf(o[e]));
-    }
-    return make_float4(o[0], o[1], o[2], o[3]);
-}
-
 // kPooled: dy is not read; it is gathered from the pooled gradient dz and the winners idx (see pooled_grad).
 template <bool kPooled>
 __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__restrict__ dy, const float *__restrict__ x,
@@ -763,7 +737,24 @@ __global__ __launch_bounds__(kRThreads) void ren_bwd_main_kernel(const float *__
         for (int k = 0; k < RU; ++k) {
             const int p = pb + k * g.ppi;
             if (p >= p1) break;
-            ov[(size_t)p * g.cq + qd] = ren_bwd_pixel(a4[k], d4[k], vv, gg, inv, p, skip_a, skip_b, sb, sg, sv, st, am);
+            const float xe[4] = {a4[k].x, a4[k].y, a4[k].z, a4[k].w};
+            const float de[4] = {d4[k].x, d4[k].y, d4[k].z, d4[k].w};
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float z = vv[e] * xe[e];
+                const float s = hard_sigmoid(z);
+                const float sp = (z > -3.0f && z < 3.0f) ? (1.0f / 6.0f) : 0.0f;
+                const float u = xe[e] * s;
+                const float du = de[e] * gg[e] * inv[e];
+                o[e] = du * (s + xe[e] * vv[e] * sp);
+                sb[e] += de[e];
+                sg[e] += de[e] * u;
+                sv[e] += du * xe[e] * xe[e] * sp;
+                st[e] += de[e] * gg[e] * u;
+                if (p != skip_a[e] && p != skip_b[e]) am = fmaxf(am, fabsf(o[e]));
+            }
+            ov[(size_t)p * g.cq + qd] = make_float4(o[0], o[1], o[2], o[3]);
         }
     }
     // fixed-order block reduction over the threads that share a channel quad
@@ -913,198 +904,6 @@ __global__ __launch_bounds__(kFinishThreads) void ren_bwd_finish_kernel(const fl
     if (absmax_out) {
         for (int r = rb * kFinishThreads + threadIdx.x; r < rows; r += nrb * kFinishThreads) am = fmaxf(am, pabs[r]);
         block_absmax_commit(am, absmax_out, lds);
-    }
-}
-
-// ---- backward of small samples, and the codes of its dx ---------------------------------------------------------
-// The late layers' samples hold a few ten thousand elements; their three dependent launches (main, finish, the
-// quantizer's rounding pass over dx) are launch latency, not bytes.  Here one block of kBwdSampleThreads threads walks
-// its whole sample and then adds the range's gradient at the saved extrema itself -- the first launch and the
-// (sample, group) half of the second in one; the other half (the parameters' column sums) rides in the launch that emits
-// the codes.  To give the bits of the separate calls, the block works as several "virtual blocks" of g.block threads
-// that take the sample's chunks in turn with ren_bwd_main_kernel's thread-to-pixel mapping and its order of additions
-// (same partial rows in `parts`), and a wave adds a pair's partial sums the way ren_bwd_finish_kernel's wave does.
-constexpr int kBwdSampleThreads = 1024;
-__global__ __launch_bounds__(kBwdSampleThreads) void ren_bwd_sample_kernel(const float *__restrict__ dy, const float *__restrict__ x,
-                                                                           RenGeom g, const float *__restrict__ v,
-                                                                           const float *__restrict__ gamma, float cm, float eps,
-                                                                           const float *__restrict__ range,
-                                                                           const int32_t *__restrict__ argmax,
-                                                                           const int32_t *__restrict__ argmin, float *__restrict__ dx,
-                                                                           float *__restrict__ parts, float *__restrict__ sample_abs) {
-    extern __shared__ float smem[];   // [V][16 * g.threads] reduction areas of the virtual blocks, then T sums [chunks][C]
-    __shared__ float lds[kBwdSampleThreads / kWave];
-    const int n = blockIdx.x;
-    const int V = kBwdSampleThreads / g.block;                       // virtual blocks (g.block is 64 .. 256)
-    const int vb = threadIdx.x / g.block, vt = threadIdx.x % g.block;
-    float *const sred = smem + (size_t)min(vb, V - 1) * 16 * g.threads;
-    float *const tsum = smem + (size_t)V * 16 * g.threads;
-    const bool active = vb < V && vt < g.threads;
-    const int qd = vt % g.cq, pl = vt / g.cq;
-    float vv[4] = {0.f, 0.f, 0.f, 0.f}, gg[4] = {0.f, 0.f, 0.f, 0.f}, inv[4] = {0.f, 0.f, 0.f, 0.f};
-    int skip_a[4] = {-1, -1, -1, -1}, skip_b[4] = {-1, -1, -1, -1};
-    if (active) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int c = qd * 4 + e, grp = c / g.m, cc = c % g.m;
-            vv[e] = v[c]; gg[e] = gamma[c];
-            inv[e] = inv_denominator(range[(size_t)n * g.groups + grp], cm, eps);
-            const int ia = argmax[(size_t)n * g.groups + grp], ib = argmin[(size_t)n * g.groups + grp];
-            skip_a[e] = (ia % g.m == cc) ? ia / g.m : -1;
-            skip_b[e] = (ib % g.m == cc) ? ib / g.m : -1;
-        }
-    }
-    const size_t base = (size_t)n * g.HW * g.C;
-    const float4 *xv = reinterpret_cast<const float4 *>(x + base);
-    const float4 *dv4 = reinterpret_cast<const float4 *>(dy + base);
-    float4 *ov = reinterpret_cast<float4 *>(dx + base);
-    float am = 0.0f;
-    const int T4 = g.threads * 4;
-    const int rounds = (g.chunks + V - 1) / V;
-    for (int rd = 0; rd < rounds; ++rd) {
-        const int chunk = rd * V + vb;
-        const bool live = vb < V && chunk < g.chunks;
-        float sb[4] = {0, 0, 0, 0}, sg[4] = {0, 0, 0, 0}, sv[4] = {0, 0, 0, 0}, st[4] = {0, 0, 0, 0};
-        if (live && active) {
-            const int p0 = chunk * g.pix_per_block, p1 = min(p0 + g.pix_per_block, g.HW);
-            for (int pb = p0 + pl; pb < p1; pb += kRU * g.ppi) {
-                float4 a4[kRU], d4[kRU];
-#pragma unroll
-                for (int k = 0; k < kRU; ++k) {
-                    const int p = pb + k * g.ppi;
-                    a4[k] = p < p1 ? xv[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
-                    d4[k] = p < p1 ? dv4[(size_t)p * g.cq + qd] : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-                for (int k = 0; k < kRU; ++k) {
-                    const int p = pb + k * g.ppi;
-                    if (p >= p1) break;
-                    ov[(size_t)p * g.cq + qd] = ren_bwd_pixel(a4[k], d4[k], vv, gg, inv, p, skip_a, skip_b, sb, sg, sv, st, am);
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                sred[0 * T4 + vt * 4 + e] = sb[e];
-                sred[1 * T4 + vt * 4 + e] = sg[e] * inv[e];
-                sred[2 * T4 + vt * 4 + e] = sv[e];
-                sred[3 * T4 + vt * 4 + e] = st[e];
-            }
-        }
-        __syncthreads();
-        if (live) {
-            const size_t row = (size_t)n * g.chunks + chunk;
-            for (int i = vt; i < 4 * g.C; i += g.block) {
-                const int qn = i / g.C, c = i % g.C;
-                float s = 0.0f;
-                for (int k = 0; k < g.ppi; ++k) s += sred[qn * T4 + (k * g.cq) * 4 + c];
-                parts[(row * 4 + qn) * g.C + c] = s;
-                if (qn == 3) tsum[chunk * g.C + c] = s;
-            }
-        }
-        __syncthreads();   // the reduction areas are written again in the next round; dx and tsum are complete after the last
-    }
-    // the gradient through the range, at the sample's saved extrema: one wave per group, as in ren_bwd_finish_kernel
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    for (int grp = wave; grp < g.groups; grp += kBwdSampleThreads / kWave) {
-        const int i = n * g.groups + grp;
-        const int ia = argmax[i], ib = argmin[i];
-        const size_t gbase = base + (size_t)grp * g.m;
-        const size_t pa = gbase + (size_t)(ia / g.m) * g.C + ia % g.m, pb = gbase + (size_t)(ib / g.m) * g.C + ib % g.m;
-        const float da = dx[pa], db = dx[pb];
-        const float rinv = inv_denominator(range[i], cm, eps);
-        float t = 0.0f;
-        for (int k0 = lane; k0 < g.chunks * g.m; k0 += 4 * kWave) {
-            float q[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k = k0 + j * kWave, ch = k / g.m, cc = k - ch * g.m;
-                q[j] = k < g.chunks * g.m ? tsum[ch * g.C + grp * g.m + cc] : 0.0f;
-            }
-            t += (q[0] + q[1]) + (q[2] + q[3]);
-        }
-        t = wave_sum(t);
-        if (lane == 0) {
-            const float dR = -cm * t * rinv * rinv;
-            if (pa != pb) {
-                const float na = da + dR, nb = db - dR;
-                dx[pa] = na;
-                dx[pb] = nb;
-                am = fmaxf(am, fmaxf(fabsf(na), fabsf(nb)));
-            } else {  // a constant slab: both extrema are its first element
-                const float na = (da + dR) - dR;
-                dx[pa] = na;
-                am = fmaxf(am, fabsf(na));
-            }
-        }
-    }
-    block_absmax_store(am, sample_abs + n, lds);
-}
-
-// The launch after it: blocks [0, 3 ceil(C/8)) add up the parameters' column sums exactly as ren_bwd_finish_kernel's do; the
-// others emit the codes of dx as the quantizer's rounding pass does (scale from the largest of the samples' maxima, one
-// Philox block per 4 elements at counter offset + index), and leave that maximum in *absmax_out for other readers of dx.
-constexpr int kCodesThreads = 256;
-template <bool kStochastic>
-__global__ __launch_bounds__(kCodesThreads) void ren_bwd_codes_kernel(const float *__restrict__ parts, int rows, int C,
-                                                                      float *__restrict__ dbeta, float *__restrict__ dgamma,
-                                                                      float *__restrict__ dv, const float *__restrict__ sample_abs,
-                                                                      int nabs, const float *__restrict__ dx, size_t len,
-                                                                      uint64_t seed, uint64_t offset, int8_t *__restrict__ q,
-                                                                      float *__restrict__ scale, float *__restrict__ absmax_out) {
-    __shared__ float s[32][8];
-    __shared__ float lds[kCodesThreads / kWave];
-    const int param_blocks = 3 * ((C + 7) / 8);
-    if ((int)blockIdx.x < param_blocks) {
-        const int qn = blockIdx.x % 3, cl = threadIdx.x % 8, sl = threadIdx.x / 8;
-        const int c = (blockIdx.x / 3) * 8 + cl;
-        float acc = 0.0f;
-        if (c < C) {
-            for (int r = sl; r < rows; r += 256) {
-                float t[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) t[k] = r + 32 * k < rows ? parts[((size_t)(r + 32 * k) * 4 + qn) * C + c] : 0.0f;
-                acc += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
-            }
-        }
-        s[sl][cl] = acc;
-        __syncthreads();
-        if (sl == 0 && c < C) {
-            float t = 0;
-            for (int k = 0; k < 32; ++k) t += s[k][cl];
-            (qn == 0 ? dbeta : qn == 1 ? dgamma : dv)[c] = t;
-        }
-        return;
-    }
-    const int rb = blockIdx.x - param_blocks, nrb = gridDim.x - param_blocks;
-    float a = 0.0f;
-    for (int i = threadIdx.x; i < nabs; i += kCodesThreads) a = fmaxf(a, sample_abs[i]);
-    a = wave_max(a);
-    if (threadIdx.x % kWave == 0) lds[threadIdx.x / kWave] = a;
-    __syncthreads();
-    a = lds[0];
-#pragma unroll
-    for (int w = 1; w < kCodesThreads / kWave; ++w) a = fmaxf(a, lds[w]);
-    const float inv = quant_inv(a);
-    if (rb == 0 && threadIdx.x == 0) {
-        *scale = quant_scale(a);
-        if (absmax_out) *absmax_out = a;
-    }
-    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-    const size_t nvec = len / 4;   // len = N * H * W * C, C a multiple of 4
-    const float4 *xv = reinterpret_cast<const float4 *>(dx);
-    uint32_t *qv = reinterpret_cast<uint32_t *>(q);
-    for (size_t i = (size_t)rb * kCodesThreads + threadIdx.x; i < nvec; i += (size_t)nrb * kCodesThreads) {
-        const float4 val = xv[i];
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-        if (kStochastic) {
-            const uint64_t blk = offset + i;
-            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), k0, k1, w);
-        }
-        const uint32_t b0 = (uint32_t)round_code(val.x, inv, kStochastic, w[0]) & 0xffu;
-        const uint32_t b1 = (uint32_t)round_code(val.y, inv, kStochastic, w[1]) & 0xffu;
-        const uint32_t b2 = (uint32_t)round_code(val.z, inv, kStochastic, w[2]) & 0xffu;
-        const uint32_t b3 = (uint32_t)round_code(val.w, inv, kStochastic, w[3]) & 0xffu;
-        qv[i] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
     }
 }
 
@@ -1361,72 +1160,6 @@ extern "C" int lpdt_range_evonorm_maxpool_bwd(const float *dz, const int32_t *id
     hipLaunchKernelGGL(ren_bwd_finish_kernel, dim3(3 * ((C + 7) / 8) + (N * groups + kFinishPairs - 1) / kFinishPairs), dim3(kFinishThreads), 0, st, parts, pabs, (int)rows, N, H * W, C,
                        groups, m, g.chunks, cm, eps, range, argmax, argmin, dx, dbeta, dgamma, dv, absmax_out);
     return launch_status("lpdt_range_evonorm_maxpool_bwd");
-}
-
-// the fused backward of small samples: geometry of the separate call, LDS for the virtual blocks and the T sums
-static bool ren_bwd_sample_path(int N, int H, int W, int C, int groups, RenGeom *g, size_t *smem) {
-    if (!ren_fast(C) || !ren_sample_path(N, H, W, C)) return false;
-    *g = ren_geom(N, H, W, C, groups, kBwdMinPix, block_cap(N, H, W, C, kBwdElems));
-    const int V = kBwdSampleThreads / g->block;
-    *smem = ((size_t)V * 16 * g->threads + (size_t)g->chunks * C) * sizeof(float);
-    return *smem <= 120 * 1024;
-}
-
-extern "C" size_t lpdt_range_evonorm_bwd_q_workspace_bytes(int N, int H, int W, int C, int groups) {
-    const size_t base = lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, groups);
-    return base ? base + round_up((size_t)(N > 1 ? N : 1) * sizeof(float), 256) : 0;
-}
-
-extern "C" int lpdt_range_evonorm_bwd_q(const float *dy, const float *x, int N, int H, int W, int C, int groups, const float *v,
-                                        const float *gamma, float eps, const float *range, const int32_t *argmax,
-                                        const int32_t *argmin, float *dx, float *dv, float *dgamma, float *dbeta, int rounding,
-                                        uint64_t seed, uint64_t offset, int8_t *q, float *scale, float *absmax_out, void *ws,
-                                        size_t ws_bytes, void *stream) {
-    int rc = check_ren(x, N, H, W, C, groups);
-    if (rc) return rc;
-    LPDT_REQUIRE(dy && v && gamma && range && argmax && argmin && dx && dv && dgamma && dbeta && q && scale, LPDT_EINVAL,
-                 "range_evonorm_bwd_q: NULL argument");
-    LPDT_REQUIRE(eps >= 0.0f, LPDT_EINVAL, "range_evonorm_bwd_q: eps must be >= 0");
-    LPDT_REQUIRE(rounding == LPDT_ROUND_NEAREST || rounding == LPDT_ROUND_STOCHASTIC, LPDT_EINVAL, "range_evonorm_bwd_q: unknown rounding mode %d", rounding);
-    LPDT_REQUIRE(aligned(x, 16) && aligned(dy, 16) && aligned(dx, 16) && aligned(q, 4), LPDT_EINVAL,
-                 "range_evonorm_bwd_q: x, dy and dx must be 16-byte aligned, q 4-byte aligned");
-    rc = check_ws(ws, ws_bytes, lpdt_range_evonorm_bwd_q_workspace_bytes(N, H, W, C, groups));
-    if (rc) return rc;
-    hipStream_t st = as_stream(stream);
-    const size_t base_ws = lpdt_range_evonorm_bwd_workspace_bytes(N, H, W, C, groups);
-    float *sample_abs = reinterpret_cast<float *>(static_cast<char *>(ws) + base_ws);   // N maxima, or the one of the whole tensor
-    const size_t len = (size_t)N * H * W * C;
-    RenGeom g;
-    size_t smem;
-    if (C % 4 == 0 && ren_bwd_sample_path(N, H, W, C, groups, &g, &smem)) {
-        const float cm = ren_cm(C / groups);
-        float *parts = static_cast<float *>(ws);
-        static bool raised = false;
-        if (!raised) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(ren_bwd_sample_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024);
-            raised = true;
-        }
-        hipLaunchKernelGGL(ren_bwd_sample_kernel, dim3(N), dim3(kBwdSampleThreads), smem, st, dy, x, g, v, gamma, cm, eps, range, argmax,
-                           argmin, dx, parts, sample_abs);
-        const int rows = N * g.chunks, param_blocks = 3 * ((C + 7) / 8);
-        size_t rblocks = (len / 4 + (size_t)kCodesThreads * 16 - 1) / ((size_t)kCodesThreads * 16);
-        if (rblocks < 1) rblocks = 1;
-        if (rblocks > 8192) rblocks = 8192;
-        if (rounding == LPDT_ROUND_STOCHASTIC)
-            hipLaunchKernelGGL(ren_bwd_codes_kernel<true>, dim3((unsigned)(param_blocks + rblocks)), dim3(kCodesThreads), 0, st, parts, rows, C,
-                               dbeta, dgamma, dv, sample_abs, N, dx, len, seed, offset, q, scale, absmax_out);
-        else
-            hipLaunchKernelGGL(ren_bwd_codes_kernel<false>, dim3((unsigned)(param_blocks + rblocks)), dim3(kCodesThreads), 0, st, parts, rows, C,
-                               dbeta, dgamma, dv, sample_abs, N, dx, len, seed, offset, q, scale, absmax_out);
-        return launch_status("lpdt_range_evonorm_bwd_q");
-    }
-    // larger samples: the separate calls' launches
-    float *am = absmax_out ? absmax_out : sample_abs;
-    rc = lpdt_range_evonorm_bwd(dy, x, N, H, W, C, groups, v, gamma, eps, range, argmax, argmin, dx, dv, dgamma, dbeta, am, ws, base_ws,
-                                stream);
-    if (rc) return rc;
-    launch_round_pass(dx, len, am, 1, rounding, seed, offset, q, scale, st);
-    return launch_status("lpdt_range_evonorm_bwd_q");
 }
 
 extern "C" int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W, int C, int groups,

@@ -113,38 +113,6 @@ def test_int8_output_forward_equals_forward_then_quantize(orc, shape):
     assert np.abs(host(q).astype(np.float64) * step - y_ref).max() <= 0.5 * step + 1e-4 * np.abs(y_ref).max()
 
 
-# small samples (the two-launch path: 64 / 128 / 192 / 256-thread virtual blocks, one to many chunks per sample, ragged last
-# chunks, more groups than waves, a single sample) and large ones (the separate calls' launches), and the generic kernels
-BWD_Q_CASES = CASES + [(64, 14, 14, 256, 32), (40, 7, 7, 512, 32), (128, 32, 32, 16, 8), (3, 8, 8, 64, 8), (1, 16, 16, 64, 32),
-                       (5, 19, 13, 48, 6), (2, 6, 5, 1024, 128), (7, 3, 3, 4, 2), (4, 30, 30, 64, 32), (2, 60, 60, 64, 32)]
-
-
-@pytest.mark.parametrize("shape", BWD_Q_CASES)
-@pytest.mark.parametrize("rounding", ["nearest", "stochastic"])
-def test_backward_with_codes_equals_backward_then_quantize(shape, rounding):
-    """lpdt_range_evonorm_bwd_q: dx, the parameters' gradients, max|dx|, the codes and the scale of lpdt_range_evonorm_bwd
-    followed by lpdt_quantize_with_absmax, bit for bit (the separate calls are the ones compared with the oracle above)."""
-    import torch
-    N, H, W, C, groups = shape
-    print("case", shape, rounding, flush=True)
-    x = wl.images(740, N, H, W, C) * np.float32(2.0)
-    v, gamma, beta = _params(741, C)
-    dy = wl.upstream_grad(742, (N, H, W, C))
-    xd, vd, gd, bd, dyd = dev(x), dev(v), dev(gamma), dev(beta), dev(dy)
-    _, r, amx, amn = lpdt.range_evonorm_fwd(xd, groups, vd, gd, bd, 1e-5)
-    mode = lpdt.ROUND_STOCHASTIC if rounding == "stochastic" else lpdt.ROUND_NEAREST
-    seed, offset = wl.PHILOX_SEED, (7 << 32) + (3 << 24)
-    dx, dv, dg, db, am = lpdt.range_evonorm_bwd(dyd, xd, groups, vd, gd, r, amx, amn, 1e-5, want_absmax=True)
-    q_ref, s_ref = lpdt.quantize_with_absmax(dx, am, mode, seed=seed, offset=offset)
-    for rep in range(2):                         # twice: the workspace's leftovers must not matter
-        dx2, dv2, dg2, db2, q, s, am2 = lpdt.range_evonorm_bwd_q(dyd, xd, groups, vd, gd, r, amx, amn, 1e-5, rounding=mode, seed=seed,
-                                                                offset=offset)
-        assert torch.equal(dx2, dx), "dx"
-        assert torch.equal(dv2, dv) and torch.equal(dg2, dg) and torch.equal(db2, db), "parameter gradients"
-        assert torch.equal(am2, am) and torch.equal(s, s_ref), "max|dx| and scale"
-        assert torch.equal(q, q_ref), "codes"
-
-
 def test_int8_output_forward_rejects_odd_channel_counts():
     import torch
     x = torch.zeros((2, 5, 5, 6), device="cuda")
