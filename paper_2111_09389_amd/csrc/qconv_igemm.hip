@@ -345,6 +345,8 @@ Tile pick_tile(const IgemmParams &p) {
     return {blocks >= 256 ? 128 : 64, 64, gmin >= 64 ? 8 : 4};
 }
 
+constexpr int kMinSplitSteps = 24;   // K-steps below which a launch with few tiles keeps its reduction whole
+
 // Fills tile counts and the K split; returns the grid.
 dim3 finish_plan(IgemmParams *p, Tile tl, bool allow_split) {
     p->tiles_n = (p->Cout + tl.BN - 1) / tl.BN;
@@ -360,7 +362,10 @@ dim3 finish_plan(IgemmParams *p, Tile tl, bool allow_split) {
     }
     int splits = 1;
     const int min_steps = 16 / tl.KG;                  // a share of the reduction is at least 16 granules deep
-    if (allow_split && blocks < 256 && max_nk >= 2 * min_steps) {  // too few tiles to fill 256 CUs: split the reduction
+    // Too few tiles to fill 256 CUs: split the reduction -- when it is long enough to pay for the two launches a split
+    // adds (zero fill before, scale after: ~8 us): a 64 -> 64 layer of ResNet-20 has 9 steps, and splitting them in two
+    // made 15 us of launches out of a 7 us kernel.
+    if (allow_split && blocks < 256 && max_nk >= 2 * min_steps && max_nk >= kMinSplitSteps) {
         splits = (int)((512 + blocks - 1) / blocks);
         if (splits > max_nk / min_steps) splits = max_nk / min_steps;
         if (splits < 1) splits = 1;

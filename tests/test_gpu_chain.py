@@ -21,8 +21,9 @@ CASES = [
     ((64, 512, 7, 7, 512, 3, 3, 1, 1), 256, 43),     # two channels per group
     ((8, 64, 56, 56, 512, 3, 3, 1, 1), 32, 44),      # GEMM-like launch with a short reduction
     ((40, 128, 28, 28, 512, 1, 1, 1, 0), 64, 44),    # 784 pixels per sample on 256-pixel tiles: up to 2 samples per tile
-    ((16, 128, 28, 28, 256, 3, 3, 2, 1), 32, 112),    # too few tiles for the fused form at this batch: the two calls
-    ((2, 64, 14, 14, 64, 3, 3, 1, 1), 8, 111),
+    ((16, 128, 28, 28, 256, 3, 3, 2, 1), 32, 12),    # too few tiles for the fused form at this batch: the two calls
+    ((2, 64, 14, 14, 64, 3, 3, 1, 1), 8, 11),
+    ((3, 384, 5, 5, 64, 3, 3, 1, 1), 8, 112),        # the two calls, the product with a split reduction
     ((3, 3, 20, 20, 16, 3, 3, 1, 1), 4, 1),          # first-layer kernel
 ]
 

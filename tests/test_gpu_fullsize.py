@@ -54,7 +54,7 @@ KERNELS = {
     "stem 7x7 s2": (1, 10, 1), "layer1 3x3": (50, 50, 60), "layer2 3x3 s2": (22, 13, 38), "layer2 1x1 s2": (22, 13, 31),
     "layer2 3x3": (22, 22, 60), "layer3 3x3 s2": (21, 22, 38), "layer3 1x1 s2": (21, 22, 31), "layer3 3x3": (21, 21, 60),
     "layer4 3x3 s2": (23, 21, 38), "layer4 1x1 s2": (23, 21, 31), "layer4 3x3": (23, 23, 60), "classifier": (3, 3, 3),
-    "resnet20 first": (1, 10, 1), "resnet20 16": (10, 10, 42), "resnet20 64": (111, 111, 60), "vgg11 first": (1, 10, 1),
+    "resnet20 first": (1, 10, 1), "resnet20 16": (10, 10, 42), "resnet20 64": (11, 11, 60), "vgg11 first": (1, 10, 1),
     "vgg11 128": (22, 14, 60), "vgg11 512": (112, 112, 63),
     "gemm 256x128 tile": (24, 12, 60), "gemm 256x256 tile": (20, 24, 62),
 }

@@ -15,7 +15,7 @@ CASES = [
     (2, 64, 14, 14, 64, 3, 3, 1, 1),
     (3, 32, 9, 11, 48, 3, 3, 1, 1),       # ragged: M = 297, Cout = 48
     (2, 64, 15, 15, 128, 3, 3, 2, 1),     # stride 2
-    (2, 128, 8, 8, 256, 3, 3, 1, 1),      # large-tile path, split reduction
+    (2, 128, 8, 8, 256, 3, 3, 1, 1),      # few tiles, 9 reduction steps: not worth a split
     (2, 64, 16, 16, 128, 1, 1, 2, 0),     # 1x1 stride-2 projection shortcut
     (5, 48, 7, 7, 80, 1, 1, 1, 0),
     (70, 64, 1, 1, 10, 1, 1, 1, 0),       # linear layer 64 -> 10
@@ -29,6 +29,8 @@ CASES = [
     (130, 3072, 1, 1, 768, 1, 1, 1, 0),
     (2, 144, 7, 7, 80, 3, 3, 1, 1),       # 81 granules of reduction: the forward's 8-granule steps end in a ragged one
     (1, 80, 5, 5, 144, 3, 3, 1, 1),       # the same for backward-data (reduction over 144 output channels x 9 taps)
+    (2, 512, 4, 4, 256, 3, 3, 1, 1),      # few tiles, 36 steps: split reduction (zero fill, atomic adds, scale pass)
+    (3, 384, 5, 5, 64, 3, 3, 1, 1),       # the same on 64 x 64 tiles
 ]
 
 
