@@ -21,6 +21,10 @@
  *  - Arguments are checked on the host before anything is enqueued.  Return
  *    value 0 = success, negative = lpdt_status; lpdt_last_error() gives a
  *    thread-local message for the last failure.
+ *  - Issue calls from one host thread at a time (any stream).  The launchers
+ *    keep per-kernel settings of the process (the dynamic-LDS limit a launch
+ *    needs is set before it), which two threads could change under each
+ *    other's launches.
  *  - Layouts: activations and their gradients NHWC, filters KRSC (K output
  *    channels, R x S taps, C input channels), parameter matrices row-major
  *    [n agents][d parameters].  Tensors are dense and contiguous.
