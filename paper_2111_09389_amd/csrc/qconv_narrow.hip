@@ -97,7 +97,7 @@ struct NarrowParams {
     int steps_per_block;
 };
 
-// NR = filter rows multiplied (4 for R <= 4, else 8).  Nothing in the row sequence depends on R or K at run time, so the
+// NR = filter rows multiplied (4 for R <= 4, 7 for R = 7, else 8).  Nothing in the row sequence depends on R or K at run time, so the
 // accumulators stay in place between the MFMAs: rows past R hold zero weights and read row R-1 of the window again,
 // channels past K hold zero weights.
 template <int NR>
@@ -176,11 +176,11 @@ __device__ __forceinline__ void narrow_static_for(F f) {
 // rows, passes them through its private LDS area to read them back transposed (pixels become the MFMA's reduction
 // axis), and multiplies.  Nothing is shared between waves, so the loop has no barrier, and the next step's loads are in
 // flight while this step is multiplied.  At the end the block's four waves add their sums up in LDS and write one copy
-// of the filter gradient; a second launch sums the copies.  NR = 4 for R <= 4, else 8: rows past R read row R-1 again
+// of the filter gradient; a second launch sums the copies.  NR = 4 for R <= 4, 7 for R = 7, else 8: rows past R read row R-1 again
 // and their sums are never stored.
 template <int NR>
 __global__ __launch_bounds__(256, 1) void narrow_wgrad_kernel(const NarrowParams p) {
-    constexpr int XS = NR * 32 + 32;              // LDS bytes per pixel of the window tile (8 banks from pixel to pixel: the transposing reads meet no conflict)
+    constexpr int XS = (NR == 7 ? 8 : NR) * 32 + 32;   // LDS bytes per pixel of the window tile (8 banks from pixel to pixel: the transposing reads meet no conflict; 7 rows keep the pitch of 8)
     constexpr int WAVE_BYTES = 32 * kGS + 32 * XS;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int t = threadIdx.x, lane = t % 64, wave = t / 64, half = lane / 32;
@@ -346,7 +346,9 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
     p.blocks_total = (p.M + 31) / 32;
     int grid = (p.blocks_total + 3) / 4;
     if (grid > 2048) grid = 2048;
+    // (7 rows, the 7 x 7 stem, have an instantiation of their own: an eighth row would be an eighth of the loads for nothing)
     if (d->R <= 4) hipLaunchKernelGGL(narrow_fwd_kernel<4>, dim3(grid), dim3(256), 0, st, p);
+    else if (d->R == 7) hipLaunchKernelGGL(narrow_fwd_kernel<7>, dim3(grid), dim3(256), 0, st, p);
     else hipLaunchKernelGGL(narrow_fwd_kernel<8>, dim3(grid), dim3(256), 0, st, p);
 }
 
@@ -360,8 +362,8 @@ void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g,
     p.blocks_total = (p.M + 31) / 32;
     int grid;
     narrow_wgrad_grid(p.M, &grid, &p.steps_per_block);
-    const int NR = d->R <= 4 ? 4 : 8;
-    size_t lds = 4 * (size_t)(32 * kGS + 32 * (NR * 32 + 32));
+    const int NR = d->R <= 4 ? 4 : d->R == 7 ? 7 : 8;
+    size_t lds = 4 * (size_t)(32 * kGS + 32 * ((NR == 7 ? 8 : NR) * 32 + 32));
     if (lds < (size_t)64 * NR * 32 * 4) lds = (size_t)64 * NR * 32 * 4;
     p.zero_off = (int)(padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w) - 64);
     auto go = [&](auto kernel) {
@@ -369,6 +371,7 @@ void launch_narrow_wgrad(const lpdt_conv_desc *d, int P, int Q, const int8_t *g,
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, st, p);
     };
     if (NR == 4) go(narrow_wgrad_kernel<4>);
+    else if (NR == 7) go(narrow_wgrad_kernel<7>);
     else go(narrow_wgrad_kernel<8>);
     launch_wgrad_reduce(partial, (long long)d->K * d->R * d->S * d->C, grid, out, out_mode, sA, sB, st);
 }
