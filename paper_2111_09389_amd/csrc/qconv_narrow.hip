@@ -345,7 +345,8 @@ void launch_narrow_fwd(const lpdt_conv_desc *d, int P, int Q, const int8_t *x, c
     p.vec_out = aligned(acc, 16) ? 1 : 0;
     p.blocks_total = (p.M + 31) / 32;
     int grid = (p.blocks_total + 3) / 4;
-    if (grid > 2048) grid = 2048;
+    if (grid > 512) grid = 512;   // two blocks per CU, each wave walking its run of row blocks (measured on the 224 x 224 stem at batch 64:
+                                  // 256 blocks 77 us, 512 69 us, 768 71 us, 1024 73 us, 2048 75 us, 4096 82 us)
     // (7 rows, the 7 x 7 stem, have an instantiation of their own: an eighth row would be an eighth of the loads for nothing)
     if (d->R <= 4) hipLaunchKernelGGL(narrow_fwd_kernel<4>, dim3(grid), dim3(256), 0, st, p);
     else if (d->R == 7) hipLaunchKernelGGL(narrow_fwd_kernel<7>, dim3(grid), dim3(256), 0, st, p);
