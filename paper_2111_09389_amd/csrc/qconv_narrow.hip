@@ -329,7 +329,7 @@ static NarrowParams narrow_params(const lpdt_conv_desc *d, int P, int Q, const i
 static void launch_pad(const lpdt_conv_desc *d, const int8_t *x, int8_t *xp, hipStream_t st) {
     const size_t total = padded_bytes(d->N, d->C, d->H, d->W, d->pad_h, d->pad_w);
     size_t blocks = (total / 4 + 256) / 256;
-    if (blocks > 16384) blocks = 16384;
+    if (blocks > 4096) blocks = 4096;   // (measured on the 224 x 224 image at batch 64: 1.6 us less than with 16384)
     hipLaunchKernelGGL(pad_image_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, d->N, d->H, d->W, d->C, d->pad_h,
                        d->H + 2 * d->pad_h, d->W + 2 * d->pad_w, xp, (unsigned)total);
 }
