@@ -460,7 +460,8 @@ int lpdt_avgpool_bwd(const float *dy, int N, int HW, int C, float *dx, void *str
 
 /* loss[0] = mean_n -log softmax(logits[n])[labels[n]] ; dlogits = (softmax - onehot)/N.
  * logits, dlogits fp32 [N,classes] (classes <= 1024); labels int32 [N] in [0,classes).
- * loss must have room for 1 + N floats: loss[1..N] receive the per-sample losses. */
+ * loss must have room for 1 + N floats: loss[1..N] receive the per-sample losses.  A label outside [0,classes)
+ * is not dereferenced: that sample's loss (and so the mean) is NaN and its gradient row is softmax/N. */
 int lpdt_softmax_xent(const float *logits, const int32_t *labels, int N, int classes, float *loss,
                       float *dlogits, void *stream);
 

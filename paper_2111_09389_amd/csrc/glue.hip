@@ -198,10 +198,12 @@ __global__ __launch_bounds__(kWave) void xent_kernel(const float *__restrict__ l
     float z = 0.0f;
     for (int j = lane; j < classes; j += kWave) z += expf(l[j] - mx);
     z = wave_sum(z);
+    // a label outside [0, classes) reads nothing: that sample's loss is NaN and its gradient has no target term
     const int lb = labels[n];
+    const bool valid = (unsigned)lb < (unsigned)classes;
     for (int j = lane; j < classes; j += kWave)
         dlogits[(size_t)n * classes + j] = (expf(l[j] - mx) / z - (j == lb ? 1.0f : 0.0f)) / (float)N;
-    if (lane == 0) sample_loss[n] = logf(z) + mx - l[lb];
+    if (lane == 0) sample_loss[n] = valid ? logf(z) + mx - l[lb] : __builtin_nanf("");
 }
 __global__ void xent_mean_kernel(const float *__restrict__ sample_loss, int N, float *__restrict__ loss) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {

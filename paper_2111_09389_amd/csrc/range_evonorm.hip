@@ -871,7 +871,10 @@ __global__ __launch_bounds__(kFinishThreads) void ren_bwd_finish_kernel(const fl
     if (i < N * groups) {
         const int n = i / groups, grp = i % groups;
         // the two elements to change are fetched while the partial sums are still being added up
-        const int ia = argmax[i], ib = argmin[i];
+        // (positions outside the slab -- not what the forward pass saved -- are taken as its first element: nothing is
+        // read or written out of bounds)
+        const int lim = HW * m;
+        const int ia = (unsigned)argmax[i] < (unsigned)lim ? argmax[i] : 0, ib = (unsigned)argmin[i] < (unsigned)lim ? argmin[i] : 0;
         const size_t base = (size_t)n * HW * C + (size_t)grp * m;
         const size_t pa = base + (size_t)(ia / m) * C + ia % m, pb = base + (size_t)(ib / m) * C + ib % m;
         const float da = dx[pa], db = dx[pb];

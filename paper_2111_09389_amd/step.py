@@ -74,6 +74,9 @@ class TrainStep:
         self.wgrad_16bit = wgrad_16bit
         self.dev = params.device
         self.params, self.grads = params, grads
+        # the call list holds raw addresses: every tensor behind one must live as long as this object (labels handed over
+        # as a temporary would otherwise be freed, and their memory reused, while the loss call still reads it)
+        self.labels, self.upstream = labels, upstream
         f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=self.dev)
         i8 = lambda *s: torch.empty(s, dtype=torch.int8, device=self.dev)
         i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=self.dev)

@@ -161,6 +161,16 @@ def test_glue(orc):
         loss, dl = lpdt.softmax_xent(dev(lg), dev(lb))
         assert abs(host(loss)[0] - loss_ref) < 1e-5 * max(1.0, abs(loss_ref))
         assert_close(host(dl), dl_ref, 1e-4, 1e-3 / N, "dlogits")
+        # labels outside [0, classes) are not dereferenced: NaN loss for those samples, gradient rows without a target term,
+        # every other sample as before
+        bad = lb.copy()
+        bad[0], bad[N - 1] = -1, classes
+        loss_b, dl_b = lpdt.softmax_xent(dev(lg), dev(bad))
+        loss_b, dl_b = host(loss_b), host(dl_b)
+        assert np.isnan(loss_b[0]) and np.isnan(loss_b[1]) and np.isnan(loss_b[N])
+        assert np.array_equal(loss_b[2:N], host(loss)[2:N]) and np.array_equal(dl_b[1:N - 1], host(dl)[1:N - 1])
+        sm = np.exp(lg[0].astype(np.float64) - lg[0].max()); sm /= sm.sum()
+        assert_close(dl_b[0], sm / N, 1e-4, 1e-3 / N, "dlogits of a sample without a valid label")
     a, b = wl.images(845, 2, 5, 5, 7), wl.images(846, 2, 5, 5, 7)
     # 350 elements: exercises the scalar tail
     assert np.array_equal(host(lpdt.add(dev(a), dev(b))), (a + b))

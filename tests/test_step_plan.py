@@ -1,0 +1,50 @@
+"""Host-side checks of the step planner (no GPU: a TrainStep on CPU tensors only plans its call list, nothing is launched)."""
+import gc
+import weakref
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from workloads import nets
+
+step_mod = pytest.importorskip("paper_2111_09389_amd.step")
+
+
+def _build(net, N, **kw):
+    """Builds a step object from temporaries only: nothing but the object itself can keep its operands alive."""
+    H, W, C = net.in_shape
+    params = nets.init_params(net, 1)
+    flat = torch.from_numpy(np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32))
+    return step_mod.TrainStep(net, N, flat, torch.zeros_like(flat), torch.from_numpy(wl.images(1, N, H, W, C)),
+                              torch.from_numpy(wl.labels_uniform(2, N, net.classes)), **kw)
+
+
+@pytest.mark.parametrize("name,N", [("resnet20", 4), ("resnet18", 2), ("vgg11", 2)])
+@pytest.mark.parametrize("kw", [{}, {"wgrad_16bit": True}, {"fuse_ren_quant": False}, {"overlap_wgrad": False}, {"fuse_conv_ren": True}],
+                         ids=["default", "wgrad16", "plain_norm", "one_stream", "conv_norm_chain"])
+def test_every_address_in_the_call_list_belongs_to_a_tensor_the_step_keeps_alive(monkeypatch, name, N, kw):
+    """The call list stores raw addresses.  A tensor behind one of them that only the caller held (labels passed as a
+    temporary, a planner local) would be freed and its memory handed to the next allocation while the calls still use it."""
+    record = []
+    plain = step_mod._p
+
+    def recording(t):
+        if t is not None:
+            record.append((weakref.ref(t), t.data_ptr(), t.numel() * t.element_size()))
+        return plain(t)
+
+    monkeypatch.setattr(step_mod, "_p", recording)
+    ts = _build(getattr(nets, name)(), N, **kw)
+    gc.collect()
+    live = []
+    for ref, _, _ in record:
+        t = ref()
+        if t is not None:
+            st = t.untyped_storage()
+            live.append((st.data_ptr(), st.data_ptr() + st.nbytes()))
+    assert record and ts.calls
+    for ref, ptr, nbytes in record:
+        # the tensor object itself, or (for a view made on the fly) the storage it pointed into, must still exist
+        assert ref() is not None or any(a <= ptr and ptr + nbytes <= b for a, b in live)
