@@ -253,18 +253,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
                                 v4i{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
             }
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            if (col < p.Cout) {
-#pragma unroll 4
-                for (int pr = t / QPR; pr < RP; pr += NT / QPR) {
-                    const int opix = opix_tab[ps * RP + pr];
+            auto store_rows = [&](auto add_mode) {
+              constexpr bool kAdd = decltype(add_mode)::value;
+                // rows in groups of 4: a call that adds to the result tensor fetches the group's four old values before it
+                // stores anything (row by row, each fetch had to wait for the store before it: the compiler cannot tell
+                // that the two never touch the same address, and a wait for a load is also a wait for every older store)
+                constexpr int RSTEP = NT / QPR, RU = 4;
+                for (int pr0 = t / QPR; pr0 < RP; pr0 += RU * RSTEP) {
+                  int opx[RU];
+                  v4f old[RU];
+#pragma unroll
+                  for (int u = 0; u < RU; ++u) {
+                      const int pr = pr0 + u * RSTEP;
+                      opx[u] = pr < RP ? opix_tab[ps * RP + pr] : -1;
+                      old[u] = v4f{0.f, 0.f, 0.f, 0.f};
+                      if (kAdd && opx[u] >= 0)
+                          old[u] = *reinterpret_cast<const v4f *>(static_cast<const float *>(p.out) + (size_t)opx[u] * p.Cout + col);
+                  }
+                  // one wait for the four fetches, stated here so that the compiler does not put one in front of every store
+                  if (kAdd) __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0)
+#pragma unroll
+                  for (int u = 0; u < RU; ++u) {
+                    const int pr = pr0 + u * RSTEP, opix = opx[u];
                     if (opix < 0) continue;
                     const v4i sv = *reinterpret_cast<const v4i *>(stg + pr * RS + cq * 4);
                     int32_t *dst = static_cast<int32_t *>(p.out) + (size_t)opix * p.Cout + col;
                     if (p.out_mode) {
                         v4f *fdst = reinterpret_cast<v4f *>(dst);
-                        const bool add = p.out_mode == 2;
-                        v4f v = {0.f, 0.f, 0.f, 0.f};
-                        if (add) v = *fdst;
+                        const bool add = kAdd;
+                        v4f v = old[u];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] = dequant_value(scale, sv[e], v[e], add);
                         *fdst = v;
@@ -285,7 +302,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
                             }
                         }
                     } else *reinterpret_cast<v4i *>(dst) = sv;
+                  }
                 }
+            };
+            // (two instantiations: with one loop for both, the compiler kept a wait for the fetches in front of every store)
+            if (col < p.Cout) {
+                if (p.out_mode == 2) store_rows(std::true_type{});
+                else store_rows(std::false_type{});
             }
         }
         if (ABSMAX) {
