@@ -73,6 +73,19 @@ class TrainStep:
         # products from the 8-bit codes
         self.wgrad_16bit = wgrad_16bit
         self.dev = params.device
+        # the library reads these tensors through raw addresses: a wrong type, size or device would be misread, not refused
+        H0, W0, C0 = net.in_shape
+        if params.dtype != torch.float32 or grads.dtype != torch.float32 or params.numel() != net.num_params() or grads.numel() != params.numel():
+            raise LpdtError(-1, f"params and grads must be float32 vectors of {net.num_params()} elements")
+        if x.dtype != torch.float32 or tuple(x.shape) != (batch, H0, W0, C0):
+            raise LpdtError(-1, f"x must be a float32 tensor of shape {(batch, H0, W0, C0)}, got {x.dtype} {tuple(x.shape)}")
+        if labels is not None and (labels.dtype != torch.int32 or labels.numel() != batch):
+            raise LpdtError(-1, f"labels must be {batch} int32 values, got {labels.dtype} x {labels.numel()}")
+        for name, t in (("grads", grads), ("x", x), ("labels", labels), ("upstream", upstream)):
+            if t is not None and (t.device != self.dev or not t.is_contiguous()):
+                raise LpdtError(-1, f"{name} must be contiguous and on {self.dev}")
+        if not params.is_contiguous():
+            raise LpdtError(-1, "params must be contiguous")
         self.params, self.grads = params, grads
         # the call list holds raw addresses: every tensor behind one must live as long as this object (labels handed over
         # as a temporary would otherwise be freed, and their memory reused, while the loss call still reads it)

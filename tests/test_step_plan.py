@@ -48,3 +48,22 @@ def test_every_address_in_the_call_list_belongs_to_a_tensor_the_step_keeps_alive
     for ref, ptr, nbytes in record:
         # the tensor object itself, or (for a view made on the fly) the storage it pointed into, must still exist
         assert ref() is not None or any(a <= ptr and ptr + nbytes <= b for a, b in live)
+
+
+def test_operands_of_the_wrong_type_or_size_are_refused():
+    """The library reads a step's tensors through raw addresses: int64 labels, a float64 image, a short parameter vector
+    would be misread, so the step object refuses them when it is built."""
+    from paper_2111_09389_amd.binding import LpdtError
+    net, N = nets.resnet20(), 4
+    H, W, C = net.in_shape
+    params = nets.init_params(net, 1)
+    flat = torch.from_numpy(np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32))
+    x = torch.from_numpy(wl.images(1, N, H, W, C))
+    lb = torch.from_numpy(wl.labels_uniform(2, N, net.classes))
+    step_mod.TrainStep(net, N, flat, torch.zeros_like(flat), x, lb)                       # the well-formed call
+    for bad in (dict(labels=lb.to(torch.int64)), dict(labels=lb[:-1]), dict(x=x.double()), dict(x=x[:, :, :-1]),
+                dict(params=flat[:-4]), dict(grads=torch.zeros(flat.numel(), dtype=torch.float64)), dict(x=x.permute(0, 2, 1, 3))):
+        kw = dict(params=flat, grads=torch.zeros_like(flat), x=x, labels=lb)
+        kw.update(bad)
+        with pytest.raises(LpdtError):
+            step_mod.TrainStep(net, N, kw["params"], kw["grads"], kw["x"], kw["labels"])
