@@ -67,3 +67,30 @@ def test_operands_of_the_wrong_type_or_size_are_refused():
         kw.update(bad)
         with pytest.raises(LpdtError):
             step_mod.TrainStep(net, N, kw["params"], kw["grads"], kw["x"], kw["labels"])
+
+
+@pytest.mark.parametrize("name,N", [("resnet20", 4), ("resnet18", 2), ("vgg11", 2), ("transformer_ffn", 8)])
+def test_call_list_invariants(name, N):
+    """Stochastic-rounding counter ranges are one per tensor (Section 3: independent rounding noise), every workspace
+    placeholder was replaced by an address and a size, second-stream calls exist only with overlap, the update is last."""
+    net = getattr(nets, name)()
+    H, W, C = net.in_shape
+    params = nets.init_params(net, 1)
+    flat = torch.from_numpy(np.concatenate([params[n].ravel() for n, _ in net.params]).astype(np.float32))
+    x = torch.from_numpy(wl.images(1, N, H, W, C))
+    if net.classes:
+        labels, upstream = torch.from_numpy(wl.labels_uniform(2, N, net.classes)), None
+    else:
+        labels, upstream = None, torch.from_numpy(wl.upstream_grad(3, (N,) + tuple(net.shapes[net.ops[-1][1]])))
+    for overlap in (True, False):
+        ts = step_mod.TrainStep(net, N, flat, torch.zeros_like(flat), x, labels, upstream, overlap_wgrad=overlap)
+        sr = [c[2] for c in ts.calls if c[2] is not None]
+        assert sr and len(sr) == len(set(sr)) and max(sr) < 256 and min(sr) >= 0
+        for fn, args, _, side in ts.calls:
+            assert "WS" not in [a for a in args if isinstance(a, str)] and "WSB" not in [a for a in args if isinstance(a, str)]
+            assert overlap or not side
+        real = [c for c in ts.calls if c[0] is not None]
+        assert real[-1][0].__name__ == "lpdt_sgd"
+        n_wgrad = sum(c[0].__name__.startswith("lpdt_qconv_bwd_weight") for c in real)
+        n_conv = sum(op[0] == "conv" for op in net.ops)
+        assert n_wgrad == n_conv
