@@ -300,7 +300,8 @@ int lpdt_range_evonorm_fwd_q(const float *x, int N, int H, int W, int C, int gro
  * the gradient through the range goes entirely to the saved arg-max (+) and arg-min (-).
  * dv, dgamma, dbeta fp32 [C] are overwritten (not accumulated).  Results do not depend
  * on launch geometry or run (fixed-order reductions).
- * absmax_out: optional fp32 scalar, set to max|dx|. */
+ * absmax_out: optional fp32 scalar, set to max|dx|.  A saved position outside its slab (not what the
+ * forward pass wrote) is taken as the slab's first element: nothing is read or written out of bounds. */
 int lpdt_range_evonorm_bwd(const float *dy, const float *x, int N, int H, int W, int C, int groups,
                            const float *v, const float *gamma, float eps, const float *range,
                            const int32_t *argmax, const int32_t *argmin, float *dx, float *dv,
